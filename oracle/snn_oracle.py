@@ -1,0 +1,290 @@
+"""CPU oracle for surrogate-gradient BPTT through a layered LIF network.
+
+TEST INFRASTRUCTURE ONLY.  This is a plain, slow, float64 NumPy statement of
+what the training step computes.  Only the tests, the smoke check and the
+benchmark's `cpu_baseline` leg may import it; the product path never does, and
+it shares no code with the HIP kernels.
+
+The network is the stack the paper builds in its Section 2.1.2 network listing:
+  Linear(no bias) -> LIF -> ... -> Linear(no bias) -> LI readout
+unrolled over time exactly like a deep RNN: at every time step the input passes
+through all layers in order.  The backward pass is the reverse sweep that
+reverse-mode differentiation of that unrolled loop performs, with the
+derivative of the Heaviside step replaced by a surrogate (Section 2.1.1).
+
+Readings of points the paper leaves open (each also listed in the design
+notes of this repository):
+  * Heaviside at exactly zero: no spike (spike iff V - theta > 0).
+  * Spike is taken from the carried-in potential, then the potential is
+    updated (Eq. 1 uses V_t, Eq. 2 produces V_{t+1}); initial state zero.
+  * Reset is theta * S_t (Eq. 2) and is NOT detached in the backward pass:
+    the LIF listing uses the same traced `spikes` value for output and reset.
+  * beta is a fixed per-layer scalar here (the paper trains a per-neuron
+    beta; that is a later row of the scope table).
+  * LI readout: y_t = beta_o * y_{t-1} + J_t, y_{-1} = 0, the updated y_t is
+    what is emitted; no threshold, no reset.
+  * Loss: softmax cross-entropy on z[b,c] = max_t y_t[b,c], mean over the
+    batch; the sub-gradient of the max goes to the FIRST maximising step.
+  * Arctan surrogate: (k/2) / (1 + (pi k x / 2)^2), the derivative of
+    (1/pi) arctan(pi k x / 2) + 1/2.  The paper only names it.
+  * Recurrent LIF: V_{t+1} = beta V_t + I_t + S_t R - theta S_t with S_t the
+    spikes just emitted from V_t; R is [from, to].  The paper only mentions
+    recurrent models.
+  * "bf16" GEMM mode: every real-valued matrix-product operand (weights,
+    current gradients) is rounded to bfloat16 (round to nearest even) where it
+    enters a product; 0/1 spikes are exact; all state, the surrogate, the loss
+    and all accumulation stay unrounded.
+
+parity unpinned (fixed by this file, nothing in the paper to check against):
+the arctan constant, the loss reduction (mean) and the readout equation.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Net:
+    sizes: Tuple[int, ...]            # N_0 .. N_L
+    recurrent: Tuple[bool, ...]       # L-1 flags
+    beta: Tuple[float, ...]           # L decays, last = readout
+    theta: float
+    surrogate: str                    # superspike | arctan | sigmoid | triangular
+    slope: float
+    gemm_round: str = "none"          # "none" | "bf16"
+
+    @property
+    def L(self) -> int:
+        return len(self.sizes) - 1
+
+
+# --------------------------------------------------------------------------
+# bfloat16 rounding (round to nearest, ties to even), used only in bf16 mode
+# --------------------------------------------------------------------------
+def rne_bf16(x: np.ndarray) -> np.ndarray:
+    """Round to the nearest bfloat16 (8 significant bits), return float64.
+
+    The value is first taken to float32 (the precision the device holds it
+    in), then the low 16 bits are rounded away, ties to even.
+    """
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+def _q(net: Net, a: np.ndarray) -> np.ndarray:
+    return rne_bf16(a) if net.gemm_round == "bf16" else a
+
+
+# --------------------------------------------------------------------------
+# surrogate derivative (Section 2.1.1) and its antiderivative (test switch)
+# --------------------------------------------------------------------------
+def surrogate_grad(kind: str, k: float, x: np.ndarray) -> np.ndarray:
+    """Backward function bwd(x) of the spiking activation, x = V - theta."""
+    if kind == "superspike":          # surrogate listing: 1 / (1 + k|x|)^2
+        return 1.0 / (1.0 + k * np.abs(x)) ** 2
+    if kind == "arctan":              # reading stated in the module header
+        return (k / 2.0) / (1.0 + (np.pi * k * x / 2.0) ** 2)
+    if kind == "sigmoid":             # derivative of sigmoid(k x)
+        s = 1.0 / (1.0 + np.exp(-k * x))
+        return k * s * (1.0 - s)
+    if kind == "triangular":          # surrogate listing: max(0, 1 - |k x|)
+        return np.maximum(0.0, 1.0 - np.abs(k * x))
+    raise ValueError(kind)
+
+
+def smooth_step(kind: str, k: float, x: np.ndarray) -> np.ndarray:
+    """A function whose exact derivative is surrogate_grad (smooth stand-in for
+    the Heaviside step; only used to check the backward sweep by finite
+    differences)."""
+    if kind == "superspike":
+        return 0.5 + x / (1.0 + k * np.abs(x))
+    if kind == "arctan":
+        return 0.5 + np.arctan(np.pi * k * x / 2.0) / np.pi
+    if kind == "sigmoid":
+        return 1.0 / (1.0 + np.exp(-k * x))
+    if kind == "triangular":
+        xc = np.clip(x, -1.0 / k, 1.0 / k)
+        return 0.5 + xc - 0.5 * k * xc * np.abs(xc)
+    raise ValueError(kind)
+
+
+# --------------------------------------------------------------------------
+# forward
+# --------------------------------------------------------------------------
+@dataclass
+class Trace:
+    I: List[np.ndarray] = field(default_factory=list)   # per spiking layer [T,B,N]
+    V: List[np.ndarray] = field(default_factory=list)   # potential the spike decision used
+    S: List[np.ndarray] = field(default_factory=list)   # spikes (0/1, or smooth values)
+    J: Optional[np.ndarray] = None                      # readout currents [T,B,C]
+    Y: Optional[np.ndarray] = None                      # readout trace    [T,B,C]
+    z: Optional[np.ndarray] = None                      # max over time    [B,C]
+    tstar: Optional[np.ndarray] = None                  # first argmax     [B,C]
+    loss_b: Optional[np.ndarray] = None                 # per-sample CE    [B]
+    loss: float = 0.0
+    v_final: List[np.ndarray] = field(default_factory=list)
+
+
+Forced = Dict[Tuple[int, int], List[Tuple[int, int, int]]]
+"""(spiking layer index 0-based, t) -> list of (b, n, value): decisions to impose."""
+
+
+def forward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
+            R: Sequence[Optional[np.ndarray]], labels: np.ndarray,
+            forced: Optional[Forced] = None, smooth: bool = False,
+            batch_norm: Optional[int] = None) -> Trace:
+    """Unroll the network over time (Eq. 1-2 per spiking layer, LI readout).
+
+    X: [T,B,N_0] 0/1.  W[l]: [N_l, N_{l+1}].  R[l]: [N,N] or None.
+    `batch_norm`: divisor of the mean loss (defaults to B; lets a caller run a
+    subset of a larger batch and keep the larger batch's scaling).
+    """
+    T, B, _ = X.shape
+    L = net.L
+    Wq = [_q(net, np.asarray(w, np.float64)) for w in W]
+    Rq = [None if r is None else _q(net, np.asarray(r, np.float64)) for r in R]
+    th = net.theta
+    tr = Trace()
+    for l in range(L - 1):
+        n = net.sizes[l + 1]
+        tr.I.append(np.zeros((T, B, n)))
+        tr.V.append(np.zeros((T, B, n)))
+        tr.S.append(np.zeros((T, B, n)))
+    C = net.sizes[L]
+    tr.J = np.zeros((T, B, C))
+    tr.Y = np.zeros((T, B, C))
+    v = [np.zeros((B, net.sizes[l + 1])) for l in range(L - 1)]   # V_0 = 0
+    y = np.zeros((B, C))                                          # y_{-1} = 0
+    Xf = X.astype(np.float64)
+    for t in range(T):
+        s_in = Xf[t]
+        for l in range(L - 1):
+            cur = s_in @ Wq[l]                       # Linear, no bias
+            if smooth:
+                s = smooth_step(net.surrogate, net.slope, v[l] - th)
+            else:
+                s = (v[l] - th > 0.0).astype(np.float64)          # Eq. 1
+            if forced and (l, t) in forced:
+                for (b, nn, val) in forced[(l, t)]:
+                    s[b, nn] = float(val)
+            tr.I[l][t] = cur
+            tr.V[l][t] = v[l]
+            tr.S[l][t] = s
+            nxt = net.beta[l] * v[l] + cur - th * s               # Eq. 2
+            if Rq[l] is not None:
+                nxt = nxt + s @ Rq[l]
+            v[l] = nxt
+            s_in = s
+        jt = s_in @ Wq[L - 1]
+        y = net.beta[L - 1] * y + jt
+        tr.J[t] = jt
+        tr.Y[t] = y
+    tr.v_final = v
+    tr.z = tr.Y.max(axis=0)
+    tr.tstar = tr.Y.argmax(axis=0)                                # first maximiser
+    zmax = tr.z.max(axis=1, keepdims=True)
+    lse = zmax[:, 0] + np.log(np.exp(tr.z - zmax).sum(axis=1))
+    tr.loss_b = lse - tr.z[np.arange(B), labels]
+    tr.loss = float(tr.loss_b.sum() / (B if batch_norm is None else batch_norm))
+    return tr
+
+
+# --------------------------------------------------------------------------
+# backward
+# --------------------------------------------------------------------------
+@dataclass
+class Grads:
+    dz: Optional[np.ndarray] = None
+    dJ: Optional[np.ndarray] = None
+    dS: List[np.ndarray] = field(default_factory=list)   # dL/dS per spiking layer
+    dI: List[np.ndarray] = field(default_factory=list)   # dL/dI per spiking layer
+    dW: List[np.ndarray] = field(default_factory=list)   # L entries
+    dR: List[Optional[np.ndarray]] = field(default_factory=list)
+
+
+def backward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
+             R: Sequence[Optional[np.ndarray]], labels: np.ndarray, tr: Trace,
+             batch_norm: Optional[int] = None) -> Grads:
+    """Reverse sweep over the unrolled loop.
+
+    g[l] is dL/dV_{t+1} of spiking layer l while step t is processed.  A
+    potential V_t reaches the loss through beta*V_t into V_{t+1} and through
+    the spike S_t, which feeds the next layer at step t, the reset
+    -theta*S_t and (if recurrent) S_t R into V_{t+1}.  dS_t/dV_t is the
+    surrogate at V_t - theta.
+    """
+    T, B, _ = X.shape
+    L = net.L
+    Wq = [_q(net, np.asarray(w, np.float64)) for w in W]
+    Rq = [None if r is None else _q(net, np.asarray(r, np.float64)) for r in R]
+    th = net.theta
+    Bn = B if batch_norm is None else batch_norm
+    C = net.sizes[L]
+
+    zmax = tr.z.max(axis=1, keepdims=True)
+    p = np.exp(tr.z - zmax)
+    p /= p.sum(axis=1, keepdims=True)
+    onehot = np.zeros((B, C))
+    onehot[np.arange(B), labels] = 1.0
+    gr = Grads()
+    gr.dz = (p - onehot) / Bn
+
+    gr.dJ = np.zeros((T, B, C))
+    for l in range(L - 1):
+        n = net.sizes[l + 1]
+        gr.dS.append(np.zeros((T, B, n)))
+        gr.dI.append(np.zeros((T, B, n)))
+    gr.dW = [np.zeros_like(w, dtype=np.float64) for w in W]
+    gr.dR = [None if r is None else np.zeros_like(r, dtype=np.float64) for r in R]
+
+    Xf = X.astype(np.float64)
+    h = np.zeros((B, C))                                   # dL/dy_{t+1} carried back
+    g = [np.zeros((B, net.sizes[l + 1])) for l in range(L - 1)]
+    tgrid = tr.tstar
+    for t in range(T - 1, -1, -1):
+        # readout: y_t = beta y_{t-1} + J_t, z picks y at tstar
+        h = net.beta[L - 1] * h + gr.dz * (tgrid == t)
+        dJt = h
+        gr.dJ[t] = dJt
+        s_below = tr.S[L - 2][t] if L >= 2 else Xf[t]
+        dJq = _q(net, dJt)
+        gr.dW[L - 1] += s_below.T @ dJq
+        d_s = dJq @ Wq[L - 1].T                            # dL/dS^{L-1}_t
+        for l in range(L - 2, -1, -1):
+            gr.dS[l][t] = d_s
+            dIt = g[l]                                     # dV_{t+1}/dI_t = 1
+            gr.dI[l][t] = dIt
+            dIq = _q(net, dIt)
+            s_in = tr.S[l - 1][t] if l >= 1 else Xf[t]
+            gr.dW[l] += s_in.T @ dIq
+            if Rq[l] is not None:
+                gr.dR[l] += tr.S[l][t].T @ dIq
+            q = d_s - th * g[l]
+            if Rq[l] is not None:
+                q = q + dIq @ Rq[l].T
+            sg = surrogate_grad(net.surrogate, net.slope, tr.V[l][t] - th)
+            g[l] = net.beta[l] * g[l] + sg * q
+            if l >= 1:
+                d_s = dIq @ Wq[l].T
+    return gr
+
+
+def sgd_step(W: Sequence[np.ndarray], R: Sequence[Optional[np.ndarray]], gr: Grads,
+             lr: float):
+    """Plain SGD on the (unrounded) master parameters."""
+    Wn = [np.asarray(w, np.float64) - lr * d for w, d in zip(W, gr.dW)]
+    Rn = [None if r is None else np.asarray(r, np.float64) - lr * d
+          for r, d in zip(R, gr.dR)]
+    return Wn, Rn
+
+
+def train_step(net: Net, X, W, R, labels, lr: float):
+    """Forward, backward and one SGD step: the unit of work the benchmark times."""
+    tr = forward(net, X, W, R, labels)
+    gr = backward(net, X, W, R, labels, tr)
+    Wn, Rn = sgd_step(W, R, gr, lr)
+    return tr, gr, Wn, Rn

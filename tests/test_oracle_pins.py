@@ -1,0 +1,347 @@
+"""Pins for the CPU oracle: closed forms, library routines, finite differences,
+brute force and structural invariants.  None of these re-types the oracle's own
+recursion; each would fail for a plausible slip (dropped term, wrong sign or
+index, transposed operand, detached reset, off-by-one in time)."""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.signal
+import scipy.special
+import torch
+
+import workloads
+from oracle import snn_oracle as O
+from oracle import snn_scalar
+from tests.helpers import net_of, tiny_net
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def single_neuron(beta, theta, c, T, surrogate="superspike", slope=25.0):
+    """One always-on input with weight c feeding one LIF neuron and a 1-class readout."""
+    net = O.Net(sizes=(1, 1, 1), recurrent=(False,), beta=(beta, 0.5), theta=theta,
+                surrogate=surrogate, slope=slope)
+    X = np.ones((T, 1, 1), np.uint8)
+    W = [np.array([[c]]), np.array([[1.0]])]
+    return net, X, W, [None], np.array([0])
+
+
+# ---------------------------------------------------------------- Eq. 1-2
+def test_worked_example_constant_current():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "lif_constant_current.txt"))
+            if l.strip() and not l.startswith("#")]
+    net, X, W, R, lab = single_neuron(0.9, 1.0, 0.3, len(rows))
+    tr = O.forward(net, X, W, R, lab)
+    for t, v, s in rows:
+        assert tr.V[0][int(t), 0, 0] == pytest.approx(float(v), abs=1e-9)
+        assert tr.S[0][int(t), 0, 0] == float(s)
+
+
+@pytest.mark.parametrize("beta,theta,c", [(0.9, 1.0, 0.3), (0.95, 1.0, 0.08), (0.8, 2.0, 0.5),
+                                          (0.9, 1.0, 0.1001), (0.9, 1.0, 0.0999), (0.5, 1.0, 3.0)])
+def test_first_spike_time_closed_form(beta, theta, c):
+    """Before the first spike V_t = c (1 - beta^t) / (1 - beta); the neuron fires first at
+    the smallest t with V_t > theta, i.e. floor(ln(1 - theta (1-beta)/c) / ln beta) + 1,
+    and never if c/(1-beta) <= theta."""
+    T = 200
+    net, X, W, R, lab = single_neuron(beta, theta, c, T)
+    tr = O.forward(net, X, W, R, lab)
+    spikes = np.flatnonzero(tr.S[0][:, 0, 0])
+    if c / (1 - beta) <= theta:
+        assert spikes.size == 0
+        t = np.arange(T)
+        assert np.allclose(tr.V[0][:, 0, 0], c * (1 - beta ** t) / (1 - beta), atol=1e-12)
+        return
+    t1 = math.floor(math.log(1 - theta * (1 - beta) / c) / math.log(beta)) + 1
+    assert spikes[0] == t1
+    t = np.arange(t1 + 1)
+    assert np.allclose(tr.V[0][:t1 + 1, 0, 0], c * (1 - beta ** t) / (1 - beta), atol=1e-12)
+    # after the reset the same geometric law restarts from beta*V - theta + c
+    v0 = beta * tr.V[0][t1, 0, 0] + c - theta
+    t2 = spikes[1]
+    j = np.arange(t2 - t1)
+    assert np.allclose(tr.V[0][t1 + 1:t2 + 1, 0, 0],
+                       beta ** j * v0 + c * (1 - beta ** j) / (1 - beta), atol=1e-12)
+
+
+@pytest.mark.parametrize("c", [0.5, 0.375, 0.25])
+def test_non_leaky_spike_count(c):
+    """beta = 1, theta = 1: total charge t*c minus one unit per spike must stay in (.., 1];
+    number of spikes emitted at steps <= t is max(0, ceil(t c) - 1)."""
+    T = 40
+    net, X, W, R, lab = single_neuron(1.0, 1.0, c, T)
+    tr = O.forward(net, X, W, R, lab)
+    counts = np.cumsum(tr.S[0][:, 0, 0])
+    for t in range(T):
+        assert counts[t] == max(0, math.ceil(t * c) - 1)
+
+
+def test_charge_balance_and_structure():
+    """v_T = sum_t beta^(T-1-t) (I_t - theta S_t + S_t R): ties spikes to potentials."""
+    rng = np.random.default_rng(5)
+    net, X, W, R, lab = tiny_net(rng, sizes=(12, 9, 7, 4), recurrent=(True, False), T=25, B=3,
+                                 surrogate="superspike", slope=25.0, gain=2.5)
+    tr = O.forward(net, X, W, R, lab)
+    T = X.shape[0]
+    for l in range(2):
+        assert tr.S[l].sum() > 0, "test must actually spike"
+        drive = tr.I[l] - net.theta * tr.S[l]
+        if R[l] is not None:
+            drive = drive + tr.S[l] @ R[l]
+        w = net.beta[l] ** (T - 1 - np.arange(T))
+        assert np.allclose(np.tensordot(w, drive, axes=(0, 0)), tr.v_final[l], atol=1e-12)
+        assert np.all(tr.S[l][0] == 0)                        # V_0 = 0 cannot spike
+        assert np.array_equal(tr.S[l], (tr.V[l] > net.theta).astype(float))
+    gr = O.backward(net, X, W, R, lab, tr)
+    for l in range(2):
+        assert np.all(gr.dI[l][T - 1] == 0)                   # last current never reaches the loss
+    assert np.allclose(gr.dz.sum(axis=1), 0, atol=1e-15)
+
+
+def test_silent_network():
+    wl = workloads.CONFIGS["tiny_ff"]
+    inp = workloads.generate(wl)
+    net = net_of(wl)
+    W0 = [np.zeros_like(w) for w in inp.W]
+    tr = O.forward(net, inp.X, W0, inp.R, inp.labels)
+    assert all(s.sum() == 0 for s in tr.S)
+    assert np.all(tr.Y == 0)
+    assert tr.loss == pytest.approx(math.log(10), abs=1e-15)
+    gr = O.backward(net, inp.X, W0, inp.R, inp.labels, tr)
+    # hidden spikes are all zero, so dW_out = S^T dJ = 0; dS = dJ * 0 = 0 upstream
+    assert all(np.all(d == 0) for d in gr.dW)
+
+
+# ---------------------------------------------------------------- library routines
+def test_readout_is_a_first_order_filter():
+    rng = np.random.default_rng(1)
+    net, X, W, R, lab = tiny_net(rng, sizes=(8, 6, 5), recurrent=(False,), T=30, B=4,
+                                 beta=(0.9, 0.83), gain=3.0, surrogate="superspike")
+    tr = O.forward(net, X, W, R, lab)
+    assert tr.S[0].sum() > 0
+    assert np.allclose(tr.J, tr.S[0] @ W[1], atol=1e-13)
+    Y = scipy.signal.lfilter([1.0], [1.0, -net.beta[1]], tr.J, axis=0)
+    assert np.allclose(tr.Y, Y, atol=1e-12)
+
+
+def test_lif_without_threshold_is_a_delayed_filter():
+    rng = np.random.default_rng(2)
+    net, X, W, R, lab = tiny_net(rng, sizes=(8, 6, 5), recurrent=(False,), T=30, B=4,
+                                 beta=(0.9, 0.83), theta=1e9)
+    tr = O.forward(net, X, W, R, lab)
+    cur = X.astype(float) @ W[0]
+    assert np.allclose(tr.I[0], cur, atol=1e-13)
+    filt = scipy.signal.lfilter([1.0], [1.0, -net.beta[0]], cur, axis=0)
+    assert np.all(tr.V[0][0] == 0)
+    assert np.allclose(tr.V[0][1:], filt[:-1], atol=1e-12)    # one-step delay
+
+
+def test_loss_matches_scipy_and_argmax_is_first():
+    rng = np.random.default_rng(3)
+    net, X, W, R, lab = tiny_net(rng, sizes=(6, 5, 4), recurrent=(False,), T=12, B=5, gain=3.0,
+                                 surrogate="superspike")
+    tr = O.forward(net, X, W, R, lab)
+    ref = -scipy.special.log_softmax(tr.z, axis=1)[np.arange(5), lab]
+    assert np.allclose(tr.loss_b, ref, atol=1e-13)
+    assert tr.loss == pytest.approx(ref.mean(), abs=1e-14)
+    gr = O.backward(net, X, W, R, lab, tr)
+    sm = scipy.special.softmax(tr.z, axis=1)
+    sm[np.arange(5), lab] -= 1
+    assert np.allclose(gr.dz, sm / 5, atol=1e-14)
+    # silent classes: readout identically zero, first maximiser must be step 0
+    W0 = [W[0], np.zeros_like(W[1])]
+    assert np.all(O.forward(net, X, W0, R, lab).tstar == 0)
+
+
+def test_bf16_rounding_matches_library():
+    rng = np.random.default_rng(4)
+    x = np.concatenate([rng.standard_normal(20000) * 10.0 ** rng.integers(-6, 6, 20000),
+                        # exact ties: halfway between two neighbouring bfloat16 values in [1, 2)
+                        (256 + 2 * np.arange(0, 64) + 1) / 256.0, [0.0, -0.0, 1.0, -1.0]])
+    want = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(O.rne_bf16(x), want)
+
+
+# ---------------------------------------------------------------- gradients
+def fd_grads(net, X, W, R, lab, h=1e-6):
+    def loss(Wp, Rp):
+        return O.forward(net, X, Wp, Rp, lab, smooth=True).loss
+    dW, dR = [], []
+    for l, w in enumerate(W):
+        d = np.zeros_like(w)
+        for idx in np.ndindex(*w.shape):
+            Wp = [a.copy() for a in W]; Wp[l][idx] += h
+            Wm = [a.copy() for a in W]; Wm[l][idx] -= h
+            d[idx] = (loss(Wp, R) - loss(Wm, R)) / (2 * h)
+        dW.append(d)
+    for l, r in enumerate(R):
+        if r is None:
+            dR.append(None); continue
+        d = np.zeros_like(r)
+        for idx in np.ndindex(*r.shape):
+            Rp = [None if a is None else a.copy() for a in R]; Rp[l][idx] += h
+            Rm = [None if a is None else a.copy() for a in R]; Rm[l][idx] -= h
+            d[idx] = (loss(W, Rp) - loss(W, Rm)) / (2 * h)
+        dR.append(d)
+    return dW, dR
+
+
+@pytest.mark.parametrize("surrogate,slope", [("sigmoid", 3.0), ("superspike", 4.0),
+                                             ("arctan", 2.0), ("triangular", 0.5)])
+@pytest.mark.parametrize("recurrent", [(False, False), (True, True), (False, True)])
+def test_backward_is_exact_gradient_of_smoothed_network(surrogate, slope, recurrent):
+    """With the step replaced by the surrogate's antiderivative the reverse sweep must be the
+    true gradient: checks the reset path (not detached), the recurrent path, the one-step
+    delay, every transpose and the readout."""
+    rng = np.random.default_rng(11)
+    net, X, W, R, lab = tiny_net(rng, recurrent=recurrent, surrogate=surrogate, slope=slope)
+    tr = O.forward(net, X, W, R, lab, smooth=True)
+    gr = O.backward(net, X, W, R, lab, tr)
+    dW, dR = fd_grads(net, X, W, R, lab)
+    for l in range(net.L):
+        assert np.abs(gr.dW[l]).max() > 1e-4
+        assert np.allclose(gr.dW[l], dW[l], rtol=2e-6, atol=2e-9), (l, np.abs(gr.dW[l] - dW[l]).max())
+    for l in range(net.L - 1):
+        if R[l] is not None:
+            assert np.allclose(gr.dR[l], dR[l], rtol=2e-6, atol=2e-9)
+
+
+def test_surrogates_are_derivatives_of_their_smooth_steps():
+    x = np.linspace(-3, 3, 601) + 1e-4
+    for kind, k in [("sigmoid", 3.0), ("superspike", 25.0), ("arctan", 2.0), ("triangular", 0.5)]:
+        h = 1e-6
+        fd = (O.smooth_step(kind, k, x + h) - O.smooth_step(kind, k, x - h)) / (2 * h)
+        assert np.allclose(fd, O.surrogate_grad(kind, k, x), atol=1e-6), kind
+    # printed formulas of the surrogate listing, at hand-picked points
+    assert O.surrogate_grad("superspike", 25.0, np.array([0.0, 0.04, -0.2]))  \
+        == pytest.approx([1.0, 0.25, 1 / 36.0])
+    assert O.surrogate_grad("triangular", 0.5, np.array([0.0, 1.0, -3.0])) == pytest.approx([1, 0.5, 0])
+    assert O.surrogate_grad("arctan", 2.0, np.array([0.0]))[0] == pytest.approx(1.0)
+
+
+def test_readout_weight_gradient_of_the_real_spiking_network():
+    """Spikes do not depend on the readout weights, so central differences on W^L of the
+    true (Heaviside) network must match dW^L."""
+    rng = np.random.default_rng(21)
+    net, X, W, R, lab = tiny_net(rng, sizes=(10, 8, 4), recurrent=(True,), T=15, B=3,
+                                 beta=(0.9, 0.8), surrogate="superspike", slope=25.0, gain=3.0)
+    tr = O.forward(net, X, W, R, lab)
+    assert tr.S[0].sum() > 5
+    gr = O.backward(net, X, W, R, lab, tr)
+    h = 1e-6
+    fd = np.zeros_like(W[1])
+    for idx in np.ndindex(*W[1].shape):
+        Wp = [W[0], W[1].copy()]; Wp[1][idx] += h
+        Wm = [W[0], W[1].copy()]; Wm[1][idx] -= h
+        fd[idx] = (O.forward(net, X, Wp, R, lab).loss - O.forward(net, X, Wm, R, lab).loss) / (2 * h)
+    assert np.allclose(gr.dW[1], fd, rtol=1e-6, atol=1e-9)
+    # closed form of the readout's reverse recursion: dJ_t = dz beta^(t*-t) for t <= t*
+    T = X.shape[0]
+    t = np.arange(T)[:, None, None]
+    closed = np.where(t <= tr.tstar[None], gr.dz[None] * net.beta[1] ** (tr.tstar[None] - t), 0.0)
+    assert np.allclose(gr.dJ, closed, atol=1e-15)
+
+
+# ---------------------------------------------------------------- brute force
+@pytest.mark.parametrize("recurrent", [(False, False), (True, False), (True, True)])
+@pytest.mark.parametrize("surrogate,slope", [("superspike", 25.0), ("arctan", 2.0)])
+def test_vectorised_oracle_equals_scalar_brute_force(recurrent, surrogate, slope):
+    rng = np.random.default_rng(31)
+    net, X, W, R, lab = tiny_net(rng, sizes=(6, 5, 4, 3), recurrent=recurrent, T=9, B=3,
+                                 surrogate=surrogate, slope=slope, gain=2.5)
+    tr = O.forward(net, X, W, R, lab)
+    gr = O.backward(net, X, W, R, lab, tr)
+    assert tr.S[0].sum() > 0 and tr.S[1].sum() > 0
+    ref = snn_scalar.run(net.sizes, net.recurrent, net.beta, net.theta, surrogate, slope,
+                         X.tolist(), [w.tolist() for w in W],
+                         [None if r is None else r.tolist() for r in R], lab.tolist())
+    for l in range(2):
+        assert np.allclose(tr.V[l], np.array(ref["V"][l]), atol=1e-12)
+        assert np.array_equal(tr.S[l], np.array(ref["S"][l]))
+    assert np.allclose(tr.Y, np.array(ref["Y"]), atol=1e-12)
+    assert np.array_equal(tr.tstar, np.array(ref["tstar"]))
+    assert tr.loss == pytest.approx(ref["loss"], abs=1e-12)
+    for l in range(3):
+        assert np.allclose(gr.dW[l], np.array(ref["dW"][l]), atol=1e-12)
+    for l in range(2):
+        if R[l] is not None:
+            assert np.allclose(gr.dR[l], np.array(ref["dR"][l]), atol=1e-12)
+
+
+# ---------------------------------------------------------------- invariants
+def test_batch_permutation_duplication_and_time_shift():
+    rng = np.random.default_rng(41)
+    net, X, W, R, lab = tiny_net(rng, sizes=(9, 7, 6, 4), recurrent=(False, True), T=14, B=4,
+                                 surrogate="superspike", slope=25.0, gain=2.5)
+    tr = O.forward(net, X, W, R, lab)
+    gr = O.backward(net, X, W, R, lab, tr)
+    perm = np.array([2, 0, 3, 1])
+    trp = O.forward(net, X[:, perm], W, R, lab[perm])
+    grp = O.backward(net, X[:, perm], W, R, lab[perm], trp)
+    assert np.array_equal(trp.S[1], tr.S[1][:, perm])
+    assert np.allclose(trp.Y, tr.Y[:, perm], atol=1e-13)
+    for l in range(3):
+        assert np.allclose(grp.dW[l], gr.dW[l], atol=1e-13)
+    # duplicating every sample leaves the mean loss and the gradients unchanged
+    X2 = np.concatenate([X, X], axis=1); lab2 = np.concatenate([lab, lab])
+    tr2 = O.forward(net, X2, W, R, lab2)
+    gr2 = O.backward(net, X2, W, R, lab2, tr2)
+    assert tr2.loss == pytest.approx(tr.loss, abs=1e-13)
+    for l in range(3):
+        assert np.allclose(gr2.dW[l], gr.dW[l], atol=1e-13)
+    assert np.allclose(gr2.dR[1], gr.dR[1], atol=1e-13)
+    # a subset with the full batch's normalisation gives the same per-sample tensors
+    sub = np.array([1, 3])
+    trs = O.forward(net, X[:, sub], W, R, lab[sub], batch_norm=4)
+    grs = O.backward(net, X[:, sub], W, R, lab[sub], trs, batch_norm=4)
+    assert np.allclose(grs.dI[0], gr.dI[0][:, sub], atol=1e-15)
+    # prepending a silent input step delays everything by one step
+    Xs = np.concatenate([np.zeros_like(X[:1]), X], axis=0)
+    trs = O.forward(net, Xs, W, R, lab)
+    assert np.array_equal(trs.S[1][1:], tr.S[1]) and np.all(trs.S[1][0] == 0)
+    assert np.allclose(trs.V[0][1:], tr.V[0], atol=1e-13)
+    assert np.allclose(trs.Y[1:], tr.Y, atol=1e-13)
+
+
+def test_forced_decisions_and_sgd():
+    rng = np.random.default_rng(51)
+    net, X, W, R, lab = tiny_net(rng, sizes=(9, 7, 4), recurrent=(False,), T=10, B=2,
+                                 beta=(0.9, 0.8), surrogate="superspike", slope=25.0, gain=2.5)
+    tr = O.forward(net, X, W, R, lab)
+    t, b, n = 4, 1, 3
+    flipped = 1 - int(tr.S[0][t, b, n])
+    trf = O.forward(net, X, W, R, lab, forced={(0, t): [(b, n, flipped)]})
+    assert trf.S[0][t, b, n] == flipped
+    assert np.array_equal(trf.S[0][:t], tr.S[0][:t])
+    # the imposed decision enters the reset: V_{t+1} differs by exactly theta
+    assert abs(abs(trf.V[0][t + 1, b, n] - tr.V[0][t + 1, b, n]) - net.theta) < 1e-12
+    assert np.array_equal(trf.V[0][:, 1 - b], tr.V[0][:, 1 - b])   # other sample untouched
+    gr = O.backward(net, X, W, R, lab, tr)
+    Wn, Rn = O.sgd_step(W, R, gr, 0.1)
+    assert np.allclose(Wn[0], W[0] - 0.1 * gr.dW[0], atol=0) and Rn == [None]
+
+
+def test_bf16_mode_close_to_fp32_mode():
+    wl = workloads.CONFIGS["tiny_ff"]
+    inp = workloads.generate(wl, w_gain=3.0)
+    a = O.forward(net_of(wl, "none"), inp.X, inp.W, inp.R, inp.labels)
+    b = O.forward(net_of(wl, "bf16"), inp.X, inp.W, inp.R, inp.labels)
+    assert abs(a.loss - b.loss) / abs(a.loss) < 2e-2
+    # bf16 mode is exactly the unrounded algorithm on rounded weights (spikes are 0/1)
+    Wr = [O.rne_bf16(w) for w in inp.W]
+    c = O.forward(net_of(wl, "none"), inp.X, Wr, inp.R, inp.labels)
+    assert np.array_equal(b.V[0], c.V[0]) and b.loss == c.loss
+
+
+def test_workload_generator_statistics():
+    wl = workloads.CONFIGS["shd_ff128"].scaled(T=64, B=32)
+    inp = workloads.generate(wl)
+    assert inp.X.dtype == np.uint8 and inp.X.shape == (64, 32, 700) and inp.X.max() == 1
+    assert 0.005 <= inp.rates.min() and inp.rates.max() <= 0.04
+    assert abs(inp.X.mean() - inp.rates.mean()) < 2e-3
+    assert abs(inp.W[0].std() * math.sqrt(700) - 1) < 0.02
+    assert inp.labels.min() >= 0 and inp.labels.max() < 20
+    again = workloads.generate(wl)
+    assert np.array_equal(again.X, inp.X) and np.array_equal(again.W[1], inp.W[1])
