@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark: training samples/s (forward + backward BPTT + SGD step) of the 700-128-128-20
+LIF network at T=128, B=256 on one MI355X, with a roofline line for the dominant kernel and
+the CPU oracle timed beside it.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload shd_ff128] [--no-cpu]
+
+Prints ONE JSON line on stdout; diagnostics go to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def algorithmic_bytes(wl, kernel, layer):
+    """HBM bytes one launch of `kernel` for text layer `layer` has to move (compulsory traffic
+    of its operands and results, each touched once), in the formats this build stores."""
+    M = wl.T * wl.B
+    bf = wl.precision == "bf16"
+    n_in, n_out = wl.sizes[layer - 1], wl.sizes[layer]
+    di = 4                           # current gradients are fp32 in memory in both modes
+    planes = 1 if bf else 3
+    if kernel == "lif_forward":      # read I (4), write V (4) and S (1 byte)
+        return M * n_out * (4 + 4 + 1)
+    if kernel == "lif_reverse":      # read dS (4) and V (4), write dI (4)
+        return M * n_out * (4 + 4 + di)
+    if kernel == "current_gemm":     # read spikes (1 byte) and the weight planes, write I (4)
+        return M * n_in + planes * 2 * n_in * n_out + M * n_out * 4
+    if kernel == "weight_grad":      # read spikes and dI, write dW
+        return M * n_in + M * n_out * di + n_in * n_out * 4
+    if kernel == "input_grad":       # read dI and the weight planes, write dS
+        return M * n_out * di + planes * 2 * n_in * n_out + M * n_in * 4
+    raise KeyError(kernel)
+
+
+def gemm_flops(wl):
+    M = wl.T * wl.B
+    f = 0
+    for l in range(1, len(wl.sizes)):
+        k, n = wl.sizes[l - 1], wl.sizes[l]
+        f += 2 * M * k * n            # current product
+        f += 2 * M * k * n            # weight gradient
+        if l > 1:
+            f += 2 * M * k * n        # input gradient
+    for l, rec in enumerate(wl.recurrent):
+        if rec:
+            n = wl.sizes[l + 1]
+            f += 3 * 2 * M * n * n    # S R, g R^T, dR
+    return f
+
+
+def cpu_baseline(wl, inp, budget_s=12.0):
+    """The oracle as it stands, whole training steps on the host cores."""
+    import numpy as np
+    from oracle import snn_oracle as O
+    from tests.helpers import net_of
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    net = net_of(wl)
+    W, R = [w.astype(np.float64) for w in inp.W], inp.R
+    O.train_step(net, inp.X, W, R, inp.labels, 0.01)          # warm-up
+    t0 = time.perf_counter()
+    n = 0
+    while True:
+        _, _, W, R = O.train_step(net, inp.X, W, R, inp.labels, 0.01)
+        n += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s or n >= 50:
+            break
+    return {"value": wl.B * n / dt, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n} full training steps (forward+backward+SGD) of the same batch, "
+                      f"T={wl.T} B={wl.B}, NumPy float64, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="shd_ff128")
+    ap.add_argument("--dominant", default="lif_reverse:1", help="kernel:layer bracketed for the roofline line")
+    ap.add_argument("--breakdown", action="store_true", help="time every kernel class first (stderr)")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads
+    from paper_2402_18994_amd.binding import from_workload, KERNELS
+
+    if not torch.cuda.is_available():
+        print("bench.py: no HIP device; there is no CPU path to time", file=sys.stderr)
+        sys.exit(3)
+    wl = workloads.CONFIGS[args.workload]
+    inp = workloads.generate(wl)
+    dev = torch.device("cuda:0")
+    snn = from_workload(wl, inp, device="cuda:0")
+    x = torch.from_numpy(inp.X).to(dev)
+    y = torch.from_numpy(inp.labels).to(dev)
+    lr = 1e-3
+
+    def step():
+        snn.forward(x, y, want_loss=False)
+        snn.backward()
+        snn.sgd_step(lr)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    if args.breakdown:
+        for name in KERNELS:
+            if name == "none":
+                continue
+            snn.profile_select(name, 0)
+            for _ in range(10):
+                step()
+            ms, n = snn.profile_read()
+            if n:
+                print(f"[breakdown] {name:16s} {ms / 10 * 1e3:9.1f} us/step over {n // 10} launches/step",
+                      file=sys.stderr)
+        snn.profile_select("none", 0)
+
+    kname, klayer = args.dominant.split(":")
+    klayer = int(klayer)
+    snn.profile_select(kname, klayer)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    k_ms, k_n = snn.profile_read()
+    snn.profile_select("none", 0)
+    loss = snn.forward(x, y)
+
+    ms_per_step = dt / args.steps * 1e3
+    value = wl.B * args.steps / dt
+    abytes = algorithmic_bytes(wl, kname, klayer)
+    k_avg_s = k_ms / max(1, k_n) * 1e-3
+    achieved = abytes / k_avg_s / 1e9 if k_n else 0.0
+    out = {
+        "metric": "training samples/sec (fwd+bwd BPTT + SGD step), T=%d, B=%d" % (wl.T, wl.B),
+        "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.precision == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {'-'.join(map(str, wl.sizes))} LIF, T={wl.T}, B={wl.B}, "
+                               f"recurrent={list(map(int, wl.recurrent))}, {wl.surrogate}({wl.slope:g}), "
+                               f"bf16 products / fp32 state" if wl.precision == "bf16" else
+                               f"{wl.name}: {'-'.join(map(str, wl.sizes))}, T={wl.T}, B={wl.B}, fp32",
+                   "final_loss": loss},
+        "roofline": {"bound": "hbm", "kernel": f"{kname} layer {klayer}", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes_per_launch": abytes,
+                     "avg_launch_us": k_avg_s * 1e6, "launches": k_n},
+        "gemm_tflops_whole_step": gemm_flops(wl) / (dt / args.steps) / 1e12,
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(wl, inp)
+    snn.destroy()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,201 @@
+/*
+ * snn.h - C ABI of the MI355X (gfx950) library for surrogate-gradient BPTT
+ * training of layered leaky-integrate-and-fire (LIF) spiking networks.
+ *
+ * The network is the stack of the paper's Section 2.1.2 network listing:
+ *     Linear(no bias) -> LIF -> ... -> Linear(no bias) -> LI readout
+ * Layers l = 1..L-1 are spiking (LIF, optionally recurrent), layer L is the
+ * non-spiking leaky readout with C = sizes[L] classes.  One training step is
+ * snn_forward + snn_backward + snn_sgd_step.
+ *
+ * Conventions
+ *   - Every tensor with a time axis is time-major [T][B][N], N fastest.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary
+ *     host memory.  The library never allocates device memory: the caller
+ *     hands over one workspace (snn_workspace_bytes) and keeps it, the input
+ *     raster and the labels alive until the calls that use them have finished
+ *     on the stream.
+ *   - All kernels are enqueued on the HIP stream given to snn_init.  Calls
+ *     return after enqueueing unless stated otherwise.
+ *   - Every function returns an snn_status; nothing throws or exits.  After
+ *     a non-zero status snn_last_error(ctx) describes it.
+ *   - There is no CPU fallback: without a usable HIP device snn_init fails
+ *     with SNN_ERR_HIP.
+ */
+#ifndef SNN_H_
+#define SNN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct snn_ctx snn_ctx;          /* opaque, host side */
+
+typedef enum {
+  SNN_OK = 0,
+  SNN_ERR_NULL = 1,          /* a required pointer was NULL                          */
+  SNN_ERR_ARG = 2,           /* value out of range (T,B,N <= 0, beta outside [0,1],
+                                theta <= 0, slope <= 0, unknown enum, bad label)    */
+  SNN_ERR_SHAPE = 3,         /* byte count does not match the tensor asked for      */
+  SNN_ERR_WORKSPACE = 4,     /* workspace too small or not 256-byte aligned         */
+  SNN_ERR_STATE = 5,         /* call order: backward needs forward, sgd needs backward */
+  SNN_ERR_HIP = 6,           /* a HIP call failed; text in snn_last_error           */
+  SNN_ERR_UNSUPPORTED = 7
+} snn_status;
+
+/* Backward function of the spiking activation (Section 2.1.1), x = V - theta, k = slope:
+ *   SUPERSPIKE  1 / (1 + k|x|)^2                  (surrogate listing, k = 25 in the paper)
+ *   ARCTAN      (k/2) / (1 + (pi k x / 2)^2)      (named by the paper; this is the derivative
+ *                                                  of (1/pi) atan(pi k x / 2) + 1/2)
+ *   SIGMOID     k s (1 - s), s = 1/(1+exp(-k x))
+ *   TRIANGULAR  max(0, 1 - |k x|)                 (surrogate listing)
+ * The forward function is always the Heaviside step with no spike at x == 0. */
+typedef enum {
+  SNN_SURR_SUPERSPIKE = 0,
+  SNN_SURR_ARCTAN = 1,
+  SNN_SURR_SIGMOID = 2,
+  SNN_SURR_TRIANGULAR = 3
+} snn_surrogate;
+
+/* Arithmetic of the matrix products.  State, surrogate, loss and accumulation are fp32 in
+ * both modes; spikes are exact 0/1 in both.
+ *   FP32       real operands are split into three bfloat16 pieces (hi+mid+lo = the fp32
+ *              value) and every needed piece product is accumulated in fp32 on the MFMA
+ *              units: products with a 0/1 operand are exact.
+ *   BF16_GEMM  the weights W and R are rounded once to bfloat16 (round to nearest even)
+ *              wherever they enter a product, forward and backward; the current gradients
+ *              enter their products as a hi+lo pair of bfloat16 (error below 2^-16
+ *              relative), so the result is the gradient of the rounded-weight network. */
+typedef enum { SNN_PREC_FP32 = 0, SNN_PREC_BF16_GEMM = 1 } snn_precision;
+
+typedef struct {
+  int32_t T;                 /* time steps                                              */
+  int32_t B;                 /* batch                                                   */
+  int32_t n_layers;          /* L = number of weight matrices = spiking layers + readout */
+  const int32_t *sizes;      /* host, L+1 entries: N_0 (input) .. N_L (classes)         */
+  const uint8_t *recurrent;  /* host, L-1 flags (may be NULL = none): 1 = recurrent LIF */
+  const float *beta;         /* host, L entries in [0,1]; last one is the readout's     */
+  float threshold;           /* theta > 0                                               */
+  int32_t surrogate;         /* snn_surrogate                                           */
+  float slope;               /* k > 0                                                   */
+  int32_t precision;         /* snn_precision                                           */
+} snn_config;
+
+/* Tensors that snn_get_tensor / snn_set_tensor move.  `layer` is 1-based as in the text:
+ * weights 1..L, spiking-layer tensors 1..L-1, readout tensors ignore it.  Element type on
+ * the host side is float unless noted; shapes are dense (no padding). */
+typedef enum {
+  SNN_T_WEIGHT = 0,      /* [N_{l-1}][N_l]  fp32 master weights (settable)                 */
+  SNN_T_RWEIGHT = 1,     /* [N_l][N_l] (from,to), recurrent layers only (settable)         */
+  SNN_T_GRAD_W = 2,      /* [N_{l-1}][N_l]                                                 */
+  SNN_T_GRAD_R = 3,      /* [N_l][N_l]                                                     */
+  SNN_T_CURRENT = 4,     /* I^l [T][B][N_l] (settable)                                     */
+  SNN_T_MEMBRANE = 5,    /* V^l [T][B][N_l]: potential the spike decision used (settable)  */
+  SNN_T_SPIKES = 6,      /* S^l [T][B][N_l], uint8 0/1 (settable)                          */
+  SNN_T_D_SPIKES = 7,    /* dL/dS^l [T][B][N_l] (settable)                                 */
+  SNN_T_D_CURRENT = 8,   /* dL/dI^l [T][B][N_l] (settable)                                 */
+  SNN_T_READOUT_CURRENT = 9,  /* J [T][B][C] (settable)                                    */
+  SNN_T_READOUT_TRACE = 10,   /* Y [T][B][C]                                               */
+  SNN_T_LOGITS = 11,     /* z [B][C] = max_t Y                                             */
+  SNN_T_ARGMAX_T = 12,   /* t* [B][C], int32: first maximising step (settable)             */
+  SNN_T_D_LOGITS = 13,   /* dL/dz [B][C] (settable)                                        */
+  SNN_T_D_READOUT_CURRENT = 14, /* dL/dJ [T][B][C] (settable)                                */
+  SNN_T_LOSS = 15,       /* 1 float                                                        */
+  SNN_T_LOSS_PER_SAMPLE = 16 /* [B]                                                        */
+} snn_tensor;
+
+/* Single steps of the path, for kernel-level tests on imposed inputs (snn_run_step). */
+typedef enum {
+  SNN_STEP_CURRENT_GEMM = 0,   /* I^l = S^{l-1} W^l (layer L: J = S^{L-1} W^L)             */
+  SNN_STEP_LIF_FORWARD = 1,    /* I^l -> V^l, S^l (recurrent layers: includes S R)         */
+  SNN_STEP_READOUT_FORWARD = 2,/* J -> Y, z, t*, loss, dz                                  */
+  SNN_STEP_READOUT_REVERSE = 3,/* dz, t* -> dJ                                             */
+  SNN_STEP_LIF_REVERSE = 4,    /* dS^l, V^l -> dI^l                                        */
+  SNN_STEP_WEIGHT_GRAD = 5,    /* dW^l = S^{l-1}^T dI^l (and dR^l); layer L uses dJ        */
+  SNN_STEP_INPUT_GRAD = 6      /* dS^{l-1} = dI^l W^l^T, l >= 2                            */
+} snn_step;
+
+/* Kernel classes for the built-in event timer (snn_profile_*). */
+typedef enum {
+  SNN_K_NONE = -1,
+  SNN_K_CURRENT_GEMM = 0, SNN_K_LIF_FORWARD = 1, SNN_K_RLIF_FORWARD = 2,
+  SNN_K_READOUT_FORWARD = 3, SNN_K_READOUT_REVERSE = 4, SNN_K_LIF_REVERSE = 5,
+  SNN_K_RLIF_REVERSE = 6, SNN_K_WEIGHT_GRAD = 7, SNN_K_INPUT_GRAD = 8, SNN_K_SGD = 9,
+  SNN_K_COUNT = 10
+} snn_kernel_class;
+
+/* Validate `cfg` and report the device bytes snn_init needs (a multiple of 256).
+ * Pure host code.  Errors: SNN_ERR_NULL, SNN_ERR_ARG. */
+int32_t snn_workspace_bytes(const snn_config *cfg, size_t *bytes);
+
+/* Build a network.  `workspace_dev`: device memory, 256-byte aligned, at least
+ * snn_workspace_bytes(cfg) bytes, owned by the caller, used exclusively by this context
+ * until snn_destroy.  `W_host`: L host pointers, W_host[l] row-major [N_l][N_{l+1}]
+ * (in, out), i.e. I = S W as in the paper's Linear layers without bias.  `R_host`: L-1
+ * host pointers ([N][N], (from, to)), entries for non-recurrent layers ignored; may be
+ * NULL when no layer is recurrent.  Weights are copied; the host arrays may be freed on
+ * return.  `hip_stream`: a hipStream_t (NULL = the default stream).  Synchronises the
+ * stream before returning.  Errors: NULL/ARG/WORKSPACE/HIP. */
+int32_t snn_init(const snn_config *cfg, void *workspace_dev, size_t workspace_bytes,
+                 const float *const *W_host, const float *const *R_host,
+                 void *hip_stream, snn_ctx **out);
+
+/* Forward pass (Eq. 1-2 per spiking layer, LI readout, softmax cross-entropy on the
+ * max-over-time readout, mean over the batch).
+ *   x_dev       device, uint8 [T][B][N_0], values 0 or 1 (anything non-zero counts as 1
+ *               is NOT promised: other values are a caller error)
+ *   labels_dev  device, int32 [B], each in [0, C)
+ *   loss_host   host float, may be NULL.  If given, the call waits for the stream and
+ *               stores the loss; a label outside [0,C) then yields SNN_ERR_ARG.
+ * x_dev and labels_dev must stay valid until the following snn_backward has finished. */
+int32_t snn_forward(snn_ctx *ctx, const uint8_t *x_dev, const int32_t *labels_dev,
+                    float *loss_host);
+
+/* Reverse sweep: readout gradient, per spiking layer the reverse-time scan with the fused
+ * surrogate derivative, the weight-gradient products dW^l = S^{l-1}^T dI^l (dR^l =
+ * S^l^T dI^l) and the input-gradient products dS^{l-1} = dI^l W^l^T.  Needs a preceding
+ * snn_forward on the current weights (else SNN_ERR_STATE). */
+int32_t snn_backward(snn_ctx *ctx);
+
+/* W <- W - lr dW, R <- R - lr dR on the fp32 masters, then refresh the bfloat16 operand
+ * copies the products read.  Needs a preceding snn_backward (else SNN_ERR_STATE). */
+int32_t snn_sgd_step(snn_ctx *ctx, float lr);
+
+/* Copy a tensor to / from dense host memory.  `bytes` must equal the tensor's dense size
+ * (else SNN_ERR_SHAPE).  Both wait for the stream.  snn_set_tensor accepts the tensors
+ * marked settable; setting a weight also refreshes its bfloat16 copies and invalidates a
+ * previous forward.  snn_get_tensor reports a pending bad-label flag as SNN_ERR_ARG. */
+int32_t snn_get_tensor(snn_ctx *ctx, int32_t tensor, int32_t layer, void *dst_host, size_t bytes);
+int32_t snn_set_tensor(snn_ctx *ctx, int32_t tensor, int32_t layer, const void *src_host,
+                       size_t bytes);
+
+/* Run one step of the path for one layer on whatever the context's buffers hold (for
+ * tests that impose a step's inputs with snn_set_tensor).  `x_dev` is needed when the step
+ * reads the input raster (CURRENT_GEMM and WEIGHT_GRAD of layer 1), `labels_dev` for
+ * READOUT_FORWARD; otherwise they may be NULL.  Does not change the forward/backward
+ * call-order state. */
+int32_t snn_run_step(snn_ctx *ctx, int32_t step, int32_t layer, const uint8_t *x_dev,
+                     const int32_t *labels_dev);
+
+/* Event timer.  snn_profile_select(ctx, k, layer) brackets every later launch of kernel
+ * class k (layer = 0: all layers, else that layer only) with a pair of HIP events on the
+ * library's stream; k = SNN_K_NONE switches it off and clears the totals.
+ * snn_profile_read waits for the stream and returns the summed elapsed milliseconds and
+ * the number of bracketed launches since the last select. */
+int32_t snn_profile_select(snn_ctx *ctx, int32_t kernel_class, int32_t layer);
+int32_t snn_profile_read(snn_ctx *ctx, double *total_ms, int64_t *launches);
+
+/* Free the host-side context (the workspace stays the caller's).  Waits for the stream. */
+int32_t snn_destroy(snn_ctx *ctx);
+
+/* Text of the last error of this context (ctx == NULL: of the last failed call that had no
+ * context, e.g. snn_init).  Owned by the library, valid until the next call. */
+const char *snn_last_error(const snn_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SNN_H_ */

@@ -30,10 +30,15 @@ notes of this repository):
   * Recurrent LIF: V_{t+1} = beta V_t + I_t + S_t R - theta S_t with S_t the
     spikes just emitted from V_t; R is [from, to].  The paper only mentions
     recurrent models.
-  * "bf16" GEMM mode: every real-valued matrix-product operand (weights,
-    current gradients) is rounded to bfloat16 (round to nearest even) where it
-    enters a product; 0/1 spikes are exact; all state, the surrogate, the loss
-    and all accumulation stay unrounded.
+  * "bf16" GEMM mode: the weight matrices (W and R) are rounded to bfloat16
+    (round to nearest even) wherever they enter a product, forward and
+    backward; 0/1 spikes are exact; all state, the surrogate, the loss, the
+    current gradients and all accumulation stay unrounded.  (The device carries
+    the current gradients into its bfloat16 products as a hi+lo pair, which
+    loses less than 2^-16 relative; a single rounding of those operands was
+    tried first and rejected: values next to a rounding boundary round
+    differently in fp32 and fp64, which alone moves weight gradients by more
+    than the 1e-4 bound.)
 
 parity unpinned (fixed by this file, nothing in the paper to check against):
 the arctan constant, the loss reduction (mean) and the readout equation.
@@ -251,25 +256,23 @@ def backward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
         dJt = h
         gr.dJ[t] = dJt
         s_below = tr.S[L - 2][t] if L >= 2 else Xf[t]
-        dJq = _q(net, dJt)
-        gr.dW[L - 1] += s_below.T @ dJq
-        d_s = dJq @ Wq[L - 1].T                            # dL/dS^{L-1}_t
+        gr.dW[L - 1] += s_below.T @ dJt
+        d_s = dJt @ Wq[L - 1].T                            # dL/dS^{L-1}_t
         for l in range(L - 2, -1, -1):
             gr.dS[l][t] = d_s
             dIt = g[l]                                     # dV_{t+1}/dI_t = 1
             gr.dI[l][t] = dIt
-            dIq = _q(net, dIt)
             s_in = tr.S[l - 1][t] if l >= 1 else Xf[t]
-            gr.dW[l] += s_in.T @ dIq
+            gr.dW[l] += s_in.T @ dIt
             if Rq[l] is not None:
-                gr.dR[l] += tr.S[l][t].T @ dIq
+                gr.dR[l] += tr.S[l][t].T @ dIt
             q = d_s - th * g[l]
             if Rq[l] is not None:
-                q = q + dIq @ Rq[l].T
+                q = q + dIt @ Rq[l].T
             sg = surrogate_grad(net.surrogate, net.slope, tr.V[l][t] - th)
             g[l] = net.beta[l] * g[l] + sg * q
             if l >= 1:
-                d_s = dIq @ Wq[l].T
+                d_s = dIt @ Wq[l].T
     return gr
 
 

@@ -1,0 +1,50 @@
+// Device helpers shared by the kernels: bfloat16 conversion and splitting,
+// MFMA operand types, LDS tile addressing.  gfx950 (CDNA4) only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace snn {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// ---------------------------------------------------------------- bfloat16
+// Round to nearest, ties to even.  Inputs are finite here (no NaN handling).
+__device__ __forceinline__ uint32_t bf16_bits(float x) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ float bf16_value(uint32_t bits) { return __uint_as_float(bits << 16); }
+
+// Piece `plane` of the three-way split x = hi + mid + lo with each piece a bfloat16.
+// plane 0: hi = rne(x); plane 1: mid = rne(x - hi); plane 2: lo = rne(x - hi - mid).
+__device__ __forceinline__ uint32_t bf16_piece(float x, int plane) {
+  uint32_t hi = bf16_bits(x);
+  if (plane == 0) return hi;
+  float r1 = x - bf16_value(hi);
+  uint32_t mid = bf16_bits(r1);
+  if (plane == 1) return mid;
+  float r2 = r1 - bf16_value(mid);
+  return bf16_bits(r2);
+}
+__device__ __forceinline__ uint32_t pack2(uint32_t lo16, uint32_t hi16) { return lo16 | (hi16 << 16); }
+
+// Two 0/1 bytes -> two bfloat16 (0.0 or 1.0) in one dword: bytes sit in bits 0 and 16.
+__device__ __forceinline__ uint32_t spikes2_to_bf16(uint32_t two_bytes_spread) {
+  return (two_bytes_spread & 0x00010001u) * 0x3F80u;
+}
+
+// ---------------------------------------------------------------- LDS operand tiles
+// An operand tile holds ROWS rows of 64 contraction elements as bfloat16: 128 bytes per row,
+// split in eight 16-byte chunks.  Chunk c of row r lives at chunk slot c ^ swz(r); the
+// permutation keeps both the 16-byte fragment reads (32 consecutive rows, same chunk) and
+// the transposing stores (rows 4 or 2 apart, same chunk) spread over all banks.
+__device__ __forceinline__ int tile_swz(int row) { return (row ^ (row >> 3)) & 7; }
+__device__ __forceinline__ int tile_off(int row, int chunk) {   // byte offset
+  return row * 128 + ((chunk ^ tile_swz(row)) << 4);
+}
+
+}  // namespace snn

@@ -1,0 +1,285 @@
+// Time scans of the training step, gfx950.  All are bound by HBM traffic: one thread owns
+// VEC adjacent chains (b, n..n+VEC-1), keeps their state in registers for all T steps and
+// streams the per-step rows.  Loads do not depend on the recurrence, so a block of U steps
+// is fetched while the previous block is being integrated.
+#pragma once
+#include "common.cuh"
+
+namespace snn {
+
+template <int VEC> struct VecF;
+template <> struct VecF<1> { typedef float type; };
+template <> struct VecF<2> { typedef float2 type; };
+template <> struct VecF<4> { typedef float4 type; };
+
+template <int VEC> __device__ __forceinline__ void vload(float (&d)[VEC], const float *p) {
+  typename VecF<VEC>::type v = *(const typename VecF<VEC>::type *)p;
+  const float *f = (const float *)&v;
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) d[i] = f[i];
+}
+template <int VEC> __device__ __forceinline__ void vstore(float *p, const float (&d)[VEC]) {
+  typename VecF<VEC>::type v;
+  float *f = (float *)&v;
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) f[i] = d[i];
+  *(typename VecF<VEC>::type *)p = v;
+}
+template <int VEC> __device__ __forceinline__ void vstore_u8(uint8_t *p, const uint32_t (&s)[VEC]) {
+  if (VEC == 1) p[0] = (uint8_t)s[0];
+  else if (VEC == 2) *(uint16_t *)p = (uint16_t)(s[0] | (s[1] << 8));
+  else *(uint32_t *)p = s[0] | (s[1] << 8) | (s[2] << 16) | (s[3] << 24);
+}
+
+// ---------------------------------------------------------------- LIF forward (Eq. 1-2)
+// S_t = [V_t > theta]; store V_t, S_t; V_{t+1} = beta V_t + I_t - theta S_t; V_0 = 0.
+// `stride` = B * ld elements between time steps; threads cover the stride (padding
+// columns included: their currents are zero, so they stay silent).
+template <int VEC, int U>
+__global__ __launch_bounds__(256) void lif_forward_kernel(const float *__restrict__ I, float *__restrict__ V,
+                                                          uint8_t *__restrict__ S, int T, long long stride,
+                                                          float beta, float theta) {
+  const long long p = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * VEC;
+  if (p >= stride) return;
+  I += p; V += p; S += p;
+  float v[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) v[i] = 0.f;
+  float a[U][VEC], b[U][VEC];
+
+  auto fetch = [&](float (&buf)[U][VEC], int t0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (t0 + u < T) vload<VEC>(buf[u], I + (long long)(t0 + u) * stride);
+  };
+  auto integrate = [&](float (&buf)[U][VEC], int t0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (t0 + u < T) {
+        uint32_t s[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) s[i] = v[i] > theta ? 1u : 0u;
+        vstore<VEC>(V + (long long)(t0 + u) * stride, v);
+        vstore_u8<VEC>(S + (long long)(t0 + u) * stride, s);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) v[i] = beta * v[i] + buf[u][i] - (s[i] ? theta : 0.f);
+      }
+  };
+  fetch(a, 0);
+  for (int t0 = 0; t0 < T; t0 += 2 * U) {
+    fetch(b, t0 + U);
+    integrate(a, t0);
+    fetch(a, t0 + 2 * U);
+    integrate(b, t0 + U);
+  }
+}
+
+// ---------------------------------------------------------------- LIF reverse, fused surrogate
+// g = 0; for t = T-1..0: dI_t = g; g = beta g + surr(V_t - theta) (dS_t - theta g).
+template <int SURR> __device__ __forceinline__ float surr(float k, float x) {
+  if (SURR == 0) { float d = 1.0f + k * fabsf(x); return 1.0f / (d * d); }
+  if (SURR == 1) { float u = 1.5707963267948966f * k * x; return (0.5f * k) / (1.0f + u * u); }
+  if (SURR == 2) { float s = 1.0f / (1.0f + __expf(-k * x)); return k * s * (1.0f - s); }
+  return fmaxf(0.0f, 1.0f - fabsf(k * x));
+}
+
+template <int VEC, int U, int SURR>
+__global__ __launch_bounds__(256) void lif_reverse_kernel(const float *__restrict__ dS, const float *__restrict__ V,
+                                                          float *__restrict__ dI, int T, long long stride,
+                                                          float beta, float theta, float slope) {
+  const long long p = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * VEC;
+  if (p >= stride) return;
+  dS += p; V += p;
+  float g[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) g[i] = 0.f;
+  float a_ds[U][VEC], a_v[U][VEC], b_ds[U][VEC], b_v[U][VEC];
+
+  // block k covers steps T-1-k*U .. T-k*U-U (descending)
+  auto fetch = [&](float (&bds)[U][VEC], float (&bv)[U][VEC], int thi) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (thi - u >= 0) {
+        vload<VEC>(bds[u], dS + (long long)(thi - u) * stride);
+        vload<VEC>(bv[u], V + (long long)(thi - u) * stride);
+      }
+  };
+  auto integrate = [&](float (&bds)[U][VEC], float (&bv)[U][VEC], int thi) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (thi - u >= 0) {
+        const long long o = (long long)(thi - u) * stride + p;
+        vstore<VEC>(dI + o, g);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i)
+          g[i] = beta * g[i] + surr<SURR>(slope, bv[u][i] - theta) * (bds[u][i] - theta * g[i]);
+      }
+  };
+  fetch(a_ds, a_v, T - 1);
+  for (int thi = T - 1; thi >= 0; thi -= 2 * U) {
+    fetch(b_ds, b_v, thi - U);
+    integrate(a_ds, a_v, thi);
+    fetch(a_ds, a_v, thi - 2 * U);
+    integrate(b_ds, b_v, thi - U);
+  }
+}
+
+// ---------------------------------------------------------------- LI readout, max over time
+// y_t = beta y_{t-1} + J_t, y_{-1} = 0; z = max_t y_t; t* = first maximiser.
+__global__ __launch_bounds__(256) void readout_forward_kernel(const float *__restrict__ J, float *__restrict__ Y,
+                                                              float *__restrict__ z, int *__restrict__ tstar,
+                                                              int T, int stride, float beta) {
+  const int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= stride) return;
+  float y = 0.f, best = -INFINITY;
+  int tb = 0;
+#pragma unroll 8
+  for (int t = 0; t < T; ++t) {
+    y = beta * y + J[(size_t)t * stride + p];
+    Y[(size_t)t * stride + p] = y;
+    if (y > best) { best = y; tb = t; }
+  }
+  z[p] = best;
+  tstar[p] = tb;
+}
+
+// Softmax cross-entropy, one wavefront per sample: lanes stride over the classes and the
+// maximum and the sum are reduced across the wavefront.
+__global__ __launch_bounds__(256) void cross_entropy_kernel(const float *__restrict__ z, const int *__restrict__ labels,
+                                                            float *__restrict__ loss_b, float *__restrict__ dz,
+                                                            int B, int C, int ldc, int *__restrict__ err) {
+  const int lane = threadIdx.x & 63;
+  const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (b >= B) return;
+  const float *zb = z + (size_t)b * ldc;
+  float m = -INFINITY;
+  for (int c = lane; c < C; c += 64) m = fmaxf(m, zb[c]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+  float sum = 0.f;
+  for (int c = lane; c < C; c += 64) sum += expf(zb[c] - m);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+  int lab = labels[b];
+  if (lab < 0 || lab >= C) { if (lane == 0) atomicOr(err, 1); lab = 0; }
+  if (lane == 0) loss_b[b] = m + logf(sum) - zb[lab];
+  const float inv = 1.0f / sum, invB = 1.0f / (float)B;
+  for (int c = lane; c < C; c += 64)
+    dz[(size_t)b * ldc + c] = (expf(zb[c] - m) * inv - (c == lab ? 1.f : 0.f)) * invB;
+}
+
+// Mean of the per-sample losses in a fixed order (one workgroup).
+__global__ __launch_bounds__(256) void loss_mean_kernel(const float *__restrict__ loss_b, float *__restrict__ loss, int B) {
+  __shared__ float part[256];
+  float s = 0.f;
+  for (int b = threadIdx.x; b < B; b += 256) s += loss_b[b];
+  part[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) loss[0] = part[0] / (float)B;
+}
+
+// Readout reverse: h_t = beta h_{t+1} + dz [t == t*]; dJ_t = h_t.
+__global__ __launch_bounds__(256) void readout_reverse_kernel(const float *__restrict__ dz, const int *__restrict__ tstar,
+                                                              float *__restrict__ dJ, int T, int stride, float beta) {
+  const int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= stride) return;
+  const float d = dz[p];
+  const int ts = tstar[p];
+  float h = 0.f;
+  for (int t = T - 1; t >= 0; --t) {
+    h = beta * h + (t == ts ? d : 0.f);
+    dJ[(size_t)t * stride + p] = h;
+  }
+}
+
+// ---------------------------------------------------------------- small utilities
+// out[i] = sum over splits of partial[s][i].  A workgroup owns 256 consecutive floats; its
+// four wavefronts each add every fourth split (16-byte loads, eight in flight) and the four
+// sums are combined through LDS in a fixed order, so the result does not depend on timing.
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part, int splits,
+                                                              long long split_stride, float *__restrict__ out,
+                                                              long long n) {
+  __shared__ float4 sm[4][64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const long long i = ((long long)blockIdx.x * 64 + lane) * 4;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < n) {
+    const float *p = part + i;
+    int k = w;
+    for (; k + 28 < splits; k += 32) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = *(const float4 *)(p + (size_t)(k + 4 * u) * split_stride);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+    }
+    for (; k < splits; k += 4) {
+      const float4 v = *(const float4 *)(p + (size_t)k * split_stride);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+  }
+  sm[w][lane] = acc;
+  __syncthreads();
+  if (w == 0 && i < n) {
+    float4 r = sm[0][lane];
+#pragma unroll
+    for (int q = 1; q < 4; ++q) { r.x += sm[q][lane].x; r.y += sm[q][lane].y; r.z += sm[q][lane].z; r.w += sm[q][lane].w; }
+    *(float4 *)(out + i) = r;
+  }
+}
+
+// Same sum for sizes that are not a multiple of four floats (one element per thread).
+__global__ __launch_bounds__(256) void reduce_partials_scalar_kernel(const float *__restrict__ part, int splits,
+                                                                     long long split_stride, float *__restrict__ out,
+                                                                     long long n) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float s[4] = {0.f, 0.f, 0.f, 0.f};      // same association as the vector kernel
+  for (int k = 0; k < splits; ++k) s[k & 3] += part[(size_t)k * split_stride + i];
+  out[i] = ((s[0] + s[1]) + s[2]) + s[3];
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *__restrict__ p, long long n_dwords) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_dwords) p[i] = 0u;
+}
+
+// Parameter update and operand refresh for one matrix W [K][N] (row-major, N fastest):
+//   W <- W - lr dW            (skipped when dW == NULL)
+//   Qb[p][k][n] = piece_p(W[k][n])     contraction over n   (skipped when Qb == NULL)
+//   Qf[p][n][k] = piece_p(W[k][n])     contraction over k   (32x32 tiles transposed in LDS)
+__global__ __launch_bounds__(256) void param_update_kernel(float *__restrict__ W, const float *__restrict__ dW, float lr,
+                                                           int K, int N, uint16_t *__restrict__ Qf, int ldqf,
+                                                           long long qf_plane, uint16_t *__restrict__ Qb, int ldqb,
+                                                           long long qb_plane, int nplanes) {
+  __shared__ uint16_t tile[3][32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int n0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int k = k0 + ty + 8 * r, n = n0 + tx;
+    float w = 0.f;
+    if (k < K && n < N) {
+      w = W[(size_t)k * N + n];
+      if (dW) { w -= lr * dW[(size_t)k * N + n]; W[(size_t)k * N + n] = w; }
+    }
+    for (int p = 0; p < nplanes; ++p) {
+      const uint16_t bits = (uint16_t)bf16_piece(w, p);
+      tile[p][ty + 8 * r][tx] = bits;
+      if (Qb && k < K && n < N) Qb[(size_t)p * qb_plane + (size_t)k * ldqb + n] = bits;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int n = n0 + ty + 8 * r, k = k0 + tx;
+    if (k < K && n < N)
+      for (int p = 0; p < nplanes; ++p) Qf[(size_t)p * qf_plane + (size_t)n * ldqf + k] = tile[p][tx][ty + 8 * r];
+  }
+}
+
+}  // namespace snn

@@ -1,0 +1,744 @@
+// C ABI of the library (see include/snn.h): context, workspace carve-up, the layer loops of
+// the forward and reverse passes, and the launches.  Host code only enqueues kernels; every
+// step of the path runs on the GPU.
+#include "../../include/snn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "gemm.cuh"
+#include "scan.cuh"
+#include "rlif.cuh"
+
+using namespace snn;
+
+namespace {
+
+inline size_t rup(size_t x, size_t m) { return (x + m - 1) / m * m; }
+
+struct Layer {
+  int K = 0, N = 0;        // fan-in, fan-out
+  int ld = 0;              // padded fan-out of the activation tensors (multiple of 8)
+  bool recurrent = false, spiking = false;
+  float beta = 0.f;
+  float *Wm = nullptr, *dW = nullptr;
+  uint16_t *Qf = nullptr, *Qb = nullptr;       // [plane][N pad 128][K pad 64], [plane][K pad 128][N pad 64]
+  int ldqf = 0, ldqb = 0;
+  long long qf_plane = 0, qb_plane = 0;
+  float *Rm = nullptr, *dR = nullptr;
+  uint16_t *QRf = nullptr, *QRb = nullptr;     // [plane][to][from], [plane][from][to]
+  int ldqr = 0;
+  long long qr_plane = 0;
+  float *I = nullptr, *V = nullptr, *dS = nullptr;   // [M][ld]; readout: I = J, V = Y
+  uint8_t *S = nullptr;
+  float *dI = nullptr;                                // [M][ld]; readout: dJ
+  float *g[2] = {nullptr, nullptr};                   // recurrent reverse state [B][ld]
+  int splits_w = 1, splits_r = 1;
+};
+
+struct Prof {
+  int cls = SNN_K_NONE, layer = 0;
+  std::vector<hipEvent_t> ev;     // start/stop pairs
+  size_t used = 0;
+};
+
+}  // namespace
+
+struct snn_ctx {
+  int T = 0, B = 0, L = 0;
+  long long M = 0;
+  std::vector<int> sizes;
+  std::vector<Layer> layers;      // index 0..L-1  (text layer l = index + 1)
+  float theta = 1.f, slope = 1.f;
+  int surrogate = 0, precision = 0, nplanes = 1;
+  int C = 0, ldC = 0;
+  float *z = nullptr, *dz = nullptr, *loss_b = nullptr, *loss = nullptr;
+  int *tstar = nullptr, *err_flag = nullptr;
+  float *partials = nullptr;
+  size_t partial_elems = 0;
+  char *ws = nullptr;
+  size_t ws_bytes = 0;
+  hipStream_t stream = nullptr;
+  int state = 0;                  // 0 fresh, 1 forward done, 2 backward done
+  const uint8_t *x_dev = nullptr;
+  const int32_t *labels_dev = nullptr;
+  std::string err;
+  Prof prof;
+};
+
+namespace {
+
+thread_local std::string g_err;   // errors of calls that have no context
+
+int fail(snn_ctx *c, int code, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf; else g_err = buf;
+  return code;
+}
+
+#define HIPCHK(c, call)                                                                     \
+  do {                                                                                      \
+    hipError_t e_ = (call);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return fail((c), SNN_ERR_HIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_),  \
+                  __FILE__, __LINE__);                                                      \
+  } while (0)
+
+int validate(const snn_config *cfg) {
+  if (!cfg) return fail(nullptr, SNN_ERR_NULL, "config is NULL");
+  if (!cfg->sizes || !cfg->beta) return fail(nullptr, SNN_ERR_NULL, "config.sizes / config.beta is NULL");
+  if (cfg->T <= 0 || cfg->B <= 0) return fail(nullptr, SNN_ERR_ARG, "T and B must be positive");
+  if (cfg->n_layers < 2 || cfg->n_layers > 64)
+    return fail(nullptr, SNN_ERR_ARG, "n_layers must be in [2, 64] (at least one spiking layer and the readout)");
+  for (int i = 0; i <= cfg->n_layers; ++i)
+    if (cfg->sizes[i] <= 0 || cfg->sizes[i] > (1 << 20)) return fail(nullptr, SNN_ERR_ARG, "sizes[%d] out of range", i);
+  for (int i = 0; i < cfg->n_layers; ++i)
+    if (!(cfg->beta[i] >= 0.f && cfg->beta[i] <= 1.f)) return fail(nullptr, SNN_ERR_ARG, "beta[%d] outside [0,1]", i);
+  if (!(cfg->threshold > 0.f)) return fail(nullptr, SNN_ERR_ARG, "threshold must be positive");
+  if (!(cfg->slope > 0.f)) return fail(nullptr, SNN_ERR_ARG, "slope must be positive");
+  if (cfg->surrogate < 0 || cfg->surrogate > 3) return fail(nullptr, SNN_ERR_ARG, "unknown surrogate");
+  if (cfg->precision < 0 || cfg->precision > 1) return fail(nullptr, SNN_ERR_ARG, "unknown precision");
+  if ((long long)cfg->T * cfg->B > (1ll << 30)) return fail(nullptr, SNN_ERR_ARG, "T*B too large");
+  return SNN_OK;
+}
+
+// Contraction splits of a weight-gradient product with `tiles` output tiles over M rows.
+int choose_splits(long long M, int tiles, long long *per_split) {
+  long long want = 512 / (tiles > 0 ? tiles : 1);
+  long long max_by_len = M / 256;
+  if (want > max_by_len) want = max_by_len;
+  if (want < 1) want = 1;
+  long long per = (long long)rup((size_t)((M + want - 1) / want), 64);
+  *per_split = per;
+  return (int)((M + per - 1) / per);
+}
+
+int wgrad_tiles(int rows, int cols) {
+  int bn = cols <= 32 ? 32 : (cols <= 64 ? 64 : 128);
+  return ((rows + 127) / 128) * ((cols + bn - 1) / bn);
+}
+
+// Walks the workspace layout; with base == nullptr it only counts.
+struct Carver {
+  char *base;
+  size_t off = 0;
+  explicit Carver(char *b) : base(b) {}
+  template <typename Tp> Tp *take(size_t n_elems) {
+    size_t bytes = rup(n_elems * sizeof(Tp), 256);
+    Tp *p = base ? (Tp *)(base + off) : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+void carve(snn_ctx &c, Carver &cv) {
+  const size_t M = (size_t)c.M;
+  const int np = c.nplanes;
+  size_t part = 0;
+  for (int l = 0; l < c.L; ++l) {
+    Layer &y = c.layers[l];
+    const size_t K = y.K, N = y.N;
+    y.Wm = cv.take<float>(K * N);
+    y.dW = cv.take<float>(K * N);
+    y.ldqf = (int)rup(K, 64);
+    y.qf_plane = (long long)rup(N, 128) * y.ldqf;
+    y.Qf = cv.take<uint16_t>((size_t)np * y.qf_plane);
+    if (l > 0) {
+      y.ldqb = (int)rup(N, 64);
+      y.qb_plane = (long long)rup(K, 128) * y.ldqb;
+      y.Qb = cv.take<uint16_t>((size_t)np * y.qb_plane);
+    }
+    long long per;
+    y.splits_w = choose_splits(c.M, wgrad_tiles(y.K, y.N), &per);
+    if (y.splits_w > 1 && (size_t)y.splits_w * K * N > part) part = (size_t)y.splits_w * K * N;
+    if (y.recurrent) {
+      y.Rm = cv.take<float>(N * N);
+      y.dR = cv.take<float>(N * N);
+      y.ldqr = (int)rup(N, 64);
+      y.qr_plane = (long long)rup(N, 128) * y.ldqr;
+      y.QRf = cv.take<uint16_t>((size_t)np * y.qr_plane);
+      y.QRb = cv.take<uint16_t>((size_t)np * y.qr_plane);
+      y.g[0] = cv.take<float>((size_t)c.B * y.ld);
+      y.g[1] = cv.take<float>((size_t)c.B * y.ld);
+      y.splits_r = choose_splits(c.M, wgrad_tiles(y.N, y.N), &per);
+      if (y.splits_r > 1 && (size_t)y.splits_r * N * N > part) part = (size_t)y.splits_r * N * N;
+    }
+    y.I = cv.take<float>(M * y.ld);
+    y.V = cv.take<float>(M * y.ld);
+    y.dI = cv.take<float>(M * y.ld);
+    if (y.spiking) {
+      y.S = cv.take<uint8_t>(M * y.ld);
+      y.dS = cv.take<float>(M * y.ld);
+    }
+  }
+  c.z = cv.take<float>((size_t)c.B * c.ldC);
+  c.dz = cv.take<float>((size_t)c.B * c.ldC);
+  c.tstar = cv.take<int>((size_t)c.B * c.ldC);
+  c.loss_b = cv.take<float>((size_t)c.B);
+  c.loss = cv.take<float>(64);
+  c.err_flag = cv.take<int>(64);
+  c.partial_elems = part;
+  c.partials = cv.take<float>(part ? part : 64);
+}
+
+void configure(snn_ctx &c, const snn_config *cfg) {
+  c.T = cfg->T; c.B = cfg->B; c.L = cfg->n_layers;
+  c.M = (long long)c.T * c.B;
+  c.sizes.assign(cfg->sizes, cfg->sizes + c.L + 1);
+  c.theta = cfg->threshold; c.slope = cfg->slope;
+  c.surrogate = cfg->surrogate; c.precision = cfg->precision;
+  c.nplanes = c.precision == SNN_PREC_FP32 ? 3 : 1;
+  c.layers.assign(c.L, Layer());
+  for (int l = 0; l < c.L; ++l) {
+    Layer &y = c.layers[l];
+    y.K = c.sizes[l]; y.N = c.sizes[l + 1];
+    y.ld = (int)rup(y.N, 8);
+    y.spiking = l < c.L - 1;
+    y.recurrent = y.spiking && cfg->recurrent && cfg->recurrent[l];
+    y.beta = cfg->beta[l];
+  }
+  c.C = c.sizes[c.L];
+  c.ldC = c.layers[c.L - 1].ld;
+}
+
+// ------------------------------------------------------------------ profiling brackets
+struct Bracket {
+  snn_ctx *c;
+  bool on;
+  Bracket(snn_ctx *ctx, int cls, int layer1) : c(ctx) {
+    on = c->prof.cls == cls && (c->prof.layer == 0 || c->prof.layer == layer1);
+    if (on) {
+      if (c->prof.used + 2 > c->prof.ev.size()) {
+        if (c->prof.ev.size() >= (1u << 16)) { on = false; return; }
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
+        c->prof.ev.push_back(a); c->prof.ev.push_back(b);
+      }
+      (void)hipEventRecord(c->prof.ev[c->prof.used], c->stream);
+    }
+  }
+  ~Bracket() {
+    if (on) {
+      (void)hipEventRecord(c->prof.ev[c->prof.used + 1], c->stream);
+      c->prof.used += 2;
+    }
+  }
+};
+
+// ------------------------------------------------------------------ launches
+hipError_t zero_async(snn_ctx *c, void *p, size_t bytes) {
+  const long long n = (long long)(bytes / 4);
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, (uint32_t *)p, n);
+  return hipGetLastError();
+}
+
+void set_terms(GemmArgs &a, int nterms, const int *tp, const int *tq) {
+  a.nterms = nterms; a.terms_p = 0; a.terms_q = 0;
+  for (int i = 0; i < nterms; ++i) { a.terms_p |= (unsigned)tp[i] << (4 * i); a.terms_q |= (unsigned)tq[i] << (4 * i); }
+}
+// Plane pairs (P plane, Q plane) of each product.  Weights have one plane when rounded to
+// bfloat16 and three for fp32 products; current gradients use hi+lo with rounded weights
+// and all pairs down to 2^-16 relative with fp32 products.
+const int kT0[6] = {0, 0, 0, 0, 0, 0};
+const int kT01[2] = {0, 1};
+const int kT012[3] = {0, 1, 2};
+const int kT6p[6] = {0, 0, 1, 0, 1, 2};
+const int kT6q[6] = {0, 1, 0, 2, 1, 0};
+
+int u8_align(const void *p, int ld, int valid, int want) {
+  const uintptr_t a = (uintptr_t)p;
+  if (want >= 8 && a % 8 == 0 && ld % 8 == 0 && valid % 8 == 0) return 8;
+  if (a % 4 == 0 && ld % 4 == 0 && valid % 4 == 0) return 4;
+  return 1;
+}
+
+// Spikes feeding layer index l: the input raster for l == 0, else S of the layer below.
+struct SpikeSrc { const uint8_t *p; int ld; int valid; };
+SpikeSrc spikes_below(snn_ctx *c, int l, const uint8_t *x) {
+  if (l == 0) return {x, c->sizes[0], c->sizes[0]};
+  return {c->layers[l - 1].S, c->layers[l - 1].ld, c->layers[l - 1].ld};
+}
+
+// I^l = S^{l-1} W^l over all T*B rows at once.
+int launch_current_gemm(snn_ctx *c, int l, const uint8_t *x) {
+  Layer &y = c->layers[l];
+  SpikeSrc s = spikes_below(c, l, x);
+  if (!s.p) return fail(c, SNN_ERR_NULL, "input raster is NULL");
+  GemmArgs a;
+  memset(&a, 0, sizeof a);
+  a.P = s.p; a.ldp = s.ld; a.kc = s.valid; a.p_align = u8_align(s.p, s.ld, s.valid, 8);
+  a.Q = y.Qf; a.ldq = y.ldqf; a.q_plane_stride = y.qf_plane;
+  a.C = y.I; a.ldc = y.ld; a.rows = (int)c->M; a.cols = y.N;
+  a.kc_per_split = (int)rup(a.kc, 64);
+  if (c->precision == SNN_PREC_FP32) set_terms(a, 3, kT0, kT012); else set_terms(a, 1, kT0, kT0);
+  Bracket br(c, SNN_K_CURRENT_GEMM, l + 1);
+  hipError_t e;
+  if (y.N <= 32) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 4, 1, 1, 1>(a, 1, c->stream);
+  else if (y.N <= 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 1>(a, 1, c->stream);
+  else e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 2>(a, 1, c->stream);
+  HIPCHK(c, e);
+  return SNN_OK;
+}
+
+// dS^{l-1} = dI^l W^l^T  (l >= 1).
+int launch_input_grad(snn_ctx *c, int l) {
+  Layer &y = c->layers[l];
+  Layer &below = c->layers[l - 1];
+  GemmArgs a;
+  memset(&a, 0, sizeof a);
+  a.P = y.dI; a.ldp = y.ld; a.kc = y.ld;
+  a.Q = y.Qb; a.ldq = y.ldqb; a.q_plane_stride = y.qb_plane;
+  a.C = below.dS; a.ldc = below.ld; a.rows = (int)c->M; a.cols = y.K;
+  a.kc_per_split = (int)rup(a.kc, 64);
+  Bracket br(c, SNN_K_INPUT_GRAD, l + 1);
+  hipError_t e;
+  if (c->precision == SNN_PREC_FP32) set_terms(a, 6, kT6p, kT6q); else set_terms(a, 2, kT01, kT0);
+  if (y.K <= 32) e = gemm_launch<P_F32S, Q_BF16, EPI_STORE, 4, 1, 1, 1>(a, 1, c->stream);
+  else e = gemm_launch<P_F32S, Q_BF16, EPI_STORE, 2, 2, 2, 2>(a, 1, c->stream);
+  HIPCHK(c, e);
+  return SNN_OK;
+}
+
+// out[rows x cols] = Sp^T G, contraction over the T*B rows, split over workgroups and
+// reduced in a fixed order.
+int launch_tn(snn_ctx *c, SpikeSrc s, int rows, const void *G, int ldg, int cols, float *out, int splits) {
+  GemmArgs a;
+  memset(&a, 0, sizeof a);
+  a.P = s.p; a.ldp = s.ld; a.p_ivalid = s.valid; a.p_align = u8_align(s.p, s.ld, s.valid, 4);
+  a.Q = G; a.ldq = ldg;
+  a.rows = rows; a.cols = cols; a.ldc = cols; a.kc = (int)c->M;
+  long long per;
+  int sp = choose_splits(c->M, wgrad_tiles(rows, cols), &per);
+  if (sp != splits) return fail(c, SNN_ERR_STATE, "internal: split count mismatch");
+  a.kc_per_split = (int)per;
+  a.c_split_stride = (long long)rows * cols;
+  a.C = splits > 1 ? c->partials : out;
+  hipError_t e;
+  if (c->precision == SNN_PREC_FP32) set_terms(a, 3, kT0, kT012); else set_terms(a, 2, kT0, kT01);
+  if (cols <= 32) e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 4, 1, 1, 1>(a, splits, c->stream);
+  else if (cols <= 64) e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 1>(a, splits, c->stream);
+  else e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 2>(a, splits, c->stream);
+  HIPCHK(c, e);
+  if (splits > 1) {
+    const long long n = (long long)rows * cols;
+    if (n % 4 == 0)
+      hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n / 4 + 63) / 64)), dim3(256), 0, c->stream,
+                         c->partials, splits, n, out, n);
+    else
+      hipLaunchKernelGGL(reduce_partials_scalar_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream,
+                         c->partials, splits, n, out, n);
+    HIPCHK(c, hipGetLastError());
+  }
+  return SNN_OK;
+}
+
+int launch_weight_grad(snn_ctx *c, int l, const uint8_t *x) {
+  Layer &y = c->layers[l];
+  SpikeSrc s = spikes_below(c, l, x);
+  if (!s.p) return fail(c, SNN_ERR_NULL, "input raster is NULL");
+  Bracket br(c, SNN_K_WEIGHT_GRAD, l + 1);
+  int rc = launch_tn(c, s, y.K, y.dI, y.ld, y.N, y.dW, y.splits_w);
+  if (rc) return rc;
+  if (y.recurrent) {
+    SpikeSrc own = {y.S, y.ld, y.ld};
+    rc = launch_tn(c, own, y.N, y.dI, y.ld, y.N, y.dR, y.splits_r);
+  }
+  return rc;
+}
+
+template <int VEC, int U>
+hipError_t lif_fwd_launch(snn_ctx *c, Layer &y) {
+  const long long stride = (long long)c->B * y.ld;
+  const long long threads = stride / VEC;
+  hipLaunchKernelGGL((lif_forward_kernel<VEC, U>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream,
+                     y.I, y.V, y.S, c->T, stride, y.beta, c->theta);
+  return hipGetLastError();
+}
+
+int launch_lif_forward(snn_ctx *c, int l) {
+  Layer &y = c->layers[l];
+  if (y.recurrent) {
+    Bracket br(c, SNN_K_RLIF_FORWARD, l + 1);
+    return rlif_forward(c->stream, c->precision == SNN_PREC_FP32, c->T, c->B, y.N, y.ld, y.I, y.V, y.S, y.QRf,
+                        y.ldqr, y.qr_plane, y.beta, c->theta) == hipSuccess
+               ? SNN_OK
+               : fail(c, SNN_ERR_HIP, "recurrent forward launch failed: %s", hipGetErrorString(hipGetLastError()));
+  }
+  Bracket br(c, SNN_K_LIF_FORWARD, l + 1);
+  const long long chains = (long long)c->B * y.ld;
+  hipError_t e;
+  if (chains >= (1 << 19)) e = lif_fwd_launch<4, 8>(c, y);
+  else if (chains >= (1 << 17)) e = lif_fwd_launch<2, 16>(c, y);
+  else e = lif_fwd_launch<1, 32>(c, y);
+  HIPCHK(c, e);
+  return SNN_OK;
+}
+
+template <int VEC, int U>
+hipError_t lif_rev_launch(snn_ctx *c, Layer &y) {
+  const long long stride = (long long)c->B * y.ld;
+  const long long threads = stride / VEC;
+  dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+#define SNN_REV(SU)                                                                                         \
+  hipLaunchKernelGGL((lif_reverse_kernel<VEC, U, SU>), grid, block, 0, c->stream, y.dS, y.V, y.dI, c->T, \
+                     stride, y.beta, c->theta, c->slope)
+  switch (c->surrogate) {
+    case 0: SNN_REV(0); break;
+    case 1: SNN_REV(1); break;
+    case 2: SNN_REV(2); break;
+    default: SNN_REV(3); break;
+  }
+#undef SNN_REV
+  return hipGetLastError();
+}
+
+int launch_lif_reverse(snn_ctx *c, int l) {
+  Layer &y = c->layers[l];
+  if (y.recurrent) {
+    Bracket br(c, SNN_K_RLIF_REVERSE, l + 1);
+    return rlif_reverse(c->stream, c->precision == SNN_PREC_FP32, c->T, c->B, y.N, y.ld, y.dS, y.V, y.dI, y.g[0],
+                        y.g[1], y.QRb, y.ldqr, y.qr_plane, y.beta, c->theta, c->surrogate, c->slope) == hipSuccess
+               ? SNN_OK
+               : fail(c, SNN_ERR_HIP, "recurrent reverse launch failed: %s", hipGetErrorString(hipGetLastError()));
+  }
+  Bracket br(c, SNN_K_LIF_REVERSE, l + 1);
+  const long long chains = (long long)c->B * y.ld;
+  hipError_t e;
+  if (chains >= (1 << 19)) e = lif_rev_launch<4, 4>(c, y);
+  else if (chains >= (1 << 17)) e = lif_rev_launch<2, 8>(c, y);
+  else e = lif_rev_launch<1, 16>(c, y);
+  HIPCHK(c, e);
+  return SNN_OK;
+}
+
+int launch_readout_forward(snn_ctx *c, const int32_t *labels) {
+  if (!labels) return fail(c, SNN_ERR_NULL, "labels are NULL");
+  Layer &y = c->layers[c->L - 1];
+  Bracket br(c, SNN_K_READOUT_FORWARD, c->L);
+  const int stride = c->B * c->ldC;
+  hipLaunchKernelGGL(readout_forward_kernel, dim3((stride + 255) / 256), dim3(256), 0, c->stream, y.I, y.V, c->z,
+                     c->tstar, c->T, stride, y.beta);
+  HIPCHK(c, hipGetLastError());
+  hipLaunchKernelGGL(cross_entropy_kernel, dim3((c->B + 3) / 4), dim3(256), 0, c->stream, c->z, labels, c->loss_b,
+                     c->dz, c->B, c->C, c->ldC, c->err_flag);
+  HIPCHK(c, hipGetLastError());
+  hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(256), 0, c->stream, c->loss_b, c->loss, c->B);
+  HIPCHK(c, hipGetLastError());
+  return SNN_OK;
+}
+
+int launch_readout_reverse(snn_ctx *c) {
+  Layer &y = c->layers[c->L - 1];
+  Bracket br(c, SNN_K_READOUT_REVERSE, c->L);
+  const int stride = c->B * c->ldC;
+  hipLaunchKernelGGL(readout_reverse_kernel, dim3((stride + 255) / 256), dim3(256), 0, c->stream, c->dz, c->tstar,
+                     y.dI, c->T, stride, y.beta);
+  HIPCHK(c, hipGetLastError());
+  return SNN_OK;
+}
+
+int launch_param_update(snn_ctx *c, float *W, const float *dW, float lr, int K, int N, uint16_t *Qf, int ldqf,
+                        long long qf_plane, uint16_t *Qb, int ldqb, long long qb_plane) {
+  dim3 grid((N + 31) / 32, (K + 31) / 32);
+  hipLaunchKernelGGL(param_update_kernel, grid, dim3(256), 0, c->stream, W, dW, lr, K, N, Qf, ldqf, qf_plane, Qb,
+                     ldqb, qb_plane, c->nplanes);
+  HIPCHK(c, hipGetLastError());
+  return SNN_OK;
+}
+
+int update_layer(snn_ctx *c, int l, bool with_grad, float lr) {
+  Layer &y = c->layers[l];
+  int rc = launch_param_update(c, y.Wm, with_grad ? y.dW : nullptr, lr, y.K, y.N, y.Qf, y.ldqf, y.qf_plane, y.Qb,
+                               y.ldqb, y.qb_plane);
+  if (rc) return rc;
+  if (y.recurrent)
+    rc = launch_param_update(c, y.Rm, with_grad ? y.dR : nullptr, lr, y.N, y.N, y.QRf, y.ldqr, y.qr_plane, y.QRb,
+                             y.ldqr, y.qr_plane);
+  return rc;
+}
+
+int check_err_flag(snn_ctx *c) {
+  int flag = 0;
+  HIPCHK(c, hipMemcpyAsync(&flag, c->err_flag, sizeof(int), hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  if (flag) {
+    HIPCHK(c, zero_async(c, c->err_flag, 256));
+    return fail(c, SNN_ERR_ARG, "a label was outside [0, C)");
+  }
+  return SNN_OK;
+}
+
+// Describes where a tensor lives: rows x cols elements, leading dimension, element size.
+struct TensorView { void *p; size_t rows, cols, ld, esz; };
+
+int view_of(snn_ctx *c, int tensor, int layer, TensorView *v, bool for_set) {
+  const size_t M = (size_t)c->M;
+  auto spiking_layer = [&](Layer **out) -> int {
+    if (layer < 1 || layer > c->L - 1) return fail(c, SNN_ERR_ARG, "layer %d is not a spiking layer", layer);
+    *out = &c->layers[layer - 1];
+    return SNN_OK;
+  };
+  auto any_layer = [&](Layer **out) -> int {
+    if (layer < 1 || layer > c->L) return fail(c, SNN_ERR_ARG, "layer %d out of range", layer);
+    *out = &c->layers[layer - 1];
+    return SNN_OK;
+  };
+  Layer *y = nullptr;
+  Layer &ro = c->layers[c->L - 1];
+  int rc;
+  switch (tensor) {
+    case SNN_T_WEIGHT:
+      if ((rc = any_layer(&y))) return rc;
+      *v = {y->Wm, (size_t)y->K, (size_t)y->N, (size_t)y->N, 4}; return SNN_OK;
+    case SNN_T_GRAD_W:
+      if ((rc = any_layer(&y))) return rc;
+      *v = {y->dW, (size_t)y->K, (size_t)y->N, (size_t)y->N, 4}; break;
+    case SNN_T_RWEIGHT:
+    case SNN_T_GRAD_R:
+      if ((rc = spiking_layer(&y))) return rc;
+      if (!y->recurrent) return fail(c, SNN_ERR_ARG, "layer %d is not recurrent", layer);
+      *v = {tensor == SNN_T_RWEIGHT ? y->Rm : y->dR, (size_t)y->N, (size_t)y->N, (size_t)y->N, 4};
+      if (tensor == SNN_T_RWEIGHT) return SNN_OK;
+      break;
+    case SNN_T_CURRENT:
+      if ((rc = spiking_layer(&y))) return rc;
+      *v = {y->I, M, (size_t)y->N, (size_t)y->ld, 4}; return SNN_OK;
+    case SNN_T_MEMBRANE:
+      if ((rc = spiking_layer(&y))) return rc;
+      *v = {y->V, M, (size_t)y->N, (size_t)y->ld, 4}; return SNN_OK;
+    case SNN_T_SPIKES:
+      if ((rc = spiking_layer(&y))) return rc;
+      *v = {y->S, M, (size_t)y->N, (size_t)y->ld, 1}; return SNN_OK;
+    case SNN_T_D_SPIKES:
+      if ((rc = spiking_layer(&y))) return rc;
+      *v = {y->dS, M, (size_t)y->N, (size_t)y->ld, 4}; return SNN_OK;
+    case SNN_T_D_CURRENT:
+      if ((rc = spiking_layer(&y))) return rc;
+      *v = {y->dI, M, (size_t)y->N, (size_t)y->ld, 4}; return SNN_OK;
+    case SNN_T_READOUT_CURRENT: *v = {ro.I, M, (size_t)c->C, (size_t)c->ldC, 4}; return SNN_OK;
+    case SNN_T_READOUT_TRACE: *v = {ro.V, M, (size_t)c->C, (size_t)c->ldC, 4}; break;
+    case SNN_T_LOGITS: *v = {c->z, (size_t)c->B, (size_t)c->C, (size_t)c->ldC, 4}; break;
+    case SNN_T_ARGMAX_T: *v = {c->tstar, (size_t)c->B, (size_t)c->C, (size_t)c->ldC, 4}; return SNN_OK;
+    case SNN_T_D_LOGITS: *v = {c->dz, (size_t)c->B, (size_t)c->C, (size_t)c->ldC, 4}; return SNN_OK;
+    case SNN_T_D_READOUT_CURRENT:
+      *v = {ro.dI, M, (size_t)c->C, (size_t)c->ldC, 4}; return SNN_OK;
+    case SNN_T_LOSS: *v = {c->loss, 1, 1, 1, 4}; break;
+    case SNN_T_LOSS_PER_SAMPLE: *v = {c->loss_b, 1, (size_t)c->B, (size_t)c->B, 4}; break;
+    default: return fail(c, SNN_ERR_ARG, "unknown tensor id %d", tensor);
+  }
+  if (for_set) return fail(c, SNN_ERR_ARG, "tensor %d cannot be set", tensor);
+  return SNN_OK;
+}
+
+}  // namespace
+
+// ====================================================================== C ABI
+extern "C" {
+
+int32_t snn_workspace_bytes(const snn_config *cfg, size_t *bytes) {
+  int rc = validate(cfg);
+  if (rc) return rc;
+  if (!bytes) return fail(nullptr, SNN_ERR_NULL, "bytes is NULL");
+  snn_ctx tmp;
+  configure(tmp, cfg);
+  Carver cv(nullptr);
+  carve(tmp, cv);
+  *bytes = cv.off;
+  return SNN_OK;
+}
+
+int32_t snn_init(const snn_config *cfg, void *workspace_dev, size_t workspace_bytes, const float *const *W_host,
+                 const float *const *R_host, void *hip_stream, snn_ctx **out) {
+  int rc = validate(cfg);
+  if (rc) return rc;
+  if (!workspace_dev || !W_host || !out) return fail(nullptr, SNN_ERR_NULL, "workspace, W_host or out is NULL");
+  if ((uintptr_t)workspace_dev % 256 != 0) return fail(nullptr, SNN_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  snn_ctx *c = new snn_ctx();
+  configure(*c, cfg);
+  Carver cv((char *)workspace_dev);
+  carve(*c, cv);
+  if (cv.off > workspace_bytes) {
+    delete c;
+    return fail(nullptr, SNN_ERR_WORKSPACE, "workspace too small: need %zu bytes, got %zu", cv.off, workspace_bytes);
+  }
+  for (int l = 0; l < c->L; ++l) {
+    if (!W_host[l]) { delete c; return fail(nullptr, SNN_ERR_NULL, "W_host[%d] is NULL", l); }
+    if (c->layers[l].recurrent && (!R_host || !R_host[l])) {
+      delete c;
+      return fail(nullptr, SNN_ERR_NULL, "R_host[%d] is NULL for a recurrent layer", l);
+    }
+  }
+  c->ws = (char *)workspace_dev; c->ws_bytes = cv.off;
+  c->stream = (hipStream_t)hip_stream;
+  auto bail = [&](hipError_t e, const char *what) {
+    fail(nullptr, SNN_ERR_HIP, "%s failed: %s", what, hipGetErrorString(e));
+    delete c;
+    return (int32_t)SNN_ERR_HIP;
+  };
+  int ndev = 0;
+  hipError_t e = hipGetDeviceCount(&ndev);
+  if (e != hipSuccess || ndev == 0) return bail(e != hipSuccess ? e : hipErrorNoDevice, "hipGetDeviceCount");
+  if ((e = hipMemsetAsync(c->ws, 0, c->ws_bytes, c->stream)) != hipSuccess) return bail(e, "hipMemsetAsync(workspace)");
+  for (int l = 0; l < c->L; ++l) {
+    Layer &y = c->layers[l];
+    if ((e = hipMemcpyAsync(y.Wm, W_host[l], sizeof(float) * y.K * y.N, hipMemcpyHostToDevice, c->stream)) != hipSuccess)
+      return bail(e, "hipMemcpyAsync(W)");
+    if (y.recurrent &&
+        (e = hipMemcpyAsync(y.Rm, R_host[l], sizeof(float) * y.N * y.N, hipMemcpyHostToDevice, c->stream)) != hipSuccess)
+      return bail(e, "hipMemcpyAsync(R)");
+    if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail(e, "hipStreamSynchronize");
+    if (update_layer(c, l, false, 0.f) != SNN_OK) { g_err = c->err; delete c; return SNN_ERR_HIP; }
+  }
+  if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail(e, "hipStreamSynchronize");
+  *out = c;
+  return SNN_OK;
+}
+
+int32_t snn_forward(snn_ctx *c, const uint8_t *x_dev, const int32_t *labels_dev, float *loss_host) {
+  if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
+  if (!x_dev || !labels_dev) return fail(c, SNN_ERR_NULL, "x_dev or labels_dev is NULL");
+  c->x_dev = x_dev; c->labels_dev = labels_dev;
+  int rc;
+  for (int l = 0; l < c->L; ++l) {
+    if ((rc = launch_current_gemm(c, l, x_dev))) return rc;
+    if (c->layers[l].spiking) {
+      if ((rc = launch_lif_forward(c, l))) return rc;
+    } else {
+      if ((rc = launch_readout_forward(c, labels_dev))) return rc;
+    }
+  }
+  c->state = 1;
+  if (loss_host) {
+    HIPCHK(c, hipMemcpyAsync(loss_host, c->loss, sizeof(float), hipMemcpyDeviceToHost, c->stream));
+    if ((rc = check_err_flag(c))) return rc;
+  }
+  return SNN_OK;
+}
+
+int32_t snn_backward(snn_ctx *c) {
+  if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
+  if (c->state < 1) return fail(c, SNN_ERR_STATE, "snn_backward needs a preceding snn_forward");
+  int rc;
+  if ((rc = launch_readout_reverse(c))) return rc;
+  for (int l = c->L - 1; l >= 0; --l) {
+    if (c->layers[l].spiking && (rc = launch_lif_reverse(c, l))) return rc;
+    if ((rc = launch_weight_grad(c, l, c->x_dev))) return rc;
+    if (l > 0 && (rc = launch_input_grad(c, l))) return rc;
+  }
+  c->state = 2;
+  return SNN_OK;
+}
+
+int32_t snn_sgd_step(snn_ctx *c, float lr) {
+  if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
+  if (c->state < 2) return fail(c, SNN_ERR_STATE, "snn_sgd_step needs a preceding snn_backward");
+  Bracket br(c, SNN_K_SGD, 0);
+  for (int l = 0; l < c->L; ++l) {
+    int rc = update_layer(c, l, true, lr);
+    if (rc) return rc;
+  }
+  c->state = 0;
+  return SNN_OK;
+}
+
+int32_t snn_get_tensor(snn_ctx *c, int32_t tensor, int32_t layer, void *dst, size_t bytes) {
+  if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
+  if (!dst) return fail(c, SNN_ERR_NULL, "dst_host is NULL");
+  TensorView v;
+  int rc = view_of(c, tensor, layer, &v, false);
+  if (rc) return rc;
+  if (bytes != v.rows * v.cols * v.esz)
+    return fail(c, SNN_ERR_SHAPE, "tensor %d needs %zu bytes, got %zu", tensor, v.rows * v.cols * v.esz, bytes);
+  HIPCHK(c, hipMemcpy2DAsync(dst, v.cols * v.esz, v.p, v.ld * v.esz, v.cols * v.esz, v.rows, hipMemcpyDeviceToHost,
+                             c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return check_err_flag(c);
+}
+
+int32_t snn_set_tensor(snn_ctx *c, int32_t tensor, int32_t layer, const void *src, size_t bytes) {
+  if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
+  if (!src) return fail(c, SNN_ERR_NULL, "src_host is NULL");
+  TensorView v;
+  int rc = view_of(c, tensor, layer, &v, true);
+  if (rc) return rc;
+  if (bytes != v.rows * v.cols * v.esz)
+    return fail(c, SNN_ERR_SHAPE, "tensor %d needs %zu bytes, got %zu", tensor, v.rows * v.cols * v.esz, bytes);
+  HIPCHK(c, hipMemcpy2DAsync(v.p, v.ld * v.esz, src, v.cols * v.esz, v.cols * v.esz, v.rows, hipMemcpyHostToDevice,
+                             c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  if (tensor == SNN_T_WEIGHT || tensor == SNN_T_RWEIGHT) {
+    if ((rc = update_layer(c, layer - 1, false, 0.f))) return rc;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    c->state = 0;
+  }
+  return SNN_OK;
+}
+
+int32_t snn_run_step(snn_ctx *c, int32_t step, int32_t layer, const uint8_t *x_dev, const int32_t *labels_dev) {
+  if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
+  if (layer < 1 || layer > c->L) return fail(c, SNN_ERR_ARG, "layer %d out of range", layer);
+  const int l = layer - 1;
+  const bool spiking = c->layers[l].spiking;
+  switch (step) {
+    case SNN_STEP_CURRENT_GEMM: return launch_current_gemm(c, l, x_dev);
+    case SNN_STEP_LIF_FORWARD:
+      if (!spiking) return fail(c, SNN_ERR_ARG, "layer %d is not spiking", layer);
+      return launch_lif_forward(c, l);
+    case SNN_STEP_READOUT_FORWARD: return launch_readout_forward(c, labels_dev);
+    case SNN_STEP_READOUT_REVERSE: return launch_readout_reverse(c);
+    case SNN_STEP_LIF_REVERSE:
+      if (!spiking) return fail(c, SNN_ERR_ARG, "layer %d is not spiking", layer);
+      return launch_lif_reverse(c, l);
+    case SNN_STEP_WEIGHT_GRAD: return launch_weight_grad(c, l, x_dev);
+    case SNN_STEP_INPUT_GRAD:
+      if (l == 0) return fail(c, SNN_ERR_ARG, "layer 1 has no input gradient");
+      return launch_input_grad(c, l);
+    default: return fail(c, SNN_ERR_ARG, "unknown step %d", step);
+  }
+}
+
+int32_t snn_profile_select(snn_ctx *c, int32_t kernel_class, int32_t layer) {
+  if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
+  if (kernel_class < SNN_K_NONE || kernel_class >= SNN_K_COUNT) return fail(c, SNN_ERR_ARG, "unknown kernel class");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  c->prof.cls = kernel_class; c->prof.layer = layer; c->prof.used = 0;
+  return SNN_OK;
+}
+
+int32_t snn_profile_read(snn_ctx *c, double *total_ms, int64_t *launches) {
+  if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
+  if (!total_ms || !launches) return fail(c, SNN_ERR_NULL, "output pointer is NULL");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  double sum = 0;
+  for (size_t i = 0; i + 1 < c->prof.used; i += 2) {
+    float ms = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&ms, c->prof.ev[i], c->prof.ev[i + 1]));
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = (int64_t)(c->prof.used / 2);
+  c->prof.used = 0;
+  return SNN_OK;
+}
+
+int32_t snn_destroy(snn_ctx *c) {
+  if (!c) return SNN_OK;
+  (void)hipStreamSynchronize(c->stream);
+  for (hipEvent_t e : c->prof.ev) (void)hipEventDestroy(e);
+  delete c;
+  return SNN_OK;
+}
+
+const char *snn_last_error(const snn_ctx *c) { return c ? c->err.c_str() : g_err.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,252 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Tolerances are those of tests/parity.py: potentials, readout and loss within
+1e-5 (scaled by max(1,|x|)), gradients within 1e-4 per tensor in max norm and 2-norm, spike
+trains identical except decisions whose potential is within 1e-5 of the threshold (counted).
+"""
+import json
+
+import numpy as np
+import pytest
+
+import workloads
+from oracle import snn_oracle as O
+from tests import parity
+from tests.helpers import net_of
+
+pytestmark = pytest.mark.gpu
+
+
+def make(wl, inp):
+    from paper_2402_18994_amd.binding import from_workload
+    return from_workload(wl, inp)
+
+
+def full_step_parity(wl, w_gain=1.0, lr=0.1, seed=None, grad_tol=parity.TOL_GRAD, check_sgd=True):
+    inp = workloads.generate(wl, w_gain=w_gain, seed=seed)
+    net = net_of(wl)
+    snn = make(wl, inp)
+    print(f"\n[case] {wl.name} T={wl.T} B={wl.B} sizes={wl.sizes} rec={wl.recurrent} "
+          f"{wl.precision} {wl.surrogate} gain={w_gain}", flush=True)
+    rep = {}
+    loss = snn.forward(inp.X, inp.labels)
+    tr = parity.compare_forward(net, inp, snn, loss, rep)
+    snn.backward()
+    gr = parity.compare_backward(net, inp, snn, tr, rep, tol=grad_tol)
+    if check_sgd:
+        snn.sgd_step(lr)
+        Wn, Rn = O.sgd_step(inp.W, inp.R, gr, lr)
+        for l in range(net.L):
+            got = snn.get_tensor("weight", l + 1)
+            # the update itself is one fp32 multiply-add on the device's own gradient
+            assert np.abs(got - Wn[l]).max() <= grad_tol * lr * np.abs(gr.dW[l]).max() + 1e-7 * np.abs(Wn[l]).max()
+        for l in range(net.L - 1):
+            if inp.R[l] is not None:
+                got = snn.get_tensor("rweight", l + 1)
+                assert np.abs(got - Rn[l]).max() <= grad_tol * lr * np.abs(gr.dR[l]).max() + 1e-7 * np.abs(Rn[l]).max()
+        # the next forward must see the updated weights (operand copies refreshed)
+        W2 = [snn.get_tensor("weight", l + 1) for l in range(net.L)]
+        R2 = [snn.get_tensor("rweight", l + 1) if inp.R[l] is not None else None for l in range(net.L - 1)]
+        inp2 = workloads.Inputs(X=inp.X, W=W2, R=R2, labels=inp.labels, rates=inp.rates)
+        loss2 = snn.forward(inp.X, inp.labels)
+        rep2 = {}
+        parity.compare_forward(net, inp2, snn, loss2, rep2)
+        rep["loss_after_step"] = loss2
+        rep["imposed_after_step"] = rep2["imposed_decisions"]
+    rep["loss"] = loss
+    print(json.dumps(rep), flush=True)
+    snn.destroy()
+    return rep
+
+
+# ---------------------------------------------------------------- feed-forward, fp32 products
+@pytest.mark.parametrize("gain", [1.0, 3.0])
+def test_tiny_ff_fp32(gain):
+    rep = full_step_parity(workloads.CONFIGS["tiny_ff"], w_gain=gain)
+    if gain == 3.0:
+        assert rep["spike_rate"][0] > 0.02
+
+
+@pytest.mark.parametrize("surrogate,slope", [("superspike", 25.0), ("arctan", 2.0), ("sigmoid", 4.0),
+                                             ("triangular", 0.5)])
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_ragged_shapes(surrogate, slope, precision):
+    """Sizes that are multiples of nothing: ragged row, column and contraction tails in every
+    product, byte-aligned input rows, a 3-class readout, T*B not a multiple of any tile."""
+    wl = workloads.Workload(name="ragged", index=11, T=37, B=7, sizes=(45, 29, 13, 3), recurrent=(False, False),
+                            beta=(0.9, 0.85, 0.8), theta=1.0, surrogate=surrogate, slope=slope,
+                            precision=precision, rate_lo=0.1, rate_hi=0.3)
+    rep = full_step_parity(wl, w_gain=2.5)
+    assert rep["spike_rate"][0] > 0.01 and rep["spike_rate"][1] > 0.001
+
+
+def test_multi_tile_fp32_theta_not_one():
+    """Several row tiles, several column tiles, several contraction tiles and splits; theta != 1
+    exercises the reset magnitude of Eq. 2."""
+    wl = workloads.Workload(name="multitile", index=12, T=40, B=24, sizes=(300, 200, 136, 20),
+                            recurrent=(False, False), beta=(0.92, 0.9, 0.95), theta=0.75, surrogate="superspike",
+                            slope=10.0, precision="fp32", rate_lo=0.02, rate_hi=0.1)
+    rep = full_step_parity(wl, w_gain=2.0)
+    assert rep["spike_rate"][1] > 0.005
+
+
+# ---------------------------------------------------------------- headline configuration, full size
+@pytest.mark.parametrize("gain", [1.0, 3.0])
+def test_shd_ff128_full_size(gain):
+    rep = full_step_parity(workloads.CONFIGS["shd_ff128"], w_gain=gain)
+    if gain == 3.0:
+        assert rep["spike_rate"][0] > 0.01 and rep["spike_rate"][1] > 0.01
+
+
+def test_shd_ff128_fp32_products():
+    wl = workloads.CONFIGS["shd_ff128"].scaled(precision="fp32", T=64, B=64)
+    full_step_parity(wl, w_gain=3.0)
+
+
+# ---------------------------------------------------------------- recurrent layers
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_recurrent_small(precision):
+    wl = workloads.Workload(name="rec_small", index=13, T=30, B=10, sizes=(50, 40, 24, 5), recurrent=(True, True),
+                            beta=(0.9, 0.9, 0.9), theta=1.0, surrogate="superspike", slope=25.0,
+                            precision=precision, rate_lo=0.05, rate_hi=0.2, rec_gain=1.0)
+    rep = full_step_parity(wl, w_gain=2.5)
+    assert rep["spike_rate"][0] > 0.01 and rep["spike_rate"][1] > 0.005
+
+
+@pytest.mark.parametrize("gain", [1.0, 3.0])
+def test_shd_rec128_full_size(gain):
+    full_step_parity(workloads.CONFIGS["shd_rec128"], w_gain=gain)
+
+
+# ---------------------------------------------------------------- single steps on imposed inputs
+def test_single_steps_on_oracle_tensors():
+    """Teacher forcing: each kernel is run alone on the oracle's own input tensors, so a wrong
+    kernel cannot hide behind (or be blamed on) another one."""
+    wl = workloads.Workload(name="steps", index=14, T=33, B=9, sizes=(70, 150, 66, 10), recurrent=(False, False),
+                            beta=(0.9, 0.9, 0.9), theta=1.0, surrogate="arctan", slope=2.0, precision="fp32",
+                            rate_lo=0.05, rate_hi=0.2)
+    inp = workloads.generate(wl, w_gain=2.5)
+    net = net_of(wl)
+    tr = O.forward(net, inp.X, inp.W, inp.R, inp.labels)
+    gr = O.backward(net, inp.X, inp.W, inp.R, inp.labels, tr)
+    snn = make(wl, inp)
+    # current products
+    snn.run_step("current_gemm", 1, x=inp.X)
+    parity.close_state("I1", snn.get_tensor("current", 1), tr.I[0])
+    snn.set_tensor("spikes", 1, tr.S[0].astype(np.uint8))
+    snn.run_step("current_gemm", 2)
+    parity.close_state("I2", snn.get_tensor("current", 2), tr.I[1])
+    snn.set_tensor("spikes", 2, tr.S[1].astype(np.uint8))
+    snn.run_step("current_gemm", 3)
+    parity.close_state("J", snn.get_tensor("readout_current"), tr.J)
+    # scans
+    snn.set_tensor("current", 2, tr.I[1])
+    snn.run_step("lif_forward", 2)
+    S2 = snn.get_tensor("spikes", 2)
+    near = np.abs(tr.V[1] - net.theta) <= parity.BAND
+    assert np.array_equal(S2[~near], tr.S[1].astype(np.uint8)[~near])
+    if np.array_equal(S2, tr.S[1].astype(np.uint8)):
+        parity.close_state("V2", snn.get_tensor("membrane", 2), tr.V[1])
+    snn.set_tensor("readout_current", 0, tr.J)
+    snn.run_step("readout_forward", 3, labels=inp.labels)
+    parity.close_state("Y", snn.get_tensor("readout_trace"), tr.Y)
+    assert np.array_equal(snn.get_tensor("argmax_t"), tr.tstar)
+    assert abs(snn.get_tensor("loss")[0] - tr.loss) <= 1e-5 * tr.loss
+    parity.close_grad("dz", snn.get_tensor("d_logits"), gr.dz)
+    # reverse steps
+    snn.set_tensor("d_logits", 0, gr.dz)
+    snn.set_tensor("argmax_t", 0, tr.tstar.astype(np.int32))
+    snn.run_step("readout_reverse", 3)
+    parity.close_grad("dJ", snn.get_tensor("d_readout_current"), gr.dJ)
+    snn.set_tensor("d_spikes", 2, gr.dS[1])
+    snn.set_tensor("membrane", 2, tr.V[1])
+    snn.run_step("lif_reverse", 2)
+    parity.close_grad("dI2", snn.get_tensor("d_current", 2), gr.dI[1])
+    snn.set_tensor("d_current", 2, gr.dI[1])
+    snn.set_tensor("spikes", 1, tr.S[0].astype(np.uint8))
+    snn.run_step("weight_grad", 2)
+    parity.close_grad("dW2", snn.get_tensor("grad_w", 2), gr.dW[1])
+    snn.run_step("input_grad", 2)
+    parity.close_grad("dS1", snn.get_tensor("d_spikes", 1), gr.dS[0])
+    snn.set_tensor("d_current", 1, gr.dI[0])
+    snn.run_step("weight_grad", 1, x=inp.X)
+    parity.close_grad("dW1", snn.get_tensor("grad_w", 1), gr.dW[0])
+    snn.set_tensor("d_readout_current", 0, gr.dJ)
+    snn.set_tensor("spikes", 2, tr.S[1].astype(np.uint8))
+    snn.run_step("weight_grad", 3)
+    parity.close_grad("dW3", snn.get_tensor("grad_w", 3), gr.dW[2])
+    snn.run_step("input_grad", 3)
+    parity.close_grad("dS2", snn.get_tensor("d_spikes", 2), gr.dS[1])
+    snn.destroy()
+
+
+# ---------------------------------------------------------------- invariants, errors, repeatability
+def test_silent_network_and_invariants():
+    wl = workloads.CONFIGS["tiny_ff"]
+    inp = workloads.generate(wl)
+    zero = workloads.Inputs(X=inp.X, W=[np.zeros_like(w) for w in inp.W], R=inp.R, labels=inp.labels, rates=inp.rates)
+    snn = make(wl, zero)
+    loss = snn.forward(inp.X, inp.labels)
+    assert abs(loss - np.log(10.0)) < 1e-6
+    snn.backward()
+    assert snn.get_tensor("spikes", 1).sum() == 0
+    for l in (1, 2):
+        assert np.all(snn.get_tensor("grad_w", l) == 0)
+    snn.destroy()
+    snn = make(wl, workloads.generate(wl, w_gain=3.0))
+    inp = workloads.generate(wl, w_gain=3.0)
+    snn.forward(inp.X, inp.labels)
+    snn.backward()
+    assert np.all(snn.get_tensor("spikes", 1)[0] == 0)          # V_0 = 0
+    assert np.all(snn.get_tensor("d_current", 1)[-1] == 0)      # last current never reaches the loss
+    assert np.abs(snn.get_tensor("d_logits").sum(axis=1)).max() < 1e-7
+    snn.destroy()
+
+
+def test_repeatable_bit_for_bit():
+    wl = workloads.CONFIGS["shd_ff128"].scaled(T=32, B=64)
+    inp = workloads.generate(wl, w_gain=3.0)
+    outs = []
+    for _ in range(2):
+        snn = make(wl, inp)
+        snn.forward(inp.X, inp.labels)
+        snn.backward()
+        outs.append([snn.get_tensor("grad_w", l + 1) for l in range(3)] + [snn.get_tensor("membrane", 2)])
+        snn.destroy()
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+
+
+def test_error_paths():
+    from paper_2402_18994_amd.binding import SnnError
+    wl = workloads.CONFIGS["tiny_ff"]
+    inp = workloads.generate(wl)
+    snn = make(wl, inp)
+    with pytest.raises(SnnError) as e:
+        snn.backward()
+    assert e.value.status == 5
+    with pytest.raises(SnnError) as e:
+        snn.sgd_step(0.1)
+    assert e.value.status == 5
+    bad = inp.labels.copy(); bad[3] = 10
+    with pytest.raises(SnnError) as e:
+        snn.forward(inp.X, bad)
+    assert e.value.status == 2
+    snn.forward(inp.X, inp.labels)                      # flag was cleared
+    import ctypes as C
+    buf = np.zeros(5, np.float32)
+    assert snn.lib.snn_get_tensor(snn.ctx, 0, 1, buf.ctypes.data, buf.nbytes) == 3        # wrong size
+    assert snn.lib.snn_get_tensor(snn.ctx, 99, 1, buf.ctypes.data, buf.nbytes) == 2       # unknown tensor
+    assert snn.lib.snn_get_tensor(snn.ctx, 1, 1, buf.ctypes.data, buf.nbytes) == 2        # not recurrent
+    assert snn.lib.snn_set_tensor(snn.ctx, 2, 1, buf.ctypes.data, buf.nbytes) == 2        # gradients not settable
+    assert snn.lib.snn_run_step(snn.ctx, 6, 1, None, None) == 2                           # no input grad for layer 1
+    assert snn.lib.snn_forward(snn.ctx, None, None, None) == 1
+    # a workspace that is too small or misaligned is refused
+    import torch
+    from paper_2402_18994_amd import binding
+    cfg = binding._Cfg(wl.T, wl.B, wl.sizes, wl.recurrent, wl.beta, wl.theta, wl.surrogate, wl.slope, wl.precision)
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    Wp = (C.c_void_p * 2)(*[np.ascontiguousarray(w).ctypes.data for w in inp.W])
+    ctx = C.c_void_p(None)
+    assert snn.lib.snn_init(C.byref(cfg.c), small.data_ptr(), 1024, Wp, None, None, C.byref(ctx)) == 4
+    assert snn.lib.snn_init(C.byref(cfg.c), small.data_ptr() + 1, 1 << 30, Wp, None, None, C.byref(ctx)) == 4
+    snn.destroy()
