@@ -32,6 +32,15 @@ __device__ __forceinline__ uint32_t bf16_piece(float x, int plane) {
 }
 __device__ __forceinline__ uint32_t pack2(uint32_t lo16, uint32_t hi16) { return lo16 | (hi16 << 16); }
 
+// "HL" form of a value entering a bfloat16 product with better than bfloat16 accuracy:
+// hi = bf16(x) in bits 0..15, lo = bf16(x - hi) in bits 16..31; hi + lo = x to 2^-16 relative.
+// (The casts compile to v_cvt_pk_bf16_f32.)
+__device__ __forceinline__ uint32_t pack_hl(float x) {
+  const __bf16 h = (__bf16)x;
+  const __bf16 l = (__bf16)(x - (float)h);
+  return (uint32_t)__builtin_bit_cast(unsigned short, h) | ((uint32_t)__builtin_bit_cast(unsigned short, l) << 16);
+}
+
 // Two 0/1 bytes -> two bfloat16 (0.0 or 1.0) in one dword: bytes sit in bits 0 and 16.
 __device__ __forceinline__ uint32_t spikes2_to_bf16(uint32_t two_bytes_spread) {
   return (two_bytes_spread & 0x00010001u) * 0x3F80u;

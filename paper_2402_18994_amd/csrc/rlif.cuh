@@ -16,17 +16,6 @@ static hipError_t fill_zero(hipStream_t st, void *p, size_t bytes) {
   return hipGetLastError();
 }
 
-static const int kR0[6] = {0, 0, 0, 0, 0, 0};
-static const int kR012[3] = {0, 1, 2};
-static const int kR6p[6] = {0, 0, 1, 0, 1, 2};
-static const int kR6q[6] = {0, 1, 0, 2, 1, 0};
-static const int kR01[2] = {0, 1};
-
-static void rl_terms(GemmArgs &a, int n, const int *tp, const int *tq) {
-  a.nterms = n; a.terms_p = 0; a.terms_q = 0;
-  for (int i = 0; i < n; ++i) { a.terms_p |= (unsigned)tp[i] << (4 * i); a.terms_q |= (unsigned)tq[i] << (4 * i); }
-}
-
 // I, V [T][B][ld] fp32, S [T][B][ld] bytes; QRf[plane][to][from] bfloat16.
 static hipError_t rlif_forward(hipStream_t st, bool fp32, int T, int B, int N, int ld, const float *I, float *V,
                                uint8_t *S, const uint16_t *QRf, int ldqr, long long qr_plane, float beta,
@@ -42,24 +31,25 @@ static hipError_t rlif_forward(hipStream_t st, bool fp32, int T, int B, int N, i
   a.rows = B; a.cols = N; a.ldc = ld;
   a.kc_per_split = (ld + 63) / 64 * 64;
   a.beta = beta; a.theta = theta;
-  if (fp32) rl_terms(a, 3, kR0, kR012); else rl_terms(a, 1, kR0, kR0);
   for (int t = 0; t + 1 < T; ++t) {
     a.P = S + t * stride;
     a.e_cur = I + t * stride; a.e_v = V + t * stride; a.e_s = S + t * stride;
     a.e_out_f = V + (t + 1) * stride; a.e_out_s = S + (t + 1) * stride;
-    if ((e = gemm_launch<P_U8, Q_BF16, EPI_RLIF_FWD, 1, 4, 1, 1>(a, 1, st)) != hipSuccess) return e;
+    if (fp32) e = gemm_launch<P_U8, Q_BF16, EPI_RLIF_FWD, 1, 4, 1, 1, 3>(a, 1, st);
+    else e = gemm_launch<P_U8, Q_BF16, EPI_RLIF_FWD, 1, 4, 1, 1, 1>(a, 1, st);
+    if (e != hipSuccess) return e;
   }
   return hipSuccess;
 }
 
-// dS, V, dI [T][B][ld] fp32; g0, g1 [B][ld] fp32
-// scratch for dL/dV_{t+1}; QRb[plane][from][to] bfloat16.
+// dS, V [T][B][ld] fp32; dI [T][B][ld] dwords (fp32, or HL with rounded weights); g0, g1
+// [B][ld] fp32 scratch for dL/dV_{t+1}; QRb[plane][from][to] bfloat16.
 static hipError_t rlif_reverse(hipStream_t st, bool fp32, int T, int B, int N, int ld, const float *dS, const float *V,
-                               float *dI, float *g0, float *g1, const uint16_t *QRb, int ldqr, long long qr_plane,
-                               float beta, float theta, int surrogate, float slope) {
+                               uint32_t *dI, float *g0, float *g1, const uint16_t *QRb, int ldqr,
+                               long long qr_plane, float beta, float theta, int surrogate, float slope) {
   const size_t stride = (size_t)B * ld;
   hipError_t e;
-  if ((e = fill_zero(st, g0, stride * 4)) != hipSuccess) return e;                       // g_T = 0
+  if ((e = fill_zero(st, g0, stride * 4)) != hipSuccess) return e;                              // g_T = 0
   if ((e = fill_zero(st, dI + (size_t)(T - 1) * stride, stride * 4)) != hipSuccess) return e;   // dI_{T-1} = 0
   GemmArgs a;
   memset(&a, 0, sizeof a);
@@ -68,7 +58,7 @@ static hipError_t rlif_reverse(hipStream_t st, bool fp32, int T, int B, int N, i
   a.rows = B; a.cols = N; a.ldc = ld;
   a.kc_per_split = (ld + 63) / 64 * 64;
   a.beta = beta; a.theta = theta; a.surrogate = surrogate; a.slope = slope;
-  if (fp32) rl_terms(a, 6, kR6p, kR6q); else rl_terms(a, 2, kR01, kR0);
+  a.e_di_hl = fp32 ? 0 : 1;
   float *g[2] = {g0, g1};
   int cur = 0;
   for (int t = T - 1; t >= 0; --t) {
@@ -76,7 +66,9 @@ static hipError_t rlif_reverse(hipStream_t st, bool fp32, int T, int B, int N, i
     a.e_cur = dS + t * stride; a.e_v = V + t * stride;
     a.e_g = g[cur]; a.e_out_f = g[cur ^ 1];
     a.e_out_di = t > 0 ? dI + (size_t)(t - 1) * stride : nullptr;
-    if ((e = gemm_launch<P_F32S, Q_BF16, EPI_RLIF_REV, 1, 4, 1, 1>(a, 1, st)) != hipSuccess) return e;
+    if (fp32) e = gemm_launch<P_F32S, Q_BF16, EPI_RLIF_REV, 1, 4, 1, 1, 3>(a, 1, st);
+    else e = gemm_launch<P_HL, Q_BF16, EPI_RLIF_REV, 1, 4, 1, 1, 1>(a, 1, st);
+    if (e != hipSuccess) return e;
     cur ^= 1;
   }
   return hipSuccess;

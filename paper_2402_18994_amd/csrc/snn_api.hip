@@ -7,6 +7,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -36,9 +37,11 @@ struct Layer {
   long long qr_plane = 0;
   float *I = nullptr, *V = nullptr, *dS = nullptr;   // [M][ld]; readout: I = J, V = Y
   uint8_t *S = nullptr;
-  float *dI = nullptr;                                // [M][ld]; readout: dJ
+  uint32_t *dI = nullptr;                             // [M][ld] fp32 bits or HL; readout: dJ
   float *g[2] = {nullptr, nullptr};                   // recurrent reverse state [B][ld]
-  int splits_w = 1, splits_r = 1;
+  int splits_w = 1, splits_r = 1;                     // contraction splits of dW and dR
+  long long per_w = 0, per_r = 0;                     // rows per split
+  float *part_w = nullptr, *part_r = nullptr;         // per-split partial results
 };
 
 struct Prof {
@@ -56,11 +59,10 @@ struct snn_ctx {
   std::vector<Layer> layers;      // index 0..L-1  (text layer l = index + 1)
   float theta = 1.f, slope = 1.f;
   int surrogate = 0, precision = 0, nplanes = 1;
+  bool hl = false;                // current gradients held in hi/lo form
   int C = 0, ldC = 0;
   float *z = nullptr, *dz = nullptr, *loss_b = nullptr, *loss = nullptr;
-  int *tstar = nullptr, *err_flag = nullptr;
-  float *partials = nullptr;
-  size_t partial_elems = 0;
+  int *tstar = nullptr, *err_flag = nullptr, *ticket = nullptr;
   char *ws = nullptr;
   size_t ws_bytes = 0;
   hipStream_t stream = nullptr;
@@ -97,8 +99,9 @@ int validate(const snn_config *cfg) {
   if (!cfg) return fail(nullptr, SNN_ERR_NULL, "config is NULL");
   if (!cfg->sizes || !cfg->beta) return fail(nullptr, SNN_ERR_NULL, "config.sizes / config.beta is NULL");
   if (cfg->T <= 0 || cfg->B <= 0) return fail(nullptr, SNN_ERR_ARG, "T and B must be positive");
-  if (cfg->n_layers < 2 || cfg->n_layers > 64)
-    return fail(nullptr, SNN_ERR_ARG, "n_layers must be in [2, 64] (at least one spiking layer and the readout)");
+  if (cfg->n_layers < 2 || cfg->n_layers > SNN_MAX_JOBS / 2)
+    return fail(nullptr, SNN_ERR_ARG, "n_layers must be in [2, %d] (at least one spiking layer and the readout)",
+                SNN_MAX_JOBS / 2);
   for (int i = 0; i <= cfg->n_layers; ++i)
     if (cfg->sizes[i] <= 0 || cfg->sizes[i] > (1 << 20)) return fail(nullptr, SNN_ERR_ARG, "sizes[%d] out of range", i);
   for (int i = 0; i < cfg->n_layers; ++i)
@@ -111,9 +114,15 @@ int validate(const snn_config *cfg) {
   return SNN_OK;
 }
 
-// Contraction splits of a weight-gradient product with `tiles` output tiles over M rows.
+// Contraction splits of a weight-gradient product with `tiles` output tiles over M rows:
+// enough workgroups to cover the chip about twice, but at least four 64-row tiles each.
 int choose_splits(long long M, int tiles, long long *per_split) {
-  long long want = 512 / (tiles > 0 ? tiles : 1);
+  static const long long target = [] {
+    const char *e = getenv("SNN_WGRAD_WORKGROUPS");      // tuning knob; default below
+    long long v = e ? atoll(e) : 0;
+    return v > 0 ? v : 512;
+  }();
+  long long want = target / (tiles > 0 ? tiles : 1);
   long long max_by_len = M / 256;
   if (want > max_by_len) want = max_by_len;
   if (want < 1) want = 1;
@@ -143,7 +152,6 @@ struct Carver {
 void carve(snn_ctx &c, Carver &cv) {
   const size_t M = (size_t)c.M;
   const int np = c.nplanes;
-  size_t part = 0;
   for (int l = 0; l < c.L; ++l) {
     Layer &y = c.layers[l];
     const size_t K = y.K, N = y.N;
@@ -157,9 +165,8 @@ void carve(snn_ctx &c, Carver &cv) {
       y.qb_plane = (long long)rup(K, 128) * y.ldqb;
       y.Qb = cv.take<uint16_t>((size_t)np * y.qb_plane);
     }
-    long long per;
-    y.splits_w = choose_splits(c.M, wgrad_tiles(y.K, y.N), &per);
-    if (y.splits_w > 1 && (size_t)y.splits_w * K * N > part) part = (size_t)y.splits_w * K * N;
+    y.splits_w = choose_splits(c.M, wgrad_tiles(y.K, y.N), &y.per_w);
+    if (y.splits_w > 1) y.part_w = cv.take<float>((size_t)y.splits_w * K * N);
     if (y.recurrent) {
       y.Rm = cv.take<float>(N * N);
       y.dR = cv.take<float>(N * N);
@@ -169,12 +176,12 @@ void carve(snn_ctx &c, Carver &cv) {
       y.QRb = cv.take<uint16_t>((size_t)np * y.qr_plane);
       y.g[0] = cv.take<float>((size_t)c.B * y.ld);
       y.g[1] = cv.take<float>((size_t)c.B * y.ld);
-      y.splits_r = choose_splits(c.M, wgrad_tiles(y.N, y.N), &per);
-      if (y.splits_r > 1 && (size_t)y.splits_r * N * N > part) part = (size_t)y.splits_r * N * N;
+      y.splits_r = choose_splits(c.M, wgrad_tiles(y.N, y.N), &y.per_r);
+      if (y.splits_r > 1) y.part_r = cv.take<float>((size_t)y.splits_r * N * N);
     }
     y.I = cv.take<float>(M * y.ld);
     y.V = cv.take<float>(M * y.ld);
-    y.dI = cv.take<float>(M * y.ld);
+    y.dI = cv.take<uint32_t>(M * y.ld);
     if (y.spiking) {
       y.S = cv.take<uint8_t>(M * y.ld);
       y.dS = cv.take<float>(M * y.ld);
@@ -186,8 +193,7 @@ void carve(snn_ctx &c, Carver &cv) {
   c.loss_b = cv.take<float>((size_t)c.B);
   c.loss = cv.take<float>(64);
   c.err_flag = cv.take<int>(64);
-  c.partial_elems = part;
-  c.partials = cv.take<float>(part ? part : 64);
+  c.ticket = cv.take<int>(64);
 }
 
 void configure(snn_ctx &c, const snn_config *cfg) {
@@ -197,6 +203,7 @@ void configure(snn_ctx &c, const snn_config *cfg) {
   c.theta = cfg->threshold; c.slope = cfg->slope;
   c.surrogate = cfg->surrogate; c.precision = cfg->precision;
   c.nplanes = c.precision == SNN_PREC_FP32 ? 3 : 1;
+  c.hl = c.precision == SNN_PREC_BF16_GEMM;
   c.layers.assign(c.L, Layer());
   for (int l = 0; l < c.L; ++l) {
     Layer &y = c.layers[l];
@@ -235,26 +242,6 @@ struct Bracket {
 };
 
 // ------------------------------------------------------------------ launches
-hipError_t zero_async(snn_ctx *c, void *p, size_t bytes) {
-  const long long n = (long long)(bytes / 4);
-  if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, (uint32_t *)p, n);
-  return hipGetLastError();
-}
-
-void set_terms(GemmArgs &a, int nterms, const int *tp, const int *tq) {
-  a.nterms = nterms; a.terms_p = 0; a.terms_q = 0;
-  for (int i = 0; i < nterms; ++i) { a.terms_p |= (unsigned)tp[i] << (4 * i); a.terms_q |= (unsigned)tq[i] << (4 * i); }
-}
-// Plane pairs (P plane, Q plane) of each product.  Weights have one plane when rounded to
-// bfloat16 and three for fp32 products; current gradients use hi+lo with rounded weights
-// and all pairs down to 2^-16 relative with fp32 products.
-const int kT0[6] = {0, 0, 0, 0, 0, 0};
-const int kT01[2] = {0, 1};
-const int kT012[3] = {0, 1, 2};
-const int kT6p[6] = {0, 0, 1, 0, 1, 2};
-const int kT6q[6] = {0, 1, 0, 2, 1, 0};
-
 int u8_align(const void *p, int ld, int valid, int want) {
   const uintptr_t a = (uintptr_t)p;
   if (want >= 8 && a % 8 == 0 && ld % 8 == 0 && valid % 8 == 0) return 8;
@@ -280,12 +267,17 @@ int launch_current_gemm(snn_ctx *c, int l, const uint8_t *x) {
   a.Q = y.Qf; a.ldq = y.ldqf; a.q_plane_stride = y.qf_plane;
   a.C = y.I; a.ldc = y.ld; a.rows = (int)c->M; a.cols = y.N;
   a.kc_per_split = (int)rup(a.kc, 64);
-  if (c->precision == SNN_PREC_FP32) set_terms(a, 3, kT0, kT012); else set_terms(a, 1, kT0, kT0);
   Bracket br(c, SNN_K_CURRENT_GEMM, l + 1);
   hipError_t e;
-  if (y.N <= 32) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 4, 1, 1, 1>(a, 1, c->stream);
-  else if (y.N <= 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 1>(a, 1, c->stream);
-  else e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 2>(a, 1, c->stream);
+  if (c->precision == SNN_PREC_FP32) {
+    if (y.N <= 32) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 4, 1, 1, 1, 3>(a, 1, c->stream);
+    else if (y.N <= 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 1, 3>(a, 1, c->stream);
+    else e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 2, 3>(a, 1, c->stream);
+  } else {
+    if (y.N <= 32) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 4, 1, 1, 1, 1>(a, 1, c->stream);
+    else if (y.N <= 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 1, 1>(a, 1, c->stream);
+    else e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 2, 1>(a, 1, c->stream);
+  }
   HIPCHK(c, e);
   return SNN_OK;
 }
@@ -302,56 +294,71 @@ int launch_input_grad(snn_ctx *c, int l) {
   a.kc_per_split = (int)rup(a.kc, 64);
   Bracket br(c, SNN_K_INPUT_GRAD, l + 1);
   hipError_t e;
-  if (c->precision == SNN_PREC_FP32) set_terms(a, 6, kT6p, kT6q); else set_terms(a, 2, kT01, kT0);
-  if (y.K <= 32) e = gemm_launch<P_F32S, Q_BF16, EPI_STORE, 4, 1, 1, 1>(a, 1, c->stream);
-  else e = gemm_launch<P_F32S, Q_BF16, EPI_STORE, 2, 2, 2, 2>(a, 1, c->stream);
+  if (c->precision == SNN_PREC_FP32) {
+    if (y.K <= 32) e = gemm_launch<P_F32S, Q_BF16, EPI_STORE, 4, 1, 1, 1, 3>(a, 1, c->stream);
+    else e = gemm_launch<P_F32S, Q_BF16, EPI_STORE, 2, 2, 1, 1, 3>(a, 1, c->stream);
+  } else {
+    if (y.K <= 32) e = gemm_launch<P_HL, Q_BF16, EPI_STORE, 4, 1, 1, 1, 1>(a, 1, c->stream);
+    else e = gemm_launch<P_HL, Q_BF16, EPI_STORE, 2, 2, 2, 2, 1>(a, 1, c->stream);
+  }
   HIPCHK(c, e);
   return SNN_OK;
 }
 
-// out[rows x cols] = Sp^T G, contraction over the T*B rows, split over workgroups and
-// reduced in a fixed order.
-int launch_tn(snn_ctx *c, SpikeSrc s, int rows, const void *G, int ldg, int cols, float *out, int splits) {
+// part[split][rows x cols] (or out directly when there is one split) = Sp^T G over one
+// slice of the T*B rows per split.
+int launch_tn(snn_ctx *c, SpikeSrc s, int rows, const void *G, int ldg, int cols, float *out, float *part,
+              int splits, long long per) {
   GemmArgs a;
   memset(&a, 0, sizeof a);
   a.P = s.p; a.ldp = s.ld; a.p_ivalid = s.valid; a.p_align = u8_align(s.p, s.ld, s.valid, 4);
   a.Q = G; a.ldq = ldg;
   a.rows = rows; a.cols = cols; a.ldc = cols; a.kc = (int)c->M;
-  long long per;
-  int sp = choose_splits(c->M, wgrad_tiles(rows, cols), &per);
-  if (sp != splits) return fail(c, SNN_ERR_STATE, "internal: split count mismatch");
   a.kc_per_split = (int)per;
   a.c_split_stride = (long long)rows * cols;
-  a.C = splits > 1 ? c->partials : out;
+  a.C = splits > 1 ? part : out;
   hipError_t e;
-  if (c->precision == SNN_PREC_FP32) set_terms(a, 3, kT0, kT012); else set_terms(a, 2, kT0, kT01);
-  if (cols <= 32) e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 4, 1, 1, 1>(a, splits, c->stream);
-  else if (cols <= 64) e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 1>(a, splits, c->stream);
-  else e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 2>(a, splits, c->stream);
-  HIPCHK(c, e);
-  if (splits > 1) {
-    const long long n = (long long)rows * cols;
-    if (n % 4 == 0)
-      hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n / 4 + 63) / 64)), dim3(256), 0, c->stream,
-                         c->partials, splits, n, out, n);
-    else
-      hipLaunchKernelGGL(reduce_partials_scalar_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream,
-                         c->partials, splits, n, out, n);
-    HIPCHK(c, hipGetLastError());
+  if (c->precision == SNN_PREC_FP32) {
+    if (cols <= 32) e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 4, 1, 1, 1, 3>(a, splits, c->stream);
+    else if (cols <= 64) e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 1, 3>(a, splits, c->stream);
+    else e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 2, 3>(a, splits, c->stream);
+  } else {
+    if (cols <= 32) e = gemm_launch<P_T_U8, Q_T_HL, EPI_STORE, 4, 1, 1, 1, 2>(a, splits, c->stream);
+    else if (cols <= 64) e = gemm_launch<P_T_U8, Q_T_HL, EPI_STORE, 2, 2, 2, 1, 2>(a, splits, c->stream);
+    else e = gemm_launch<P_T_U8, Q_T_HL, EPI_STORE, 2, 2, 2, 2, 2>(a, splits, c->stream);
   }
+  HIPCHK(c, e);
   return SNN_OK;
 }
 
-int launch_weight_grad(snn_ctx *c, int l, const uint8_t *x) {
+void add_reduce_job(ReduceJobs &jobs, const float *part, float *out, int splits, long long n) {
+  if (splits <= 1) return;
+  const int j = jobs.njobs++;
+  jobs.part[j] = part; jobs.out[j] = out; jobs.splits[j] = splits; jobs.n[j] = n;
+  jobs.first_block[j + 1] = jobs.first_block[j] + (int)((n + 255) / 256);
+}
+
+int launch_reduce(snn_ctx *c, const ReduceJobs &jobs) {
+  if (jobs.njobs == 0) return SNN_OK;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(jobs.first_block[jobs.njobs]), dim3(256), 0, c->stream, jobs);
+  HIPCHK(c, hipGetLastError());
+  return SNN_OK;
+}
+
+// dW^l = S^{l-1}^T dI^l and, for a recurrent layer, dR^l = S^l^T dI^l: the split products.
+// Their partial sums are queued on `jobs` and reduced by one launch for all layers.
+int launch_weight_grad(snn_ctx *c, int l, const uint8_t *x, ReduceJobs &jobs) {
   Layer &y = c->layers[l];
   SpikeSrc s = spikes_below(c, l, x);
   if (!s.p) return fail(c, SNN_ERR_NULL, "input raster is NULL");
   Bracket br(c, SNN_K_WEIGHT_GRAD, l + 1);
-  int rc = launch_tn(c, s, y.K, y.dI, y.ld, y.N, y.dW, y.splits_w);
+  int rc = launch_tn(c, s, y.K, y.dI, y.ld, y.N, y.dW, y.part_w, y.splits_w, y.per_w);
   if (rc) return rc;
+  add_reduce_job(jobs, y.part_w, y.dW, y.splits_w, (long long)y.K * y.N);
   if (y.recurrent) {
     SpikeSrc own = {y.S, y.ld, y.ld};
-    rc = launch_tn(c, own, y.N, y.dI, y.ld, y.N, y.dR, y.splits_r);
+    rc = launch_tn(c, own, y.N, y.dI, y.ld, y.N, y.dR, y.part_r, y.splits_r, y.per_r);
+    add_reduce_job(jobs, y.part_r, y.dR, y.splits_r, (long long)y.N * y.N);
   }
   return rc;
 }
@@ -369,10 +376,9 @@ int launch_lif_forward(snn_ctx *c, int l) {
   Layer &y = c->layers[l];
   if (y.recurrent) {
     Bracket br(c, SNN_K_RLIF_FORWARD, l + 1);
-    return rlif_forward(c->stream, c->precision == SNN_PREC_FP32, c->T, c->B, y.N, y.ld, y.I, y.V, y.S, y.QRf,
-                        y.ldqr, y.qr_plane, y.beta, c->theta) == hipSuccess
-               ? SNN_OK
-               : fail(c, SNN_ERR_HIP, "recurrent forward launch failed: %s", hipGetErrorString(hipGetLastError()));
+    HIPCHK(c, rlif_forward(c->stream, c->precision == SNN_PREC_FP32, c->T, c->B, y.N, y.ld, y.I, y.V, y.S, y.QRf,
+                           y.ldqr, y.qr_plane, y.beta, c->theta));
+    return SNN_OK;
   }
   Bracket br(c, SNN_K_LIF_FORWARD, l + 1);
   const long long chains = (long long)c->B * y.ld;
@@ -384,13 +390,13 @@ int launch_lif_forward(snn_ctx *c, int l) {
   return SNN_OK;
 }
 
-template <int VEC, int U>
-hipError_t lif_rev_launch(snn_ctx *c, Layer &y) {
+template <int VEC, int U, bool HL>
+hipError_t lif_rev_launch2(snn_ctx *c, Layer &y) {
   const long long stride = (long long)c->B * y.ld;
   const long long threads = stride / VEC;
   dim3 grid((unsigned)((threads + 255) / 256)), block(256);
-#define SNN_REV(SU)                                                                                         \
-  hipLaunchKernelGGL((lif_reverse_kernel<VEC, U, SU>), grid, block, 0, c->stream, y.dS, y.V, y.dI, c->T, \
+#define SNN_REV(SU)                                                                                          \
+  hipLaunchKernelGGL((lif_reverse_kernel<VEC, U, SU, HL>), grid, block, 0, c->stream, y.dS, y.V, y.dI, c->T, \
                      stride, y.beta, c->theta, c->slope)
   switch (c->surrogate) {
     case 0: SNN_REV(0); break;
@@ -401,15 +407,18 @@ hipError_t lif_rev_launch(snn_ctx *c, Layer &y) {
 #undef SNN_REV
   return hipGetLastError();
 }
+template <int VEC, int U>
+hipError_t lif_rev_launch(snn_ctx *c, Layer &y) {
+  return c->hl ? lif_rev_launch2<VEC, U, true>(c, y) : lif_rev_launch2<VEC, U, false>(c, y);
+}
 
 int launch_lif_reverse(snn_ctx *c, int l) {
   Layer &y = c->layers[l];
   if (y.recurrent) {
     Bracket br(c, SNN_K_RLIF_REVERSE, l + 1);
-    return rlif_reverse(c->stream, c->precision == SNN_PREC_FP32, c->T, c->B, y.N, y.ld, y.dS, y.V, y.dI, y.g[0],
-                        y.g[1], y.QRb, y.ldqr, y.qr_plane, y.beta, c->theta, c->surrogate, c->slope) == hipSuccess
-               ? SNN_OK
-               : fail(c, SNN_ERR_HIP, "recurrent reverse launch failed: %s", hipGetErrorString(hipGetLastError()));
+    HIPCHK(c, rlif_reverse(c->stream, c->precision == SNN_PREC_FP32, c->T, c->B, y.N, y.ld, y.dS, y.V, y.dI,
+                           y.g[0], y.g[1], y.QRb, y.ldqr, y.qr_plane, y.beta, c->theta, c->surrogate, c->slope));
+    return SNN_OK;
   }
   Bracket br(c, SNN_K_LIF_REVERSE, l + 1);
   const long long chains = (long long)c->B * y.ld;
@@ -425,6 +434,23 @@ int launch_readout_forward(snn_ctx *c, const int32_t *labels) {
   if (!labels) return fail(c, SNN_ERR_NULL, "labels are NULL");
   Layer &y = c->layers[c->L - 1];
   Bracket br(c, SNN_K_READOUT_FORWARD, c->L);
+  if (c->C <= 64) {
+    const int cw = c->C <= 8 ? 8 : (c->C <= 16 ? 16 : (c->C <= 32 ? 32 : 64));
+    const int spb = 256 / cw;
+    dim3 grid((c->B + spb - 1) / spb), block(256);
+#define SNN_RO(CW)                                                                                              \
+  hipLaunchKernelGGL(readout_loss_kernel<CW>, grid, block, 0, c->stream, y.I, y.V, c->z, c->tstar, labels,      \
+                     c->loss_b, c->dz, c->loss, c->ticket, c->err_flag, c->T, c->B, c->C, c->ldC, y.beta)
+    switch (cw) {
+      case 8: SNN_RO(8); break;
+      case 16: SNN_RO(16); break;
+      case 32: SNN_RO(32); break;
+      default: SNN_RO(64); break;
+    }
+#undef SNN_RO
+    HIPCHK(c, hipGetLastError());
+    return SNN_OK;
+  }
   const int stride = c->B * c->ldC;
   hipLaunchKernelGGL(readout_forward_kernel, dim3((stride + 255) / 256), dim3(256), 0, c->stream, y.I, y.V, c->z,
                      c->tstar, c->T, stride, y.beta);
@@ -441,30 +467,41 @@ int launch_readout_reverse(snn_ctx *c) {
   Layer &y = c->layers[c->L - 1];
   Bracket br(c, SNN_K_READOUT_REVERSE, c->L);
   const int stride = c->B * c->ldC;
-  hipLaunchKernelGGL(readout_reverse_kernel, dim3((stride + 255) / 256), dim3(256), 0, c->stream, c->dz, c->tstar,
-                     y.dI, c->T, stride, y.beta);
+  if (c->hl)
+    hipLaunchKernelGGL(readout_reverse_kernel<true>, dim3((stride + 255) / 256), dim3(256), 0, c->stream, c->dz,
+                       c->tstar, y.dI, c->T, stride, y.beta);
+  else
+    hipLaunchKernelGGL(readout_reverse_kernel<false>, dim3((stride + 255) / 256), dim3(256), 0, c->stream, c->dz,
+                       c->tstar, y.dI, c->T, stride, y.beta);
   HIPCHK(c, hipGetLastError());
   return SNN_OK;
 }
 
-int launch_param_update(snn_ctx *c, float *W, const float *dW, float lr, int K, int N, uint16_t *Qf, int ldqf,
-                        long long qf_plane, uint16_t *Qb, int ldqb, long long qb_plane) {
-  dim3 grid((N + 31) / 32, (K + 31) / 32);
-  hipLaunchKernelGGL(param_update_kernel, grid, dim3(256), 0, c->stream, W, dW, lr, K, N, Qf, ldqf, qf_plane, Qb,
-                     ldqb, qb_plane, c->nplanes);
-  HIPCHK(c, hipGetLastError());
-  return SNN_OK;
+void add_param_job(ParamJobs &jobs, float *W, const float *dW, int K, int N, uint16_t *Qf, int ldqf,
+                   long long qf_plane, uint16_t *Qb, int ldqb, long long qb_plane) {
+  const int j = jobs.njobs++;
+  jobs.W[j] = W; jobs.dW[j] = dW; jobs.K[j] = K; jobs.N[j] = N;
+  jobs.Qf[j] = Qf; jobs.ldqf[j] = ldqf; jobs.qf_plane[j] = qf_plane;
+  jobs.Qb[j] = Qb; jobs.ldqb[j] = ldqb; jobs.qb_plane[j] = qb_plane;
+  jobs.blocks_x[j] = (N + 31) / 32;
+  jobs.first_block[j + 1] = jobs.first_block[j] + jobs.blocks_x[j] * ((K + 31) / 32);
 }
 
-int update_layer(snn_ctx *c, int l, bool with_grad, float lr) {
-  Layer &y = c->layers[l];
-  int rc = launch_param_update(c, y.Wm, with_grad ? y.dW : nullptr, lr, y.K, y.N, y.Qf, y.ldqf, y.qf_plane, y.Qb,
-                               y.ldqb, y.qb_plane);
-  if (rc) return rc;
-  if (y.recurrent)
-    rc = launch_param_update(c, y.Rm, with_grad ? y.dR : nullptr, lr, y.N, y.N, y.QRf, y.ldqr, y.qr_plane, y.QRb,
-                             y.ldqr, y.qr_plane);
-  return rc;
+// SGD (when with_grad) and refresh of the bfloat16 operand planes for layers [l0, l1).
+int update_layers(snn_ctx *c, int l0, int l1, bool with_grad, float lr) {
+  ParamJobs jobs;
+  memset(&jobs, 0, sizeof jobs);
+  for (int l = l0; l < l1; ++l) {
+    Layer &y = c->layers[l];
+    add_param_job(jobs, y.Wm, with_grad ? y.dW : nullptr, y.K, y.N, y.Qf, y.ldqf, y.qf_plane, y.Qb, y.ldqb, y.qb_plane);
+    if (y.recurrent)
+      add_param_job(jobs, y.Rm, with_grad ? y.dR : nullptr, y.N, y.N, y.QRf, y.ldqr, y.qr_plane, y.QRb, y.ldqr,
+                    y.qr_plane);
+  }
+  hipLaunchKernelGGL(param_update_kernel, dim3(jobs.first_block[jobs.njobs]), dim3(256), 0, c->stream, jobs, lr,
+                     c->nplanes);
+  HIPCHK(c, hipGetLastError());
+  return SNN_OK;
 }
 
 int check_err_flag(snn_ctx *c) {
@@ -472,14 +509,15 @@ int check_err_flag(snn_ctx *c) {
   HIPCHK(c, hipMemcpyAsync(&flag, c->err_flag, sizeof(int), hipMemcpyDeviceToHost, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
   if (flag) {
-    HIPCHK(c, zero_async(c, c->err_flag, 256));
+    HIPCHK(c, fill_zero(c->stream, c->err_flag, 256));
     return fail(c, SNN_ERR_ARG, "a label was outside [0, C)");
   }
   return SNN_OK;
 }
 
-// Describes where a tensor lives: rows x cols elements, leading dimension, element size.
-struct TensorView { void *p; size_t rows, cols, ld, esz; };
+// Describes where a tensor lives: rows x cols elements, leading dimension, element size;
+// `hl`: held on the device in hi/lo form, fp32 on the host side.
+struct TensorView { void *p; size_t rows, cols, ld, esz; bool hl; };
 
 int view_of(snn_ctx *c, int tensor, int layer, TensorView *v, bool for_set) {
   const size_t M = (size_t)c->M;
@@ -496,48 +534,61 @@ int view_of(snn_ctx *c, int tensor, int layer, TensorView *v, bool for_set) {
   Layer *y = nullptr;
   Layer &ro = c->layers[c->L - 1];
   int rc;
+  bool settable = true;
   switch (tensor) {
     case SNN_T_WEIGHT:
       if ((rc = any_layer(&y))) return rc;
-      *v = {y->Wm, (size_t)y->K, (size_t)y->N, (size_t)y->N, 4}; return SNN_OK;
+      *v = {y->Wm, (size_t)y->K, (size_t)y->N, (size_t)y->N, 4, false}; break;
     case SNN_T_GRAD_W:
       if ((rc = any_layer(&y))) return rc;
-      *v = {y->dW, (size_t)y->K, (size_t)y->N, (size_t)y->N, 4}; break;
+      *v = {y->dW, (size_t)y->K, (size_t)y->N, (size_t)y->N, 4, false}; settable = false; break;
     case SNN_T_RWEIGHT:
     case SNN_T_GRAD_R:
       if ((rc = spiking_layer(&y))) return rc;
       if (!y->recurrent) return fail(c, SNN_ERR_ARG, "layer %d is not recurrent", layer);
-      *v = {tensor == SNN_T_RWEIGHT ? y->Rm : y->dR, (size_t)y->N, (size_t)y->N, (size_t)y->N, 4};
-      if (tensor == SNN_T_RWEIGHT) return SNN_OK;
+      *v = {tensor == SNN_T_RWEIGHT ? y->Rm : y->dR, (size_t)y->N, (size_t)y->N, (size_t)y->N, 4, false};
+      settable = tensor == SNN_T_RWEIGHT;
       break;
     case SNN_T_CURRENT:
       if ((rc = spiking_layer(&y))) return rc;
-      *v = {y->I, M, (size_t)y->N, (size_t)y->ld, 4}; return SNN_OK;
+      *v = {y->I, M, (size_t)y->N, (size_t)y->ld, 4, false}; break;
     case SNN_T_MEMBRANE:
       if ((rc = spiking_layer(&y))) return rc;
-      *v = {y->V, M, (size_t)y->N, (size_t)y->ld, 4}; return SNN_OK;
+      *v = {y->V, M, (size_t)y->N, (size_t)y->ld, 4, false}; break;
     case SNN_T_SPIKES:
       if ((rc = spiking_layer(&y))) return rc;
-      *v = {y->S, M, (size_t)y->N, (size_t)y->ld, 1}; return SNN_OK;
+      *v = {y->S, M, (size_t)y->N, (size_t)y->ld, 1, false}; break;
     case SNN_T_D_SPIKES:
       if ((rc = spiking_layer(&y))) return rc;
-      *v = {y->dS, M, (size_t)y->N, (size_t)y->ld, 4}; return SNN_OK;
+      *v = {y->dS, M, (size_t)y->N, (size_t)y->ld, 4, false}; break;
     case SNN_T_D_CURRENT:
       if ((rc = spiking_layer(&y))) return rc;
-      *v = {y->dI, M, (size_t)y->N, (size_t)y->ld, 4}; return SNN_OK;
-    case SNN_T_READOUT_CURRENT: *v = {ro.I, M, (size_t)c->C, (size_t)c->ldC, 4}; return SNN_OK;
-    case SNN_T_READOUT_TRACE: *v = {ro.V, M, (size_t)c->C, (size_t)c->ldC, 4}; break;
-    case SNN_T_LOGITS: *v = {c->z, (size_t)c->B, (size_t)c->C, (size_t)c->ldC, 4}; break;
-    case SNN_T_ARGMAX_T: *v = {c->tstar, (size_t)c->B, (size_t)c->C, (size_t)c->ldC, 4}; return SNN_OK;
-    case SNN_T_D_LOGITS: *v = {c->dz, (size_t)c->B, (size_t)c->C, (size_t)c->ldC, 4}; return SNN_OK;
-    case SNN_T_D_READOUT_CURRENT:
-      *v = {ro.dI, M, (size_t)c->C, (size_t)c->ldC, 4}; return SNN_OK;
-    case SNN_T_LOSS: *v = {c->loss, 1, 1, 1, 4}; break;
-    case SNN_T_LOSS_PER_SAMPLE: *v = {c->loss_b, 1, (size_t)c->B, (size_t)c->B, 4}; break;
+      *v = {y->dI, M, (size_t)y->N, (size_t)y->ld, 4, c->hl}; break;
+    case SNN_T_READOUT_CURRENT: *v = {ro.I, M, (size_t)c->C, (size_t)c->ldC, 4, false}; break;
+    case SNN_T_READOUT_TRACE: *v = {ro.V, M, (size_t)c->C, (size_t)c->ldC, 4, false}; settable = false; break;
+    case SNN_T_LOGITS: *v = {c->z, (size_t)c->B, (size_t)c->C, (size_t)c->ldC, 4, false}; settable = false; break;
+    case SNN_T_ARGMAX_T: *v = {c->tstar, (size_t)c->B, (size_t)c->C, (size_t)c->ldC, 4, false}; break;
+    case SNN_T_D_LOGITS: *v = {c->dz, (size_t)c->B, (size_t)c->C, (size_t)c->ldC, 4, false}; break;
+    case SNN_T_D_READOUT_CURRENT: *v = {ro.dI, M, (size_t)c->C, (size_t)c->ldC, 4, c->hl}; break;
+    case SNN_T_LOSS: *v = {c->loss, 1, 1, 1, 4, false}; settable = false; break;
+    case SNN_T_LOSS_PER_SAMPLE: *v = {c->loss_b, 1, (size_t)c->B, (size_t)c->B, 4, false}; settable = false; break;
     default: return fail(c, SNN_ERR_ARG, "unknown tensor id %d", tensor);
   }
-  if (for_set) return fail(c, SNN_ERR_ARG, "tensor %d cannot be set", tensor);
+  if (for_set && !settable) return fail(c, SNN_ERR_ARG, "tensor %d cannot be set", tensor);
   return SNN_OK;
+}
+
+// Host-side twin of the device's hi/lo form (used only to move tensors in and out).
+inline uint16_t host_bf16(float x) {
+  uint32_t u;
+  memcpy(&u, &x, 4);
+  return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+inline float host_bf16_value(uint16_t b) {
+  uint32_t u = (uint32_t)b << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
 }
 
 }  // namespace
@@ -596,9 +647,9 @@ int32_t snn_init(const snn_config *cfg, void *workspace_dev, size_t workspace_by
     if (y.recurrent &&
         (e = hipMemcpyAsync(y.Rm, R_host[l], sizeof(float) * y.N * y.N, hipMemcpyHostToDevice, c->stream)) != hipSuccess)
       return bail(e, "hipMemcpyAsync(R)");
-    if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail(e, "hipStreamSynchronize");
-    if (update_layer(c, l, false, 0.f) != SNN_OK) { g_err = c->err; delete c; return SNN_ERR_HIP; }
   }
+  if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail(e, "hipStreamSynchronize");
+  if (update_layers(c, 0, c->L, false, 0.f) != SNN_OK) { g_err = c->err; delete c; return SNN_ERR_HIP; }
   if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail(e, "hipStreamSynchronize");
   *out = c;
   return SNN_OK;
@@ -629,11 +680,17 @@ int32_t snn_backward(snn_ctx *c) {
   if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
   if (c->state < 1) return fail(c, SNN_ERR_STATE, "snn_backward needs a preceding snn_forward");
   int rc;
+  ReduceJobs jobs;
+  memset(&jobs, 0, sizeof jobs);
   if ((rc = launch_readout_reverse(c))) return rc;
   for (int l = c->L - 1; l >= 0; --l) {
     if (c->layers[l].spiking && (rc = launch_lif_reverse(c, l))) return rc;
-    if ((rc = launch_weight_grad(c, l, c->x_dev))) return rc;
+    if ((rc = launch_weight_grad(c, l, c->x_dev, jobs))) return rc;
     if (l > 0 && (rc = launch_input_grad(c, l))) return rc;
+  }
+  {
+    Bracket br(c, SNN_K_WEIGHT_GRAD, 0);
+    if ((rc = launch_reduce(c, jobs))) return rc;
   }
   c->state = 2;
   return SNN_OK;
@@ -643,10 +700,8 @@ int32_t snn_sgd_step(snn_ctx *c, float lr) {
   if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
   if (c->state < 2) return fail(c, SNN_ERR_STATE, "snn_sgd_step needs a preceding snn_backward");
   Bracket br(c, SNN_K_SGD, 0);
-  for (int l = 0; l < c->L; ++l) {
-    int rc = update_layer(c, l, true, lr);
-    if (rc) return rc;
-  }
+  int rc = update_layers(c, 0, c->L, true, lr);
+  if (rc) return rc;
   c->state = 0;
   return SNN_OK;
 }
@@ -662,6 +717,12 @@ int32_t snn_get_tensor(snn_ctx *c, int32_t tensor, int32_t layer, void *dst, siz
   HIPCHK(c, hipMemcpy2DAsync(dst, v.cols * v.esz, v.p, v.ld * v.esz, v.cols * v.esz, v.rows, hipMemcpyDeviceToHost,
                              c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
+  if (v.hl) {                                   // hi + lo -> fp32, in place
+    uint32_t *w = (uint32_t *)dst;
+    float *f = (float *)dst;
+    for (size_t i = 0; i < v.rows * v.cols; ++i)
+      f[i] = host_bf16_value((uint16_t)(w[i] & 0xFFFFu)) + host_bf16_value((uint16_t)(w[i] >> 16));
+  }
   return check_err_flag(c);
 }
 
@@ -673,11 +734,22 @@ int32_t snn_set_tensor(snn_ctx *c, int32_t tensor, int32_t layer, const void *sr
   if (rc) return rc;
   if (bytes != v.rows * v.cols * v.esz)
     return fail(c, SNN_ERR_SHAPE, "tensor %d needs %zu bytes, got %zu", tensor, v.rows * v.cols * v.esz, bytes);
+  std::vector<uint32_t> tmp;
+  if (v.hl) {                                   // fp32 -> hi/lo words
+    const float *f = (const float *)src;
+    tmp.resize(v.rows * v.cols);
+    for (size_t i = 0; i < tmp.size(); ++i) {
+      const uint16_t h = host_bf16(f[i]);
+      const uint16_t l = host_bf16(f[i] - host_bf16_value(h));
+      tmp[i] = (uint32_t)h | ((uint32_t)l << 16);
+    }
+    src = tmp.data();
+  }
   HIPCHK(c, hipMemcpy2DAsync(v.p, v.ld * v.esz, src, v.cols * v.esz, v.cols * v.esz, v.rows, hipMemcpyHostToDevice,
                              c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
   if (tensor == SNN_T_WEIGHT || tensor == SNN_T_RWEIGHT) {
-    if ((rc = update_layer(c, layer - 1, false, 0.f))) return rc;
+    if ((rc = update_layers(c, layer - 1, layer, false, 0.f))) return rc;
     HIPCHK(c, hipStreamSynchronize(c->stream));
     c->state = 0;
   }
@@ -699,7 +771,12 @@ int32_t snn_run_step(snn_ctx *c, int32_t step, int32_t layer, const uint8_t *x_d
     case SNN_STEP_LIF_REVERSE:
       if (!spiking) return fail(c, SNN_ERR_ARG, "layer %d is not spiking", layer);
       return launch_lif_reverse(c, l);
-    case SNN_STEP_WEIGHT_GRAD: return launch_weight_grad(c, l, x_dev);
+    case SNN_STEP_WEIGHT_GRAD: {
+      ReduceJobs jobs;
+      memset(&jobs, 0, sizeof jobs);
+      int rc = launch_weight_grad(c, l, x_dev, jobs);
+      return rc ? rc : launch_reduce(c, jobs);
+    }
     case SNN_STEP_INPUT_GRAD:
       if (l == 0) return fail(c, SNN_ERR_ARG, "layer 1 has no input gradient");
       return launch_input_grad(c, l);

@@ -4,6 +4,7 @@ seeded inputs.  Tolerances are those of tests/parity.py: potentials, readout and
 trains identical except decisions whose potential is within 1e-5 of the threshold (counted).
 """
 import json
+import os
 
 import numpy as np
 import pytest
@@ -53,7 +54,12 @@ def full_step_parity(wl, w_gain=1.0, lr=0.1, seed=None, grad_tol=parity.TOL_GRAD
         rep["loss_after_step"] = loss2
         rep["imposed_after_step"] = rep2["imposed_decisions"]
     rep["loss"] = loss
+    rep["case"] = f"{wl.name} T={wl.T} B={wl.B} {wl.precision} gain={w_gain}"
     print(json.dumps(rep), flush=True)
+    out_dir = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(out_dir):
+        with open(os.path.join(out_dir, "parity_reports.jsonl"), "a") as f:
+            f.write(json.dumps(rep) + "\n")
     snn.destroy()
     return rep
 
