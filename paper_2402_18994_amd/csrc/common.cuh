@@ -46,6 +46,15 @@ __device__ __forceinline__ uint32_t spikes2_to_bf16(uint32_t two_bytes_spread) {
   return (two_bytes_spread & 0x00010001u) * 0x3F80u;
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load (vmcnt(0)), which would expose the full memory latency at each
+// barrier and defeat the register prefetch ring of the product kernels.  Here only the LDS
+// counter is drained; global loads stay in flight and are waited for where their registers
+// are first used.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // ---------------------------------------------------------------- LDS operand tiles
 // An operand tile holds ROWS rows of 64 contraction elements as bfloat16: 128 bytes per row,
 // split in eight 16-byte chunks.  Chunk c of row r lives at chunk slot c ^ swz(r); the

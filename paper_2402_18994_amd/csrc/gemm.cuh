@@ -21,6 +21,11 @@
 // pairs (p, q) with p + q < max(#P planes, #Q planes): all pairs whose product is above
 // 2^-24 relative.  0/1 operands have a single, exact plane.
 //
+// Global loads are buffer loads: a per-lane byte offset computed once per workgroup, plus a
+// scalar offset that walks the contraction, so the inner loop spends no vector ALU work on
+// addresses.  A lane that must read nothing (row, column or contraction tail) is given an
+// offset beyond the buffer's size, for which the hardware returns zero.
+//
 // Epilogues: plain store (optionally one partial result per contraction split), or one step
 // of a recurrent LIF layer, forward or reverse, applied to the recurrent product.
 #pragma once
@@ -36,13 +41,14 @@ struct GemmArgs {
   const void *P;
   const void *Q;
   float *C;
+  unsigned p_bytes, q_bytes; // sizes of the P and Q buffers (reads beyond them return zero)
   int rows, cols;            // extent of C
   int kc;                    // contraction length (elements that may be read along k)
   int ldp, ldq, ldc;         // leading dimensions in elements
-  int p_align;               // P_U8 / P_T_U8: widest aligned load allowed (8, 4 or 1 bytes)
   int p_ivalid;              // P_T_U8: number of valid columns of P (rows of C)
   long long q_plane_stride;  // Q_BF16: elements between planes
-  int kc_per_split;          // contraction range per blockIdx.y (multiple of 64)
+  int kc_per_split;          // contraction range per split (multiple of 64)
+  int splits;
   long long c_split_stride;  // elements between partial results
   int tiles_m, tiles_n;
   // recurrent-step epilogues (rows = B, cols = N, all [B][ld] with ld = ldc)
@@ -67,177 +73,171 @@ __device__ __forceinline__ float surrogate_eval(int kind, float k, float x) {
   }
 }
 
+// ------------------------------------------------------------------ buffer loads
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+constexpr int OOB = 0x7FFFFF00;          // beyond any buffer here: the load returns zero
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void *base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ uint32_t ld_b8(rsrc_t r, int voff, int soff) {
+  return (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(r, voff, soff, 0);
+}
+__device__ __forceinline__ uint32_t ld_b32(rsrc_t r, int voff, int soff) {
+  return __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0);
+}
+__device__ __forceinline__ u32x2 ld_b64(rsrc_t r, int voff, int soff) {
+  return __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+}
+__device__ __forceinline__ u32x4 ld_b128(rsrc_t r, int voff, int soff) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+}
+
 // ------------------------------------------------------------------ operand loaders
-// Each loader keeps one tile's worth of raw global data in registers (load) and later
-// converts and writes all its planes to LDS (store), so global latency overlaps the MFMAs.
-// `tile` points at plane 0; plane p starts ROWS*128 bytes further.
+// setup(): per-lane byte offsets and LDS offsets, once per workgroup.
+// load():  issue the global loads of the 64-wide contraction tile starting at k0 into
+//          registers (raw).  `kend` is the end of this workgroup's contraction range.
+// store(): convert and write all planes to LDS.  `tile` points at plane 0; plane p starts
+//          ROWS*128 bytes further.
 
 template <int MODE, int ROWS> struct LoaderP;
 
+// P[row][k] bytes (0/1).
 template <int ROWS> struct LoaderP<P_U8, ROWS> {
   static constexpr int PLANES = 1;
   static constexpr int CH = (ROWS * 8 + 255) / 256;
+  int voff[CH], loff[CH], kch[CH];
   uint32_t raw[CH][2];
-  __device__ __forceinline__ void load(const GemmArgs &a, int row0, int k0, int kend, int tid) {
-    const uint8_t *P = (const uint8_t *)a.P;
+  __device__ __forceinline__ void setup(const GemmArgs &a, int row0, int tid) {
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-      int cid = tid + 256 * c;
-      int r = cid >> 3, ch = cid & 7;
-      int grow = row0 + r, k = k0 + ch * 8;
-      uint32_t lo = 0, hi = 0;
-      if (cid < ROWS * 8 && grow < a.rows && k < kend) {
-        const uint8_t *p = P + (size_t)grow * a.ldp + k;
-        if (a.p_align == 8) {
-          uint2 v = *(const uint2 *)p; lo = v.x; hi = v.y;
-        } else if (a.p_align == 4) {
-          lo = *(const uint32_t *)p;
-          if (k + 4 < kend) hi = *(const uint32_t *)(p + 4);
-        } else {
+      const int cid = tid + 256 * c;
+      const int r = cid >> 3, ch = cid & 7;
+      const bool ok = cid < ROWS * 8 && row0 + r < a.rows;
+      voff[c] = ok ? (row0 + r) * a.ldp + ch * 8 : OOB;
+      loff[c] = tile_off(r & (ROWS - 1), ch);
+      kch[c] = ch * 8;
+    }
+  }
+  // Rows are 4-byte aligned and kend is a multiple of 4 (the host pads the raster otherwise):
+  // two dword loads per chunk, no branches, so the loads of several tiles can stay in flight.
+  __device__ __forceinline__ void load(const GemmArgs &, rsrc_t rs, int k0, int kend) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            if (k + e < kend) lo |= (uint32_t)p[e] << (8 * e);
-            if (k + 4 + e < kend) hi |= (uint32_t)p[4 + e] << (8 * e);
-          }
-        }
-      }
-      raw[c][0] = lo; raw[c][1] = hi;
+    for (int c = 0; c < CH; ++c) {
+      const int k = k0 + kch[c];
+      raw[c][0] = ld_b32(rs, k >= kend ? OOB : voff[c], k0);
+      raw[c][1] = ld_b32(rs, k + 4 >= kend ? OOB : voff[c] + 4, k0);
     }
   }
   __device__ __forceinline__ void store(char *tile, int tid) {
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-      int cid = tid + 256 * c;
-      if (cid < ROWS * 8) {
+      if (tid + 256 * c < ROWS * 8) {
         uint4 d;
         d.x = spikes2_to_bf16(__builtin_amdgcn_perm(0u, raw[c][0], 0x0C010C00u));
         d.y = spikes2_to_bf16(__builtin_amdgcn_perm(0u, raw[c][0], 0x0C030C02u));
         d.z = spikes2_to_bf16(__builtin_amdgcn_perm(0u, raw[c][1], 0x0C010C00u));
         d.w = spikes2_to_bf16(__builtin_amdgcn_perm(0u, raw[c][1], 0x0C030C02u));
-        *(uint4 *)(tile + tile_off(cid >> 3, cid & 7)) = d;
+        *(uint4 *)(tile + loff[c]) = d;
       }
     }
   }
 };
 
-// P[m][k] dwords, each holding hi (bits 0..15) and lo (bits 16..31) of one value.
-template <int ROWS> struct LoaderP<P_HL, ROWS> {
-  static constexpr int PLANES = 2;
+// P[row][k] dwords: HL words (two planes) or fp32 (three planes, split here).
+template <int ROWS, bool HL> struct LoaderPWord {
+  static constexpr int PLANES = HL ? 2 : 3;
   static constexpr int CH = (ROWS * 8 + 255) / 256;
-  uint4 raw[CH][2];
-  __device__ __forceinline__ void load(const GemmArgs &a, int row0, int k0, int kend, int tid) {
-    const uint32_t *P = (const uint32_t *)a.P;
+  int voff[CH], loff[CH], kch[CH];
+  u32x4 raw[CH][2];
+  __device__ __forceinline__ void setup(const GemmArgs &a, int row0, int tid) {
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-      int cid = tid + 256 * c;
-      int r = cid >> 3, ch = cid & 7;
-      int grow = row0 + r, k = k0 + ch * 8;
-      uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
-      if (cid < ROWS * 8 && grow < a.rows && k < kend) {
-        const uint4 *p = (const uint4 *)(P + (size_t)grow * a.ldp + k);
-        v0 = p[0]; v1 = p[1];
-      }
-      raw[c][0] = v0; raw[c][1] = v1;
+      const int cid = tid + 256 * c;
+      const int r = cid >> 3, ch = cid & 7;
+      const bool ok = cid < ROWS * 8 && row0 + r < a.rows;
+      voff[c] = ok ? ((row0 + r) * a.ldp + ch * 8) * 4 : OOB;
+      loff[c] = tile_off(r & (ROWS - 1), ch);
+      kch[c] = ch * 8;
+    }
+  }
+  __device__ __forceinline__ void load(const GemmArgs &, rsrc_t rs, int k0, int kend) {
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {                 // kend is a multiple of 8 here
+      const int vo = k0 + kch[c] >= kend ? OOB : voff[c];
+      raw[c][0] = ld_b128(rs, vo, k0 * 4);
+      raw[c][1] = ld_b128(rs, vo + 16, k0 * 4);
     }
   }
   __device__ __forceinline__ void store(char *tile, int tid) {
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-      int cid = tid + 256 * c;
-      if (cid < ROWS * 8) {
-        const int off = tile_off(cid >> 3, cid & 7);
-        uint4 h, l;
-        h.x = __builtin_amdgcn_perm(raw[c][0].y, raw[c][0].x, 0x05040100u);
-        h.y = __builtin_amdgcn_perm(raw[c][0].w, raw[c][0].z, 0x05040100u);
-        h.z = __builtin_amdgcn_perm(raw[c][1].y, raw[c][1].x, 0x05040100u);
-        h.w = __builtin_amdgcn_perm(raw[c][1].w, raw[c][1].z, 0x05040100u);
-        l.x = __builtin_amdgcn_perm(raw[c][0].y, raw[c][0].x, 0x07060302u);
-        l.y = __builtin_amdgcn_perm(raw[c][0].w, raw[c][0].z, 0x07060302u);
-        l.z = __builtin_amdgcn_perm(raw[c][1].y, raw[c][1].x, 0x07060302u);
-        l.w = __builtin_amdgcn_perm(raw[c][1].w, raw[c][1].z, 0x07060302u);
-        *(uint4 *)(tile + off) = h;
-        *(uint4 *)(tile + ROWS * 128 + off) = l;
-      }
-    }
-  }
-};
-
-template <int ROWS> struct LoaderP<P_F32S, ROWS> {
-  static constexpr int PLANES = 3;
-  static constexpr int CH = (ROWS * 8 + 255) / 256;
-  float4 raw[CH][2];
-  __device__ __forceinline__ void load(const GemmArgs &a, int row0, int k0, int kend, int tid) {
-    const float *P = (const float *)a.P;
+      if (tid + 256 * c < ROWS * 8) {
+        if (HL) {
+          uint4 h, l;
+          h.x = __builtin_amdgcn_perm(raw[c][0].y, raw[c][0].x, 0x05040100u);
+          h.y = __builtin_amdgcn_perm(raw[c][0].w, raw[c][0].z, 0x05040100u);
+          h.z = __builtin_amdgcn_perm(raw[c][1].y, raw[c][1].x, 0x05040100u);
+          h.w = __builtin_amdgcn_perm(raw[c][1].w, raw[c][1].z, 0x05040100u);
+          l.x = __builtin_amdgcn_perm(raw[c][0].y, raw[c][0].x, 0x07060302u);
+          l.y = __builtin_amdgcn_perm(raw[c][0].w, raw[c][0].z, 0x07060302u);
+          l.z = __builtin_amdgcn_perm(raw[c][1].y, raw[c][1].x, 0x07060302u);
+          l.w = __builtin_amdgcn_perm(raw[c][1].w, raw[c][1].z, 0x07060302u);
+          *(uint4 *)(tile + loff[c]) = h;
+          *(uint4 *)(tile + ROWS * 128 + loff[c]) = l;
+        } else {
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      int cid = tid + 256 * c;
-      int r = cid >> 3, ch = cid & 7;
-      int grow = row0 + r, k = k0 + ch * 8;
-      float4 v0 = make_float4(0, 0, 0, 0), v1 = v0;
-      if (cid < ROWS * 8 && grow < a.rows && k < kend) {
-        const float4 *p = (const float4 *)(P + (size_t)grow * a.ldp + k);
-        v0 = p[0]; v1 = p[1];
-      }
-      raw[c][0] = v0; raw[c][1] = v1;
-    }
-  }
-  __device__ __forceinline__ void store(char *tile, int tid) {
-#pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      int cid = tid + 256 * c;
-      if (cid < ROWS * 8) {
-        const int off = tile_off(cid >> 3, cid & 7);
-#pragma unroll
-        for (int pl = 0; pl < 3; ++pl) {
-          uint4 d;
-          d.x = pack2(bf16_piece(raw[c][0].x, pl), bf16_piece(raw[c][0].y, pl));
-          d.y = pack2(bf16_piece(raw[c][0].z, pl), bf16_piece(raw[c][0].w, pl));
-          d.z = pack2(bf16_piece(raw[c][1].x, pl), bf16_piece(raw[c][1].y, pl));
-          d.w = pack2(bf16_piece(raw[c][1].z, pl), bf16_piece(raw[c][1].w, pl));
-          *(uint4 *)(tile + pl * ROWS * 128 + off) = d;
+          for (int pl = 0; pl < 3; ++pl) {
+            uint4 d;
+            d.x = pack2(bf16_piece(__uint_as_float(raw[c][0].x), pl), bf16_piece(__uint_as_float(raw[c][0].y), pl));
+            d.y = pack2(bf16_piece(__uint_as_float(raw[c][0].z), pl), bf16_piece(__uint_as_float(raw[c][0].w), pl));
+            d.z = pack2(bf16_piece(__uint_as_float(raw[c][1].x), pl), bf16_piece(__uint_as_float(raw[c][1].y), pl));
+            d.w = pack2(bf16_piece(__uint_as_float(raw[c][1].z), pl), bf16_piece(__uint_as_float(raw[c][1].w), pl));
+            *(uint4 *)(tile + pl * ROWS * 128 + loff[c]) = d;
+          }
         }
       }
     }
   }
 };
+template <int ROWS> struct LoaderP<P_HL, ROWS> : LoaderPWord<ROWS, true> {};
+template <int ROWS> struct LoaderP<P_F32S, ROWS> : LoaderPWord<ROWS, false> {};
 
 // P[m][i] bytes, contraction index m slowest.  One unit = 8 consecutive m x 4 consecutive i.
 template <int ROWS> struct LoaderP<P_T_U8, ROWS> {
   static constexpr int PLANES = 1;
   static constexpr int UNITS = ROWS * 2;                  // (ROWS/4) column groups x 8 m groups
   static constexpr int UP = (UNITS + 255) / 256;
+  int voff[UP], loff[UP][4], mrow[UP];
   uint32_t raw[UP][8];
-  __device__ __forceinline__ void load(const GemmArgs &a, int row0, int k0, int kend, int tid) {
-    const uint8_t *P = (const uint8_t *)a.P;
+  // Rows are 4-byte aligned and the number of valid columns is a multiple of 4 (the host pads
+  // the raster otherwise): one dword load per row, no branches.
+  __device__ __forceinline__ void setup(const GemmArgs &a, int row0, int tid) {
 #pragma unroll
     for (int c = 0; c < UP; ++c) {
-      int u = tid + 256 * c;
-      int ig = u % (ROWS / 4), mg = u / (ROWS / 4);
-      int i = row0 + 4 * ig;
+      const int u = tid + 256 * c;
+      const int ig = u % (ROWS / 4), mg = u / (ROWS / 4);
+      const int i = row0 + 4 * ig;
+      voff[c] = (u < UNITS && i < a.p_ivalid) ? 8 * mg * a.ldp + i : OOB;
+      mrow[c] = 8 * mg;
 #pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        int m = k0 + 8 * mg + r;
-        uint32_t v = 0;
-        if (u < UNITS && m < kend && i < a.p_ivalid) {
-          const uint8_t *p = P + (size_t)m * a.ldp + i;
-          if (a.p_align >= 4) {
-            v = *(const uint32_t *)p;
-          } else {
+      for (int e = 0; e < 4; ++e) loff[c][e] = tile_off((4 * ig + e) & (ROWS - 1), mg & 7);
+    }
+  }
+  __device__ __forceinline__ void load(const GemmArgs &a, rsrc_t rs, int k0, int kend) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (i + e < a.p_ivalid) v |= (uint32_t)p[e] << (8 * e);
-          }
-        }
-        raw[c][r] = v;
-      }
+    for (int c = 0; c < UP; ++c) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r)
+        raw[c][r] = ld_b32(rs, k0 + mrow[c] + r >= kend ? OOB : voff[c], (k0 + r) * a.ldp);
     }
   }
   __device__ __forceinline__ void store(char *tile, int tid) {
 #pragma unroll
     for (int c = 0; c < UP; ++c) {
-      int u = tid + 256 * c;
-      if (u < UNITS) {
-        int ig = u % (ROWS / 4), mg = u / (ROWS / 4);
+      if (tid + 256 * c < UNITS) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           // byte e of raw[2h] -> bits 0..7, byte e of raw[2h+1] -> bits 16..23
@@ -247,7 +247,7 @@ template <int ROWS> struct LoaderP<P_T_U8, ROWS> {
           d.y = spikes2_to_bf16(__builtin_amdgcn_perm(raw[c][3], raw[c][2], sel));
           d.z = spikes2_to_bf16(__builtin_amdgcn_perm(raw[c][5], raw[c][4], sel));
           d.w = spikes2_to_bf16(__builtin_amdgcn_perm(raw[c][7], raw[c][6], sel));
-          *(uint4 *)(tile + tile_off(4 * ig + e, mg)) = d;
+          *(uint4 *)(tile + loff[c][e]) = d;
         }
       }
     }
@@ -260,136 +260,107 @@ template <int MODE, int ROWS, int NPL> struct LoaderQ;
 template <int ROWS, int NPL> struct LoaderQ<Q_BF16, ROWS, NPL> {
   static constexpr int PLANES = NPL;
   static constexpr int CH = (ROWS * 8 + 255) / 256;
-  uint4 raw[NPL][CH];
-  __device__ __forceinline__ void load(const GemmArgs &a, int col0, int k0, int, int tid) {
+  int voff[CH], loff[CH];
+  u32x4 raw[NPL][CH];
+  __device__ __forceinline__ void setup(const GemmArgs &a, int col0, int tid) {
 #pragma unroll
-    for (int pl = 0; pl < NPL; ++pl) {
-      const uint16_t *Q = (const uint16_t *)a.Q + (size_t)pl * a.q_plane_stride;
-#pragma unroll
-      for (int c = 0; c < CH; ++c) {
-        int cid = tid + 256 * c;
-        int r = cid >> 3, ch = cid & 7;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (cid < ROWS * 8) v = *(const uint4 *)(Q + (size_t)(col0 + r) * a.ldq + k0 + ch * 8);
-        raw[pl][c] = v;
-      }
+    for (int c = 0; c < CH; ++c) {
+      const int cid = tid + 256 * c;
+      const int r = cid >> 3, ch = cid & 7;
+      voff[c] = cid < ROWS * 8 ? ((col0 + r) * a.ldq + ch * 8) * 2 : OOB;
+      loff[c] = tile_off(r & (ROWS - 1), ch);
     }
+  }
+  __device__ __forceinline__ void load(const GemmArgs &a, rsrc_t rs, int k0, int kend) {
+    const bool past = k0 >= kend;                  // uniform: a padding tile of the ring
+#pragma unroll
+    for (int pl = 0; pl < NPL; ++pl)
+#pragma unroll
+      for (int c = 0; c < CH; ++c)
+        raw[pl][c] = ld_b128(rs, past ? OOB : voff[c], (k0 + pl * (int)a.q_plane_stride) * 2);
   }
   __device__ __forceinline__ void store(char *tile, int tid) {
 #pragma unroll
     for (int pl = 0; pl < NPL; ++pl)
 #pragma unroll
-      for (int c = 0; c < CH; ++c) {
-        int cid = tid + 256 * c;
-        if (cid < ROWS * 8) *(uint4 *)(tile + pl * ROWS * 128 + tile_off(cid >> 3, cid & 7)) = raw[pl][c];
-      }
+      for (int c = 0; c < CH; ++c)
+        if (tid + 256 * c < ROWS * 8) *(u32x4 *)(tile + pl * ROWS * 128 + loff[c]) = raw[pl][c];
   }
 };
 
-// Q[m][j] HL dwords, contraction index m slowest, ld a multiple of 8 with zero padding.
-// One unit = 8 consecutive m x 2 consecutive j.
-template <int ROWS, int NPL> struct LoaderQ<Q_T_HL, ROWS, NPL> {
+// Q[m][j] dwords, contraction index m slowest, ld a multiple of 8 with zero padding: HL words
+// (two planes) or fp32 (three planes, split here).  One unit = 8 consecutive m x 2
+// consecutive j.
+template <int ROWS, bool HL> struct LoaderQTWord {
+  static constexpr int PLANES = HL ? 2 : 3;
+  static constexpr int UNITS = ROWS * 4;
+  static constexpr int UQ = (UNITS + 255) / 256;
+  int voff[UQ], loff[UQ][2], mrow[UQ];
+  u32x2 raw[UQ][8];
+  __device__ __forceinline__ void setup(const GemmArgs &a, int col0, int tid) {
+#pragma unroll
+    for (int c = 0; c < UQ; ++c) {
+      const int u = tid + 256 * c;
+      const int jg = u % (ROWS / 2), mg = u / (ROWS / 2);
+      const int j = col0 + 2 * jg;
+      voff[c] = (u < UNITS && j < a.ldq) ? (8 * mg * a.ldq + j) * 4 : OOB;
+      mrow[c] = 8 * mg;
+      loff[c][0] = tile_off((2 * jg) & (ROWS - 1), mg & 7);
+      loff[c][1] = tile_off((2 * jg + 1) & (ROWS - 1), mg & 7);
+    }
+  }
+  __device__ __forceinline__ void load(const GemmArgs &a, rsrc_t rs, int k0, int kend) {
+#pragma unroll
+    for (int c = 0; c < UQ; ++c)
+#pragma unroll
+      for (int r = 0; r < 8; ++r)
+        raw[c][r] = ld_b64(rs, k0 + mrow[c] + r >= kend ? OOB : voff[c], (k0 + r) * a.ldq * 4);
+  }
+  __device__ __forceinline__ void store(char *tile, int tid) {
+#pragma unroll
+    for (int c = 0; c < UQ; ++c) {
+      if (tid + 256 * c < UNITS) {
+#pragma unroll
+        for (int pl = 0; pl < PLANES; ++pl) {
+          uint4 d0, d1;
+          if (HL) {
+            const uint32_t sel = pl == 0 ? 0x05040100u : 0x07060302u;
+            d0.x = __builtin_amdgcn_perm(raw[c][1].x, raw[c][0].x, sel);
+            d0.y = __builtin_amdgcn_perm(raw[c][3].x, raw[c][2].x, sel);
+            d0.z = __builtin_amdgcn_perm(raw[c][5].x, raw[c][4].x, sel);
+            d0.w = __builtin_amdgcn_perm(raw[c][7].x, raw[c][6].x, sel);
+            d1.x = __builtin_amdgcn_perm(raw[c][1].y, raw[c][0].y, sel);
+            d1.y = __builtin_amdgcn_perm(raw[c][3].y, raw[c][2].y, sel);
+            d1.z = __builtin_amdgcn_perm(raw[c][5].y, raw[c][4].y, sel);
+            d1.w = __builtin_amdgcn_perm(raw[c][7].y, raw[c][6].y, sel);
+          } else {
+#define SNN_PC(r_, f_) bf16_piece(__uint_as_float(raw[c][r_].f_), pl)
+            d0.x = pack2(SNN_PC(0, x), SNN_PC(1, x)); d0.y = pack2(SNN_PC(2, x), SNN_PC(3, x));
+            d0.z = pack2(SNN_PC(4, x), SNN_PC(5, x)); d0.w = pack2(SNN_PC(6, x), SNN_PC(7, x));
+            d1.x = pack2(SNN_PC(0, y), SNN_PC(1, y)); d1.y = pack2(SNN_PC(2, y), SNN_PC(3, y));
+            d1.z = pack2(SNN_PC(4, y), SNN_PC(5, y)); d1.w = pack2(SNN_PC(6, y), SNN_PC(7, y));
+#undef SNN_PC
+          }
+          *(uint4 *)(tile + pl * ROWS * 128 + loff[c][0]) = d0;
+          *(uint4 *)(tile + pl * ROWS * 128 + loff[c][1]) = d1;
+        }
+      }
+    }
+  }
+};
+template <int ROWS, int NPL> struct LoaderQ<Q_T_HL, ROWS, NPL> : LoaderQTWord<ROWS, true> {
   static_assert(NPL == 2, "hi and lo");
-  static constexpr int PLANES = 2;
-  static constexpr int UNITS = ROWS * 4;
-  static constexpr int UQ = (UNITS + 255) / 256;
-  uint2 raw[UQ][8];
-  __device__ __forceinline__ void load(const GemmArgs &a, int col0, int k0, int kend, int tid) {
-    const uint32_t *Q = (const uint32_t *)a.Q;
-#pragma unroll
-    for (int c = 0; c < UQ; ++c) {
-      int u = tid + 256 * c;
-      int jg = u % (ROWS / 2), mg = u / (ROWS / 2);
-      int j = col0 + 2 * jg;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        int m = k0 + 8 * mg + r;
-        uint2 v = make_uint2(0u, 0u);
-        if (u < UNITS && m < kend && j < a.ldq) v = *(const uint2 *)(Q + (size_t)m * a.ldq + j);
-        raw[c][r] = v;
-      }
-    }
-  }
-  __device__ __forceinline__ void store(char *tile, int tid) {
-#pragma unroll
-    for (int c = 0; c < UQ; ++c) {
-      int u = tid + 256 * c;
-      if (u < UNITS) {
-        int jg = u % (ROWS / 2), mg = u / (ROWS / 2);
-        const int o0 = tile_off(2 * jg, mg), o1 = tile_off(2 * jg + 1, mg);
-#pragma unroll
-        for (int pl = 0; pl < 2; ++pl) {
-          const uint32_t sel = pl == 0 ? 0x05040100u : 0x07060302u;
-          uint4 d0, d1;
-          d0.x = __builtin_amdgcn_perm(raw[c][1].x, raw[c][0].x, sel);
-          d0.y = __builtin_amdgcn_perm(raw[c][3].x, raw[c][2].x, sel);
-          d0.z = __builtin_amdgcn_perm(raw[c][5].x, raw[c][4].x, sel);
-          d0.w = __builtin_amdgcn_perm(raw[c][7].x, raw[c][6].x, sel);
-          d1.x = __builtin_amdgcn_perm(raw[c][1].y, raw[c][0].y, sel);
-          d1.y = __builtin_amdgcn_perm(raw[c][3].y, raw[c][2].y, sel);
-          d1.z = __builtin_amdgcn_perm(raw[c][5].y, raw[c][4].y, sel);
-          d1.w = __builtin_amdgcn_perm(raw[c][7].y, raw[c][6].y, sel);
-          *(uint4 *)(tile + pl * ROWS * 128 + o0) = d0;
-          *(uint4 *)(tile + pl * ROWS * 128 + o1) = d1;
-        }
-      }
-    }
-  }
 };
-
-// Q[m][j] fp32, contraction index m slowest; split into three bfloat16 pieces on the way.
-template <int ROWS, int NPL> struct LoaderQ<Q_T_F32S, ROWS, NPL> {
+template <int ROWS, int NPL> struct LoaderQ<Q_T_F32S, ROWS, NPL> : LoaderQTWord<ROWS, false> {
   static_assert(NPL == 3, "hi, mid and lo");
-  static constexpr int PLANES = 3;
-  static constexpr int UNITS = ROWS * 4;
-  static constexpr int UQ = (UNITS + 255) / 256;
-  float2 raw[UQ][8];
-  __device__ __forceinline__ void load(const GemmArgs &a, int col0, int k0, int kend, int tid) {
-    const float *Q = (const float *)a.Q;
-#pragma unroll
-    for (int c = 0; c < UQ; ++c) {
-      int u = tid + 256 * c;
-      int jg = u % (ROWS / 2), mg = u / (ROWS / 2);
-      int j = col0 + 2 * jg;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        int m = k0 + 8 * mg + r;
-        float2 v = make_float2(0.f, 0.f);
-        if (u < UNITS && m < kend && j < a.ldq) v = *(const float2 *)(Q + (size_t)m * a.ldq + j);
-        raw[c][r] = v;
-      }
-    }
-  }
-  __device__ __forceinline__ void store(char *tile, int tid) {
-#pragma unroll
-    for (int c = 0; c < UQ; ++c) {
-      int u = tid + 256 * c;
-      if (u < UNITS) {
-        int jg = u % (ROWS / 2), mg = u / (ROWS / 2);
-        const int o0 = tile_off(2 * jg, mg), o1 = tile_off(2 * jg + 1, mg);
-#pragma unroll
-        for (int pl = 0; pl < 3; ++pl) {
-          uint4 d0, d1;
-          d0.x = pack2(bf16_piece(raw[c][0].x, pl), bf16_piece(raw[c][1].x, pl));
-          d0.y = pack2(bf16_piece(raw[c][2].x, pl), bf16_piece(raw[c][3].x, pl));
-          d0.z = pack2(bf16_piece(raw[c][4].x, pl), bf16_piece(raw[c][5].x, pl));
-          d0.w = pack2(bf16_piece(raw[c][6].x, pl), bf16_piece(raw[c][7].x, pl));
-          d1.x = pack2(bf16_piece(raw[c][0].y, pl), bf16_piece(raw[c][1].y, pl));
-          d1.y = pack2(bf16_piece(raw[c][2].y, pl), bf16_piece(raw[c][3].y, pl));
-          d1.z = pack2(bf16_piece(raw[c][4].y, pl), bf16_piece(raw[c][5].y, pl));
-          d1.w = pack2(bf16_piece(raw[c][6].y, pl), bf16_piece(raw[c][7].y, pl));
-          *(uint4 *)(tile + pl * ROWS * 128 + o0) = d0;
-          *(uint4 *)(tile + pl * ROWS * 128 + o1) = d1;
-        }
-      }
-    }
-  }
 };
 
 // ------------------------------------------------------------------ the kernel
-// 256 threads = WM x WN wavefronts, each owning TM x TN MFMA tiles of 32x32.  One LDS stage;
-// the next tile's global loads are in flight while the MFMAs of the current one run.
-template <int PM, int QM, int EPI, int WM, int WN, int TM, int TN, int NQP>
+// 256 threads = WM x WN wavefronts, each owning TM x TN MFMA tiles of 32x32.  One LDS stage.
+// D register sets form a ring: the global loads of the next D tiles are always in flight, so
+// that a workgroup alone keeps enough bytes outstanding to cover HBM/L2 latency even when
+// few workgroups fit a compute unit.
+template <int PM, int QM, int EPI, int WM, int WN, int TM, int TN, int NQP, int D>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
   static_assert(WM * WN == 4, "four wavefronts per workgroup");
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
@@ -402,20 +373,30 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
   __shared__ __attribute__((aligned(16))) char lds[NPP * PT + NQP * QT];
   char *const lds_q = lds + NPP * PT;
 
-  // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
-  // tiles (column tiles fastest) so that tiles sharing a row slab of P share an L2.
+  // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Without
+  // contraction splits an XCD gets a contiguous run of tiles (column tiles fastest), so tiles
+  // sharing a row slab of P share an L2.  With splits, XCD x takes the splits x, x+8, .. of
+  // every tile: the tiles of one split read the same rows of both operands.
   const int ntiles = a.tiles_m * a.tiles_n;
-  const int per_xcd = (ntiles + 7) >> 3;
-  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (tile >= ntiles) return;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  int tile, split;
+  if (a.splits == 1) {
+    tile = xcd * ((ntiles + 7) >> 3) + slot;
+    split = 0;
+  } else {
+    tile = slot % ntiles;
+    split = (slot / ntiles) * 8 + xcd;
+  }
+  if (tile >= ntiles || split >= a.splits) return;
   const int row0 = (tile / a.tiles_n) * BM;
   const int col0 = (tile % a.tiles_n) * BN;
-  const int kbeg = blockIdx.y * a.kc_per_split;
+  const int kbeg = split * a.kc_per_split;
   const int kend = min(a.kc, kbeg + a.kc_per_split);
   const int nk = kend > kbeg ? (kend - kbeg + 63) >> 6 : 0;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
+  const rsrc_t rp = make_rsrc(a.P, a.p_bytes), rq = make_rsrc(a.Q, a.q_bytes);
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -425,62 +406,70 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  LP lp;
-  LQ lq;
-  if (nk > 0) {
-    lp.load(a, row0, kbeg, kend, tid);
-    lq.load(a, col0, kbeg, kend, tid);
-    lp.store(lds, tid);
-    lq.store(lds_q, tid);
+  LP lp[D];
+  LQ lq[D];
+#pragma unroll
+  for (int d = 0; d < D; ++d) {
+    lp[d].setup(a, row0, tid);
+    lq[d].setup(a, col0, tid);
+    lp[d].load(a, rp, kbeg + d * 64, kend);        // beyond kend the loads return zero
+    lq[d].load(a, rq, kbeg + d * 64, kend);
   }
-  __syncthreads();
 
-  for (int kt = 0; kt < nk; ++kt) {
-    const bool more = kt + 1 < nk;
-    if (more) {
-      lp.load(a, row0, kbeg + (kt + 1) * 64, kend, tid);
-      lq.load(a, col0, kbeg + (kt + 1) * 64, kend, tid);
-    }
+  // fragment addresses: row (lane & 31) of each 32-row block, chunk (lane >> 5) of step 0
+  int fa[TM], fb[TN];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 af[NPP][TM], bq[NQP][TN];
-      const int chunk = ks * 2 + (lane >> 5);
+  for (int i = 0; i < TM; ++i) fa[i] = (wm * TM + i) * 32 + (lane & 31);
 #pragma unroll
-      for (int p = 0; p < NPP; ++p)
+  for (int j = 0; j < TN; ++j) fb[j] = (wn * TN + j) * 32 + (lane & 31);
+
+  // The loop body is free of branches: the ring is run for a multiple of D tiles and the
+  // tiles beyond the range load zeros.  (A load issued under a condition would make every
+  // later wait conservative and serialise the ring.)
+  const int nk_ring = (nk + D - 1) / D * D;
+  for (int kt0 = 0; kt0 < nk_ring; kt0 += D) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-          af[p][i] = *(const bf16x8 *)(lds + p * PT + tile_off((wm * TM + i) * 32 + (lane & 31), chunk));
+    for (int d = 0; d < D; ++d) {
+      const int kt = kt0 + d;
+      lp[d].store(lds, tid);
+      lq[d].store(lds_q, tid);
+      lp[d].load(a, rp, kbeg + (kt + D) * 64, kend);
+      lq[d].load(a, rq, kbeg + (kt + D) * 64, kend);
+      lds_barrier();
 #pragma unroll
-      for (int q = 0; q < NQP; ++q)
+      for (int ks = 0; ks < 4; ++ks) {
+        bf16x8 af[NPP][TM], bq[NQP][TN];
+        const int chunk = ks * 2 + (lane >> 5);
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          bq[q][j] = *(const bf16x8 *)(lds_q + q * QT + tile_off((wn * TN + j) * 32 + (lane & 31), chunk));
-      // smallest products first
+        for (int p = 0; p < NPP; ++p)
 #pragma unroll
-      for (int s = NMAX - 1; s >= 0; --s)
+          for (int i = 0; i < TM; ++i) af[p][i] = *(const bf16x8 *)(lds + p * PT + tile_off(fa[i], chunk));
 #pragma unroll
-        for (int p = 0; p < NPP; ++p) {
-          const int q = s - p;
-          if (q >= 0 && q < NQP) {
+        for (int q = 0; q < NQP; ++q)
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+          for (int j = 0; j < TN; ++j) bq[q][j] = *(const bf16x8 *)(lds_q + q * QT + tile_off(fb[j], chunk));
+        // smallest products first
 #pragma unroll
-              for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[p][i], bq[q][j], acc[i][j], 0, 0, 0);
+        for (int s = NMAX - 1; s >= 0; --s)
+#pragma unroll
+          for (int p = 0; p < NPP; ++p) {
+            const int q = s - p;
+            if (q >= 0 && q < NQP) {
+#pragma unroll
+              for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                  acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[p][i], bq[q][j], acc[i][j], 0, 0, 0);
+            }
           }
-        }
-    }
-    if (more) {
-      __syncthreads();
-      lp.store(lds, tid);
-      lq.store(lds_q, tid);
-      __syncthreads();
+      }
+      lds_barrier();                                 // every wavefront is done with the stage
     }
   }
 
   // Accumulator layout of the 32x32 MFMA: lane holds column (lane & 31); register r holds
   // row 8*(r/4) + 4*(lane/32) + (r%4).
-  float *C = a.C + (size_t)blockIdx.y * a.c_split_stride;
+  float *C = a.C + (size_t)split * a.c_split_stride;
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -513,15 +502,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
     }
 }
 
-template <int PM, int QM, int EPI, int WM, int WN, int TM, int TN, int NQP>
+template <int PM, int QM, int EPI, int WM, int WN, int TM, int TN, int NQP, int D>
 static hipError_t gemm_launch(GemmArgs a, int splits, hipStream_t st) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   a.tiles_m = (a.rows + BM - 1) / BM;
   a.tiles_n = (a.cols + BN - 1) / BN;
   const int ntiles = a.tiles_m * a.tiles_n;
-  const int per_xcd = (ntiles + 7) / 8;
-  dim3 grid(per_xcd * 8, splits, 1);
-  hipLaunchKernelGGL((gemm_kernel<PM, QM, EPI, WM, WN, TM, TN, NQP>), grid, dim3(256), 0, st, a);
+  a.splits = splits;
+  dim3 grid(splits == 1 ? (ntiles + 7) / 8 * 8 : 8 * ntiles * ((splits + 7) / 8), 1, 1);
+  hipLaunchKernelGGL((gemm_kernel<PM, QM, EPI, WM, WN, TM, TN, NQP, D>), grid, dim3(256), 0, st, a);
   return hipGetLastError();
 }
 

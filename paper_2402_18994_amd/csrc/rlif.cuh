@@ -26,8 +26,8 @@ static hipError_t rlif_forward(hipStream_t st, bool fp32, int T, int B, int N, i
   if ((e = fill_zero(st, S, stride)) != hipSuccess) return e;         // hence S_0 = 0
   GemmArgs a;
   memset(&a, 0, sizeof a);
-  a.ldp = ld; a.kc = ld; a.p_align = 8;
-  a.Q = QRf; a.ldq = ldqr; a.q_plane_stride = qr_plane;
+  a.ldp = ld; a.kc = ld; a.p_bytes = (unsigned)stride;
+  a.Q = QRf; a.ldq = ldqr; a.q_plane_stride = qr_plane; a.q_bytes = (unsigned)((fp32 ? 3 : 1) * qr_plane * 2);
   a.rows = B; a.cols = N; a.ldc = ld;
   a.kc_per_split = (ld + 63) / 64 * 64;
   a.beta = beta; a.theta = theta;
@@ -35,8 +35,8 @@ static hipError_t rlif_forward(hipStream_t st, bool fp32, int T, int B, int N, i
     a.P = S + t * stride;
     a.e_cur = I + t * stride; a.e_v = V + t * stride; a.e_s = S + t * stride;
     a.e_out_f = V + (t + 1) * stride; a.e_out_s = S + (t + 1) * stride;
-    if (fp32) e = gemm_launch<P_U8, Q_BF16, EPI_RLIF_FWD, 1, 4, 1, 1, 3>(a, 1, st);
-    else e = gemm_launch<P_U8, Q_BF16, EPI_RLIF_FWD, 1, 4, 1, 1, 1>(a, 1, st);
+    if (fp32) e = gemm_launch<P_U8, Q_BF16, EPI_RLIF_FWD, 1, 4, 1, 1, 3, 1>(a, 1, st);
+    else e = gemm_launch<P_U8, Q_BF16, EPI_RLIF_FWD, 1, 4, 1, 1, 1, 2>(a, 1, st);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
@@ -53,8 +53,8 @@ static hipError_t rlif_reverse(hipStream_t st, bool fp32, int T, int B, int N, i
   if ((e = fill_zero(st, dI + (size_t)(T - 1) * stride, stride * 4)) != hipSuccess) return e;   // dI_{T-1} = 0
   GemmArgs a;
   memset(&a, 0, sizeof a);
-  a.ldp = ld; a.kc = ld;
-  a.Q = QRb; a.ldq = ldqr; a.q_plane_stride = qr_plane;
+  a.ldp = ld; a.kc = ld; a.p_bytes = (unsigned)(stride * 4);
+  a.Q = QRb; a.ldq = ldqr; a.q_plane_stride = qr_plane; a.q_bytes = (unsigned)((fp32 ? 3 : 1) * qr_plane * 2);
   a.rows = B; a.cols = N; a.ldc = ld;
   a.kc_per_split = (ld + 63) / 64 * 64;
   a.beta = beta; a.theta = theta; a.surrogate = surrogate; a.slope = slope;
@@ -66,8 +66,8 @@ static hipError_t rlif_reverse(hipStream_t st, bool fp32, int T, int B, int N, i
     a.e_cur = dS + t * stride; a.e_v = V + t * stride;
     a.e_g = g[cur]; a.e_out_f = g[cur ^ 1];
     a.e_out_di = t > 0 ? dI + (size_t)(t - 1) * stride : nullptr;
-    if (fp32) e = gemm_launch<P_F32S, Q_BF16, EPI_RLIF_REV, 1, 4, 1, 1, 3>(a, 1, st);
-    else e = gemm_launch<P_HL, Q_BF16, EPI_RLIF_REV, 1, 4, 1, 1, 1>(a, 1, st);
+    if (fp32) e = gemm_launch<P_F32S, Q_BF16, EPI_RLIF_REV, 1, 4, 1, 1, 3, 1>(a, 1, st);
+    else e = gemm_launch<P_HL, Q_BF16, EPI_RLIF_REV, 1, 4, 1, 1, 1, 2>(a, 1, st);
     if (e != hipSuccess) return e;
     cur ^= 1;
   }

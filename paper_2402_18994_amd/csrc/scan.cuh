@@ -140,6 +140,107 @@ __global__ __launch_bounds__(256) void lif_reverse_kernel(const float *__restric
   }
 }
 
+// ---------------------------------------------------------------- cooperative scans
+// With few chains (B*N of the order of the number of SIMDs) one wavefront per 64 chains
+// cannot keep enough loads in flight: a wavefront has at most 63 outstanding memory
+// operations.  Here NW wavefronts share 64 chains.  Time is cut into rounds of NW*U steps;
+// in a round wavefront w fetches steps [w*U, w*U+U) of the round (all NW*U rows in flight at
+// once, the next round's already requested), then the wavefronts integrate their segments
+// one after the other, handing the state on through LDS.  The serial part is a few
+// instructions per step; the memory system sees NW times the parallelism.
+template <int NW, int U>
+__global__ __launch_bounds__(NW * 64) void lif_forward_coop_kernel(const float *__restrict__ I, float *__restrict__ V,
+                                                                   uint8_t *__restrict__ S, int T, long long stride,
+                                                                   float beta, float theta) {
+  __shared__ float hand[64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const long long p0 = (long long)blockIdx.x * 64 + lane;
+  const bool live = p0 < stride;
+  const long long p = live ? p0 : 0;
+  I += p; V += p; S += p;
+  float a[U], b[U];
+  auto fetch = [&](float (&buf)[U], int t0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (t0 + u < T) buf[u] = I[(long long)(t0 + u) * stride];
+  };
+  auto turn = [&](float (&buf)[U], int t0) {
+    for (int ww = 0; ww < NW; ++ww) {
+      if (ww == w) {
+        float v = hand[lane];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (t0 + u < T) {
+            const bool s = v > theta;
+            if (live) {
+              V[(long long)(t0 + u) * stride] = v;
+              S[(long long)(t0 + u) * stride] = s ? 1 : 0;
+            }
+            v = beta * v + buf[u] - (s ? theta : 0.f);
+          }
+        hand[lane] = v;
+      }
+      lds_barrier();
+    }
+  };
+  if (w == 0) hand[lane] = 0.f;                    // V_0 = 0
+  fetch(a, w * U);
+  lds_barrier();
+  for (int r0 = 0; r0 < T; r0 += 2 * NW * U) {
+    fetch(b, r0 + NW * U + w * U);
+    turn(a, r0 + w * U);
+    fetch(a, r0 + 2 * NW * U + w * U);
+    turn(b, r0 + NW * U + w * U);
+  }
+}
+
+template <int NW, int U, int SURR, bool HL>
+__global__ __launch_bounds__(NW * 64) void lif_reverse_coop_kernel(const float *__restrict__ dS,
+                                                                   const float *__restrict__ V,
+                                                                   uint32_t *__restrict__ dI, int T, long long stride,
+                                                                   float beta, float theta, float slope) {
+  __shared__ float hand[64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const long long p0 = (long long)blockIdx.x * 64 + lane;
+  const bool live = p0 < stride;
+  const long long p = live ? p0 : 0;
+  dS += p; V += p; dI += p;
+  float a_ds[U], a_v[U], b_ds[U], b_v[U];
+  // a segment covers steps thi, thi-1, .., thi-U+1
+  auto fetch = [&](float (&bds)[U], float (&bv)[U], int thi) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (thi - u >= 0) {
+        bds[u] = dS[(long long)(thi - u) * stride];
+        bv[u] = V[(long long)(thi - u) * stride];
+      }
+  };
+  auto turn = [&](float (&bds)[U], float (&bv)[U], int thi) {
+    for (int ww = 0; ww < NW; ++ww) {
+      if (ww == w) {
+        float g = hand[lane];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (thi - u >= 0) {
+            if (live) dI[(long long)(thi - u) * stride] = HL ? pack_hl(g) : __float_as_uint(g);
+            g = beta * g + surr<SURR>(slope, bv[u] - theta) * (bds[u] - theta * g);
+          }
+        hand[lane] = g;
+      }
+      lds_barrier();
+    }
+  };
+  if (w == 0) hand[lane] = 0.f;                    // g_T = 0
+  fetch(a_ds, a_v, T - 1 - w * U);
+  lds_barrier();
+  for (int r0 = T - 1; r0 >= 0; r0 -= 2 * NW * U) {
+    fetch(b_ds, b_v, r0 - NW * U - w * U);
+    turn(a_ds, a_v, r0 - w * U);
+    fetch(a_ds, a_v, r0 - 2 * NW * U - w * U);
+    turn(b_ds, b_v, r0 - NW * U - w * U);
+  }
+}
+
 // ---------------------------------------------------------------- LI readout, max over time
 // y_t = beta y_{t-1} + J_t, y_{-1} = 0; z = max_t y_t; t* = first maximiser.
 __global__ __launch_bounds__(256) void readout_forward_kernel(const float *__restrict__ J, float *__restrict__ Y,
@@ -290,6 +391,16 @@ __global__ __launch_bounds__(256) void readout_reverse_kernel(const float *__res
 }
 
 // ---------------------------------------------------------------- small utilities
+// dst[m][0..ld) = src[m][0..n) followed by zeros (input rasters whose rows are not 4-byte multiples).
+__global__ __launch_bounds__(256) void pad_rows_kernel(const uint8_t *__restrict__ src, uint8_t *__restrict__ dst,
+                                                       long long rows, int n, int ld) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows * ld) return;
+  const long long r = i / ld;
+  const int k = (int)(i - r * ld);
+  dst[i] = k < n ? src[r * n + k] : 0;
+}
+
 __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *__restrict__ p, long long n_dwords) {
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n_dwords) p[i] = 0u;

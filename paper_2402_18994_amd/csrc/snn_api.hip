@@ -67,7 +67,9 @@ struct snn_ctx {
   size_t ws_bytes = 0;
   hipStream_t stream = nullptr;
   int state = 0;                  // 0 fresh, 1 forward done, 2 backward done
-  const uint8_t *x_dev = nullptr;
+  const uint8_t *x_eff = nullptr;  // raster the products read: the caller's, or x_pad
+  uint8_t *x_pad = nullptr;        // zero-padded copy, only when N_0 is not a multiple of 4
+  int ldx = 0;                     // row length of x_eff
   const int32_t *labels_dev = nullptr;
   std::string err;
   Prof prof;
@@ -111,6 +113,9 @@ int validate(const snn_config *cfg) {
   if (cfg->surrogate < 0 || cfg->surrogate > 3) return fail(nullptr, SNN_ERR_ARG, "unknown surrogate");
   if (cfg->precision < 0 || cfg->precision > 1) return fail(nullptr, SNN_ERR_ARG, "unknown precision");
   if ((long long)cfg->T * cfg->B > (1ll << 30)) return fail(nullptr, SNN_ERR_ARG, "T*B too large");
+  for (int i = 0; i <= cfg->n_layers; ++i)      // byte offsets into one tensor are 31-bit
+    if ((long long)cfg->T * cfg->B * (cfg->sizes[i] + 8) * 4 >= (1ll << 31))
+      return fail(nullptr, SNN_ERR_ARG, "T*B*sizes[%d] too large: a tensor must stay below 2 GiB", i);
   return SNN_OK;
 }
 
@@ -134,6 +139,17 @@ int choose_splits(long long M, int tiles, long long *per_split) {
 int wgrad_tiles(int rows, int cols) {
   int bn = cols <= 32 ? 32 : (cols <= 64 ? 64 : 128);
   return ((rows + 127) / 128) * ((cols + bn - 1) / bn);
+}
+
+// Rows of C per workgroup for the products over all T*B rows whose output is wider than 64
+// columns: the tallest tile that still gives every compute unit a few workgroups.
+int pick_rows_per_tile(long long rows, int cols) {
+  static const int forced = [] { const char *e = getenv("SNN_TILE_ROWS"); return e ? atoi(e) : 0; }();
+  if (forced == 32 || forced == 64 || forced == 128) return forced;     // tuning knob
+  const long long col_tiles = (cols + 127) / 128;
+  if ((rows + 127) / 128 * col_tiles >= 512) return 128;
+  if ((rows + 63) / 64 * col_tiles >= 512) return 64;
+  return 32;
 }
 
 // Walks the workspace layout; with base == nullptr it only counts.
@@ -187,6 +203,8 @@ void carve(snn_ctx &c, Carver &cv) {
       y.dS = cv.take<float>(M * y.ld);
     }
   }
+  c.ldx = c.sizes[0] % 4 == 0 ? c.sizes[0] : (int)rup(c.sizes[0], 8);
+  if (c.ldx != c.sizes[0]) c.x_pad = cv.take<uint8_t>(M * c.ldx);
   c.z = cv.take<float>((size_t)c.B * c.ldC);
   c.dz = cv.take<float>((size_t)c.B * c.ldC);
   c.tstar = cv.take<int>((size_t)c.B * c.ldC);
@@ -242,41 +260,57 @@ struct Bracket {
 };
 
 // ------------------------------------------------------------------ launches
-int u8_align(const void *p, int ld, int valid, int want) {
-  const uintptr_t a = (uintptr_t)p;
-  if (want >= 8 && a % 8 == 0 && ld % 8 == 0 && valid % 8 == 0) return 8;
-  if (a % 4 == 0 && ld % 4 == 0 && valid % 4 == 0) return 4;
-  return 1;
+// The product kernels read spike rows with 4-byte loads.  A raster whose row length is not a
+// multiple of 4 is first copied into a zero-padded buffer of the workspace (one extra pass,
+// only for such sizes); otherwise it is read in place.
+int prepare_input(snn_ctx *c, const uint8_t *x) {
+  if (!x) return fail(c, SNN_ERR_NULL, "input raster is NULL");
+  if (c->x_pad) {
+    const long long n = c->M * c->ldx;
+    hipLaunchKernelGGL(pad_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, x, c->x_pad,
+                       c->M, c->sizes[0], c->ldx);
+    HIPCHK(c, hipGetLastError());
+    c->x_eff = c->x_pad;
+  } else {
+    if ((uintptr_t)x % 4 != 0) return fail(c, SNN_ERR_ARG, "x_dev must be 4-byte aligned");
+    c->x_eff = x;
+  }
+  return SNN_OK;
 }
 
 // Spikes feeding layer index l: the input raster for l == 0, else S of the layer below.
-struct SpikeSrc { const uint8_t *p; int ld; int valid; };
-SpikeSrc spikes_below(snn_ctx *c, int l, const uint8_t *x) {
-  if (l == 0) return {x, c->sizes[0], c->sizes[0]};
-  return {c->layers[l - 1].S, c->layers[l - 1].ld, c->layers[l - 1].ld};
+struct SpikeSrc { const uint8_t *p; int ld; int valid; unsigned bytes; };
+SpikeSrc spikes_below(snn_ctx *c, int l) {
+  if (l == 0) return {c->x_eff, c->ldx, c->ldx, (unsigned)(c->M * c->ldx)};
+  return {c->layers[l - 1].S, c->layers[l - 1].ld, c->layers[l - 1].ld, (unsigned)(c->M * c->layers[l - 1].ld)};
 }
 
 // I^l = S^{l-1} W^l over all T*B rows at once.
-int launch_current_gemm(snn_ctx *c, int l, const uint8_t *x) {
+int launch_current_gemm(snn_ctx *c, int l) {
   Layer &y = c->layers[l];
-  SpikeSrc s = spikes_below(c, l, x);
+  SpikeSrc s = spikes_below(c, l);
   if (!s.p) return fail(c, SNN_ERR_NULL, "input raster is NULL");
   GemmArgs a;
   memset(&a, 0, sizeof a);
-  a.P = s.p; a.ldp = s.ld; a.kc = s.valid; a.p_align = u8_align(s.p, s.ld, s.valid, 8);
-  a.Q = y.Qf; a.ldq = y.ldqf; a.q_plane_stride = y.qf_plane;
+  a.P = s.p; a.ldp = s.ld; a.kc = s.valid; a.p_bytes = s.bytes;
+  a.Q = y.Qf; a.ldq = y.ldqf; a.q_plane_stride = y.qf_plane; a.q_bytes = (unsigned)(c->nplanes * y.qf_plane * 2);
   a.C = y.I; a.ldc = y.ld; a.rows = (int)c->M; a.cols = y.N;
   a.kc_per_split = (int)rup(a.kc, 64);
   Bracket br(c, SNN_K_CURRENT_GEMM, l + 1);
   hipError_t e;
+  const int bm = pick_rows_per_tile(c->M, y.N);
   if (c->precision == SNN_PREC_FP32) {
-    if (y.N <= 32) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 4, 1, 1, 1, 3>(a, 1, c->stream);
-    else if (y.N <= 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 1, 3>(a, 1, c->stream);
-    else e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 2, 3>(a, 1, c->stream);
+    if (y.N <= 32) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 4, 1, 1, 1, 3, 1>(a, 1, c->stream);
+    else if (y.N <= 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 1, 3, 1>(a, 1, c->stream);
+    else if (bm == 128) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 2, 3, 1>(a, 1, c->stream);
+    else if (bm == 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 1, 2, 3, 1>(a, 1, c->stream);
+    else e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 1, 4, 1, 1, 3, 1>(a, 1, c->stream);
   } else {
-    if (y.N <= 32) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 4, 1, 1, 1, 1>(a, 1, c->stream);
-    else if (y.N <= 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 1, 1>(a, 1, c->stream);
-    else e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 2, 1>(a, 1, c->stream);
+    if (y.N <= 32) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 4, 1, 1, 1, 1, 1>(a, 1, c->stream);
+    else if (y.N <= 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 1, 1, 1>(a, 1, c->stream);
+    else if (bm == 128) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 2, 1, 1>(a, 1, c->stream);
+    else if (bm == 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 1, 2, 1, 1>(a, 1, c->stream);
+    else e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 1, 4, 1, 1, 1, 1>(a, 1, c->stream);
   }
   HIPCHK(c, e);
   return SNN_OK;
@@ -288,18 +322,21 @@ int launch_input_grad(snn_ctx *c, int l) {
   Layer &below = c->layers[l - 1];
   GemmArgs a;
   memset(&a, 0, sizeof a);
-  a.P = y.dI; a.ldp = y.ld; a.kc = y.ld;
-  a.Q = y.Qb; a.ldq = y.ldqb; a.q_plane_stride = y.qb_plane;
+  a.P = y.dI; a.ldp = y.ld; a.kc = y.ld; a.p_bytes = (unsigned)(c->M * y.ld * 4);
+  a.Q = y.Qb; a.ldq = y.ldqb; a.q_plane_stride = y.qb_plane; a.q_bytes = (unsigned)(c->nplanes * y.qb_plane * 2);
   a.C = below.dS; a.ldc = below.ld; a.rows = (int)c->M; a.cols = y.K;
   a.kc_per_split = (int)rup(a.kc, 64);
   Bracket br(c, SNN_K_INPUT_GRAD, l + 1);
   hipError_t e;
+  const int bm = pick_rows_per_tile(c->M, y.K);
   if (c->precision == SNN_PREC_FP32) {
-    if (y.K <= 32) e = gemm_launch<P_F32S, Q_BF16, EPI_STORE, 4, 1, 1, 1, 3>(a, 1, c->stream);
-    else e = gemm_launch<P_F32S, Q_BF16, EPI_STORE, 2, 2, 1, 1, 3>(a, 1, c->stream);
+    if (y.K <= 32) e = gemm_launch<P_F32S, Q_BF16, EPI_STORE, 4, 1, 1, 1, 3, 1>(a, 1, c->stream);
+    else e = gemm_launch<P_F32S, Q_BF16, EPI_STORE, 2, 2, 1, 1, 3, 1>(a, 1, c->stream);
   } else {
-    if (y.K <= 32) e = gemm_launch<P_HL, Q_BF16, EPI_STORE, 4, 1, 1, 1, 1>(a, 1, c->stream);
-    else e = gemm_launch<P_HL, Q_BF16, EPI_STORE, 2, 2, 2, 2, 1>(a, 1, c->stream);
+    if (y.K <= 32) e = gemm_launch<P_HL, Q_BF16, EPI_STORE, 4, 1, 1, 1, 1, 2>(a, 1, c->stream);
+    else if (bm == 128) e = gemm_launch<P_HL, Q_BF16, EPI_STORE, 2, 2, 2, 2, 1, 2>(a, 1, c->stream);
+    else if (bm == 64) e = gemm_launch<P_HL, Q_BF16, EPI_STORE, 2, 2, 1, 2, 1, 2>(a, 1, c->stream);
+    else e = gemm_launch<P_HL, Q_BF16, EPI_STORE, 1, 4, 1, 1, 1, 2>(a, 1, c->stream);
   }
   HIPCHK(c, e);
   return SNN_OK;
@@ -311,21 +348,21 @@ int launch_tn(snn_ctx *c, SpikeSrc s, int rows, const void *G, int ldg, int cols
               int splits, long long per) {
   GemmArgs a;
   memset(&a, 0, sizeof a);
-  a.P = s.p; a.ldp = s.ld; a.p_ivalid = s.valid; a.p_align = u8_align(s.p, s.ld, s.valid, 4);
-  a.Q = G; a.ldq = ldg;
+  a.P = s.p; a.ldp = s.ld; a.p_ivalid = s.valid; a.p_bytes = s.bytes;
+  a.Q = G; a.ldq = ldg; a.q_bytes = (unsigned)(c->M * ldg * 4);
   a.rows = rows; a.cols = cols; a.ldc = cols; a.kc = (int)c->M;
   a.kc_per_split = (int)per;
   a.c_split_stride = (long long)rows * cols;
   a.C = splits > 1 ? part : out;
   hipError_t e;
   if (c->precision == SNN_PREC_FP32) {
-    if (cols <= 32) e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 4, 1, 1, 1, 3>(a, splits, c->stream);
-    else if (cols <= 64) e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 1, 3>(a, splits, c->stream);
-    else e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 2, 3>(a, splits, c->stream);
+    if (cols <= 32) e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 4, 1, 1, 1, 3, 1>(a, splits, c->stream);
+    else if (cols <= 64) e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 1, 3, 1>(a, splits, c->stream);
+    else e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 2, 3, 1>(a, splits, c->stream);
   } else {
-    if (cols <= 32) e = gemm_launch<P_T_U8, Q_T_HL, EPI_STORE, 4, 1, 1, 1, 2>(a, splits, c->stream);
-    else if (cols <= 64) e = gemm_launch<P_T_U8, Q_T_HL, EPI_STORE, 2, 2, 2, 1, 2>(a, splits, c->stream);
-    else e = gemm_launch<P_T_U8, Q_T_HL, EPI_STORE, 2, 2, 2, 2, 2>(a, splits, c->stream);
+    if (cols <= 32) e = gemm_launch<P_T_U8, Q_T_HL, EPI_STORE, 4, 1, 1, 1, 2, 1>(a, splits, c->stream);
+    else if (cols <= 64) e = gemm_launch<P_T_U8, Q_T_HL, EPI_STORE, 2, 2, 2, 1, 2, 1>(a, splits, c->stream);
+    else e = gemm_launch<P_T_U8, Q_T_HL, EPI_STORE, 2, 2, 2, 2, 2, 1>(a, splits, c->stream);
   }
   HIPCHK(c, e);
   return SNN_OK;
@@ -347,27 +384,74 @@ int launch_reduce(snn_ctx *c, const ReduceJobs &jobs) {
 
 // dW^l = S^{l-1}^T dI^l and, for a recurrent layer, dR^l = S^l^T dI^l: the split products.
 // Their partial sums are queued on `jobs` and reduced by one launch for all layers.
-int launch_weight_grad(snn_ctx *c, int l, const uint8_t *x, ReduceJobs &jobs) {
+int launch_weight_grad(snn_ctx *c, int l, ReduceJobs &jobs) {
   Layer &y = c->layers[l];
-  SpikeSrc s = spikes_below(c, l, x);
+  SpikeSrc s = spikes_below(c, l);
   if (!s.p) return fail(c, SNN_ERR_NULL, "input raster is NULL");
   Bracket br(c, SNN_K_WEIGHT_GRAD, l + 1);
   int rc = launch_tn(c, s, y.K, y.dI, y.ld, y.N, y.dW, y.part_w, y.splits_w, y.per_w);
   if (rc) return rc;
   add_reduce_job(jobs, y.part_w, y.dW, y.splits_w, (long long)y.K * y.N);
   if (y.recurrent) {
-    SpikeSrc own = {y.S, y.ld, y.ld};
+    SpikeSrc own = {y.S, y.ld, y.ld, (unsigned)(c->M * y.ld)};
     rc = launch_tn(c, own, y.N, y.dI, y.ld, y.N, y.dR, y.part_r, y.splits_r, y.per_r);
     add_reduce_job(jobs, y.part_r, y.dR, y.splits_r, (long long)y.N * y.N);
   }
   return rc;
 }
 
+// Which scan kernel: 1 = four wavefronts share 64 chains, 2 = eight do, 0 = one thread per
+// VEC chains.  The cooperative forms are for chain counts too small to fill the chip.
+int scan_mode(long long chains) {
+  static const int forced = [] { const char *e = getenv("SNN_SCAN_MODE"); return e ? atoi(e) : -1; }();
+  if (forced >= 0 && forced <= 2) return forced;     // tuning knob
+  (void)chains;
+  return 0;
+}
+
+// Threads per workgroup of the one-thread-per-chain scans: single wavefronts while that is
+// what it takes to give each of the 256 compute units (8 XCDs x 32) something to do.
+int scan_block(long long threads) {
+  static const int forced = [] { const char *e = getenv("SNN_SCAN_BLOCK"); return e ? atoi(e) : 0; }();
+  if (forced == 64 || forced == 128 || forced == 256) return forced;    // tuning knob
+  return threads >= 256 * 1024 ? 256 : 64;
+}
+
+template <int NW, int U>
+hipError_t lif_fwd_coop_launch(snn_ctx *c, Layer &y) {
+  const long long stride = (long long)c->B * y.ld;
+  hipLaunchKernelGGL((lif_forward_coop_kernel<NW, U>), dim3((unsigned)((stride + 63) / 64)), dim3(NW * 64), 0,
+                     c->stream, y.I, y.V, y.S, c->T, stride, y.beta, c->theta);
+  return hipGetLastError();
+}
+
+template <int NW, int U, bool HL>
+hipError_t lif_rev_coop_launch2(snn_ctx *c, Layer &y) {
+  const long long stride = (long long)c->B * y.ld;
+  dim3 grid((unsigned)((stride + 63) / 64)), block(NW * 64);
+#define SNN_REVC(SU)                                                                                            \
+  hipLaunchKernelGGL((lif_reverse_coop_kernel<NW, U, SU, HL>), grid, block, 0, c->stream, y.dS, y.V, y.dI, c->T, \
+                     stride, y.beta, c->theta, c->slope)
+  switch (c->surrogate) {
+    case 0: SNN_REVC(0); break;
+    case 1: SNN_REVC(1); break;
+    case 2: SNN_REVC(2); break;
+    default: SNN_REVC(3); break;
+  }
+#undef SNN_REVC
+  return hipGetLastError();
+}
+template <int NW, int U>
+hipError_t lif_rev_coop_launch(snn_ctx *c, Layer &y) {
+  return c->hl ? lif_rev_coop_launch2<NW, U, true>(c, y) : lif_rev_coop_launch2<NW, U, false>(c, y);
+}
+
 template <int VEC, int U>
 hipError_t lif_fwd_launch(snn_ctx *c, Layer &y) {
   const long long stride = (long long)c->B * y.ld;
   const long long threads = stride / VEC;
-  hipLaunchKernelGGL((lif_forward_kernel<VEC, U>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream,
+  const int bs = scan_block(threads);
+  hipLaunchKernelGGL((lif_forward_kernel<VEC, U>), dim3((unsigned)((threads + bs - 1) / bs)), dim3(bs), 0, c->stream,
                      y.I, y.V, y.S, c->T, stride, y.beta, c->theta);
   return hipGetLastError();
 }
@@ -383,7 +467,10 @@ int launch_lif_forward(snn_ctx *c, int l) {
   Bracket br(c, SNN_K_LIF_FORWARD, l + 1);
   const long long chains = (long long)c->B * y.ld;
   hipError_t e;
-  if (chains >= (1 << 19)) e = lif_fwd_launch<4, 8>(c, y);
+  const int mode = scan_mode(chains);
+  if (mode == 1) e = lif_fwd_coop_launch<4, 32>(c, y);
+  else if (mode == 2) e = lif_fwd_coop_launch<8, 16>(c, y);
+  else if (chains >= (1 << 19)) e = lif_fwd_launch<4, 8>(c, y);
   else if (chains >= (1 << 17)) e = lif_fwd_launch<2, 16>(c, y);
   else e = lif_fwd_launch<1, 32>(c, y);
   HIPCHK(c, e);
@@ -394,7 +481,8 @@ template <int VEC, int U, bool HL>
 hipError_t lif_rev_launch2(snn_ctx *c, Layer &y) {
   const long long stride = (long long)c->B * y.ld;
   const long long threads = stride / VEC;
-  dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+  const int bs = scan_block(threads);
+  dim3 grid((unsigned)((threads + bs - 1) / bs)), block(bs);
 #define SNN_REV(SU)                                                                                          \
   hipLaunchKernelGGL((lif_reverse_kernel<VEC, U, SU, HL>), grid, block, 0, c->stream, y.dS, y.V, y.dI, c->T, \
                      stride, y.beta, c->theta, c->slope)
@@ -423,7 +511,10 @@ int launch_lif_reverse(snn_ctx *c, int l) {
   Bracket br(c, SNN_K_LIF_REVERSE, l + 1);
   const long long chains = (long long)c->B * y.ld;
   hipError_t e;
-  if (chains >= (1 << 19)) e = lif_rev_launch<4, 4>(c, y);
+  const int mode = scan_mode(chains);
+  if (mode == 1) e = lif_rev_coop_launch<4, 16>(c, y);
+  else if (mode == 2) e = lif_rev_coop_launch<8, 16>(c, y);
+  else if (chains >= (1 << 19)) e = lif_rev_launch<4, 4>(c, y);
   else if (chains >= (1 << 17)) e = lif_rev_launch<2, 8>(c, y);
   else e = lif_rev_launch<1, 16>(c, y);
   HIPCHK(c, e);
@@ -658,10 +749,11 @@ int32_t snn_init(const snn_config *cfg, void *workspace_dev, size_t workspace_by
 int32_t snn_forward(snn_ctx *c, const uint8_t *x_dev, const int32_t *labels_dev, float *loss_host) {
   if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
   if (!x_dev || !labels_dev) return fail(c, SNN_ERR_NULL, "x_dev or labels_dev is NULL");
-  c->x_dev = x_dev; c->labels_dev = labels_dev;
+  c->labels_dev = labels_dev;
   int rc;
+  if ((rc = prepare_input(c, x_dev))) return rc;
   for (int l = 0; l < c->L; ++l) {
-    if ((rc = launch_current_gemm(c, l, x_dev))) return rc;
+    if ((rc = launch_current_gemm(c, l))) return rc;
     if (c->layers[l].spiking) {
       if ((rc = launch_lif_forward(c, l))) return rc;
     } else {
@@ -685,7 +777,7 @@ int32_t snn_backward(snn_ctx *c) {
   if ((rc = launch_readout_reverse(c))) return rc;
   for (int l = c->L - 1; l >= 0; --l) {
     if (c->layers[l].spiking && (rc = launch_lif_reverse(c, l))) return rc;
-    if ((rc = launch_weight_grad(c, l, c->x_dev, jobs))) return rc;
+    if ((rc = launch_weight_grad(c, l, jobs))) return rc;
     if (l > 0 && (rc = launch_input_grad(c, l))) return rc;
   }
   {
@@ -761,8 +853,12 @@ int32_t snn_run_step(snn_ctx *c, int32_t step, int32_t layer, const uint8_t *x_d
   if (layer < 1 || layer > c->L) return fail(c, SNN_ERR_ARG, "layer %d out of range", layer);
   const int l = layer - 1;
   const bool spiking = c->layers[l].spiking;
+  if (x_dev) {
+    int rc = prepare_input(c, x_dev);
+    if (rc) return rc;
+  }
   switch (step) {
-    case SNN_STEP_CURRENT_GEMM: return launch_current_gemm(c, l, x_dev);
+    case SNN_STEP_CURRENT_GEMM: return launch_current_gemm(c, l);
     case SNN_STEP_LIF_FORWARD:
       if (!spiking) return fail(c, SNN_ERR_ARG, "layer %d is not spiking", layer);
       return launch_lif_forward(c, l);
@@ -774,7 +870,7 @@ int32_t snn_run_step(snn_ctx *c, int32_t step, int32_t layer, const uint8_t *x_d
     case SNN_STEP_WEIGHT_GRAD: {
       ReduceJobs jobs;
       memset(&jobs, 0, sizeof jobs);
-      int rc = launch_weight_grad(c, l, x_dev, jobs);
+      int rc = launch_weight_grad(c, l, jobs);
       return rc ? rc : launch_reduce(c, jobs);
     }
     case SNN_STEP_INPUT_GRAD:
