@@ -90,7 +90,10 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="shd_ff128")
-    ap.add_argument("--dominant", default="lif_reverse:1", help="kernel:layer bracketed for the roofline line")
+    ap.add_argument("--dominant", default="lif_reverse:0",
+                    help="kernel:layer bracketed for the roofline line (layer 0 = every layer)")
+    ap.add_argument("--traffic", type=float, default=None,
+                    help="measured HBM bytes per launch of the dominant kernel (from the rocprofv3 --pmc runs)")
     ap.add_argument("--breakdown", action="store_true", help="time every kernel class first (stderr)")
     ap.add_argument("--no-cpu", action="store_true")
     args = ap.parse_args()
@@ -118,6 +121,17 @@ def main():
         snn.backward()
         snn.sgd_step(lr)
 
+    # A plain device copy of known size: the reference the FETCH_SIZE / WRITE_SIZE counters of a
+    # rocprofv3 --pmc run are scaled by (256 MiB read, 256 MiB written; the source is pushed out
+    # of the caches first by writing 512 MiB elsewhere).
+    cal_src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
+    cal_dst = torch.empty_like(cal_src)
+    torch.empty(512 << 20, dtype=torch.uint8, device=dev).zero_()
+    cal_dst.copy_(cal_src)
+    del cal_src, cal_dst
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -135,8 +149,17 @@ def main():
                       file=sys.stderr)
         snn.profile_select("none", 0)
 
+    # cost of an empty pair of events on the stream: subtracted from the bracketed launches
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(100)]
+    for i in range(0, 100, 2):
+        evs[i].record(); evs[i + 1].record()
+    torch.cuda.synchronize()
+    gaps = sorted(evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(0, 100, 2))
+    ev_overhead_us = gaps[len(gaps) // 2]
+
     kname, klayer = args.dominant.split(":")
     klayer = int(klayer)
+    blayer = klayer if klayer else 1          # layers of equal width move equal bytes per launch
     snn.profile_select(kname, klayer)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -150,8 +173,9 @@ def main():
 
     ms_per_step = dt / args.steps * 1e3
     value = wl.B * args.steps / dt
-    abytes = algorithmic_bytes(wl, kname, klayer)
-    k_avg_s = k_ms / max(1, k_n) * 1e-3
+    abytes = algorithmic_bytes(wl, kname, blayer)
+    k_raw_us = k_ms / max(1, k_n) * 1e3
+    k_avg_s = max(k_raw_us - ev_overhead_us, 1e-3) * 1e-6
     achieved = abytes / k_avg_s / 1e9 if k_n else 0.0
     out = {
         "metric": "training samples/sec (fwd+bwd BPTT + SGD step), T=%d, B=%d" % (wl.T, wl.B),
@@ -163,10 +187,12 @@ def main():
                                f"bf16 products / fp32 state" if wl.precision == "bf16" else
                                f"{wl.name}: {'-'.join(map(str, wl.sizes))}, T={wl.T}, B={wl.B}, fp32",
                    "final_loss": loss},
-        "roofline": {"bound": "hbm", "kernel": f"{kname} layer {klayer}", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": f"{kname}" + (f" layer {klayer}" if klayer else " (all layers)"),
+                     "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "algorithmic_bytes_per_launch": abytes,
-                     "avg_launch_us": k_avg_s * 1e6, "launches": k_n},
+                     "traffic": args.traffic, "algorithmic_bytes_per_launch": abytes,
+                     "avg_launch_us": k_avg_s * 1e6, "avg_launch_us_with_events": k_raw_us,
+                     "event_pair_overhead_us": ev_overhead_us, "launches": k_n},
         "gemm_tflops_whole_step": gemm_flops(wl) / (dt / args.steps) / 1e12,
     }
     if not args.no_cpu:

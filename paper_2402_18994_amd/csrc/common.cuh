@@ -46,6 +46,47 @@ __device__ __forceinline__ uint32_t spikes2_to_bf16(uint32_t two_bytes_spread) {
   return (two_bytes_spread & 0x00010001u) * 0x3F80u;
 }
 
+// ---------------------------------------------------------------- buffer addressing
+// Global accesses of the hot kernels go through buffer instructions: a 128-bit resource
+// (base, size), a per-lane byte offset kept in one register, and a scalar byte offset.  The
+// per-step or per-tile address arithmetic then runs on the scalar unit, and a lane offset
+// beyond the size reads zero / drops the store.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+constexpr int OOB = 0x7FFFFF00;          // beyond any buffer here
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void *base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ uint32_t ld_b8(rsrc_t r, int voff, int soff) {
+  return (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(r, voff, soff, 0);
+}
+__device__ __forceinline__ uint32_t ld_b32(rsrc_t r, int voff, int soff) {
+  return __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0);
+}
+__device__ __forceinline__ u32x2 ld_b64(rsrc_t r, int voff, int soff) {
+  return __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+}
+__device__ __forceinline__ u32x4 ld_b128(rsrc_t r, int voff, int soff) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+}
+__device__ __forceinline__ void st_b8(rsrc_t r, int voff, int soff, uint32_t v) {
+  __builtin_amdgcn_raw_buffer_store_b8((unsigned char)v, r, voff, soff, 0);
+}
+__device__ __forceinline__ void st_b16(rsrc_t r, int voff, int soff, uint32_t v) {
+  __builtin_amdgcn_raw_buffer_store_b16((unsigned short)v, r, voff, soff, 0);
+}
+__device__ __forceinline__ void st_b32(rsrc_t r, int voff, int soff, uint32_t v) {
+  __builtin_amdgcn_raw_buffer_store_b32(v, r, voff, soff, 0);
+}
+__device__ __forceinline__ void st_b64(rsrc_t r, int voff, int soff, u32x2 v) {
+  __builtin_amdgcn_raw_buffer_store_b64(v, r, voff, soff, 0);
+}
+__device__ __forceinline__ void st_b128(rsrc_t r, int voff, int soff, u32x4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, soff, 0);
+}
+
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
 // outstanding global load (vmcnt(0)), which would expose the full memory latency at each
 // barrier and defeat the register prefetch ring of the product kernels.  Here only the LDS

@@ -73,28 +73,6 @@ __device__ __forceinline__ float surrogate_eval(int kind, float k, float x) {
   }
 }
 
-// ------------------------------------------------------------------ buffer loads
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-constexpr int OOB = 0x7FFFFF00;          // beyond any buffer here: the load returns zero
-
-__device__ __forceinline__ rsrc_t make_rsrc(const void *base, unsigned bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
-}
-__device__ __forceinline__ uint32_t ld_b8(rsrc_t r, int voff, int soff) {
-  return (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(r, voff, soff, 0);
-}
-__device__ __forceinline__ uint32_t ld_b32(rsrc_t r, int voff, int soff) {
-  return __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0);
-}
-__device__ __forceinline__ u32x2 ld_b64(rsrc_t r, int voff, int soff) {
-  return __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
-}
-__device__ __forceinline__ u32x4 ld_b128(rsrc_t r, int voff, int soff) {
-  return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
-}
-
 // ------------------------------------------------------------------ operand loaders
 // setup(): per-lane byte offsets and LDS offsets, once per workgroup.
 // load():  issue the global loads of the 64-wide contraction tile starting at k0 into

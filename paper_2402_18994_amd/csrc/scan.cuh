@@ -9,52 +9,44 @@
 
 namespace snn {
 
-template <int VEC> struct VecF;
-template <> struct VecF<1> { typedef float type; };
-template <> struct VecF<2> { typedef float2 type; };
-template <> struct VecF<4> { typedef float4 type; };
-template <int VEC> struct VecU;
-template <> struct VecU<1> { typedef uint32_t type; };
-template <> struct VecU<2> { typedef uint2 type; };
-template <> struct VecU<4> { typedef uint4 type; };
-
-template <int VEC> __device__ __forceinline__ void vload(float (&d)[VEC], const float *p) {
-  typename VecF<VEC>::type v = *(const typename VecF<VEC>::type *)p;
-  const float *f = (const float *)&v;
+// VEC adjacent fp32 / dword / byte values at lane offset `voff` (+ scalar offset `soff`).
+template <int VEC> __device__ __forceinline__ void ldv(float (&d)[VEC], rsrc_t r, int voff, int soff) {
+  if (VEC == 1) d[0] = __uint_as_float(ld_b32(r, voff, soff));
+  else if (VEC == 2) { const u32x2 v = ld_b64(r, voff, soff); d[0] = __uint_as_float(v[0]); d[1] = __uint_as_float(v[1]); }
+  else { const u32x4 v = ld_b128(r, voff, soff);
 #pragma unroll
-  for (int i = 0; i < VEC; ++i) d[i] = f[i];
+    for (int i = 0; i < VEC; ++i) d[i] = __uint_as_float(v[i]); }
 }
-template <int VEC> __device__ __forceinline__ void vstore(float *p, const float (&d)[VEC]) {
-  typename VecF<VEC>::type v;
-  float *f = (float *)&v;
+template <int VEC> __device__ __forceinline__ void stv(rsrc_t r, int voff, int soff, const uint32_t (&d)[VEC]) {
+  if (VEC == 1) st_b32(r, voff, soff, d[0]);
+  else if (VEC == 2) { u32x2 v; v[0] = d[0]; v[1] = d[1]; st_b64(r, voff, soff, v); }
+  else { u32x4 v;
 #pragma unroll
-  for (int i = 0; i < VEC; ++i) f[i] = d[i];
-  *(typename VecF<VEC>::type *)p = v;
+    for (int i = 0; i < VEC; ++i) v[i] = d[i];
+    st_b128(r, voff, soff, v); }
 }
-template <int VEC> __device__ __forceinline__ void vstore_u32(uint32_t *p, const uint32_t (&d)[VEC]) {
-  typename VecU<VEC>::type v;
-  uint32_t *f = (uint32_t *)&v;
-#pragma unroll
-  for (int i = 0; i < VEC; ++i) f[i] = d[i];
-  *(typename VecU<VEC>::type *)p = v;
-}
-template <int VEC> __device__ __forceinline__ void vstore_u8(uint8_t *p, const uint32_t (&s)[VEC]) {
-  if (VEC == 1) p[0] = (uint8_t)s[0];
-  else if (VEC == 2) *(uint16_t *)p = (uint16_t)(s[0] | (s[1] << 8));
-  else *(uint32_t *)p = s[0] | (s[1] << 8) | (s[2] << 16) | (s[3] << 24);
+template <int VEC> __device__ __forceinline__ void st_spikes(rsrc_t r, int voff, int soff, const uint32_t (&s)[VEC]) {
+  if (VEC == 1) st_b8(r, voff, soff, s[0]);
+  else if (VEC == 2) st_b16(r, voff, soff, s[0] | (s[1] << 8));
+  else st_b32(r, voff, soff, s[0] | (s[1] << 8) | (s[2] << 16) | (s[3] << 24));
 }
 
 // ---------------------------------------------------------------- LIF forward (Eq. 1-2)
 // S_t = [V_t > theta]; store V_t, S_t; V_{t+1} = beta V_t + I_t - theta S_t; V_0 = 0.
 // `stride` = B * ld elements between time steps; threads cover the stride (padding
-// columns included: their currents are zero, so they stay silent).
+// columns included: their currents are zero, so they stay silent).  A lane's offset into a
+// time row never changes, the row offset is scalar: no per-access vector address
+// arithmetic.  Whole blocks of 2U steps run without a branch; fetches past the end re-read
+// the last row (never used), the ragged tail runs guarded.
 template <int VEC, int U>
 __global__ __launch_bounds__(256) void lif_forward_kernel(const float *__restrict__ I, float *__restrict__ V,
-                                                          uint8_t *__restrict__ S, int T, long long stride,
+                                                          uint8_t *__restrict__ S, int T, int stride,
                                                           float beta, float theta) {
-  const long long p = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * VEC;
+  const int p = (blockIdx.x * blockDim.x + threadIdx.x) * VEC;
   if (p >= stride) return;
-  I += p; V += p; S += p;
+  const rsrc_t rI = make_rsrc(I, (unsigned)T * stride * 4u), rV = make_rsrc(V, (unsigned)T * stride * 4u);
+  const rsrc_t rS = make_rsrc(S, (unsigned)T * stride);
+  const int vo4 = p * 4, vo1 = p, row4 = stride * 4;
   float v[VEC];
 #pragma unroll
   for (int i = 0; i < VEC; ++i) v[i] = 0.f;
@@ -62,28 +54,33 @@ __global__ __launch_bounds__(256) void lif_forward_kernel(const float *__restric
 
   auto fetch = [&](float (&buf)[U][VEC], int t0) {
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (t0 + u < T) vload<VEC>(buf[u], I + (long long)(t0 + u) * stride);
+    for (int u = 0; u < U; ++u) ldv<VEC>(buf[u], rI, vo4, min(t0 + u, T - 1) * row4);
   };
-  auto integrate = [&](float (&buf)[U][VEC], int t0) {
+  auto step = [&](const float (&cur)[VEC], int t) {
+    uint32_t s[VEC], w[VEC];
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (t0 + u < T) {
-        uint32_t s[VEC];
+    for (int i = 0; i < VEC; ++i) { s[i] = v[i] > theta ? 1u : 0u; w[i] = __float_as_uint(v[i]); }
+    stv<VEC>(rV, vo4, t * row4, w);
+    st_spikes<VEC>(rS, vo1, t * stride, s);
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) s[i] = v[i] > theta ? 1u : 0u;
-        vstore<VEC>(V + (long long)(t0 + u) * stride, v);
-        vstore_u8<VEC>(S + (long long)(t0 + u) * stride, s);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) v[i] = beta * v[i] + buf[u][i] - (s[i] ? theta : 0.f);
-      }
+    for (int i = 0; i < VEC; ++i) v[i] = beta * v[i] + cur[i] - (s[i] ? theta : 0.f);
   };
   fetch(a, 0);
-  for (int t0 = 0; t0 < T; t0 += 2 * U) {
+  int t0 = 0;
+  for (; t0 + 2 * U <= T; t0 += 2 * U) {
     fetch(b, t0 + U);
-    integrate(a, t0);
+#pragma unroll
+    for (int u = 0; u < U; ++u) step(a[u], t0 + u);
     fetch(a, t0 + 2 * U);
-    integrate(b, t0 + U);
+#pragma unroll
+    for (int u = 0; u < U; ++u) step(b[u], t0 + U + u);
+  }
+  if (t0 < T) {                                     // fewer than 2U steps left; a holds t0..
+    fetch(b, t0 + U);
+#pragma unroll
+    for (int u = 0; u < U; ++u) if (t0 + u < T) step(a[u], t0 + u);
+#pragma unroll
+    for (int u = 0; u < U; ++u) if (t0 + U + u < T) step(b[u], t0 + U + u);
   }
 }
 
@@ -99,145 +96,51 @@ template <int SURR> __device__ __forceinline__ float surr(float k, float x) {
 
 template <int VEC, int U, int SURR, bool HL>
 __global__ __launch_bounds__(256) void lif_reverse_kernel(const float *__restrict__ dS, const float *__restrict__ V,
-                                                          uint32_t *__restrict__ dI, int T, long long stride,
+                                                          uint32_t *__restrict__ dI, int T, int stride,
                                                           float beta, float theta, float slope) {
-  const long long p = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * VEC;
+  const int p = (blockIdx.x * blockDim.x + threadIdx.x) * VEC;
   if (p >= stride) return;
-  dS += p; V += p; dI += p;
+  const unsigned bytes = (unsigned)T * stride * 4u;
+  const rsrc_t rdS = make_rsrc(dS, bytes), rV = make_rsrc(V, bytes), rdI = make_rsrc(dI, bytes);
+  const int vo4 = p * 4, row4 = stride * 4;
   float g[VEC];
 #pragma unroll
   for (int i = 0; i < VEC; ++i) g[i] = 0.f;
   float a_ds[U][VEC], a_v[U][VEC], b_ds[U][VEC], b_v[U][VEC];
 
-  // a block covers steps thi, thi-1, .., thi-U+1
+  // a block covers steps thi, thi-1, .., thi-U+1 (clamped at 0: re-reads, never used)
   auto fetch = [&](float (&bds)[U][VEC], float (&bv)[U][VEC], int thi) {
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (thi - u >= 0) {
-        vload<VEC>(bds[u], dS + (long long)(thi - u) * stride);
-        vload<VEC>(bv[u], V + (long long)(thi - u) * stride);
-      }
+    for (int u = 0; u < U; ++u) {
+      const int so = max(thi - u, 0) * row4;
+      ldv<VEC>(bds[u], rdS, vo4, so);
+      ldv<VEC>(bv[u], rV, vo4, so);
+    }
   };
-  auto integrate = [&](float (&bds)[U][VEC], float (&bv)[U][VEC], int thi) {
+  auto step = [&](const float (&ds)[VEC], const float (&vv)[VEC], int t) {
+    uint32_t w[VEC];
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (thi - u >= 0) {
-        uint32_t w[VEC];
+    for (int i = 0; i < VEC; ++i) w[i] = HL ? pack_hl(g[i]) : __float_as_uint(g[i]);
+    stv<VEC>(rdI, vo4, t * row4, w);
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) w[i] = HL ? pack_hl(g[i]) : __float_as_uint(g[i]);
-        vstore_u32<VEC>(dI + (long long)(thi - u) * stride, w);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i)
-          g[i] = beta * g[i] + surr<SURR>(slope, bv[u][i] - theta) * (bds[u][i] - theta * g[i]);
-      }
+    for (int i = 0; i < VEC; ++i) g[i] = beta * g[i] + surr<SURR>(slope, vv[i] - theta) * (ds[i] - theta * g[i]);
   };
   fetch(a_ds, a_v, T - 1);
-  for (int thi = T - 1; thi >= 0; thi -= 2 * U) {
+  int thi = T - 1;
+  for (; thi - 2 * U + 1 >= 0; thi -= 2 * U) {
     fetch(b_ds, b_v, thi - U);
-    integrate(a_ds, a_v, thi);
+#pragma unroll
+    for (int u = 0; u < U; ++u) step(a_ds[u], a_v[u], thi - u);
     fetch(a_ds, a_v, thi - 2 * U);
-    integrate(b_ds, b_v, thi - U);
+#pragma unroll
+    for (int u = 0; u < U; ++u) step(b_ds[u], b_v[u], thi - U - u);
   }
-}
-
-// ---------------------------------------------------------------- cooperative scans
-// With few chains (B*N of the order of the number of SIMDs) one wavefront per 64 chains
-// cannot keep enough loads in flight: a wavefront has at most 63 outstanding memory
-// operations.  Here NW wavefronts share 64 chains.  Time is cut into rounds of NW*U steps;
-// in a round wavefront w fetches steps [w*U, w*U+U) of the round (all NW*U rows in flight at
-// once, the next round's already requested), then the wavefronts integrate their segments
-// one after the other, handing the state on through LDS.  The serial part is a few
-// instructions per step; the memory system sees NW times the parallelism.
-template <int NW, int U>
-__global__ __launch_bounds__(NW * 64) void lif_forward_coop_kernel(const float *__restrict__ I, float *__restrict__ V,
-                                                                   uint8_t *__restrict__ S, int T, long long stride,
-                                                                   float beta, float theta) {
-  __shared__ float hand[64];
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const long long p0 = (long long)blockIdx.x * 64 + lane;
-  const bool live = p0 < stride;
-  const long long p = live ? p0 : 0;
-  I += p; V += p; S += p;
-  float a[U], b[U];
-  auto fetch = [&](float (&buf)[U], int t0) {
+  if (thi >= 0) {
+    fetch(b_ds, b_v, thi - U);
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (t0 + u < T) buf[u] = I[(long long)(t0 + u) * stride];
-  };
-  auto turn = [&](float (&buf)[U], int t0) {
-    for (int ww = 0; ww < NW; ++ww) {
-      if (ww == w) {
-        float v = hand[lane];
+    for (int u = 0; u < U; ++u) if (thi - u >= 0) step(a_ds[u], a_v[u], thi - u);
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-          if (t0 + u < T) {
-            const bool s = v > theta;
-            if (live) {
-              V[(long long)(t0 + u) * stride] = v;
-              S[(long long)(t0 + u) * stride] = s ? 1 : 0;
-            }
-            v = beta * v + buf[u] - (s ? theta : 0.f);
-          }
-        hand[lane] = v;
-      }
-      lds_barrier();
-    }
-  };
-  if (w == 0) hand[lane] = 0.f;                    // V_0 = 0
-  fetch(a, w * U);
-  lds_barrier();
-  for (int r0 = 0; r0 < T; r0 += 2 * NW * U) {
-    fetch(b, r0 + NW * U + w * U);
-    turn(a, r0 + w * U);
-    fetch(a, r0 + 2 * NW * U + w * U);
-    turn(b, r0 + NW * U + w * U);
-  }
-}
-
-template <int NW, int U, int SURR, bool HL>
-__global__ __launch_bounds__(NW * 64) void lif_reverse_coop_kernel(const float *__restrict__ dS,
-                                                                   const float *__restrict__ V,
-                                                                   uint32_t *__restrict__ dI, int T, long long stride,
-                                                                   float beta, float theta, float slope) {
-  __shared__ float hand[64];
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const long long p0 = (long long)blockIdx.x * 64 + lane;
-  const bool live = p0 < stride;
-  const long long p = live ? p0 : 0;
-  dS += p; V += p; dI += p;
-  float a_ds[U], a_v[U], b_ds[U], b_v[U];
-  // a segment covers steps thi, thi-1, .., thi-U+1
-  auto fetch = [&](float (&bds)[U], float (&bv)[U], int thi) {
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (thi - u >= 0) {
-        bds[u] = dS[(long long)(thi - u) * stride];
-        bv[u] = V[(long long)(thi - u) * stride];
-      }
-  };
-  auto turn = [&](float (&bds)[U], float (&bv)[U], int thi) {
-    for (int ww = 0; ww < NW; ++ww) {
-      if (ww == w) {
-        float g = hand[lane];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-          if (thi - u >= 0) {
-            if (live) dI[(long long)(thi - u) * stride] = HL ? pack_hl(g) : __float_as_uint(g);
-            g = beta * g + surr<SURR>(slope, bv[u] - theta) * (bds[u] - theta * g);
-          }
-        hand[lane] = g;
-      }
-      lds_barrier();
-    }
-  };
-  if (w == 0) hand[lane] = 0.f;                    // g_T = 0
-  fetch(a_ds, a_v, T - 1 - w * U);
-  lds_barrier();
-  for (int r0 = T - 1; r0 >= 0; r0 -= 2 * NW * U) {
-    fetch(b_ds, b_v, r0 - NW * U - w * U);
-    turn(a_ds, a_v, r0 - w * U);
-    fetch(a_ds, a_v, r0 - 2 * NW * U - w * U);
-    turn(b_ds, b_v, r0 - NW * U - w * U);
+    for (int u = 0; u < U; ++u) if (thi - U - u >= 0) step(b_ds[u], b_v[u], thi - U - u);
   }
 }
 
@@ -299,47 +202,65 @@ __global__ __launch_bounds__(256) void loss_mean_kernel(const float *__restrict_
   if (threadIdx.x == 0) loss[0] = part[0] / (float)B;
 }
 
-// The three kernels above in one launch, for C <= 64.  A wavefront holds 64/CW samples, CW
-// lanes each (CW = power of two >= C); a lane scans one (b, c) chain over time, then the
-// softmax is reduced across the CW lanes of a sample.  Per-sample losses go to loss_b; the
-// workgroup that takes the last ticket adds them up in index order, so the mean is the same
-// on every run.
-template <int CW>
-__global__ __launch_bounds__(256) void readout_loss_kernel(const float *__restrict__ J, float *__restrict__ Y,
-                                                           float *__restrict__ z, int *__restrict__ tstar,
-                                                           const int *__restrict__ labels, float *__restrict__ loss_b,
-                                                           float *__restrict__ dz, float *__restrict__ loss,
-                                                           int *__restrict__ ticket, int *__restrict__ err, int T,
-                                                           int B, int C, int ldc, float beta) {
-  constexpr int SPB = 256 / CW;                       // samples per workgroup
+// Readout scan, loss and readout reverse in one launch, for C <= 64.  A single-wavefront
+// workgroup holds 64/CW samples, CW lanes each (CW = power of two >= C); a lane scans one
+// (b, c) chain over time with the rows of J prefetched in blocks, the softmax is reduced
+// across the CW lanes of a sample, and the lane then writes its chain of dJ: with the max
+// over time, dJ_t = beta^(t*-t) dz for t <= t* and 0 after (the recursion
+// h_t = beta h_{t+1} + dz [t == t*]).  Idle lanes address beyond the buffers: their loads
+// return zero and their stores are dropped.  Per-sample losses go to loss_b; the workgroup
+// that takes the last ticket adds them up in index order, so the mean is the same on
+// every run.
+template <int CW, bool HL>
+__global__ __launch_bounds__(64) void readout_loss_kernel(const float *__restrict__ J, float *__restrict__ Y,
+                                                          float *__restrict__ z, int *__restrict__ tstar,
+                                                          const int *__restrict__ labels, float *__restrict__ loss_b,
+                                                          float *__restrict__ dz, float *__restrict__ loss,
+                                                          int *__restrict__ ticket, int *__restrict__ err,
+                                                          uint32_t *__restrict__ dJ, int T, int B, int C, int ldc,
+                                                          float beta, int dbg) {
+  constexpr int SPB = 64 / CW;                        // samples per workgroup
+  constexpr int U = 16;
   const int c = threadIdx.x % CW;
   const int b = blockIdx.x * SPB + threadIdx.x / CW;
   const bool live = b < B && c < C;
-  const size_t stride = (size_t)B * ldc;
-  const size_t p = live ? (size_t)b * ldc + c : 0;
+  const int stride = B * ldc, row4 = stride * 4;
+  const int p = live ? b * ldc + c : 0;
+  const int vo = live ? p * 4 : OOB;
+  const unsigned bytes = (unsigned)T * stride * 4u;
+  const rsrc_t rJ = make_rsrc(J, bytes), rY = make_rsrc(Y, bytes), rdJ = make_rsrc(dJ, bytes);
+
   float y = 0.f, best = -INFINITY;
   int tb = 0;
-  if (live) {
-    int t = 0;
-    for (; t + 8 <= T; t += 8) {
-      float j[8];
+  float ja[U], jb[U];
+  auto fetch = [&](float (&buf)[U], int t0) {
 #pragma unroll
-      for (int u = 0; u < 8; ++u) j[u] = J[(size_t)(t + u) * stride + p];
+    for (int u = 0; u < U; ++u) buf[u] = __uint_as_float(ld_b32(rJ, vo, min(t0 + u, T - 1) * row4));
+  };
+  auto step = [&](float j, int t) {
+    y = beta * y + j;
+    st_b32(rY, vo, t * row4, __float_as_uint(y));
+    if (y > best) { best = y; tb = t; }
+  };
+  fetch(ja, 0);
+  int t0 = 0;
+  for (; t0 + 2 * U <= T; t0 += 2 * U) {
+    fetch(jb, t0 + U);
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        y = beta * y + j[u];
-        Y[(size_t)(t + u) * stride + p] = y;
-        if (y > best) { best = y; tb = t + u; }
-      }
-    }
-    for (; t < T; ++t) {
-      y = beta * y + J[(size_t)t * stride + p];
-      Y[(size_t)t * stride + p] = y;
-      if (y > best) { best = y; tb = t; }
-    }
-    z[p] = best;
-    tstar[p] = tb;
+    for (int u = 0; u < U; ++u) step(ja[u], t0 + u);
+    fetch(ja, t0 + 2 * U);
+#pragma unroll
+    for (int u = 0; u < U; ++u) step(jb[u], t0 + U + u);
   }
+  if (t0 < T) {
+    fetch(jb, t0 + U);
+#pragma unroll
+    for (int u = 0; u < U; ++u) if (t0 + u < T) step(ja[u], t0 + u);
+#pragma unroll
+    for (int u = 0; u < U; ++u) if (t0 + U + u < T) step(jb[u], t0 + U + u);
+  }
+  if (live) { z[p] = best; tstar[p] = tb; }
+
   float m = live ? best : -INFINITY;
 #pragma unroll
   for (int o = CW / 2; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
@@ -352,26 +273,30 @@ __global__ __launch_bounds__(256) void readout_loss_kernel(const float *__restri
   float zl = (live && c == lab) ? best : 0.f;          // z[label], gathered across the group
 #pragma unroll
   for (int o = CW / 2; o > 0; o >>= 1) zl += __shfl_xor(zl, o);
-  if (live) dz[p] = (e / sum - (c == lab ? 1.f : 0.f)) / (float)B;
+  const float d = live ? (e / sum - (c == lab ? 1.f : 0.f)) / (float)B : 0.f;
+  if (live) dz[p] = d;
   if (b < B && c == 0) loss_b[b] = m + logf(sum) - zl;
 
-  __shared__ int last;
+  float h = 0.f;
+  if (!(dbg & 1))
+#pragma unroll 8
+  for (int t = T - 1; t >= 0; --t) {
+    h = beta * h + (t == tb ? d : 0.f);
+    st_b32(rdJ, vo, t * row4, HL ? pack_hl(h) : __float_as_uint(h));
+  }
+
+  if (dbg & 2) return;
   __threadfence();
-  __syncthreads();
+  int last = 0;
   if (threadIdx.x == 0) last = atomicAdd(ticket, 1) == (int)gridDim.x - 1;
-  __syncthreads();
+  last = __shfl(last, 0);
   if (last) {
     __threadfence();
-    __shared__ float part[256];
     float s = 0.f;
-    for (int i = threadIdx.x; i < B; i += 256) s += loss_b[i];
-    part[threadIdx.x] = s;
-    __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-      if ((int)threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
-      __syncthreads();
-    }
-    if (threadIdx.x == 0) { loss[0] = part[0] / (float)B; *ticket = 0; }
+    for (int i = threadIdx.x; i < B; i += 64) s += loss_b[i];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (threadIdx.x == 0) { loss[0] = s / (float)B; *ticket = 0; }
   }
 }
 

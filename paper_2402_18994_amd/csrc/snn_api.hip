@@ -67,6 +67,7 @@ struct snn_ctx {
   size_t ws_bytes = 0;
   hipStream_t stream = nullptr;
   int state = 0;                  // 0 fresh, 1 forward done, 2 backward done
+  bool dj_ready = false;          // the fused readout kernel has already written dJ
   const uint8_t *x_eff = nullptr;  // raster the products read: the caller's, or x_pad
   uint8_t *x_pad = nullptr;        // zero-padded copy, only when N_0 is not a multiple of 4
   int ldx = 0;                     // row length of x_eff
@@ -400,15 +401,6 @@ int launch_weight_grad(snn_ctx *c, int l, ReduceJobs &jobs) {
   return rc;
 }
 
-// Which scan kernel: 1 = four wavefronts share 64 chains, 2 = eight do, 0 = one thread per
-// VEC chains.  The cooperative forms are for chain counts too small to fill the chip.
-int scan_mode(long long chains) {
-  static const int forced = [] { const char *e = getenv("SNN_SCAN_MODE"); return e ? atoi(e) : -1; }();
-  if (forced >= 0 && forced <= 2) return forced;     // tuning knob
-  (void)chains;
-  return 0;
-}
-
 // Threads per workgroup of the one-thread-per-chain scans: single wavefronts while that is
 // what it takes to give each of the 256 compute units (8 XCDs x 32) something to do.
 int scan_block(long long threads) {
@@ -417,39 +409,10 @@ int scan_block(long long threads) {
   return threads >= 256 * 1024 ? 256 : 64;
 }
 
-template <int NW, int U>
-hipError_t lif_fwd_coop_launch(snn_ctx *c, Layer &y) {
-  const long long stride = (long long)c->B * y.ld;
-  hipLaunchKernelGGL((lif_forward_coop_kernel<NW, U>), dim3((unsigned)((stride + 63) / 64)), dim3(NW * 64), 0,
-                     c->stream, y.I, y.V, y.S, c->T, stride, y.beta, c->theta);
-  return hipGetLastError();
-}
-
-template <int NW, int U, bool HL>
-hipError_t lif_rev_coop_launch2(snn_ctx *c, Layer &y) {
-  const long long stride = (long long)c->B * y.ld;
-  dim3 grid((unsigned)((stride + 63) / 64)), block(NW * 64);
-#define SNN_REVC(SU)                                                                                            \
-  hipLaunchKernelGGL((lif_reverse_coop_kernel<NW, U, SU, HL>), grid, block, 0, c->stream, y.dS, y.V, y.dI, c->T, \
-                     stride, y.beta, c->theta, c->slope)
-  switch (c->surrogate) {
-    case 0: SNN_REVC(0); break;
-    case 1: SNN_REVC(1); break;
-    case 2: SNN_REVC(2); break;
-    default: SNN_REVC(3); break;
-  }
-#undef SNN_REVC
-  return hipGetLastError();
-}
-template <int NW, int U>
-hipError_t lif_rev_coop_launch(snn_ctx *c, Layer &y) {
-  return c->hl ? lif_rev_coop_launch2<NW, U, true>(c, y) : lif_rev_coop_launch2<NW, U, false>(c, y);
-}
-
 template <int VEC, int U>
 hipError_t lif_fwd_launch(snn_ctx *c, Layer &y) {
-  const long long stride = (long long)c->B * y.ld;
-  const long long threads = stride / VEC;
+  const int stride = c->B * y.ld;               // T * stride * 4 < 2 GiB was checked at init
+  const int threads = stride / VEC;
   const int bs = scan_block(threads);
   hipLaunchKernelGGL((lif_forward_kernel<VEC, U>), dim3((unsigned)((threads + bs - 1) / bs)), dim3(bs), 0, c->stream,
                      y.I, y.V, y.S, c->T, stride, y.beta, c->theta);
@@ -467,10 +430,7 @@ int launch_lif_forward(snn_ctx *c, int l) {
   Bracket br(c, SNN_K_LIF_FORWARD, l + 1);
   const long long chains = (long long)c->B * y.ld;
   hipError_t e;
-  const int mode = scan_mode(chains);
-  if (mode == 1) e = lif_fwd_coop_launch<4, 32>(c, y);
-  else if (mode == 2) e = lif_fwd_coop_launch<8, 16>(c, y);
-  else if (chains >= (1 << 19)) e = lif_fwd_launch<4, 8>(c, y);
+  if (chains >= (1 << 19)) e = lif_fwd_launch<4, 8>(c, y);
   else if (chains >= (1 << 17)) e = lif_fwd_launch<2, 16>(c, y);
   else e = lif_fwd_launch<1, 32>(c, y);
   HIPCHK(c, e);
@@ -479,8 +439,8 @@ int launch_lif_forward(snn_ctx *c, int l) {
 
 template <int VEC, int U, bool HL>
 hipError_t lif_rev_launch2(snn_ctx *c, Layer &y) {
-  const long long stride = (long long)c->B * y.ld;
-  const long long threads = stride / VEC;
+  const int stride = c->B * y.ld;
+  const int threads = stride / VEC;
   const int bs = scan_block(threads);
   dim3 grid((unsigned)((threads + bs - 1) / bs)), block(bs);
 #define SNN_REV(SU)                                                                                          \
@@ -511,10 +471,7 @@ int launch_lif_reverse(snn_ctx *c, int l) {
   Bracket br(c, SNN_K_LIF_REVERSE, l + 1);
   const long long chains = (long long)c->B * y.ld;
   hipError_t e;
-  const int mode = scan_mode(chains);
-  if (mode == 1) e = lif_rev_coop_launch<4, 16>(c, y);
-  else if (mode == 2) e = lif_rev_coop_launch<8, 16>(c, y);
-  else if (chains >= (1 << 19)) e = lif_rev_launch<4, 4>(c, y);
+  if (chains >= (1 << 19)) e = lif_rev_launch<4, 4>(c, y);
   else if (chains >= (1 << 17)) e = lif_rev_launch<2, 8>(c, y);
   else e = lif_rev_launch<1, 16>(c, y);
   HIPCHK(c, e);
@@ -525,23 +482,21 @@ int launch_readout_forward(snn_ctx *c, const int32_t *labels) {
   if (!labels) return fail(c, SNN_ERR_NULL, "labels are NULL");
   Layer &y = c->layers[c->L - 1];
   Bracket br(c, SNN_K_READOUT_FORWARD, c->L);
-  if (c->C <= 64) {
-    const int cw = c->C <= 8 ? 8 : (c->C <= 16 ? 16 : (c->C <= 32 ? 32 : 64));
-    const int spb = 256 / cw;
-    dim3 grid((c->B + spb - 1) / spb), block(256);
-#define SNN_RO(CW)                                                                                              \
-  hipLaunchKernelGGL(readout_loss_kernel<CW>, grid, block, 0, c->stream, y.I, y.V, c->z, c->tstar, labels,      \
-                     c->loss_b, c->dz, c->loss, c->ticket, c->err_flag, c->T, c->B, c->C, c->ldC, y.beta)
-    switch (cw) {
-      case 8: SNN_RO(8); break;
-      case 16: SNN_RO(16); break;
-      case 32: SNN_RO(32); break;
-      default: SNN_RO(64); break;
-    }
-#undef SNN_RO
+  if (c->ldC <= 64) {
+    const int cw = c->ldC <= 16 ? 16 : c->ldC <= 32 ? 32 : 64;
+    dim3 grid((c->B + 64 / cw - 1) / (64 / cw)), block(64);
+#define SNN_RDL(CW, HL)                                                                                          \
+  hipLaunchKernelGGL((readout_loss_kernel<CW, HL>), grid, block, 0, c->stream, y.I, y.V, c->z, c->tstar, labels, \
+                     c->loss_b, c->dz, c->loss, c->ticket, c->err_flag, y.dI, c->T, c->B, c->C, c->ldC, y.beta, dbg)
+    static const int dbg = [] { const char *e = getenv("SNN_DBG"); return e ? atoi(e) : 0; }();
+    if (c->hl) { if (cw == 16) SNN_RDL(16, true); else if (cw == 32) SNN_RDL(32, true); else SNN_RDL(64, true); }
+    else { if (cw == 16) SNN_RDL(16, false); else if (cw == 32) SNN_RDL(32, false); else SNN_RDL(64, false); }
+#undef SNN_RDL
     HIPCHK(c, hipGetLastError());
+    c->dj_ready = true;
     return SNN_OK;
   }
+  c->dj_ready = false;
   const int stride = c->B * c->ldC;
   hipLaunchKernelGGL(readout_forward_kernel, dim3((stride + 255) / 256), dim3(256), 0, c->stream, y.I, y.V, c->z,
                      c->tstar, c->T, stride, y.beta);
@@ -774,7 +729,7 @@ int32_t snn_backward(snn_ctx *c) {
   int rc;
   ReduceJobs jobs;
   memset(&jobs, 0, sizeof jobs);
-  if ((rc = launch_readout_reverse(c))) return rc;
+  if (!c->dj_ready && (rc = launch_readout_reverse(c))) return rc;
   for (int l = c->L - 1; l >= 0; --l) {
     if (c->layers[l].spiking && (rc = launch_lif_reverse(c, l))) return rc;
     if ((rc = launch_weight_grad(c, l, jobs))) return rc;
@@ -840,6 +795,7 @@ int32_t snn_set_tensor(snn_ctx *c, int32_t tensor, int32_t layer, const void *sr
   HIPCHK(c, hipMemcpy2DAsync(v.p, v.ld * v.esz, src, v.cols * v.esz, v.cols * v.esz, v.rows, hipMemcpyHostToDevice,
                              c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
+  if (tensor == SNN_T_D_LOGITS || tensor == SNN_T_ARGMAX_T) c->dj_ready = false;   // dJ must be recomputed
   if (tensor == SNN_T_WEIGHT || tensor == SNN_T_RWEIGHT) {
     if ((rc = update_layers(c, layer - 1, layer, false, 0.f))) return rc;
     HIPCHK(c, hipStreamSynchronize(c->stream));
