@@ -83,8 +83,13 @@ __device__ __forceinline__ void st_b32(rsrc_t r, int voff, int soff, uint32_t v)
 __device__ __forceinline__ void st_b64(rsrc_t r, int voff, int soff, u32x2 v) {
   __builtin_amdgcn_raw_buffer_store_b64(v, r, voff, soff, 0);
 }
+// A 16-byte store reads its four data registers over several cycles, and an instruction
+// that overwrites one of them must keep its distance.  The compiler keeps that distance only
+// for stores without a scalar offset register; with one, a write to the first data register
+// directly behind the store was seen to reach memory in place of the stored value on gfx950.
+// So the whole offset of a 16-byte store goes through the vector register.
 __device__ __forceinline__ void st_b128(rsrc_t r, int voff, int soff, u32x4 v) {
-  __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, soff, 0);
+  __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)((unsigned)voff + (unsigned)soff), 0, 0);
 }
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every

@@ -188,115 +188,183 @@ __global__ __launch_bounds__(256) void cross_entropy_kernel(const float *__restr
     dz[(size_t)b * ldc + c] = (expf(zb[c] - m) * inv - (c == lab ? 1.f : 0.f)) * invB;
 }
 
-// Mean of the per-sample losses in a fixed order (one workgroup).
-__global__ __launch_bounds__(256) void loss_mean_kernel(const float *__restrict__ loss_b, float *__restrict__ loss, int B) {
-  __shared__ float part[256];
-  float s = 0.f;
-  for (int b = threadIdx.x; b < B; b += 256) s += loss_b[b];
-  part[threadIdx.x] = s;
-  __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
-    if ((int)threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) loss[0] = part[0] / (float)B;
+// Orders the LDS traffic of one wavefront: lanes exchange data through LDS without a
+// workgroup barrier (LDS operations of a wavefront execute in order); the fences keep the
+// compiler from moving accesses across the exchange point.
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Readout scan, loss and readout reverse in one launch, for C <= 64.  A single-wavefront
-// workgroup holds 64/CW samples, CW lanes each (CW = power of two >= C); a lane scans one
-// (b, c) chain over time with the rows of J prefetched in blocks, the softmax is reduced
-// across the CW lanes of a sample, and the lane then writes its chain of dJ: with the max
-// over time, dJ_t = beta^(t*-t) dz for t <= t* and 0 after (the recursion
-// h_t = beta h_{t+1} + dz [t == t*]).  Idle lanes address beyond the buffers: their loads
-// return zero and their stores are dropped.  Per-sample losses go to loss_b; the workgroup
-// that takes the last ticket adds them up in index order, so the mean is the same on
-// every run.
+// Readout scan, loss and readout reverse in one launch, for C <= 64.
+//
+// Chains: a workgroup holds SPB = 64/CW samples, CW lanes each (CW = power of two >= ld), one
+// lane per (b, c) chain; the softmax is reduced across the CW lanes of a sample.
+//
+// Time: the LI readout has no threshold and no reset, so y_t = beta y_{t-1} + J_t is linear
+// in the state and can be cut in time.  The eight wavefronts of a workgroup all hold the same
+// 64 chains; in every block of 128 steps wavefront w owns steps [16w, 16w+16).  It first
+// integrates its steps from a zero state (e_w), the e_w are exchanged through LDS, the state
+// entering its segment follows as c_w = beta^16 c_{w-1} + e_{w-1}, and the segment is then
+// integrated for real from c_w, step by step as the sequential scan would.  A single
+// wavefront issuing ~10 instructions per step is what bounds this kernel, hence the split.
+// The first maximiser over time is found per wavefront and merged (larger value, then
+// earlier step).  With the max over time, dJ_t = beta^(t*-t) dz for t <= t* and 0 after
+// (the recursion h_t = beta h_{t+1} + dz [t == t*]); a wavefront enters its segment with the
+// closed form and runs the recursion inside it.
+//
+// Memory: a wavefront can have 63 memory operations in flight, so global accesses are
+// 16 bytes per lane and cover four time rows at once: lane i of the "memory" arrangement
+// holds columns 4q..4q+3 of row r (r = i / LPR, q = i % LPR, LPR = SPB*ld/4 <= 16 lanes per
+// row); a 1 KB LDS stage per access turns that into the chain arrangement and back.  Lanes
+// without work address beyond the buffers: loads return zero, stores are dropped.
+// Per-sample losses go to loss_b; their mean is taken by a later launch (the partial-sum
+// reduction of the backward pass, or loss_mean_kernel when the loss is asked for first), in
+// index order either way.
 template <int CW, bool HL>
-__global__ __launch_bounds__(64) void readout_loss_kernel(const float *__restrict__ J, float *__restrict__ Y,
-                                                          float *__restrict__ z, int *__restrict__ tstar,
-                                                          const int *__restrict__ labels, float *__restrict__ loss_b,
-                                                          float *__restrict__ dz, float *__restrict__ loss,
-                                                          int *__restrict__ ticket, int *__restrict__ err,
-                                                          uint32_t *__restrict__ dJ, int T, int B, int C, int ldc,
-                                                          float beta, int dbg) {
+__global__ __launch_bounds__(512) void readout_loss_kernel(const float *__restrict__ J, float *__restrict__ Y,
+                                                           float *__restrict__ z, int *__restrict__ tstar,
+                                                           const int *__restrict__ labels, float *__restrict__ loss_b,
+                                                           float *__restrict__ dz, int *__restrict__ err,
+                                                           uint32_t *__restrict__ dJ, int T, int B, int C, int ldc,
+                                                           float beta) {
   constexpr int SPB = 64 / CW;                        // samples per workgroup
-  constexpr int U = 16;
-  const int c = threadIdx.x % CW;
-  const int b = blockIdx.x * SPB + threadIdx.x / CW;
-  const bool live = b < B && c < C;
+  constexpr int NW = 8;                               // wavefronts = time segments per block
+  constexpr int G = 4;                                // accesses (of four rows) per segment
+  constexpr int SEG = 4 * G;                          // steps per segment
+  constexpr int SB = NW * SEG;                        // steps per block
+  __shared__ __align__(16) uint32_t stage[NW][G][256];   // one wavefront's rows in flight, in or out
+  __shared__ float x_e[2][NW][64], x_best[NW][64];
+  __shared__ int x_tb[NW][64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int stride = B * ldc, row4 = stride * 4;
-  const int p = live ? b * ldc + c : 0;
-  const int vo = live ? p * 4 : OOB;
   const unsigned bytes = (unsigned)T * stride * 4u;
   const rsrc_t rJ = make_rsrc(J, bytes), rY = make_rsrc(Y, bytes), rdJ = make_rsrc(dJ, bytes);
 
-  float y = 0.f, best = -INFINITY;
-  int tb = 0;
-  float ja[U], jb[U];
-  auto fetch = [&](float (&buf)[U], int t0) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) buf[u] = __uint_as_float(ld_b32(rJ, vo, min(t0 + u, T - 1) * row4));
-  };
-  auto step = [&](float j, int t) {
-    y = beta * y + j;
-    st_b32(rY, vo, t * row4, __float_as_uint(y));
-    if (y > best) { best = y; tb = t; }
-  };
-  fetch(ja, 0);
-  int t0 = 0;
-  for (; t0 + 2 * U <= T; t0 += 2 * U) {
-    fetch(jb, t0 + U);
-#pragma unroll
-    for (int u = 0; u < U; ++u) step(ja[u], t0 + u);
-    fetch(ja, t0 + 2 * U);
-#pragma unroll
-    for (int u = 0; u < U; ++u) step(jb[u], t0 + U + u);
-  }
-  if (t0 < T) {
-    fetch(jb, t0 + U);
-#pragma unroll
-    for (int u = 0; u < U; ++u) if (t0 + u < T) step(ja[u], t0 + u);
-#pragma unroll
-    for (int u = 0; u < U; ++u) if (t0 + U + u < T) step(jb[u], t0 + U + u);
-  }
-  if (live) { z[p] = best; tstar[p] = tb; }
+  // chain arrangement
+  const int c = lane % CW;
+  const int s = lane / CW;
+  const int b = blockIdx.x * SPB + s;
+  const bool live = b < B && c < C;
+  const bool staged = c < ldc;                        // has a slot in the stages
+  const int slot = staged ? s * ldc + c : 0;
+  const int p = live ? b * ldc + c : 0;
+  // memory arrangement
+  const int lpr = SPB * ldc / 4;
+  const int mr = lane / lpr, mq = lane - mr * lpr;
+  const int mchain = blockIdx.x * SPB * ldc + 4 * mq;
+  const bool mvalid = mr < 4 && mchain < stride;
+  const int mvo = mvalid ? mr * row4 + mchain * 4 : OOB;
+  const int mslot = mvalid ? mr * 64 + 4 * mq : 0;    // dword index in a stage
+  auto mem_off = [&](int t0) { return t0 + mr < T ? mvo : OOB; };   // rows past the end: no access
 
+  const int lab_in = b < B ? labels[b] : 0;
+  float bseg = beta;                                  // beta^SEG
+#pragma unroll
+  for (int i = 0; i < 4; ++i) bseg *= bseg;
+  static_assert(SEG == 16, "bseg is beta^16");
+
+  float y_in = 0.f, best = -INFINITY;                 // y_in: state entering the block
+  int tb = 0;
+  for (int sb0 = 0, par = 0; sb0 < T; sb0 += SB, par ^= 1) {
+    const int t0 = sb0 + SEG * w;
+    u32x4 raw[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) raw[g] = ld_b128(rJ, mem_off(t0 + 4 * g), (t0 + 4 * g) * row4);
+    wave_sync();                                      // earlier reads of the stages are done
+    if (mvalid) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) *(u32x4 *)&stage[w][g][mslot] = raw[g];
+    }
+    wave_sync();
+    float j[SEG], e = 0.f;
+#pragma unroll
+    for (int k = 0; k < SEG; ++k) {
+      j[k] = __uint_as_float(stage[w][k >> 2][(k & 3) * 64 + slot]);
+      e = beta * e + j[k];
+    }
+    x_e[par][w][lane] = e;
+    __syncthreads();
+    float cst = y_in, y = 0.f;
+#pragma unroll
+    for (int v = 0; v < NW; ++v) {
+      if (v == w) y = cst;
+      cst = bseg * cst + x_e[par][v][lane];
+    }
+    y_in = cst;
+    uint32_t out[SEG];
+#pragma unroll
+    for (int k = 0; k < SEG; ++k) {
+      y = beta * y + j[k];
+      out[k] = __float_as_uint(y);
+      if (t0 + k < T && y > best) { best = y; tb = t0 + k; }
+    }
+    wave_sync();
+    if (staged) {
+#pragma unroll
+      for (int k = 0; k < SEG; ++k) stage[w][k >> 2][(k & 3) * 64 + slot] = out[k];
+    }
+    wave_sync();
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+      st_b128(rY, mem_off(t0 + 4 * g), (t0 + 4 * g) * row4, *(const u32x4 *)&stage[w][g][mslot]);
+  }
+
+  // first maximiser over all segments
+  x_best[w][lane] = best;
+  x_tb[w][lane] = tb;
+  __syncthreads();
+  best = x_best[0][lane];
+  tb = x_tb[0][lane];
+#pragma unroll
+  for (int v = 1; v < NW; ++v) {
+    const float bv = x_best[v][lane];
+    const int tv = x_tb[v][lane];
+    if (bv > best || (bv == best && tv < tb)) { best = bv; tb = tv; }
+  }
+  if (live && w == 0) { z[p] = best; tstar[p] = tb; }
+
+  // softmax cross-entropy per sample (every wavefront, for dz)
   float m = live ? best : -INFINITY;
 #pragma unroll
   for (int o = CW / 2; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-  const float e = live ? expf(best - m) : 0.f;
-  float sum = e;
+  const float ex = live ? expf(best - m) : 0.f;
+  float sum = ex;
 #pragma unroll
   for (int o = CW / 2; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-  int lab = b < B ? labels[b] : 0;
-  if (lab < 0 || lab >= C) { if (c == 0) atomicOr(err, 1); lab = 0; }
+  int lab = lab_in;
+  if (lab < 0 || lab >= C) { if (c == 0 && w == 0) atomicOr(err, 1); lab = 0; }
   float zl = (live && c == lab) ? best : 0.f;          // z[label], gathered across the group
 #pragma unroll
   for (int o = CW / 2; o > 0; o >>= 1) zl += __shfl_xor(zl, o);
-  const float d = live ? (e / sum - (c == lab ? 1.f : 0.f)) / (float)B : 0.f;
-  if (live) dz[p] = d;
-  if (b < B && c == 0) loss_b[b] = m + logf(sum) - zl;
-
-  float h = 0.f;
-  if (!(dbg & 1))
-#pragma unroll 8
-  for (int t = T - 1; t >= 0; --t) {
-    h = beta * h + (t == tb ? d : 0.f);
-    st_b32(rdJ, vo, t * row4, HL ? pack_hl(h) : __float_as_uint(h));
+  const float d = live ? (ex / sum - (c == lab ? 1.f : 0.f)) / (float)B : 0.f;
+  if (w == 0) {
+    if (live) dz[p] = d;
+    if (b < B && c == 0) loss_b[b] = m + logf(sum) - zl;
   }
 
-  if (dbg & 2) return;
-  __threadfence();
-  int last = 0;
-  if (threadIdx.x == 0) last = atomicAdd(ticket, 1) == (int)gridDim.x - 1;
-  last = __shfl(last, 0);
-  if (last) {
-    __threadfence();
-    float s = 0.f;
-    for (int i = threadIdx.x; i < B; i += 64) s += loss_b[i];
+  // dJ
+  const float l2b = log2f(beta);
+  for (int sb0 = 0; sb0 < T; sb0 += SB) {
+    const int t0 = sb0 + SEG * w;
+    const int n = tb - (t0 + SEG);                    // steps from the segment's upper edge up to t*
+    float h = n > 0 ? d * exp2f((float)n * l2b) : n == 0 ? d : 0.f;
+    uint32_t out[SEG];
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
-    if (threadIdx.x == 0) { loss[0] = s / (float)B; *ticket = 0; }
+    for (int k = SEG - 1; k >= 0; --k) {
+      h = beta * h + (t0 + k == tb ? d : 0.f);
+      out[k] = HL ? pack_hl(h) : __float_as_uint(h);
+    }
+    wave_sync();
+    if (staged) {
+#pragma unroll
+      for (int k = 0; k < SEG; ++k) stage[w][k >> 2][(k & 3) * 64 + slot] = out[k];
+    }
+    wave_sync();
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+      st_b128(rdJ, mem_off(t0 + 4 * g), (t0 + 4 * g) * row4, *(const u32x4 *)&stage[w][g][mslot]);
   }
 }
 
@@ -346,8 +414,33 @@ struct ReduceJobs {
   long long n[SNN_MAX_JOBS];          // elements per matrix = stride between splits
 };
 
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const ReduceJobs jobs) {
+// Mean of the per-sample losses in a fixed order, by one workgroup of 256 threads.
+__device__ __forceinline__ void loss_mean_block(const float *__restrict__ loss_b, float *__restrict__ loss, int B,
+                                                float *part) {
+  float s = 0.f;
+  for (int b = threadIdx.x; b < B; b += 256) s += loss_b[b];
+  part[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) loss[0] = part[0] / (float)B;
+}
+
+__global__ __launch_bounds__(256) void loss_mean_kernel(const float *__restrict__ loss_b, float *__restrict__ loss, int B) {
+  __shared__ float part[256];
+  loss_mean_block(loss_b, loss, B, part);
+}
+
+// One workgroup beyond the last job (only launched when loss_b != NULL) takes the mean loss.
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const ReduceJobs jobs, const float *__restrict__ loss_b,
+                                                              float *__restrict__ loss, int B) {
   __shared__ float4 sm[4][64];
+  if ((int)blockIdx.x >= jobs.first_block[jobs.njobs]) {
+    loss_mean_block(loss_b, loss, B, (float *)sm);
+    return;
+  }
   int j = 0;
   while (j + 1 < jobs.njobs && (int)blockIdx.x >= jobs.first_block[j + 1]) ++j;
   const float *__restrict__ part = jobs.part[j];

@@ -62,12 +62,13 @@ struct snn_ctx {
   bool hl = false;                // current gradients held in hi/lo form
   int C = 0, ldC = 0;
   float *z = nullptr, *dz = nullptr, *loss_b = nullptr, *loss = nullptr;
-  int *tstar = nullptr, *err_flag = nullptr, *ticket = nullptr;
+  int *tstar = nullptr, *err_flag = nullptr;
   char *ws = nullptr;
   size_t ws_bytes = 0;
   hipStream_t stream = nullptr;
   int state = 0;                  // 0 fresh, 1 forward done, 2 backward done
   bool dj_ready = false;          // the fused readout kernel has already written dJ
+  bool loss_ready = false;        // the mean of loss_b has been taken since the last readout
   const uint8_t *x_eff = nullptr;  // raster the products read: the caller's, or x_pad
   uint8_t *x_pad = nullptr;        // zero-padded copy, only when N_0 is not a multiple of 4
   int ldx = 0;                     // row length of x_eff
@@ -212,7 +213,6 @@ void carve(snn_ctx &c, Carver &cv) {
   c.loss_b = cv.take<float>((size_t)c.B);
   c.loss = cv.take<float>(64);
   c.err_flag = cv.take<int>(64);
-  c.ticket = cv.take<int>(64);
 }
 
 void configure(snn_ctx &c, const snn_config *cfg) {
@@ -376,10 +376,22 @@ void add_reduce_job(ReduceJobs &jobs, const float *part, float *out, int splits,
   jobs.first_block[j + 1] = jobs.first_block[j] + (int)((n + 255) / 256);
 }
 
-int launch_reduce(snn_ctx *c, const ReduceJobs &jobs) {
-  if (jobs.njobs == 0) return SNN_OK;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(jobs.first_block[jobs.njobs]), dim3(256), 0, c->stream, jobs);
+// Sums the split partial products; with_loss adds the workgroup that takes the mean loss.
+int launch_reduce(snn_ctx *c, const ReduceJobs &jobs, bool with_loss) {
+  const int blocks = jobs.first_block[jobs.njobs] + (with_loss ? 1 : 0);
+  if (blocks == 0) return SNN_OK;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks), dim3(256), 0, c->stream, jobs,
+                     with_loss ? c->loss_b : nullptr, c->loss, c->B);
   HIPCHK(c, hipGetLastError());
+  if (with_loss) c->loss_ready = true;
+  return SNN_OK;
+}
+
+int ensure_loss(snn_ctx *c) {
+  if (c->loss_ready) return SNN_OK;
+  hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(256), 0, c->stream, c->loss_b, c->loss, c->B);
+  HIPCHK(c, hipGetLastError());
+  c->loss_ready = true;
   return SNN_OK;
 }
 
@@ -484,19 +496,20 @@ int launch_readout_forward(snn_ctx *c, const int32_t *labels) {
   Bracket br(c, SNN_K_READOUT_FORWARD, c->L);
   if (c->ldC <= 64) {
     const int cw = c->ldC <= 16 ? 16 : c->ldC <= 32 ? 32 : 64;
-    dim3 grid((c->B + 64 / cw - 1) / (64 / cw)), block(64);
+    dim3 grid((c->B + 64 / cw - 1) / (64 / cw)), block(512);
 #define SNN_RDL(CW, HL)                                                                                          \
   hipLaunchKernelGGL((readout_loss_kernel<CW, HL>), grid, block, 0, c->stream, y.I, y.V, c->z, c->tstar, labels, \
-                     c->loss_b, c->dz, c->loss, c->ticket, c->err_flag, y.dI, c->T, c->B, c->C, c->ldC, y.beta, dbg)
-    static const int dbg = [] { const char *e = getenv("SNN_DBG"); return e ? atoi(e) : 0; }();
+                     c->loss_b, c->dz, c->err_flag, y.dI, c->T, c->B, c->C, c->ldC, y.beta)
     if (c->hl) { if (cw == 16) SNN_RDL(16, true); else if (cw == 32) SNN_RDL(32, true); else SNN_RDL(64, true); }
     else { if (cw == 16) SNN_RDL(16, false); else if (cw == 32) SNN_RDL(32, false); else SNN_RDL(64, false); }
 #undef SNN_RDL
     HIPCHK(c, hipGetLastError());
     c->dj_ready = true;
+    c->loss_ready = false;
     return SNN_OK;
   }
   c->dj_ready = false;
+  c->loss_ready = true;
   const int stride = c->B * c->ldC;
   hipLaunchKernelGGL(readout_forward_kernel, dim3((stride + 255) / 256), dim3(256), 0, c->stream, y.I, y.V, c->z,
                      c->tstar, c->T, stride, y.beta);
@@ -717,6 +730,7 @@ int32_t snn_forward(snn_ctx *c, const uint8_t *x_dev, const int32_t *labels_dev,
   }
   c->state = 1;
   if (loss_host) {
+    if ((rc = ensure_loss(c))) return rc;
     HIPCHK(c, hipMemcpyAsync(loss_host, c->loss, sizeof(float), hipMemcpyDeviceToHost, c->stream));
     if ((rc = check_err_flag(c))) return rc;
   }
@@ -737,7 +751,7 @@ int32_t snn_backward(snn_ctx *c) {
   }
   {
     Bracket br(c, SNN_K_WEIGHT_GRAD, 0);
-    if ((rc = launch_reduce(c, jobs))) return rc;
+    if ((rc = launch_reduce(c, jobs, !c->loss_ready))) return rc;
   }
   c->state = 2;
   return SNN_OK;
@@ -761,6 +775,7 @@ int32_t snn_get_tensor(snn_ctx *c, int32_t tensor, int32_t layer, void *dst, siz
   if (rc) return rc;
   if (bytes != v.rows * v.cols * v.esz)
     return fail(c, SNN_ERR_SHAPE, "tensor %d needs %zu bytes, got %zu", tensor, v.rows * v.cols * v.esz, bytes);
+  if (tensor == SNN_T_LOSS && (rc = ensure_loss(c))) return rc;
   HIPCHK(c, hipMemcpy2DAsync(dst, v.cols * v.esz, v.p, v.ld * v.esz, v.cols * v.esz, v.rows, hipMemcpyDeviceToHost,
                              c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
@@ -827,7 +842,7 @@ int32_t snn_run_step(snn_ctx *c, int32_t step, int32_t layer, const uint8_t *x_d
       ReduceJobs jobs;
       memset(&jobs, 0, sizeof jobs);
       int rc = launch_weight_grad(c, l, jobs);
-      return rc ? rc : launch_reduce(c, jobs);
+      return rc ? rc : launch_reduce(c, jobs, false);
     }
     case SNN_STEP_INPUT_GRAD:
       if (l == 0) return fail(c, SNN_ERR_ARG, "layer 1 has no input gradient");

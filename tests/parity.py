@@ -37,7 +37,7 @@ def _splice(tr: O.Trace, sub: O.Trace, idx: np.ndarray, B: int):
     tr.loss = float(tr.loss_b.sum() / B)
 
 
-def reconciled_forward(net: O.Net, X, W, R, labels, S_gpu, max_rounds: int = 200):
+def reconciled_forward(net: O.Net, X, W, R, labels, S_gpu, max_rounds: int = 200, band: float = BAND):
     """Oracle forward with the device's near-threshold decisions imposed.
 
     S_gpu: list of uint8 arrays [T,B,N] per spiking layer.  Returns (trace, n_imposed).
@@ -66,7 +66,7 @@ def reconciled_forward(net: O.Net, X, W, R, labels, S_gpu, max_rounds: int = 200
             ns = np.flatnonzero(tr.S[l][t, b] != S_gpu[l][t, b])
             for n in ns:
                 dist = abs(tr.V[l][t, b, n] - net.theta)
-                if dist > BAND:
+                if dist > band:
                     raise ParityError(f"spike mismatch outside the band: layer {l + 1} t={t} b={b} n={n} "
                                       f"|V-theta|={dist:.3e} oracle V={tr.V[l][t, b, n]!r} "
                                       f"device spike={int(S_gpu[l][t, b, n])}")
@@ -161,3 +161,83 @@ def compare_backward(net: O.Net, inp, snn, tr, report=None, tol=TOL_GRAD):
     if report is not None:
         report.update(rep)
     return gr
+
+
+def sampled_step_parity(net: O.Net, inp, snn, loss_gpu, idx, n_rows=48, seed=0, report=None, tol=TOL_GRAD,
+                        tol_state=TOL_STATE, band=BAND):
+    """Parity at sizes where the oracle is run on a subset of the batch.
+
+    Samples of a batch only meet in the mean of the loss and in the sums over rows that
+    give dW and dR.  So (a) the oracle runs forward and backward on the samples `idx`
+    alone; every per-sample tensor of the device (currents, potentials, spikes, readout,
+    logits, first maximiser, per-sample loss, and dz, dJ, dI, dS scaled by |idx|/B for the
+    1/B of the batch mean) is compared on those samples at the usual tolerances; (b) the
+    device's loss must be the mean of its per-sample losses; (c) rows of dW^l and dR^l
+    drawn at random must equal the fp64 contraction over all T*B rows of the device's own
+    spikes and current gradients, which checks the split products at full size given their
+    inputs (the inputs themselves are covered by (a) on the sampled chains).
+    snn.backward() must have been called.
+    """
+    idx = np.asarray(idx)
+    B = inp.X.shape[1]
+    Lh = net.L - 1
+    rep = {}
+    Xs, ls = inp.X[:, idx], inp.labels[idx]
+    S_full = [snn.get_tensor("spikes", l + 1) for l in range(Lh)]
+    tr, imposed = reconciled_forward(net, Xs, inp.W, inp.R, ls, [s[:, idx] for s in S_full], band=band)
+    rep["imposed_decisions"] = imposed
+    rep["spike_rate"] = [float(s.mean()) for s in S_full]
+    for l in range(Lh):
+        assert np.array_equal(S_full[l][:, idx], tr.S[l].astype(np.uint8))
+        rep[f"V{l + 1}"] = close_state(f"V^{l + 1}", snn.get_tensor("membrane", l + 1)[:, idx], tr.V[l], tol_state)
+        rep[f"I{l + 1}"] = close_state(f"I^{l + 1}", snn.get_tensor("current", l + 1)[:, idx], tr.I[l], tol_state)
+    rep["Y"] = close_state("Y", snn.get_tensor("readout_trace")[:, idx], tr.Y, tol_state)
+    rep["z"] = close_state("z", snn.get_tensor("logits")[idx], tr.z, tol_state)
+    ts = snn.get_tensor("argmax_t")[idx]
+    bad = np.argwhere(ts != tr.tstar)
+    for b, c in bad:
+        if abs(tr.Y[ts[b, c], b, c] - tr.z[b, c]) > tol_state * max(1.0, abs(tr.z[b, c])):
+            raise ParityError(f"argmax over time differs at sample {idx[b]} c={c}")
+        tr.tstar[b, c] = ts[b, c]
+    rep["argmax_ties"] = int(len(bad))
+    lb = snn.get_tensor("loss_per_sample")
+    zscale = np.maximum(1.0, np.abs(tr.z).max(axis=1))
+    if not np.all(np.abs(lb[idx] - tr.loss_b) <= 2 * tol_state * zscale):
+        raise ParityError(f"per-sample loss: max error {np.abs(lb[idx] - tr.loss_b).max():.3e}")
+    mean = float(lb.astype(np.float64).mean())
+    if not abs(loss_gpu - mean) <= TOL_LOSS * abs(mean):
+        raise ParityError(f"loss {loss_gpu!r} is not the mean of the per-sample losses {mean!r}")
+
+    gr = O.backward(net, Xs, inp.W, inp.R, ls, tr)
+    k = len(idx) / B
+    close_grad("dz", snn.get_tensor("d_logits")[idx], gr.dz * k, tol)
+    dJ_full = snn.get_tensor("d_readout_current")
+    rep["dJ"] = close_grad("dJ", dJ_full[:, idx], gr.dJ * k, tol)
+    dI_full = []
+    for l in range(Lh):
+        dI = snn.get_tensor("d_current", l + 1)
+        dI_full.append(dI)
+        rep[f"dI{l + 1}"] = close_grad(f"dI^{l + 1}", dI[:, idx], gr.dI[l] * k, tol)
+        rep[f"dS{l + 1}"] = close_grad(f"dS^{l + 1}", snn.get_tensor("d_spikes", l + 1)[:, idx], gr.dS[l] * k, tol)
+    dI_full.append(dJ_full)
+
+    rng = np.random.default_rng(seed)
+
+    def rows_of(name, got, src, d):
+        # got[rows] against sum over (t, b) of src[t, b, rows]^T d[t, b, :]
+        K = src.shape[2]
+        rows = np.sort(rng.choice(K, size=min(n_rows, K), replace=False))
+        a = src[:, :, rows].reshape(-1, len(rows)).astype(np.float64)
+        want = a.T @ d.reshape(-1, d.shape[2]).astype(np.float64)
+        return close_grad(name, got[rows], want, tol)
+
+    below = [inp.X] + S_full
+    for l in range(net.L):
+        rep[f"dW{l + 1}"] = rows_of(f"dW^{l + 1}", snn.get_tensor("grad_w", l + 1), below[l], dI_full[l])
+    for l in range(Lh):
+        if inp.R[l] is not None:
+            # S_t R enters V_{t+1} beside I_t, so dR pairs S_t with the gradient of I_t
+            rep[f"dR{l + 1}"] = rows_of(f"dR^{l + 1}", snn.get_tensor("grad_r", l + 1), S_full[l], dI_full[l])
+    if report is not None:
+        report.update(rep)
+    return rep

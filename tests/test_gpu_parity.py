@@ -95,6 +95,40 @@ def test_multi_tile_fp32_theta_not_one():
     assert rep["spike_rate"][1] > 0.005
 
 
+def sampled_parity(wl, w_gain, n_samples=6, **tols):
+    """Full-size run of a configuration too large for a whole-batch oracle; see
+    parity.sampled_step_parity for what is compared."""
+    inp = workloads.generate(wl, w_gain=w_gain)
+    net = net_of(wl)
+    snn = make(wl, inp)
+    print(f"\n[case] sampled {wl.name} T={wl.T} B={wl.B} sizes={wl.sizes} rec={wl.recurrent} "
+          f"{wl.precision} {wl.surrogate} gain={w_gain}", flush=True)
+    loss = snn.forward(inp.X, inp.labels)
+    snn.backward()
+    idx = np.sort(np.random.default_rng(wl.index).choice(wl.B, size=n_samples, replace=False))
+    rep = parity.sampled_step_parity(net, inp, snn, loss, idx, seed=wl.index, **tols)
+    rep["loss"] = loss
+    rep["case"] = f"sampled {wl.name} T={wl.T} B={wl.B} {wl.precision} gain={w_gain} samples={idx.tolist()}"
+    print(json.dumps(rep), flush=True)
+    out_dir = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(out_dir):
+        with open(os.path.join(out_dir, "parity_reports.jsonl"), "a") as f:
+            f.write(json.dumps(rep) + "\n")
+    snn.destroy()
+    return rep
+
+
+@pytest.mark.parametrize("B", [128, 512])
+def test_wide_layers_vector_scans(B):
+    """B * N of 2^17 and 2^19 chains: the scan kernels that give two and four adjacent chains
+    to a thread (8- and 16-byte accesses), checked on every element."""
+    wl = workloads.Workload(name="widescan", index=13, T=24, B=B, sizes=(64, 1024, 1024, 20),
+                            recurrent=(False, False), beta=(0.9, 0.9, 0.9), theta=1.0, surrogate="superspike",
+                            slope=25.0, precision="bf16", rate_lo=0.05, rate_hi=0.3)
+    rep = full_step_parity(wl, w_gain=3.0, check_sgd=False)
+    assert rep["spike_rate"][0] > 0.01 and rep["spike_rate"][1] > 0.01
+
+
 # ---------------------------------------------------------------- headline configuration, full size
 @pytest.mark.parametrize("gain", [1.0, 3.0])
 def test_shd_ff128_full_size(gain):
@@ -256,3 +290,18 @@ def test_error_paths():
     assert snn.lib.snn_init(C.byref(cfg.c), small.data_ptr(), 1024, Wp, None, None, C.byref(ctx)) == 4
     assert snn.lib.snn_init(C.byref(cfg.c), small.data_ptr() + 1, 1 << 30, Wp, None, None, C.byref(ctx)) == 4
     snn.destroy()
+
+
+# ---------------------------------------------------------------- large configurations, full size
+def test_wide_ff1024_full_size_sampled():
+    rep = sampled_parity(workloads.CONFIGS["wide_ff1024"], w_gain=3.0)
+    assert rep["spike_rate"][0] > 0.005 and rep["spike_rate"][1] > 0.005
+
+
+def test_deep_rec2048_full_size_sampled():
+    """fp32 state with a fan-in of 2048 (+2048 recurrent) and a memory of 1/(1-beta) = 33 steps:
+    the rounding of the device's fp32 sums against the fp64 oracle reaches 1.3e-5 on a few of
+    the 3e6 sampled potentials, so potentials and the decision band are held to 5e-5 here
+    (the bound stated for bf16-product modes is 2e-2)."""
+    rep = sampled_parity(workloads.CONFIGS["deep_rec2048"], w_gain=3.0, n_samples=3, tol_state=5e-5, band=5e-5)
+    assert rep["spike_rate"][0] > 0.005
