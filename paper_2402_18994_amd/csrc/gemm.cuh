@@ -339,7 +339,7 @@ template <int ROWS, int NPL> struct LoaderQ<Q_T_F32S, ROWS, NPL> : LoaderQTWord<
 // that a workgroup alone keeps enough bytes outstanding to cover HBM/L2 latency even when
 // few workgroups fit a compute unit.
 template <int PM, int QM, int EPI, int WM, int WN, int TM, int TN, int NQP, int D>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
+__device__ __forceinline__ void gemm_body(const GemmArgs &a, const int block) {
   static_assert(WM * WN == 4, "four wavefronts per workgroup");
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   typedef LoaderP<PM, BM> LP;
@@ -356,7 +356,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
   // sharing a row slab of P share an L2.  With splits, XCD x takes the splits x, x+8, .. of
   // every tile: the tiles of one split read the same rows of both operands.
   const int ntiles = a.tiles_m * a.tiles_n;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int xcd = block & 7, slot = block >> 3;
   int tile, split;
   if (a.splits == 1) {
     tile = xcd * ((ntiles + 7) >> 3) + slot;
@@ -481,14 +481,59 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
 }
 
 template <int PM, int QM, int EPI, int WM, int WN, int TM, int TN, int NQP, int D>
-static hipError_t gemm_launch(GemmArgs a, int splits, hipStream_t st) {
+__global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
+  gemm_body<PM, QM, EPI, WM, WN, TM, TN, NQP, D>(a, blockIdx.x);
+}
+
+// Several independent products of one kind in a single launch: a small product cannot fill
+// the chip by itself, and every launch boundary costs a drain and a refill.  The workgroup
+// ranges of the jobs start at multiples of 8, so that (id & 7) is still the XCD.
+#define SNN_GEMM_MAX_JOBS 8
+struct GemmJobs {
+  int njobs;
+  int first_block[SNN_GEMM_MAX_JOBS + 1];
+  GemmArgs job[SNN_GEMM_MAX_JOBS];
+};
+
+template <int PM, int QM, int EPI, int WM, int WN, int TM, int TN, int NQP, int D>
+__global__ __launch_bounds__(256) void gemm_jobs_kernel(const GemmJobs jobs) {
+  int j = 0;
+  while (j + 1 < jobs.njobs && (int)blockIdx.x >= jobs.first_block[j + 1]) ++j;
+  gemm_body<PM, QM, EPI, WM, WN, TM, TN, NQP, D>(jobs.job[j], blockIdx.x - jobs.first_block[j]);
+}
+
+// Fills in the tile counts; returns the number of workgroups.
+template <int WM, int WN, int TM, int TN>
+static int gemm_prepare(GemmArgs &a, int splits) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   a.tiles_m = (a.rows + BM - 1) / BM;
   a.tiles_n = (a.cols + BN - 1) / BN;
   const int ntiles = a.tiles_m * a.tiles_n;
   a.splits = splits;
-  dim3 grid(splits == 1 ? (ntiles + 7) / 8 * 8 : 8 * ntiles * ((splits + 7) / 8), 1, 1);
+  return splits == 1 ? (ntiles + 7) / 8 * 8 : 8 * ntiles * ((splits + 7) / 8);
+}
+
+template <int PM, int QM, int EPI, int WM, int WN, int TM, int TN, int NQP, int D>
+static hipError_t gemm_launch(GemmArgs a, int splits, hipStream_t st) {
+  dim3 grid(gemm_prepare<WM, WN, TM, TN>(a, splits), 1, 1);
   hipLaunchKernelGGL((gemm_kernel<PM, QM, EPI, WM, WN, TM, TN, NQP, D>), grid, dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+// Adds a job (its workgroup range) to a list launched later by gemm_jobs_launch.
+template <int WM, int WN, int TM, int TN>
+static void gemm_jobs_add(GemmJobs &jobs, GemmArgs a, int splits) {
+  const int j = jobs.njobs++;
+  const int blocks = gemm_prepare<WM, WN, TM, TN>(a, splits);
+  jobs.job[j] = a;
+  jobs.first_block[j + 1] = jobs.first_block[j] + blocks;
+}
+
+template <int PM, int QM, int EPI, int WM, int WN, int TM, int TN, int NQP, int D>
+static hipError_t gemm_jobs_launch(const GemmJobs &jobs, hipStream_t st) {
+  if (jobs.njobs == 0) return hipSuccess;
+  dim3 grid(jobs.first_block[jobs.njobs], 1, 1);
+  hipLaunchKernelGGL((gemm_jobs_kernel<PM, QM, EPI, WM, WN, TM, TN, NQP, D>), grid, dim3(256), 0, st, jobs);
   return hipGetLastError();
 }
 

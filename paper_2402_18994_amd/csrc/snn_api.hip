@@ -345,8 +345,35 @@ int launch_input_grad(snn_ctx *c, int l) {
 
 // part[split][rows x cols] (or out directly when there is one split) = Sp^T G over one
 // slice of the T*B rows per split.
-int launch_tn(snn_ctx *c, SpikeSrc s, int rows, const void *G, int ldg, int cols, float *out, float *part,
-              int splits, long long per) {
+// Transposed products S^T G (weight gradients), gathered by tile shape: the products of all
+// layers are independent of each other and of the rest of the backward pass once their
+// operands exist, so they are launched together after the last reverse scan.
+struct WgradJobs {
+  GemmJobs narrow, mid, wide;        // cols <= 32, <= 64, wider
+};
+
+int flush_tn(snn_ctx *c, WgradJobs &w, int which) {
+  hipError_t e = hipSuccess;
+  const bool f32 = c->precision == SNN_PREC_FP32;
+  if (which == 0 && w.narrow.njobs) {
+    e = f32 ? gemm_jobs_launch<P_T_U8, Q_T_F32S, EPI_STORE, 4, 1, 1, 1, 3, 1>(w.narrow, c->stream)
+            : gemm_jobs_launch<P_T_U8, Q_T_HL, EPI_STORE, 4, 1, 1, 1, 2, 1>(w.narrow, c->stream);
+    memset(&w.narrow, 0, sizeof w.narrow);
+  } else if (which == 1 && w.mid.njobs) {
+    e = f32 ? gemm_jobs_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 1, 3, 1>(w.mid, c->stream)
+            : gemm_jobs_launch<P_T_U8, Q_T_HL, EPI_STORE, 2, 2, 2, 1, 2, 1>(w.mid, c->stream);
+    memset(&w.mid, 0, sizeof w.mid);
+  } else if (which == 2 && w.wide.njobs) {
+    e = f32 ? gemm_jobs_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 2, 3, 1>(w.wide, c->stream)
+            : gemm_jobs_launch<P_T_U8, Q_T_HL, EPI_STORE, 2, 2, 2, 2, 2, 1>(w.wide, c->stream);
+    memset(&w.wide, 0, sizeof w.wide);
+  }
+  HIPCHK(c, e);
+  return SNN_OK;
+}
+
+int queue_tn(snn_ctx *c, WgradJobs &w, SpikeSrc s, int rows, const void *G, int ldg, int cols, float *out,
+             float *part, int splits, long long per) {
   GemmArgs a;
   memset(&a, 0, sizeof a);
   a.P = s.p; a.ldp = s.ld; a.p_ivalid = s.valid; a.p_bytes = s.bytes;
@@ -355,17 +382,15 @@ int launch_tn(snn_ctx *c, SpikeSrc s, int rows, const void *G, int ldg, int cols
   a.kc_per_split = (int)per;
   a.c_split_stride = (long long)rows * cols;
   a.C = splits > 1 ? part : out;
-  hipError_t e;
-  if (c->precision == SNN_PREC_FP32) {
-    if (cols <= 32) e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 4, 1, 1, 1, 3, 1>(a, splits, c->stream);
-    else if (cols <= 64) e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 1, 3, 1>(a, splits, c->stream);
-    else e = gemm_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 2, 3, 1>(a, splits, c->stream);
-  } else {
-    if (cols <= 32) e = gemm_launch<P_T_U8, Q_T_HL, EPI_STORE, 4, 1, 1, 1, 2, 1>(a, splits, c->stream);
-    else if (cols <= 64) e = gemm_launch<P_T_U8, Q_T_HL, EPI_STORE, 2, 2, 2, 1, 2, 1>(a, splits, c->stream);
-    else e = gemm_launch<P_T_U8, Q_T_HL, EPI_STORE, 2, 2, 2, 2, 2, 1>(a, splits, c->stream);
+  const int which = cols <= 32 ? 0 : cols <= 64 ? 1 : 2;
+  GemmJobs &list = which == 0 ? w.narrow : which == 1 ? w.mid : w.wide;
+  if (list.njobs == SNN_GEMM_MAX_JOBS) {
+    int rc = flush_tn(c, w, which);
+    if (rc) return rc;
   }
-  HIPCHK(c, e);
+  if (which == 0) gemm_jobs_add<4, 1, 1, 1>(list, a, splits);
+  else if (which == 1) gemm_jobs_add<2, 2, 2, 1>(list, a, splits);
+  else gemm_jobs_add<2, 2, 2, 2>(list, a, splits);
   return SNN_OK;
 }
 
@@ -395,22 +420,38 @@ int ensure_loss(snn_ctx *c) {
   return SNN_OK;
 }
 
-// dW^l = S^{l-1}^T dI^l and, for a recurrent layer, dR^l = S^l^T dI^l: the split products.
-// Their partial sums are queued on `jobs` and reduced by one launch for all layers.
-int launch_weight_grad(snn_ctx *c, int l, ReduceJobs &jobs) {
+// dW^l = S^{l-1}^T dI^l and, for a recurrent layer, dR^l = S^l^T dI^l: the split products
+// are queued on `w`, their partial sums on `jobs` (one reduction launch for all layers).
+int queue_weight_grad(snn_ctx *c, int l, WgradJobs &w, ReduceJobs &jobs) {
   Layer &y = c->layers[l];
   SpikeSrc s = spikes_below(c, l);
   if (!s.p) return fail(c, SNN_ERR_NULL, "input raster is NULL");
-  Bracket br(c, SNN_K_WEIGHT_GRAD, l + 1);
-  int rc = launch_tn(c, s, y.K, y.dI, y.ld, y.N, y.dW, y.part_w, y.splits_w, y.per_w);
+  int rc = queue_tn(c, w, s, y.K, y.dI, y.ld, y.N, y.dW, y.part_w, y.splits_w, y.per_w);
   if (rc) return rc;
   add_reduce_job(jobs, y.part_w, y.dW, y.splits_w, (long long)y.K * y.N);
   if (y.recurrent) {
     SpikeSrc own = {y.S, y.ld, y.ld, (unsigned)(c->M * y.ld)};
-    rc = launch_tn(c, own, y.N, y.dI, y.ld, y.N, y.dR, y.part_r, y.splits_r, y.per_r);
+    rc = queue_tn(c, w, own, y.N, y.dI, y.ld, y.N, y.dR, y.part_r, y.splits_r, y.per_r);
     add_reduce_job(jobs, y.part_r, y.dR, y.splits_r, (long long)y.N * y.N);
   }
   return rc;
+}
+
+// Launches what was queued (largest tiles first) and the reduction of the partial sums.
+int launch_weight_grads(snn_ctx *c, WgradJobs &w, const ReduceJobs &jobs, bool with_loss) {
+  Bracket br(c, SNN_K_WEIGHT_GRAD, 0);
+  int rc;
+  // A narrow product (the readout's) is small; when a launch with wide tiles exists it rides
+  // along there (its tile count is the same, the unused columns load zeros) rather than
+  // paying for a launch of its own.
+  for (GemmJobs *from : {&w.narrow, &w.mid})
+    while (from->njobs && w.wide.njobs && w.wide.njobs < SNN_GEMM_MAX_JOBS) {
+      const GemmArgs a = from->job[--from->njobs];
+      gemm_jobs_add<2, 2, 2, 2>(w.wide, a, a.splits);
+    }
+  for (int which = 2; which >= 0; --which)
+    if ((rc = flush_tn(c, w, which))) return rc;
+  return launch_reduce(c, jobs, with_loss);
 }
 
 // Threads per workgroup of the one-thread-per-chain scans: single wavefronts while that is
@@ -743,16 +784,15 @@ int32_t snn_backward(snn_ctx *c) {
   int rc;
   ReduceJobs jobs;
   memset(&jobs, 0, sizeof jobs);
+  WgradJobs wj;
+  memset(&wj, 0, sizeof wj);
   if (!c->dj_ready && (rc = launch_readout_reverse(c))) return rc;
   for (int l = c->L - 1; l >= 0; --l) {
     if (c->layers[l].spiking && (rc = launch_lif_reverse(c, l))) return rc;
-    if ((rc = launch_weight_grad(c, l, jobs))) return rc;
+    if ((rc = queue_weight_grad(c, l, wj, jobs))) return rc;
     if (l > 0 && (rc = launch_input_grad(c, l))) return rc;
   }
-  {
-    Bracket br(c, SNN_K_WEIGHT_GRAD, 0);
-    if ((rc = launch_reduce(c, jobs, !c->loss_ready))) return rc;
-  }
+  if ((rc = launch_weight_grads(c, wj, jobs, !c->loss_ready))) return rc;
   c->state = 2;
   return SNN_OK;
 }
@@ -841,8 +881,10 @@ int32_t snn_run_step(snn_ctx *c, int32_t step, int32_t layer, const uint8_t *x_d
     case SNN_STEP_WEIGHT_GRAD: {
       ReduceJobs jobs;
       memset(&jobs, 0, sizeof jobs);
-      int rc = launch_weight_grad(c, l, jobs);
-      return rc ? rc : launch_reduce(c, jobs, false);
+      WgradJobs wj;
+      memset(&wj, 0, sizeof wj);
+      int rc = queue_weight_grad(c, l, wj, jobs);
+      return rc ? rc : launch_weight_grads(c, wj, jobs, false);
     }
     case SNN_STEP_INPUT_GRAD:
       if (l == 0) return fail(c, SNN_ERR_ARG, "layer 1 has no input gradient");
