@@ -121,8 +121,9 @@ int validate(const snn_config *cfg) {
   return SNN_OK;
 }
 
-// Contraction splits of a weight-gradient product with `tiles` output tiles over M rows:
-// enough workgroups to cover the chip about twice, but at least four 64-row tiles each.
+// Contraction splits of the weight-gradient products, which share one launch with `tiles`
+// output tiles in total over M rows each: enough workgroups to cover the chip about twice,
+// but at least four 64-row tiles per workgroup.
 int choose_splits(long long M, int tiles, long long *per_split) {
   static const long long target = [] {
     const char *e = getenv("SNN_WGRAD_WORKGROUPS");      // tuning knob; default below
@@ -170,6 +171,11 @@ struct Carver {
 void carve(snn_ctx &c, Carver &cv) {
   const size_t M = (size_t)c.M;
   const int np = c.nplanes;
+  int wg_tiles = 0;                                   // output tiles of all weight-gradient products
+  for (int l = 0; l < c.L; ++l) {
+    wg_tiles += wgrad_tiles(c.layers[l].K, c.layers[l].N);
+    if (c.layers[l].recurrent) wg_tiles += wgrad_tiles(c.layers[l].N, c.layers[l].N);
+  }
   for (int l = 0; l < c.L; ++l) {
     Layer &y = c.layers[l];
     const size_t K = y.K, N = y.N;
@@ -183,7 +189,7 @@ void carve(snn_ctx &c, Carver &cv) {
       y.qb_plane = (long long)rup(K, 128) * y.ldqb;
       y.Qb = cv.take<uint16_t>((size_t)np * y.qb_plane);
     }
-    y.splits_w = choose_splits(c.M, wgrad_tiles(y.K, y.N), &y.per_w);
+    y.splits_w = choose_splits(c.M, wg_tiles, &y.per_w);
     if (y.splits_w > 1) y.part_w = cv.take<float>((size_t)y.splits_w * K * N);
     if (y.recurrent) {
       y.Rm = cv.take<float>(N * N);
@@ -194,7 +200,7 @@ void carve(snn_ctx &c, Carver &cv) {
       y.QRb = cv.take<uint16_t>((size_t)np * y.qr_plane);
       y.g[0] = cv.take<float>((size_t)c.B * y.ld);
       y.g[1] = cv.take<float>((size_t)c.B * y.ld);
-      y.splits_r = choose_splits(c.M, wgrad_tiles(y.N, y.N), &y.per_r);
+      y.splits_r = choose_splits(c.M, wg_tiles, &y.per_r);
       if (y.splits_r > 1) y.part_r = cv.take<float>((size_t)y.splits_r * N * N);
     }
     y.I = cv.take<float>(M * y.ld);
