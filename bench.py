@@ -103,7 +103,7 @@ def main():
 
     import torch
     import workloads
-    from paper_2402_18994_amd.binding import from_workload, KERNELS
+    from paper_2402_18994_amd.binding import from_workload, KERNELS, CALIBRATE_US
 
     if not torch.cuda.is_available():
         print("bench.py: no HIP device; there is no CPU path to time", file=sys.stderr)
@@ -138,7 +138,7 @@ def main():
 
     if args.breakdown:
         for name in KERNELS:
-            if name == "none":
+            if name in ("none", "calibrate"):
                 continue
             snn.profile_select(name, 0)
             for _ in range(10):
@@ -149,13 +149,14 @@ def main():
                       file=sys.stderr)
         snn.profile_select("none", 0)
 
-    # cost of an empty pair of events on the stream: subtracted from the bracketed launches
-    evs = [torch.cuda.Event(enable_timing=True) for _ in range(100)]
-    for i in range(0, 100, 2):
-        evs[i].record(); evs[i + 1].record()
-    torch.cuda.synchronize()
-    gaps = sorted(evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(0, 100, 2))
-    ev_overhead_us = gaps[len(gaps) // 2]
+    # What a bracket adds to the kernel it times: the library brackets a kernel that waits a
+    # known time on the device clock, in the middle of a step; the excess is subtracted from
+    # the bracketed launches below.
+    snn.profile_select("calibrate", 0)
+    for _ in range(50):
+        step()
+    e_ms, e_n = snn.profile_read()
+    ev_overhead_us = e_ms / max(1, e_n) * 1e3 - CALIBRATE_US
 
     kname, klayer = args.dominant.split(":")
     klayer = int(klayer)

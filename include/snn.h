@@ -124,8 +124,13 @@ typedef enum {
   SNN_K_CURRENT_GEMM = 0, SNN_K_LIF_FORWARD = 1, SNN_K_RLIF_FORWARD = 2,
   SNN_K_READOUT_FORWARD = 3, SNN_K_READOUT_REVERSE = 4, SNN_K_LIF_REVERSE = 5,
   SNN_K_RLIF_REVERSE = 6, SNN_K_WEIGHT_GRAD = 7, SNN_K_INPUT_GRAD = 8, SNN_K_SGD = 9,
-  SNN_K_COUNT = 10
+  SNN_K_CALIBRATE = 10,        /* once per snn_backward, between two launches: a bracket around a
+                                  one-wavefront kernel that waits SNN_CALIBRATE_US on the device
+                                  clock; elapsed - SNN_CALIBRATE_US is what a bracket adds to the
+                                  kernel it times (launched only while this class is selected) */
+  SNN_K_COUNT = 11
 } snn_kernel_class;
+#define SNN_CALIBRATE_US 10
 
 /* Validate `cfg` and report the device bytes snn_init needs (a multiple of 256).
  * Pure host code.  Errors: SNN_ERR_NULL, SNN_ERR_ARG. */

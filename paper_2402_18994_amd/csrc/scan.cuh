@@ -384,6 +384,15 @@ __global__ __launch_bounds__(256) void readout_reverse_kernel(const float *__res
 }
 
 // ---------------------------------------------------------------- small utilities
+// One wavefront that returns once `ticks` of the constant-rate device clock have passed (or
+// after a bounded number of polls): a kernel of known duration for calibrating event timers.
+__global__ __launch_bounds__(64) void wait_ticks_kernel(long long ticks, long long *__restrict__ out) {
+  const long long t0 = wall_clock64();
+  long long t = t0;
+  for (int i = 0; i < (1 << 20) && t - t0 < ticks; ++i) t = wall_clock64();
+  if (threadIdx.x == 0) out[0] = t - t0;
+}
+
 // dst[m][0..ld) = src[m][0..n) followed by zeros (input rasters whose rows are not 4-byte multiples).
 __global__ __launch_bounds__(256) void pad_rows_kernel(const uint8_t *__restrict__ src, uint8_t *__restrict__ dst,
                                                        long long rows, int n, int ld) {

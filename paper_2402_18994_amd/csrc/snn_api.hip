@@ -69,6 +69,7 @@ struct snn_ctx {
   int state = 0;                  // 0 fresh, 1 forward done, 2 backward done
   bool dj_ready = false;          // the fused readout kernel has already written dJ
   bool loss_ready = false;        // the mean of loss_b has been taken since the last readout
+  int wall_khz = 100000;          // rate of the device's constant clock
   const uint8_t *x_eff = nullptr;  // raster the products read: the caller's, or x_pad
   uint8_t *x_pad = nullptr;        // zero-padded copy, only when N_0 is not a multiple of 4
   int ldx = 0;                     // row length of x_eff
@@ -745,6 +746,12 @@ int32_t snn_init(const snn_config *cfg, void *workspace_dev, size_t workspace_by
   int ndev = 0;
   hipError_t e = hipGetDeviceCount(&ndev);
   if (e != hipSuccess || ndev == 0) return bail(e != hipSuccess ? e : hipErrorNoDevice, "hipGetDeviceCount");
+  {
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
+      c->wall_khz = khz;
+  }
   if ((e = hipMemsetAsync(c->ws, 0, c->ws_bytes, c->stream)) != hipSuccess) return bail(e, "hipMemsetAsync(workspace)");
   for (int l = 0; l < c->L; ++l) {
     Layer &y = c->layers[l];
@@ -795,6 +802,12 @@ int32_t snn_backward(snn_ctx *c) {
   if (!c->dj_ready && (rc = launch_readout_reverse(c))) return rc;
   for (int l = c->L - 1; l >= 0; --l) {
     if (c->layers[l].spiking && (rc = launch_lif_reverse(c, l))) return rc;
+    if (l == 0 && c->prof.cls == SNN_K_CALIBRATE) {
+      Bracket br(c, SNN_K_CALIBRATE, 0);
+      hipLaunchKernelGGL(wait_ticks_kernel, dim3(1), dim3(64), 0, c->stream,
+                         (long long)c->wall_khz * SNN_CALIBRATE_US / 1000, (long long *)c->err_flag + 8);
+      HIPCHK(c, hipGetLastError());
+    }
     if ((rc = queue_weight_grad(c, l, wj, jobs))) return rc;
     if (l > 0 && (rc = launch_input_grad(c, l))) return rc;
   }
