@@ -347,9 +347,9 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, const int block) {
   constexpr int NPP = LP::PLANES;
   constexpr int NMAX = NPP > NQP ? NPP : NQP;
   constexpr int PT = BM * 128, QT = BN * 128;       // bytes of one plane of a tile
-  static_assert(NPP * PT + NQP * QT <= 65536, "static LDS limit");
+  constexpr int DR = D;
+  static_assert(NPP * PT + NQP * QT <= 65536, "one stage, several workgroups per compute unit");
   __shared__ __attribute__((aligned(16))) char lds[NPP * PT + NQP * QT];
-  char *const lds_q = lds + NPP * PT;
 
   // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Without
   // contraction splits an XCD gets a contiguous run of tiles (column tiles fastest), so tiles
@@ -384,10 +384,10 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, const int block) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  LP lp[D];
-  LQ lq[D];
+  LP lp[DR];
+  LQ lq[DR];
 #pragma unroll
-  for (int d = 0; d < D; ++d) {
+  for (int d = 0; d < DR; ++d) {
     lp[d].setup(a, row0, tid);
     lq[d].setup(a, col0, tid);
     lp[d].load(a, rp, kbeg + d * 64, kend);        // beyond kend the loads return zero
@@ -401,47 +401,55 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, const int block) {
 #pragma unroll
   for (int j = 0; j < TN; ++j) fb[j] = (wn * TN + j) * 32 + (lane & 31);
 
-  // The loop body is free of branches: the ring is run for a multiple of D tiles and the
-  // tiles beyond the range load zeros.  (A load issued under a condition would make every
-  // later wait conservative and serialise the ring.)
-  const int nk_ring = (nk + D - 1) / D * D;
-  for (int kt0 = 0; kt0 < nk_ring; kt0 += D) {
+  // the products of one 64-wide contraction tile held in the stage at `st`
+  auto multiply = [&](const char *st) {
+    const char *sq = st + NPP * PT;
 #pragma unroll
-    for (int d = 0; d < D; ++d) {
-      const int kt = kt0 + d;
-      lp[d].store(lds, tid);
-      lq[d].store(lds_q, tid);
-      lp[d].load(a, rp, kbeg + (kt + D) * 64, kend);
-      lq[d].load(a, rq, kbeg + (kt + D) * 64, kend);
-      lds_barrier();
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 af[NPP][TM], bq[NQP][TN];
+      const int chunk = ks * 2 + (lane >> 5);
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        bf16x8 af[NPP][TM], bq[NQP][TN];
-        const int chunk = ks * 2 + (lane >> 5);
+      for (int p = 0; p < NPP; ++p)
 #pragma unroll
-        for (int p = 0; p < NPP; ++p)
+        for (int i = 0; i < TM; ++i) af[p][i] = *(const bf16x8 *)(st + p * PT + tile_off(fa[i], chunk));
 #pragma unroll
-          for (int i = 0; i < TM; ++i) af[p][i] = *(const bf16x8 *)(lds + p * PT + tile_off(fa[i], chunk));
+      for (int q = 0; q < NQP; ++q)
 #pragma unroll
-        for (int q = 0; q < NQP; ++q)
+        for (int j = 0; j < TN; ++j) bq[q][j] = *(const bf16x8 *)(sq + q * QT + tile_off(fb[j], chunk));
+      // smallest products first
 #pragma unroll
-          for (int j = 0; j < TN; ++j) bq[q][j] = *(const bf16x8 *)(lds_q + q * QT + tile_off(fb[j], chunk));
-        // smallest products first
+      for (int s = NMAX - 1; s >= 0; --s)
 #pragma unroll
-        for (int s = NMAX - 1; s >= 0; --s)
+        for (int p = 0; p < NPP; ++p) {
+          const int q = s - p;
+          if (q >= 0 && q < NQP) {
 #pragma unroll
-          for (int p = 0; p < NPP; ++p) {
-            const int q = s - p;
-            if (q >= 0 && q < NQP) {
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-              for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                  acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[p][i], bq[q][j], acc[i][j], 0, 0, 0);
-            }
+              for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[p][i], bq[q][j], acc[i][j], 0, 0, 0);
           }
+        }
+    }
+  };
+
+  {
+    // One LDS stage.  The loop body is free of branches: the ring is run for a multiple of D
+    // tiles and the tiles beyond the range load zeros.  (A load issued under a condition
+    // would make every later wait conservative and serialise the ring.)
+    const int nk_ring = (nk + DR - 1) / DR * DR;
+    for (int kt0 = 0; kt0 < nk_ring; kt0 += DR) {
+#pragma unroll
+      for (int d = 0; d < DR; ++d) {
+        const int kt = kt0 + d;
+        lp[d].store(lds, tid);
+        lq[d].store(lds + NPP * PT, tid);
+        lp[d].load(a, rp, kbeg + (kt + DR) * 64, kend);
+        lq[d].load(a, rq, kbeg + (kt + DR) * 64, kend);
+        lds_barrier();
+        multiply(lds);
+        lds_barrier();                               // every wavefront is done with the stage
       }
-      lds_barrier();                                 // every wavefront is done with the stage
     }
   }
 

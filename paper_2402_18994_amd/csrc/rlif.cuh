@@ -1,8 +1,10 @@
 // Recurrent LIF layers: V_{t+1} = beta V_t + I_t + S_t R - theta S_t, with S_t the spikes
 // just emitted from V_t (R is [from][to]).  Every step needs all N spikes of a sample from
-// the step before, so time is walked on the host side of the stream: one launch per step,
-// each a [B x N] x [N x N] MFMA product whose epilogue applies the LIF update (forward) or
-// the surrogate-gradient recursion (reverse).  Stream order is the inter-step barrier.
+// the step before.  Layers of up to 128 neurons run their whole time loop in one kernel (a
+// workgroup owns a batch tile and all neurons).  Wider layers walk time on the host side of
+// the stream: one launch per step, each a [B x N] x [N x N] MFMA product whose epilogue
+// applies the LIF update (forward) or the surrogate-gradient recursion (reverse); stream
+// order is the inter-step barrier.
 #pragma once
 #include "gemm.cuh"
 #include "scan.cuh"
@@ -16,10 +18,249 @@ static hipError_t fill_zero(hipStream_t st, void *p, size_t bytes) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- narrow layers: one launch
+// For N <= 128 a workgroup can own a batch tile of 32 samples with ALL neurons of the layer:
+// the recurrence then never leaves the workgroup and the whole time loop runs inside one
+// kernel.  The product is taken transposed, (S_t R)^T = R^T S_t^T: the MFMA's row operand is a
+// 32-neuron slab of R^T (or of R for the reverse pass), loaded once and kept in registers for
+// all T steps; the column operand is the 32 x 128 tile of the samples' current spikes (or of
+// the planes of g), exchanged between the four wavefronts through LDS, double-buffered, one
+// barrier per step.  In the 32x32 accumulator a lane holds sample (lane & 31) and sixteen
+// neurons in four groups of four adjacent ones, so state, loads and stores are per-lane
+// 16-byte vectors and the LIF update needs no shuffles.  Wavefront w owns neurons
+// [32w, 32w+32).  Rows of I (or dS and V) are fetched PF steps ahead of their use.
+constexpr int RL_PITCH = 272;                 // bytes per sample row of an exchange tile (128 bf16 + pad)
+
+// The sixteen-byte fragment of a weight plane [row][k] (k contiguous, pitch ldq) for MFMA step ks.
+__device__ __forceinline__ bf16x8 rl_weight_frag(rsrc_t r, int row, int ldq, int ks, int lane) {
+  const int k = 16 * ks + 8 * (lane >> 5);
+  const u32x4 v = ld_b128(r, k < ldq ? (row * ldq + k) * 2 : OOB, 0);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+template <int NP>   // weight planes: 1 (bfloat16 weights) or 3 (fp32 as hi + mid + lo)
+__global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__restrict__ I, float *__restrict__ V,
+                                                                 uint8_t *__restrict__ S,
+                                                                 const uint16_t *__restrict__ QRf, int ldqr,
+                                                                 long long qr_plane, int T, int B, int N, int ld,
+                                                                 float beta, float theta) {
+  constexpr int PF = 4;
+  __shared__ __align__(16) char xs[2][32 * RL_PITCH];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int b = blockIdx.x * 32 + (lane & 31);
+  const int row4 = B * ld * 4;
+  const unsigned bytes = (unsigned)T * B * ld * 4u;
+  const rsrc_t rI = make_rsrc(I, bytes), rV = make_rsrc(V, bytes), rS = make_rsrc(S, bytes / 4);
+  const rsrc_t rQ = make_rsrc(QRf, (unsigned)(NP * qr_plane * 2));
+
+  bf16x8 wf[NP][8];                             // R^T[32w + (lane&31)][:], all planes, all k steps
+#pragma unroll
+  for (int p = 0; p < NP; ++p)
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+      wf[p][ks] = rl_weight_frag(rQ, (int)(p * (qr_plane / ldqr)) + 32 * w + (lane & 31), ldqr, ks, lane);
+
+  int vo4[4], vo1[4], xo[4];                    // per group of four neurons
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const int n = 32 * w + 8 * g + 4 * (lane >> 5);
+    const bool ok = b < B && n < ld;
+    vo4[g] = ok ? (b * ld + n) * 4 : OOB;
+    vo1[g] = ok ? b * ld + n : OOB;
+    xo[g] = (lane & 31) * RL_PITCH + n * 2;
+  }
+  float v[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) v[i] = 0.f;      // V_0 = 0
+  u32x4 cur[PF][4];
+#pragma unroll
+  for (int d = 0; d < PF; ++d)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) cur[d][g] = ld_b128(rI, vo4[g], min(d, T - 1) * row4);
+
+  auto step = [&](u32x4 (&in)[4], int t) {
+    uint32_t sp[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sp[i] = v[i] > theta ? 1u : 0u;
+    char *x = xs[t & 1];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      u32x4 vv;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) vv[i] = __float_as_uint(v[4 * g + i]);
+      st_b128(rV, vo4[g], t * row4, vv);
+      st_b32(rS, vo1[g], t * (row4 >> 2), sp[4 * g] | (sp[4 * g + 1] << 8) | (sp[4 * g + 2] << 16) | (sp[4 * g + 3] << 24));
+      u32x2 sx;                                  // four spikes as bfloat16 0.0 / 1.0
+      sx[0] = (sp[4 * g] | (sp[4 * g + 1] << 16)) * 0x3F80u;
+      sx[1] = (sp[4 * g + 2] | (sp[4 * g + 3] << 16)) * 0x3F80u;
+      *(u32x2 *)(x + xo[g]) = sx;
+    }
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    lds_barrier();
+    if (t + 1 < T) {                             // the last state is not used
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 sf = *(const bf16x8 *)(x + (lane & 31) * RL_PITCH + (16 * ks + 8 * (lane >> 5)) * 2);
+#pragma unroll
+        for (int p = NP - 1; p >= 0; --p) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[p][ks], sf, acc, 0, 0, 0);
+      }
+    }
+    // accumulator register r: neuron 32w + 8*(r/4) + 4*(lane/32) + r%4, i.e. group r/4, element r%4
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      v[i] = beta * v[i] + __uint_as_float(in[i >> 2][i & 3]) + acc[i] - (sp[i] ? theta : 0.f);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) in[g] = ld_b128(rI, vo4[g], min(t + PF, T - 1) * row4);
+  };
+  int t = 0;
+  for (; t + PF <= T; t += PF) {
+#pragma unroll
+    for (int d = 0; d < PF; ++d) step(cur[d], t + d);
+  }
+#pragma unroll
+  for (int d = 0; d < PF; ++d)
+    if (t + d < T) step(cur[d], t + d);
+}
+
+// Reverse pass of the same layers: g <- beta g + surr(V_t - theta) (dS_t - theta g + g R^T), dI_t = g
+// before the update.  g is real-valued, so it enters the product as bfloat16 planes (hi + lo
+// with bfloat16 weights, hi + mid + lo with fp32 weights); (g R^T)^T = R g^T with R[from][to]
+// as the row operand.
+template <int NP, int SURR>
+__global__ __launch_bounds__(256) void rlif_reverse_fused_kernel(const float *__restrict__ dS,
+                                                                 const float *__restrict__ V,
+                                                                 uint32_t *__restrict__ dI,
+                                                                 const uint16_t *__restrict__ QRb, int ldqr,
+                                                                 long long qr_plane, int T, int B, int N, int ld,
+                                                                 float beta, float theta, float slope) {
+  constexpr int PF = 2;
+  constexpr int GP = NP == 1 ? 2 : 3;           // planes of g
+  constexpr bool HL = NP == 1;                  // dI is stored in hi/lo form with bfloat16 weights
+  __shared__ __align__(16) char xs[2][GP][32 * RL_PITCH];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int b = blockIdx.x * 32 + (lane & 31);
+  const int row4 = B * ld * 4;
+  const unsigned bytes = (unsigned)T * B * ld * 4u;
+  const rsrc_t rdS = make_rsrc(dS, bytes), rV = make_rsrc(V, bytes), rdI = make_rsrc(dI, bytes);
+  const rsrc_t rQ = make_rsrc(QRb, (unsigned)(NP * qr_plane * 2));
+
+  bf16x8 wf[NP][8];                             // R[32w + (lane&31)][:]
+#pragma unroll
+  for (int p = 0; p < NP; ++p)
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+      wf[p][ks] = rl_weight_frag(rQ, (int)(p * (qr_plane / ldqr)) + 32 * w + (lane & 31), ldqr, ks, lane);
+
+  int vo4[4], xo[4];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const int n = 32 * w + 8 * g + 4 * (lane >> 5);
+    const bool ok = b < B && n < ld;
+    vo4[g] = ok ? (b * ld + n) * 4 : OOB;
+    xo[g] = (lane & 31) * RL_PITCH + n * 2;
+  }
+  float gv[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) gv[i] = 0.f;     // g_T = 0
+  u32x4 cds[PF][4], cv[PF][4];
+#pragma unroll
+  for (int d = 0; d < PF; ++d)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int so = max(T - 1 - d, 0) * row4;
+      cds[d][g] = ld_b128(rdS, vo4[g], so);
+      cv[d][g] = ld_b128(rV, vo4[g], so);
+    }
+
+  auto step = [&](u32x4 (&ds)[4], u32x4 (&vv)[4], int t) {
+    char *x = (char *)xs[t & 1];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      u32x4 o;
+      uint32_t pl[GP][4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float gg = gv[4 * g + i];
+        if (HL) {
+          const uint32_t hl = pack_hl(gg);
+          o[i] = hl;
+          pl[0][i] = hl & 0xFFFFu;
+          pl[1][i] = hl >> 16;
+        } else {
+          o[i] = __float_as_uint(gg);
+#pragma unroll
+          for (int q = 0; q < GP; ++q) pl[q][i] = bf16_piece(gg, q);
+        }
+      }
+      st_b128(rdI, vo4[g], t * row4, o);
+#pragma unroll
+      for (int q = 0; q < GP; ++q) {
+        u32x2 px;
+        px[0] = pl[q][0] | (pl[q][1] << 16);
+        px[1] = pl[q][2] | (pl[q][3] << 16);
+        *(u32x2 *)(x + q * 32 * RL_PITCH + xo[g]) = px;
+      }
+    }
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    lds_barrier();
+    if (t > 0) {                                 // the g leaving step 0 is not used
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        bf16x8 gf[GP];
+#pragma unroll
+        for (int q = 0; q < GP; ++q)
+          gf[q] = *(const bf16x8 *)(x + q * 32 * RL_PITCH + (lane & 31) * RL_PITCH + (16 * ks + 8 * (lane >> 5)) * 2);
+        // smallest products first
+#pragma unroll
+        for (int sum = NP + GP - 2; sum >= 0; --sum)
+#pragma unroll
+          for (int p = 0; p < NP; ++p) {
+            const int q = sum - p;
+            if (q >= 0 && q < GP && (NP == 1 || p + q < 3))
+              acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[p][ks], gf[q], acc, 0, 0, 0);
+          }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float q = __uint_as_float(ds[i >> 2][i & 3]) - theta * gv[i] + acc[i];
+      gv[i] = beta * gv[i] + surr<SURR>(slope, __uint_as_float(vv[i >> 2][i & 3]) - theta) * q;
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int so = max(t - PF, 0) * row4;
+      ds[g] = ld_b128(rdS, vo4[g], so);
+      vv[g] = ld_b128(rV, vo4[g], so);
+    }
+  };
+  int t = T - 1;
+  for (; t - PF + 1 >= 0; t -= PF) {
+#pragma unroll
+    for (int d = 0; d < PF; ++d) step(cds[d], cv[d], t - d);
+  }
+#pragma unroll
+  for (int d = 0; d < PF; ++d)
+    if (t - d >= 0) step(cds[d], cv[d], t - d);
+}
+
 // I, V [T][B][ld] fp32, S [T][B][ld] bytes; QRf[plane][to][from] bfloat16.
 static hipError_t rlif_forward(hipStream_t st, bool fp32, int T, int B, int N, int ld, const float *I, float *V,
                                uint8_t *S, const uint16_t *QRf, int ldqr, long long qr_plane, float beta,
                                float theta) {
+  if (ld <= 128) {                              // the whole time loop in one launch
+    dim3 grid((B + 31) / 32), block(256);
+    if (fp32)
+      hipLaunchKernelGGL(rlif_forward_fused_kernel<3>, grid, block, 0, st, I, V, S, QRf, ldqr, qr_plane, T, B, N, ld,
+                         beta, theta);
+    else
+      hipLaunchKernelGGL(rlif_forward_fused_kernel<1>, grid, block, 0, st, I, V, S, QRf, ldqr, qr_plane, T, B, N, ld,
+                         beta, theta);
+    return hipGetLastError();
+  }
   const size_t stride = (size_t)B * ld;
   hipError_t e;
   if ((e = fill_zero(st, V, stride * 4)) != hipSuccess) return e;     // V_0 = 0
@@ -47,6 +288,21 @@ static hipError_t rlif_forward(hipStream_t st, bool fp32, int T, int B, int N, i
 static hipError_t rlif_reverse(hipStream_t st, bool fp32, int T, int B, int N, int ld, const float *dS, const float *V,
                                uint32_t *dI, float *g0, float *g1, const uint16_t *QRb, int ldqr,
                                long long qr_plane, float beta, float theta, int surrogate, float slope) {
+  if (ld <= 128) {
+    dim3 grid((B + 31) / 32), block(256);
+#define SNN_RLR(NP, SU)                                                                                         \
+  hipLaunchKernelGGL((rlif_reverse_fused_kernel<NP, SU>), grid, block, 0, st, dS, V, dI, QRb, ldqr, qr_plane, T, B, \
+                     N, ld, beta, theta, slope)
+    if (fp32) {
+      switch (surrogate) { case 0: SNN_RLR(3, 0); break; case 1: SNN_RLR(3, 1); break;
+                           case 2: SNN_RLR(3, 2); break; default: SNN_RLR(3, 3); break; }
+    } else {
+      switch (surrogate) { case 0: SNN_RLR(1, 0); break; case 1: SNN_RLR(1, 1); break;
+                           case 2: SNN_RLR(1, 2); break; default: SNN_RLR(1, 3); break; }
+    }
+#undef SNN_RLR
+    return hipGetLastError();
+  }
   const size_t stride = (size_t)B * ld;
   hipError_t e;
   if ((e = fill_zero(st, g0, stride * 4)) != hipSuccess) return e;                              // g_T = 0

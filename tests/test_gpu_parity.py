@@ -145,11 +145,22 @@ def test_shd_ff128_fp32_products():
 # ---------------------------------------------------------------- recurrent layers
 @pytest.mark.parametrize("precision", ["fp32", "bf16"])
 def test_recurrent_small(precision):
-    wl = workloads.Workload(name="rec_small", index=13, T=30, B=10, sizes=(50, 40, 24, 5), recurrent=(True, True),
+    wl = workloads.Workload(name="rec_small", index=13, T=31, B=40, sizes=(50, 40, 24, 5), recurrent=(True, True),
                             beta=(0.9, 0.9, 0.9), theta=1.0, surrogate="superspike", slope=25.0,
                             precision=precision, rate_lo=0.05, rate_hi=0.2, rec_gain=1.0)
     rep = full_step_parity(wl, w_gain=2.5)
     assert rep["spike_rate"][0] > 0.01 and rep["spike_rate"][1] > 0.005
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_recurrent_wider_than_one_workgroup(precision):
+    """A recurrent layer of more than 128 neurons walks time with one launch per step; an odd
+    number of steps and a partial batch tile on the side."""
+    wl = workloads.Workload(name="rec_wide", index=15, T=21, B=11, sizes=(60, 168, 5), recurrent=(True,),
+                            beta=(0.9, 0.9), theta=1.0, surrogate="arctan", slope=2.0,
+                            precision=precision, rate_lo=0.05, rate_hi=0.2, rec_gain=1.0)
+    rep = full_step_parity(wl, w_gain=2.5)
+    assert rep["spike_rate"][0] > 0.01
 
 
 @pytest.mark.parametrize("gain", [1.0, 3.0])
