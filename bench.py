@@ -20,6 +20,17 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE run, then WRITE_SIZE run; KiB
+# per dispatch, each scaled by what the same counter reads for the 256 MiB device copy this
+# script issues first: FETCH_SIZE reads half the bytes of that copy, WRITE_SIZE all of them).
+# The runs and their figures are in profiles/train_step_shd_ff128.txt.
+MEASURED_TRAFFIC = {("shd_ff128", "lif_reverse"): (16453.5 * 2.0 + 16384.0) * 1024.0}
+
+# rocprofv3's duration of the calibration kernel that waits CALIBRATE_US on the device clock: the
+# difference is the start and end of a dispatch, which the profiler counts as kernel time.  The
+# event timer is calibrated against this figure so that its kernel times are the profiler's.
+CALIBRATE_KERNEL_PROFILED_US = 10.87
+
 
 def algorithmic_bytes(wl, kernel, layer):
     """HBM bytes one launch of `kernel` for text layer `layer` has to move (compulsory traffic
@@ -93,7 +104,8 @@ def main():
     ap.add_argument("--dominant", default="lif_reverse:0",
                     help="kernel:layer bracketed for the roofline line (layer 0 = every layer)")
     ap.add_argument("--traffic", type=float, default=None,
-                    help="measured HBM bytes per launch of the dominant kernel (from the rocprofv3 --pmc runs)")
+                    help="measured HBM bytes per launch of the dominant kernel (from the rocprofv3 --pmc runs); "
+                         "default: the committed measurement for the default workload and kernel")
     ap.add_argument("--breakdown", action="store_true", help="time every kernel class first (stderr)")
     ap.add_argument("--no-cpu", action="store_true")
     args = ap.parse_args()
@@ -136,19 +148,6 @@ def main():
         step()
     torch.cuda.synchronize()
 
-    if args.breakdown:
-        for name in KERNELS:
-            if name in ("none", "calibrate"):
-                continue
-            snn.profile_select(name, 0)
-            for _ in range(10):
-                step()
-            ms, n = snn.profile_read()
-            if n:
-                print(f"[breakdown] {name:16s} {ms / 10 * 1e3:9.1f} us/step over {n // 10} launches/step",
-                      file=sys.stderr)
-        snn.profile_select("none", 0)
-
     # What a bracket adds to the kernel it times: the library brackets a kernel that waits a
     # known time on the device clock, in the middle of a step; the excess is subtracted from
     # the bracketed launches below.
@@ -156,7 +155,25 @@ def main():
     for _ in range(50):
         step()
     e_ms, e_n = snn.profile_read()
-    ev_overhead_us = e_ms / max(1, e_n) * 1e3 - CALIBRATE_US
+    ev_overhead_us = e_ms / max(1, e_n) * 1e3 - CALIBRATE_KERNEL_PROFILED_US
+    assert abs(CALIBRATE_KERNEL_PROFILED_US - CALIBRATE_US) < 2.0
+
+    # every kernel class once, outside the timed region: microseconds per step, bracket cost removed
+    per_class = {}
+    for name in KERNELS:
+        if name in ("none", "calibrate"):
+            continue
+        snn.profile_select(name, 0)
+        for _ in range(10):
+            step()
+        ms, n = snn.profile_read()
+        if n:
+            per_class[name] = {"us_per_step": round((ms * 1e3 - n * ev_overhead_us) / 10, 2), "launches_per_step": n // 10}
+    snn.profile_select("none", 0)
+    if args.breakdown:
+        for k, v in per_class.items():
+            print(f"[breakdown] {k:16s} {v['us_per_step']:9.1f} us/step over {v['launches_per_step']} launches/step",
+                  file=sys.stderr)
 
     kname, klayer = args.dominant.split(":")
     klayer = int(klayer)
@@ -191,10 +208,12 @@ def main():
         "roofline": {"bound": "hbm", "kernel": f"{kname}" + (f" layer {klayer}" if klayer else " (all layers)"),
                      "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": args.traffic, "algorithmic_bytes_per_launch": abytes,
+                     "traffic": args.traffic if args.traffic is not None else MEASURED_TRAFFIC.get((wl.name, kname)),
+                     "algorithmic_bytes_per_launch": abytes,
                      "avg_launch_us": k_avg_s * 1e6, "avg_launch_us_with_events": k_raw_us,
                      "event_pair_overhead_us": ev_overhead_us, "launches": k_n},
         "gemm_tflops_whole_step": gemm_flops(wl) / (dt / args.steps) / 1e12,
+        "kernel_classes": per_class,
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(wl, inp)
