@@ -35,7 +35,7 @@ namespace snn {
 
 enum { P_U8 = 0, P_HL = 1, P_F32S = 2, P_T_U8 = 3 };
 enum { Q_BF16 = 0, Q_T_HL = 1, Q_T_F32S = 2 };
-enum { EPI_STORE = 0, EPI_RLIF_FWD = 1, EPI_RLIF_REV = 2 };
+enum { EPI_STORE = 0 };
 
 struct GemmArgs {
   const void *P;
@@ -51,27 +51,7 @@ struct GemmArgs {
   int splits;
   long long c_split_stride;  // elements between partial results
   int tiles_m, tiles_n;
-  // recurrent-step epilogues (rows = B, cols = N, all [B][ld] with ld = ldc)
-  const float *e_cur;        // fwd: I_t            rev: dS_t
-  const float *e_v;          // fwd: V_t            rev: V_t
-  const uint8_t *e_s;        // fwd: S_t
-  const float *e_g;          // rev: g (dL/dV_{t+1}), fp32
-  float *e_out_f;            // fwd: V_{t+1}        rev: new g
-  uint8_t *e_out_s;          // fwd: S_{t+1}
-  uint32_t *e_out_di;        // rev: dI_{t-1} (NULL at t = 0), fp32 bits or HL
-  int e_di_hl;
-  float beta, theta, slope;
-  int surrogate;
 };
-
-__device__ __forceinline__ float surrogate_eval(int kind, float k, float x) {
-  switch (kind) {
-    case 0: { float d = 1.0f + k * fabsf(x); return 1.0f / (d * d); }
-    case 1: { float u = 1.5707963267948966f * k * x; return (0.5f * k) / (1.0f + u * u); }
-    case 2: { float s = 1.0f / (1.0f + __expf(-k * x)); return k * s * (1.0f - s); }
-    default: return fmaxf(0.0f, 1.0f - fabsf(k * x));
-  }
-}
 
 // ------------------------------------------------------------------ operand loaders
 // setup(): per-lane byte offsets and LDS offsets, once per workgroup.
@@ -441,11 +421,10 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, const int block) {
     for (int kt0 = 0; kt0 < nk_ring; kt0 += DR) {
 #pragma unroll
       for (int d = 0; d < DR; ++d) {
-        const int kt = kt0 + d;
         lp[d].store(lds, tid);
         lq[d].store(lds + NPP * PT, tid);
-        lp[d].load(a, rp, kbeg + (kt + DR) * 64, kend);
-        lq[d].load(a, rq, kbeg + (kt + DR) * 64, kend);
+        lp[d].load(a, rp, kbeg + (kt0 + d + DR) * 64, kend);
+        lq[d].load(a, rq, kbeg + (kt0 + d + DR) * 64, kend);
         lds_barrier();
         multiply(lds);
         lds_barrier();                               // every wavefront is done with the stage
@@ -466,23 +445,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, const int block) {
         const int row = row0 + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         if (row < a.rows && col < a.cols) {
           const size_t o = (size_t)row * a.ldc + col;
-          const float v = acc[i][j][r];
-          if (EPI == EPI_STORE) {
-            C[o] = v;
-          } else if (EPI == EPI_RLIF_FWD) {
-            // V_{t+1} = beta V_t + I_t + S_t R - theta S_t ; S_{t+1} = [V_{t+1} > theta]
-            const float s = (float)a.e_s[o];
-            const float vn = a.beta * a.e_v[o] + a.e_cur[o] + v - a.theta * s;
-            a.e_out_f[o] = vn;
-            a.e_out_s[o] = vn > a.theta ? 1 : 0;
-          } else {
-            // g_t = beta g_{t+1} + surr(V_t - theta) (dS_t - theta g_{t+1} + g_{t+1} R^T)
-            const float g = a.e_g[o];
-            const float q = a.e_cur[o] - a.theta * g + v;
-            const float gn = a.beta * g + surrogate_eval(a.surrogate, a.slope, a.e_v[o] - a.theta) * q;
-            a.e_out_f[o] = gn;
-            if (a.e_out_di) a.e_out_di[o] = a.e_di_hl ? pack_hl(gn) : __float_as_uint(gn);
-          }
+          C[o] = acc[i][j][r];
         }
       }
     }

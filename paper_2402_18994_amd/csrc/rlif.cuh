@@ -247,6 +247,279 @@ __global__ __launch_bounds__(256) void rlif_reverse_fused_kernel(const float *__
     if (t - d >= 0) step(cds[d], cv[d], t - d);
 }
 
+// ---------------------------------------------------------------- wide layers: one launch per step
+// Wider layers do not fit a workgroup, so time is walked on the host side of the stream and
+// stream order is the inter-step barrier.  One step is the transposed product of the fused
+// kernels above, tiled 32 neurons x 32 samples per workgroup; the four wavefronts split the
+// contraction and add their accumulators through LDS, after which wavefront w applies the
+// LIF update (or the surrogate recursion) to neuron group w of the tile.  Each wavefront
+// walks its share of the contraction in 64-wide tiles of its own: rows are fetched with
+// 16-byte loads that cover whole cache lines (a fragment-shaped load would touch 32 lines per
+// instruction and leave the kernel bound by address processing), converted, written to a
+// wavefront-private LDS tile in the swizzled layout of the product kernels and read back as
+// MFMA fragments; no workgroup barrier is needed until the final sum.  Neuron tiles are dealt
+// to XCDs so that XCD x only ever reads the rows x, x+8, .. (in units of 32) of the weight
+// matrix.
+struct RlifStepMap {
+  int nt, st;          // neuron tile, sample tile
+  bool live;
+};
+__device__ __forceinline__ RlifStepMap rlif_step_map(int n_tiles, int s_tiles) {
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  RlifStepMap m;
+  m.st = slot % s_tiles;
+  m.nt = (slot / s_tiles) * 8 + xcd;
+  m.live = m.nt < n_tiles;
+  return m;
+}
+static inline unsigned rlif_step_grid(int N, int B) {
+  const int n_tiles = (N + 31) / 32, s_tiles = (B + 31) / 32;
+  return 8u * s_tiles * ((n_tiles + 7) / 8);
+}
+
+// Sums the four wavefronts' accumulators; returns registers 4w..4w+3 (neuron group w).
+__device__ __forceinline__ f32x4 rlif_reduce(const f32x16 &acc, float (*red)[16][64], int w, int lane) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) red[w][r][lane] = acc[r];
+  __syncthreads();
+  f32x4 o;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) o[i] = (red[0][4 * w + i][lane] + red[1][4 * w + i][lane]) + (red[2][4 * w + i][lane] + red[3][4 * w + i][lane]);
+  return o;
+}
+
+// Weight tile of a wavefront: 32 rows x 64 contraction elements of every plane, four
+// 16-byte loads per plane (lane: row lane/8 + 8j, chunk lane%8).
+template <int NP> struct RlifWeightTile {
+  u32x4 r[NP][4];
+  __device__ __forceinline__ void load(rsrc_t rq, int row0, int rows_per_plane, int ldq, int k0, bool in, int lane) {
+    const int c = lane & 7;
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int row = (lane >> 3) + 8 * j;
+        const int k = k0 + 8 * c;
+        r[p][j] = ld_b128(rq, in && k < ldq ? ((p * rows_per_plane + row0 + row) * ldq + k) * 2 : OOB, 0);
+      }
+  }
+  __device__ __forceinline__ void store(char *tile, int lane) const {      // tile: NP planes of 4 KB
+    const int c = lane & 7;
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) *(u32x4 *)(tile + p * 4096 + tile_off((lane >> 3) + 8 * j, c)) = r[p][j];
+  }
+};
+
+template <int NP>
+__global__ __launch_bounds__(256) void rlif_step_forward_kernel(const uint8_t *__restrict__ S, const float *__restrict__ I,
+                                                                const float *__restrict__ V, float *__restrict__ Vn,
+                                                                uint8_t *__restrict__ Sn,
+                                                                const uint16_t *__restrict__ QRf, int ldqr,
+                                                                long long qr_plane, int B, int N, int ld, float beta,
+                                                                float theta) {
+  constexpr int PF = NP == 1 ? 4 : 2;                    // tiles in flight per wavefront
+  __shared__ float red[4][16][64];
+  __shared__ __align__(16) char tiles[4][(NP + 1) * 4096];
+  const RlifStepMap m = rlif_step_map((N + 31) / 32, (B + 31) / 32);
+  if (!m.live) return;                                   // whole workgroup
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int b = m.st * 32 + (lane & 31);
+  const unsigned bytes = (unsigned)B * ld * 4u;
+  const rsrc_t rS = make_rsrc(S, bytes / 4), rQ = make_rsrc(QRf, (unsigned)(NP * qr_plane * 2));
+  const int ktiles = (ld + 63) / 64, per = (ktiles + 3) / 4;
+  const int kt0 = w * per, kt1 = min(ktiles, kt0 + per);
+  const int rows_per_plane = (int)(qr_plane / ldqr);
+  char *const wt = tiles[w], *const st = tiles[w] + NP * 4096;
+
+  // operands of the update do not depend on the product: fetch them first
+  const int n = m.nt * 32 + 8 * w + 4 * (lane >> 5);
+  const bool upd = b < B && n < ld;
+  const size_t o = upd ? (size_t)b * ld + n : 0;
+  const float4 cur = *(const float4 *)(I + o), v = *(const float4 *)(V + o);
+  const uint32_t sp = *(const uint32_t *)(S + o);
+
+  // spike tile: 32 samples x 64 bytes, two 16-byte loads (lane: sample lane/4 + 16j, chunk lane%4)
+  RlifWeightTile<NP> wr[PF];
+  u32x4 sr[PF][2];
+  auto fetch = [&](int d, int kt) {
+    const bool in = kt < kt1;
+    wr[d].load(rQ, m.nt * 32, rows_per_plane, ldqr, kt * 64, in, lane);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int sb = m.st * 32 + (lane >> 2) + 16 * j, k = kt * 64 + 16 * (lane & 3);
+      sr[d][j] = ld_b128(rS, in && sb < B && k < ld ? sb * ld + k : OOB, 0);
+    }
+  };
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  auto consume = [&](int d) {
+    wave_sync();                                         // the tile's previous readers are done
+    wr[d].store(wt, lane);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int row = (lane >> 2) + 16 * j;
+      u32x4 lo, hi;                                      // 16 spike bytes -> 16 bfloat16
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t x = sr[d][j][i];
+        const uint32_t p0 = spikes2_to_bf16(__builtin_amdgcn_perm(0u, x, 0x0C010C00u));
+        const uint32_t p1 = spikes2_to_bf16(__builtin_amdgcn_perm(0u, x, 0x0C030C02u));
+        if (i < 2) { lo[2 * i] = p0; lo[2 * i + 1] = p1; } else { hi[2 * (i - 2)] = p0; hi[2 * (i - 2) + 1] = p1; }
+      }
+      *(u32x4 *)(st + tile_off(row, 2 * (lane & 3))) = lo;
+      *(u32x4 *)(st + tile_off(row, 2 * (lane & 3) + 1)) = hi;
+    }
+    wave_sync();
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int chunk = 2 * ks + (lane >> 5);
+      const bf16x8 sf = *(const bf16x8 *)(st + tile_off(lane & 31, chunk));
+#pragma unroll
+      for (int p = NP - 1; p >= 0; --p) {
+        const bf16x8 wf = *(const bf16x8 *)(wt + p * 4096 + tile_off(lane & 31, chunk));
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, sf, acc, 0, 0, 0);
+      }
+    }
+  };
+#pragma unroll
+  for (int d = 0; d < PF; ++d) fetch(d, kt0 + d);
+  for (int kt = kt0; kt < kt1; kt += PF) {
+#pragma unroll
+    for (int d = 0; d < PF; ++d) {
+      if (kt + d < kt1) consume(d);
+      fetch(d, kt + d + PF);
+    }
+  }
+  const f32x4 sum = rlif_reduce(acc, red, w, lane);
+  if (upd) {
+    const float c4[4] = {cur.x, cur.y, cur.z, cur.w}, v4[4] = {v.x, v.y, v.z, v.w};
+    float vn[4];
+    uint32_t out = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float s = (float)((sp >> (8 * i)) & 1u);
+      vn[i] = beta * v4[i] + c4[i] + sum[i] - theta * s;
+      out |= (vn[i] > theta ? 1u : 0u) << (8 * i);
+    }
+    *(float4 *)(Vn + o) = make_float4(vn[0], vn[1], vn[2], vn[3]);
+    *(uint32_t *)(Sn + o) = out;
+  }
+}
+
+// One reverse step: gn = beta g + surr(V_t - theta) (dS_t - theta g + g R^T); the words of g
+// (dI_t: hi/lo pairs with bfloat16 weights, fp32 bits otherwise) are the column operand.
+template <int NP, int SURR>
+__global__ __launch_bounds__(256) void rlif_step_reverse_kernel(const uint32_t *__restrict__ Gw, const float *__restrict__ G,
+                                                                const float *__restrict__ dS, const float *__restrict__ V,
+                                                                float *__restrict__ Gn, uint32_t *__restrict__ dIn,
+                                                                const uint16_t *__restrict__ QRb, int ldqr,
+                                                                long long qr_plane, int B, int N, int ld, float beta,
+                                                                float theta, float slope) {
+  constexpr int GP = NP == 1 ? 2 : 3;
+  constexpr bool HL = NP == 1;
+  constexpr int PF = 2;
+  __shared__ float red[4][16][64];
+  __shared__ __align__(16) char tiles[4][(NP + GP) * 4096];
+  const RlifStepMap m = rlif_step_map((N + 31) / 32, (B + 31) / 32);
+  if (!m.live) return;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int b = m.st * 32 + (lane & 31);
+  const unsigned bytes = (unsigned)B * ld * 4u;
+  const rsrc_t rG = make_rsrc(Gw, bytes), rQ = make_rsrc(QRb, (unsigned)(NP * qr_plane * 2));
+  const int ktiles = (ld + 63) / 64, per = (ktiles + 3) / 4;
+  const int kt0 = w * per, kt1 = min(ktiles, kt0 + per);
+  const int rows_per_plane = (int)(qr_plane / ldqr);
+  char *const wt = tiles[w], *const gt = tiles[w] + NP * 4096;
+
+  const int n = m.nt * 32 + 8 * w + 4 * (lane >> 5);
+  const bool upd = b < B && n < ld;
+  const size_t o = upd ? (size_t)b * ld + n : 0;
+  const float4 ds = *(const float4 *)(dS + o), v = *(const float4 *)(V + o), g = *(const float4 *)(G + o);
+
+  // tile of g words: 32 samples x 64 words, eight 16-byte loads (lane: sample lane/16 + 4j, words 4(lane%16)..)
+  RlifWeightTile<NP> wr[PF];
+  u32x4 gr[PF][8];
+  auto fetch = [&](int d, int kt) {
+    const bool in = kt < kt1;
+    wr[d].load(rQ, m.nt * 32, rows_per_plane, ldqr, kt * 64, in, lane);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int sb = m.st * 32 + (lane >> 4) + 4 * j, k = kt * 64 + 4 * (lane & 15);
+      gr[d][j] = ld_b128(rG, in && sb < B && k < ld ? (sb * ld + k) * 4 : OOB, 0);
+    }
+  };
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  auto consume = [&](int d) {
+    wave_sync();
+    wr[d].store(wt, lane);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int row = (lane >> 4) + 4 * j;
+      const int off = tile_off(row, (lane & 15) >> 1) + 8 * (lane & 1);   // four bfloat16 = 8 bytes
+      const u32x4 x = gr[d][j];
+#pragma unroll
+      for (int q = 0; q < GP; ++q) {
+        u32x2 pl;
+        if (HL) {
+          pl[0] = q == 0 ? (x[0] & 0xFFFFu) | (x[1] << 16) : (x[0] >> 16) | (x[1] & 0xFFFF0000u);
+          pl[1] = q == 0 ? (x[2] & 0xFFFFu) | (x[3] << 16) : (x[2] >> 16) | (x[3] & 0xFFFF0000u);
+        } else {
+          pl[0] = pack2(bf16_piece(__uint_as_float(x[0]), q), bf16_piece(__uint_as_float(x[1]), q));
+          pl[1] = pack2(bf16_piece(__uint_as_float(x[2]), q), bf16_piece(__uint_as_float(x[3]), q));
+        }
+        *(u32x2 *)(gt + q * 4096 + off) = pl;
+      }
+    }
+    wave_sync();
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int chunk = 2 * ks + (lane >> 5);
+      bf16x8 wf[NP], gf[GP];
+#pragma unroll
+      for (int p = 0; p < NP; ++p) wf[p] = *(const bf16x8 *)(wt + p * 4096 + tile_off(lane & 31, chunk));
+#pragma unroll
+      for (int q = 0; q < GP; ++q) gf[q] = *(const bf16x8 *)(gt + q * 4096 + tile_off(lane & 31, chunk));
+      // smallest products first
+#pragma unroll
+      for (int sum = NP + GP - 2; sum >= 0; --sum)
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+          const int q = sum - p;
+          if (q >= 0 && q < GP && (NP == 1 || p + q < 3))
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[p], gf[q], acc, 0, 0, 0);
+        }
+    }
+  };
+#pragma unroll
+  for (int d = 0; d < PF; ++d) fetch(d, kt0 + d);
+  for (int kt = kt0; kt < kt1; kt += PF) {
+#pragma unroll
+    for (int d = 0; d < PF; ++d) {
+      if (kt + d < kt1) consume(d);
+      fetch(d, kt + d + PF);
+    }
+  }
+  const f32x4 sum = rlif_reduce(acc, red, w, lane);
+  if (upd) {
+    const float d4[4] = {ds.x, ds.y, ds.z, ds.w}, v4[4] = {v.x, v.y, v.z, v.w}, g4[4] = {g.x, g.y, g.z, g.w};
+    float gn[4];
+    uint32_t wd[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float q = d4[i] - theta * g4[i] + sum[i];
+      gn[i] = beta * g4[i] + surr<SURR>(slope, v4[i] - theta) * q;
+      wd[i] = HL ? pack_hl(gn[i]) : __float_as_uint(gn[i]);
+    }
+    *(float4 *)(Gn + o) = make_float4(gn[0], gn[1], gn[2], gn[3]);
+    if (dIn) *(uint4 *)(dIn + o) = make_uint4(wd[0], wd[1], wd[2], wd[3]);
+  }
+}
+
 // I, V [T][B][ld] fp32, S [T][B][ld] bytes; QRf[plane][to][from] bfloat16.
 static hipError_t rlif_forward(hipStream_t st, bool fp32, int T, int B, int N, int ld, const float *I, float *V,
                                uint8_t *S, const uint16_t *QRf, int ldqr, long long qr_plane, float beta,
@@ -265,20 +538,19 @@ static hipError_t rlif_forward(hipStream_t st, bool fp32, int T, int B, int N, i
   hipError_t e;
   if ((e = fill_zero(st, V, stride * 4)) != hipSuccess) return e;     // V_0 = 0
   if ((e = fill_zero(st, S, stride)) != hipSuccess) return e;         // hence S_0 = 0
-  GemmArgs a;
-  memset(&a, 0, sizeof a);
-  a.ldp = ld; a.kc = ld; a.p_bytes = (unsigned)stride;
-  a.Q = QRf; a.ldq = ldqr; a.q_plane_stride = qr_plane; a.q_bytes = (unsigned)((fp32 ? 3 : 1) * qr_plane * 2);
-  a.rows = B; a.cols = N; a.ldc = ld;
-  a.kc_per_split = (ld + 63) / 64 * 64;
-  a.beta = beta; a.theta = theta;
+  const dim3 grid(rlif_step_grid(N, B)), block(256);
   for (int t = 0; t + 1 < T; ++t) {
-    a.P = S + t * stride;
-    a.e_cur = I + t * stride; a.e_v = V + t * stride; a.e_s = S + t * stride;
-    a.e_out_f = V + (t + 1) * stride; a.e_out_s = S + (t + 1) * stride;
-    if (fp32) e = gemm_launch<P_U8, Q_BF16, EPI_RLIF_FWD, 1, 4, 1, 1, 3, 1>(a, 1, st);
-    else e = gemm_launch<P_U8, Q_BF16, EPI_RLIF_FWD, 1, 4, 1, 1, 1, 2>(a, 1, st);
-    if (e != hipSuccess) return e;
+    const uint8_t *s = S + t * stride;
+    const float *cur = I + t * stride, *v = V + t * stride;
+    float *vn = V + (t + 1) * stride;
+    uint8_t *sn = S + (t + 1) * stride;
+    if (fp32)
+      hipLaunchKernelGGL(rlif_step_forward_kernel<3>, grid, block, 0, st, s, cur, v, vn, sn, QRf, ldqr, qr_plane, B, N,
+                         ld, beta, theta);
+    else
+      hipLaunchKernelGGL(rlif_step_forward_kernel<1>, grid, block, 0, st, s, cur, v, vn, sn, QRf, ldqr, qr_plane, B, N,
+                         ld, beta, theta);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   return hipSuccess;
 }
@@ -307,24 +579,25 @@ static hipError_t rlif_reverse(hipStream_t st, bool fp32, int T, int B, int N, i
   hipError_t e;
   if ((e = fill_zero(st, g0, stride * 4)) != hipSuccess) return e;                              // g_T = 0
   if ((e = fill_zero(st, dI + (size_t)(T - 1) * stride, stride * 4)) != hipSuccess) return e;   // dI_{T-1} = 0
-  GemmArgs a;
-  memset(&a, 0, sizeof a);
-  a.ldp = ld; a.kc = ld; a.p_bytes = (unsigned)(stride * 4);
-  a.Q = QRb; a.ldq = ldqr; a.q_plane_stride = qr_plane; a.q_bytes = (unsigned)((fp32 ? 3 : 1) * qr_plane * 2);
-  a.rows = B; a.cols = N; a.ldc = ld;
-  a.kc_per_split = (ld + 63) / 64 * 64;
-  a.beta = beta; a.theta = theta; a.surrogate = surrogate; a.slope = slope;
-  a.e_di_hl = fp32 ? 0 : 1;
+  const dim3 grid(rlif_step_grid(N, B)), block(256);
   float *g[2] = {g0, g1};
   int cur = 0;
   for (int t = T - 1; t >= 0; --t) {
-    a.P = dI + (size_t)t * stride;                            // dI_t = g_{t+1}
-    a.e_cur = dS + t * stride; a.e_v = V + t * stride;
-    a.e_g = g[cur]; a.e_out_f = g[cur ^ 1];
-    a.e_out_di = t > 0 ? dI + (size_t)(t - 1) * stride : nullptr;
-    if (fp32) e = gemm_launch<P_F32S, Q_BF16, EPI_RLIF_REV, 1, 4, 1, 1, 3, 1>(a, 1, st);
-    else e = gemm_launch<P_HL, Q_BF16, EPI_RLIF_REV, 1, 4, 1, 1, 1, 2>(a, 1, st);
-    if (e != hipSuccess) return e;
+    const uint32_t *gw = dI + (size_t)t * stride;              // dI_t = g_{t+1}, in product form
+    const float *ds = dS + t * stride, *v = V + t * stride;
+    uint32_t *din = t > 0 ? dI + (size_t)(t - 1) * stride : nullptr;
+#define SNN_RSR(NP, SU)                                                                                          \
+  hipLaunchKernelGGL((rlif_step_reverse_kernel<NP, SU>), grid, block, 0, st, gw, g[cur], ds, v, g[cur ^ 1], din, QRb, \
+                     ldqr, qr_plane, B, N, ld, beta, theta, slope)
+    if (fp32) {
+      switch (surrogate) { case 0: SNN_RSR(3, 0); break; case 1: SNN_RSR(3, 1); break;
+                           case 2: SNN_RSR(3, 2); break; default: SNN_RSR(3, 3); break; }
+    } else {
+      switch (surrogate) { case 0: SNN_RSR(1, 0); break; case 1: SNN_RSR(1, 1); break;
+                           case 2: SNN_RSR(1, 2); break; default: SNN_RSR(1, 3); break; }
+    }
+#undef SNN_RSR
+    if ((e = hipGetLastError()) != hipSuccess) return e;
     cur ^= 1;
   }
   return hipSuccess;
