@@ -328,7 +328,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, const int block) {
   constexpr int NMAX = NPP > NQP ? NPP : NQP;
   constexpr int PT = BM * 128, QT = BN * 128;       // bytes of one plane of a tile
   constexpr int DR = D;
-  static_assert(NPP * PT + NQP * QT <= 65536, "one stage, several workgroups per compute unit");
+  static_assert(NPP * PT + NQP * QT <= 81920, "one stage, at least two workgroups per compute unit");
   __shared__ __attribute__((aligned(16))) char lds[NPP * PT + NQP * QT];
 
   // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Without
