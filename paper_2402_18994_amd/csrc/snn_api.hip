@@ -508,7 +508,7 @@ int launch_lif_forward(snn_ctx *c, int l) {
   hipError_t e;
   if (chains >= (1 << 19)) e = lif_fwd_launch<4, 8>(c, y);
   else if (chains >= (1 << 17)) e = lif_fwd_launch<2, 16>(c, y);
-  else e = lif_fwd_launch<1, 32>(c, y);
+  else e = lif_fwd_launch<1, 16>(c, y);
   HIPCHK(c, e);
   return SNN_OK;
 }
