@@ -107,6 +107,8 @@ def main():
                     help="measured HBM bytes per launch of the dominant kernel (from the rocprofv3 --pmc runs); "
                          "default: the committed measurement for the default workload and kernel")
     ap.add_argument("--breakdown", action="store_true", help="time every kernel class first (stderr)")
+    ap.add_argument("--packed", action="store_true",
+                    help="feed the raster packed along time (eight spikes per byte) through snn_forward_packed")
     ap.add_argument("--no-cpu", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -128,8 +130,15 @@ def main():
     y = torch.from_numpy(inp.labels).to(dev)
     lr = 1e-3
 
+    if args.packed:
+        import numpy as np
+        xp = torch.from_numpy(np.packbits(inp.X, axis=0)).to(dev)
+
     def step():
-        snn.forward(x, y, want_loss=False)
+        if args.packed:
+            snn.forward_packed(xp, y, want_loss=False)
+        else:
+            snn.forward(x, y, want_loss=False)
         snn.backward()
         snn.sgd_step(lr)
 
@@ -202,7 +211,8 @@ def main():
         "dtype": "bf16" if wl.precision == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {'-'.join(map(str, wl.sizes))} LIF, T={wl.T}, B={wl.B}, "
                                f"recurrent={list(map(int, wl.recurrent))}, {wl.surrogate}({wl.slope:g}), "
-                               f"bf16 products / fp32 state" if wl.precision == "bf16" else
+                               f"bf16 products / fp32 state" + (", input packed along time" if args.packed else "")
+                               if wl.precision == "bf16" else
                                f"{wl.name}: {'-'.join(map(str, wl.sizes))}, T={wl.T}, B={wl.B}, fp32",
                    "final_loss": loss},
         "roofline": {"bound": "hbm", "kernel": f"{kname}" + (f" layer {klayer}" if klayer else " (all layers)"),

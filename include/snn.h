@@ -159,6 +159,18 @@ int32_t snn_init(const snn_config *cfg, void *workspace_dev, size_t workspace_by
 int32_t snn_forward(snn_ctx *ctx, const uint8_t *x_dev, const int32_t *labels_dev,
                     float *loss_host);
 
+/* The same with the input raster packed along time, eight spikes per byte, as the paper
+ * keeps its datasets on the device (Section 2.1.4, numpy.packbits along the temporal axis)
+ * and decompresses them batch by batch inside the training step:
+ *   x_packed_dev  device, uint8 [ceil(T/8)][B][N_0]; bit 7-(t%8) of byte [t/8][b][n] is
+ *                 the spike at step t (the first step in the most significant bit; bits
+ *                 of steps >= T are ignored)
+ * The raster is unpacked into the workspace by a pre-pass; x_packed_dev may be released
+ * when the call returns only after the stream has passed that pre-pass (it is not read by
+ * snn_backward).  Everything else as for snn_forward. */
+int32_t snn_forward_packed(snn_ctx *ctx, const uint8_t *x_packed_dev, const int32_t *labels_dev,
+                           float *loss_host);
+
 /* Reverse sweep: readout gradient, per spiking layer the reverse-time scan with the fused
  * surrogate derivative, the weight-gradient products dW^l = S^{l-1}^T dI^l (dR^l =
  * S^l^T dI^l) and the input-gradient products dS^{l-1} = dI^l W^l^T.  Needs a preceding

@@ -63,6 +63,7 @@ def load_library():
     lib.snn_workspace_bytes.argtypes = [C.POINTER(snn_config), C.POINTER(sz)]
     lib.snn_init.argtypes = [C.POINTER(snn_config), vp, sz, C.POINTER(vp), C.POINTER(vp), vp, C.POINTER(vp)]
     lib.snn_forward.argtypes = [vp, vp, vp, C.POINTER(C.c_float)]
+    lib.snn_forward_packed.argtypes = [vp, vp, vp, C.POINTER(C.c_float)]
     lib.snn_backward.argtypes = [vp]
     lib.snn_sgd_step.argtypes = [vp, C.c_float]
     lib.snn_get_tensor.argtypes = [vp, i32, i32, vp, sz]
@@ -73,7 +74,7 @@ def load_library():
     lib.snn_destroy.argtypes = [vp]
     lib.snn_last_error.argtypes = [vp]
     lib.snn_last_error.restype = C.c_char_p
-    for name in ("snn_workspace_bytes", "snn_init", "snn_forward", "snn_backward", "snn_sgd_step",
+    for name in ("snn_workspace_bytes", "snn_init", "snn_forward", "snn_forward_packed", "snn_backward", "snn_sgd_step",
                  "snn_get_tensor", "snn_set_tensor", "snn_run_step", "snn_profile_select",
                  "snn_profile_read", "snn_destroy"):
         getattr(lib, name).restype = i32
@@ -193,6 +194,17 @@ class SNN:
         loss = C.c_float(0.0)
         rc = self.lib.snn_forward(self.ctx, self._x.data_ptr(), self._labels.data_ptr(),
                                   C.byref(loss) if want_loss else None)
+        self._chk(rc, self.ctx)
+        return loss.value if want_loss else None
+
+    def forward_packed(self, x_packed, labels, want_loss: bool = True):
+        """snn_forward_packed.  x_packed: uint8 [ceil(T/8),B,N0] = numpy.packbits(x, axis=0)."""
+        self._x, self._labels = self._dev_u8(x_packed), self._dev_i32(labels)
+        assert tuple(self._x.shape) == ((self.T + 7) // 8, self.B, self.sizes[0]), tuple(self._x.shape)
+        assert tuple(self._labels.shape) == (self.B,)
+        loss = C.c_float(0.0)
+        rc = self.lib.snn_forward_packed(self.ctx, self._x.data_ptr(), self._labels.data_ptr(),
+                                         C.byref(loss) if want_loss else None)
         self._chk(rc, self.ctx)
         return loss.value if want_loss else None
 

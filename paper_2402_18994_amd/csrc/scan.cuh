@@ -403,6 +403,25 @@ __global__ __launch_bounds__(256) void pad_rows_kernel(const uint8_t *__restrict
   dst[i] = k < n ? src[r * n + k] : 0;
 }
 
+// Input raster packed along time as numpy.packbits(x, axis=0) writes it (Section 2.1.4: eight
+// spikes per byte, first step in the most significant bit): src [ceil(T/8)][B][n] -> dst
+// [T][B][ld] bytes 0/1.  One thread per packed byte.
+__global__ __launch_bounds__(256) void unpack_time_bits_kernel(const uint8_t *__restrict__ src, uint8_t *__restrict__ dst,
+                                                               int T, int B, int n, int ld) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long per_step = (long long)B * n;
+  if (i >= (long long)((T + 7) / 8) * per_step) return;
+  const int tp = (int)(i / per_step);
+  const long long r = i - tp * per_step;
+  const int b = (int)(r / n), k = (int)(r - (long long)b * n);
+  const uint32_t bits = src[i];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int t = 8 * tp + j;
+    if (t < T) dst[((long long)t * B + b) * ld + k] = (uint8_t)((bits >> (7 - j)) & 1u);
+  }
+}
+
 __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *__restrict__ p, long long n_dwords) {
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n_dwords) p[i] = 0u;

@@ -71,8 +71,9 @@ struct snn_ctx {
   bool loss_ready = false;        // the mean of loss_b has been taken since the last readout
   int wall_khz = 100000;          // rate of the device's constant clock
   bool wg_tall = false;           // weight-gradient products use 256 x 128 tiles
-  const uint8_t *x_eff = nullptr;  // raster the products read: the caller's, or x_pad
-  uint8_t *x_pad = nullptr;        // zero-padded copy, only when N_0 is not a multiple of 4
+  const uint8_t *x_eff = nullptr;  // raster the products read: the caller's, or x_buf
+  uint8_t *x_buf = nullptr;        // [T*B][ldx]: zero-padded copy (N_0 not a multiple of 4) or unpacked input
+  bool x_padded = false;           // the caller's raster must be copied into x_buf
   int ldx = 0;                     // row length of x_eff
   const int32_t *labels_dev = nullptr;
   std::string err;
@@ -225,7 +226,8 @@ void carve(snn_ctx &c, Carver &cv) {
     }
   }
   c.ldx = c.sizes[0] % 4 == 0 ? c.sizes[0] : (int)rup(c.sizes[0], 8);
-  if (c.ldx != c.sizes[0]) c.x_pad = cv.take<uint8_t>(M * c.ldx);
+  c.x_padded = c.ldx != c.sizes[0];
+  c.x_buf = cv.take<uint8_t>(M * c.ldx);
   c.z = cv.take<float>((size_t)c.B * c.ldC);
   c.dz = cv.take<float>((size_t)c.B * c.ldC);
   c.tstar = cv.take<int>((size_t)c.B * c.ldC);
@@ -280,17 +282,28 @@ struct Bracket {
 };
 
 // ------------------------------------------------------------------ launches
+// Dynamic decompression of a raster packed along time (Section 2.1.4) into the workspace.
+int prepare_packed_input(snn_ctx *c, const uint8_t *xp) {
+  if (!xp) return fail(c, SNN_ERR_NULL, "packed input raster is NULL");
+  const long long n = (long long)((c->T + 7) / 8) * c->B * c->sizes[0];
+  hipLaunchKernelGGL(unpack_time_bits_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, xp, c->x_buf,
+                     c->T, c->B, c->sizes[0], c->ldx);
+  HIPCHK(c, hipGetLastError());
+  c->x_eff = c->x_buf;
+  return SNN_OK;
+}
+
 // The product kernels read spike rows with 4-byte loads.  A raster whose row length is not a
 // multiple of 4 is first copied into a zero-padded buffer of the workspace (one extra pass,
 // only for such sizes); otherwise it is read in place.
 int prepare_input(snn_ctx *c, const uint8_t *x) {
   if (!x) return fail(c, SNN_ERR_NULL, "input raster is NULL");
-  if (c->x_pad) {
+  if (c->x_padded) {
     const long long n = c->M * c->ldx;
-    hipLaunchKernelGGL(pad_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, x, c->x_pad,
+    hipLaunchKernelGGL(pad_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, x, c->x_buf,
                        c->M, c->sizes[0], c->ldx);
     HIPCHK(c, hipGetLastError());
-    c->x_eff = c->x_pad;
+    c->x_eff = c->x_buf;
   } else {
     if ((uintptr_t)x % 4 != 0) return fail(c, SNN_ERR_ARG, "x_dev must be 4-byte aligned");
     c->x_eff = x;
@@ -784,12 +797,8 @@ int32_t snn_init(const snn_config *cfg, void *workspace_dev, size_t workspace_by
   return SNN_OK;
 }
 
-int32_t snn_forward(snn_ctx *c, const uint8_t *x_dev, const int32_t *labels_dev, float *loss_host) {
-  if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
-  if (!x_dev || !labels_dev) return fail(c, SNN_ERR_NULL, "x_dev or labels_dev is NULL");
-  c->labels_dev = labels_dev;
+static int32_t forward_layers(snn_ctx *c, const int32_t *labels_dev, float *loss_host) {
   int rc;
-  if ((rc = prepare_input(c, x_dev))) return rc;
   for (int l = 0; l < c->L; ++l) {
     if ((rc = launch_current_gemm(c, l))) return rc;
     if (c->layers[l].spiking) {
@@ -805,6 +814,24 @@ int32_t snn_forward(snn_ctx *c, const uint8_t *x_dev, const int32_t *labels_dev,
     if ((rc = check_err_flag(c))) return rc;
   }
   return SNN_OK;
+}
+
+int32_t snn_forward(snn_ctx *c, const uint8_t *x_dev, const int32_t *labels_dev, float *loss_host) {
+  if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
+  if (!x_dev || !labels_dev) return fail(c, SNN_ERR_NULL, "x_dev or labels_dev is NULL");
+  c->labels_dev = labels_dev;
+  int rc;
+  if ((rc = prepare_input(c, x_dev))) return rc;
+  return forward_layers(c, labels_dev, loss_host);
+}
+
+int32_t snn_forward_packed(snn_ctx *c, const uint8_t *x_packed_dev, const int32_t *labels_dev, float *loss_host) {
+  if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
+  if (!x_packed_dev || !labels_dev) return fail(c, SNN_ERR_NULL, "x_packed_dev or labels_dev is NULL");
+  c->labels_dev = labels_dev;
+  int rc;
+  if ((rc = prepare_packed_input(c, x_packed_dev))) return rc;
+  return forward_layers(c, labels_dev, loss_host);
 }
 
 int32_t snn_backward(snn_ctx *c) {

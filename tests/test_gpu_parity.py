@@ -316,3 +316,32 @@ def test_deep_rec2048_full_size_sampled():
     (the bound stated for bf16-product modes is 2e-2)."""
     rep = sampled_parity(workloads.CONFIGS["deep_rec2048"], w_gain=3.0, n_samples=3, tol_state=5e-5, band=5e-5)
     assert rep["spike_rate"][0] > 0.005
+
+
+# ---------------------------------------------------------------- input packed along time
+@pytest.mark.parametrize("T", [37, 40])
+def test_packed_input_matches_plain_input(T):
+    """snn_forward_packed on numpy.packbits(X, axis=0) (the paper's storage format, Section
+    2.1.4) must give bit-identical tensors to snn_forward on X, for T a multiple of 8 and
+    not, and row lengths that are and are not multiples of 4; the plain path is the one
+    held against the oracle by the other tests (and once more here)."""
+    for sizes in ((45, 29, 13, 3), (64, 40, 10)):
+        wl = workloads.Workload(name="packed", index=16, T=T, B=7, sizes=sizes, recurrent=(False,) * (len(sizes) - 2),
+                                beta=(0.9,) * (len(sizes) - 1), theta=1.0, surrogate="superspike", slope=25.0,
+                                precision="bf16", rate_lo=0.1, rate_hi=0.3)
+        inp = workloads.generate(wl, w_gain=2.5)
+        net = net_of(wl)
+        snn = make(wl, inp)
+        loss = snn.forward(inp.X, inp.labels)
+        parity.compare_forward(net, inp, snn, loss, {})
+        names = [("spikes", 1), ("membrane", 1), ("readout_trace", 0), ("logits", 0), ("loss_per_sample", 0)]
+        plain = [snn.get_tensor(n, l) if l else snn.get_tensor(n) for n, l in names]
+        xp = np.packbits(inp.X, axis=0)
+        assert xp.shape == ((T + 7) // 8, wl.B, sizes[0])
+        loss_p = snn.forward_packed(xp, inp.labels)
+        assert loss_p == loss
+        for (n, l), ref in zip(names, plain):
+            got = snn.get_tensor(n, l) if l else snn.get_tensor(n)
+            assert np.array_equal(got, ref), n
+        snn.backward()
+        snn.destroy()
