@@ -129,6 +129,17 @@ def test_wide_layers_vector_scans(B):
     assert rep["spike_rate"][0] > 0.01 and rep["spike_rate"][1] > 0.01
 
 
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_more_than_64_classes(precision):
+    """A readout wider than one wavefront takes the separate scan / cross-entropy / reverse
+    kernels instead of the fused readout kernel."""
+    wl = workloads.Workload(name="manyclass", index=17, T=21, B=6, sizes=(40, 32, 70), recurrent=(False,),
+                            beta=(0.9, 0.8), theta=1.0, surrogate="superspike", slope=25.0,
+                            precision=precision, rate_lo=0.1, rate_hi=0.3)
+    rep = full_step_parity(wl, w_gain=2.5)
+    assert rep["spike_rate"][0] > 0.01
+
+
 # ---------------------------------------------------------------- headline configuration, full size
 @pytest.mark.parametrize("gain", [1.0, 3.0])
 def test_shd_ff128_full_size(gain):
