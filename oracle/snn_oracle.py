@@ -23,8 +23,11 @@ notes of this repository):
     beta; that is a later row of the scope table).
   * LI readout: y_t = beta_o * y_{t-1} + J_t, y_{-1} = 0, the updated y_t is
     what is emitted; no threshold, no reset.
-  * Loss: softmax cross-entropy on z[b,c] = max_t y_t[b,c], mean over the
+  * Loss "max": softmax cross-entropy on z[b,c] = max_t y_t[b,c], mean over the
     batch; the sub-gradient of the max goes to the FIRST maximising step.
+  * Loss "integral" (Section 2.1.3 names an integral cross-entropy for rate-coded
+    objectives and gives no formula): the same cross-entropy on the readout
+    trace summed over time, z[b,c] = sum_t y_t[b,c]; no label smoothing.
   * Arctan surrogate: (k/2) / (1 + (pi k x / 2)^2), the derivative of
     (1/pi) arctan(pi k x / 2) + 1/2.  The paper only names it.
   * Recurrent LIF: V_{t+1} = beta V_t + I_t + S_t R - theta S_t with S_t the
@@ -41,7 +44,8 @@ notes of this repository):
     than the 1e-4 bound.)
 
 parity unpinned (fixed by this file, nothing in the paper to check against):
-the arctan constant, the loss reduction (mean) and the readout equation.
+the arctan constant, the loss reduction (mean), the readout equation and the
+form of the integral loss.
 """
 from __future__ import annotations
 
@@ -60,6 +64,7 @@ class Net:
     surrogate: str                    # superspike | arctan | sigmoid | triangular
     slope: float
     gemm_round: str = "none"          # "none" | "bf16"
+    loss: str = "max"                 # "max" | "integral": how the readout trace is reduced over time
 
     @property
     def L(self) -> int:
@@ -189,8 +194,12 @@ def forward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
         tr.J[t] = jt
         tr.Y[t] = y
     tr.v_final = v
-    tr.z = tr.Y.max(axis=0)
-    tr.tstar = tr.Y.argmax(axis=0)                                # first maximiser
+    if net.loss == "integral":
+        tr.z = tr.Y.sum(axis=0)
+        tr.tstar = np.zeros((B, C), dtype=np.int64)               # not used
+    else:
+        tr.z = tr.Y.max(axis=0)
+        tr.tstar = tr.Y.argmax(axis=0)                            # first maximiser
     zmax = tr.z.max(axis=1, keepdims=True)
     lse = zmax[:, 0] + np.log(np.exp(tr.z - zmax).sum(axis=1))
     tr.loss_b = lse - tr.z[np.arange(B), labels]
@@ -251,8 +260,8 @@ def backward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
     g = [np.zeros((B, net.sizes[l + 1])) for l in range(L - 1)]
     tgrid = tr.tstar
     for t in range(T - 1, -1, -1):
-        # readout: y_t = beta y_{t-1} + J_t, z picks y at tstar
-        h = net.beta[L - 1] * h + gr.dz * (tgrid == t)
+        # readout: y_t = beta y_{t-1} + J_t; z picks y at tstar, or sums y over all steps
+        h = net.beta[L - 1] * h + (gr.dz if net.loss == "integral" else gr.dz * (tgrid == t))
         dJt = h
         gr.dJ[t] = dJt
         s_below = tr.S[L - 2][t] if L >= 2 else Xf[t]

@@ -208,6 +208,48 @@ def test_backward_is_exact_gradient_of_smoothed_network(surrogate, slope, recurr
             assert np.allclose(gr.dR[l], dR[l], rtol=2e-6, atol=2e-9)
 
 
+@pytest.mark.parametrize("recurrent", [(False, False), (True, True)])
+def test_integral_loss_backward_is_exact_gradient_of_smoothed_network(recurrent):
+    """Same finite-difference check with the readout trace summed over time."""
+    rng = np.random.default_rng(12)
+    net, X, W, R, lab = tiny_net(rng, recurrent=recurrent, surrogate="sigmoid", slope=3.0, loss="integral")
+    tr = O.forward(net, X, W, R, lab, smooth=True)
+    gr = O.backward(net, X, W, R, lab, tr)
+    dW, dR = fd_grads(net, X, W, R, lab)
+    for l in range(net.L):
+        assert np.abs(gr.dW[l]).max() > 1e-4
+        assert np.allclose(gr.dW[l], dW[l], rtol=2e-6, atol=2e-9), (l, np.abs(gr.dW[l] - dW[l]).max())
+    for l in range(net.L - 1):
+        if R[l] is not None:
+            assert np.allclose(gr.dR[l], dR[l], rtol=2e-6, atol=2e-9)
+
+
+def test_integral_loss_closed_forms():
+    """z is the sum over time of a first-order filter of J (library filter + library
+    log-softmax), and the readout's reverse recursion with dz fed in at every step has the
+    closed form dJ_t = dz (1 - beta^(T-t)) / (1 - beta)."""
+    from scipy.signal import lfilter
+    from scipy.special import log_softmax
+    rng = np.random.default_rng(22)
+    net, X, W, R, lab = tiny_net(rng, sizes=(10, 8, 4), recurrent=(False,), T=15, B=3, beta=(0.9, 0.8),
+                                 surrogate="superspike", slope=25.0, gain=3.0, loss="integral")
+    tr = O.forward(net, X, W, R, lab)
+    assert tr.S[0].sum() > 5
+    Y = lfilter([1.0], [1.0, -net.beta[1]], tr.J, axis=0)
+    assert np.allclose(tr.z, Y.sum(axis=0), atol=1e-12)
+    want = -log_softmax(Y.sum(axis=0), axis=1)[np.arange(3), lab].mean()
+    assert tr.loss == pytest.approx(want, rel=1e-12)
+    gr = O.backward(net, X, W, R, lab, tr)
+    T = X.shape[0]
+    t = np.arange(T)[:, None, None]
+    closed = gr.dz[None] * (1.0 - net.beta[1] ** (T - t)) / (1.0 - net.beta[1])
+    assert np.allclose(gr.dJ, closed, atol=1e-14)
+    # and it differs from the max-over-time loss on the same network
+    import dataclasses
+    tr_max = O.forward(dataclasses.replace(net, loss="max"), X, W, R, lab)
+    assert abs(tr_max.loss - tr.loss) > 1e-3
+
+
 def test_surrogates_are_derivatives_of_their_smooth_steps():
     x = np.linspace(-3, 3, 601) + 1e-4
     for kind, k in [("sigmoid", 3.0), ("superspike", 25.0), ("arctan", 2.0), ("triangular", 0.5)]:

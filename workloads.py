@@ -37,6 +37,7 @@ class Workload:
     rate_lo: float
     rate_hi: float
     rec_gain: float = 0.5           # recurrent weights ~ N(0, rec_gain / sqrt(N))
+    loss: str = "max"               # "max" (over time) | "integral" (sum over time) of the readout trace
 
     @property
     def n_layers(self) -> int:
