@@ -71,6 +71,16 @@ typedef enum {
  *              relative), so the result is the gradient of the rounded-weight network. */
 typedef enum { SNN_PREC_FP32 = 0, SNN_PREC_BF16_GEMM = 1 } snn_precision;
 
+/* How the readout trace y_t is reduced over time before the softmax cross-entropy (mean over
+ * the batch):
+ *   MAX_OVER_TIME  z = max_t y_t; the gradient goes to the first maximising step
+ *   INTEGRAL       z = sum_t y_t (the integral cross-entropy Section 2.1.3 names for
+ *                  rate-coded objectives; no label smoothing) */
+typedef enum {
+  SNN_LOSS_MAX_OVER_TIME = 0,
+  SNN_LOSS_INTEGRAL = 1
+} snn_loss;
+
 typedef struct {
   int32_t T;                 /* time steps                                              */
   int32_t B;                 /* batch                                                   */
@@ -82,6 +92,7 @@ typedef struct {
   int32_t surrogate;         /* snn_surrogate                                           */
   float slope;               /* k > 0                                                   */
   int32_t precision;         /* snn_precision                                           */
+  int32_t loss;              /* snn_loss                                                */
 } snn_config;
 
 /* Tensors that snn_get_tensor / snn_set_tensor move.  `layer` is 1-based as in the text:

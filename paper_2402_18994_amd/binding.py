@@ -16,6 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 SURROGATES = {"superspike": 0, "arctan": 1, "sigmoid": 2, "triangular": 3}
 PRECISIONS = {"fp32": 0, "bf16": 1}
+LOSSES = {"max": 0, "integral": 1}
 TENSORS = {"weight": 0, "rweight": 1, "grad_w": 2, "grad_r": 3, "current": 4, "membrane": 5,
            "spikes": 6, "d_spikes": 7, "d_current": 8, "readout_current": 9, "readout_trace": 10,
            "logits": 11, "argmax_t": 12, "d_logits": 13, "d_readout_current": 14, "loss": 15,
@@ -40,7 +41,7 @@ class snn_config(C.Structure):
     _fields_ = [("T", C.c_int32), ("B", C.c_int32), ("n_layers", C.c_int32),
                 ("sizes", C.POINTER(C.c_int32)), ("recurrent", C.POINTER(C.c_uint8)),
                 ("beta", C.POINTER(C.c_float)), ("threshold", C.c_float), ("surrogate", C.c_int32),
-                ("slope", C.c_float), ("precision", C.c_int32)]
+                ("slope", C.c_float), ("precision", C.c_int32), ("loss", C.c_int32)]
 
 
 def library_path() -> str:
@@ -85,7 +86,7 @@ def load_library():
 class _Cfg:
     """Keeps the arrays a snn_config points to alive."""
 
-    def __init__(self, T, B, sizes, recurrent, beta, theta, surrogate, slope, precision):
+    def __init__(self, T, B, sizes, recurrent, beta, theta, surrogate, slope, precision, loss="max"):
         L = len(sizes) - 1
         self.sizes = (C.c_int32 * (L + 1))(*[int(s) for s in sizes])
         rec = list(recurrent) if recurrent is not None else [0] * (L - 1)
@@ -94,12 +95,13 @@ class _Cfg:
         self.c = snn_config(int(T), int(B), L, self.sizes, self.rec, self.beta, float(theta),
                             SURROGATES[surrogate] if isinstance(surrogate, str) else int(surrogate),
                             float(slope),
-                            PRECISIONS[precision] if isinstance(precision, str) else int(precision))
+                            PRECISIONS[precision] if isinstance(precision, str) else int(precision),
+                            LOSSES[loss] if isinstance(loss, str) else int(loss))
 
 
-def workspace_bytes(T, B, sizes, recurrent, beta, theta, surrogate, slope, precision) -> int:
+def workspace_bytes(T, B, sizes, recurrent, beta, theta, surrogate, slope, precision, loss="max") -> int:
     lib = load_library()
-    cfg = _Cfg(T, B, sizes, recurrent, beta, theta, surrogate, slope, precision)
+    cfg = _Cfg(T, B, sizes, recurrent, beta, theta, surrogate, slope, precision, loss)
     n = C.c_size_t(0)
     rc = lib.snn_workspace_bytes(C.byref(cfg.c), C.byref(n))
     if rc:
@@ -112,7 +114,7 @@ class SNN:
 
     def __init__(self, T, B, sizes, recurrent, beta, theta, surrogate, slope, precision,
                  W: Sequence[np.ndarray], R: Optional[Sequence[Optional[np.ndarray]]] = None,
-                 device: str = "cuda:0"):
+                 device: str = "cuda:0", loss: str = "max"):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no HIP device: this library has no CPU path")
@@ -123,7 +125,7 @@ class SNN:
         self.L = len(self.sizes) - 1
         self.recurrent = [bool(r) for r in (recurrent if recurrent is not None else [0] * (self.L - 1))]
         self.precision = precision
-        self._cfg = _Cfg(T, B, sizes, self.recurrent, beta, theta, surrogate, slope, precision)
+        self._cfg = _Cfg(T, B, sizes, self.recurrent, beta, theta, surrogate, slope, precision, loss)
         n = C.c_size_t(0)
         self._chk(self.lib.snn_workspace_bytes(C.byref(self._cfg.c), C.byref(n)), None)
         self.workspace = torch.empty(n.value, dtype=torch.uint8, device=self.device)
@@ -261,4 +263,4 @@ class SNN:
 def from_workload(wl, inputs, device: str = "cuda:0") -> SNN:
     """Build an SNN for a workloads.Workload and the weights of a workloads.Inputs."""
     return SNN(wl.T, wl.B, wl.sizes, wl.recurrent, wl.beta, wl.theta, wl.surrogate, wl.slope,
-               wl.precision, inputs.W, inputs.R, device=device)
+               wl.precision, inputs.W, inputs.R, device=device, loss=getattr(wl, "loss", "max"))

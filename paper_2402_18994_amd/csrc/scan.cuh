@@ -146,21 +146,23 @@ __global__ __launch_bounds__(256) void lif_reverse_kernel(const float *__restric
 
 // ---------------------------------------------------------------- LI readout, max over time
 // y_t = beta y_{t-1} + J_t, y_{-1} = 0; z = max_t y_t; t* = first maximiser.
+// `integral`: z = sum_t y_t instead (t* = 0, not used).
 __global__ __launch_bounds__(256) void readout_forward_kernel(const float *__restrict__ J, float *__restrict__ Y,
                                                               float *__restrict__ z, int *__restrict__ tstar,
-                                                              int T, int stride, float beta) {
+                                                              int T, int stride, float beta, int integral) {
   const int p = blockIdx.x * blockDim.x + threadIdx.x;
   if (p >= stride) return;
-  float y = 0.f, best = -INFINITY;
+  float y = 0.f, best = -INFINITY, sum = 0.f;
   int tb = 0;
 #pragma unroll 8
   for (int t = 0; t < T; ++t) {
     y = beta * y + J[(size_t)t * stride + p];
     Y[(size_t)t * stride + p] = y;
+    sum += y;
     if (y > best) { best = y; tb = t; }
   }
-  z[p] = best;
-  tstar[p] = tb;
+  z[p] = integral ? sum : best;
+  tstar[p] = integral ? 0 : tb;
 }
 
 // Softmax cross-entropy, one wavefront per sample: lanes stride over the classes and the
@@ -222,7 +224,7 @@ __device__ __forceinline__ void wave_sync() {
 // Per-sample losses go to loss_b; their mean is taken by a later launch (the partial-sum
 // reduction of the backward pass, or loss_mean_kernel when the loss is asked for first), in
 // index order either way.
-template <int CW, bool HL>
+template <int CW, bool HL, bool INTEGRAL>
 __global__ __launch_bounds__(512) void readout_loss_kernel(const float *__restrict__ J, float *__restrict__ Y,
                                                            float *__restrict__ z, int *__restrict__ tstar,
                                                            const int *__restrict__ labels, float *__restrict__ loss_b,
@@ -265,7 +267,7 @@ __global__ __launch_bounds__(512) void readout_loss_kernel(const float *__restri
   for (int i = 0; i < 4; ++i) bseg *= bseg;
   static_assert(SEG == 16, "bseg is beta^16");
 
-  float y_in = 0.f, best = -INFINITY;                 // y_in: state entering the block
+  float y_in = 0.f, best = -INFINITY, ysum = 0.f;     // y_in: state entering the block
   int tb = 0;
   for (int sb0 = 0, par = 0; sb0 < T; sb0 += SB, par ^= 1) {
     const int t0 = sb0 + SEG * w;
@@ -298,7 +300,8 @@ __global__ __launch_bounds__(512) void readout_loss_kernel(const float *__restri
     for (int k = 0; k < SEG; ++k) {
       y = beta * y + j[k];
       out[k] = __float_as_uint(y);
-      if (t0 + k < T && y > best) { best = y; tb = t0 + k; }
+      if (INTEGRAL) { if (t0 + k < T) ysum += y; }
+      else if (t0 + k < T && y > best) { best = y; tb = t0 + k; }
     }
     wave_sync();
     if (staged) {
@@ -311,8 +314,9 @@ __global__ __launch_bounds__(512) void readout_loss_kernel(const float *__restri
       st_b128(rY, mem_off(t0 + 4 * g), (t0 + 4 * g) * row4, *(const u32x4 *)&stage[w][g][mslot]);
   }
 
-  // first maximiser over all segments
-  x_best[w][lane] = best;
+  // first maximiser over all segments (or, for the integral loss, the sum of the segments'
+  // sums, added in wavefront order)
+  x_best[w][lane] = INTEGRAL ? ysum : best;
   x_tb[w][lane] = tb;
   __syncthreads();
   best = x_best[0][lane];
@@ -321,7 +325,8 @@ __global__ __launch_bounds__(512) void readout_loss_kernel(const float *__restri
   for (int v = 1; v < NW; ++v) {
     const float bv = x_best[v][lane];
     const int tv = x_tb[v][lane];
-    if (bv > best || (bv == best && tv < tb)) { best = bv; tb = tv; }
+    if (INTEGRAL) best += bv;
+    else if (bv > best || (bv == best && tv < tb)) { best = bv; tb = tv; }
   }
   if (live && w == 0) { z[p] = best; tstar[p] = tb; }
 
@@ -348,12 +353,19 @@ __global__ __launch_bounds__(512) void readout_loss_kernel(const float *__restri
   const float l2b = log2f(beta);
   for (int sb0 = 0; sb0 < T; sb0 += SB) {
     const int t0 = sb0 + SEG * w;
-    const int n = tb - (t0 + SEG);                    // steps from the segment's upper edge up to t*
-    float h = n > 0 ? d * exp2f((float)n * l2b) : n == 0 ? d : 0.f;
+    float h;
+    if (INTEGRAL) {
+      // dz enters at every step: h_t = dz (1 - beta^(T-t)) / (1 - beta) at the segment's upper edge
+      const int n = T - (t0 + SEG);
+      h = n <= 0 ? 0.f : beta == 1.f ? d * (float)n : d * (1.f - exp2f((float)n * l2b)) / (1.f - beta);
+    } else {
+      const int n = tb - (t0 + SEG);                  // steps from the segment's upper edge up to t*
+      h = n > 0 ? d * exp2f((float)n * l2b) : n == 0 ? d : 0.f;
+    }
     uint32_t out[SEG];
 #pragma unroll
     for (int k = SEG - 1; k >= 0; --k) {
-      h = beta * h + (t0 + k == tb ? d : 0.f);
+      h = beta * h + ((INTEGRAL ? t0 + k < T : t0 + k == tb) ? d : 0.f);
       out[k] = HL ? pack_hl(h) : __float_as_uint(h);
     }
     wave_sync();
@@ -371,14 +383,15 @@ __global__ __launch_bounds__(512) void readout_loss_kernel(const float *__restri
 // Readout reverse: h_t = beta h_{t+1} + dz [t == t*]; dJ_t = h_t.
 template <bool HL>
 __global__ __launch_bounds__(256) void readout_reverse_kernel(const float *__restrict__ dz, const int *__restrict__ tstar,
-                                                              uint32_t *__restrict__ dJ, int T, int stride, float beta) {
+                                                              uint32_t *__restrict__ dJ, int T, int stride, float beta,
+                                                              int integral) {
   const int p = blockIdx.x * blockDim.x + threadIdx.x;
   if (p >= stride) return;
   const float d = dz[p];
   const int ts = tstar[p];
   float h = 0.f;
   for (int t = T - 1; t >= 0; --t) {
-    h = beta * h + (t == ts ? d : 0.f);
+    h = beta * h + (integral || t == ts ? d : 0.f);     // integral loss: every step feeds dz in
     dJ[(size_t)t * stride + p] = HL ? pack_hl(h) : __float_as_uint(h);
   }
 }

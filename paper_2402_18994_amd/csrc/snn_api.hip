@@ -71,6 +71,7 @@ struct snn_ctx {
   bool loss_ready = false;        // the mean of loss_b has been taken since the last readout
   int wall_khz = 100000;          // rate of the device's constant clock
   bool wg_tall = false;           // weight-gradient products use 256 x 128 tiles
+  bool integral = false;          // integral cross-entropy instead of max over time
   const uint8_t *x_eff = nullptr;  // raster the products read: the caller's, or x_buf
   uint8_t *x_buf = nullptr;        // [T*B][ldx]: zero-padded copy (N_0 not a multiple of 4) or unpacked input
   bool x_padded = false;           // the caller's raster must be copied into x_buf
@@ -117,6 +118,7 @@ int validate(const snn_config *cfg) {
   if (!(cfg->slope > 0.f)) return fail(nullptr, SNN_ERR_ARG, "slope must be positive");
   if (cfg->surrogate < 0 || cfg->surrogate > 3) return fail(nullptr, SNN_ERR_ARG, "unknown surrogate");
   if (cfg->precision < 0 || cfg->precision > 1) return fail(nullptr, SNN_ERR_ARG, "unknown precision");
+  if (cfg->loss < 0 || cfg->loss > 1) return fail(nullptr, SNN_ERR_ARG, "unknown loss");
   if ((long long)cfg->T * cfg->B > (1ll << 30)) return fail(nullptr, SNN_ERR_ARG, "T*B too large");
   for (int i = 0; i <= cfg->n_layers; ++i)      // byte offsets into one tensor are 31-bit
     if ((long long)cfg->T * cfg->B * (cfg->sizes[i] + 8) * 4 >= (1ll << 31))
@@ -242,6 +244,7 @@ void configure(snn_ctx &c, const snn_config *cfg) {
   c.sizes.assign(cfg->sizes, cfg->sizes + c.L + 1);
   c.theta = cfg->threshold; c.slope = cfg->slope;
   c.surrogate = cfg->surrogate; c.precision = cfg->precision;
+  c.integral = cfg->loss == SNN_LOSS_INTEGRAL;
   c.nplanes = c.precision == SNN_PREC_FP32 ? 3 : 1;
   c.hl = c.precision == SNN_PREC_BF16_GEMM;
   c.layers.assign(c.L, Layer());
@@ -575,8 +578,14 @@ int launch_readout_forward(snn_ctx *c, const int32_t *labels) {
     const int cw = c->ldC <= 16 ? 16 : c->ldC <= 32 ? 32 : 64;
     dim3 grid((c->B + 64 / cw - 1) / (64 / cw)), block(512);
 #define SNN_RDL(CW, HL)                                                                                          \
-  hipLaunchKernelGGL((readout_loss_kernel<CW, HL>), grid, block, 0, c->stream, y.I, y.V, c->z, c->tstar, labels, \
-                     c->loss_b, c->dz, c->err_flag, y.dI, c->T, c->B, c->C, c->ldC, y.beta)
+  do {                                                                                                           \
+    if (c->integral)                                                                                             \
+      hipLaunchKernelGGL((readout_loss_kernel<CW, HL, true>), grid, block, 0, c->stream, y.I, y.V, c->z, c->tstar, \
+                         labels, c->loss_b, c->dz, c->err_flag, y.dI, c->T, c->B, c->C, c->ldC, y.beta);         \
+    else                                                                                                         \
+      hipLaunchKernelGGL((readout_loss_kernel<CW, HL, false>), grid, block, 0, c->stream, y.I, y.V, c->z, c->tstar, \
+                         labels, c->loss_b, c->dz, c->err_flag, y.dI, c->T, c->B, c->C, c->ldC, y.beta);         \
+  } while (0)
     if (c->hl) { if (cw == 16) SNN_RDL(16, true); else if (cw == 32) SNN_RDL(32, true); else SNN_RDL(64, true); }
     else { if (cw == 16) SNN_RDL(16, false); else if (cw == 32) SNN_RDL(32, false); else SNN_RDL(64, false); }
 #undef SNN_RDL
@@ -589,7 +598,7 @@ int launch_readout_forward(snn_ctx *c, const int32_t *labels) {
   c->loss_ready = true;
   const int stride = c->B * c->ldC;
   hipLaunchKernelGGL(readout_forward_kernel, dim3((stride + 255) / 256), dim3(256), 0, c->stream, y.I, y.V, c->z,
-                     c->tstar, c->T, stride, y.beta);
+                     c->tstar, c->T, stride, y.beta, c->integral ? 1 : 0);
   HIPCHK(c, hipGetLastError());
   hipLaunchKernelGGL(cross_entropy_kernel, dim3((c->B + 3) / 4), dim3(256), 0, c->stream, c->z, labels, c->loss_b,
                      c->dz, c->B, c->C, c->ldC, c->err_flag);
@@ -605,10 +614,10 @@ int launch_readout_reverse(snn_ctx *c) {
   const int stride = c->B * c->ldC;
   if (c->hl)
     hipLaunchKernelGGL(readout_reverse_kernel<true>, dim3((stride + 255) / 256), dim3(256), 0, c->stream, c->dz,
-                       c->tstar, y.dI, c->T, stride, y.beta);
+                       c->tstar, y.dI, c->T, stride, y.beta, c->integral ? 1 : 0);
   else
     hipLaunchKernelGGL(readout_reverse_kernel<false>, dim3((stride + 255) / 256), dim3(256), 0, c->stream, c->dz,
-                       c->tstar, y.dI, c->T, stride, y.beta);
+                       c->tstar, y.dI, c->T, stride, y.beta, c->integral ? 1 : 0);
   HIPCHK(c, hipGetLastError());
   return SNN_OK;
 }

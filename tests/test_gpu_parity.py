@@ -356,3 +356,25 @@ def test_packed_input_matches_plain_input(T):
             assert np.array_equal(got, ref), n
         snn.backward()
         snn.destroy()
+
+
+# ---------------------------------------------------------------- integral cross-entropy
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_integral_loss_small_shapes(precision):
+    """Readout trace summed over time instead of its maximum: ragged shapes (one block of the
+    time-split readout kernel), a recurrent net, and a readout wider than 64 classes (separate
+    kernels)."""
+    for sizes, rec, T, B in (((45, 29, 13, 3), (False, False), 37, 7), ((50, 40, 5), (True,), 30, 10),
+                             ((40, 32, 70), (False,), 21, 6)):
+        wl = workloads.Workload(name="integral", index=18, T=T, B=B, sizes=sizes, recurrent=rec,
+                                beta=(0.9,) * (len(sizes) - 1), theta=1.0, surrogate="arctan", slope=2.0,
+                                precision=precision, rate_lo=0.1, rate_hi=0.3, rec_gain=1.0, loss="integral")
+        rep = full_step_parity(wl, w_gain=2.5)
+        assert rep["spike_rate"][0] > 0.01
+
+
+def test_integral_loss_headline_shape_long_horizon():
+    """Headline layer sizes with T = 300: three blocks of the time-split readout kernel, the
+    last one ragged."""
+    wl = workloads.CONFIGS["shd_ff128"].scaled(T=300, B=32, loss="integral")
+    full_step_parity(wl, w_gain=3.0, check_sgd=False)
