@@ -19,8 +19,12 @@ notes of this repository):
     updated (Eq. 1 uses V_t, Eq. 2 produces V_{t+1}); initial state zero.
   * Reset is theta * S_t (Eq. 2) and is NOT detached in the backward pass:
     the LIF listing uses the same traced `spikes` value for output and reset.
-  * beta is a fixed per-layer scalar here (the paper trains a per-neuron
-    beta; that is a later row of the scope table).
+  * beta: Net.beta holds one scalar per layer; `betas` (one array per layer,
+    one entry per neuron / class) overrides it.  The LIF listing holds beta as
+    a per-neuron parameter clipped to [0, 1] inside the forward function; here
+    the parameter itself is kept in [0, 1]: `sgd_step` clips after the update
+    (the forward values are the same; a parameter pushed outside the interval
+    comes back instead of staying there with zero gradient).
   * LI readout: y_t = beta_o * y_{t-1} + J_t, y_{-1} = 0, the updated y_t is
     what is emitted; no threshold, no reset.
   * Loss "max": softmax cross-entropy on z[b,c] = max_t y_t[b,c], mean over the
@@ -143,10 +147,20 @@ Forced = Dict[Tuple[int, int], List[Tuple[int, int, int]]]
 """(spiking layer index 0-based, t) -> list of (b, n, value): decisions to impose."""
 
 
+def _betas(net: Net, betas):
+    """Per-layer decay, per neuron: the given arrays, else the layer scalars."""
+    if betas is None:
+        return [np.full(net.sizes[l + 1], net.beta[l], dtype=np.float64) for l in range(net.L)]
+    out = [np.asarray(b, np.float64) for b in betas]
+    assert [len(b) for b in out] == [net.sizes[l + 1] for l in range(net.L)]
+    return out
+
+
 def forward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
             R: Sequence[Optional[np.ndarray]], labels: np.ndarray,
             forced: Optional[Forced] = None, smooth: bool = False,
-            batch_norm: Optional[int] = None) -> Trace:
+            batch_norm: Optional[int] = None,
+            betas: Optional[Sequence[np.ndarray]] = None) -> Trace:
     """Unroll the network over time (Eq. 1-2 per spiking layer, LI readout).
 
     X: [T,B,N_0] 0/1.  W[l]: [N_l, N_{l+1}].  R[l]: [N,N] or None.
@@ -158,6 +172,7 @@ def forward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
     Wq = [_q(net, np.asarray(w, np.float64)) for w in W]
     Rq = [None if r is None else _q(net, np.asarray(r, np.float64)) for r in R]
     th = net.theta
+    be = _betas(net, betas)
     tr = Trace()
     for l in range(L - 1):
         n = net.sizes[l + 1]
@@ -184,13 +199,13 @@ def forward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
             tr.I[l][t] = cur
             tr.V[l][t] = v[l]
             tr.S[l][t] = s
-            nxt = net.beta[l] * v[l] + cur - th * s               # Eq. 2
+            nxt = be[l] * v[l] + cur - th * s                     # Eq. 2
             if Rq[l] is not None:
                 nxt = nxt + s @ Rq[l]
             v[l] = nxt
             s_in = s
         jt = s_in @ Wq[L - 1]
-        y = net.beta[L - 1] * y + jt
+        y = be[L - 1] * y + jt
         tr.J[t] = jt
         tr.Y[t] = y
     tr.v_final = v
@@ -218,24 +233,29 @@ class Grads:
     dI: List[np.ndarray] = field(default_factory=list)   # dL/dI per spiking layer
     dW: List[np.ndarray] = field(default_factory=list)   # L entries
     dR: List[Optional[np.ndarray]] = field(default_factory=list)
+    dbeta: List[np.ndarray] = field(default_factory=list) # L entries, one value per neuron / class
 
 
 def backward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
              R: Sequence[Optional[np.ndarray]], labels: np.ndarray, tr: Trace,
-             batch_norm: Optional[int] = None) -> Grads:
+             batch_norm: Optional[int] = None,
+             betas: Optional[Sequence[np.ndarray]] = None) -> Grads:
     """Reverse sweep over the unrolled loop.
 
     g[l] is dL/dV_{t+1} of spiking layer l while step t is processed.  A
     potential V_t reaches the loss through beta*V_t into V_{t+1} and through
     the spike S_t, which feeds the next layer at step t, the reset
     -theta*S_t and (if recurrent) S_t R into V_{t+1}.  dS_t/dV_t is the
-    surrogate at V_t - theta.
+    surrogate at V_t - theta.  beta_n multiplies V_t[:, n] on the way to
+    V_{t+1}[:, n], so dL/dbeta_n = sum over t and b of g_{t+1} V_t (readout:
+    h_t y_{t-1}).
     """
     T, B, _ = X.shape
     L = net.L
     Wq = [_q(net, np.asarray(w, np.float64)) for w in W]
     Rq = [None if r is None else _q(net, np.asarray(r, np.float64)) for r in R]
     th = net.theta
+    be = _betas(net, betas)
     Bn = B if batch_norm is None else batch_norm
     C = net.sizes[L]
 
@@ -254,6 +274,7 @@ def backward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
         gr.dI.append(np.zeros((T, B, n)))
     gr.dW = [np.zeros_like(w, dtype=np.float64) for w in W]
     gr.dR = [None if r is None else np.zeros_like(r, dtype=np.float64) for r in R]
+    gr.dbeta = [np.zeros(net.sizes[l + 1]) for l in range(L)]
 
     Xf = X.astype(np.float64)
     h = np.zeros((B, C))                                   # dL/dy_{t+1} carried back
@@ -261,8 +282,10 @@ def backward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
     tgrid = tr.tstar
     for t in range(T - 1, -1, -1):
         # readout: y_t = beta y_{t-1} + J_t; z picks y at tstar, or sums y over all steps
-        h = net.beta[L - 1] * h + (gr.dz if net.loss == "integral" else gr.dz * (tgrid == t))
+        h = be[L - 1] * h + (gr.dz if net.loss == "integral" else gr.dz * (tgrid == t))
         dJt = h
+        if t >= 1:
+            gr.dbeta[L - 1] += (h * tr.Y[t - 1]).sum(axis=0)   # y_t = beta y_{t-1} + J_t, y_{-1} = 0
         gr.dJ[t] = dJt
         s_below = tr.S[L - 2][t] if L >= 2 else Xf[t]
         gr.dW[L - 1] += s_below.T @ dJt
@@ -279,7 +302,8 @@ def backward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
             if Rq[l] is not None:
                 q = q + dIt @ Rq[l].T
             sg = surrogate_grad(net.surrogate, net.slope, tr.V[l][t] - th)
-            g[l] = net.beta[l] * g[l] + sg * q
+            gr.dbeta[l] += (g[l] * tr.V[l][t]).sum(axis=0)      # V_{t+1} = beta V_t + ..
+            g[l] = be[l] * g[l] + sg * q
             if l >= 1:
                 d_s = dIt @ Wq[l].T
     return gr
@@ -292,6 +316,11 @@ def sgd_step(W: Sequence[np.ndarray], R: Sequence[Optional[np.ndarray]], gr: Gra
     Rn = [None if r is None else np.asarray(r, np.float64) - lr * d
           for r, d in zip(R, gr.dR)]
     return Wn, Rn
+
+
+def sgd_step_beta(betas: Sequence[np.ndarray], gr: Grads, lr: float):
+    """SGD on the decays, kept inside [0, 1] (the clip of the LIF listing)."""
+    return [np.clip(np.asarray(b, np.float64) - lr * d, 0.0, 1.0) for b, d in zip(betas, gr.dbeta)]
 
 
 def train_step(net: Net, X, W, R, labels, lr: float):

@@ -26,9 +26,15 @@ def _surr(kind, k, x):
 def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels):
     """Forward + backward.  X[t][b][i] in {0,1}; W[l][i][j]; R[l][i][j] or None.
 
+    beta[l] is a number or a list with one decay per neuron of layer l.
+
     Returns a dict with V, S (per spiking layer, [t][b][n]), Y [t][b][c], loss,
-    dW (per layer [i][j]) and dR.
+    dW (per layer [i][j]), dR and dbeta (per layer, per neuron).
     """
+
+    def bt(l, n):
+        return beta[l][n] if isinstance(beta[l], (list, tuple)) else beta[l]
+
     T = len(X)
     B = len(X[0])
     L = len(sizes) - 1
@@ -57,7 +63,7 @@ def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels):
                     if R[l] is not None:
                         for i in range(n_out):
                             rec += spikes[i] * R[l][i][n]
-                    new_v[n] = beta[l] * v[l][n] + cur + rec - theta * spikes[n]
+                    new_v[n] = bt(l, n) * v[l][n] + cur + rec - theta * spikes[n]
                     V[l][t][b][n] = v[l][n]
                     S[l][t][b][n] = spikes[n]
                 v[l] = new_v
@@ -66,7 +72,7 @@ def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels):
                 j = 0.0
                 for i in range(sizes[L - 1]):
                     j += below[i] * W[L - 1][i][c]
-                y[c] = beta[L - 1] * y[c] + j
+                y[c] = bt(L - 1, c) * y[c] + j
                 Y[t][b][c] = y[c]
 
     # ---------------- loss ----------------
@@ -86,12 +92,15 @@ def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels):
     dW = [[[0.0] * sizes[l + 1] for _ in range(sizes[l])] for l in range(L)]
     dR = [None if R[l] is None else [[0.0] * sizes[l + 1] for _ in range(sizes[l + 1])]
           for l in range(H)]
+    dbeta = [[0.0] * sizes[l + 1] for l in range(L)]
     for b in range(B):
         hy = [0.0] * C
         g = [[0.0] * sizes[l + 1] for l in range(H)]          # dL/dV_{t+1}
         for t in range(T - 1, -1, -1):
             for c in range(C):
-                hy[c] = beta[L - 1] * hy[c] + (dz[b][c] if tstar[b][c] == t else 0.0)
+                hy[c] = bt(L - 1, c) * hy[c] + (dz[b][c] if tstar[b][c] == t else 0.0)
+                if t >= 1:
+                    dbeta[L - 1][c] += hy[c] * Y[t - 1][b][c]
             below = S[H - 1][t][b] if H >= 1 else [float(x) for x in X[t][b]]
             for i in range(sizes[L - 1]):
                 for c in range(C):
@@ -113,8 +122,9 @@ def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels):
                             # and the recurrent weight gradient, entry (n -> m_)
                         for m_ in range(n_out):
                             dR[l][n][m_] += S[l][t][b][n] * d_i[m_]
-                    new_g[n] = beta[l] * g[l][n] + _surr(surrogate, slope, V[l][t][b][n] - theta) * q
+                    dbeta[l][n] += g[l][n] * V[l][t][b][n]
+                    new_g[n] = bt(l, n) * g[l][n] + _surr(surrogate, slope, V[l][t][b][n] - theta) * q
                 if l >= 1:
                     d_s = [sum(d_i[n] * W[l][i][n] for n in range(n_out)) for i in range(sizes[l])]
                 g[l] = new_g
-    return dict(V=V, S=S, Y=Y, z=z, tstar=tstar, loss=loss, dz=dz, dW=dW, dR=dR)
+    return dict(V=V, S=S, Y=Y, z=z, tstar=tstar, loss=loss, dz=dz, dW=dW, dR=dR, dbeta=dbeta)

@@ -312,6 +312,85 @@ def test_vectorised_oracle_equals_scalar_brute_force(recurrent, surrogate, slope
             assert np.allclose(gr.dR[l], np.array(ref["dR"][l]), atol=1e-12)
 
 
+# ---------------------------------------------------------------- per-neuron decay
+def _random_betas(rng, net):
+    return [rng.uniform(0.6, 0.98, size=net.sizes[l + 1]) for l in range(net.L)]
+
+
+@pytest.mark.parametrize("recurrent", [(False, False), (True, True)])
+def test_per_neuron_beta_equals_scalar_brute_force(recurrent):
+    """Per-neuron decays (the LIF listing's beta parameter) and their gradient, against the
+    one-number-at-a-time version."""
+    rng = np.random.default_rng(41)
+    net, X, W, R, lab = tiny_net(rng, sizes=(6, 5, 4, 3), recurrent=recurrent, T=9, B=3,
+                                 surrogate="superspike", slope=25.0, gain=2.5)
+    betas = _random_betas(rng, net)
+    tr = O.forward(net, X, W, R, lab, betas=betas)
+    gr = O.backward(net, X, W, R, lab, tr, betas=betas)
+    assert tr.S[0].sum() > 0 and tr.S[1].sum() > 0
+    ref = snn_scalar.run(net.sizes, net.recurrent, [b.tolist() for b in betas], net.theta, "superspike", 25.0,
+                         X.tolist(), [w.tolist() for w in W],
+                         [None if r is None else r.tolist() for r in R], lab.tolist())
+    for l in range(2):
+        assert np.allclose(tr.V[l], np.array(ref["V"][l]), atol=1e-12)
+        assert np.array_equal(tr.S[l], np.array(ref["S"][l]))
+    assert np.allclose(tr.Y, np.array(ref["Y"]), atol=1e-12)
+    assert tr.loss == pytest.approx(ref["loss"], abs=1e-12)
+    for l in range(3):
+        assert np.allclose(gr.dW[l], np.array(ref["dW"][l]), atol=1e-12)
+        assert np.allclose(gr.dbeta[l], np.array(ref["dbeta"][l]), atol=1e-12)
+        assert np.abs(gr.dbeta[l]).max() > 0
+    # scalars are the special case of equal entries
+    tr0 = O.forward(net, X, W, R, lab)
+    tr1 = O.forward(net, X, W, R, lab, betas=[np.full(net.sizes[l + 1], net.beta[l]) for l in range(net.L)])
+    assert np.array_equal(tr0.Y, tr1.Y)
+
+
+@pytest.mark.parametrize("loss", ["max", "integral"])
+@pytest.mark.parametrize("recurrent", [(False, False), (True, True)])
+def test_dbeta_is_exact_gradient_of_smoothed_network(recurrent, loss):
+    """Central differences on every decay of the smoothed network (reset, recurrence and
+    readout included)."""
+    rng = np.random.default_rng(42)
+    net, X, W, R, lab = tiny_net(rng, recurrent=recurrent, surrogate="sigmoid", slope=3.0, loss=loss)
+    betas = _random_betas(rng, net)
+    tr = O.forward(net, X, W, R, lab, smooth=True, betas=betas)
+    gr = O.backward(net, X, W, R, lab, tr, betas=betas)
+    h = 1e-6
+    for l in range(net.L):
+        fd = np.zeros_like(betas[l])
+        for n in range(len(betas[l])):
+            bp = [b.copy() for b in betas]; bp[l][n] += h
+            bm = [b.copy() for b in betas]; bm[l][n] -= h
+            fd[n] = (O.forward(net, X, W, R, lab, smooth=True, betas=bp).loss
+                     - O.forward(net, X, W, R, lab, smooth=True, betas=bm).loss) / (2 * h)
+        assert np.abs(fd).max() > 1e-5
+        assert np.allclose(gr.dbeta[l], fd, rtol=2e-6, atol=2e-9), (l, np.abs(gr.dbeta[l] - fd).max())
+
+
+def test_readout_dbeta_of_the_real_spiking_network_and_clip():
+    """Spikes do not depend on the readout decay, so central differences on it hold for the
+    true (Heaviside) network; the update keeps decays inside [0, 1]."""
+    rng = np.random.default_rng(43)
+    net, X, W, R, lab = tiny_net(rng, sizes=(10, 8, 4), recurrent=(True,), T=15, B=3,
+                                 beta=(0.9, 0.8), surrogate="superspike", slope=25.0, gain=3.0)
+    betas = _random_betas(rng, net)
+    tr = O.forward(net, X, W, R, lab, betas=betas)
+    gr = O.backward(net, X, W, R, lab, tr, betas=betas)
+    h = 1e-6
+    for c in range(4):
+        bp = [b.copy() for b in betas]; bp[1][c] += h
+        bm = [b.copy() for b in betas]; bm[1][c] -= h
+        fd = (O.forward(net, X, W, R, lab, betas=bp).loss - O.forward(net, X, W, R, lab, betas=bm).loss) / (2 * h)
+        # the first maximiser does not move for a perturbation this small
+        assert gr.dbeta[1][c] == pytest.approx(fd, rel=1e-5, abs=1e-9)
+    new = O.sgd_step_beta(betas, gr, lr=1e6)
+    assert all(np.all((b >= 0.0) & (b <= 1.0)) for b in new)
+    assert any(np.any(b == 0.0) or np.any(b == 1.0) for b in new)
+    same = O.sgd_step_beta(betas, gr, lr=1e-3)
+    assert np.allclose(same[0], betas[0] - 1e-3 * gr.dbeta[0], atol=0, rtol=0)
+
+
 # ---------------------------------------------------------------- invariants
 def test_batch_permutation_duplication_and_time_shift():
     rng = np.random.default_rng(41)
