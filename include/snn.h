@@ -93,6 +93,11 @@ typedef struct {
   float slope;               /* k > 0                                                   */
   int32_t precision;         /* snn_precision                                           */
   int32_t loss;              /* snn_loss                                                */
+  int32_t learn_beta;        /* 0: decays fixed.  1: the per-neuron decays are trained as in
+                                the LIF listing (Section 2.1.2): snn_backward also yields
+                                dL/dbeta, snn_sgd_step also does beta <- clip(beta - lr
+                                dbeta, 0, 1).  Either way every neuron (and readout class)
+                                has its own decay, initialised from `beta` and settable   */
 } snn_config;
 
 /* Tensors that snn_get_tensor / snn_set_tensor move.  `layer` is 1-based as in the text:
@@ -115,7 +120,9 @@ typedef enum {
   SNN_T_D_LOGITS = 13,   /* dL/dz [B][C] (settable)                                        */
   SNN_T_D_READOUT_CURRENT = 14, /* dL/dJ [T][B][C] (settable)                                */
   SNN_T_LOSS = 15,       /* 1 float                                                        */
-  SNN_T_LOSS_PER_SAMPLE = 16 /* [B]                                                        */
+  SNN_T_LOSS_PER_SAMPLE = 16, /* [B]                                                       */
+  SNN_T_BETA = 17,       /* [N_l] decays of layer l (1..L, L = readout), in [0,1] (settable)   */
+  SNN_T_GRAD_BETA = 18   /* [N_l] dL/dbeta of layer l; needs learn_beta (else SNN_ERR_STATE)   */
 } snn_tensor;
 
 /* Single steps of the path, for kernel-level tests on imposed inputs (snn_run_step). */

@@ -20,7 +20,7 @@ LOSSES = {"max": 0, "integral": 1}
 TENSORS = {"weight": 0, "rweight": 1, "grad_w": 2, "grad_r": 3, "current": 4, "membrane": 5,
            "spikes": 6, "d_spikes": 7, "d_current": 8, "readout_current": 9, "readout_trace": 10,
            "logits": 11, "argmax_t": 12, "d_logits": 13, "d_readout_current": 14, "loss": 15,
-           "loss_per_sample": 16}
+           "loss_per_sample": 16, "beta": 17, "grad_beta": 18}
 STEPS = {"current_gemm": 0, "lif_forward": 1, "readout_forward": 2, "readout_reverse": 3,
          "lif_reverse": 4, "weight_grad": 5, "input_grad": 6}
 KERNELS = {"none": -1, "current_gemm": 0, "lif_forward": 1, "rlif_forward": 2, "readout_forward": 3,
@@ -41,7 +41,7 @@ class snn_config(C.Structure):
     _fields_ = [("T", C.c_int32), ("B", C.c_int32), ("n_layers", C.c_int32),
                 ("sizes", C.POINTER(C.c_int32)), ("recurrent", C.POINTER(C.c_uint8)),
                 ("beta", C.POINTER(C.c_float)), ("threshold", C.c_float), ("surrogate", C.c_int32),
-                ("slope", C.c_float), ("precision", C.c_int32), ("loss", C.c_int32)]
+                ("slope", C.c_float), ("precision", C.c_int32), ("loss", C.c_int32), ("learn_beta", C.c_int32)]
 
 
 def library_path() -> str:
@@ -86,7 +86,8 @@ def load_library():
 class _Cfg:
     """Keeps the arrays a snn_config points to alive."""
 
-    def __init__(self, T, B, sizes, recurrent, beta, theta, surrogate, slope, precision, loss="max"):
+    def __init__(self, T, B, sizes, recurrent, beta, theta, surrogate, slope, precision, loss="max",
+                 learn_beta=False):
         L = len(sizes) - 1
         self.sizes = (C.c_int32 * (L + 1))(*[int(s) for s in sizes])
         rec = list(recurrent) if recurrent is not None else [0] * (L - 1)
@@ -96,7 +97,7 @@ class _Cfg:
                             SURROGATES[surrogate] if isinstance(surrogate, str) else int(surrogate),
                             float(slope),
                             PRECISIONS[precision] if isinstance(precision, str) else int(precision),
-                            LOSSES[loss] if isinstance(loss, str) else int(loss))
+                            LOSSES[loss] if isinstance(loss, str) else int(loss), int(bool(learn_beta)))
 
 
 def workspace_bytes(T, B, sizes, recurrent, beta, theta, surrogate, slope, precision, loss="max") -> int:
@@ -114,7 +115,7 @@ class SNN:
 
     def __init__(self, T, B, sizes, recurrent, beta, theta, surrogate, slope, precision,
                  W: Sequence[np.ndarray], R: Optional[Sequence[Optional[np.ndarray]]] = None,
-                 device: str = "cuda:0", loss: str = "max"):
+                 device: str = "cuda:0", loss: str = "max", learn_beta: bool = False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no HIP device: this library has no CPU path")
@@ -125,7 +126,7 @@ class SNN:
         self.L = len(self.sizes) - 1
         self.recurrent = [bool(r) for r in (recurrent if recurrent is not None else [0] * (self.L - 1))]
         self.precision = precision
-        self._cfg = _Cfg(T, B, sizes, self.recurrent, beta, theta, surrogate, slope, precision, loss)
+        self._cfg = _Cfg(T, B, sizes, self.recurrent, beta, theta, surrogate, slope, precision, loss, learn_beta)
         n = C.c_size_t(0)
         self._chk(self.lib.snn_workspace_bytes(C.byref(self._cfg.c), C.byref(n)), None)
         self.workspace = torch.empty(n.value, dtype=torch.uint8, device=self.device)
@@ -181,6 +182,8 @@ class SNN:
             return (B, s[L]), np.float32
         if name == "argmax_t":
             return (B, s[L]), np.int32
+        if name in ("beta", "grad_beta"):
+            return (s[layer],), np.float32
         if name == "loss":
             return (1,), np.float32
         if name == "loss_per_sample":
@@ -260,7 +263,8 @@ class SNN:
             pass
 
 
-def from_workload(wl, inputs, device: str = "cuda:0") -> SNN:
+def from_workload(wl, inputs, device: str = "cuda:0", learn_beta: bool = False) -> SNN:
     """Build an SNN for a workloads.Workload and the weights of a workloads.Inputs."""
     return SNN(wl.T, wl.B, wl.sizes, wl.recurrent, wl.beta, wl.theta, wl.surrogate, wl.slope,
-               wl.precision, inputs.W, inputs.R, device=device, loss=getattr(wl, "loss", "max"))
+               wl.precision, inputs.W, inputs.R, device=device, loss=getattr(wl, "loss", "max"),
+               learn_beta=learn_beta)

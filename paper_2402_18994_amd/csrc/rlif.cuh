@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__
                                                                  uint8_t *__restrict__ S,
                                                                  const uint16_t *__restrict__ QRf, int ldqr,
                                                                  long long qr_plane, int T, int B, int N, int ld,
-                                                                 float beta, float theta) {
+                                                                 const float *__restrict__ beta_v, float theta) {
   constexpr int PF = 4;
   __shared__ __align__(16) char xs[2][32 * RL_PITCH];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -69,9 +69,13 @@ __global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__
     vo1[g] = ok ? b * ld + n : OOB;
     xo[g] = (lane & 31) * RL_PITCH + n * 2;
   }
-  float v[16];
+  float v[16], beta[16];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) v[i] = 0.f;      // V_0 = 0
+  for (int i = 0; i < 16; ++i) {
+    v[i] = 0.f;                                  // V_0 = 0
+    const int n = 32 * w + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+    beta[i] = n < ld ? beta_v[n] : 0.f;          // one decay per neuron
+  }
   u32x4 cur[PF][4];
 #pragma unroll
   for (int d = 0; d < PF; ++d)
@@ -110,7 +114,7 @@ __global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__
     // accumulator register r: neuron 32w + 8*(r/4) + 4*(lane/32) + r%4, i.e. group r/4, element r%4
 #pragma unroll
     for (int i = 0; i < 16; ++i)
-      v[i] = beta * v[i] + __uint_as_float(in[i >> 2][i & 3]) + acc[i] - (sp[i] ? theta : 0.f);
+      v[i] = beta[i] * v[i] + __uint_as_float(in[i >> 2][i & 3]) + acc[i] - (sp[i] ? theta : 0.f);
 #pragma unroll
     for (int g = 0; g < 4; ++g) in[g] = ld_b128(rI, vo4[g], min(t + PF, T - 1) * row4);
   };
@@ -134,7 +138,8 @@ __global__ __launch_bounds__(256) void rlif_reverse_fused_kernel(const float *__
                                                                  uint32_t *__restrict__ dI,
                                                                  const uint16_t *__restrict__ QRb, int ldqr,
                                                                  long long qr_plane, int T, int B, int N, int ld,
-                                                                 float beta, float theta, float slope) {
+                                                                 const float *__restrict__ beta_v, float theta, float slope,
+                                                                 float *__restrict__ db_part) {
   constexpr int PF = 2;
   constexpr int GP = NP == 1 ? 2 : 3;           // planes of g
   constexpr bool HL = NP == 1;                  // dI is stored in hi/lo form with bfloat16 weights
@@ -161,9 +166,14 @@ __global__ __launch_bounds__(256) void rlif_reverse_fused_kernel(const float *__
     vo4[g] = ok ? (b * ld + n) * 4 : OOB;
     xo[g] = (lane & 31) * RL_PITCH + n * 2;
   }
-  float gv[16];
+  float gv[16], beta[16], db[16];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) gv[i] = 0.f;     // g_T = 0
+  for (int i = 0; i < 16; ++i) {
+    gv[i] = 0.f;                                 // g_T = 0
+    db[i] = 0.f;                                 // sum over t of g_{t+1} V_t
+    const int n = 32 * w + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+    beta[i] = n < ld ? beta_v[n] : 0.f;
+  }
   u32x4 cds[PF][4], cv[PF][4];
 #pragma unroll
   for (int d = 0; d < PF; ++d)
@@ -228,7 +238,9 @@ __global__ __launch_bounds__(256) void rlif_reverse_fused_kernel(const float *__
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const float q = __uint_as_float(ds[i >> 2][i & 3]) - theta * gv[i] + acc[i];
-      gv[i] = beta * gv[i] + surr<SURR>(slope, __uint_as_float(vv[i >> 2][i & 3]) - theta) * q;
+      const float vt = __uint_as_float(vv[i >> 2][i & 3]);
+      db[i] += gv[i] * vt;
+      gv[i] = beta[i] * gv[i] + surr<SURR>(slope, vt - theta) * q;
     }
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -245,6 +257,13 @@ __global__ __launch_bounds__(256) void rlif_reverse_fused_kernel(const float *__
 #pragma unroll
   for (int d = 0; d < PF; ++d)
     if (t - d >= 0) step(cds[d], cv[d], t - d);
+  if (db_part) {                                 // per sample; summed over the batch by the reduction launch
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int n = 32 * w + 8 * g + 4 * (lane >> 5);
+      if (b < B && n < ld) *(float4 *)(db_part + (size_t)b * ld + n) = make_float4(db[4 * g], db[4 * g + 1], db[4 * g + 2], db[4 * g + 3]);
+    }
+  }
 }
 
 // ---------------------------------------------------------------- wide layers: one launch per step
@@ -317,8 +336,8 @@ __global__ __launch_bounds__(256) void rlif_step_forward_kernel(const uint8_t *_
                                                                 const float *__restrict__ V, float *__restrict__ Vn,
                                                                 uint8_t *__restrict__ Sn,
                                                                 const uint16_t *__restrict__ QRf, int ldqr,
-                                                                long long qr_plane, int B, int N, int ld, float beta,
-                                                                float theta) {
+                                                                long long qr_plane, int B, int N, int ld,
+                                                                const float *__restrict__ beta_v, float theta) {
   constexpr int PF = NP == 1 ? 4 : 2;                    // tiles in flight per wavefront
   __shared__ float red[4][16][64];
   __shared__ __align__(16) char tiles[4][(NP + 1) * 4096];
@@ -339,6 +358,7 @@ __global__ __launch_bounds__(256) void rlif_step_forward_kernel(const uint8_t *_
   const size_t o = upd ? (size_t)b * ld + n : 0;
   const float4 cur = *(const float4 *)(I + o), v = *(const float4 *)(V + o);
   const uint32_t sp = *(const uint32_t *)(S + o);
+  const float4 be = *(const float4 *)(beta_v + (upd ? n : 0));
 
   // spike tile: 32 samples x 64 bytes, two 16-byte loads (lane: sample lane/4 + 16j, chunk lane%4)
   RlifWeightTile<NP> wr[PF];
@@ -395,13 +415,13 @@ __global__ __launch_bounds__(256) void rlif_step_forward_kernel(const uint8_t *_
   }
   const f32x4 sum = rlif_reduce(acc, red, w, lane);
   if (upd) {
-    const float c4[4] = {cur.x, cur.y, cur.z, cur.w}, v4[4] = {v.x, v.y, v.z, v.w};
+    const float c4[4] = {cur.x, cur.y, cur.z, cur.w}, v4[4] = {v.x, v.y, v.z, v.w}, b4[4] = {be.x, be.y, be.z, be.w};
     float vn[4];
     uint32_t out = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const float s = (float)((sp >> (8 * i)) & 1u);
-      vn[i] = beta * v4[i] + c4[i] + sum[i] - theta * s;
+      vn[i] = b4[i] * v4[i] + c4[i] + sum[i] - theta * s;
       out |= (vn[i] > theta ? 1u : 0u) << (8 * i);
     }
     *(float4 *)(Vn + o) = make_float4(vn[0], vn[1], vn[2], vn[3]);
@@ -416,8 +436,9 @@ __global__ __launch_bounds__(256) void rlif_step_reverse_kernel(const uint32_t *
                                                                 const float *__restrict__ dS, const float *__restrict__ V,
                                                                 float *__restrict__ Gn, uint32_t *__restrict__ dIn,
                                                                 const uint16_t *__restrict__ QRb, int ldqr,
-                                                                long long qr_plane, int B, int N, int ld, float beta,
-                                                                float theta, float slope) {
+                                                                long long qr_plane, int B, int N, int ld,
+                                                                const float *__restrict__ beta_v, float theta, float slope,
+                                                                float *__restrict__ db_part) {
   constexpr int GP = NP == 1 ? 2 : 3;
   constexpr bool HL = NP == 1;
   constexpr int PF = 2;
@@ -438,6 +459,7 @@ __global__ __launch_bounds__(256) void rlif_step_reverse_kernel(const uint32_t *
   const bool upd = b < B && n < ld;
   const size_t o = upd ? (size_t)b * ld + n : 0;
   const float4 ds = *(const float4 *)(dS + o), v = *(const float4 *)(V + o), g = *(const float4 *)(G + o);
+  const float4 be = *(const float4 *)(beta_v + (upd ? n : 0));
 
   // tile of g words: 32 samples x 64 words, eight 16-byte loads (lane: sample lane/16 + 4j, words 4(lane%16)..)
   RlifWeightTile<NP> wr[PF];
@@ -507,13 +529,19 @@ __global__ __launch_bounds__(256) void rlif_step_reverse_kernel(const uint32_t *
   const f32x4 sum = rlif_reduce(acc, red, w, lane);
   if (upd) {
     const float d4[4] = {ds.x, ds.y, ds.z, ds.w}, v4[4] = {v.x, v.y, v.z, v.w}, g4[4] = {g.x, g.y, g.z, g.w};
+    const float b4[4] = {be.x, be.y, be.z, be.w};
     float gn[4];
     uint32_t wd[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const float q = d4[i] - theta * g4[i] + sum[i];
-      gn[i] = beta * g4[i] + surr<SURR>(slope, v4[i] - theta) * q;
+      gn[i] = b4[i] * g4[i] + surr<SURR>(slope, v4[i] - theta) * q;
       wd[i] = HL ? pack_hl(gn[i]) : __float_as_uint(gn[i]);
+    }
+    if (db_part) {                                     // dL/dbeta per sample, accumulated over the steps
+      float4 acc4 = *(float4 *)(db_part + o);
+      acc4.x += g4[0] * v4[0]; acc4.y += g4[1] * v4[1]; acc4.z += g4[2] * v4[2]; acc4.w += g4[3] * v4[3];
+      *(float4 *)(db_part + o) = acc4;
     }
     *(float4 *)(Gn + o) = make_float4(gn[0], gn[1], gn[2], gn[3]);
     if (dIn) *(uint4 *)(dIn + o) = make_uint4(wd[0], wd[1], wd[2], wd[3]);
@@ -522,7 +550,7 @@ __global__ __launch_bounds__(256) void rlif_step_reverse_kernel(const uint32_t *
 
 // I, V [T][B][ld] fp32, S [T][B][ld] bytes; QRf[plane][to][from] bfloat16.
 static hipError_t rlif_forward(hipStream_t st, bool fp32, int T, int B, int N, int ld, const float *I, float *V,
-                               uint8_t *S, const uint16_t *QRf, int ldqr, long long qr_plane, float beta,
+                               uint8_t *S, const uint16_t *QRf, int ldqr, long long qr_plane, const float *beta,
                                float theta) {
   if (ld <= 128) {                              // the whole time loop in one launch
     dim3 grid((B + 31) / 32), block(256);
@@ -559,12 +587,12 @@ static hipError_t rlif_forward(hipStream_t st, bool fp32, int T, int B, int N, i
 // [B][ld] fp32 scratch for dL/dV_{t+1}; QRb[plane][from][to] bfloat16.
 static hipError_t rlif_reverse(hipStream_t st, bool fp32, int T, int B, int N, int ld, const float *dS, const float *V,
                                uint32_t *dI, float *g0, float *g1, const uint16_t *QRb, int ldqr,
-                               long long qr_plane, float beta, float theta, int surrogate, float slope) {
+                               long long qr_plane, const float *beta, float theta, int surrogate, float slope, float *db_part) {
   if (ld <= 128) {
     dim3 grid((B + 31) / 32), block(256);
 #define SNN_RLR(NP, SU)                                                                                         \
   hipLaunchKernelGGL((rlif_reverse_fused_kernel<NP, SU>), grid, block, 0, st, dS, V, dI, QRb, ldqr, qr_plane, T, B, \
-                     N, ld, beta, theta, slope)
+                     N, ld, beta, theta, slope, db_part)
     if (fp32) {
       switch (surrogate) { case 0: SNN_RLR(3, 0); break; case 1: SNN_RLR(3, 1); break;
                            case 2: SNN_RLR(3, 2); break; default: SNN_RLR(3, 3); break; }
@@ -578,6 +606,7 @@ static hipError_t rlif_reverse(hipStream_t st, bool fp32, int T, int B, int N, i
   const size_t stride = (size_t)B * ld;
   hipError_t e;
   if ((e = fill_zero(st, g0, stride * 4)) != hipSuccess) return e;                              // g_T = 0
+  if (db_part && (e = fill_zero(st, db_part, stride * 4)) != hipSuccess) return e;              // accumulated step by step
   if ((e = fill_zero(st, dI + (size_t)(T - 1) * stride, stride * 4)) != hipSuccess) return e;   // dI_{T-1} = 0
   const dim3 grid(rlif_step_grid(N, B)), block(256);
   float *g[2] = {g0, g1};
@@ -588,7 +617,7 @@ static hipError_t rlif_reverse(hipStream_t st, bool fp32, int T, int B, int N, i
     uint32_t *din = t > 0 ? dI + (size_t)(t - 1) * stride : nullptr;
 #define SNN_RSR(NP, SU)                                                                                          \
   hipLaunchKernelGGL((rlif_step_reverse_kernel<NP, SU>), grid, block, 0, st, gw, g[cur], ds, v, g[cur ^ 1], din, QRb, \
-                     ldqr, qr_plane, B, N, ld, beta, theta, slope)
+                     ldqr, qr_plane, B, N, ld, beta, theta, slope, db_part)
     if (fp32) {
       switch (surrogate) { case 0: SNN_RSR(3, 0); break; case 1: SNN_RSR(3, 1); break;
                            case 2: SNN_RSR(3, 2); break; default: SNN_RSR(3, 3); break; }

@@ -41,9 +41,12 @@ template <int VEC> __device__ __forceinline__ void st_spikes(rsrc_t r, int voff,
 template <int VEC, int U>
 __global__ __launch_bounds__(256) void lif_forward_kernel(const float *__restrict__ I, float *__restrict__ V,
                                                           uint8_t *__restrict__ S, int T, int stride,
-                                                          float beta, float theta) {
+                                                          const float *__restrict__ beta_v, int ld, float theta) {
   const int p = (blockIdx.x * blockDim.x + threadIdx.x) * VEC;
   if (p >= stride) return;
+  float beta[VEC];                                   // one decay per neuron (column p % ld)
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) beta[i] = beta_v[p % ld + i];
   const rsrc_t rI = make_rsrc(I, (unsigned)T * stride * 4u), rV = make_rsrc(V, (unsigned)T * stride * 4u);
   const rsrc_t rS = make_rsrc(S, (unsigned)T * stride);
   const int vo4 = p * 4, vo1 = p, row4 = stride * 4;
@@ -63,7 +66,7 @@ __global__ __launch_bounds__(256) void lif_forward_kernel(const float *__restric
     stv<VEC>(rV, vo4, t * row4, w);
     st_spikes<VEC>(rS, vo1, t * stride, s);
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) v[i] = beta * v[i] + cur[i] - (s[i] ? theta : 0.f);
+    for (int i = 0; i < VEC; ++i) v[i] = beta[i] * v[i] + cur[i] - (s[i] ? theta : 0.f);
   };
   fetch(a, 0);
   int t0 = 0;
@@ -86,6 +89,7 @@ __global__ __launch_bounds__(256) void lif_forward_kernel(const float *__restric
 
 // ---------------------------------------------------------------- LIF reverse, fused surrogate
 // g = 0; for t = T-1..0: dI_t = g; g = beta g + surr(V_t - theta) (dS_t - theta g).
+// With db_part: also dL/dbeta per chain, sum_t g_{t+1} V_t (V_{t+1} = beta V_t + ..).
 // dI is written as fp32 or, when HL, in the hi/lo form the bfloat16 products read.
 template <int SURR> __device__ __forceinline__ float surr(float k, float x) {
   if (SURR == 0) { float d = 1.0f + k * fabsf(x); return 1.0f / (d * d); }
@@ -97,9 +101,13 @@ template <int SURR> __device__ __forceinline__ float surr(float k, float x) {
 template <int VEC, int U, int SURR, bool HL>
 __global__ __launch_bounds__(256) void lif_reverse_kernel(const float *__restrict__ dS, const float *__restrict__ V,
                                                           uint32_t *__restrict__ dI, int T, int stride,
-                                                          float beta, float theta, float slope) {
+                                                          const float *__restrict__ beta_v, int ld, float theta,
+                                                          float slope, float *__restrict__ db_part) {
   const int p = (blockIdx.x * blockDim.x + threadIdx.x) * VEC;
   if (p >= stride) return;
+  float beta[VEC], db[VEC];                          // decay per neuron; sum over t of g_{t+1} V_t
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) { beta[i] = beta_v[p % ld + i]; db[i] = 0.f; }
   const unsigned bytes = (unsigned)T * stride * 4u;
   const rsrc_t rdS = make_rsrc(dS, bytes), rV = make_rsrc(V, bytes), rdI = make_rsrc(dI, bytes);
   const int vo4 = p * 4, row4 = stride * 4;
@@ -123,7 +131,10 @@ __global__ __launch_bounds__(256) void lif_reverse_kernel(const float *__restric
     for (int i = 0; i < VEC; ++i) w[i] = HL ? pack_hl(g[i]) : __float_as_uint(g[i]);
     stv<VEC>(rdI, vo4, t * row4, w);
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) g[i] = beta * g[i] + surr<SURR>(slope, vv[i] - theta) * (ds[i] - theta * g[i]);
+    for (int i = 0; i < VEC; ++i) {
+      db[i] += g[i] * vv[i];
+      g[i] = beta[i] * g[i] + surr<SURR>(slope, vv[i] - theta) * (ds[i] - theta * g[i]);
+    }
   };
   fetch(a_ds, a_v, T - 1);
   int thi = T - 1;
@@ -142,6 +153,10 @@ __global__ __launch_bounds__(256) void lif_reverse_kernel(const float *__restric
 #pragma unroll
     for (int u = 0; u < U; ++u) if (thi - U - u >= 0) step(b_ds[u], b_v[u], thi - U - u);
   }
+  if (db_part) {                                     // per sample; summed over the batch by the reduction launch
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) db_part[p + i] = db[i];
+  }
 }
 
 // ---------------------------------------------------------------- LI readout, max over time
@@ -149,9 +164,11 @@ __global__ __launch_bounds__(256) void lif_reverse_kernel(const float *__restric
 // `integral`: z = sum_t y_t instead (t* = 0, not used).
 __global__ __launch_bounds__(256) void readout_forward_kernel(const float *__restrict__ J, float *__restrict__ Y,
                                                               float *__restrict__ z, int *__restrict__ tstar,
-                                                              int T, int stride, float beta, int integral) {
+                                                              int T, int stride, const float *__restrict__ beta_v,
+                                                              int ld, int integral) {
   const int p = blockIdx.x * blockDim.x + threadIdx.x;
   if (p >= stride) return;
+  const float beta = beta_v[p % ld];
   float y = 0.f, best = -INFINITY, sum = 0.f;
   int tb = 0;
 #pragma unroll 8
@@ -230,7 +247,7 @@ __global__ __launch_bounds__(512) void readout_loss_kernel(const float *__restri
                                                            const int *__restrict__ labels, float *__restrict__ loss_b,
                                                            float *__restrict__ dz, int *__restrict__ err,
                                                            uint32_t *__restrict__ dJ, int T, int B, int C, int ldc,
-                                                           float beta) {
+                                                           const float *__restrict__ beta_v) {
   constexpr int SPB = 64 / CW;                        // samples per workgroup
   constexpr int NW = 8;                               // wavefronts = time segments per block
   constexpr int G = 4;                                // accesses (of four rows) per segment
@@ -262,6 +279,7 @@ __global__ __launch_bounds__(512) void readout_loss_kernel(const float *__restri
   auto mem_off = [&](int t0) { return t0 + mr < T ? mvo : OOB; };   // rows past the end: no access
 
   const int lab_in = b < B ? labels[b] : 0;
+  const float beta = c < ldc ? beta_v[c] : 0.f;       // the class's decay
   float bseg = beta;                                  // beta^SEG
 #pragma unroll
   for (int i = 0; i < 4; ++i) bseg *= bseg;
@@ -383,10 +401,11 @@ __global__ __launch_bounds__(512) void readout_loss_kernel(const float *__restri
 // Readout reverse: h_t = beta h_{t+1} + dz [t == t*]; dJ_t = h_t.
 template <bool HL>
 __global__ __launch_bounds__(256) void readout_reverse_kernel(const float *__restrict__ dz, const int *__restrict__ tstar,
-                                                              uint32_t *__restrict__ dJ, int T, int stride, float beta,
-                                                              int integral) {
+                                                              uint32_t *__restrict__ dJ, int T, int stride,
+                                                              const float *__restrict__ beta_v, int ld, int integral) {
   const int p = blockIdx.x * blockDim.x + threadIdx.x;
   if (p >= stride) return;
+  const float beta = beta_v[p % ld];
   const float d = dz[p];
   const int ts = tstar[p];
   float h = 0.f;
@@ -394,6 +413,41 @@ __global__ __launch_bounds__(256) void readout_reverse_kernel(const float *__res
     h = beta * h + (integral || t == ts ? d : 0.f);     // integral loss: every step feeds dz in
     dJ[(size_t)t * stride + p] = HL ? pack_hl(h) : __float_as_uint(h);
   }
+}
+
+// Gradient of the readout decays, per chain: y_t = beta y_{t-1} + J_t gives
+// dL/dbeta = sum_{t >= 1} h_t y_{t-1} with h_t = dJ_t.  Summed over the batch by the reduction
+// launch.  Only run when the decays are trained.
+template <bool HL>
+__global__ __launch_bounds__(256) void readout_beta_grad_kernel(const uint32_t *__restrict__ dJ, const float *__restrict__ Y,
+                                                                float *__restrict__ db_part, int T, int stride) {
+  const int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= stride) return;
+  float acc = 0.f;
+#pragma unroll 4
+  for (int t = 1; t < T; ++t) {
+    const uint32_t w = dJ[(size_t)t * stride + p];
+    const float h = HL ? bf16_value(w & 0xFFFFu) + bf16_value(w >> 16) : __uint_as_float(w);
+    acc += h * Y[(size_t)(t - 1) * stride + p];
+  }
+  db_part[p] = acc;
+}
+
+#define SNN_MAX_JOBS 24
+// beta <- clip(beta - lr dbeta, 0, 1) for several layers in one launch (the clip of the LIF listing).
+struct BetaJobs {
+  int njobs;
+  int first[SNN_MAX_JOBS + 1];
+  float *beta[SNN_MAX_JOBS];
+  const float *dbeta[SNN_MAX_JOBS];
+};
+__global__ __launch_bounds__(256) void beta_update_kernel(const BetaJobs jobs, float lr) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= jobs.first[jobs.njobs]) return;
+  int j = 0;
+  while (j + 1 < jobs.njobs && i >= jobs.first[j + 1]) ++j;
+  const int k = i - jobs.first[j];
+  jobs.beta[j][k] = fminf(1.f, fmaxf(0.f, jobs.beta[j][k] - lr * jobs.dbeta[j][k]));
 }
 
 // ---------------------------------------------------------------- small utilities
@@ -445,7 +499,6 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *__restrict__ p
 // of one job; its four wavefronts each add every fourth split (16-byte loads, eight in
 // flight) and the four sums are combined through LDS in a fixed order, so the result does
 // not depend on timing.  Tails that are not a multiple of four floats are done one by one.
-#define SNN_MAX_JOBS 16
 struct ReduceJobs {
   int njobs;
   int first_block[SNN_MAX_JOBS + 1];

@@ -26,7 +26,10 @@ struct Layer {
   int K = 0, N = 0;        // fan-in, fan-out
   int ld = 0;              // padded fan-out of the activation tensors (multiple of 8)
   bool recurrent = false, spiking = false;
-  float beta = 0.f;
+  float beta = 0.f;        // initial decay of the layer (config); the live values are beta_v
+  float *beta_v = nullptr; // [ld] one decay per neuron / class (padding 0)
+  float *dbeta = nullptr;  // [ld] gradient of the decays (only with learn_beta)
+  float *part_b = nullptr; // [B][ld] per-sample parts of dbeta
   float *Wm = nullptr, *dW = nullptr;
   uint16_t *Qf = nullptr, *Qb = nullptr;       // [plane][N pad 128][K pad 64], [plane][K pad 128][N pad 64]
   int ldqf = 0, ldqb = 0;
@@ -72,6 +75,7 @@ struct snn_ctx {
   int wall_khz = 100000;          // rate of the device's constant clock
   bool wg_tall = false;           // weight-gradient products use 256 x 128 tiles
   bool integral = false;          // integral cross-entropy instead of max over time
+  bool learn_beta = false;        // decays are trained: dbeta in snn_backward, clipped update in snn_sgd_step
   const uint8_t *x_eff = nullptr;  // raster the products read: the caller's, or x_buf
   uint8_t *x_buf = nullptr;        // [T*B][ldx]: zero-padded copy (N_0 not a multiple of 4) or unpacked input
   bool x_padded = false;           // the caller's raster must be copied into x_buf
@@ -119,6 +123,7 @@ int validate(const snn_config *cfg) {
   if (cfg->surrogate < 0 || cfg->surrogate > 3) return fail(nullptr, SNN_ERR_ARG, "unknown surrogate");
   if (cfg->precision < 0 || cfg->precision > 1) return fail(nullptr, SNN_ERR_ARG, "unknown precision");
   if (cfg->loss < 0 || cfg->loss > 1) return fail(nullptr, SNN_ERR_ARG, "unknown loss");
+  if (cfg->learn_beta < 0 || cfg->learn_beta > 1) return fail(nullptr, SNN_ERR_ARG, "learn_beta must be 0 or 1");
   if ((long long)cfg->T * cfg->B > (1ll << 30)) return fail(nullptr, SNN_ERR_ARG, "T*B too large");
   for (int i = 0; i <= cfg->n_layers; ++i)      // byte offsets into one tensor are 31-bit
     if ((long long)cfg->T * cfg->B * (cfg->sizes[i] + 8) * 4 >= (1ll << 31))
@@ -219,6 +224,9 @@ void carve(snn_ctx &c, Carver &cv) {
       y.splits_r = choose_splits(c.M, wg_tiles, &y.per_r);
       if (y.splits_r > 1) y.part_r = cv.take<float>((size_t)y.splits_r * N * N);
     }
+    y.beta_v = cv.take<float>(y.ld);
+    y.dbeta = cv.take<float>(y.ld);
+    if (c.learn_beta) y.part_b = cv.take<float>((size_t)c.B * y.ld);
     y.I = cv.take<float>(M * y.ld);
     y.V = cv.take<float>(M * y.ld);
     y.dI = cv.take<uint32_t>(M * y.ld);
@@ -245,6 +253,7 @@ void configure(snn_ctx &c, const snn_config *cfg) {
   c.theta = cfg->threshold; c.slope = cfg->slope;
   c.surrogate = cfg->surrogate; c.precision = cfg->precision;
   c.integral = cfg->loss == SNN_LOSS_INTEGRAL;
+  c.learn_beta = cfg->learn_beta != 0;
   c.nplanes = c.precision == SNN_PREC_FP32 ? 3 : 1;
   c.hl = c.precision == SNN_PREC_BF16_GEMM;
   c.layers.assign(c.L, Layer());
@@ -432,8 +441,8 @@ int queue_tn(snn_ctx *c, WgradJobs &w, SpikeSrc s, int rows, const void *G, int 
   return SNN_OK;
 }
 
-void add_reduce_job(ReduceJobs &jobs, const float *part, float *out, int splits, long long n) {
-  if (splits <= 1) return;
+void add_reduce_job(ReduceJobs &jobs, const float *part, float *out, int splits, long long n, bool always = false) {
+  if (splits <= 1 && !always) return;       // a single split was written straight to `out`
   const int j = jobs.njobs++;
   jobs.part[j] = part; jobs.out[j] = out; jobs.splits[j] = splits; jobs.n[j] = n;
   jobs.first_block[j + 1] = jobs.first_block[j] + (int)((n + 255) / 256);
@@ -507,7 +516,7 @@ hipError_t lif_fwd_launch(snn_ctx *c, Layer &y) {
   const int threads = stride / VEC;
   const int bs = scan_block(threads);
   hipLaunchKernelGGL((lif_forward_kernel<VEC, U>), dim3((unsigned)((threads + bs - 1) / bs)), dim3(bs), 0, c->stream,
-                     y.I, y.V, y.S, c->T, stride, y.beta, c->theta);
+                     y.I, y.V, y.S, c->T, stride, y.beta_v, y.ld, c->theta);
   return hipGetLastError();
 }
 
@@ -516,7 +525,7 @@ int launch_lif_forward(snn_ctx *c, int l) {
   if (y.recurrent) {
     Bracket br(c, SNN_K_RLIF_FORWARD, l + 1);
     HIPCHK(c, rlif_forward(c->stream, c->precision == SNN_PREC_FP32, c->T, c->B, y.N, y.ld, y.I, y.V, y.S, y.QRf,
-                           y.ldqr, y.qr_plane, y.beta, c->theta));
+                           y.ldqr, y.qr_plane, y.beta_v, c->theta));
     return SNN_OK;
   }
   Bracket br(c, SNN_K_LIF_FORWARD, l + 1);
@@ -537,7 +546,7 @@ hipError_t lif_rev_launch2(snn_ctx *c, Layer &y) {
   dim3 grid((unsigned)((threads + bs - 1) / bs)), block(bs);
 #define SNN_REV(SU)                                                                                          \
   hipLaunchKernelGGL((lif_reverse_kernel<VEC, U, SU, HL>), grid, block, 0, c->stream, y.dS, y.V, y.dI, c->T, \
-                     stride, y.beta, c->theta, c->slope)
+                     stride, y.beta_v, y.ld, c->theta, c->slope, y.part_b)
   switch (c->surrogate) {
     case 0: SNN_REV(0); break;
     case 1: SNN_REV(1); break;
@@ -557,7 +566,8 @@ int launch_lif_reverse(snn_ctx *c, int l) {
   if (y.recurrent) {
     Bracket br(c, SNN_K_RLIF_REVERSE, l + 1);
     HIPCHK(c, rlif_reverse(c->stream, c->precision == SNN_PREC_FP32, c->T, c->B, y.N, y.ld, y.dS, y.V, y.dI,
-                           y.g[0], y.g[1], y.QRb, y.ldqr, y.qr_plane, y.beta, c->theta, c->surrogate, c->slope));
+                           y.g[0], y.g[1], y.QRb, y.ldqr, y.qr_plane, y.beta_v, c->theta, c->surrogate, c->slope,
+                           y.part_b));
     return SNN_OK;
   }
   Bracket br(c, SNN_K_LIF_REVERSE, l + 1);
@@ -581,10 +591,10 @@ int launch_readout_forward(snn_ctx *c, const int32_t *labels) {
   do {                                                                                                           \
     if (c->integral)                                                                                             \
       hipLaunchKernelGGL((readout_loss_kernel<CW, HL, true>), grid, block, 0, c->stream, y.I, y.V, c->z, c->tstar, \
-                         labels, c->loss_b, c->dz, c->err_flag, y.dI, c->T, c->B, c->C, c->ldC, y.beta);         \
+                         labels, c->loss_b, c->dz, c->err_flag, y.dI, c->T, c->B, c->C, c->ldC, y.beta_v);       \
     else                                                                                                         \
       hipLaunchKernelGGL((readout_loss_kernel<CW, HL, false>), grid, block, 0, c->stream, y.I, y.V, c->z, c->tstar, \
-                         labels, c->loss_b, c->dz, c->err_flag, y.dI, c->T, c->B, c->C, c->ldC, y.beta);         \
+                         labels, c->loss_b, c->dz, c->err_flag, y.dI, c->T, c->B, c->C, c->ldC, y.beta_v);       \
   } while (0)
     if (c->hl) { if (cw == 16) SNN_RDL(16, true); else if (cw == 32) SNN_RDL(32, true); else SNN_RDL(64, true); }
     else { if (cw == 16) SNN_RDL(16, false); else if (cw == 32) SNN_RDL(32, false); else SNN_RDL(64, false); }
@@ -598,7 +608,7 @@ int launch_readout_forward(snn_ctx *c, const int32_t *labels) {
   c->loss_ready = true;
   const int stride = c->B * c->ldC;
   hipLaunchKernelGGL(readout_forward_kernel, dim3((stride + 255) / 256), dim3(256), 0, c->stream, y.I, y.V, c->z,
-                     c->tstar, c->T, stride, y.beta, c->integral ? 1 : 0);
+                     c->tstar, c->T, stride, y.beta_v, c->ldC, c->integral ? 1 : 0);
   HIPCHK(c, hipGetLastError());
   hipLaunchKernelGGL(cross_entropy_kernel, dim3((c->B + 3) / 4), dim3(256), 0, c->stream, c->z, labels, c->loss_b,
                      c->dz, c->B, c->C, c->ldC, c->err_flag);
@@ -614,10 +624,10 @@ int launch_readout_reverse(snn_ctx *c) {
   const int stride = c->B * c->ldC;
   if (c->hl)
     hipLaunchKernelGGL(readout_reverse_kernel<true>, dim3((stride + 255) / 256), dim3(256), 0, c->stream, c->dz,
-                       c->tstar, y.dI, c->T, stride, y.beta, c->integral ? 1 : 0);
+                       c->tstar, y.dI, c->T, stride, y.beta_v, c->ldC, c->integral ? 1 : 0);
   else
     hipLaunchKernelGGL(readout_reverse_kernel<false>, dim3((stride + 255) / 256), dim3(256), 0, c->stream, c->dz,
-                       c->tstar, y.dI, c->T, stride, y.beta, c->integral ? 1 : 0);
+                       c->tstar, y.dI, c->T, stride, y.beta_v, c->ldC, c->integral ? 1 : 0);
   HIPCHK(c, hipGetLastError());
   return SNN_OK;
 }
@@ -693,6 +703,13 @@ int view_of(snn_ctx *c, int tensor, int layer, TensorView *v, bool for_set) {
       if (!y->recurrent) return fail(c, SNN_ERR_ARG, "layer %d is not recurrent", layer);
       *v = {tensor == SNN_T_RWEIGHT ? y->Rm : y->dR, (size_t)y->N, (size_t)y->N, (size_t)y->N, 4, false};
       settable = tensor == SNN_T_RWEIGHT;
+      break;
+    case SNN_T_BETA:
+    case SNN_T_GRAD_BETA:
+      if ((rc = any_layer(&y))) return rc;
+      if (tensor == SNN_T_GRAD_BETA && !c->learn_beta) return fail(c, SNN_ERR_STATE, "decays are not trained (learn_beta = 0)");
+      *v = {tensor == SNN_T_BETA ? y->beta_v : y->dbeta, 1, (size_t)y->N, (size_t)y->ld, 4, false};
+      settable = tensor == SNN_T_BETA;
       break;
     case SNN_T_CURRENT:
       if ((rc = spiking_layer(&y))) return rc;
@@ -791,8 +808,12 @@ int32_t snn_init(const snn_config *cfg, void *workspace_dev, size_t workspace_by
       c->wall_khz = khz;
   }
   if ((e = hipMemsetAsync(c->ws, 0, c->ws_bytes, c->stream)) != hipSuccess) return bail(e, "hipMemsetAsync(workspace)");
+  std::vector<std::vector<float>> beta_host(c->L);        // alive until the synchronisation below
   for (int l = 0; l < c->L; ++l) {
     Layer &y = c->layers[l];
+    beta_host[l].assign(y.N, y.beta);
+    if ((e = hipMemcpyAsync(y.beta_v, beta_host[l].data(), sizeof(float) * y.N, hipMemcpyHostToDevice, c->stream)) != hipSuccess)
+      return bail(e, "hipMemcpyAsync(beta)");
     if ((e = hipMemcpyAsync(y.Wm, W_host[l], sizeof(float) * y.K * y.N, hipMemcpyHostToDevice, c->stream)) != hipSuccess)
       return bail(e, "hipMemcpyAsync(W)");
     if (y.recurrent &&
@@ -863,6 +884,20 @@ int32_t snn_backward(snn_ctx *c) {
     if ((rc = queue_weight_grad(c, l, wj, jobs))) return rc;
     if (l > 0 && (rc = launch_input_grad(c, l))) return rc;
   }
+  if (c->learn_beta) {
+    // per-sample parts of dL/dbeta: written by the reverse scans for the spiking layers, by a
+    // kernel of its own for the readout; summed over the batch by the reduction launch
+    Layer &ro = c->layers[c->L - 1];
+    const int stride = c->B * c->ldC;
+    if (c->hl)
+      hipLaunchKernelGGL(readout_beta_grad_kernel<true>, dim3((stride + 255) / 256), dim3(256), 0, c->stream, ro.dI,
+                         ro.V, ro.part_b, c->T, stride);
+    else
+      hipLaunchKernelGGL(readout_beta_grad_kernel<false>, dim3((stride + 255) / 256), dim3(256), 0, c->stream, ro.dI,
+                         ro.V, ro.part_b, c->T, stride);
+    HIPCHK(c, hipGetLastError());
+    for (int l = 0; l < c->L; ++l) add_reduce_job(jobs, c->layers[l].part_b, c->layers[l].dbeta, c->B, c->layers[l].ld, true);
+  }
   if ((rc = launch_weight_grads(c, wj, jobs, !c->loss_ready))) return rc;
   c->state = 2;
   return SNN_OK;
@@ -874,6 +909,17 @@ int32_t snn_sgd_step(snn_ctx *c, float lr) {
   Bracket br(c, SNN_K_SGD, 0);
   int rc = update_layers(c, 0, c->L, true, lr);
   if (rc) return rc;
+  if (c->learn_beta) {
+    BetaJobs bj;
+    memset(&bj, 0, sizeof bj);
+    for (int l = 0; l < c->L; ++l) {
+      const int j = bj.njobs++;
+      bj.beta[j] = c->layers[l].beta_v; bj.dbeta[j] = c->layers[l].dbeta;
+      bj.first[j + 1] = bj.first[j] + c->layers[l].N;
+    }
+    hipLaunchKernelGGL(beta_update_kernel, dim3((bj.first[bj.njobs] + 255) / 256), dim3(256), 0, c->stream, bj, lr);
+    HIPCHK(c, hipGetLastError());
+  }
   c->state = 0;
   return SNN_OK;
 }
@@ -907,6 +953,11 @@ int32_t snn_set_tensor(snn_ctx *c, int32_t tensor, int32_t layer, const void *sr
   if (rc) return rc;
   if (bytes != v.rows * v.cols * v.esz)
     return fail(c, SNN_ERR_SHAPE, "tensor %d needs %zu bytes, got %zu", tensor, v.rows * v.cols * v.esz, bytes);
+  if (tensor == SNN_T_BETA) {
+    const float *f = (const float *)src;
+    for (size_t i = 0; i < v.cols; ++i)
+      if (!(f[i] >= 0.f && f[i] <= 1.f)) return fail(c, SNN_ERR_ARG, "beta[%zu] outside [0,1]", i);
+  }
   std::vector<uint32_t> tmp;
   if (v.hl) {                                   // fp32 -> hi/lo words
     const float *f = (const float *)src;

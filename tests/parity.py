@@ -37,13 +37,13 @@ def _splice(tr: O.Trace, sub: O.Trace, idx: np.ndarray, B: int):
     tr.loss = float(tr.loss_b.sum() / B)
 
 
-def reconciled_forward(net: O.Net, X, W, R, labels, S_gpu, max_rounds: int = 200, band: float = BAND):
+def reconciled_forward(net: O.Net, X, W, R, labels, S_gpu, max_rounds: int = 200, band: float = BAND, betas=None):
     """Oracle forward with the device's near-threshold decisions imposed.
 
     S_gpu: list of uint8 arrays [T,B,N] per spiking layer.  Returns (trace, n_imposed).
     """
     T, B, _ = X.shape
-    tr = O.forward(net, X, W, R, labels)
+    tr = O.forward(net, X, W, R, labels, betas=betas)
     forced = {b: {} for b in range(B)}          # per sample: (l,t) -> [(n,val)]
     imposed = 0
     for _ in range(max_rounds):
@@ -76,7 +76,7 @@ def reconciled_forward(net: O.Net, X, W, R, labels, S_gpu, max_rounds: int = 200
         for j, b in enumerate(idx):
             for key, lst in forced[int(b)].items():
                 sub_forced.setdefault(key, []).extend((j, n, v) for n, v in lst)
-        sub = O.forward(net, X[:, idx], W, R, labels[idx], forced=sub_forced, batch_norm=B)
+        sub = O.forward(net, X[:, idx], W, R, labels[idx], forced=sub_forced, batch_norm=B, betas=betas)
         _splice(tr, sub, idx, B)
     raise ParityError("spike reconciliation did not converge")
 
@@ -105,11 +105,11 @@ def close_grad(name, a, b, tol=TOL_GRAD):
     return float(einf / ninf), float(e2 / n2)
 
 
-def compare_forward(net: O.Net, inp, snn, loss_gpu, report=None):
+def compare_forward(net: O.Net, inp, snn, loss_gpu, report=None, betas=None):
     """Fetch the device's forward tensors and check them against the reconciled oracle."""
     Lh = net.L - 1
     S_gpu = [snn.get_tensor("spikes", l + 1) for l in range(Lh)]
-    tr, imposed = reconciled_forward(net, inp.X, inp.W, inp.R, inp.labels, S_gpu)
+    tr, imposed = reconciled_forward(net, inp.X, inp.W, inp.R, inp.labels, S_gpu, betas=betas)
     rep = {"imposed_decisions": imposed, "spike_rate": [float(s.mean()) for s in S_gpu]}
     for l in range(Lh):
         assert np.array_equal(S_gpu[l], tr.S[l].astype(np.uint8))
@@ -140,8 +140,8 @@ def compare_forward(net: O.Net, inp, snn, loss_gpu, report=None):
     return tr
 
 
-def compare_backward(net: O.Net, inp, snn, tr, report=None, tol=TOL_GRAD):
-    gr = O.backward(net, inp.X, inp.W, inp.R, inp.labels, tr)
+def compare_backward(net: O.Net, inp, snn, tr, report=None, tol=TOL_GRAD, betas=None, learn_beta=False):
+    gr = O.backward(net, inp.X, inp.W, inp.R, inp.labels, tr, betas=betas)
     rep = {}
     close_grad("dz", snn.get_tensor("d_logits"), gr.dz, tol)
     # current gradients
@@ -158,6 +158,9 @@ def compare_backward(net: O.Net, inp, snn, tr, report=None, tol=TOL_GRAD):
     for l in range(net.L - 1):
         if inp.R[l] is not None:
             rep[f"dR{l + 1}"] = close_grad(f"dR^{l + 1}", snn.get_tensor("grad_r", l + 1), gr.dR[l], tol)
+    if learn_beta:
+        for l in range(net.L):
+            rep[f"dbeta{l + 1}"] = close_grad(f"dbeta^{l + 1}", snn.get_tensor("grad_beta", l + 1), gr.dbeta[l], tol)
     if report is not None:
         report.update(rep)
     return gr

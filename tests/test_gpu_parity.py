@@ -378,3 +378,73 @@ def test_integral_loss_headline_shape_long_horizon():
     last one ragged."""
     wl = workloads.CONFIGS["shd_ff128"].scaled(T=300, B=32, loss="integral")
     full_step_parity(wl, w_gain=3.0, check_sgd=False)
+
+
+# ---------------------------------------------------------------- per-neuron, trainable decay
+def beta_step_parity(wl, w_gain=2.5, lr=0.05):
+    """Random per-neuron decays set through SNN_T_BETA; forward, backward with dL/dbeta, and
+    the clipped update, against the oracle."""
+    inp = workloads.generate(wl, w_gain=w_gain)
+    net = net_of(wl)
+    rng = np.random.default_rng(wl.seed + 7)
+    betas = [rng.uniform(0.7, 0.99, size=n).astype(np.float32) for n in wl.sizes[1:]]
+    betas[0][:2] = (0.0, 1.0)                              # the ends of the interval
+    from paper_2402_18994_amd.binding import from_workload
+    snn = from_workload(wl, inp, learn_beta=True)
+    print(f"\n[case] trainable beta {wl.name} T={wl.T} B={wl.B} sizes={wl.sizes} rec={wl.recurrent} {wl.precision} {wl.loss}",
+          flush=True)
+    for l, b in enumerate(betas):
+        snn.set_tensor("beta", l + 1, b)
+        assert np.array_equal(snn.get_tensor("beta", l + 1), b)
+    b64 = [b.astype(np.float64) for b in betas]
+    rep = {}
+    loss = snn.forward(inp.X, inp.labels)
+    tr = parity.compare_forward(net, inp, snn, loss, rep, betas=b64)
+    snn.backward()
+    gr = parity.compare_backward(net, inp, snn, tr, rep, betas=b64, learn_beta=True)
+    snn.sgd_step(lr)
+    new = O.sgd_step_beta(b64, gr, lr)
+    for l in range(net.L):
+        got = snn.get_tensor("beta", l + 1)
+        assert got.min() >= 0.0 and got.max() <= 1.0
+        assert np.abs(got - new[l]).max() <= parity.TOL_GRAD * lr * np.abs(gr.dbeta[l]).max() + 1e-7
+    print(json.dumps(rep), flush=True)
+    snn.destroy()
+    return rep, gr, new
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_trainable_beta_feedforward_and_wide_readout(precision):
+    for sizes, T, B, loss in (((45, 29, 13, 3), 37, 7, "max"), ((40, 32, 70), 21, 6, "integral")):
+        wl = workloads.Workload(name="beta_ff", index=19, T=T, B=B, sizes=sizes, recurrent=(False,) * (len(sizes) - 2),
+                                beta=(0.9,) * (len(sizes) - 1), theta=1.0, surrogate="superspike", slope=25.0,
+                                precision=precision, rate_lo=0.1, rate_hi=0.3, loss=loss)
+        rep, gr, new = beta_step_parity(wl)
+        assert all(np.abs(d).max() > 0 for d in gr.dbeta)
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_trainable_beta_recurrent_narrow_and_wide(precision):
+    """Both recurrent code paths: the single-kernel one (N <= 128) and one launch per step."""
+    for sizes, T, B in (((50, 40, 24, 5), 31, 40), ((60, 168, 5), 21, 11)):
+        wl = workloads.Workload(name="beta_rec", index=20, T=T, B=B, sizes=sizes, recurrent=(True,) * (len(sizes) - 2),
+                                beta=(0.9,) * (len(sizes) - 1), theta=1.0, surrogate="arctan", slope=2.0,
+                                precision=precision, rate_lo=0.05, rate_hi=0.2, rec_gain=1.0)
+        beta_step_parity(wl)
+
+
+def test_trainable_beta_large_update_is_clipped():
+    wl = workloads.Workload(name="beta_clip", index=21, T=20, B=5, sizes=(30, 20, 4), recurrent=(False,),
+                            beta=(0.9, 0.9), theta=1.0, surrogate="superspike", slope=25.0, precision="fp32",
+                            rate_lo=0.1, rate_hi=0.3)
+    rep, gr, new = beta_step_parity(wl, lr=1e5)
+    assert any(np.any(b == 0.0) or np.any(b == 1.0) for b in new)
+
+
+def test_headline_shape_with_trainable_beta_vector_scans():
+    """Headline layer sizes at reduced T and B, and a layer wide enough for the two-chain scan."""
+    beta_step_parity(workloads.CONFIGS["shd_ff128"].scaled(T=64, B=64), w_gain=3.0)
+    wl = workloads.Workload(name="beta_wide", index=22, T=24, B=128, sizes=(64, 1024, 20), recurrent=(False,),
+                            beta=(0.9, 0.9), theta=1.0, surrogate="superspike", slope=25.0, precision="bf16",
+                            rate_lo=0.05, rate_hi=0.3)
+    beta_step_parity(wl, w_gain=3.0)
