@@ -34,6 +34,9 @@ notes of this repository):
     trace summed over time, z[b,c] = sum_t y_t[b,c]; no label smoothing.
   * Arctan surrogate: (k/2) / (1 + (pi k x / 2)^2), the derivative of
     (1/pi) arctan(pi k x / 2) + 1/2.  The paper only names it.
+  * Boxcar surrogate (only named): 1/2 where |k x| <= 1, else 0 (a box of
+    width 2/k and height 1/2).  Straight-through estimator (the default the
+    paper states for its activation builder): derivative 1 everywhere.
   * Recurrent LIF: V_{t+1} = beta V_t + I_t + S_t R - theta S_t with S_t the
     spikes just emitted from V_t; R is [from, to].  The paper only mentions
     recurrent models.
@@ -48,8 +51,8 @@ notes of this repository):
     than the 1e-4 bound.)
 
 parity unpinned (fixed by this file, nothing in the paper to check against):
-the arctan constant, the loss reduction (mean), the readout equation and the
-form of the integral loss.
+the arctan constant, the boxcar's width and height, the loss reduction (mean),
+the readout equation and the form of the integral loss.
 """
 from __future__ import annotations
 
@@ -65,7 +68,7 @@ class Net:
     recurrent: Tuple[bool, ...]       # L-1 flags
     beta: Tuple[float, ...]           # L decays, last = readout
     theta: float
-    surrogate: str                    # superspike | arctan | sigmoid | triangular
+    surrogate: str                    # superspike | arctan | sigmoid | triangular | boxcar | ste
     slope: float
     gemm_round: str = "none"          # "none" | "bf16"
     loss: str = "max"                 # "max" | "integral": how the readout trace is reduced over time
@@ -107,6 +110,10 @@ def surrogate_grad(kind: str, k: float, x: np.ndarray) -> np.ndarray:
         return k * s * (1.0 - s)
     if kind == "triangular":          # surrogate listing: max(0, 1 - |k x|)
         return np.maximum(0.0, 1.0 - np.abs(k * x))
+    if kind == "boxcar":              # named in Section 2.1.1, no formula: 1/2 on |k x| <= 1, else 0
+        return np.where(np.abs(k * x) <= 1.0, 0.5, 0.0)
+    if kind == "ste":                 # straight-through estimator (the stated default): derivative 1
+        return np.ones_like(np.asarray(x, dtype=np.float64))
     raise ValueError(kind)
 
 
@@ -123,6 +130,10 @@ def smooth_step(kind: str, k: float, x: np.ndarray) -> np.ndarray:
     if kind == "triangular":
         xc = np.clip(x, -1.0 / k, 1.0 / k)
         return 0.5 + xc - 0.5 * k * xc * np.abs(xc)
+    if kind == "boxcar":
+        return 0.5 + 0.5 * np.clip(x, -1.0 / k, 1.0 / k)
+    if kind == "ste":
+        return 0.5 + x
     raise ValueError(kind)
 
 

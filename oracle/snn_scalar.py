@@ -20,6 +20,10 @@ def _surr(kind, k, x):
         return k * s * (1.0 - s)
     if kind == "triangular":
         return max(0.0, 1.0 - abs(k * x))
+    if kind == "boxcar":
+        return 0.5 if abs(k * x) <= 1.0 else 0.0
+    if kind == "ste":
+        return 1.0
     raise ValueError(kind)
 
 

@@ -189,7 +189,7 @@ def fd_grads(net, X, W, R, lab, h=1e-6):
 
 
 @pytest.mark.parametrize("surrogate,slope", [("sigmoid", 3.0), ("superspike", 4.0),
-                                             ("arctan", 2.0), ("triangular", 0.5)])
+                                             ("arctan", 2.0), ("triangular", 0.5), ("boxcar", 0.4), ("ste", 1.0)])
 @pytest.mark.parametrize("recurrent", [(False, False), (True, True), (False, True)])
 def test_backward_is_exact_gradient_of_smoothed_network(surrogate, slope, recurrent):
     """With the step replaced by the surrogate's antiderivative the reverse sweep must be the
@@ -252,7 +252,8 @@ def test_integral_loss_closed_forms():
 
 def test_surrogates_are_derivatives_of_their_smooth_steps():
     x = np.linspace(-3, 3, 601) + 1e-4
-    for kind, k in [("sigmoid", 3.0), ("superspike", 25.0), ("arctan", 2.0), ("triangular", 0.5)]:
+    for kind, k in [("sigmoid", 3.0), ("superspike", 25.0), ("arctan", 2.0), ("triangular", 0.5),
+                    ("boxcar", 0.7), ("ste", 1.0)]:
         h = 1e-6
         fd = (O.smooth_step(kind, k, x + h) - O.smooth_step(kind, k, x - h)) / (2 * h)
         assert np.allclose(fd, O.surrogate_grad(kind, k, x), atol=1e-6), kind
@@ -261,6 +262,9 @@ def test_surrogates_are_derivatives_of_their_smooth_steps():
         == pytest.approx([1.0, 0.25, 1 / 36.0])
     assert O.surrogate_grad("triangular", 0.5, np.array([0.0, 1.0, -3.0])) == pytest.approx([1, 0.5, 0])
     assert O.surrogate_grad("arctan", 2.0, np.array([0.0]))[0] == pytest.approx(1.0)
+    assert O.surrogate_grad("boxcar", 1.0, np.array([0.0, 0.99, -1.0, 1.01, -3.0])) == pytest.approx([0.5, 0.5, 0.5, 0, 0])
+    assert O.surrogate_grad("boxcar", 4.0, np.array([0.2, 0.3])) == pytest.approx([0.5, 0.0])
+    assert O.surrogate_grad("ste", 7.0, np.array([-5.0, 0.0, 2.0])) == pytest.approx([1.0, 1.0, 1.0])
 
 
 def test_readout_weight_gradient_of_the_real_spiking_network():
@@ -288,7 +292,7 @@ def test_readout_weight_gradient_of_the_real_spiking_network():
 
 # ---------------------------------------------------------------- brute force
 @pytest.mark.parametrize("recurrent", [(False, False), (True, False), (True, True)])
-@pytest.mark.parametrize("surrogate,slope", [("superspike", 25.0), ("arctan", 2.0)])
+@pytest.mark.parametrize("surrogate,slope", [("superspike", 25.0), ("arctan", 2.0), ("boxcar", 1.0), ("ste", 1.0)])
 def test_vectorised_oracle_equals_scalar_brute_force(recurrent, surrogate, slope):
     rng = np.random.default_rng(31)
     net, X, W, R, lab = tiny_net(rng, sizes=(6, 5, 4, 3), recurrent=recurrent, T=9, B=3,
