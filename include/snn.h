@@ -52,12 +52,17 @@ typedef enum {
  *                                                  of (1/pi) atan(pi k x / 2) + 1/2)
  *   SIGMOID     k s (1 - s), s = 1/(1+exp(-k x))
  *   TRIANGULAR  max(0, 1 - |k x|)                 (surrogate listing)
+ *   BOXCAR      1/2 where |k x| <= 1, else 0      (named by the paper; width 2/k, height 1/2)
+ *   STE         1                                 (straight-through estimator, the default the
+ *                                                  paper states for its activation builder)
  * The forward function is always the Heaviside step with no spike at x == 0. */
 typedef enum {
   SNN_SURR_SUPERSPIKE = 0,
   SNN_SURR_ARCTAN = 1,
   SNN_SURR_SIGMOID = 2,
-  SNN_SURR_TRIANGULAR = 3
+  SNN_SURR_TRIANGULAR = 3,
+  SNN_SURR_BOXCAR = 4,
+  SNN_SURR_STE = 5
 } snn_surrogate;
 
 /* Arithmetic of the matrix products.  State, surrogate, loss and accumulation are fp32 in

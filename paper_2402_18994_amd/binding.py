@@ -14,7 +14,7 @@ import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 
-SURROGATES = {"superspike": 0, "arctan": 1, "sigmoid": 2, "triangular": 3}
+SURROGATES = {"superspike": 0, "arctan": 1, "sigmoid": 2, "triangular": 3, "boxcar": 4, "ste": 5}
 PRECISIONS = {"fp32": 0, "bf16": 1}
 LOSSES = {"max": 0, "integral": 1}
 TENSORS = {"weight": 0, "rweight": 1, "grad_w": 2, "grad_r": 3, "current": 4, "membrane": 5,

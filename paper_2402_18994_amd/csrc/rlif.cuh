@@ -595,10 +595,12 @@ static hipError_t rlif_reverse(hipStream_t st, bool fp32, int T, int B, int N, i
                      N, ld, beta, theta, slope, db_part)
     if (fp32) {
       switch (surrogate) { case 0: SNN_RLR(3, 0); break; case 1: SNN_RLR(3, 1); break;
-                           case 2: SNN_RLR(3, 2); break; default: SNN_RLR(3, 3); break; }
+                           case 2: SNN_RLR(3, 2); break; case 3: SNN_RLR(3, 3); break;
+                           case 4: SNN_RLR(3, 4); break; default: SNN_RLR(3, 5); break; }
     } else {
       switch (surrogate) { case 0: SNN_RLR(1, 0); break; case 1: SNN_RLR(1, 1); break;
-                           case 2: SNN_RLR(1, 2); break; default: SNN_RLR(1, 3); break; }
+                           case 2: SNN_RLR(1, 2); break; case 3: SNN_RLR(1, 3); break;
+                           case 4: SNN_RLR(1, 4); break; default: SNN_RLR(1, 5); break; }
     }
 #undef SNN_RLR
     return hipGetLastError();
@@ -620,10 +622,12 @@ static hipError_t rlif_reverse(hipStream_t st, bool fp32, int T, int B, int N, i
                      ldqr, qr_plane, B, N, ld, beta, theta, slope, db_part)
     if (fp32) {
       switch (surrogate) { case 0: SNN_RSR(3, 0); break; case 1: SNN_RSR(3, 1); break;
-                           case 2: SNN_RSR(3, 2); break; default: SNN_RSR(3, 3); break; }
+                           case 2: SNN_RSR(3, 2); break; case 3: SNN_RSR(3, 3); break;
+                           case 4: SNN_RSR(3, 4); break; default: SNN_RSR(3, 5); break; }
     } else {
       switch (surrogate) { case 0: SNN_RSR(1, 0); break; case 1: SNN_RSR(1, 1); break;
-                           case 2: SNN_RSR(1, 2); break; default: SNN_RSR(1, 3); break; }
+                           case 2: SNN_RSR(1, 2); break; case 3: SNN_RSR(1, 3); break;
+                           case 4: SNN_RSR(1, 4); break; default: SNN_RSR(1, 5); break; }
     }
 #undef SNN_RSR
     if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -95,7 +95,9 @@ template <int SURR> __device__ __forceinline__ float surr(float k, float x) {
   if (SURR == 0) { float d = 1.0f + k * fabsf(x); return 1.0f / (d * d); }
   if (SURR == 1) { float u = 1.5707963267948966f * k * x; return (0.5f * k) / (1.0f + u * u); }
   if (SURR == 2) { float s = 1.0f / (1.0f + __expf(-k * x)); return k * s * (1.0f - s); }
-  return fmaxf(0.0f, 1.0f - fabsf(k * x));
+  if (SURR == 3) return fmaxf(0.0f, 1.0f - fabsf(k * x));
+  if (SURR == 4) return fabsf(k * x) <= 1.0f ? 0.5f : 0.0f;      // boxcar
+  return 1.0f;                                                   // straight-through
 }
 
 template <int VEC, int U, int SURR, bool HL>

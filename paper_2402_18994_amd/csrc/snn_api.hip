@@ -120,7 +120,7 @@ int validate(const snn_config *cfg) {
     if (!(cfg->beta[i] >= 0.f && cfg->beta[i] <= 1.f)) return fail(nullptr, SNN_ERR_ARG, "beta[%d] outside [0,1]", i);
   if (!(cfg->threshold > 0.f)) return fail(nullptr, SNN_ERR_ARG, "threshold must be positive");
   if (!(cfg->slope > 0.f)) return fail(nullptr, SNN_ERR_ARG, "slope must be positive");
-  if (cfg->surrogate < 0 || cfg->surrogate > 3) return fail(nullptr, SNN_ERR_ARG, "unknown surrogate");
+  if (cfg->surrogate < 0 || cfg->surrogate > 5) return fail(nullptr, SNN_ERR_ARG, "unknown surrogate");
   if (cfg->precision < 0 || cfg->precision > 1) return fail(nullptr, SNN_ERR_ARG, "unknown precision");
   if (cfg->loss < 0 || cfg->loss > 1) return fail(nullptr, SNN_ERR_ARG, "unknown loss");
   if (cfg->learn_beta < 0 || cfg->learn_beta > 1) return fail(nullptr, SNN_ERR_ARG, "learn_beta must be 0 or 1");
@@ -551,7 +551,9 @@ hipError_t lif_rev_launch2(snn_ctx *c, Layer &y) {
     case 0: SNN_REV(0); break;
     case 1: SNN_REV(1); break;
     case 2: SNN_REV(2); break;
-    default: SNN_REV(3); break;
+    case 3: SNN_REV(3); break;
+    case 4: SNN_REV(4); break;
+    default: SNN_REV(5); break;
   }
 #undef SNN_REV
   return hipGetLastError();

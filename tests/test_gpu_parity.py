@@ -73,7 +73,7 @@ def test_tiny_ff_fp32(gain):
 
 
 @pytest.mark.parametrize("surrogate,slope", [("superspike", 25.0), ("arctan", 2.0), ("sigmoid", 4.0),
-                                             ("triangular", 0.5)])
+                                             ("triangular", 0.5), ("boxcar", 1.0), ("ste", 1.0)])
 @pytest.mark.parametrize("precision", ["fp32", "bf16"])
 def test_ragged_shapes(surrogate, slope, precision):
     """Sizes that are multiples of nothing: ragged row, column and contraction tails in every
@@ -161,6 +161,16 @@ def test_recurrent_small(precision):
                             precision=precision, rate_lo=0.05, rate_hi=0.2, rec_gain=1.0)
     rep = full_step_parity(wl, w_gain=2.5)
     assert rep["spike_rate"][0] > 0.01 and rep["spike_rate"][1] > 0.005
+
+
+@pytest.mark.parametrize("surrogate", ["boxcar", "ste"])
+def test_recurrent_other_surrogates(surrogate):
+    """The surrogates that the other recurrent cases do not use, on both recurrent code paths."""
+    for sizes, T, B in (((50, 40, 5), 30, 10), ((60, 168, 5), 21, 11)):
+        wl = workloads.Workload(name="rec_surr", index=23, T=T, B=B, sizes=sizes, recurrent=(True,),
+                                beta=(0.9, 0.9), theta=1.0, surrogate=surrogate, slope=1.0,
+                                precision="bf16", rate_lo=0.05, rate_hi=0.2, rec_gain=1.0)
+        full_step_parity(wl, w_gain=2.5, check_sgd=False)
 
 
 @pytest.mark.parametrize("precision", ["fp32", "bf16"])
