@@ -312,6 +312,15 @@ def test_error_paths():
     assert snn.lib.snn_set_tensor(snn.ctx, 2, 1, buf.ctypes.data, buf.nbytes) == 2        # gradients not settable
     assert snn.lib.snn_run_step(snn.ctx, 6, 1, None, None) == 2                           # no input grad for layer 1
     assert snn.lib.snn_forward(snn.ctx, None, None, None) == 1
+    assert snn.lib.snn_forward_packed(snn.ctx, None, None, None) == 1
+    # decays: out of range refused, gradient only when they are trained, wrong size
+    b = np.full(wl.sizes[1], 0.5, np.float32)
+    assert snn.lib.snn_set_tensor(snn.ctx, 17, 1, b.ctypes.data, b.nbytes) == 0
+    b[3] = 1.5
+    assert snn.lib.snn_set_tensor(snn.ctx, 17, 1, b.ctypes.data, b.nbytes) == 2
+    assert snn.lib.snn_set_tensor(snn.ctx, 17, 1, b.ctypes.data, b.nbytes - 4) == 3
+    assert snn.lib.snn_get_tensor(snn.ctx, 18, 1, b.ctypes.data, b.nbytes) == 5          # learn_beta = 0
+    assert snn.lib.snn_set_tensor(snn.ctx, 18, 1, b.ctypes.data, b.nbytes) in (2, 5)     # never settable
     # a workspace that is too small or misaligned is refused
     import torch
     from paper_2402_18994_amd import binding
@@ -321,6 +330,12 @@ def test_error_paths():
     ctx = C.c_void_p(None)
     assert snn.lib.snn_init(C.byref(cfg.c), small.data_ptr(), 1024, Wp, None, None, C.byref(ctx)) == 4
     assert snn.lib.snn_init(C.byref(cfg.c), small.data_ptr() + 1, 1 << 30, Wp, None, None, C.byref(ctx)) == 4
+    # unknown enums in the configuration
+    n = C.c_size_t(0)
+    for field, bad_value in (("surrogate", 6), ("precision", 2), ("loss", 2), ("learn_beta", 2)):
+        cfg2 = binding._Cfg(wl.T, wl.B, wl.sizes, wl.recurrent, wl.beta, wl.theta, wl.surrogate, wl.slope, wl.precision)
+        setattr(cfg2.c, field, bad_value)
+        assert snn.lib.snn_workspace_bytes(C.byref(cfg2.c), C.byref(n)) == 2, field
     snn.destroy()
 
 

@@ -53,8 +53,12 @@ def test_workspace_size_and_validation(lib):
     assert n > 0 and n % 256 == 0
     assert ws(lib, T=16) > n
     assert ws(lib, recurrent=(1,)) > n
+    assert ws(lib, loss="integral") == n
+    for s_ in ("boxcar", "ste"):
+        assert ws(lib, surrogate=s_) == n
     for bad in (dict(T=0), dict(B=-1), dict(sizes=(10, 0, 3)), dict(beta=(0.9, 1.5)), dict(theta=0.0),
-                dict(slope=-1.0), dict(surrogate=9), dict(precision=5), dict(sizes=(10, 3), beta=(0.9,), recurrent=())):
+                dict(slope=-1.0), dict(surrogate=9), dict(precision=5), dict(loss=7),
+                dict(sizes=(10, 3), beta=(0.9,), recurrent=())):
         with pytest.raises(binding.SnnError) as e:
             ws(lib, **bad)
         assert e.value.status == 2, bad
@@ -62,6 +66,7 @@ def test_workspace_size_and_validation(lib):
     assert lib.snn_workspace_bytes(None, None) == 1
     assert b"NULL" in lib.snn_last_error(None)
     assert lib.snn_forward(None, None, None, None) == 1
+    assert lib.snn_forward_packed(None, None, None, None) == 1
     assert lib.snn_backward(None) == 1
     assert lib.snn_sgd_step(None, C.c_float(0.1)) == 1
     assert lib.snn_destroy(None) == 0
