@@ -1,0 +1,258 @@
+// The current product I = S W for large layers, gfx950: C[i][j] = sum_k P(i,k) * Q(j,k) with
+// P the 0/1 spike bytes [row][k] and Q one bfloat16 plane of W^T [j][k] (rounded weights).
+//
+// The general product kernel stages operand tiles through registers: wait for the global
+// loads, convert, write to LDS, issue the next loads, barrier, multiply, barrier.  Measured
+// on the part, every phase is bound by what one wavefront can issue (a 16-byte LDS write
+// about every 36 cycles, a buffer load about every 60), and the phases of a workgroup do not
+// overlap.  This kernel removes the staging phase instead of hiding it:
+//
+//   * both operand tiles travel from memory straight into LDS (buffer_load ... lds, 16 bytes
+//     per lane): no staging registers, no LDS write instructions, no conversion before the
+//     barrier.  A wavefront's 64 lanes fill 1 KiB of consecutive LDS, so the bank swizzle is
+//     applied on the global side: each lane fetches the 16-byte unit that belongs at its slot;
+//   * the spikes stay bytes in LDS (half the LDS traffic of the P operand) and become
+//     bfloat16 in registers, after the fragment read, between the MFMAs;
+//   * four LDS stages of 32 contraction elements and one barrier per stage: the loads of
+//     stage t+3 are issued during stage t and have almost three stages to land (the P operand
+//     comes from HBM on first touch; two stages of 64 left a third of a microsecond of wait
+//     per tile);
+//   * fragments are read one MFMA step ahead of their use, across the stage boundary too:
+//     the barrier sits between the two steps of a stage.
+//
+// Contraction order inside a stage.  A lane holds 8 consecutive k per MFMA.  Reading a lane's
+// P bytes 16 at a time (two steps' worth) fixes which k a step covers: step s of lane half
+// h = lane/32 covers k = 16h + 8s .. +7, and the Q fragment of that step is read from the
+// matching 16-byte chunk 2h + s of the row.
+//
+// Tails.  Rows of P beyond the product read as zero (lane offset beyond the buffer).  Along
+// k nothing is masked on the P side: Q is zero-padded to a multiple of 64 along k, and
+// whatever bytes P yields there are reduced to 0/1 before they meet those zeros.
+#pragma once
+#include "gemm.cuh"
+
+namespace snn {
+
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+// 16 bytes per lane from a buffer straight into LDS: lane L's bytes land at lds_addr + 16 L
+// (lds_addr: byte address within LDS, the same for the whole wavefront); a lane whose offset
+// is beyond the buffer writes zeros.  Written as asm on purpose.  The compiler would guard
+// every later LDS read it cannot tell apart from such a load's target with a wait for the
+// load, and at a loop head with a wait for all loads in flight, which undoes a prefetch
+// distance of several stages.  This way the loads are invisible to it: the kernel waits
+// explicitly (vmcnt) and orders with barriers.  The descriptor is the usual raw buffer
+// resource (base, 0 stride, size, 0x00020000); M0 carries the LDS address and has no other
+// use in a kernel that includes this.
+__device__ __forceinline__ u32x4 raw_rsrc(const void *base, unsigned bytes) {
+  const unsigned long long b = (unsigned long long)base;
+  u32x4 r;
+  r.x = (unsigned)b;
+  r.y = (unsigned)(b >> 32) & 0xFFFFu;
+  r.z = bytes;
+  r.w = 0x00020000u;
+  return r;
+}
+__device__ __forceinline__ void load_to_lds_b128(u32x4 rsrc, unsigned lds_addr, int voff, int soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+               : "memory");
+}
+
+template <int WM, int WN, int TM, int TN>
+__global__ __launch_bounds__(256, 2) void spike_gemm_kernel(const GemmArgs a) {
+  static_assert(WM * WN == 4, "four wavefronts per workgroup");
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  constexpr int PT = BM * 32, QT = BN * 64, ST = PT + QT;   // bytes: P part, Q part, stage (32 k)
+  constexpr int PI = BM / 128, QI = BN / 64;                 // load instructions per wavefront and stage
+  constexpr int NL = PI + QI;
+  static_assert(BM % 128 == 0 && BN % 64 == 0, "whole KiB per wavefront");
+  static_assert(4 * ST <= 81920, "four stages, two workgroups per compute unit");
+  __shared__ __attribute__((aligned(16))) char lds[4 * ST];
+
+  // An XCD gets a contiguous run of tiles (column tiles fastest): tiles sharing a row slab of
+  // P share an L2.
+  const int block = blockIdx.x;
+  const int ntiles = a.tiles_m * a.tiles_n;
+  const int tile = (block & 7) * ((ntiles + 7) >> 3) + (block >> 3);
+  if (tile >= ntiles) return;
+  const int row0 = (tile / a.tiles_n) * BM;
+  const int col0 = (tile % a.tiles_n) * BN;
+  const int nk = (a.kc + 31) >> 5;                           // stages
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const u32x4 rp = raw_rsrc(a.P, a.p_bytes), rq = raw_rsrc(a.Q, a.q_bytes);
+  const unsigned lds0 = (unsigned)(uintptr_t)(lds_ptr_t)lds;
+
+  // Global side of the loads.  P instruction q of this wavefront fills rows 32 (wave + 4 q) ..
+  // +31 of the stage, 32 bytes each: lane -> row lane/2, slot lane%2, which holds the 16-byte
+  // unit slot ^ ((row / 8) % 2).  Q instruction q fills rows 16 (wave + 4 q) .. +15, 64 bytes
+  // each: lane -> row lane/4, slot lane%4, holding the 16-byte chunk slot ^ ((row / 4) % 4).
+  // With these permutations the fragment reads below (32 consecutive rows, one unit or chunk)
+  // touch every bank equally.
+  int pv[PI], qv[QI];
+#pragma unroll
+  for (int q = 0; q < PI; ++q) {
+    const int row = 32 * (wave + 4 * q) + (lane >> 1);
+    const int unit = (lane & 1) ^ ((row >> 3) & 1);
+    pv[q] = row0 + row < a.rows ? (row0 + row) * a.ldp + unit * 16 : OOB;
+  }
+#pragma unroll
+  for (int q = 0; q < QI; ++q) {
+    const int row = 16 * (wave + 4 * q) + (lane >> 2);
+    const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+    qv[q] = ((col0 + row) * a.ldq + chunk * 8) * 2;
+  }
+  // Stage kt into buffer `buf`.  Beyond the contraction range the descriptors get size 0:
+  // the instruction count (which the vmcnt waits rely on) stays the same, nothing is fetched.
+  auto issue = [&](int kt_any, int buf) {
+    const int kt = __builtin_amdgcn_readfirstlane(kt_any);   // uniform; keeps the offsets scalar
+    u32x4 p = rp, qr = rq;
+    if (kt >= nk) p.z = qr.z = 0;
+    const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + buf * ST + 1024 * wave);
+#pragma unroll
+    for (int q = 0; q < PI; ++q) load_to_lds_b128(p, dst + 4096 * q, pv[q], kt * 32);
+#pragma unroll
+    for (int q = 0; q < QI; ++q) load_to_lds_b128(qr, dst + PT + 4096 * q, qv[q], kt * 64);
+  };
+
+  // LDS side of the fragment reads: lane half h reads P unit h (16 k, two MFMA steps' worth)
+  // and, for step s, Q chunk 2h + s.  Rows 32 apart share the permutation.
+  const int h = lane >> 5;
+  int fa, fb[2];
+  {
+    const int ra = wm * TM * 32 + (lane & 31), rb = wn * TN * 32 + (lane & 31);
+    fa = ra * 32 + ((h ^ ((ra >> 3) & 1)) << 4);
+#pragma unroll
+    for (int st = 0; st < 2; ++st) fb[st] = PT + rb * 64 + (((2 * h + st) ^ ((rb >> 2) & 3)) << 4);
+  }
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  typedef u32x4 frag_t;
+  auto read_first = [&](int buf, frag_t (&pa)[TM], frag_t (&qb)[TN]) {   // P bytes of a stage, Q of its step 0
+    const char *st = lds + buf * ST;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) pa[i] = *(const frag_t *)(st + fa + i * 1024);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) qb[j] = *(const frag_t *)(st + fb[0] + j * 2048);
+  };
+  auto products = [&](const frag_t (&pa)[TM], const frag_t (&qb)[TN], int st) {
+    bf16x8 af[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const uint32_t w0 = pa[i][2 * st], w1 = pa[i][2 * st + 1];
+      u32x4 d;
+      d.x = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w0, 0x0C010C00u));
+      d.y = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w0, 0x0C030C02u));
+      d.z = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w1, 0x0C010C00u));
+      d.w = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w1, 0x0C030C02u));
+      af[i] = __builtin_bit_cast(bf16x8, d);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, qb[j]), af[i], acc[i][j], 0, 0, 0);
+  };
+  // One stage in buffer u.  On entry the stage's P bytes (pa) and step-0 Q fragments (qb) are
+  // in registers (or on their way).  The barrier sits between the two MFMA steps: past it,
+  // every wavefront has left stage kt-1 (its buffer, u+3, may be overwritten: the loads of
+  // stage kt+3 go there) and has seen its own loads of stage kt+1 land (so buffer u+1 is
+  // complete and its first fragments can be read under the MFMAs of step 1).
+  auto stage = [&](int u, int kt, frag_t (&pa)[TM], frag_t (&qb)[TN], frag_t (&pa_next)[TM], frag_t (&qb_next)[TN]) {
+    frag_t q1[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) q1[j] = *(const frag_t *)(lds + u * ST + fb[1] + j * 2048);
+    products(pa, qb, 0);
+    // (ties the accumulators to this point: the MFMAs of step 0 are issued before the waits,
+    // not moved behind the barrier by the scheduler)
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(acc[i][j]));
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NL) : "memory");   // stage kt+2 may still be in flight
+    lds_barrier();
+    issue(kt + 3, (u + 3) & 3);
+    read_first((u + 1) & 3, pa_next, qb_next);
+    products(pa, q1, 1);
+  };
+
+  issue(0, 0);
+  issue(1, 1);
+  issue(2, 2);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NL) : "memory");
+  lds_barrier();
+  frag_t pa0[TM], qb0[TN], pa1[TM], qb1[TN];
+  read_first(0, pa0, qb0);
+  for (int kt = 0; kt < nk; kt += 4) {
+    stage(0, kt, pa0, qb0, pa1, qb1);
+    if (kt + 1 >= nk) break;
+    stage(1, kt + 1, pa1, qb1, pa0, qb0);
+    if (kt + 2 >= nk) break;
+    stage(2, kt + 2, pa0, qb0, pa1, qb1);
+    if (kt + 3 >= nk) break;
+    stage(3, kt + 3, pa1, qb1, pa0, qb0);
+  }
+  // The loads beyond the range wrote zeros: they too are over before the buffers are reused.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  lds_barrier();
+
+  // Epilogue.  The MFMAs take Q as their first operand, so a tile comes out transposed: the
+  // lane holds row (lane & 31) of C and register r holds column 8*(r/4) + 4*(lane/32) + (r%4),
+  // four consecutive columns per register quad.  The quads go to LDS (the stages are free
+  // now; 16 rows of the tile fit one) and come back as whole rows, so that every store
+  // instruction writes full, consecutive cache lines: row-per-register stores (two 128-byte
+  // pieces per instruction) cost four times the instructions, and 16-byte stores straight
+  // from the quads scatter 32-byte pieces over 32 rows, which slowed the loads of the
+  // neighbouring workgroup.  The LDS row pitch of BN*4 + 16 bytes spreads the 16-byte writes
+  // of 16 consecutive rows over all banks.
+  static_assert(WM == 2 && WN == 2, "stage 2 wm + (row / 16) takes 16 rows");
+  constexpr int CP = BN * 4 + 16;                     // bytes between rows of C in LDS
+  static_assert(16 * CP <= ST, "16 rows of C fit a stage");
+  constexpr int LPR = BN / 4;                         // lanes per row of the tile when storing
+  constexpr int RPI = 64 / LPR;                       // rows per store instruction
+  const rsrc_t rc = make_rsrc(a.C, (unsigned)((size_t)a.rows * a.ldc * 4));
+  char *mine = lds + (2 * wm + ((lane >> 4) & 1)) * ST + (lane & 15) * CP;   // where this lane's quads go
+  const char *from = lds + wave * ST;                                        // whose rows this wavefront stores
+  const int srow = lane / LPR, scol = (lane % LPR) * 4;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        u32x4 v;
+        v.x = __float_as_uint(acc[i][j][4 * q]);
+        v.y = __float_as_uint(acc[i][j][4 * q + 1]);
+        v.z = __float_as_uint(acc[i][j][4 * q + 2]);
+        v.w = __float_as_uint(acc[i][j][4 * q + 3]);
+        *(u32x4 *)(mine + ((wn * TN + j) * 32 + 8 * q + 4 * h) * 4) = v;
+      }
+    lds_barrier();
+#pragma unroll
+    for (int t = 0; t < 16; t += RPI) {
+      const u32x4 v = *(const u32x4 *)(from + (srow + t) * CP + scol * 4);
+      const int row = row0 + ((wave >> 1) * TM + i) * 32 + 16 * (wave & 1) + srow + t, col = col0 + scol;
+      st_b128(rc, row < a.rows && col < a.ldc ? (row * a.ldc + col) * 4 : OOB, 0, v);
+    }
+    if (i + 1 < TM) lds_barrier();                    // the rows are read before the next quads land
+  }
+}
+
+template <int WM, int WN, int TM, int TN>
+static hipError_t spike_gemm_launch(GemmArgs a, hipStream_t st) {
+  dim3 grid(gemm_prepare<WM, WN, TM, TN>(a, 1), 1, 1);
+  hipLaunchKernelGGL((spike_gemm_kernel<WM, WN, TM, TN>), grid, dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace snn

@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "gemm.cuh"
+#include "gemm_stream.cuh"
 #include "scan.cuh"
 #include "rlif.cuh"
 
@@ -330,6 +331,11 @@ SpikeSrc spikes_below(snn_ctx *c, int l) {
   return {c->layers[l - 1].S, c->layers[l - 1].ld, c->layers[l - 1].ld, (unsigned)(c->M * c->layers[l - 1].ld)};
 }
 
+static bool stream_gemm() {
+  static const int v = [] { const char *e = getenv("SNN_STREAM_GEMM"); return e ? atoi(e) : 1; }();
+  return v != 0;
+}
+
 // I^l = S^{l-1} W^l over all T*B rows at once.
 int launch_current_gemm(snn_ctx *c, int l) {
   Layer &y = c->layers[l];
@@ -353,6 +359,8 @@ int launch_current_gemm(snn_ctx *c, int l) {
   } else {
     if (y.N <= 32) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 4, 1, 1, 1, 1, 1>(a, 1, c->stream);
     else if (y.N <= 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 1, 1, 1>(a, 1, c->stream);
+    else if (bm == 128 && y.N >= 256 && stream_gemm()) e = spike_gemm_launch<2, 2, 2, 4>(a, c->stream);
+    else if (bm == 128 && stream_gemm()) e = spike_gemm_launch<2, 2, 2, 2>(a, c->stream);
     else if (bm == 128 && y.N >= 256) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 4, 1, 1>(a, 1, c->stream);
     else if (bm == 128) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 2, 1, 1>(a, 1, c->stream);
     else if (bm == 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 1, 2, 1, 1>(a, 1, c->stream);
