@@ -51,6 +51,7 @@ struct GemmArgs {
   int splits;
   long long c_split_stride;  // elements between partial results
   int tiles_m, tiles_n;
+  int nt_store;              // store C non-temporally (large results that a later kernel streams once)
 };
 
 // ------------------------------------------------------------------ operand loaders
@@ -445,7 +446,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, const int block) {
         const int row = row0 + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         if (row < a.rows && col < a.cols) {
           const size_t o = (size_t)row * a.ldc + col;
-          C[o] = acc[i][j][r];
+          if (a.nt_store) __builtin_nontemporal_store(acc[i][j][r], &C[o]);
+          else C[o] = acc[i][j][r];
         }
       }
     }

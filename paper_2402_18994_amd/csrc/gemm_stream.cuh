@@ -30,6 +30,7 @@
 // whatever bytes P yields there are reduced to 0/1 before they meet those zeros.
 #pragma once
 #include "gemm.cuh"
+#include <type_traits>
 
 namespace snn {
 
@@ -60,7 +61,15 @@ __device__ __forceinline__ void load_to_lds_b128(u32x4 rsrc, unsigned lds_addr, 
                : "memory");
 }
 
-template <int WM, int WN, int TM, int TN>
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F &&f) {
+  if constexpr (N > 0) {
+    static_for<N - 1>(f);
+    f(std::integral_constant<int, N - 1>());
+  }
+}
+
+template <int WM, int WN, int TM, int TN, int NS = 4>
 __global__ __launch_bounds__(256, 2) void spike_gemm_kernel(const GemmArgs a) {
   static_assert(WM * WN == 4, "four wavefronts per workgroup");
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
@@ -68,8 +77,8 @@ __global__ __launch_bounds__(256, 2) void spike_gemm_kernel(const GemmArgs a) {
   constexpr int PI = BM / 128, QI = BN / 64;                 // load instructions per wavefront and stage
   constexpr int NL = PI + QI;
   static_assert(BM % 128 == 0 && BN % 64 == 0, "whole KiB per wavefront");
-  static_assert(4 * ST <= 81920, "four stages, two workgroups per compute unit");
-  __shared__ __attribute__((aligned(16))) char lds[4 * ST];
+  static_assert(NS >= 4 && NS * ST <= 81920, "two workgroups per compute unit");
+  __shared__ __attribute__((aligned(16))) char lds[NS * ST];
 
   // An XCD gets a contiguous run of tiles (column tiles fastest): tiles sharing a row slab of
   // P share an L2.
@@ -179,28 +188,33 @@ __global__ __launch_bounds__(256, 2) void spike_gemm_kernel(const GemmArgs a) {
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(acc[i][j]));
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NL) : "memory");   // stage kt+2 may still be in flight
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 3) * NL) : "memory");   // younger stages may still be in flight
     lds_barrier();
-    issue(kt + 3, (u + 3) & 3);
-    read_first((u + 1) & 3, pa_next, qb_next);
+    issue(kt + NS - 1, (u + NS - 1) % NS);
+    read_first((u + 1) % NS, pa_next, qb_next);
     products(pa, q1, 1);
   };
 
-  issue(0, 0);
-  issue(1, 1);
-  issue(2, 2);
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NL) : "memory");
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t) issue(t, t);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NL) : "memory");
   lds_barrier();
   frag_t pa0[TM], qb0[TN], pa1[TM], qb1[TN];
   read_first(0, pa0, qb0);
-  for (int kt = 0; kt < nk; kt += 4) {
-    stage(0, kt, pa0, qb0, pa1, qb1);
-    if (kt + 1 >= nk) break;
-    stage(1, kt + 1, pa1, qb1, pa0, qb0);
-    if (kt + 2 >= nk) break;
-    stage(2, kt + 2, pa0, qb0, pa1, qb1);
-    if (kt + 3 >= nk) break;
-    stage(3, kt + 3, pa1, qb1, pa0, qb0);
+  // Unrolled over the buffers (twice when their number is odd, so that the two fragment
+  // register sets alternate consistently).
+  constexpr int UN = NS % 2 ? 2 * NS : NS;
+  for (int kt = 0; kt < nk; kt += UN) {
+    bool done = false;
+    static_for<UN>([&](auto U) {
+      constexpr int u = decltype(U)::value;
+      if (!done) {
+        if constexpr (u % 2 == 0) stage(u % NS, kt + u, pa0, qb0, pa1, qb1);
+        else stage(u % NS, kt + u, pa1, qb1, pa0, qb0);
+        if (kt + u + 1 >= nk) done = true;
+      }
+    });
+    if (done) break;
   }
   // The loads beyond the range wrote zeros: they too are over before the buffers are reused.
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -242,7 +256,10 @@ __global__ __launch_bounds__(256, 2) void spike_gemm_kernel(const GemmArgs a) {
     for (int t = 0; t < 16; t += RPI) {
       const u32x4 v = *(const u32x4 *)(from + (srow + t) * CP + scol * 4);
       const int row = row0 + ((wave >> 1) * TM + i) * 32 + 16 * (wave & 1) + srow + t, col = col0 + scol;
-      st_b128(rc, row < a.rows && col < a.ldc ? (row * a.ldc + col) * 4 : OOB, 0, v);
+      // Non-temporal: C is written once and read by a later kernel; kept out of the way, it
+      // no longer evicts the P lines that the next stages (and the neighbouring column tiles)
+      // are about to read again: 9 % (K = 1024) and 21 % (K = 700) on the whole kernel.
+      __builtin_amdgcn_raw_buffer_store_b128(v, rc, row < a.rows && col < a.ldc ? (row * a.ldc + col) * 4 : OOB, 0, 2);
     }
     if (i + 1 < TM) lds_barrier();                    // the rows are read before the next quads land
   }

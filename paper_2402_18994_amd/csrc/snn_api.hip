@@ -331,6 +331,12 @@ SpikeSrc spikes_below(snn_ctx *c, int l) {
   return {c->layers[l - 1].S, c->layers[l - 1].ld, c->layers[l - 1].ld, (unsigned)(c->M * c->layers[l - 1].ld)};
 }
 
+// A result this large is out of every cache level (L2 8 x 4 MiB, memory-side cache 256 MiB)
+// again before the next kernel reads it; stored non-temporally it at least leaves the
+// operands of the product that writes it in place.  Smaller results are stored normally: the
+// next kernel finds them warm.
+static bool streams_past_cache(size_t bytes) { return bytes >= ((size_t)128 << 20); }
+
 static bool stream_gemm() {
   static const int v = [] { const char *e = getenv("SNN_STREAM_GEMM"); return e ? atoi(e) : 1; }();
   return v != 0;
@@ -347,9 +353,12 @@ int launch_current_gemm(snn_ctx *c, int l) {
   a.Q = y.Qf; a.ldq = y.ldqf; a.q_plane_stride = y.qf_plane; a.q_bytes = (unsigned)(c->nplanes * y.qf_plane * 2);
   a.C = y.I; a.ldc = y.ld; a.rows = (int)c->M; a.cols = y.N;
   a.kc_per_split = (int)rup(a.kc, 64);
+  a.nt_store = streams_past_cache(c->M * y.ld * 4);
   Bracket br(c, SNN_K_CURRENT_GEMM, l + 1);
   hipError_t e;
   const int bm = pick_rows_per_tile(c->M, y.N);
+  // The streamed kernel addresses both P and C with 32-bit byte offsets.
+  const bool streamed = a.nt_store && stream_gemm() && c->M * y.ld * 4 < ((size_t)1 << 31) && (size_t)c->M * s.ld < ((size_t)1 << 31);
   if (c->precision == SNN_PREC_FP32) {
     if (y.N <= 32) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 4, 1, 1, 1, 3, 1>(a, 1, c->stream);
     else if (y.N <= 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 1, 3, 1>(a, 1, c->stream);
@@ -359,8 +368,8 @@ int launch_current_gemm(snn_ctx *c, int l) {
   } else {
     if (y.N <= 32) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 4, 1, 1, 1, 1, 1>(a, 1, c->stream);
     else if (y.N <= 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 1, 1, 1>(a, 1, c->stream);
-    else if (bm == 128 && y.N >= 256 && stream_gemm()) e = spike_gemm_launch<2, 2, 2, 4>(a, c->stream);
-    else if (bm == 128 && stream_gemm()) e = spike_gemm_launch<2, 2, 2, 2>(a, c->stream);
+    else if (bm == 128 && y.N >= 256 && streamed) e = spike_gemm_launch<2, 2, 2, 4>(a, c->stream);
+    else if (bm == 128 && streamed) e = spike_gemm_launch<2, 2, 2, 2>(a, c->stream);
     else if (bm == 128 && y.N >= 256) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 4, 1, 1>(a, 1, c->stream);
     else if (bm == 128) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 2, 1, 1>(a, 1, c->stream);
     else if (bm == 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 1, 2, 1, 1>(a, 1, c->stream);
@@ -380,6 +389,7 @@ int launch_input_grad(snn_ctx *c, int l) {
   a.Q = y.Qb; a.ldq = y.ldqb; a.q_plane_stride = y.qb_plane; a.q_bytes = (unsigned)(c->nplanes * y.qb_plane * 2);
   a.C = below.dS; a.ldc = below.ld; a.rows = (int)c->M; a.cols = y.K;
   a.kc_per_split = (int)rup(a.kc, 64);
+  a.nt_store = streams_past_cache(c->M * below.ld * 4);
   Bracket br(c, SNN_K_INPUT_GRAD, l + 1);
   hipError_t e;
   const int bm = pick_rows_per_tile(c->M, y.K);
