@@ -533,8 +533,13 @@ hipError_t lif_fwd_launch(snn_ctx *c, Layer &y) {
   const int stride = c->B * y.ld;               // T * stride * 4 < 2 GiB was checked at init
   const int threads = stride / VEC;
   const int bs = scan_block(threads);
-  hipLaunchKernelGGL((lif_forward_kernel<VEC, U>), dim3((unsigned)((threads + bs - 1) / bs)), dim3(bs), 0, c->stream,
-                     y.I, y.V, y.S, c->T, stride, y.beta_v, y.ld, c->theta);
+  const dim3 grid((unsigned)((threads + bs - 1) / bs)), block(bs);
+  if (streams_past_cache(c->M * y.ld * 4))
+    hipLaunchKernelGGL((lif_forward_kernel<VEC, U, NT>), grid, block, 0, c->stream, y.I, y.V, y.S, c->T, stride,
+                       y.beta_v, y.ld, c->theta);
+  else
+    hipLaunchKernelGGL((lif_forward_kernel<VEC, U, 0>), grid, block, 0, c->stream, y.I, y.V, y.S, c->T, stride,
+                       y.beta_v, y.ld, c->theta);
   return hipGetLastError();
 }
 
@@ -562,9 +567,16 @@ hipError_t lif_rev_launch2(snn_ctx *c, Layer &y) {
   const int threads = stride / VEC;
   const int bs = scan_block(threads);
   dim3 grid((unsigned)((threads + bs - 1) / bs)), block(bs);
-#define SNN_REV(SU)                                                                                          \
-  hipLaunchKernelGGL((lif_reverse_kernel<VEC, U, SU, HL>), grid, block, 0, c->stream, y.dS, y.V, y.dI, c->T, \
-                     stride, y.beta_v, y.ld, c->theta, c->slope, y.part_b)
+  const bool nt = streams_past_cache(c->M * y.ld * 4);
+#define SNN_REV(SU)                                                                                              \
+  do {                                                                                                           \
+    if (nt)                                                                                                      \
+      hipLaunchKernelGGL((lif_reverse_kernel<VEC, U, SU, HL, NT>), grid, block, 0, c->stream, y.dS, y.V, y.dI, c->T, \
+                         stride, y.beta_v, y.ld, c->theta, c->slope, y.part_b);                                  \
+    else                                                                                                         \
+      hipLaunchKernelGGL((lif_reverse_kernel<VEC, U, SU, HL, 0>), grid, block, 0, c->stream, y.dS, y.V, y.dI, c->T,  \
+                         stride, y.beta_v, y.ld, c->theta, c->slope, y.part_b);                                  \
+  } while (0)
   switch (c->surrogate) {
     case 0: SNN_REV(0); break;
     case 1: SNN_REV(1); break;
