@@ -259,7 +259,9 @@ __global__ __launch_bounds__(256, 2) void spike_gemm_kernel(const GemmArgs a) {
       // Non-temporal: C is written once and read by a later kernel; kept out of the way, it
       // no longer evicts the P lines that the next stages (and the neighbouring column tiles)
       // are about to read again: 9 % (K = 1024) and 21 % (K = 700) on the whole kernel.
-      __builtin_amdgcn_raw_buffer_store_b128(v, rc, row < a.rows && col < a.ldc ? (row * a.ldc + col) * 4 : OOB, 0, 2);
+      const int vo = row < a.rows && col < a.ldc ? (row * a.ldc + col) * 4 : OOB;
+      if (a.nt_store) __builtin_amdgcn_raw_buffer_store_b128(v, rc, vo, 0, NT);
+      else __builtin_amdgcn_raw_buffer_store_b128(v, rc, vo, 0, 0);
     }
     if (i + 1 < TM) lds_barrier();                    // the rows are read before the next quads land
   }

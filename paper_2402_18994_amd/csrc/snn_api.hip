@@ -160,8 +160,9 @@ int wgrad_tiles(int rows, int cols, bool tall) {
 // Rows of C per workgroup for the products over all T*B rows whose output is wider than 64
 // columns: the tallest tile that still gives every compute unit a few workgroups.
 int pick_rows_per_tile(long long rows, int cols) {
-  static const int forced = [] { const char *e = getenv("SNN_TILE_ROWS"); return e ? atoi(e) : 0; }();
-  if (forced == 32 || forced == 64 || forced == 128) return forced;     // tuning knob
+  const char *e = getenv("SNN_TILE_ROWS");                              // tuning and test knob, read per call
+  const int forced = e ? atoi(e) : 0;
+  if (forced == 32 || forced == 64 || forced == 128) return forced;
   const long long col_tiles = (cols + 127) / 128;
   if ((rows + 127) / 128 * col_tiles >= 512) return 128;
   if ((rows + 63) / 64 * col_tiles >= 512) return 64;
@@ -335,11 +336,15 @@ SpikeSrc spikes_below(snn_ctx *c, int l) {
 // again before the next kernel reads it; stored non-temporally it at least leaves the
 // operands of the product that writes it in place.  Smaller results are stored normally: the
 // next kernel finds them warm.
-static bool streams_past_cache(size_t bytes) { return bytes >= ((size_t)128 << 20); }
+// (SNN_STREAM_MIN_MB moves the limit; the tests set it to 0 to run these paths on small shapes.)
+static bool streams_past_cache(size_t bytes) {
+  const char *e = getenv("SNN_STREAM_MIN_MB");
+  return bytes >= ((size_t)(e ? atoi(e) : 128) << 20);
+}
 
 static bool stream_gemm() {
-  static const int v = [] { const char *e = getenv("SNN_STREAM_GEMM"); return e ? atoi(e) : 1; }();
-  return v != 0;
+  const char *e = getenv("SNN_STREAM_GEMM");
+  return !e || atoi(e) != 0;
 }
 
 // I^l = S^{l-1} W^l over all T*B rows at once.

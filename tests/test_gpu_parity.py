@@ -95,6 +95,35 @@ def test_multi_tile_fp32_theta_not_one():
     assert rep["spike_rate"][1] > 0.005
 
 
+@pytest.fixture
+def large_tensor_paths(monkeypatch):
+    """The kernels chosen for tensors that stream past the caches (the streamed current product,
+    non-temporal scan loads and product stores) on shapes an element-by-element oracle run can
+    cover: the library reads these two knobs at every launch."""
+    monkeypatch.setenv("SNN_STREAM_MIN_MB", "0")
+    monkeypatch.setenv("SNN_TILE_ROWS", "128")
+
+
+@pytest.mark.parametrize("sizes", [(100, 200, 136, 10), (300, 330, 260, 20)], ids=["narrow-tiles", "wide-tiles"])
+def test_large_tensor_paths_ragged(large_tensor_paths, sizes):
+    """Streamed current product with partial row tiles (T*B = 437), partial column tiles, a
+    contraction that is neither a multiple of 32 nor of 16 bytes per row, and both tile widths;
+    scans with non-temporal loads."""
+    wl = workloads.Workload(name="streamed-ragged", index=13, T=19, B=23, sizes=sizes,
+                            recurrent=(False, False), beta=(0.92, 0.9, 0.95), theta=1.0, surrogate="superspike",
+                            slope=10.0, precision="bf16", rate_lo=0.02, rate_hi=0.1)
+    rep = full_step_parity(wl, w_gain=2.0)
+    assert rep["spike_rate"][1] > 0.005
+
+
+def test_large_tensor_paths_single_stage(large_tensor_paths):
+    """Contractions shorter than the pipeline: 20 inputs (one stage of the four) and 40 (two)."""
+    wl = workloads.Workload(name="streamed-short", index=14, T=16, B=16, sizes=(20, 130, 40, 140, 5),
+                            recurrent=(False, False, False), beta=(0.9, 0.9, 0.9, 0.9), theta=1.0,
+                            surrogate="arctan", slope=2.0, precision="bf16", rate_lo=0.1, rate_hi=0.3)
+    full_step_parity(wl, w_gain=2.5)
+
+
 def sampled_parity(wl, w_gain, n_samples=6, **tols):
     """Full-size run of a configuration too large for a whole-batch oracle; see
     parity.sampled_step_parity for what is compared."""
