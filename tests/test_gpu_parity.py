@@ -374,6 +374,14 @@ def test_wide_ff1024_full_size_sampled():
     assert rep["spike_rate"][0] > 0.005 and rep["spike_rate"][1] > 0.005
 
 
+@pytest.mark.parametrize("name", ["table1_ff128", "table1_ff512"])
+def test_table1_shapes_full_size_sampled(name):
+    """The shapes of the paper's timing runs (Table 1); at width 512 the tensors are 134 MB, the
+    smallest size that takes the large-tensor kernel paths by itself."""
+    rep = sampled_parity(workloads.CONFIGS[name], w_gain=3.0)
+    assert rep["spike_rate"][0] > 0.005 and rep["spike_rate"][1] > 0.005
+
+
 def test_deep_rec2048_full_size_sampled():
     """fp32 state with a fan-in of 2048 (+2048 recurrent) and a memory of 1/(1-beta) = 33 steps:
     the rounding of the device's fp32 sums against the fp64 oracle reaches 1.3e-5 on a few of

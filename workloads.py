@@ -78,6 +78,12 @@ CONFIGS = {
     # 5: deep, long horizon, first hidden layer recurrent
     "deep_rec2048": _wl("deep_rec2048", 5, 512, 128, (700, 2048, 2048, 2048, 20),
                         (1, 0, 0), 0.97, "arctan", 2.0, "bf16"),
+    # beyond the five configurations: the shapes of the paper's own timing runs (Table 1: hidden
+    # width 128 or 512, rasters of 256 steps, batch 256), with the input statistics of config 2
+    "table1_ff128": _wl("table1_ff128", 6, 256, 256, (700, 128, 128, 20), (0, 0), 0.95,
+                        "superspike", 25.0, "bf16"),
+    "table1_ff512": _wl("table1_ff512", 7, 256, 256, (700, 512, 512, 20), (0, 0), 0.95,
+                        "superspike", 25.0, "bf16"),
 }
 CONFIG_ORDER = ["tiny_ff", "shd_ff128", "shd_rec128", "wide_ff1024", "deep_rec2048"]
 
