@@ -95,6 +95,17 @@ def test_multi_tile_fp32_theta_not_one():
     assert rep["spike_rate"][1] > 0.005
 
 
+@pytest.mark.parametrize("recurrent", [(False, False), (True, False)], ids=["ff", "rec"])
+def test_non_leaky_neurons(recurrent):
+    """beta = 1: integrate-and-fire hidden neurons (Section 2.2 names non-leaking neurons) and a
+    pure integrator as readout; the end of the decay range the library accepts."""
+    wl = workloads.Workload(name="if-neurons", index=15, T=33, B=20, sizes=(100, 96, 72, 10),
+                            recurrent=recurrent, beta=(1.0, 1.0, 1.0), theta=1.0, surrogate="arctan",
+                            slope=2.0, precision="fp32", rate_lo=0.02, rate_hi=0.08)
+    rep = full_step_parity(wl, w_gain=1.5)
+    assert rep["spike_rate"][0] > 0.005
+
+
 @pytest.fixture
 def large_tensor_paths(monkeypatch):
     """The kernels chosen for tensors that stream past the caches (the streamed current product,
