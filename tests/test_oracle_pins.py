@@ -39,6 +39,33 @@ def test_worked_example_constant_current():
         assert tr.S[0][int(t), 0, 0] == float(s)
 
 
+@pytest.mark.parametrize("c_num,c_den,theta_num", [(3, 8, 1), (7, 16, 1), (5, 8, 2), (9, 8, 1), (1, 4, 1)])
+def test_non_leaky_neuron_exact_rational(c_num, c_den, theta_num):
+    """beta = 1 (integrate and fire, Section 2.2's non-leaking neuron): under a constant current
+    the potential stays a multiple of 1/c_den, so Eq. 1-2 can be iterated in exact rational
+    arithmetic; the currents are dyadic, so the float recursion has to agree exactly, ties at the
+    threshold (strict inequality: no spike at V = theta, which c = 1/4 reaches) included.  The
+    long-run firing rate is c/theta when the reset keeps up (c <= theta); with c > theta the
+    neuron fires at every step and the potential grows by c - theta per step."""
+    from fractions import Fraction
+    T = 120
+    c, theta = Fraction(c_num, c_den), Fraction(theta_num)
+    net, X, W, R, lab = single_neuron(1.0, float(theta), float(c), T)
+    tr = O.forward(net, X, W, R, lab)
+    v, spikes = Fraction(0), []
+    for t in range(T):
+        s = 1 if v > theta else 0
+        spikes.append(s)
+        assert tr.S[0][t, 0, 0] == s
+        assert tr.V[0][t, 0, 0] == float(v)
+        v = v + c - theta * s
+    if c <= theta:
+        assert abs(sum(spikes) / T - float(c / theta)) <= 2.0 / T
+    else:
+        assert sum(spikes) == T - 1            # S_0 = 0 (V_0 = 0), then every step
+        assert tr.V[0][-1, 0, 0] == pytest.approx(float(c + (T - 2) * (c - theta)))
+
+
 @pytest.mark.parametrize("beta,theta,c", [(0.9, 1.0, 0.3), (0.95, 1.0, 0.08), (0.8, 2.0, 0.5),
                                           (0.9, 1.0, 0.1001), (0.9, 1.0, 0.0999), (0.5, 1.0, 3.0)])
 def test_first_spike_time_closed_form(beta, theta, c):
