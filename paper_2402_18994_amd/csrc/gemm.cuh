@@ -164,25 +164,28 @@ template <int ROWS, bool HL> struct LoaderPWord {
 template <int ROWS> struct LoaderP<P_HL, ROWS> : LoaderPWord<ROWS, true> {};
 template <int ROWS> struct LoaderP<P_F32S, ROWS> : LoaderPWord<ROWS, false> {};
 
-// P[m][i] bytes, contraction index m slowest.  One unit = 8 consecutive m x 4 consecutive i.
+// P[m][i] bytes, contraction index m slowest.  One unit = 8 consecutive m x 8 consecutive i:
+// eight 8-byte loads, one per row (a wavefront's loads of one row cover 256 consecutive bytes),
+// transposed in registers into eight 16-byte LDS writes.
 template <int ROWS> struct LoaderP<P_T_U8, ROWS> {
   static constexpr int PLANES = 1;
-  static constexpr int UNITS = ROWS * 2;                  // (ROWS/4) column groups x 8 m groups
+  static constexpr int UNITS = ROWS;                      // (ROWS/8) column groups x 8 m groups
   static constexpr int UP = (UNITS + 255) / 256;
-  int voff[UP], loff[UP][4], mrow[UP];
-  uint32_t raw[UP][8];
+  int voff[UP], loff[UP][8], mrow[UP];
+  u32x2 raw[UP][8];
   // Rows are 4-byte aligned and the number of valid columns is a multiple of 4 (the host pads
-  // the raster otherwise): one dword load per row, no branches.
+  // the raster otherwise): no branches.  A unit that straddles the last valid column reads
+  // what follows it in memory; those bytes only reach rows of the product that are not stored.
   __device__ __forceinline__ void setup(const GemmArgs &a, int row0, int tid) {
 #pragma unroll
     for (int c = 0; c < UP; ++c) {
       const int u = tid + 256 * c;
-      const int ig = u % (ROWS / 4), mg = u / (ROWS / 4);
-      const int i = row0 + 4 * ig;
+      const int ig = u % (ROWS / 8), mg = u / (ROWS / 8);
+      const int i = row0 + 8 * ig;
       voff[c] = (u < UNITS && i < a.p_ivalid) ? 8 * mg * a.ldp + i : OOB;
       mrow[c] = 8 * mg;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) loff[c][e] = tile_off((4 * ig + e) & (ROWS - 1), mg & 7);
+      for (int e = 0; e < 8; ++e) loff[c][e] = tile_off((8 * ig + e) & (ROWS - 1), mg & 7);
     }
   }
   __device__ __forceinline__ void load(const GemmArgs &a, rsrc_t rs, int k0, int kend) {
@@ -190,7 +193,7 @@ template <int ROWS> struct LoaderP<P_T_U8, ROWS> {
     for (int c = 0; c < UP; ++c) {
 #pragma unroll
       for (int r = 0; r < 8; ++r)
-        raw[c][r] = ld_b32(rs, k0 + mrow[c] + r >= kend ? OOB : voff[c], (k0 + r) * a.ldp);
+        raw[c][r] = ld_b64(rs, k0 + mrow[c] + r >= kend ? OOB : voff[c], (k0 + r) * a.ldp);
     }
   }
   __device__ __forceinline__ void store(char *tile, int tid) {
@@ -198,14 +201,15 @@ template <int ROWS> struct LoaderP<P_T_U8, ROWS> {
     for (int c = 0; c < UP; ++c) {
       if (tid + 256 * c < UNITS) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          // byte e of raw[2h] -> bits 0..7, byte e of raw[2h+1] -> bits 16..23
-          const uint32_t sel = 0x0C000C00u | ((4u + e) << 16) | (uint32_t)e;
+        for (int e = 0; e < 8; ++e) {
+          // byte e%4 of word e/4: of row 2h -> bits 0..7, of row 2h+1 -> bits 16..23
+          const uint32_t sel = 0x0C000C00u | ((4u + (e & 3)) << 16) | (uint32_t)(e & 3);
+          const int w = e >> 2;
           uint4 d;
-          d.x = spikes2_to_bf16(__builtin_amdgcn_perm(raw[c][1], raw[c][0], sel));
-          d.y = spikes2_to_bf16(__builtin_amdgcn_perm(raw[c][3], raw[c][2], sel));
-          d.z = spikes2_to_bf16(__builtin_amdgcn_perm(raw[c][5], raw[c][4], sel));
-          d.w = spikes2_to_bf16(__builtin_amdgcn_perm(raw[c][7], raw[c][6], sel));
+          d.x = spikes2_to_bf16(__builtin_amdgcn_perm(raw[c][1][w], raw[c][0][w], sel));
+          d.y = spikes2_to_bf16(__builtin_amdgcn_perm(raw[c][3][w], raw[c][2][w], sel));
+          d.z = spikes2_to_bf16(__builtin_amdgcn_perm(raw[c][5][w], raw[c][4][w], sel));
+          d.w = spikes2_to_bf16(__builtin_amdgcn_perm(raw[c][7][w], raw[c][6][w], sel));
           *(uint4 *)(tile + loff[c][e]) = d;
         }
       }
@@ -248,24 +252,24 @@ template <int ROWS, int NPL> struct LoaderQ<Q_BF16, ROWS, NPL> {
 };
 
 // Q[m][j] dwords, contraction index m slowest, ld a multiple of 8 with zero padding: HL words
-// (two planes) or fp32 (three planes, split here).  One unit = 8 consecutive m x 2
-// consecutive j.
+// (two planes) or fp32 (three planes, split here).  One unit = 8 consecutive m x 4
+// consecutive j: eight 16-byte loads, transposed into four 16-byte LDS writes per plane.
 template <int ROWS, bool HL> struct LoaderQTWord {
   static constexpr int PLANES = HL ? 2 : 3;
-  static constexpr int UNITS = ROWS * 4;
+  static constexpr int UNITS = ROWS * 2;
   static constexpr int UQ = (UNITS + 255) / 256;
-  int voff[UQ], loff[UQ][2], mrow[UQ];
-  u32x2 raw[UQ][8];
+  int voff[UQ], loff[UQ][4], mrow[UQ];
+  u32x4 raw[UQ][8];
   __device__ __forceinline__ void setup(const GemmArgs &a, int col0, int tid) {
 #pragma unroll
     for (int c = 0; c < UQ; ++c) {
       const int u = tid + 256 * c;
-      const int jg = u % (ROWS / 2), mg = u / (ROWS / 2);
-      const int j = col0 + 2 * jg;
+      const int jg = u % (ROWS / 4), mg = u / (ROWS / 4);
+      const int j = col0 + 4 * jg;
       voff[c] = (u < UNITS && j < a.ldq) ? (8 * mg * a.ldq + j) * 4 : OOB;
       mrow[c] = 8 * mg;
-      loff[c][0] = tile_off((2 * jg) & (ROWS - 1), mg & 7);
-      loff[c][1] = tile_off((2 * jg + 1) & (ROWS - 1), mg & 7);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) loff[c][e] = tile_off((4 * jg + e) & (ROWS - 1), mg & 7);
     }
   }
   __device__ __forceinline__ void load(const GemmArgs &a, rsrc_t rs, int k0, int kend) {
@@ -273,36 +277,31 @@ template <int ROWS, bool HL> struct LoaderQTWord {
     for (int c = 0; c < UQ; ++c)
 #pragma unroll
       for (int r = 0; r < 8; ++r)
-        raw[c][r] = ld_b64(rs, k0 + mrow[c] + r >= kend ? OOB : voff[c], (k0 + r) * a.ldq * 4);
+        raw[c][r] = ld_b128(rs, k0 + mrow[c] + r >= kend ? OOB : voff[c], (k0 + r) * a.ldq * 4);
   }
   __device__ __forceinline__ void store(char *tile, int tid) {
 #pragma unroll
     for (int c = 0; c < UQ; ++c) {
       if (tid + 256 * c < UNITS) {
 #pragma unroll
-        for (int pl = 0; pl < PLANES; ++pl) {
-          uint4 d0, d1;
-          if (HL) {
-            const uint32_t sel = pl == 0 ? 0x05040100u : 0x07060302u;
-            d0.x = __builtin_amdgcn_perm(raw[c][1].x, raw[c][0].x, sel);
-            d0.y = __builtin_amdgcn_perm(raw[c][3].x, raw[c][2].x, sel);
-            d0.z = __builtin_amdgcn_perm(raw[c][5].x, raw[c][4].x, sel);
-            d0.w = __builtin_amdgcn_perm(raw[c][7].x, raw[c][6].x, sel);
-            d1.x = __builtin_amdgcn_perm(raw[c][1].y, raw[c][0].y, sel);
-            d1.y = __builtin_amdgcn_perm(raw[c][3].y, raw[c][2].y, sel);
-            d1.z = __builtin_amdgcn_perm(raw[c][5].y, raw[c][4].y, sel);
-            d1.w = __builtin_amdgcn_perm(raw[c][7].y, raw[c][6].y, sel);
-          } else {
-#define SNN_PC(r_, f_) bf16_piece(__uint_as_float(raw[c][r_].f_), pl)
-            d0.x = pack2(SNN_PC(0, x), SNN_PC(1, x)); d0.y = pack2(SNN_PC(2, x), SNN_PC(3, x));
-            d0.z = pack2(SNN_PC(4, x), SNN_PC(5, x)); d0.w = pack2(SNN_PC(6, x), SNN_PC(7, x));
-            d1.x = pack2(SNN_PC(0, y), SNN_PC(1, y)); d1.y = pack2(SNN_PC(2, y), SNN_PC(3, y));
-            d1.z = pack2(SNN_PC(4, y), SNN_PC(5, y)); d1.w = pack2(SNN_PC(6, y), SNN_PC(7, y));
+        for (int pl = 0; pl < PLANES; ++pl)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            uint4 d;
+            if (HL) {
+              const uint32_t sel = pl == 0 ? 0x05040100u : 0x07060302u;
+              d.x = __builtin_amdgcn_perm(raw[c][1][e], raw[c][0][e], sel);
+              d.y = __builtin_amdgcn_perm(raw[c][3][e], raw[c][2][e], sel);
+              d.z = __builtin_amdgcn_perm(raw[c][5][e], raw[c][4][e], sel);
+              d.w = __builtin_amdgcn_perm(raw[c][7][e], raw[c][6][e], sel);
+            } else {
+#define SNN_PC(r_) bf16_piece(__uint_as_float(raw[c][r_][e]), pl)
+              d.x = pack2(SNN_PC(0), SNN_PC(1)); d.y = pack2(SNN_PC(2), SNN_PC(3));
+              d.z = pack2(SNN_PC(4), SNN_PC(5)); d.w = pack2(SNN_PC(6), SNN_PC(7));
 #undef SNN_PC
+            }
+            *(uint4 *)(tile + pl * ROWS * 128 + loff[c][e]) = d;
           }
-          *(uint4 *)(tile + pl * ROWS * 128 + loff[c][0]) = d0;
-          *(uint4 *)(tile + pl * ROWS * 128 + loff[c][1]) = d1;
-        }
       }
     }
   }
@@ -454,7 +453,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, const int block) {
 }
 
 template <int PM, int QM, int EPI, int WM, int WN, int TM, int TN, int NQP, int D>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a) {
   gemm_body<PM, QM, EPI, WM, WN, TM, TN, NQP, D>(a, blockIdx.x);
 }
 
@@ -469,7 +468,7 @@ struct GemmJobs {
 };
 
 template <int PM, int QM, int EPI, int WM, int WN, int TM, int TN, int NQP, int D>
-__global__ __launch_bounds__(256) void gemm_jobs_kernel(const GemmJobs jobs) {
+__global__ __launch_bounds__(256, 2) void gemm_jobs_kernel(const GemmJobs jobs) {
   int j = 0;
   while (j + 1 < jobs.njobs && (int)blockIdx.x >= jobs.first_block[j + 1]) ++j;
   gemm_body<PM, QM, EPI, WM, WN, TM, TN, NQP, D>(jobs.job[j], blockIdx.x - jobs.first_block[j]);
