@@ -56,8 +56,8 @@ def full_step_parity(wl, w_gain=1.0, lr=0.1, seed=None, grad_tol=parity.TOL_GRAD
     rep["loss"] = loss
     rep["case"] = f"{wl.name} T={wl.T} B={wl.B} {wl.precision} gain={w_gain}"
     print(json.dumps(rep), flush=True)
-    out_dir = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(out_dir):
+    out_dir = os.environ.get("SNN_PARITY_REPORT_DIR", "")      # optional: append the report to a file there
+    if out_dir and os.path.isdir(out_dir):
         with open(os.path.join(out_dir, "parity_reports.jsonl"), "a") as f:
             f.write(json.dumps(rep) + "\n")
     snn.destroy()
@@ -150,8 +150,8 @@ def sampled_parity(wl, w_gain, n_samples=6, **tols):
     rep["loss"] = loss
     rep["case"] = f"sampled {wl.name} T={wl.T} B={wl.B} {wl.precision} gain={w_gain} samples={idx.tolist()}"
     print(json.dumps(rep), flush=True)
-    out_dir = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(out_dir):
+    out_dir = os.environ.get("SNN_PARITY_REPORT_DIR", "")      # optional: append the report to a file there
+    if out_dir and os.path.isdir(out_dir):
         with open(os.path.join(out_dir, "parity_reports.jsonl"), "a") as f:
             f.write(json.dumps(rep) + "\n")
     snn.destroy()
