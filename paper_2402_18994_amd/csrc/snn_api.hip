@@ -133,18 +133,38 @@ int validate(const snn_config *cfg) {
 }
 
 // Contraction splits of the weight-gradient products, which share one launch with `tiles`
-// output tiles in total over M rows each: enough workgroups to cover the chip about twice,
-// but at least four 64-row tiles per workgroup.
-int choose_splits(long long M, int tiles, long long *per_split) {
+// output tiles in total over M rows each.  `weights`: elements of all gradient matrices (a
+// split writes that many partial sums); `row_bytes`: operand bytes the products read per row
+// of the contraction.  Measured facts behind the rule:
+//   * the splits of a tile are dealt round-robin to the 8 XCDs (see gemm_body), so a count
+//     that is not a multiple of 8 leaves some XCDs with a split more than others and the
+//     launch lasts as long as the fullest (700-512-512-20, T*B = 65536: 21 splits 253 us,
+//     24 splits 225 us, 32 splits 180 us);
+//   * 512 workgroups run at once (two per compute unit).  Slightly more than that (24 splits
+//     x 22 tiles = 528) is the worst case: the stragglers run a whole workgroup's work alone.
+//     Either everything fits at once, or there are at least 1.3 rounds of shorter workgroups;
+//   * every split writes and the reduction re-reads all partial sums: with large matrices
+//     (2048 wide: 56 MB per split) more splits cost more than they gain (64 splits: 10.2 ms
+//     against 3.3 ms with 8), and 16 splits never beat 8 at 1024 wide.
+int choose_splits(long long M, int tiles, long long weights, long long row_bytes, long long *per_split) {
   static const long long target = [] {
-    const char *e = getenv("SNN_WGRAD_WORKGROUPS");      // tuning knob; default below
+    const char *e = getenv("SNN_WGRAD_WORKGROUPS");      // tuning knob: workgroups resident at once
     long long v = e ? atoll(e) : 0;
     return v > 0 ? v : 512;
   }();
-  long long want = target / (tiles > 0 ? tiles : 1);
-  long long max_by_len = M / 256;
+  if (tiles < 1) tiles = 1;
+  const long long max_by_len = M / 256;                  // at least four 64-row tiles per workgroup
+  long long want = target / tiles;
   if (want > max_by_len) want = max_by_len;
   if (want < 1) want = 1;
+  if (want >= 8) {
+    want = want / 8 * 8;                                 // all at once, balanced over the XCDs
+    // when that leaves more than 15 % of the chip idle: more, shorter workgroups, as long as
+    // each keeps 16 tiles of the contraction and the partial sums stay below a quarter of the
+    // operand bytes
+    const long long more = ((target * 13 / 10 + tiles - 1) / tiles + 7) / 8 * 8;
+    if (want * tiles * 100 < target * 85 && M / more >= 1024 && more * weights * 4 * 4 <= M * row_bytes) want = more;
+  }
   long long per = (long long)rup((size_t)((M + want - 1) / want), 64);
   *per_split = per;
   return (int)((M + per - 1) / per);
@@ -199,6 +219,12 @@ void carve(snn_ctx &c, Carver &cv) {
   static const int tall_knob = [] { const char *e = getenv("SNN_WGRAD_TALL"); return e ? atoi(e) : -1; }();
   c.wg_tall = c.precision != SNN_PREC_FP32 && (tall_knob >= 0 ? tall_knob != 0 : count_tiles(false) >= 32);
   const int wg_tiles = count_tiles(c.wg_tall);
+  long long wg_weights = 0, wg_row_bytes = 0;             // what the merged launch writes per split / reads per row
+  for (int l = 0; l < c.L; ++l) {
+    const Layer &y = c.layers[l];
+    wg_weights += (long long)y.K * y.N + (y.recurrent ? (long long)y.N * y.N : 0);
+    wg_row_bytes += y.K + 4ll * y.N + (y.recurrent ? y.N : 0);   // spike bytes below, 4-byte current gradients
+  }
   for (int l = 0; l < c.L; ++l) {
     Layer &y = c.layers[l];
     const size_t K = y.K, N = y.N;
@@ -212,7 +238,7 @@ void carve(snn_ctx &c, Carver &cv) {
       y.qb_plane = (long long)rup(K, 128) * y.ldqb;
       y.Qb = cv.take<uint16_t>((size_t)np * y.qb_plane);
     }
-    y.splits_w = choose_splits(c.M, wg_tiles, &y.per_w);
+    y.splits_w = choose_splits(c.M, wg_tiles, wg_weights, wg_row_bytes, &y.per_w);
     if (y.splits_w > 1) y.part_w = cv.take<float>((size_t)y.splits_w * K * N);
     if (y.recurrent) {
       y.Rm = cv.take<float>(N * N);
@@ -223,7 +249,7 @@ void carve(snn_ctx &c, Carver &cv) {
       y.QRb = cv.take<uint16_t>((size_t)np * y.qr_plane);
       y.g[0] = cv.take<float>((size_t)c.B * y.ld);
       y.g[1] = cv.take<float>((size_t)c.B * y.ld);
-      y.splits_r = choose_splits(c.M, wg_tiles, &y.per_r);
+      y.splits_r = choose_splits(c.M, wg_tiles, wg_weights, wg_row_bytes, &y.per_r);
       if (y.splits_r > 1) y.part_r = cv.take<float>((size_t)y.splits_r * N * N);
     }
     y.beta_v = cv.take<float>(y.ld);
