@@ -101,7 +101,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="shd_ff128")
-    ap.add_argument("--dominant", default="lif_reverse:0",
+    ap.add_argument("--dominant", default="lif_reverse:1",
                     help="kernel:layer bracketed for the roofline line (layer 0 = every layer)")
     ap.add_argument("--traffic", type=float, default=None,
                     help="measured HBM bytes per launch of the dominant kernel (from the rocprofv3 --pmc runs); "

@@ -73,6 +73,7 @@ struct snn_ctx {
   int state = 0;                  // 0 fresh, 1 forward done, 2 backward done
   bool dj_ready = false;          // the fused readout kernel has already written dJ
   bool loss_ready = false;        // the mean of loss_b has been taken since the last readout
+  bool top_ds_ready = true;       // dS of the last spiking layer is in memory (false: its reverse scan formed it itself)
   int wall_khz = 100000;          // rate of the device's constant clock
   bool wg_tall = false;           // weight-gradient products use 256 x 128 tiles
   bool integral = false;          // integral cross-entropy instead of max over time
@@ -643,6 +644,48 @@ int launch_lif_reverse(snn_ctx *c, int l) {
   return SNN_OK;
 }
 
+// The last spiking layer can take dS = dJ W^T from the readout's current gradients inside its
+// reverse scan (lif_reverse_top_kernel) when it is feed-forward, its rows hold whole
+// wavefronts (ld a multiple of 64), it is narrow enough for one chain per lane, the readout
+// has at most 32 padded classes and the products run on rounded weights.
+bool top_fusable(const snn_ctx *c) {
+  const char *e = getenv("SNN_FUSE_TOP");                 // test knob, read per call
+  if (e && atoi(e) == 0) return false;
+  if (c->L < 2) return false;
+  const Layer &y = c->layers[c->L - 2];
+  return c->hl && y.spiking && !y.recurrent && y.ld % 64 == 0 && (long long)c->B * y.ld < (1 << 17) && c->ldC <= 32;
+}
+
+int launch_lif_reverse_top(snn_ctx *c) {
+  const int l = c->L - 2;
+  Layer &y = c->layers[l];
+  Layer &ro = c->layers[c->L - 1];
+  Bracket br(c, SNN_K_LIF_REVERSE, l + 1);
+  const int stride = c->B * y.ld;
+  const dim3 grid((unsigned)(stride / 64)), block(64);
+  const bool nt = streams_past_cache(c->M * y.ld * 4);
+#define SNN_REVT(SU)                                                                                             \
+  do {                                                                                                           \
+    if (nt)                                                                                                      \
+      hipLaunchKernelGGL((lif_reverse_top_kernel<SU, NT>), grid, block, 0, c->stream, ro.dI, c->ldC, ro.Qb, ro.ldqb, \
+                         y.V, y.dI, c->T, c->B, stride, y.beta_v, y.ld, c->theta, c->slope, y.part_b);           \
+    else                                                                                                         \
+      hipLaunchKernelGGL((lif_reverse_top_kernel<SU, 0>), grid, block, 0, c->stream, ro.dI, c->ldC, ro.Qb, ro.ldqb,  \
+                         y.V, y.dI, c->T, c->B, stride, y.beta_v, y.ld, c->theta, c->slope, y.part_b);           \
+  } while (0)
+  switch (c->surrogate) {
+    case 0: SNN_REVT(0); break;
+    case 1: SNN_REVT(1); break;
+    case 2: SNN_REVT(2); break;
+    case 3: SNN_REVT(3); break;
+    case 4: SNN_REVT(4); break;
+    default: SNN_REVT(5); break;
+  }
+#undef SNN_REVT
+  HIPCHK(c, hipGetLastError());
+  return SNN_OK;
+}
+
 int launch_readout_forward(snn_ctx *c, const int32_t *labels) {
   if (!labels) return fail(c, SNN_ERR_NULL, "labels are NULL");
   Layer &y = c->layers[c->L - 1];
@@ -936,8 +979,10 @@ int32_t snn_backward(snn_ctx *c) {
   WgradJobs wj;
   memset(&wj, 0, sizeof wj);
   if (!c->dj_ready && (rc = launch_readout_reverse(c))) return rc;
+  const bool fuse_top = top_fusable(c);
+  c->top_ds_ready = !fuse_top;
   for (int l = c->L - 1; l >= 0; --l) {
-    if (c->layers[l].spiking && (rc = launch_lif_reverse(c, l))) return rc;
+    if (c->layers[l].spiking && (rc = fuse_top && l == c->L - 2 ? launch_lif_reverse_top(c) : launch_lif_reverse(c, l))) return rc;
     if (l == 0 && c->prof.cls == SNN_K_CALIBRATE) {
       Bracket br(c, SNN_K_CALIBRATE, 0);
       hipLaunchKernelGGL(wait_ticks_kernel, dim3(1), dim3(64), 0, c->stream,
@@ -945,7 +990,7 @@ int32_t snn_backward(snn_ctx *c) {
       HIPCHK(c, hipGetLastError());
     }
     if ((rc = queue_weight_grad(c, l, wj, jobs))) return rc;
-    if (l > 0 && (rc = launch_input_grad(c, l))) return rc;
+    if (l > 0 && !(fuse_top && l == c->L - 1) && (rc = launch_input_grad(c, l))) return rc;
   }
   if (c->learn_beta) {
     // per-sample parts of dL/dbeta: written by the reverse scans for the spiking layers, by a
@@ -996,6 +1041,10 @@ int32_t snn_get_tensor(snn_ctx *c, int32_t tensor, int32_t layer, void *dst, siz
   if (bytes != v.rows * v.cols * v.esz)
     return fail(c, SNN_ERR_SHAPE, "tensor %d needs %zu bytes, got %zu", tensor, v.rows * v.cols * v.esz, bytes);
   if (tensor == SNN_T_LOSS && (rc = ensure_loss(c))) return rc;
+  if (tensor == SNN_T_D_SPIKES && layer == c->L - 1 && !c->top_ds_ready) {   // formed on the fly in snn_backward
+    if ((rc = launch_input_grad(c, c->L - 1))) return rc;
+    c->top_ds_ready = true;
+  }
   HIPCHK(c, hipMemcpy2DAsync(dst, v.cols * v.esz, v.p, v.ld * v.esz, v.cols * v.esz, v.rows, hipMemcpyDeviceToHost,
                              c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
