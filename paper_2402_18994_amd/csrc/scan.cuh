@@ -222,6 +222,105 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// ---------------------------------------------------------------- LIF forward below the readout
+// The forward scan of the last spiking layer, which also forms the readout's currents
+// J_t = S_t W of the steps it has just produced: that product has only C <= 32 columns, a
+// launch of its own reads all spikes again for 3 MB of result.  A workgroup owns one sample:
+// NW wavefronts of 64 chains each (ld = 64 NW).  Per block of 16 steps a wavefront writes its
+// spikes as bfloat16 into a private 16 x 64 LDS tile, reads them back as the A operand of
+// 16x16x32 MFMAs (rows = steps, k = its 64 neurons; B = the rounded readout weights of those
+// neurons, lane: class lane%16 of a group of 16, neurons 8 (lane/16) .. +7 of a half), and
+// the per-wavefront partial sums are added across the workgroup in a fixed order.
+// Wq: bfloat16 [class][neuron] rows of ldq elements, zero beyond the C classes and N neurons.
+template <int NW, int POL>
+__global__ __launch_bounds__(64 * NW) void lif_forward_top_kernel(const float *__restrict__ I, float *__restrict__ V,
+                                                                  uint8_t *__restrict__ S, float *__restrict__ J,
+                                                                  int ldc, const uint16_t *__restrict__ Wq, int ldq,
+                                                                  int q_rows, int T, int B, int stride,
+                                                                  const float *__restrict__ beta_v, float theta) {
+  constexpr int U = 16, LD = 64 * NW, TP = 144;             // steps per block; row length; tile pitch in bytes
+  __shared__ __attribute__((aligned(16))) char tile[NW][U * TP];
+  __shared__ float red[2][NW][U][32];                       // double-buffered: one barrier per block
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int b = blockIdx.x, n = 64 * w + lane;
+  const int p = b * LD + n;
+  const float beta = beta_v[n];
+  const unsigned bytes = (unsigned)T * stride * 4u;
+  const rsrc_t rI = make_rsrc(I, bytes), rV = make_rsrc(V, bytes), rS = make_rsrc(S, (unsigned)T * stride);
+  const rsrc_t rW = make_rsrc(Wq, (unsigned)q_rows * ldq * 2u);
+  const int vo4 = p * 4, row4 = stride * 4;
+  const int kg = lane >> 4;
+
+  bf16x8 wf[2][2];                                          // [class group][neuron half]
+#pragma unroll
+  for (int cg = 0; cg < 2; ++cg)
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const int cls = 16 * cg + (lane & 15);
+      wf[cg][ks] = __builtin_bit_cast(bf16x8, ld_b128(rW, cls < q_rows ? (cls * ldq + 64 * w + 32 * ks + 8 * kg) * 2 : OOB, 0));
+    }
+
+  float v = 0.f;
+  float a[U], bb[U];
+  auto fetch = [&](float (&buf)[U], int t0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) buf[u] = __uint_as_float(ld_b32<POL>(rI, vo4, min(t0 + u, T - 1) * row4));
+  };
+  // 16 steps from t0; steps beyond T leave no trace in memory and put zeros into the tile
+  auto block = [&](const float (&cur)[U], int t0, int par) {
+    char *const mine = tile[w];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + u;
+      const bool live = t < T;
+      const uint32_t s = live && v > theta ? 1u : 0u;
+      if (live) {
+        st_b32(rV, vo4, t * row4, __float_as_uint(v));
+        st_b8(rS, p, t * stride, s);
+        v = beta * v + cur[u] - (s ? theta : 0.f);
+      }
+      *(uint16_t *)(mine + u * TP + 2 * lane) = s ? 0x3F80 : 0;
+    }
+    wave_sync();
+    bf16x8 af[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) af[ks] = *(const bf16x8 *)(mine + (lane & 15) * TP + (32 * ks + 8 * kg) * 2);
+#pragma unroll
+    for (int cg = 0; cg < 2; ++cg) {
+      f32x4 d = {0.f, 0.f, 0.f, 0.f};
+      d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[0], wf[cg][0], d, 0, 0, 0);
+      d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[1], wf[cg][1], d, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) red[par][w][4 * kg + r][16 * cg + (lane & 15)] = d[r];
+    }
+    __syncthreads();
+    // J[t0 + step][b][c]: thread -> class tid % 32, steps tid / 32 + (2 NW) k
+    {
+      const int c = threadIdx.x & 31;
+#pragma unroll
+      for (int st = threadIdx.x >> 5; st < U; st += 2 * NW) {
+        float sum = red[par][0][st][c];
+#pragma unroll
+        for (int x = 1; x < NW; ++x) sum += red[par][x][st][c];
+        if (c < ldc && t0 + st < T) J[((size_t)(t0 + st) * B + b) * ldc + c] = sum;
+      }
+    }
+  };
+  fetch(a, 0);
+  int t0 = 0;
+  for (; t0 + 2 * U <= T; t0 += 2 * U) {
+    fetch(bb, t0 + U);
+    block(a, t0, 0);
+    fetch(a, t0 + 2 * U);
+    block(bb, t0 + U, 1);
+  }
+  if (t0 < T) {
+    fetch(bb, t0 + U);
+    block(a, t0, 0);
+    if (t0 + U < T) block(bb, t0 + U, 1);
+  }
+}
+
 // ---------------------------------------------------------------- LIF reverse below the readout
 // The reverse scan of the last spiking layer, taking dS_t = dJ_t W^T from the readout's
 // current gradients itself instead of reading it from memory: the product has only C <= 32

@@ -656,6 +656,39 @@ bool top_fusable(const snn_ctx *c) {
   return c->hl && y.spiking && !y.recurrent && y.ld % 64 == 0 && (long long)c->B * y.ld < (1 << 17) && c->ldC <= 32;
 }
 
+// Forward counterpart: the last spiking layer's scan also forms the readout's currents
+// (lif_forward_top_kernel), one workgroup per sample.
+bool top_forward_fusable(const snn_ctx *c) {
+  if (!top_fusable(c)) return false;
+  const int ld = c->layers[c->L - 2].ld;
+  return c->nplanes == 1 && (ld == 64 || ld == 128 || ld == 256);
+}
+
+int launch_lif_forward_top(snn_ctx *c) {
+  const int l = c->L - 2;
+  Layer &y = c->layers[l];
+  Layer &ro = c->layers[c->L - 1];
+  Bracket br(c, SNN_K_LIF_FORWARD, l + 1);
+  const int stride = c->B * y.ld;
+  const int q_rows = (int)(ro.qf_plane / ro.ldqf);
+  const bool nt = streams_past_cache(c->M * y.ld * 4);
+#define SNN_FWDT(NW)                                                                                              \
+  do {                                                                                                            \
+    if (nt)                                                                                                       \
+      hipLaunchKernelGGL((lif_forward_top_kernel<NW, NT>), dim3(c->B), dim3(64 * NW), 0, c->stream, y.I, y.V, y.S, ro.I, \
+                         c->ldC, ro.Qf, ro.ldqf, q_rows, c->T, c->B, stride, y.beta_v, c->theta);                  \
+    else                                                                                                          \
+      hipLaunchKernelGGL((lif_forward_top_kernel<NW, 0>), dim3(c->B), dim3(64 * NW), 0, c->stream, y.I, y.V, y.S, ro.I,  \
+                         c->ldC, ro.Qf, ro.ldqf, q_rows, c->T, c->B, stride, y.beta_v, c->theta);                  \
+  } while (0)
+  if (y.ld == 64) SNN_FWDT(1);
+  else if (y.ld == 128) SNN_FWDT(2);
+  else SNN_FWDT(4);
+#undef SNN_FWDT
+  HIPCHK(c, hipGetLastError());
+  return SNN_OK;
+}
+
 int launch_lif_reverse_top(snn_ctx *c) {
   const int l = c->L - 2;
   Layer &y = c->layers[l];
@@ -935,10 +968,11 @@ int32_t snn_init(const snn_config *cfg, void *workspace_dev, size_t workspace_by
 
 static int32_t forward_layers(snn_ctx *c, const int32_t *labels_dev, float *loss_host) {
   int rc;
+  const bool fuse_top = top_forward_fusable(c);         // the last spiking layer's scan forms the readout's currents
   for (int l = 0; l < c->L; ++l) {
-    if ((rc = launch_current_gemm(c, l))) return rc;
+    if (!(fuse_top && l == c->L - 1) && (rc = launch_current_gemm(c, l))) return rc;
     if (c->layers[l].spiking) {
-      if ((rc = launch_lif_forward(c, l))) return rc;
+      if ((rc = fuse_top && l == c->L - 2 ? launch_lif_forward_top(c) : launch_lif_forward(c, l))) return rc;
     } else {
       if ((rc = launch_readout_forward(c, labels_dev))) return rc;
     }

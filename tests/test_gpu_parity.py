@@ -107,13 +107,15 @@ def test_non_leaky_neurons(recurrent):
 
 
 @pytest.mark.parametrize("T,top,surrogate,slope", [(37, 64, "superspike", 10.0), (16, 192, "arctan", 2.0),
-                                                    (50, 128, "triangular", 1.0), (5, 64, "sigmoid", 4.0)])
-def test_top_layer_reverse_forms_its_spike_gradient(T, top, surrogate, slope):
+                                                    (50, 128, "triangular", 1.0), (5, 64, "sigmoid", 4.0),
+                                                    (33, 256, "superspike", 25.0)])
+def test_top_layer_scans_take_over_the_readout_products(T, top, surrogate, slope):
     """bf16 products, last spiking layer a multiple of 64 wide: its reverse scan takes
     dS = dJ W^T from the readout's current gradients itself (no input-gradient launch for the
-    readout).  Ragged T (blocks of 16 steps), one to three wavefronts per sample, 10 classes
-    (padded to 16) and 20 (padded to 24); dS read back afterwards comes from the product
-    kernel and must agree with the oracle as well."""
+    readout), and at 64, 128 or 256 neurons its forward scan forms the readout's currents
+    J = S W (no product launch for the readout).  Ragged T (blocks of 16 steps), one to four
+    wavefronts per sample, 10 classes (padded to 16) and 20 (padded to 24); dS read back
+    afterwards comes from the product kernel and must agree with the oracle as well."""
     wl = workloads.Workload(name="top-fused", index=16, T=T, B=7, sizes=(90, 72, top, 10 if top == 64 else 20),
                             recurrent=(False, False), beta=(0.9, 0.93, 0.95), theta=1.0, surrogate=surrogate,
                             slope=slope, precision="bf16", rate_lo=0.03, rate_hi=0.12)
@@ -121,9 +123,9 @@ def test_top_layer_reverse_forms_its_spike_gradient(T, top, surrogate, slope):
     assert rep["spike_rate"][1] > 0.005
 
 
-def test_top_layer_reverse_same_as_unfused(monkeypatch):
-    """The same backward pass with and without the fusion: current gradients and weight
-    gradients agree to rounding (the two paths add the class terms in different orders)."""
+def test_top_layer_scans_same_as_unfused(monkeypatch):
+    """The same step with and without the two fusions: readout currents, current gradients and
+    weight gradients agree to rounding (the paths add their terms in different orders)."""
     wl = workloads.CONFIGS["shd_ff128"].scaled(T=48, B=16)
     inp = workloads.generate(wl, w_gain=3.0)
     out = []
@@ -133,7 +135,8 @@ def test_top_layer_reverse_same_as_unfused(monkeypatch):
         snn.forward(inp.X, inp.labels)
         snn.backward()
         out.append([snn.get_tensor("d_current", 2), snn.get_tensor("d_spikes", 2), snn.get_tensor("grad_w", 1),
-                    snn.get_tensor("grad_w", 2), snn.get_tensor("grad_w", 3)])
+                    snn.get_tensor("grad_w", 2), snn.get_tensor("grad_w", 3), snn.get_tensor("readout_current"),
+                    snn.get_tensor("readout_trace")])
         snn.destroy()
     for a, b in zip(*out):
         assert np.abs(a - b).max() <= 1e-5 * np.abs(b).max()
