@@ -646,14 +646,16 @@ int launch_lif_reverse(snn_ctx *c, int l) {
 
 // The last spiking layer can take dS = dJ W^T from the readout's current gradients inside its
 // reverse scan (lif_reverse_top_kernel) when it is feed-forward, its rows hold whole
-// wavefronts (ld a multiple of 64), it is narrow enough for one chain per lane, the readout
-// has at most 32 padded classes and the products run on rounded weights.
+// wavefronts (ld a multiple of 64), the readout has at most 32 padded classes and the
+// products run on rounded weights.  (One chain per lane also at large widths: at 1024 neurons
+// the fused scan takes 216 us where the four-chains-per-lane scan plus the readout's
+// input-gradient launch took 290 + 100.)
 bool top_fusable(const snn_ctx *c) {
   const char *e = getenv("SNN_FUSE_TOP");                 // test knob, read per call
   if (e && atoi(e) == 0) return false;
   if (c->L < 2) return false;
   const Layer &y = c->layers[c->L - 2];
-  return c->hl && y.spiking && !y.recurrent && y.ld % 64 == 0 && (long long)c->B * y.ld < (1 << 17) && c->ldC <= 32;
+  return c->hl && y.spiking && !y.recurrent && y.ld % 64 == 0 && c->ldC <= 32;
 }
 
 // Forward counterpart: the last spiking layer's scan also forms the readout's currents
