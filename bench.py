@@ -24,7 +24,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # per dispatch, each scaled by what the same counter reads for the 256 MiB device copy this
 # script issues first: FETCH_SIZE reads half the bytes of that copy, WRITE_SIZE all of them).
 # The runs and their figures are in profiles/train_step_shd_ff128.txt.
-MEASURED_TRAFFIC = {("shd_ff128", "lif_reverse"): (16458.0 * 2.0 + 16384.0) * 1024.0}
+MEASURED_TRAFFIC = {("shd_ff128", "weight_grad"): (33297.0 * 2.0 + 27136.0) * 1024.0}
 
 # rocprofv3's duration of the calibration kernel that waits CALIBRATE_US on the device clock: the
 # difference is the start and end of a dispatch, which the profiler counts as kernel time.  The
@@ -37,17 +37,28 @@ def algorithmic_bytes(wl, kernel, layer):
     of its operands and results, each touched once), in the formats this build stores."""
     M = wl.T * wl.B
     bf = wl.precision == "bf16"
-    n_in, n_out = wl.sizes[layer - 1], wl.sizes[layer]
-    di = 4                           # current gradients are fp32 in memory in both modes
+    di = 4                           # current gradients are 4 bytes in memory in both modes
     planes = 1 if bf else 3
-    if kernel == "lif_forward":      # read I (4), write V (4) and S (1 byte)
-        return M * n_out * (4 + 4 + 1)
-    if kernel == "lif_reverse":      # read dS (4) and V (4), write dI (4)
-        return M * n_out * (4 + 4 + di)
+    L = len(wl.sizes) - 1
+    if kernel == "weight_grad" and layer == 0:   # the merged launch: every layer's spikes below, dI and dW (+ dR)
+        return sum(algorithmic_bytes(wl, kernel, l) for l in range(1, L + 1))
+    n_in, n_out = wl.sizes[layer - 1], wl.sizes[layer]
+    pad8 = lambda n: (n + 7) // 8 * 8
+    # a feed-forward layer a multiple of 64 wide under a layer of at most 128 padded columns forms dS
+    # in its reverse scan from that layer's current gradients (bf16 products)
+    fused_rev = (bf and layer < L and not wl.recurrent[layer - 1] and n_out % 64 == 0
+                 and pad8(wl.sizes[layer + 1]) <= 128)
+    fused_fwd = fused_rev and layer == L - 1 and n_out in (64, 128, 256) and pad8(wl.sizes[L]) <= 32
+    if kernel == "lif_forward":      # read I (4), write V (4) and S (1 byte) [+ the readout's currents]
+        return M * n_out * (4 + 4 + 1) + (M * pad8(wl.sizes[L]) * 4 if fused_fwd else 0)
+    if kernel == "lif_reverse":      # read dS (4) [or the current gradients above] and V (4), write dI (4)
+        above = pad8(wl.sizes[layer + 1]) if fused_rev else n_out
+        return M * (above * 4 + n_out * (4 + di))
     if kernel == "current_gemm":     # read spikes (1 byte) and the weight planes, write I (4)
         return M * n_in + planes * 2 * n_in * n_out + M * n_out * 4
-    if kernel == "weight_grad":      # read spikes and dI, write dW
-        return M * n_in + M * n_out * di + n_in * n_out * 4
+    if kernel == "weight_grad":      # read spikes and dI, write dW (recurrent: own spikes too, and dR)
+        rec = layer < L and wl.recurrent[layer - 1]
+        return M * n_in + M * n_out * di + n_in * n_out * 4 + (M * n_out + n_out * n_out * 4 if rec else 0)
     if kernel == "input_grad":       # read dI and the weight planes, write dS
         return M * n_out * di + planes * 2 * n_in * n_out + M * n_in * 4
     raise KeyError(kernel)
@@ -101,7 +112,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="shd_ff128")
-    ap.add_argument("--dominant", default="lif_reverse:1",
+    ap.add_argument("--dominant", default="weight_grad:0",
                     help="kernel:layer bracketed for the roofline line (layer 0 = every layer)")
     ap.add_argument("--traffic", type=float, default=None,
                     help="measured HBM bytes per launch of the dominant kernel (from the rocprofv3 --pmc runs); "
@@ -186,7 +197,9 @@ def main():
 
     kname, klayer = args.dominant.split(":")
     klayer = int(klayer)
-    blayer = klayer if klayer else 1          # layers of equal width move equal bytes per launch
+    # the weight-gradient products of all layers are one launch (layer 0); for the scans, layers of
+    # equal width move equal bytes per launch
+    blayer = klayer if (klayer or kname == "weight_grad") else 1
     snn.profile_select(kname, klayer)
     torch.cuda.synchronize()
     t0 = time.perf_counter()

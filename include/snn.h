@@ -151,7 +151,9 @@ typedef enum {
                                   one-wavefront kernel that waits SNN_CALIBRATE_US on the device
                                   clock; elapsed - SNN_CALIBRATE_US is what a bracket adds to the
                                   kernel it times (launched only while this class is selected) */
-  SNN_K_COUNT = 11
+  SNN_K_GRAD_REDUCE = 11,      /* the launch that adds the per-split partial sums of the weight
+                                  gradients (SNN_K_WEIGHT_GRAD covers the products alone)      */
+  SNN_K_COUNT = 12
 } snn_kernel_class;
 #define SNN_CALIBRATE_US 10
 

@@ -25,7 +25,7 @@ STEPS = {"current_gemm": 0, "lif_forward": 1, "readout_forward": 2, "readout_rev
          "lif_reverse": 4, "weight_grad": 5, "input_grad": 6}
 KERNELS = {"none": -1, "current_gemm": 0, "lif_forward": 1, "rlif_forward": 2, "readout_forward": 3,
            "readout_reverse": 4, "lif_reverse": 5, "rlif_reverse": 6, "weight_grad": 7,
-           "input_grad": 8, "sgd": 9, "calibrate": 10}
+           "input_grad": 8, "sgd": 9, "calibrate": 10, "grad_reduce": 11}
 CALIBRATE_US = 10.0
 STATUS = {0: "SNN_OK", 1: "SNN_ERR_NULL", 2: "SNN_ERR_ARG", 3: "SNN_ERR_SHAPE", 4: "SNN_ERR_WORKSPACE",
           5: "SNN_ERR_STATE", 6: "SNN_ERR_HIP", 7: "SNN_ERR_UNSUPPORTED"}

@@ -321,29 +321,32 @@ __global__ __launch_bounds__(64 * NW) void lif_forward_top_kernel(const float *_
   }
 }
 
-// ---------------------------------------------------------------- LIF reverse below the readout
-// The reverse scan of the last spiking layer, taking dS_t = dJ_t W^T from the readout's
-// current gradients itself instead of reading it from memory: the product has only C <= 32
-// terms per element, so a separate launch writes 4 bytes per element and this scan reads them
-// back for nothing (a third of its traffic).  One wavefront owns 64 chains, all of one sample
-// (ld is a multiple of 64 here), and per block of 16 steps forms the 16 x 64 block of dS with
-// 16x16x32 bfloat16 MFMAs:
-//   A  rows = the 16 steps, k = class: the hi and the lo halves of the dJ words of this
-//      sample (lane: step lane%16, classes 8 (lane/16) .. +7), two passes, lo first
-//   B  columns = 16 chains, k = class: the rounded readout weights W[n][c] (lane: chain
-//      lane%16 of the group, classes 8 (lane/16) .. +7), fetched once per group of 16 chains
+// ---------------------------------------------------------------- LIF reverse below a narrow layer
+// The reverse scan of a spiking layer that takes dS_t = dX_t W^T from the current gradients dX
+// of the layer above itself instead of reading it from memory, for a layer above of at most
+// 128 columns (32 KS): the readout (dX = dJ, C <= 32 classes) or a narrow spiking layer.  With
+// so few terms per element a separate product launch writes 4 bytes per element and this scan
+// reads them back for nothing (a third of its traffic).  One wavefront owns 64 chains, all of
+// one sample (ld is a multiple of 64 here), and per block of 16 steps forms the 16 x 64 block
+// of dS with 16x16x32 bfloat16 MFMAs:
+//   A  rows = the 16 steps, k = column of the layer above: the hi and the lo halves of the dX
+//      words of this sample (lane: step lane%16, columns 32 ks + 8 (lane/16) .. +7), two
+//      passes, lo first
+//   B  columns = 16 chains, k as in A: the rounded weights W[n][k] (lane: chain lane%16 of the
+//      group), fetched once per group of 16 chains
 //   D  lane holds chain lane%16 of the group at steps 4 (lane/16) .. +3
 // The block goes through 4 KiB of LDS private to the wavefront and comes back with one chain
 // per lane; after that the kernel is lif_reverse_kernel with one chain per lane.
-// dJ: hi/lo words [T][B][ldc], Wq: bfloat16 [ld rows][ldq] (row n = neuron), zero beyond C.
-template <int SURR, int POL>
-__global__ __launch_bounds__(64) void lif_reverse_top_kernel(const uint32_t *__restrict__ dJ, int ldc,
+// dX: hi/lo words [T][B][ldc], Wq: bfloat16 [ld rows][ldq] (row n = neuron of this layer),
+// zero beyond the valid columns.
+template <int KS, int SURR, int POL>
+__global__ __launch_bounds__(64) void lif_reverse_top_kernel(const uint32_t *__restrict__ dX, int ldc,
                                                              const uint16_t *__restrict__ Wq, int ldq,
                                                              const float *__restrict__ V, uint32_t *__restrict__ dI,
                                                              int T, int B, int stride,
                                                              const float *__restrict__ beta_v, int ld, float theta,
                                                              float slope, float *__restrict__ db_part) {
-  constexpr int U = 16, H = U / 16;                        // steps per block (32 measured slower); MFMA blocks in it
+  constexpr int U = 16;                                     // steps per block (32 measured slower)
   __shared__ float blk[U][64];
   const int lane = threadIdx.x;
   const int p0 = blockIdx.x * 64, p = p0 + lane;           // stride is a multiple of 64
@@ -352,25 +355,29 @@ __global__ __launch_bounds__(64) void lif_reverse_top_kernel(const uint32_t *__r
   float db = 0.f, g = 0.f;
   const unsigned bytes = (unsigned)T * stride * 4u;
   const rsrc_t rV = make_rsrc(V, bytes), rdI = make_rsrc(dI, bytes);
-  const rsrc_t rJ = make_rsrc(dJ, (unsigned)T * B * ldc * 4u), rW = make_rsrc(Wq, (unsigned)ld * ldq * 2u);
+  const rsrc_t rX = make_rsrc(dX, (unsigned)T * B * ldc * 4u), rW = make_rsrc(Wq, (unsigned)ld * ldq * 2u);
   const int vo4 = p * 4, row4 = stride * 4;
   const int kg = lane >> 4;
 
-  bf16x8 wf[4];                                             // B fragments: the weights of 4 x 16 chains
+  bf16x8 wf[4][KS];                                         // B fragments: the weights of 4 x 16 chains
 #pragma unroll
   for (int grp = 0; grp < 4; ++grp)
-    wf[grp] = __builtin_bit_cast(bf16x8, ld_b128(rW, 8 * kg < ldq ? ((n0 + 16 * grp + (lane & 15)) * ldq + 8 * kg) * 2 : OOB, 0));
-
-  // dJ words of a block: steps thi-15 .. thi of sample b (row lane%16), classes 8 kg .. +7
-  const int jrow = B * ldc * 4;
-  const int jlane = 8 * kg + 7 < ldc ? (b * ldc + 8 * kg) * 4 : OOB;
-  auto fetch_j = [&](u32x4 (&j)[H][2], int thi) {
 #pragma unroll
-    for (int q = 0; q < H; ++q) {
-      const int t = thi - (U - 1) + 16 * q + (lane & 15);  // the row differs per lane: all of it in the lane offset
-      const int jo = t >= 0 && jlane != OOB ? jlane + t * jrow : OOB;
-      j[q][0] = ld_b128(rJ, jo, 0);
-      j[q][1] = ld_b128(rJ, jo == OOB ? OOB : jo + 16, 0);
+    for (int ks = 0; ks < KS; ++ks) {
+      const int k = 32 * ks + 8 * kg;
+      wf[grp][ks] = __builtin_bit_cast(bf16x8, ld_b128(rW, k < ldq ? ((n0 + 16 * grp + (lane & 15)) * ldq + k) * 2 : OOB, 0));
+    }
+
+  // dX words of a block: steps thi-15 .. thi of sample b (row lane%16), columns 32 ks + 8 kg .. +7
+  const int xrow = B * ldc * 4;
+  auto fetch_x = [&](u32x4 (&x)[KS][2], int thi) {
+    const int t = thi - (U - 1) + (lane & 15);             // the row differs per lane: all of it in the lane offset
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int k = 32 * ks + 8 * kg;
+      const int xo = t >= 0 && k + 7 < ldc ? t * xrow + (b * ldc + k) * 4 : OOB;
+      x[ks][0] = ld_b128(rX, xo, 0);
+      x[ks][1] = ld_b128(rX, xo == OOB ? OOB : xo + 16, 0);
     }
   };
   auto fetch_v = [&](float (&v)[U], int thi) {
@@ -378,25 +385,29 @@ __global__ __launch_bounds__(64) void lif_reverse_top_kernel(const uint32_t *__r
     for (int u = 0; u < U; ++u) v[u] = __uint_as_float(ld_b32<POL>(rV, vo4, max(thi - u, 0) * row4));
   };
   // dS of the block with last step thi: ds[u] = dS at step thi - u of this lane's chain
-  auto spikes_grad = [&](const u32x4 (&jj)[H][2], float (&ds)[U]) {
-    wave_sync();                                            // the previous block has been read
+  auto spikes_grad = [&](const u32x4 (&x)[KS][2], float (&ds)[U]) {
+    bf16x8 hi[KS], lo[KS];
 #pragma unroll
-    for (int q = 0; q < H; ++q) {
-      const u32x4 (&j)[2] = jj[q];
+    for (int ks = 0; ks < KS; ++ks) {
+      const u32x4 (&j)[2] = x[ks];
       u32x4 h, l;
       h.x = __builtin_amdgcn_perm(j[0].y, j[0].x, 0x05040100u); l.x = __builtin_amdgcn_perm(j[0].y, j[0].x, 0x07060302u);
       h.y = __builtin_amdgcn_perm(j[0].w, j[0].z, 0x05040100u); l.y = __builtin_amdgcn_perm(j[0].w, j[0].z, 0x07060302u);
       h.z = __builtin_amdgcn_perm(j[1].y, j[1].x, 0x05040100u); l.z = __builtin_amdgcn_perm(j[1].y, j[1].x, 0x07060302u);
       h.w = __builtin_amdgcn_perm(j[1].w, j[1].z, 0x05040100u); l.w = __builtin_amdgcn_perm(j[1].w, j[1].z, 0x07060302u);
-      const bf16x8 hi = __builtin_bit_cast(bf16x8, h), lo = __builtin_bit_cast(bf16x8, l);
+      hi[ks] = __builtin_bit_cast(bf16x8, h);
+      lo[ks] = __builtin_bit_cast(bf16x8, l);
+    }
+    wave_sync();                                            // the previous block has been read
 #pragma unroll
-      for (int grp = 0; grp < 4; ++grp) {
-        f32x4 d = {0.f, 0.f, 0.f, 0.f};
-        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo, wf[grp], d, 0, 0, 0);
-        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi, wf[grp], d, 0, 0, 0);
+    for (int grp = 0; grp < 4; ++grp) {
+      f32x4 d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int r = 0; r < 4; ++r) blk[16 * q + 4 * kg + r][16 * grp + (lane & 15)] = d[r];
-      }
+      for (int ks = 0; ks < KS; ++ks) d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo[ks], wf[grp][ks], d, 0, 0, 0);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi[ks], wf[grp][ks], d, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) blk[4 * kg + r][16 * grp + (lane & 15)] = d[r];
     }
     wave_sync();
 #pragma unroll
@@ -409,30 +420,30 @@ __global__ __launch_bounds__(64) void lif_reverse_top_kernel(const uint32_t *__r
   };
 
   // The dS block of the next 16 steps is formed before the current 16 are scanned, so that its
-  // trip through the MFMA units and LDS runs under the scan's arithmetic; the dJ words are
+  // trip through the MFMA units and LDS runs under the scan's arithmetic; the dX words are
   // fetched two blocks ahead, the potentials one.  (Blocks beyond step 0 read nothing.)
-  u32x4 ja[H][2], jb[H][2];
+  u32x4 xa[KS][2], xb[KS][2];
   float va[U], vb[U], dsa[U], dsb[U];
-  fetch_j(ja, T - 1);
+  fetch_x(xa, T - 1);
   fetch_v(va, T - 1);
-  fetch_j(jb, T - 1 - U);
-  spikes_grad(ja, dsa);
+  fetch_x(xb, T - 1 - U);
+  spikes_grad(xa, dsa);
   int thi = T - 1;
   for (; thi - 2 * U + 1 >= 0; thi -= 2 * U) {
     fetch_v(vb, thi - U);
-    fetch_j(ja, thi - 2 * U);
-    spikes_grad(jb, dsb);
+    fetch_x(xa, thi - 2 * U);
+    spikes_grad(xb, dsb);
 #pragma unroll
     for (int u = 0; u < U; ++u) step(dsa[u], va[u], thi - u);
     fetch_v(va, thi - 2 * U);
-    fetch_j(jb, thi - 3 * U);
-    spikes_grad(ja, dsa);
+    fetch_x(xb, thi - 3 * U);
+    spikes_grad(xa, dsa);
 #pragma unroll
     for (int u = 0; u < U; ++u) step(dsb[u], vb[u], thi - U - u);
   }
   if (thi >= 0) {
     fetch_v(vb, thi - U);
-    spikes_grad(jb, dsb);
+    spikes_grad(xb, dsb);
 #pragma unroll
     for (int u = 0; u < U; ++u) if (thi - u >= 0) step(dsa[u], va[u], thi - u);
 #pragma unroll

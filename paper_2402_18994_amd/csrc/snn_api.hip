@@ -43,6 +43,7 @@ struct Layer {
   uint8_t *S = nullptr;
   uint32_t *dI = nullptr;                             // [M][ld] fp32 bits or HL; readout: dJ
   float *g[2] = {nullptr, nullptr};                   // recurrent reverse state [B][ld]
+  bool ds_ready = true;    // dS is in memory (false: the layer's reverse scan formed it itself in the last backward pass)
   int splits_w = 1, splits_r = 1;                     // contraction splits of dW and dR
   long long per_w = 0, per_r = 0;                     // rows per split
   float *part_w = nullptr, *part_r = nullptr;         // per-split partial results
@@ -73,7 +74,6 @@ struct snn_ctx {
   int state = 0;                  // 0 fresh, 1 forward done, 2 backward done
   bool dj_ready = false;          // the fused readout kernel has already written dJ
   bool loss_ready = false;        // the mean of loss_b has been taken since the last readout
-  bool top_ds_ready = true;       // dS of the last spiking layer is in memory (false: its reverse scan formed it itself)
   int wall_khz = 100000;          // rate of the device's constant clock
   bool wg_tall = false;           // weight-gradient products use 256 x 128 tiles
   bool integral = false;          // integral cross-entropy instead of max over time
@@ -536,8 +536,9 @@ int queue_weight_grad(snn_ctx *c, int l, WgradJobs &w, ReduceJobs &jobs) {
 
 // Launches what was queued (largest tiles first) and the reduction of the partial sums.
 int launch_weight_grads(snn_ctx *c, WgradJobs &w, const ReduceJobs &jobs, bool with_loss) {
-  Bracket br(c, SNN_K_WEIGHT_GRAD, 0);
   int rc;
+  {
+  Bracket br(c, SNN_K_WEIGHT_GRAD, 0);
   // A narrow product (the readout's) is small; when a launch with wide tiles exists it rides
   // along there (its tile count is the same, the unused columns load zeros) rather than
   // paying for a launch of its own.
@@ -549,6 +550,8 @@ int launch_weight_grads(snn_ctx *c, WgradJobs &w, const ReduceJobs &jobs, bool w
     }
   for (int which = 2; which >= 0; --which)
     if ((rc = flush_tn(c, w, which))) return rc;
+  }
+  Bracket br(c, SNN_K_GRAD_REDUCE, 0);
   return launch_reduce(c, jobs, with_loss);
 }
 
@@ -644,26 +647,27 @@ int launch_lif_reverse(snn_ctx *c, int l) {
   return SNN_OK;
 }
 
-// The last spiking layer can take dS = dJ W^T from the readout's current gradients inside its
-// reverse scan (lif_reverse_top_kernel) when it is feed-forward, its rows hold whole
-// wavefronts (ld a multiple of 64), the readout has at most 32 padded classes and the
-// products run on rounded weights.  (One chain per lane also at large widths: at 1024 neurons
-// the fused scan takes 216 us where the four-chains-per-lane scan plus the readout's
-// input-gradient launch took 290 + 100.)
-bool top_fusable(const snn_ctx *c) {
+// A spiking layer can take dS = dX W^T from the current gradients dX of the layer above inside
+// its reverse scan (lif_reverse_top_kernel) when it is feed-forward, its rows hold whole
+// wavefronts (ld a multiple of 64), the layer above has at most 128 padded columns (the
+// readout, or a narrow spiking layer) and the products run on rounded weights.  (One chain per
+// lane also at large widths: at 1024 neurons below the readout the fused scan takes 216 us
+// where the four-chains-per-lane scan plus the readout's input-gradient launch took 290 + 100.)
+int columns_above(const snn_ctx *c, int l) { return l + 1 == c->L - 1 ? c->ldC : c->layers[l + 1].ld; }
+bool reverse_fusable(const snn_ctx *c, int l) {
   const char *e = getenv("SNN_FUSE_TOP");                 // test knob, read per call
   if (e && atoi(e) == 0) return false;
-  if (c->L < 2) return false;
-  const Layer &y = c->layers[c->L - 2];
-  return c->hl && y.spiking && !y.recurrent && y.ld % 64 == 0 && c->ldC <= 32;
+  if (l < 0 || l > c->L - 2) return false;
+  const Layer &y = c->layers[l];
+  return c->hl && y.spiking && !y.recurrent && y.ld % 64 == 0 && columns_above(c, l) <= 128;
 }
 
 // Forward counterpart: the last spiking layer's scan also forms the readout's currents
 // (lif_forward_top_kernel), one workgroup per sample.
 bool top_forward_fusable(const snn_ctx *c) {
-  if (!top_fusable(c)) return false;
+  if (c->L < 2 || !reverse_fusable(c, c->L - 2)) return false;
   const int ld = c->layers[c->L - 2].ld;
-  return c->nplanes == 1 && (ld == 64 || ld == 128 || ld == 256);
+  return c->nplanes == 1 && c->ldC <= 32 && (ld == 64 || ld == 128 || ld == 256);
 }
 
 int launch_lif_forward_top(snn_ctx *c) {
@@ -691,22 +695,26 @@ int launch_lif_forward_top(snn_ctx *c) {
   return SNN_OK;
 }
 
-int launch_lif_reverse_top(snn_ctx *c) {
-  const int l = c->L - 2;
+int launch_lif_reverse_fused(snn_ctx *c, int l) {
   Layer &y = c->layers[l];
-  Layer &ro = c->layers[c->L - 1];
+  Layer &up = c->layers[l + 1];
   Bracket br(c, SNN_K_LIF_REVERSE, l + 1);
-  const int stride = c->B * y.ld;
+  const int stride = c->B * y.ld, ldc = columns_above(c, l);
   const dim3 grid((unsigned)(stride / 64)), block(64);
   const bool nt = streams_past_cache(c->M * y.ld * 4);
-#define SNN_REVT(SU)                                                                                             \
+#define SNN_REVT2(KS, SU)                                                                                        \
   do {                                                                                                           \
     if (nt)                                                                                                      \
-      hipLaunchKernelGGL((lif_reverse_top_kernel<SU, NT>), grid, block, 0, c->stream, ro.dI, c->ldC, ro.Qb, ro.ldqb, \
+      hipLaunchKernelGGL((lif_reverse_top_kernel<KS, SU, NT>), grid, block, 0, c->stream, up.dI, ldc, up.Qb, up.ldqb, \
                          y.V, y.dI, c->T, c->B, stride, y.beta_v, y.ld, c->theta, c->slope, y.part_b);           \
     else                                                                                                         \
-      hipLaunchKernelGGL((lif_reverse_top_kernel<SU, 0>), grid, block, 0, c->stream, ro.dI, c->ldC, ro.Qb, ro.ldqb,  \
+      hipLaunchKernelGGL((lif_reverse_top_kernel<KS, SU, 0>), grid, block, 0, c->stream, up.dI, ldc, up.Qb, up.ldqb,  \
                          y.V, y.dI, c->T, c->B, stride, y.beta_v, y.ld, c->theta, c->slope, y.part_b);           \
+  } while (0)
+#define SNN_REVT(SU)                                                                                             \
+  do {                                                                                                           \
+    if (ldc <= 32) SNN_REVT2(1, SU); else if (ldc <= 64) SNN_REVT2(2, SU);                                       \
+    else if (ldc <= 96) SNN_REVT2(3, SU); else SNN_REVT2(4, SU);                                                 \
   } while (0)
   switch (c->surrogate) {
     case 0: SNN_REVT(0); break;
@@ -717,6 +725,7 @@ int launch_lif_reverse_top(snn_ctx *c) {
     default: SNN_REVT(5); break;
   }
 #undef SNN_REVT
+#undef SNN_REVT2
   HIPCHK(c, hipGetLastError());
   return SNN_OK;
 }
@@ -1015,10 +1024,12 @@ int32_t snn_backward(snn_ctx *c) {
   WgradJobs wj;
   memset(&wj, 0, sizeof wj);
   if (!c->dj_ready && (rc = launch_readout_reverse(c))) return rc;
-  const bool fuse_top = top_fusable(c);
-  c->top_ds_ready = !fuse_top;
   for (int l = c->L - 1; l >= 0; --l) {
-    if (c->layers[l].spiking && (rc = fuse_top && l == c->L - 2 ? launch_lif_reverse_top(c) : launch_lif_reverse(c, l))) return rc;
+    const bool fused = reverse_fusable(c, l);           // this layer's scan forms its own dS
+    if (c->layers[l].spiking) {
+      c->layers[l].ds_ready = !fused;
+      if ((rc = fused ? launch_lif_reverse_fused(c, l) : launch_lif_reverse(c, l))) return rc;
+    }
     if (l == 0 && c->prof.cls == SNN_K_CALIBRATE) {
       Bracket br(c, SNN_K_CALIBRATE, 0);
       hipLaunchKernelGGL(wait_ticks_kernel, dim3(1), dim3(64), 0, c->stream,
@@ -1026,7 +1037,7 @@ int32_t snn_backward(snn_ctx *c) {
       HIPCHK(c, hipGetLastError());
     }
     if ((rc = queue_weight_grad(c, l, wj, jobs))) return rc;
-    if (l > 0 && !(fuse_top && l == c->L - 1) && (rc = launch_input_grad(c, l))) return rc;
+    if (l > 0 && !reverse_fusable(c, l - 1) && (rc = launch_input_grad(c, l))) return rc;
   }
   if (c->learn_beta) {
     // per-sample parts of dL/dbeta: written by the reverse scans for the spiking layers, by a
@@ -1077,9 +1088,9 @@ int32_t snn_get_tensor(snn_ctx *c, int32_t tensor, int32_t layer, void *dst, siz
   if (bytes != v.rows * v.cols * v.esz)
     return fail(c, SNN_ERR_SHAPE, "tensor %d needs %zu bytes, got %zu", tensor, v.rows * v.cols * v.esz, bytes);
   if (tensor == SNN_T_LOSS && (rc = ensure_loss(c))) return rc;
-  if (tensor == SNN_T_D_SPIKES && layer == c->L - 1 && !c->top_ds_ready) {   // formed on the fly in snn_backward
-    if ((rc = launch_input_grad(c, c->L - 1))) return rc;
-    c->top_ds_ready = true;
+  if (tensor == SNN_T_D_SPIKES && layer >= 1 && layer <= c->L - 1 && !c->layers[layer - 1].ds_ready) {
+    if ((rc = launch_input_grad(c, layer))) return rc;   // formed on the fly in snn_backward: materialise it now
+    c->layers[layer - 1].ds_ready = true;
   }
   HIPCHK(c, hipMemcpy2DAsync(dst, v.cols * v.esz, v.p, v.ld * v.esz, v.cols * v.esz, v.rows, hipMemcpyDeviceToHost,
                              c->stream));

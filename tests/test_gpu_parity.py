@@ -123,6 +123,19 @@ def test_top_layer_scans_take_over_the_readout_products(T, top, surrogate, slope
     assert rep["spike_rate"][1] > 0.005
 
 
+@pytest.mark.parametrize("above,rec_above", [(40, False), (64, False), (96, False), (128, False), (128, True)])
+def test_reverse_scan_below_a_narrow_layer(above, rec_above):
+    """A spiking layer of at most 128 neurons above a layer that is a multiple of 64 wide: the
+    lower layer's reverse scan forms dS from the upper layer's current gradients (one to four
+    32-wide contraction steps; the upper layer feed-forward or recurrent), and so does the
+    upper layer's when it is a multiple of 64 wide itself."""
+    wl = workloads.Workload(name="narrow-above", index=17, T=41, B=6, sizes=(80, 128, above, 10),
+                            recurrent=(False, rec_above), beta=(0.9, 0.93, 0.95), theta=1.0, surrogate="superspike",
+                            slope=10.0, precision="bf16", rate_lo=0.03, rate_hi=0.12)
+    rep = full_step_parity(wl, w_gain=2.0)
+    assert rep["spike_rate"][1] > 0.005
+
+
 def test_top_layer_scans_same_as_unfused(monkeypatch):
     """The same step with and without the two fusions: readout currents, current gradients and
     weight gradients agree to rounding (the paths add their terms in different orders)."""
@@ -134,7 +147,8 @@ def test_top_layer_scans_same_as_unfused(monkeypatch):
         snn = make(wl, inp)
         snn.forward(inp.X, inp.labels)
         snn.backward()
-        out.append([snn.get_tensor("d_current", 2), snn.get_tensor("d_spikes", 2), snn.get_tensor("grad_w", 1),
+        out.append([snn.get_tensor("d_current", 1), snn.get_tensor("d_spikes", 1),
+                    snn.get_tensor("d_current", 2), snn.get_tensor("d_spikes", 2), snn.get_tensor("grad_w", 1),
                     snn.get_tensor("grad_w", 2), snn.get_tensor("grad_w", 3), snn.get_tensor("readout_current"),
                     snn.get_tensor("readout_trace")])
         snn.destroy()
