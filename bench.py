@@ -24,12 +24,12 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # per dispatch, each scaled by what the same counter reads for the 256 MiB device copy this
 # script issues first: FETCH_SIZE reads half the bytes of that copy, WRITE_SIZE all of them).
 # The runs and their figures are in profiles/train_step_shd_ff128.txt.
-MEASURED_TRAFFIC = {("shd_ff128", "weight_grad"): (33297.0 * 2.0 + 27136.0) * 1024.0}
+MEASURED_TRAFFIC = {("shd_ff128", "weight_grad"): (33302.9 * 2.0 + 27136.0) * 1024.0}
 
 # rocprofv3's duration of the calibration kernel that waits CALIBRATE_US on the device clock: the
 # difference is the start and end of a dispatch, which the profiler counts as kernel time.  The
 # event timer is calibrated against this figure so that its kernel times are the profiler's.
-CALIBRATE_KERNEL_PROFILED_US = 10.83
+CALIBRATE_KERNEL_PROFILED_US = 10.96
 
 
 def algorithmic_bytes(wl, kernel, layer):
