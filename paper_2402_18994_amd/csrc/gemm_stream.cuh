@@ -69,15 +69,149 @@ __device__ __forceinline__ void static_for(F &&f) {
   }
 }
 
+// Geometry and main loop of one tile, shared by the kernels built on this pipeline.  `run`
+// expects the per-lane global offsets of the wavefront's load instructions (pv: P, row-major
+// bytes; qv: Q, bfloat16), takes the stages through `lds` (NS * ST bytes) and leaves the
+// products in acc; on return every load has landed and every wavefront is past its last
+// fragment read, so the caller may reuse the LDS.
+template <int WM, int WN, int TM, int TN, int NS>
+struct SpikeTile {
+  static_assert(WM * WN == 4, "four wavefronts per workgroup");
+  static constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  static constexpr int PT = BM * 32, QT = BN * 64, ST = PT + QT;   // bytes: P part, Q part, stage (32 k)
+  static constexpr int PI = BM / 128, QI = BN / 64;                 // load instructions per wavefront and stage
+  static constexpr int NL = PI + QI;
+  static_assert(BM % 128 == 0 && BN % 64 == 0, "whole KiB per wavefront");
+  static_assert(NS >= 4, "the waits assume at least four stages");
+  typedef u32x4 frag_t;
+
+  // Global side of the loads.  P instruction q of a wavefront fills rows 32 (wave + 4 q) ..
+  // +31 of the stage, 32 bytes each: lane -> row lane/2, slot lane%2, which holds the 16-byte
+  // unit slot ^ ((row / 8) % 2).  Q instruction q fills rows 16 (wave + 4 q) .. +15, 64 bytes
+  // each: lane -> row lane/4, slot lane%4, holding the 16-byte chunk slot ^ ((row / 4) % 4).
+  // With these permutations the fragment reads (32 consecutive rows, one unit or chunk)
+  // touch every bank equally.
+  static __device__ __forceinline__ int p_row(int wave, int lane, int q) { return 32 * (wave + 4 * q) + (lane >> 1); }
+  static __device__ __forceinline__ int p_unit(int row, int lane) { return (lane & 1) ^ ((row >> 3) & 1); }
+  static __device__ __forceinline__ int q_row(int wave, int lane, int q) { return 16 * (wave + 4 * q) + (lane >> 2); }
+  static __device__ __forceinline__ int q_chunk(int row, int lane) { return (lane & 3) ^ ((row >> 2) & 3); }
+
+  static __device__ __forceinline__ void run(char *lds, const u32x4 rp, const u32x4 rq, const int (&pv)[PI],
+                                             const int (&qv)[QI], const int nk, const int wave, const int lane,
+                                             f32x16 (&acc)[TM][TN]) {
+    const int wm = wave / WN, wn = wave % WN;
+    const unsigned lds0 = (unsigned)(uintptr_t)(lds_ptr_t)lds;
+    // Stage kt into buffer `buf`.  Beyond the contraction range the descriptors get size 0:
+    // the instruction count (which the vmcnt waits rely on) stays the same, nothing is fetched.
+    auto issue = [&](int kt_any, int buf) {
+      const int kt = __builtin_amdgcn_readfirstlane(kt_any);   // uniform; keeps the offsets scalar
+      u32x4 p = rp, qr = rq;
+      if (kt >= nk) p.z = qr.z = 0;
+      const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + buf * ST + 1024 * wave);
+#pragma unroll
+      for (int q = 0; q < PI; ++q) load_to_lds_b128(p, dst + 4096 * q, pv[q], kt * 32);
+#pragma unroll
+      for (int q = 0; q < QI; ++q) load_to_lds_b128(qr, dst + PT + 4096 * q, qv[q], kt * 64);
+    };
+
+    // LDS side of the fragment reads: lane half h reads P unit h (16 k, two MFMA steps' worth)
+    // and, for step s, Q chunk 2h + s.  Rows 32 apart share the permutation.
+    const int h = lane >> 5;
+    int fa, fb[2];
+    {
+      const int ra = wm * TM * 32 + (lane & 31), rb = wn * TN * 32 + (lane & 31);
+      fa = ra * 32 + ((h ^ ((ra >> 3) & 1)) << 4);
+#pragma unroll
+      for (int st = 0; st < 2; ++st) fb[st] = PT + rb * 64 + (((2 * h + st) ^ ((rb >> 2) & 3)) << 4);
+    }
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    auto read_first = [&](int buf, frag_t (&pa)[TM], frag_t (&qb)[TN]) {   // P bytes of a stage, Q of its step 0
+      const char *st = lds + buf * ST;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) pa[i] = *(const frag_t *)(st + fa + i * 1024);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) qb[j] = *(const frag_t *)(st + fb[0] + j * 2048);
+    };
+    auto products = [&](const frag_t (&pa)[TM], const frag_t (&qb)[TN], int st) {
+      bf16x8 af[TM];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const uint32_t w0 = pa[i][2 * st], w1 = pa[i][2 * st + 1];
+        u32x4 d;
+        d.x = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w0, 0x0C010C00u));
+        d.y = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w0, 0x0C030C02u));
+        d.z = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w1, 0x0C010C00u));
+        d.w = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w1, 0x0C030C02u));
+        af[i] = __builtin_bit_cast(bf16x8, d);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, qb[j]), af[i], acc[i][j], 0, 0, 0);
+    };
+    // One stage in buffer u.  On entry the stage's P bytes (pa) and step-0 Q fragments (qb) are
+    // in registers (or on their way).  The barrier sits between the two MFMA steps: past it,
+    // every wavefront has left stage kt-1 (its buffer, u+3, may be overwritten: the loads of
+    // stage kt+3 go there) and has seen its own loads of stage kt+1 land (so buffer u+1 is
+    // complete and its first fragments can be read under the MFMAs of step 1).
+    auto stage = [&](int u, int kt, frag_t (&pa)[TM], frag_t (&qb)[TN], frag_t (&pa_next)[TM], frag_t (&qb_next)[TN]) {
+      frag_t q1[TN];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) q1[j] = *(const frag_t *)(lds + u * ST + fb[1] + j * 2048);
+      products(pa, qb, 0);
+      // (ties the accumulators to this point: the MFMAs of step 0 are issued before the waits,
+      // not moved behind the barrier by the scheduler)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(acc[i][j]));
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 3) * NL) : "memory");   // younger stages may still be in flight
+      lds_barrier();
+      issue(kt + NS - 1, (u + NS - 1) % NS);
+      read_first((u + 1) % NS, pa_next, qb_next);
+      products(pa, q1, 1);
+    };
+
+#pragma unroll
+    for (int t = 0; t < NS - 1; ++t) issue(t, t);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NL) : "memory");
+    lds_barrier();
+    frag_t pa0[TM], qb0[TN], pa1[TM], qb1[TN];
+    read_first(0, pa0, qb0);
+    // Unrolled over the buffers (twice when their number is odd, so that the two fragment
+    // register sets alternate consistently).
+    constexpr int UN = NS % 2 ? 2 * NS : NS;
+    for (int kt = 0; kt < nk; kt += UN) {
+      bool done = false;
+      static_for<UN>([&](auto U) {
+        constexpr int u = decltype(U)::value;
+        if (!done) {
+          if constexpr (u % 2 == 0) stage(u % NS, kt + u, pa0, qb0, pa1, qb1);
+          else stage(u % NS, kt + u, pa1, qb1, pa0, qb0);
+          if (kt + u + 1 >= nk) done = true;
+        }
+      });
+      if (done) break;
+    }
+    // The loads beyond the range wrote zeros: they too are over before the buffers are reused.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_barrier();
+  }
+};
+
 template <int WM, int WN, int TM, int TN, int NS = 4>
 __global__ __launch_bounds__(256, 2) void spike_gemm_kernel(const GemmArgs a) {
-  static_assert(WM * WN == 4, "four wavefronts per workgroup");
-  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-  constexpr int PT = BM * 32, QT = BN * 64, ST = PT + QT;   // bytes: P part, Q part, stage (32 k)
-  constexpr int PI = BM / 128, QI = BN / 64;                 // load instructions per wavefront and stage
-  constexpr int NL = PI + QI;
-  static_assert(BM % 128 == 0 && BN % 64 == 0, "whole KiB per wavefront");
-  static_assert(NS >= 4 && NS * ST <= 81920, "two workgroups per compute unit");
+  typedef SpikeTile<WM, WN, TM, TN, NS> Tile;
+  constexpr int BM = Tile::BM, BN = Tile::BN, ST = Tile::ST, PI = Tile::PI, QI = Tile::QI;
+  static_assert(NS * ST <= 81920, "two workgroups per compute unit");
   __shared__ __attribute__((aligned(16))) char lds[NS * ST];
 
   // An XCD gets a contiguous run of tiles (column tiles fastest): tiles sharing a row slab of
@@ -92,133 +226,22 @@ __global__ __launch_bounds__(256, 2) void spike_gemm_kernel(const GemmArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
+  const int h = lane >> 5;
   const u32x4 rp = raw_rsrc(a.P, a.p_bytes), rq = raw_rsrc(a.Q, a.q_bytes);
-  const unsigned lds0 = (unsigned)(uintptr_t)(lds_ptr_t)lds;
 
-  // Global side of the loads.  P instruction q of this wavefront fills rows 32 (wave + 4 q) ..
-  // +31 of the stage, 32 bytes each: lane -> row lane/2, slot lane%2, which holds the 16-byte
-  // unit slot ^ ((row / 8) % 2).  Q instruction q fills rows 16 (wave + 4 q) .. +15, 64 bytes
-  // each: lane -> row lane/4, slot lane%4, holding the 16-byte chunk slot ^ ((row / 4) % 4).
-  // With these permutations the fragment reads below (32 consecutive rows, one unit or chunk)
-  // touch every bank equally.
   int pv[PI], qv[QI];
 #pragma unroll
   for (int q = 0; q < PI; ++q) {
-    const int row = 32 * (wave + 4 * q) + (lane >> 1);
-    const int unit = (lane & 1) ^ ((row >> 3) & 1);
-    pv[q] = row0 + row < a.rows ? (row0 + row) * a.ldp + unit * 16 : OOB;
+    const int row = Tile::p_row(wave, lane, q);
+    pv[q] = row0 + row < a.rows ? (row0 + row) * a.ldp + Tile::p_unit(row, lane) * 16 : OOB;
   }
 #pragma unroll
   for (int q = 0; q < QI; ++q) {
-    const int row = 16 * (wave + 4 * q) + (lane >> 2);
-    const int chunk = (lane & 3) ^ ((row >> 2) & 3);
-    qv[q] = ((col0 + row) * a.ldq + chunk * 8) * 2;
+    const int row = Tile::q_row(wave, lane, q);
+    qv[q] = ((col0 + row) * a.ldq + Tile::q_chunk(row, lane) * 8) * 2;
   }
-  // Stage kt into buffer `buf`.  Beyond the contraction range the descriptors get size 0:
-  // the instruction count (which the vmcnt waits rely on) stays the same, nothing is fetched.
-  auto issue = [&](int kt_any, int buf) {
-    const int kt = __builtin_amdgcn_readfirstlane(kt_any);   // uniform; keeps the offsets scalar
-    u32x4 p = rp, qr = rq;
-    if (kt >= nk) p.z = qr.z = 0;
-    const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + buf * ST + 1024 * wave);
-#pragma unroll
-    for (int q = 0; q < PI; ++q) load_to_lds_b128(p, dst + 4096 * q, pv[q], kt * 32);
-#pragma unroll
-    for (int q = 0; q < QI; ++q) load_to_lds_b128(qr, dst + PT + 4096 * q, qv[q], kt * 64);
-  };
-
-  // LDS side of the fragment reads: lane half h reads P unit h (16 k, two MFMA steps' worth)
-  // and, for step s, Q chunk 2h + s.  Rows 32 apart share the permutation.
-  const int h = lane >> 5;
-  int fa, fb[2];
-  {
-    const int ra = wm * TM * 32 + (lane & 31), rb = wn * TN * 32 + (lane & 31);
-    fa = ra * 32 + ((h ^ ((ra >> 3) & 1)) << 4);
-#pragma unroll
-    for (int st = 0; st < 2; ++st) fb[st] = PT + rb * 64 + (((2 * h + st) ^ ((rb >> 2) & 3)) << 4);
-  }
-
   f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  typedef u32x4 frag_t;
-  auto read_first = [&](int buf, frag_t (&pa)[TM], frag_t (&qb)[TN]) {   // P bytes of a stage, Q of its step 0
-    const char *st = lds + buf * ST;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) pa[i] = *(const frag_t *)(st + fa + i * 1024);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) qb[j] = *(const frag_t *)(st + fb[0] + j * 2048);
-  };
-  auto products = [&](const frag_t (&pa)[TM], const frag_t (&qb)[TN], int st) {
-    bf16x8 af[TM];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const uint32_t w0 = pa[i][2 * st], w1 = pa[i][2 * st + 1];
-      u32x4 d;
-      d.x = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w0, 0x0C010C00u));
-      d.y = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w0, 0x0C030C02u));
-      d.z = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w1, 0x0C010C00u));
-      d.w = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w1, 0x0C030C02u));
-      af[i] = __builtin_bit_cast(bf16x8, d);
-    }
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, qb[j]), af[i], acc[i][j], 0, 0, 0);
-  };
-  // One stage in buffer u.  On entry the stage's P bytes (pa) and step-0 Q fragments (qb) are
-  // in registers (or on their way).  The barrier sits between the two MFMA steps: past it,
-  // every wavefront has left stage kt-1 (its buffer, u+3, may be overwritten: the loads of
-  // stage kt+3 go there) and has seen its own loads of stage kt+1 land (so buffer u+1 is
-  // complete and its first fragments can be read under the MFMAs of step 1).
-  auto stage = [&](int u, int kt, frag_t (&pa)[TM], frag_t (&qb)[TN], frag_t (&pa_next)[TM], frag_t (&qb_next)[TN]) {
-    frag_t q1[TN];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) q1[j] = *(const frag_t *)(lds + u * ST + fb[1] + j * 2048);
-    products(pa, qb, 0);
-    // (ties the accumulators to this point: the MFMAs of step 0 are issued before the waits,
-    // not moved behind the barrier by the scheduler)
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(acc[i][j]));
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 3) * NL) : "memory");   // younger stages may still be in flight
-    lds_barrier();
-    issue(kt + NS - 1, (u + NS - 1) % NS);
-    read_first((u + 1) % NS, pa_next, qb_next);
-    products(pa, q1, 1);
-  };
-
-#pragma unroll
-  for (int t = 0; t < NS - 1; ++t) issue(t, t);
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NL) : "memory");
-  lds_barrier();
-  frag_t pa0[TM], qb0[TN], pa1[TM], qb1[TN];
-  read_first(0, pa0, qb0);
-  // Unrolled over the buffers (twice when their number is odd, so that the two fragment
-  // register sets alternate consistently).
-  constexpr int UN = NS % 2 ? 2 * NS : NS;
-  for (int kt = 0; kt < nk; kt += UN) {
-    bool done = false;
-    static_for<UN>([&](auto U) {
-      constexpr int u = decltype(U)::value;
-      if (!done) {
-        if constexpr (u % 2 == 0) stage(u % NS, kt + u, pa0, qb0, pa1, qb1);
-        else stage(u % NS, kt + u, pa1, qb1, pa0, qb0);
-        if (kt + u + 1 >= nk) done = true;
-      }
-    });
-    if (done) break;
-  }
-  // The loads beyond the range wrote zeros: they too are over before the buffers are reused.
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  lds_barrier();
+  Tile::run(lds, rp, rq, pv, qv, nk, wave, lane, acc);
 
   // Epilogue.  The MFMAs take Q as their first operand, so a tile comes out transposed: the
   // lane holds row (lane & 31) of C and register r holds column 8*(r/4) + 4*(lane/32) + (r%4),

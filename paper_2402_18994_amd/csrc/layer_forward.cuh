@@ -1,0 +1,187 @@
+// Forward pass of a whole feed-forward LIF layer in one launch (Eq. 1-2): currents
+// I = S_below W, the scan over time, V and S stored; I never goes to memory.
+//
+// As separate launches the product writes I (4 bytes per element) and the scan reads it back:
+// at 128 neurons that round trip is most of both kernels' traffic, and at 32 768 chains the
+// scan has two wavefronts per compute unit which each issue a load and two stores per step.
+// Here a workgroup owns one sample and BN = 64 or 128 of the layer's neurons (a layer of ld
+// neurons is cut in ld / BN parts; the parts of a sample run on the same XCD and share its
+// spike rows in that L2).  Per block of 128 steps:
+//   1. product: the 128 rows (t, b) of the spike tensor below times the rounded weights, on
+//      the streamed pipeline of the large current products (operands straight into LDS,
+//      four stages, see gemm_stream.cuh); the rows of the tile are the sample's time steps,
+//      so W passes through the workgroup once per block and the spikes once in all;
+//   2. the 128 x BN tile of currents goes to LDS (the stages are free by then);
+//   3. scan: BN / 64 wavefronts hold one neuron per lane and walk the 128 steps on LDS: read
+//      I_t (16 steps ahead), write V_t back in place.  The spike decision is taken without a
+//      compare: s = clamp((V - theta) 2^100) is exactly 1 when V > theta and 0 otherwise
+//      (for theta in [2^-60, 2^26]: the difference of two floats, when positive, is at least
+//      2^-24 theta, and the scaling is exact in the fused multiply-add), and V' = (beta V + I)
+//      - theta s is the value the plain scan computes.  Compare, select and subtract cost 57
+//      cycles per step as a dependent chain (the compare's result travels through a scalar
+//      register); the two fused multiply-adds take 20;
+//   4. store: all four wavefronts write V as whole rows, 16 bytes per lane, and S as 16
+//      neurons per lane, decided again from the stored V (the same exact comparison).
+// The potential is carried in the scanning lanes' registers from block to block.
+// Rows past T read as zero and are not stored; columns of W past the fan-in are zero.
+#pragma once
+#include "gemm_stream.cuh"
+
+namespace snn {
+
+struct LayerForwardArgs {
+  const uint8_t *P;        // spikes below [T*B][ldp], bytes 0/1
+  int ldp, kc;             // row length, fan-in
+  unsigned p_bytes;
+  const uint16_t *Q;       // rounded W^T [ld or more][ldq] bfloat16, zero beyond the fan-in and fan-out
+  int ldq;
+  unsigned q_bytes;
+  float *V;                // [T*B][ld]
+  uint8_t *S;              // [T*B][ld]
+  const float *beta_v;     // [ld]
+  float theta;             // in [2^-60, 2^26]
+  int T, B, ld;            // ld: a multiple of the workgroup's 64 or 128 neurons
+  int nt_store;            // V and S stream past the caches
+#ifdef SNN_LAYER_PROBE
+  unsigned long long *probe;   // [B][8] device clock at the phase boundaries of the first block (development builds only)
+#endif
+};
+#ifdef SNN_LAYER_PROBE
+#define SNN_PROBE(i) do { if (tid == 0 && t0 == 0 && n0 == 0) a.probe[b * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define SNN_PROBE(i) do { } while (0)
+#endif
+
+template <int TN, int NS = 4>
+__global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerForwardArgs a) {
+  typedef SpikeTile<2, 2, 2, TN, NS> Tile;
+  constexpr int TM = 2, WN = 2, BM = Tile::BM, BN = Tile::BN, PI = Tile::PI, QI = Tile::QI;
+  static_assert(BM == 128 && PI == 1 && (BN == 64 || BN == 128), "128 steps x 64 or 128 neurons");
+  constexpr int CP = BN * 4 + 16;                     // bytes between time rows of the current tile in LDS
+  constexpr int TILE = BM * CP;
+  constexpr int LDS_BYTES = NS * Tile::ST > TILE ? NS * Tile::ST : TILE;   // the stages share the tile's space
+  static_assert(LDS_BYTES <= 80 * 1024, "two workgroups per compute unit");
+  __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+
+  // Workgroup ids are dealt round-robin to the 8 XCDs: the parts of a sample take ids 8 apart.
+  const int parts = a.ld / BN;
+  const int part = (blockIdx.x >> 3) % parts;
+  const int b = (blockIdx.x >> 3) / parts * 8 + (blockIdx.x & 7);
+  if (b >= a.B) return;
+  const int n0 = part * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN, h = lane >> 5;
+  const int nk = (a.kc + 31) >> 5;
+  const u32x4 rp = raw_rsrc(a.P, a.p_bytes), rq = raw_rsrc(a.Q, a.q_bytes);
+  const rsrc_t rV = make_rsrc(a.V, (unsigned)a.T * a.B * a.ld * 4u), rS = make_rsrc(a.S, (unsigned)a.T * a.B * a.ld);
+
+  int qv[QI];
+#pragma unroll
+  for (int q = 0; q < QI; ++q) {
+    const int row = Tile::q_row(wave, lane, q);
+    qv[q] = ((n0 + row) * a.ldq + Tile::q_chunk(row, lane) * 8) * 2;
+  }
+  const float beta = a.beta_v[n0 + tid % BN];
+  const float theta = a.theta;
+  const float big = 0x1p100f, mtheta_big = -theta * 0x1p100f, mtheta = -theta;
+  float v = 0.f;                                      // potential of neuron n0 + tid (scanning wavefronts)
+
+  for (int t0 = 0; t0 < a.T; t0 += BM) {
+    SNN_PROBE(0);
+    // 1. product
+    int pv[PI];
+    {
+      const int row = Tile::p_row(wave, lane, 0);
+      pv[0] = t0 + row < a.T ? ((t0 + row) * a.B + b) * a.ldp + Tile::p_unit(row, lane) * 16 : OOB;
+    }
+    f32x16 acc[TM][TN];
+    Tile::run(lds, rp, rq, pv, qv, nk, wave, lane, acc);
+    SNN_PROBE(1);
+
+    // 2. The MFMAs take Q as their first operand, so a tile comes out transposed: the lane
+    // holds time row (lane & 31) and register r neuron 8*(r/4) + 4*(lane/32) + (r%4).
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          u32x4 x;
+          x.x = __float_as_uint(acc[i][j][4 * q]);
+          x.y = __float_as_uint(acc[i][j][4 * q + 1]);
+          x.z = __float_as_uint(acc[i][j][4 * q + 2]);
+          x.w = __float_as_uint(acc[i][j][4 * q + 3]);
+          const int row = (wm * TM + i) * 32 + (lane & 31), col = (wn * TN + j) * 32 + 8 * q + 4 * h;
+          *(u32x4 *)(lds + row * CP + col * 4) = x;
+        }
+    __syncthreads();
+    SNN_PROBE(2);
+
+    // 3. scan (steps past T run on zero currents; nothing of them is stored, and v is not
+    // used after the last block)
+    if (wave < BN / 64) {
+      float *cell = (float *)(lds + tid * 4);
+      constexpr int U = 16;
+      float nxt[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) nxt[u] = cell[u * (CP / 4)];
+      for (int s0 = 0; s0 < BM; s0 += U) {
+        // The currents of the next 16 steps are read before the 16 steps at hand are taken
+        // (the empty asm keeps the reads here, not next to their use).
+        float cur[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) cur[u] = nxt[u];
+        if (s0 + U < BM) {
+#pragma unroll
+          for (int u = 0; u < U; ++u) nxt[u] = cell[(s0 + U + u) * (CP / 4)];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) asm volatile("" : "+v"(cur[u]));
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          cell[(s0 + u) * (CP / 4)] = v;
+          float s;                                    // 1 if v > theta, else 0
+          asm("v_fma_f32 %0, %1, %2, %3 clamp" : "=v"(s) : "v"(v), "v"(big), "v"(mtheta_big));
+          v = __builtin_fmaf(mtheta, s, __builtin_fmaf(beta, v, cur[u]));
+        }
+      }
+    }
+    __syncthreads();
+    SNN_PROBE(3);
+
+    // 4. store.  V: BN/4 lanes x 16 bytes per row.  S: BN/16 lanes x 16 neurons per row.
+    {
+      constexpr int LPR = BN / 4, RPI = 256 / LPR;
+#pragma unroll
+      for (int k = 0; k < BM / RPI; ++k) {
+        const int row = RPI * k + tid / LPR, col = (tid % LPR) * 4;
+        const u32x4 x = *(const u32x4 *)(lds + row * CP + col * 4);
+        const int vo = t0 + row < a.T ? (((t0 + row) * a.B + b) * a.ld + n0 + col) * 4 : OOB;
+        if (a.nt_store) __builtin_amdgcn_raw_buffer_store_b128(x, rV, vo, 0, NT);
+        else __builtin_amdgcn_raw_buffer_store_b128(x, rV, vo, 0, 0);
+      }
+    }
+    {
+      constexpr int LPR = BN / 16, RPI = 256 / LPR;
+#pragma unroll
+      for (int k = 0; k < BM / RPI; ++k) {
+        const int row = RPI * k + tid / LPR, col = (tid % LPR) * 16;
+        u32x4 x;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 p = *(const f32x4 *)(lds + row * CP + (col + 4 * q) * 4);
+          x[q] = (p[0] > theta ? 1u : 0u) | (p[1] > theta ? 0x100u : 0u) | (p[2] > theta ? 0x10000u : 0u) |
+                 (p[3] > theta ? 0x1000000u : 0u);
+        }
+        const int so = t0 + row < a.T ? ((t0 + row) * a.B + b) * a.ld + n0 + col : OOB;
+        if (a.nt_store) __builtin_amdgcn_raw_buffer_store_b128(x, rS, so, 0, NT);
+        else __builtin_amdgcn_raw_buffer_store_b128(x, rS, so, 0, 0);
+      }
+    }
+    SNN_PROBE(4);
+    __syncthreads();                                  // the next block's stages overwrite the tile
+    SNN_PROBE(5);
+  }
+}
+
+}  // namespace snn

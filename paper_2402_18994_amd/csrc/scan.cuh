@@ -340,16 +340,20 @@ __global__ __launch_bounds__(64 * NW) void lif_forward_top_kernel(const float *_
 // dX: hi/lo words [T][B][ldc], Wq: bfloat16 [ld rows][ldq] (row n = neuron of this layer),
 // zero beyond the valid columns.
 template <int KS, int SURR, int POL>
-__global__ __launch_bounds__(64) void lif_reverse_top_kernel(const uint32_t *__restrict__ dX, int ldc,
+__global__ __launch_bounds__(256) void lif_reverse_top_kernel(const uint32_t *__restrict__ dX, int ldc,
                                                              const uint16_t *__restrict__ Wq, int ldq,
                                                              const float *__restrict__ V, uint32_t *__restrict__ dI,
                                                              int T, int B, int stride,
                                                              const float *__restrict__ beta_v, int ld, float theta,
                                                              float slope, float *__restrict__ db_part) {
   constexpr int U = 16;                                     // steps per block (32 measured slower)
-  __shared__ float blk[U][64];
-  const int lane = threadIdx.x;
-  const int p0 = blockIdx.x * 64, p = p0 + lane;           // stride is a multiple of 64
+  __shared__ float blks[4][U][64];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  float (&blk)[U][64] = blks[wv];
+  // The wavefronts of a workgroup (1, 2 or 4) are neighbours in the row and so belong to one
+  // sample: they fetch the same dX words, the second fetch is served by the CU's cache.  (As
+  // workgroups of their own they land on different XCDs and each fetch goes to memory.)
+  const int p0 = (blockIdx.x * (blockDim.x >> 6) + wv) * 64, p = p0 + lane;   // stride is a multiple of 64
   const int b = p0 / ld, n0 = p0 % ld;                     // one sample per wavefront
   const float beta = beta_v[n0 + lane];
   float db = 0.f, g = 0.f;

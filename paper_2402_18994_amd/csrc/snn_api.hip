@@ -14,6 +14,7 @@
 
 #include "gemm.cuh"
 #include "gemm_stream.cuh"
+#include "layer_forward.cuh"
 #include "scan.cuh"
 #include "rlif.cuh"
 
@@ -43,6 +44,7 @@ struct Layer {
   uint8_t *S = nullptr;
   uint32_t *dI = nullptr;                             // [M][ld] fp32 bits or HL; readout: dJ
   float *g[2] = {nullptr, nullptr};                   // recurrent reverse state [B][ld]
+  bool i_ready = true;     // I is in memory (false: the last forward pass ran the layer in one launch and never stored it)
   bool ds_ready = true;    // dS is in memory (false: the layer's reverse scan formed it itself in the last backward pass)
   int splits_w = 1, splits_r = 1;                     // contraction splits of dW and dR
   long long per_w = 0, per_r = 0;                     // rows per split
@@ -408,6 +410,7 @@ int launch_current_gemm(snn_ctx *c, int l) {
     else e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 1, 4, 1, 1, 1, 1>(a, 1, c->stream);
   }
   HIPCHK(c, e);
+  y.i_ready = true;
   return SNN_OK;
 }
 
@@ -700,7 +703,8 @@ int launch_lif_reverse_fused(snn_ctx *c, int l) {
   Layer &up = c->layers[l + 1];
   Bracket br(c, SNN_K_LIF_REVERSE, l + 1);
   const int stride = c->B * y.ld, ldc = columns_above(c, l);
-  const dim3 grid((unsigned)(stride / 64)), block(64);
+  const int wpg = (y.ld / 64) % 4 == 0 ? 4 : (y.ld / 64) % 2 == 0 ? 2 : 1;   // wavefronts per workgroup: one sample's
+  const dim3 grid((unsigned)(stride / 64 / wpg)), block(64 * wpg);
   const bool nt = streams_past_cache(c->M * y.ld * 4);
 #define SNN_REVT2(KS, SU)                                                                                        \
   do {                                                                                                           \
@@ -727,6 +731,51 @@ int launch_lif_reverse_fused(snn_ctx *c, int l) {
 #undef SNN_REVT
 #undef SNN_REVT2
   HIPCHK(c, hipGetLastError());
+  return SNN_OK;
+}
+
+// A feed-forward spiking layer of 64, 128, 192 or 256 (padded) neurons on rounded weights runs
+// as ONE launch, product and scan (lif_layer_forward_kernel): I is not stored.  A workgroup
+// owns a sample and 64 or 128 neurons, so it needs enough samples to fill the chip; 32-bit
+// byte offsets into the spikes below and V; a threshold the scan's compare-free spike
+// decision is exact for.
+// SNN_FUSE_LAYER: 0 never, 1 all but the last spiking layer, 2 (default) every such layer;
+// SNN_FUSE_LAYER_MIN_B: samples from which it is used (default 128); SNN_LAYER_NEURONS: 64 or
+// 128 neurons per workgroup.  All read per call.
+int layer_fuse_mode() {
+  const char *e = getenv("SNN_FUSE_LAYER");
+  return e ? atoi(e) : 2;
+}
+bool layer_forward_fusable(snn_ctx *c, int l) {
+  if (l < 0 || l > c->L - 2) return false;
+  const Layer &y = c->layers[l];
+  const char *e = getenv("SNN_FUSE_LAYER_MIN_B");
+  const int min_b = e ? atoi(e) : 128;
+  const SpikeSrc s = spikes_below(c, l);
+  return c->nplanes == 1 && y.spiking && !y.recurrent && y.ld % 64 == 0 && y.ld <= 256 && c->B >= min_b &&
+         s.ld % 4 == 0 && (size_t)c->M * s.ld < ((size_t)1 << 31) && (size_t)c->M * y.ld * 4 < ((size_t)1 << 31) &&
+         y.qf_plane >= (long long)y.ld * y.ldqf && c->theta >= 0x1p-60f && c->theta <= 0x1p26f;
+}
+
+int launch_layer_forward(snn_ctx *c, int l) {
+  Layer &y = c->layers[l];
+  const SpikeSrc s = spikes_below(c, l);
+  if (!s.p) return fail(c, SNN_ERR_NULL, "input raster is NULL");
+  LayerForwardArgs a;
+  memset(&a, 0, sizeof a);
+  a.P = s.p; a.ldp = s.ld; a.kc = s.valid; a.p_bytes = s.bytes;
+  a.Q = y.Qf; a.ldq = y.ldqf; a.q_bytes = (unsigned)(y.qf_plane * 2);
+  a.V = y.V; a.S = y.S; a.beta_v = y.beta_v; a.theta = c->theta;
+  a.T = c->T; a.B = c->B; a.ld = y.ld;
+  a.nt_store = streams_past_cache(c->M * y.ld * 4);
+  Bracket br(c, SNN_K_LIF_FORWARD, l + 1);
+  const char *e = getenv("SNN_LAYER_NEURONS");
+  const int bn = y.ld % 128 ? 64 : e ? atoi(e) : 128;   // 128: 108.0 us per step at 700-128-128-20, 64: 109.7
+  const dim3 grid((unsigned)(rup(c->B, 8) * (y.ld / bn)));
+  if (bn == 64) hipLaunchKernelGGL((lif_layer_forward_kernel<1, 4>), grid, dim3(256), 0, c->stream, a);
+  else hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4>), grid, dim3(256), 0, c->stream, a);
+  HIPCHK(c, hipGetLastError());
+  y.i_ready = false;
   return SNN_OK;
 }
 
@@ -979,8 +1028,14 @@ int32_t snn_init(const snn_config *cfg, void *workspace_dev, size_t workspace_by
 
 static int32_t forward_layers(snn_ctx *c, const int32_t *labels_dev, float *loss_host) {
   int rc;
-  const bool fuse_top = top_forward_fusable(c);         // the last spiking layer's scan forms the readout's currents
+  const int whole = layer_fuse_mode();                  // layers that run as one launch, product and scan
+  const bool whole_top = whole >= 2 && layer_forward_fusable(c, c->L - 2);
+  const bool fuse_top = !whole_top && top_forward_fusable(c);   // the last spiking layer's scan forms the readout's currents
   for (int l = 0; l < c->L; ++l) {
+    if (whole >= 1 && (l < c->L - 2 || whole_top) && layer_forward_fusable(c, l)) {
+      if ((rc = launch_layer_forward(c, l))) return rc;
+      continue;
+    }
     if (!(fuse_top && l == c->L - 1) && (rc = launch_current_gemm(c, l))) return rc;
     if (c->layers[l].spiking) {
       if ((rc = fuse_top && l == c->L - 2 ? launch_lif_forward_top(c) : launch_lif_forward(c, l))) return rc;
@@ -1088,6 +1143,9 @@ int32_t snn_get_tensor(snn_ctx *c, int32_t tensor, int32_t layer, void *dst, siz
   if (bytes != v.rows * v.cols * v.esz)
     return fail(c, SNN_ERR_SHAPE, "tensor %d needs %zu bytes, got %zu", tensor, v.rows * v.cols * v.esz, bytes);
   if (tensor == SNN_T_LOSS && (rc = ensure_loss(c))) return rc;
+  if (tensor == SNN_T_CURRENT && layer >= 1 && layer <= c->L - 1 && !c->layers[layer - 1].i_ready) {
+    if ((rc = launch_current_gemm(c, layer - 1))) return rc;   // the layer ran as one launch: materialise I now
+  }
   if (tensor == SNN_T_D_SPIKES && layer >= 1 && layer <= c->L - 1 && !c->layers[layer - 1].ds_ready) {
     if ((rc = launch_input_grad(c, layer))) return rc;   // formed on the fly in snn_backward: materialise it now
     c->layers[layer - 1].ds_ready = true;

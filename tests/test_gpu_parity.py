@@ -157,6 +157,55 @@ def test_top_layer_scans_same_as_unfused(monkeypatch):
     assert np.abs(out[0][0]).max() > 0
 
 
+@pytest.mark.parametrize("T,sizes,nt,bn", [(37, (90, 128, 128, 10), False, 128), (150, (203, 128, 121, 20), False, 64),
+                                           (260, (20, 128, 64, 10), True, 128), (128, (700, 128, 128, 20), False, 128),
+                                           (70, (150, 192, 256, 20), False, 128), (45, (64, 256, 128, 10), True, 64)],
+                         ids=["one-block", "two-blocks-ragged-fan-in", "three-blocks-nontemporal", "headline-widths",
+                              "192-and-256-neurons", "256-neurons-in-four-parts"])
+def test_layer_forward_in_one_launch(monkeypatch, T, sizes, nt, bn):
+    """bf16 products, feed-forward spiking layers of 64 to 256 (padded) neurons: product and scan
+    run as one launch per layer, a workgroup per sample and 64 or 128 neurons, and I is never
+    stored (read back, it comes from the product kernel).  The library uses the path from 128
+    samples on; the knob lowers that so that an element-by-element oracle run covers it: one,
+    two and three blocks of 128 steps with ragged tails, fan-ins that are no multiple of 32 or
+    of 16 bytes, a layer of 121 neurons padded to 128, layers of 64, 192 and 256 neurons, both
+    workgroup widths, stores with and without the non-temporal hint."""
+    monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
+    monkeypatch.setenv("SNN_LAYER_NEURONS", str(bn))
+    if nt:
+        monkeypatch.setenv("SNN_STREAM_MIN_MB", "0")
+    wl = workloads.Workload(name="layer-launch", index=18, T=T, B=5, sizes=sizes, recurrent=(False, False),
+                            beta=(0.9, 0.93, 0.95), theta=1.0, surrogate="superspike", slope=10.0, precision="bf16",
+                            rate_lo=0.03, rate_hi=0.12)
+    rep = full_step_parity(wl, w_gain=2.0)
+    assert rep["spike_rate"][0] > 0.005
+
+
+def test_layer_forward_in_one_launch_same_as_separate_launches(monkeypatch):
+    """The same forward pass with and without the one-launch layers: potentials and readout
+    agree to rounding, spikes are identical away from the threshold."""
+    wl = workloads.CONFIGS["shd_ff128"].scaled(T=140, B=12)
+    inp = workloads.generate(wl, w_gain=3.0)
+    monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
+    out = []
+    for knob in ("2", "1", "0"):
+        monkeypatch.setenv("SNN_FUSE_LAYER", knob)
+        snn = make(wl, inp)
+        snn.forward(inp.X, inp.labels)
+        out.append([snn.get_tensor("membrane", 1), snn.get_tensor("spikes", 1), snn.get_tensor("current", 1),
+                    snn.get_tensor("membrane", 2), snn.get_tensor("spikes", 2), snn.get_tensor("readout_trace")])
+        snn.destroy()
+    ref = out[2]
+    for got in out[:2]:
+        same = all(np.array_equal(got[i], ref[i]) for i in (1, 4))
+        near = np.abs(ref[0] - wl.theta) <= parity.BAND
+        assert np.array_equal(got[1][~near], ref[1][~near])
+        if same:
+            for i in (0, 2, 3, 5):
+                assert np.abs(got[i] - ref[i]).max() <= 1e-5 * np.abs(ref[i]).max()
+    assert ref[1].mean() > 0.005
+
+
 @pytest.fixture
 def large_tensor_paths(monkeypatch):
     """The kernels chosen for tensors that stream past the caches (the streamed current product,
