@@ -21,7 +21,10 @@
 //      cycles per step as a dependent chain (the compare's result travels through a scalar
 //      register); the two fused multiply-adds take 20;
 //   4. store: all four wavefronts write V as whole rows, 16 bytes per lane, and S as 16
-//      neurons per lane, decided again from the stored V (the same exact comparison).
+//      neurons per lane, decided again from the stored V (the same exact comparison);
+//   5. (last spiking layer of 128 neurons, at most 32 padded classes) the readout's currents
+//      J = S W_out of the block, eight 32x32x16 MFMAs per wavefront on the spikes in LDS: no
+//      product launch for the readout.
 // The potential is carried in the scanning lanes' registers from block to block.
 // Rows past T read as zero and are not stored; columns of W past the fan-in are zero.
 #pragma once
@@ -42,6 +45,13 @@ struct LayerForwardArgs {
   float theta;             // in [2^-60, 2^26]
   int T, B, ld;            // ld: a multiple of the workgroup's 64 or 128 neurons
   int nt_store;            // V and S stream past the caches
+  // Readout currents J = S W_out, formed from the block's spikes while they are in LDS (only
+  // the kernel variant for a last spiking layer of exactly 128 padded neurons uses these):
+  float *J;                // [T*B][ldj], ldj a multiple of 8, at most 32
+  int ldj;
+  const uint16_t *Qr;      // rounded W_out^T [32 or more rows: class][ldqr: neuron] bfloat16, zero beyond the classes
+  int ldqr;
+  unsigned qr_bytes;
 #ifdef SNN_LAYER_PROBE
   unsigned long long *probe;   // [B][8] device clock at the phase boundaries of the first block (development builds only)
 #endif
@@ -52,8 +62,9 @@ struct LayerForwardArgs {
 #define SNN_PROBE(i) do { } while (0)
 #endif
 
-template <int TN, int NS = 4>
+template <int TN, int NS = 4, bool READOUT = false>
 __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerForwardArgs a) {
+  static_assert(!READOUT || TN == 2, "the readout variant holds the whole layer");
   typedef SpikeTile<2, 2, 2, TN, NS> Tile;
   constexpr int TM = 2, WN = 2, BM = Tile::BM, BN = Tile::BN, PI = Tile::PI, QI = Tile::QI;
   static_assert(BM == 128 && PI == 1 && (BN == 64 || BN == 128), "128 steps x 64 or 128 neurons");
@@ -85,6 +96,16 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
   const float theta = a.theta;
   const float big = 0x1p100f, mtheta_big = -theta * 0x1p100f, mtheta = -theta;
   float v = 0.f;                                      // potential of neuron n0 + tid (scanning wavefronts)
+
+  // Readout variant: W_out^T as the first MFMA operand, lane -> class (lane & 31), neurons
+  // 16 kk + 8 h .. +7; resident.
+  bf16x8 wr[READOUT ? 8 : 1];
+  if (READOUT) {
+    const rsrc_t rQ = make_rsrc(a.Qr, a.qr_bytes);
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+      wr[kk] = __builtin_bit_cast(bf16x8, ld_b128(rQ, ((lane & 31) * a.ldqr + 16 * kk + 8 * h) * 2, 0));
+  }
 
   for (int t0 = 0; t0 < a.T; t0 += BM) {
     SNN_PROBE(0);
@@ -176,6 +197,38 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
         const int so = t0 + row < a.T ? ((t0 + row) * a.B + b) * a.ld + n0 + col : OOB;
         if (a.nt_store) __builtin_amdgcn_raw_buffer_store_b128(x, rS, so, 0, NT);
         else __builtin_amdgcn_raw_buffer_store_b128(x, rS, so, 0, 0);
+      }
+    }
+    // 5. readout currents of the block: J^T (32 classes x 128 steps) = W_out^T S^T, a wavefront
+    // takes 32 steps.  Second operand: lane -> step 32 wave + (lane & 31), neurons 16 kk + 8 h
+    // .. +7, their spikes decided once more from V in the tile (exactly as in the scan) and
+    // rounded to bfloat16 pairs.  The lane ends up with its step's currents, four consecutive
+    // classes per register quad.
+    if (READOUT) {
+      f32x16 jt;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) jt[r] = 0.f;
+      const int row = 32 * wave + (lane & 31);
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        const f32x4 p0 = *(const f32x4 *)(lds + row * CP + (16 * kk + 8 * h) * 4);
+        const f32x4 p1 = *(const f32x4 *)(lds + row * CP + (16 * kk + 8 * h + 4) * 4);
+        u32x4 sp;
+        sp.x = (p0[0] > theta ? 0x3F80u : 0u) | (p0[1] > theta ? 0x3F800000u : 0u);
+        sp.y = (p0[2] > theta ? 0x3F80u : 0u) | (p0[3] > theta ? 0x3F800000u : 0u);
+        sp.z = (p1[0] > theta ? 0x3F80u : 0u) | (p1[1] > theta ? 0x3F800000u : 0u);
+        sp.w = (p1[2] > theta ? 0x3F80u : 0u) | (p1[3] > theta ? 0x3F800000u : 0u);
+        jt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[kk], __builtin_bit_cast(bf16x8, sp), jt, 0, 0, 0);
+      }
+      const rsrc_t rJ = make_rsrc(a.J, (unsigned)a.T * a.B * a.ldj * 4u);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int c = 8 * q + 4 * h;
+        u32x4 x;
+        x.x = __float_as_uint(jt[4 * q]); x.y = __float_as_uint(jt[4 * q + 1]);
+        x.z = __float_as_uint(jt[4 * q + 2]); x.w = __float_as_uint(jt[4 * q + 3]);
+        const int jo = t0 + row < a.T && c + 3 < a.ldj ? (((t0 + row) * a.B + b) * a.ldj + c) * 4 : OOB;
+        __builtin_amdgcn_raw_buffer_store_b128(x, rJ, jo, 0, 0);
       }
     }
     SNN_PROBE(4);

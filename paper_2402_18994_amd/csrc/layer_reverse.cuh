@@ -1,0 +1,244 @@
+// Reverse pass of a whole feed-forward LIF layer below a narrow layer in one launch: the
+// spike gradients dS = dX W^T from the current gradients dX of the layer above (at most 128
+// columns: the readout or a narrow spiking layer), the surrogate, the reverse scan
+// g_t -> dI_t (Eq. 1-2 differentiated; see lif_reverse_kernel), dI stored as hi/lo words.
+//
+// lif_reverse_top_kernel does the same with one wavefront per 64 chains, each lane walking
+// its chain through global memory: per step a load, a store and a share of the dX fetches,
+// which is what bounds it (a wavefront issues a memory instruction about every 60 cycles).
+// Here a workgroup owns one sample and 128 neurons, and per block of 64 steps, last block
+// first:
+//   1. V (64 x 128) and dX (64 x ldc words) arrive through 16-byte loads issued one block
+//      ahead (they land during the previous block's scan) and go to LDS;
+//   2. dS: 32x32x16 bfloat16 MFMAs, the rounded weights of the wavefront's 64 neurons resident
+//      in registers, the hi and lo halves of dX as the second operand, lo first; a wavefront
+//      holds 32 steps x 64 neurons of the result;
+//   3. still in the MFMA layout, every lane turns its elements into the two coefficients of
+//      the step: with s = surr(V - theta), g' = beta g + s (dS - theta g) = c1 g + c2,
+//      c1 = beta - s theta, c2 = s dS.  The surrogate (a division or an exponential) is
+//      computed here by all four wavefronts, not inside the sequential scan;
+//   4. scan: two wavefronts, one neuron per lane, 64 steps of one fused multiply-add each on
+//      LDS (coefficients read 16 steps ahead, g written back in place of c2);
+//   5. store: all wavefronts pack g into hi/lo words and write whole rows, 16 bytes per lane.
+// g (and the decay gradient's partial sum) stay in the scanning lanes' registers from block
+// to block.  Rows past T read as zero: c2 = 0 there and g, zero at the start, stays zero.
+#pragma once
+#include "scan.cuh"
+#include <type_traits>
+
+namespace snn {
+
+struct LayerReverseArgs {
+  const uint32_t *dX;      // current gradients of the layer above [T*B][ldc], hi/lo words
+  int ldc;                 // its padded columns (multiple of 8, at most 128)
+  const uint16_t *Wq;      // rounded W[n][c] bfloat16, row n = neuron of this layer, zero beyond the valid columns
+  int ldq;
+  unsigned wq_bytes;
+  const float *V;          // [T*B][ld]
+  uint32_t *dI;            // [T*B][ld] hi/lo words
+  const float *beta_v;     // [ld]
+  float theta, slope;
+  float *db_part;          // [B][ld] per-sample parts of the decay gradient, or NULL
+  int T, B, ld;            // ld: a multiple of 128
+  int nt_store;            // dI streams past the caches
+#ifdef SNN_LAYER_PROBE
+  unsigned long long *probe;   // [B][2][8] device clock at the phase boundaries of the first two blocks (development builds only)
+#endif
+};
+#ifdef SNN_LAYER_PROBE
+#define SNN_RPROBE(i) do { if (tid == 0 && n0 == 0 && blk < 2) a.probe[b * 16 + blk * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define SNN_RPROBE(i) do { } while (0)
+#endif
+
+// The surrogates with the hardware reciprocal (1 ulp) instead of an IEEE division: the division
+// alone made step 3 take 1.6 us per block of 64 steps, as much as the rest of the block.
+template <int SURR> __device__ __forceinline__ float surr_rcp(float k, float x) {
+  if (SURR == 0) { const float d = 1.0f + k * fabsf(x); return __builtin_amdgcn_rcpf(d * d); }
+  if (SURR == 1) { const float u = 1.5707963267948966f * k * x; return (0.5f * k) * __builtin_amdgcn_rcpf(1.0f + u * u); }
+  if (SURR == 2) { const float s = __builtin_amdgcn_rcpf(1.0f + __expf(-k * x)); return k * s * (1.0f - s); }
+  return surr<SURR>(k, x);
+}
+
+template <int KS, int SURR>
+__global__ __launch_bounds__(256) void lif_layer_reverse_kernel(const LayerReverseArgs a) {
+  constexpr int BM = 64, BN = 128;
+  constexpr int CP = BN * 4 + 16;                     // bytes between time rows of the fp32 tiles
+  constexpr int PITCH = CP / 4;
+  constexpr int XP = KS * 128 + 16;                   // bytes between time rows of the dX tile (32 KS words)
+  constexpr int TILE = BM * CP;
+  constexpr int KK = 2 * KS;                          // 16-wide MFMA steps over the columns above
+  static_assert(XP <= CP, "the dX tile shares the space of a coefficient tile");
+  __shared__ __attribute__((aligned(16))) char lds[3 * TILE];
+  __shared__ __attribute__((aligned(16))) float betas[BN];
+  char *const Vt = lds, *const C1 = lds + TILE, *const C2 = lds + 2 * TILE, *const Xt = C1;
+
+  // Workgroup ids are dealt round-robin to the 8 XCDs: the parts of a sample take ids 8 apart.
+  const int parts = a.ld / BN;
+  const int part = (blockIdx.x >> 3) % parts;
+  const int b = (blockIdx.x >> 3) / parts * 8 + (blockIdx.x & 7);
+  if (b >= a.B) return;
+  const int n0 = part * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1, h = lane >> 5;
+  const float theta = a.theta, slope = a.slope;
+  const unsigned vbytes = (unsigned)a.T * a.B * a.ld * 4u;
+  const rsrc_t rV = make_rsrc(a.V, vbytes), rdI = make_rsrc(a.dI, vbytes);
+  const rsrc_t rX = make_rsrc(a.dX, (unsigned)a.T * a.B * a.ldc * 4u), rW = make_rsrc(a.Wq, a.wq_bytes);
+  if (tid < BN) betas[tid] = a.beta_v[n0 + tid];
+
+  // First MFMA operand: W[n][c], lane -> neuron (lane & 31) of the 32-neuron tile, columns
+  // 16 kk + 8 h .. +7.  Resident for the whole kernel.
+  bf16x8 wf[2][KK];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const int n = n0 + 64 * wn + 32 * j + (lane & 31), c = 16 * kk + 8 * h;
+      wf[j][kk] = __builtin_bit_cast(bf16x8, ld_b128(rW, c + 7 < a.ldq ? (n * a.ldq + c) * 2 : OOB, 0));
+    }
+
+  // A block's global loads: V as 8 x 16 bytes per thread (row = 8 k + tid / 32), dX as KK x 16
+  // bytes per thread over rows of 8 KS chunks (chunks beyond ldc read as zero).
+  u32x4 xv[8], xd[KK];
+  auto fetch = [&](int t0) {                          // t0 < 0: nothing is read
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int t = t0 + 8 * k + (tid >> 5), col = (tid & 31) * 4;
+      xv[k] = ld_b128(rV, t0 >= 0 && t < a.T ? ((t * a.B + b) * a.ld + n0 + col) * 4 : OOB, 0);
+    }
+#pragma unroll
+    for (int k = 0; k < KK; ++k) {
+      const int idx = k * 256 + tid, row = idx / (8 * KS), ch = idx % (8 * KS), t = t0 + row;
+      xd[k] = ld_b128(rX, t0 >= 0 && t < a.T && ch * 4 + 3 < a.ldc ? ((t * a.B + b) * a.ldc + ch * 4) * 4 : OOB, 0);
+    }
+  };
+  auto fill = [&]() {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) *(u32x4 *)(Vt + (8 * k + (tid >> 5)) * CP + (tid & 31) * 16) = xv[k];
+#pragma unroll
+    for (int k = 0; k < KK; ++k) {
+      const int idx = k * 256 + tid, row = idx / (8 * KS), ch = idx % (8 * KS);
+      *(u32x4 *)(Xt + row * XP + ch * 16) = xd[k];
+    }
+  };
+
+  float g = 0.f, db = 0.f;                            // state of neuron n0 + tid (wavefronts 0 and 1)
+
+  int t0 = (a.T - 1) / BM * BM;
+  fetch(t0);
+  for (int blk = 0; t0 >= 0; t0 -= BM, ++blk) {
+    SNN_RPROBE(0);
+    fill();
+    __syncthreads();
+    fetch(t0 - BM);
+    SNN_RPROBE(1);
+
+    // 2. dS^T tile: rows = neurons, columns = steps; the lane holds step 32 wm + (lane & 31)
+    // and register r neuron 8 (r / 4) + 4 h + (r % 4) of its 32-neuron tile.
+    f32x16 acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    {
+      bf16x8 hi[KK];
+      const char *px = Xt + (32 * wm + (lane & 31)) * XP + 32 * h;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const u32x4 j0 = *(const u32x4 *)(px + 64 * kk), j1 = *(const u32x4 *)(px + 64 * kk + 16);
+        u32x4 hh, ll;
+        hh.x = __builtin_amdgcn_perm(j0.y, j0.x, 0x05040100u); ll.x = __builtin_amdgcn_perm(j0.y, j0.x, 0x07060302u);
+        hh.y = __builtin_amdgcn_perm(j0.w, j0.z, 0x05040100u); ll.y = __builtin_amdgcn_perm(j0.w, j0.z, 0x07060302u);
+        hh.z = __builtin_amdgcn_perm(j1.y, j1.x, 0x05040100u); ll.z = __builtin_amdgcn_perm(j1.y, j1.x, 0x07060302u);
+        hh.w = __builtin_amdgcn_perm(j1.w, j1.z, 0x05040100u); ll.w = __builtin_amdgcn_perm(j1.w, j1.z, 0x07060302u);
+        hi[kk] = __builtin_bit_cast(bf16x8, hh);
+        const bf16x8 lo = __builtin_bit_cast(bf16x8, ll);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j][kk], lo, acc[j], 0, 0, 0);
+      }
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j][kk], hi[kk], acc[j], 0, 0, 0);
+    }
+    __syncthreads();                                  // every wavefront has read the dX tile: C1 takes its place
+    SNN_RPROBE(2);
+
+    // 3. coefficients
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int t = 32 * wm + (lane & 31), n = 64 * wn + 32 * j + 8 * q + 4 * h;
+        const f32x4 vv = *(const f32x4 *)(Vt + t * CP + n * 4);
+        const f32x4 bb = *(const f32x4 *)(&betas[n]);
+        f32x4 c1, c2;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float s = surr_rcp<SURR>(slope, vv[e] - theta);
+          c1[e] = bb[e] - s * theta;
+          c2[e] = s * acc[j][4 * q + e];
+        }
+        *(f32x4 *)(C1 + t * CP + n * 4) = c1;
+        *(f32x4 *)(C2 + t * CP + n * 4) = c2;
+      }
+    __syncthreads();
+    SNN_RPROBE(3);
+
+    // 4. scan, steps t0 + 63 down to t0: dI_t = g, then g <- c1 g + c2 (and db += g V_t)
+    if (wave < 2) {
+      const float *p1 = (const float *)(C1 + tid * 4), *pv = (const float *)(Vt + tid * 4);
+      float *p2 = (float *)(C2 + tid * 4);
+      auto scan = [&](auto DB) {
+        constexpr bool with_db = decltype(DB)::value;
+        constexpr int U = 16;
+        float n1[U], n2[U], nv[U];
+        auto read = [&](int s0) {
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            n1[u] = p1[(s0 + u) * PITCH];
+            n2[u] = p2[(s0 + u) * PITCH];
+            if (with_db) nv[u] = pv[(s0 + u) * PITCH];
+          }
+        };
+        read(BM - U);
+        for (int s0 = BM - U; s0 >= 0; s0 -= U) {
+          float c1[U], c2[U], vv[U];
+#pragma unroll
+          for (int u = 0; u < U; ++u) { c1[u] = n1[u]; c2[u] = n2[u]; vv[u] = with_db ? nv[u] : 0.f; }
+          if (s0 >= U) read(s0 - U);                  // the next 16 steps' coefficients, before these 16 are taken
+#pragma unroll
+          for (int u = 0; u < U; ++u) asm volatile("" : "+v"(c1[u]), "+v"(c2[u]));
+#pragma unroll
+          for (int u = U - 1; u >= 0; --u) {
+            p2[(s0 + u) * PITCH] = g;
+            if (with_db) db = __builtin_fmaf(g, vv[u], db);
+            g = __builtin_fmaf(c1[u], g, c2[u]);
+          }
+        }
+      };
+      if (a.db_part) scan(std::true_type()); else scan(std::false_type());
+    }
+    __syncthreads();
+    SNN_RPROBE(4);
+
+    // 5. store: 32 lanes x 16 bytes per row, 8 rows per instruction
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int row = 8 * k + (tid >> 5), col = (tid & 31) * 4, t = t0 + row;
+      const f32x4 gq = *(const f32x4 *)(C2 + row * CP + col * 4);
+      u32x4 w;
+      w.x = pack_hl(gq[0]); w.y = pack_hl(gq[1]); w.z = pack_hl(gq[2]); w.w = pack_hl(gq[3]);
+      const int vo = t < a.T ? ((t * a.B + b) * a.ld + n0 + col) * 4 : OOB;
+      if (a.nt_store) __builtin_amdgcn_raw_buffer_store_b128(w, rdI, vo, 0, NT);
+      else __builtin_amdgcn_raw_buffer_store_b128(w, rdI, vo, 0, 0);
+    }
+    SNN_RPROBE(5);
+    // (The next block's fill writes V and dX = C1, which nobody reads any more; C2 is written
+    // again only after two more barriers.)
+  }
+  if (a.db_part && tid < BN) a.db_part[b * a.ld + n0 + tid] = db;
+}
+
+}  // namespace snn

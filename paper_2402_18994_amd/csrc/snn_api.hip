@@ -16,6 +16,7 @@
 #include "gemm_stream.cuh"
 #include "layer_forward.cuh"
 #include "scan.cuh"
+#include "layer_reverse.cuh"
 #include "rlif.cuh"
 
 using namespace snn;
@@ -698,7 +699,53 @@ int launch_lif_forward_top(snn_ctx *c) {
   return SNN_OK;
 }
 
+// The same reverse pass as one workgroup per sample and 128 neurons on LDS
+// (lif_layer_reverse_kernel): layers of 128 or 256 neurons, enough samples to fill the chip,
+// 32-bit byte offsets.  SNN_FUSE_LAYER_REV=0 switches it off; SNN_FUSE_LAYER_MIN_B as for the
+// forward pass.  Both read per call.
+bool layer_reverse_whole(snn_ctx *c, int l) {
+  const char *e = getenv("SNN_FUSE_LAYER_REV");
+  if (e && atoi(e) == 0) return false;
+  const Layer &y = c->layers[l];
+  const char *m = getenv("SNN_FUSE_LAYER_MIN_B");
+  const int min_b = m ? atoi(m) : 128;
+  return reverse_fusable(c, l) && y.ld % 128 == 0 && y.ld <= 256 && c->B >= min_b &&
+         (size_t)c->M * y.ld * 4 < ((size_t)1 << 31) && (size_t)c->M * columns_above(c, l) * 4 < ((size_t)1 << 31);
+}
+
+int launch_layer_reverse(snn_ctx *c, int l) {
+  Layer &y = c->layers[l];
+  Layer &up = c->layers[l + 1];
+  LayerReverseArgs a;
+  memset(&a, 0, sizeof a);
+  a.dX = up.dI; a.ldc = columns_above(c, l);
+  a.Wq = up.Qb; a.ldq = up.ldqb; a.wq_bytes = (unsigned)(up.qb_plane * 2);
+  a.V = y.V; a.dI = y.dI; a.beta_v = y.beta_v; a.theta = c->theta; a.slope = c->slope; a.db_part = y.part_b;
+  a.T = c->T; a.B = c->B; a.ld = y.ld;
+  a.nt_store = streams_past_cache(c->M * y.ld * 4);
+  Bracket br(c, SNN_K_LIF_REVERSE, l + 1);
+  const dim3 grid((unsigned)(rup(c->B, 8) * (y.ld / 128))), block(256);
+#define SNN_LREV(SU)                                                                                             \
+  do {                                                                                                           \
+    if (a.ldc <= 32) hipLaunchKernelGGL((lif_layer_reverse_kernel<1, SU>), grid, block, 0, c->stream, a);        \
+    else if (a.ldc <= 64) hipLaunchKernelGGL((lif_layer_reverse_kernel<2, SU>), grid, block, 0, c->stream, a);   \
+    else hipLaunchKernelGGL((lif_layer_reverse_kernel<4, SU>), grid, block, 0, c->stream, a);                    \
+  } while (0)
+  switch (c->surrogate) {
+    case 0: SNN_LREV(0); break;
+    case 1: SNN_LREV(1); break;
+    case 2: SNN_LREV(2); break;
+    case 3: SNN_LREV(3); break;
+    case 4: SNN_LREV(4); break;
+    default: SNN_LREV(5); break;
+  }
+#undef SNN_LREV
+  HIPCHK(c, hipGetLastError());
+  return SNN_OK;
+}
+
 int launch_lif_reverse_fused(snn_ctx *c, int l) {
+  if (layer_reverse_whole(c, l)) return launch_layer_reverse(c, l);
   Layer &y = c->layers[l];
   Layer &up = c->layers[l + 1];
   Bracket br(c, SNN_K_LIF_REVERSE, l + 1);
@@ -739,12 +786,13 @@ int launch_lif_reverse_fused(snn_ctx *c, int l) {
 // owns a sample and 64 or 128 neurons, so it needs enough samples to fill the chip; 32-bit
 // byte offsets into the spikes below and V; a threshold the scan's compare-free spike
 // decision is exact for.
-// SNN_FUSE_LAYER: 0 never, 1 all but the last spiking layer, 2 (default) every such layer;
+// SNN_FUSE_LAYER: 0 never, 1 all but the last spiking layer, 2 every such layer, 3 (default)
+// the last one also forms the readout's currents when it has exactly 128 padded neurons;
 // SNN_FUSE_LAYER_MIN_B: samples from which it is used (default 128); SNN_LAYER_NEURONS: 64 or
 // 128 neurons per workgroup.  All read per call.
 int layer_fuse_mode() {
   const char *e = getenv("SNN_FUSE_LAYER");
-  return e ? atoi(e) : 2;
+  return e ? atoi(e) : 3;
 }
 bool layer_forward_fusable(snn_ctx *c, int l) {
   if (l < 0 || l > c->L - 2) return false;
@@ -757,7 +805,15 @@ bool layer_forward_fusable(snn_ctx *c, int l) {
          y.qf_plane >= (long long)y.ld * y.ldqf && c->theta >= 0x1p-60f && c->theta <= 0x1p26f;
 }
 
-int launch_layer_forward(snn_ctx *c, int l) {
+// with_readout: l is the last spiking layer and the launch also forms the readout's currents.
+bool layer_forward_takes_readout(snn_ctx *c) {
+  const char *e = getenv("SNN_LAYER_NEURONS");
+  const Layer &ro = c->layers[c->L - 1];
+  return c->L >= 2 && layer_fuse_mode() >= 3 && layer_forward_fusable(c, c->L - 2) && c->layers[c->L - 2].ld == 128 &&
+         (!e || atoi(e) == 128) && c->ldC <= 32 && ro.qf_plane >= 32ll * ro.ldqf && ro.ldqf >= 128;
+}
+
+int launch_layer_forward(snn_ctx *c, int l, bool with_readout) {
   Layer &y = c->layers[l];
   const SpikeSrc s = spikes_below(c, l);
   if (!s.p) return fail(c, SNN_ERR_NULL, "input raster is NULL");
@@ -772,7 +828,12 @@ int launch_layer_forward(snn_ctx *c, int l) {
   const char *e = getenv("SNN_LAYER_NEURONS");
   const int bn = y.ld % 128 ? 64 : e ? atoi(e) : 128;   // 128: 108.0 us per step at 700-128-128-20, 64: 109.7
   const dim3 grid((unsigned)(rup(c->B, 8) * (y.ld / bn)));
-  if (bn == 64) hipLaunchKernelGGL((lif_layer_forward_kernel<1, 4>), grid, dim3(256), 0, c->stream, a);
+  if (with_readout) {
+    Layer &ro = c->layers[c->L - 1];
+    a.J = ro.I; a.ldj = c->ldC; a.Qr = ro.Qf; a.ldqr = ro.ldqf; a.qr_bytes = (unsigned)(ro.qf_plane * 2);
+    hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, true>), grid, dim3(256), 0, c->stream, a);
+    ro.i_ready = true;
+  } else if (bn == 64) hipLaunchKernelGGL((lif_layer_forward_kernel<1, 4>), grid, dim3(256), 0, c->stream, a);
   else hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4>), grid, dim3(256), 0, c->stream, a);
   HIPCHK(c, hipGetLastError());
   y.i_ready = false;
@@ -1030,10 +1091,15 @@ static int32_t forward_layers(snn_ctx *c, const int32_t *labels_dev, float *loss
   int rc;
   const int whole = layer_fuse_mode();                  // layers that run as one launch, product and scan
   const bool whole_top = whole >= 2 && layer_forward_fusable(c, c->L - 2);
+  const bool with_readout = whole_top && layer_forward_takes_readout(c);
   const bool fuse_top = !whole_top && top_forward_fusable(c);   // the last spiking layer's scan forms the readout's currents
   for (int l = 0; l < c->L; ++l) {
     if (whole >= 1 && (l < c->L - 2 || whole_top) && layer_forward_fusable(c, l)) {
-      if ((rc = launch_layer_forward(c, l))) return rc;
+      if ((rc = launch_layer_forward(c, l, l == c->L - 2 && with_readout))) return rc;
+      continue;
+    }
+    if (l == c->L - 1 && with_readout) {                // J is there already
+      if ((rc = launch_readout_forward(c, labels_dev))) return rc;
       continue;
     }
     if (!(fuse_top && l == c->L - 1) && (rc = launch_current_gemm(c, l))) return rc;

@@ -188,15 +188,15 @@ def test_layer_forward_in_one_launch_same_as_separate_launches(monkeypatch):
     inp = workloads.generate(wl, w_gain=3.0)
     monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
     out = []
-    for knob in ("2", "1", "0"):
+    for knob in ("3", "2", "1", "0"):                 # 3: the last layer's launch also forms the readout's currents
         monkeypatch.setenv("SNN_FUSE_LAYER", knob)
         snn = make(wl, inp)
         snn.forward(inp.X, inp.labels)
         out.append([snn.get_tensor("membrane", 1), snn.get_tensor("spikes", 1), snn.get_tensor("current", 1),
                     snn.get_tensor("membrane", 2), snn.get_tensor("spikes", 2), snn.get_tensor("readout_trace")])
         snn.destroy()
-    ref = out[2]
-    for got in out[:2]:
+    ref = out[3]
+    for got in out[:3]:
         same = all(np.array_equal(got[i], ref[i]) for i in (1, 4))
         near = np.abs(ref[0] - wl.theta) <= parity.BAND
         assert np.array_equal(got[1][~near], ref[1][~near])
@@ -204,6 +204,32 @@ def test_layer_forward_in_one_launch_same_as_separate_launches(monkeypatch):
             for i in (0, 2, 3, 5):
                 assert np.abs(got[i] - ref[i]).max() <= 1e-5 * np.abs(ref[i]).max()
     assert ref[1].mean() > 0.005
+
+
+@pytest.mark.parametrize("T,sizes,surrogate,slope", [(41, (80, 128, 128, 10), "superspike", 10.0),
+                                                      (150, (90, 128, 40, 20), "arctan", 2.0),
+                                                      (64, (60, 256, 96, 10), "sigmoid", 4.0),
+                                                      (129, (50, 128, 256, 20), "triangular", 1.0),
+                                                      (70, (70, 128, 128, 3), "boxcar", 1.0),
+                                                      (33, (70, 256, 64, 12), "ste", 1.0)])
+def test_layer_reverse_in_one_launch(monkeypatch, T, sizes, surrogate, slope):
+    """bf16 products, feed-forward spiking layers of 128 or 256 neurons below a layer of at most
+    128 columns: dS, surrogate, reverse scan and the hi/lo store run as one launch, a workgroup
+    per sample and 128 neurons, in blocks of 64 steps from the end.  One to three blocks with
+    ragged first blocks, 24 to 128 columns above (one, two and four 32-wide contraction steps),
+    every surrogate; the library uses the path from 128 samples on, the knob lowers that."""
+    monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
+    wl = workloads.Workload(name="layer-reverse", index=23, T=T, B=5, sizes=sizes, recurrent=(False, False),
+                            beta=(0.9, 0.93, 0.95), theta=1.0, surrogate=surrogate, slope=slope, precision="bf16",
+                            rate_lo=0.03, rate_hi=0.12)
+    rep = full_step_parity(wl, w_gain=2.0)
+    assert rep["spike_rate"][0] > 0.005
+
+
+def test_layer_reverse_in_one_launch_with_trainable_decays(monkeypatch):
+    """The same path with the decay gradients' partial sums taken inside the scan."""
+    monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
+    beta_step_parity(workloads.CONFIGS["shd_ff128"].scaled(T=100, B=12), w_gain=3.0)
 
 
 @pytest.fixture
