@@ -49,6 +49,12 @@ def algorithmic_bytes(wl, kernel, layer):
     fused_rev = (bf and layer < L and not wl.recurrent[layer - 1] and n_out % 64 == 0
                  and pad8(wl.sizes[layer + 1]) <= 128)
     fused_fwd = fused_rev and layer == L - 1 and n_out in (64, 128, 256) and pad8(wl.sizes[L]) <= 32
+    # a feed-forward layer of 64..256 padded neurons runs product and scan as one launch from 128 samples on
+    whole_fwd = (bf and layer < L and not wl.recurrent[layer - 1] and pad8(n_out) % 64 == 0 and pad8(n_out) <= 256
+                 and wl.B >= 128)
+    if kernel == "lif_forward" and whole_fwd:   # read the spikes below (1) and W, write V (4) and S (1) [+ J]
+        with_j = layer == L - 1 and pad8(n_out) == 128 and pad8(wl.sizes[L]) <= 32
+        return M * n_in + 2 * n_in * n_out + M * n_out * (4 + 1) + (M * pad8(wl.sizes[L]) * 4 if with_j else 0)
     if kernel == "lif_forward":      # read I (4), write V (4) and S (1 byte) [+ the readout's currents]
         return M * n_out * (4 + 4 + 1) + (M * pad8(wl.sizes[L]) * 4 if fused_fwd else 0)
     if kernel == "lif_reverse":      # read dS (4) [or the current gradients above] and V (4), write dI (4)

@@ -6,19 +6,20 @@
 // lif_reverse_top_kernel does the same with one wavefront per 64 chains, each lane walking
 // its chain through global memory: per step a load, a store and a share of the dX fetches,
 // which is what bounds it (a wavefront issues a memory instruction about every 60 cycles).
-// Here a workgroup owns one sample and 128 neurons, and per block of 64 steps, last block
-// first:
-//   1. V (64 x 128) and dX (64 x ldc words) arrive through 16-byte loads issued one block
+// Here a workgroup owns one sample and BN = 64 neurons (128 also builds; measured slower: one
+// workgroup per compute unit, nothing overlaps its phases), and per block of 64 steps, last
+// block first:
+//   1. V (64 x BN) and dX (64 x ldc words) arrive through 16-byte loads issued one block
 //      ahead (they land during the previous block's scan) and go to LDS;
-//   2. dS: 32x32x16 bfloat16 MFMAs, the rounded weights of the wavefront's 64 neurons resident
+//   2. dS: 32x32x16 bfloat16 MFMAs, the rounded weights of the wavefront's BN/2 neurons resident
 //      in registers, the hi and lo halves of dX as the second operand, lo first; a wavefront
-//      holds 32 steps x 64 neurons of the result;
+//      holds 32 steps x BN/2 neurons of the result;
 //   3. still in the MFMA layout, every lane turns its elements into the two coefficients of
 //      the step: with s = surr(V - theta), g' = beta g + s (dS - theta g) = c1 g + c2,
 //      c1 = beta - s theta, c2 = s dS.  The surrogate (a division or an exponential) is
 //      computed here by all four wavefronts, not inside the sequential scan;
-//   4. scan: two wavefronts, one neuron per lane, 64 steps of one fused multiply-add each on
-//      LDS (coefficients read 16 steps ahead, g written back in place of c2);
+//   4. scan: BN/64 wavefronts, one neuron per lane, 64 steps of one fused multiply-add each on
+//      LDS (coefficients read 8 steps ahead, g written back in place of c2);
 //   5. store: all wavefronts pack g into hi/lo words and write whole rows, 16 bytes per lane.
 // g (and the decay gradient's partial sum) stay in the scanning lanes' registers from block
 // to block.  Rows past T read as zero: c2 = 0 there and g, zero at the start, stays zero.
@@ -39,7 +40,7 @@ struct LayerReverseArgs {
   const float *beta_v;     // [ld]
   float theta, slope;
   float *db_part;          // [B][ld] per-sample parts of the decay gradient, or NULL
-  int T, B, ld;            // ld: a multiple of 128
+  int T, B, ld;            // ld: a multiple of the workgroup's neurons
   int nt_store;            // dI streams past the caches
 #ifdef SNN_LAYER_PROBE
   unsigned long long *probe;   // [B][2][8] device clock at the phase boundaries of the first two blocks (development builds only)
@@ -60,15 +61,19 @@ template <int SURR> __device__ __forceinline__ float surr_rcp(float k, float x) 
   return surr<SURR>(k, x);
 }
 
-template <int KS, int SURR>
-__global__ __launch_bounds__(256) void lif_layer_reverse_kernel(const LayerReverseArgs a) {
-  constexpr int BM = 64, BN = 128;
+template <int KS, int SURR, int BN>
+__global__ __launch_bounds__(256, BN == 64 ? 2 : 1) void lif_layer_reverse_kernel(const LayerReverseArgs a) {
+  static_assert(BN == 64 || BN == 128, "neurons per workgroup");
+  constexpr int BM = 64;
+  constexpr int NJ = BN / 64;                         // 32-neuron MFMA tiles per wavefront
+  constexpr int NV = BN / 16;                         // 16-byte accesses per thread to a 64 x BN fp32 tile
+  constexpr int LPR = BN / 4;                         // lanes per row in those accesses
   constexpr int CP = BN * 4 + 16;                     // bytes between time rows of the fp32 tiles
   constexpr int PITCH = CP / 4;
   constexpr int XP = KS * 128 + 16;                   // bytes between time rows of the dX tile (32 KS words)
   constexpr int TILE = BM * CP;
   constexpr int KK = 2 * KS;                          // 16-wide MFMA steps over the columns above
-  static_assert(XP <= CP, "the dX tile shares the space of a coefficient tile");
+  static_assert(BM * XP <= 2 * TILE, "the dX tile shares the space of the coefficient tiles");
   __shared__ __attribute__((aligned(16))) char lds[3 * TILE];
   __shared__ __attribute__((aligned(16))) float betas[BN];
   char *const Vt = lds, *const C1 = lds + TILE, *const C2 = lds + 2 * TILE, *const Xt = C1;
@@ -89,22 +94,22 @@ __global__ __launch_bounds__(256) void lif_layer_reverse_kernel(const LayerRever
 
   // First MFMA operand: W[n][c], lane -> neuron (lane & 31) of the 32-neuron tile, columns
   // 16 kk + 8 h .. +7.  Resident for the whole kernel.
-  bf16x8 wf[2][KK];
+  bf16x8 wf[NJ][KK];
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+  for (int j = 0; j < NJ; ++j)
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      const int n = n0 + 64 * wn + 32 * j + (lane & 31), c = 16 * kk + 8 * h;
+      const int n = n0 + 32 * NJ * wn + 32 * j + (lane & 31), c = 16 * kk + 8 * h;
       wf[j][kk] = __builtin_bit_cast(bf16x8, ld_b128(rW, c + 7 < a.ldq ? (n * a.ldq + c) * 2 : OOB, 0));
     }
 
   // A block's global loads: V as 8 x 16 bytes per thread (row = 8 k + tid / 32), dX as KK x 16
   // bytes per thread over rows of 8 KS chunks (chunks beyond ldc read as zero).
-  u32x4 xv[8], xd[KK];
+  u32x4 xv[NV], xd[KK];
   auto fetch = [&](int t0) {                          // t0 < 0: nothing is read
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int t = t0 + 8 * k + (tid >> 5), col = (tid & 31) * 4;
+    for (int k = 0; k < NV; ++k) {
+      const int t = t0 + (256 / LPR) * k + tid / LPR, col = (tid % LPR) * 4;
       xv[k] = ld_b128(rV, t0 >= 0 && t < a.T ? ((t * a.B + b) * a.ld + n0 + col) * 4 : OOB, 0);
     }
 #pragma unroll
@@ -115,7 +120,7 @@ __global__ __launch_bounds__(256) void lif_layer_reverse_kernel(const LayerRever
   };
   auto fill = [&]() {
 #pragma unroll
-    for (int k = 0; k < 8; ++k) *(u32x4 *)(Vt + (8 * k + (tid >> 5)) * CP + (tid & 31) * 16) = xv[k];
+    for (int k = 0; k < NV; ++k) *(u32x4 *)(Vt + ((256 / LPR) * k + tid / LPR) * CP + (tid % LPR) * 16) = xv[k];
 #pragma unroll
     for (int k = 0; k < KK; ++k) {
       const int idx = k * 256 + tid, row = idx / (8 * KS), ch = idx % (8 * KS);
@@ -136,9 +141,9 @@ __global__ __launch_bounds__(256) void lif_layer_reverse_kernel(const LayerRever
 
     // 2. dS^T tile: rows = neurons, columns = steps; the lane holds step 32 wm + (lane & 31)
     // and register r neuron 8 (r / 4) + 4 h + (r % 4) of its 32-neuron tile.
-    f32x16 acc[2];
+    f32x16 acc[NJ];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
     {
@@ -155,22 +160,22 @@ __global__ __launch_bounds__(256) void lif_layer_reverse_kernel(const LayerRever
         hi[kk] = __builtin_bit_cast(bf16x8, hh);
         const bf16x8 lo = __builtin_bit_cast(bf16x8, ll);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j][kk], lo, acc[j], 0, 0, 0);
+        for (int j = 0; j < NJ; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j][kk], lo, acc[j], 0, 0, 0);
       }
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j][kk], hi[kk], acc[j], 0, 0, 0);
+        for (int j = 0; j < NJ; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j][kk], hi[kk], acc[j], 0, 0, 0);
     }
     __syncthreads();                                  // every wavefront has read the dX tile: C1 takes its place
     SNN_RPROBE(2);
 
     // 3. coefficients
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int t = 32 * wm + (lane & 31), n = 64 * wn + 32 * j + 8 * q + 4 * h;
+        const int t = 32 * wm + (lane & 31), n = 32 * NJ * wn + 32 * j + 8 * q + 4 * h;
         const f32x4 vv = *(const f32x4 *)(Vt + t * CP + n * 4);
         const f32x4 bb = *(const f32x4 *)(&betas[n]);
         f32x4 c1, c2;
@@ -187,12 +192,12 @@ __global__ __launch_bounds__(256) void lif_layer_reverse_kernel(const LayerRever
     SNN_RPROBE(3);
 
     // 4. scan, steps t0 + 63 down to t0: dI_t = g, then g <- c1 g + c2 (and db += g V_t)
-    if (wave < 2) {
+    if (wave < BN / 64) {
       const float *p1 = (const float *)(C1 + tid * 4), *pv = (const float *)(Vt + tid * 4);
       float *p2 = (float *)(C2 + tid * 4);
       auto scan = [&](auto DB) {
         constexpr bool with_db = decltype(DB)::value;
-        constexpr int U = 16;
+        constexpr int U = 8;
         float n1[U], n2[U], nv[U];
         auto read = [&](int s0) {
 #pragma unroll
@@ -207,7 +212,7 @@ __global__ __launch_bounds__(256) void lif_layer_reverse_kernel(const LayerRever
           float c1[U], c2[U], vv[U];
 #pragma unroll
           for (int u = 0; u < U; ++u) { c1[u] = n1[u]; c2[u] = n2[u]; vv[u] = with_db ? nv[u] : 0.f; }
-          if (s0 >= U) read(s0 - U);                  // the next 16 steps' coefficients, before these 16 are taken
+          if (s0 >= U) read(s0 - U);                  // the next 8 steps' coefficients, before these 8 are taken
 #pragma unroll
           for (int u = 0; u < U; ++u) asm volatile("" : "+v"(c1[u]), "+v"(c2[u]));
 #pragma unroll
@@ -223,10 +228,10 @@ __global__ __launch_bounds__(256) void lif_layer_reverse_kernel(const LayerRever
     __syncthreads();
     SNN_RPROBE(4);
 
-    // 5. store: 32 lanes x 16 bytes per row, 8 rows per instruction
+    // 5. store: BN/4 lanes x 16 bytes per row
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int row = 8 * k + (tid >> 5), col = (tid & 31) * 4, t = t0 + row;
+    for (int k = 0; k < NV; ++k) {
+      const int row = (256 / LPR) * k + tid / LPR, col = (tid % LPR) * 4, t = t0 + row;
       const f32x4 gq = *(const f32x4 *)(C2 + row * CP + col * 4);
       u32x4 w;
       w.x = pack_hl(gq[0]); w.y = pack_hl(gq[1]); w.z = pack_hl(gq[2]); w.w = pack_hl(gq[3]);
@@ -235,8 +240,9 @@ __global__ __launch_bounds__(256) void lif_layer_reverse_kernel(const LayerRever
       else __builtin_amdgcn_raw_buffer_store_b128(w, rdI, vo, 0, 0);
     }
     SNN_RPROBE(5);
-    // (The next block's fill writes V and dX = C1, which nobody reads any more; C2 is written
-    // again only after two more barriers.)
+    // The next block's fill writes V and dX, which takes the place of C1 and, when its rows are
+    // longer than a coefficient row, of part of C2, which this store phase is still reading.
+    if (XP > CP) __syncthreads();
   }
   if (a.db_part && tid < BN) a.db_part[b * a.ld + n0 + tid] = db;
 }

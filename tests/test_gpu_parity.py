@@ -211,11 +211,12 @@ def test_layer_forward_in_one_launch_same_as_separate_launches(monkeypatch):
                                                       (64, (60, 256, 96, 10), "sigmoid", 4.0),
                                                       (129, (50, 128, 256, 20), "triangular", 1.0),
                                                       (70, (70, 128, 128, 3), "boxcar", 1.0),
-                                                      (33, (70, 256, 64, 12), "ste", 1.0)])
+                                                      (33, (70, 256, 64, 12), "ste", 1.0),
+                                                      (50, (40, 192, 64, 10), "superspike", 25.0)])
 def test_layer_reverse_in_one_launch(monkeypatch, T, sizes, surrogate, slope):
-    """bf16 products, feed-forward spiking layers of 128 or 256 neurons below a layer of at most
+    """bf16 products, feed-forward spiking layers of 64 to 256 neurons below a layer of at most
     128 columns: dS, surrogate, reverse scan and the hi/lo store run as one launch, a workgroup
-    per sample and 128 neurons, in blocks of 64 steps from the end.  One to three blocks with
+    per sample and 64 neurons, in blocks of 64 steps from the end.  One to three blocks with
     ragged first blocks, 24 to 128 columns above (one, two and four 32-wide contraction steps),
     every surrogate; the library uses the path from 128 samples on, the knob lowers that."""
     monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
