@@ -233,6 +233,23 @@ def test_layer_reverse_in_one_launch_with_trainable_decays(monkeypatch):
     beta_step_parity(workloads.CONFIGS["shd_ff128"].scaled(T=100, B=12), w_gain=3.0)
 
 
+@pytest.mark.parametrize("theta,beta,T,B", [(0.37, (0.9, 0.93, 0.95), 40, 5), (2.5, (1.0, 0.0, 0.9), 70, 6),
+                                            (1.0, (0.9, 0.9, 0.9), 1, 9), (1.0, (0.9, 0.9, 0.9), 2, 9),
+                                            (0.8, (0.95, 0.9, 0.9), 21, 131)])
+def test_layer_launches_thresholds_decays_and_batch_tails(monkeypatch, theta, beta, T, B):
+    """The one-launch layer kernels away from theta = 1 (their scan decides spikes without a
+    compare, exactly for any threshold in [2^-60, 2^26]), with non-leaky (beta = 1) and
+    memoryless (beta = 0) layers, one and two time steps, and a batch of 131 samples, which takes
+    the path without the test knob and leaves five of the launched workgroups without a sample."""
+    if B < 128:
+        monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
+    wl = workloads.Workload(name="layer-edge", index=24, T=T, B=B, sizes=(60, 128, 128, 10), recurrent=(False, False),
+                            beta=beta, theta=theta, surrogate="superspike", slope=10.0, precision="bf16",
+                            rate_lo=0.03, rate_hi=0.12)
+    rep = full_step_parity(wl, w_gain=2.0 * theta)
+    assert T < 20 or rep["spike_rate"][0] > 0.005
+
+
 @pytest.fixture
 def large_tensor_paths(monkeypatch):
     """The kernels chosen for tensors that stream past the caches (the streamed current product,
