@@ -24,7 +24,12 @@
 //      neurons per lane, decided again from the stored V (the same exact comparison);
 //   5. (last spiking layer of 128 neurons, at most 32 padded classes) the readout's currents
 //      J = S W_out of the block, eight 32x32x16 MFMAs per wavefront on the spikes in LDS: no
-//      product launch for the readout.
+//      product launch for the readout;
+//   6. (same case) the readout itself: the LI scan of the block in eight segments of 16 steps
+//      (linear in the state, so segments are integrated from zero, chained, and integrated
+//      again from their true entry state), the maximum over time or the integral, and after
+//      the last block softmax cross-entropy, dz and the readout's current gradients in closed
+//      form per segment: no launch for the readout at all.
 // The potential is carried in the scanning lanes' registers from block to block.
 // Rows past T read as zero and are not stored; columns of W past the fan-in are zero.
 #pragma once
@@ -52,6 +57,18 @@ struct LayerForwardArgs {
   const uint16_t *Qr;      // rounded W_out^T [32 or more rows: class][ldqr: neuron] bfloat16, zero beyond the classes
   int ldqr;
   unsigned qr_bytes;
+  // ... and the whole readout (variants READOUT >= 2): LI scan, max over time or integral,
+  // softmax cross-entropy and the readout's current gradients, as readout_loss_kernel computes them
+  float *Y;                // [T*B][ldj] readout trace
+  float *z;                // [B][ldj] logits
+  int *tstar;              // [B][ldj] first maximising step
+  const int *labels;       // [B]
+  float *loss_b;           // [B] per-sample loss
+  float *dz;               // [B][ldj]
+  int *err;                // flag: bit 0 = label out of range
+  uint32_t *dJ;            // [T*B][ldj] hi/lo words
+  const float *beta_r;     // [ldj] decays of the readout
+  int C;                   // classes
 #ifdef SNN_LAYER_PROBE
   unsigned long long *probe;   // [B][8] device clock at the phase boundaries of the first block (development builds only)
 #endif
@@ -62,9 +79,15 @@ struct LayerForwardArgs {
 #define SNN_PROBE(i) do { } while (0)
 #endif
 
-template <int TN, int NS = 4, bool READOUT = false>
+// READOUT: 0 none; 1 the launch also forms the readout's currents J; 2 and the LI scan, the
+// maximum over time, the loss and dJ; 3 the same with the integral loss.
+template <int TN, int NS = 4, int READOUT = 0>
 __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerForwardArgs a) {
-  static_assert(!READOUT || TN == 2, "the readout variant holds the whole layer");
+  static_assert(!READOUT || TN == 2, "the readout variants hold the whole layer");
+  constexpr bool LOSS = READOUT >= 2, INTEGRAL = READOUT == 3;
+  constexpr int JP = 36;                              // floats between rows of the 128 x 32 readout tile in LDS
+  __shared__ float x_e[LOSS ? 2 : 1][8][32], x_best[8][32];
+  __shared__ int x_tb[8][32];
   typedef SpikeTile<2, 2, 2, TN, NS> Tile;
   constexpr int TM = 2, WN = 2, BM = Tile::BM, BN = Tile::BN, PI = Tile::PI, QI = Tile::QI;
   static_assert(BM == 128 && PI == 1 && (BN == 64 || BN == 128), "128 steps x 64 or 128 neurons");
@@ -106,6 +129,14 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
     for (int kk = 0; kk < 8; ++kk)
       wr[kk] = __builtin_bit_cast(bf16x8, ld_b128(rQ, ((lane & 31) * a.ldqr + 16 * kk + 8 * h) * 2, 0));
   }
+
+  // Readout state of class tid % 32 (variants with the loss)
+  const float beta_r = LOSS && (tid & 31) < a.ldj ? a.beta_r[tid & 31] : 0.f;
+  float bseg = beta_r;                                // beta^16
+#pragma unroll
+  for (int i = 0; i < 4; ++i) bseg *= bseg;
+  float y_in = 0.f, best = -INFINITY, ysum = 0.f;
+  int tb = 0, par = 0;
 
   for (int t0 = 0; t0 < a.T; t0 += BM) {
     SNN_PROBE(0);
@@ -230,10 +261,125 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
         const int jo = t0 + row < a.T && c + 3 < a.ldj ? (((t0 + row) * a.B + b) * a.ldj + c) * 4 : OOB;
         __builtin_amdgcn_raw_buffer_store_b128(x, rJ, jo, 0, 0);
       }
+      if (LOSS) {
+        // 6. readout scan of the block.  The LI readout is linear in its state, so the 128 steps
+        // are cut in eight segments of 16: thread -> (segment tid / 32, class tid % 32).  A
+        // segment is first integrated from a zero state, the results are exchanged, the state
+        // entering each segment follows, and the segment is integrated again from it, step by
+        // step as the sequential scan would (the scheme of readout_loss_kernel, which has the
+        // eight wavefronts of a workgroup where this has the eight 32-lane groups).
+        __syncthreads();                              // V has been stored: the tile's space is free
+        float *Jt = (float *)lds;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          f32x4 x = {jt[4 * q], jt[4 * q + 1], jt[4 * q + 2], jt[4 * q + 3]};
+          *(f32x4 *)&Jt[row * JP + 8 * q + 4 * h] = x;
+        }
+        __syncthreads();
+        const int g = tid >> 5, c = tid & 31, ts0 = t0 + 16 * g;
+        float j[16], e = 0.f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+          j[k] = Jt[(16 * g + k) * JP + c];
+          e = beta_r * e + j[k];
+        }
+        x_e[par][g][c] = e;
+        __syncthreads();
+        float cst = y_in, y = 0.f;
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+          if (v == g) y = cst;
+          cst = bseg * cst + x_e[par][v][c];
+        }
+        y_in = cst;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+          y = beta_r * y + j[k];
+          Jt[(16 * g + k) * JP + c] = y;
+          if (INTEGRAL) { if (ts0 + k < a.T) ysum += y; }
+          else if (ts0 + k < a.T && y > best) { best = y; tb = ts0 + k; }
+        }
+        par ^= 1;
+        __syncthreads();
+        const rsrc_t rY = make_rsrc(a.Y, (unsigned)a.T * a.B * a.ldj * 4u);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {                 // 8 lanes x 16 bytes per row, 32 rows per instruction
+          const int r = 32 * k + (tid >> 3), cc = (tid & 7) * 4;
+          const u32x4 x = *(const u32x4 *)&Jt[r * JP + cc];
+          st_b128(rY, t0 + r < a.T && cc + 3 < a.ldj ? (((t0 + r) * a.B + b) * a.ldj + cc) * 4 : OOB, 0, x);
+        }
+      }
     }
     SNN_PROBE(4);
     __syncthreads();                                  // the next block's stages overwrite the tile
     SNN_PROBE(5);
+  }
+
+  if (LOSS) {
+    // first maximiser over the segments (integral loss: the sum of the segments' sums, in order)
+    const int g = tid >> 5, c = tid & 31;
+    x_best[g][c] = INTEGRAL ? ysum : best;
+    x_tb[g][c] = tb;
+    __syncthreads();
+    best = x_best[0][c];
+    tb = x_tb[0][c];
+#pragma unroll
+    for (int v = 1; v < 8; ++v) {
+      const float bv = x_best[v][c];
+      const int tv = x_tb[v][c];
+      if (INTEGRAL) best += bv;
+      else if (bv > best || (bv == best && tv < tb)) { best = bv; tb = tv; }
+    }
+    const bool live = c < a.C;
+    const int p = b * a.ldj + c;
+    if (live && g == 0) { a.z[p] = best; a.tstar[p] = tb; }
+    // softmax cross-entropy of the sample (every 32-lane group, for dz)
+    float m = live ? best : -INFINITY;
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    const float ex = live ? expf(best - m) : 0.f;
+    float sum = ex;
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    int lab = a.labels[b];
+    if (lab < 0 || lab >= a.C) { if (tid == 0) atomicOr(a.err, 1); lab = 0; }
+    float zl = (live && c == lab) ? best : 0.f;
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) zl += __shfl_xor(zl, o);
+    const float d = live ? (ex / sum - (c == lab ? 1.f : 0.f)) / (float)a.B : 0.f;
+    if (g == 0) {
+      if (live) a.dz[p] = d;
+      if (c == 0) a.loss_b[b] = m + logf(sum) - zl;
+    }
+    // dJ_t = h_t with h_t = beta h_{t+1} + dz [t == t*] (integral loss: dz at every step): entered
+    // per segment in closed form, the recursion inside it
+    const float l2b = log2f(beta_r);
+    const rsrc_t rdJ = make_rsrc(a.dJ, (unsigned)a.T * a.B * a.ldj * 4u);
+    uint32_t *Ht = (uint32_t *)lds;
+    for (int t0 = 0; t0 < a.T; t0 += BM) {
+      const int ts0 = t0 + 16 * g;
+      float hh;
+      if (INTEGRAL) {
+        const int n = a.T - (ts0 + 16);
+        hh = n <= 0 ? 0.f : beta_r == 1.f ? d * (float)n : d * (1.f - exp2f((float)n * l2b)) / (1.f - beta_r);
+      } else {
+        const int n = tb - (ts0 + 16);
+        hh = n > 0 ? d * exp2f((float)n * l2b) : n == 0 ? d : 0.f;
+      }
+      __syncthreads();                                // the previous block's rows have been stored
+#pragma unroll
+      for (int k = 15; k >= 0; --k) {
+        hh = beta_r * hh + ((INTEGRAL ? ts0 + k < a.T : ts0 + k == tb) ? d : 0.f);
+        Ht[(16 * g + k) * JP + c] = pack_hl(hh);
+      }
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int r = 32 * k + (tid >> 3), cc = (tid & 7) * 4;
+        const u32x4 x = *(const u32x4 *)&Ht[r * JP + cc];
+        st_b128(rdJ, t0 + r < a.T && cc + 3 < a.ldj ? (((t0 + r) * a.B + b) * a.ldj + cc) * 4 : OOB, 0, x);
+      }
+    }
   }
 }
 

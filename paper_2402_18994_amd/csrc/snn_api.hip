@@ -788,13 +788,14 @@ int launch_lif_reverse_fused(snn_ctx *c, int l) {
 // owns a sample and 64 or 128 neurons, so it needs enough samples to fill the chip; 32-bit
 // byte offsets into the spikes below and V; a threshold the scan's compare-free spike
 // decision is exact for.
-// SNN_FUSE_LAYER: 0 never, 1 all but the last spiking layer, 2 every such layer, 3 (default)
-// the last one also forms the readout's currents when it has exactly 128 padded neurons;
+// SNN_FUSE_LAYER: 0 never, 1 all but the last spiking layer, 2 every such layer, 3 the last one
+// also forms the readout's currents when it has exactly 128 padded neurons, 4 (default) and runs
+// the readout scan, the loss and the readout's current gradients;
 // SNN_FUSE_LAYER_MIN_B: samples from which it is used (default 128); SNN_LAYER_NEURONS: 64 or
 // 128 neurons per workgroup.  All read per call.
 int layer_fuse_mode() {
   const char *e = getenv("SNN_FUSE_LAYER");
-  return e ? atoi(e) : 3;
+  return e ? atoi(e) : 4;
 }
 bool layer_forward_fusable(snn_ctx *c, int l) {
   if (l < 0 || l > c->L - 2) return false;
@@ -807,15 +808,18 @@ bool layer_forward_fusable(snn_ctx *c, int l) {
          y.qf_plane >= (long long)y.ld * y.ldqf && c->theta >= 0x1p-60f && c->theta <= 0x1p26f;
 }
 
-// with_readout: l is the last spiking layer and the launch also forms the readout's currents.
-bool layer_forward_takes_readout(snn_ctx *c) {
+// What the launch of the last spiking layer takes over from the readout: 0 nothing, 1 its
+// currents J, 2 also the LI scan, the loss and dJ (what readout_loss_kernel does).
+int layer_forward_takes_readout(snn_ctx *c) {
   const char *e = getenv("SNN_LAYER_NEURONS");
   const Layer &ro = c->layers[c->L - 1];
-  return c->L >= 2 && layer_fuse_mode() >= 3 && layer_forward_fusable(c, c->L - 2) && c->layers[c->L - 2].ld == 128 &&
-         (!e || atoi(e) == 128) && c->ldC <= 32 && ro.qf_plane >= 32ll * ro.ldqf && ro.ldqf >= 128;
+  const int mode = layer_fuse_mode();
+  const bool ok = c->L >= 2 && mode >= 3 && layer_forward_fusable(c, c->L - 2) && c->layers[c->L - 2].ld == 128 &&
+                  (!e || atoi(e) == 128) && c->ldC <= 32 && ro.qf_plane >= 32ll * ro.ldqf && ro.ldqf >= 128;
+  return !ok ? 0 : mode >= 4 && c->hl ? 2 : 1;
 }
 
-int launch_layer_forward(snn_ctx *c, int l, bool with_readout) {
+int launch_layer_forward(snn_ctx *c, int l, int with_readout, const int32_t *labels) {
   Layer &y = c->layers[l];
   const SpikeSrc s = spikes_below(c, l);
   if (!s.p) return fail(c, SNN_ERR_NULL, "input raster is NULL");
@@ -833,7 +837,17 @@ int launch_layer_forward(snn_ctx *c, int l, bool with_readout) {
   if (with_readout) {
     Layer &ro = c->layers[c->L - 1];
     a.J = ro.I; a.ldj = c->ldC; a.Qr = ro.Qf; a.ldqr = ro.ldqf; a.qr_bytes = (unsigned)(ro.qf_plane * 2);
-    hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, true>), grid, dim3(256), 0, c->stream, a);
+    if (with_readout == 2) {
+      if (!labels) return fail(c, SNN_ERR_NULL, "labels are NULL");
+      a.Y = ro.V; a.z = c->z; a.tstar = c->tstar; a.labels = labels; a.loss_b = c->loss_b; a.dz = c->dz;
+      a.err = c->err_flag; a.dJ = ro.dI; a.beta_r = ro.beta_v; a.C = c->C;
+      if (c->integral) hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, 3>), grid, dim3(256), 0, c->stream, a);
+      else hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, 2>), grid, dim3(256), 0, c->stream, a);
+      c->dj_ready = true;
+      c->loss_ready = false;
+    } else {
+      hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, 1>), grid, dim3(256), 0, c->stream, a);
+    }
     ro.i_ready = true;
   } else if (bn == 64) hipLaunchKernelGGL((lif_layer_forward_kernel<1, 4>), grid, dim3(256), 0, c->stream, a);
   else hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4>), grid, dim3(256), 0, c->stream, a);
@@ -1093,15 +1107,15 @@ static int32_t forward_layers(snn_ctx *c, const int32_t *labels_dev, float *loss
   int rc;
   const int whole = layer_fuse_mode();                  // layers that run as one launch, product and scan
   const bool whole_top = whole >= 2 && layer_forward_fusable(c, c->L - 2);
-  const bool with_readout = whole_top && layer_forward_takes_readout(c);
+  const int with_readout = whole_top ? layer_forward_takes_readout(c) : 0;
   const bool fuse_top = !whole_top && top_forward_fusable(c);   // the last spiking layer's scan forms the readout's currents
   for (int l = 0; l < c->L; ++l) {
     if (whole >= 1 && (l < c->L - 2 || whole_top) && layer_forward_fusable(c, l)) {
-      if ((rc = launch_layer_forward(c, l, l == c->L - 2 && with_readout))) return rc;
+      if ((rc = launch_layer_forward(c, l, l == c->L - 2 ? with_readout : 0, labels_dev))) return rc;
       continue;
     }
-    if (l == c->L - 1 && with_readout) {                // J is there already
-      if ((rc = launch_readout_forward(c, labels_dev))) return rc;
+    if (l == c->L - 1 && with_readout) {                // J is there already, perhaps the whole readout
+      if (with_readout == 1 && (rc = launch_readout_forward(c, labels_dev))) return rc;
       continue;
     }
     if (!(fuse_top && l == c->L - 1) && (rc = launch_current_gemm(c, l))) return rc;

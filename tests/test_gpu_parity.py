@@ -188,20 +188,22 @@ def test_layer_forward_in_one_launch_same_as_separate_launches(monkeypatch):
     inp = workloads.generate(wl, w_gain=3.0)
     monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
     out = []
-    for knob in ("3", "2", "1", "0"):                 # 3: the last layer's launch also forms the readout's currents
+    # 3: the last layer's launch also forms the readout's currents; 4: and runs the whole readout
+    for knob in ("4", "3", "2", "1", "0"):
         monkeypatch.setenv("SNN_FUSE_LAYER", knob)
         snn = make(wl, inp)
         snn.forward(inp.X, inp.labels)
         out.append([snn.get_tensor("membrane", 1), snn.get_tensor("spikes", 1), snn.get_tensor("current", 1),
-                    snn.get_tensor("membrane", 2), snn.get_tensor("spikes", 2), snn.get_tensor("readout_trace")])
+                    snn.get_tensor("membrane", 2), snn.get_tensor("spikes", 2), snn.get_tensor("readout_trace"),
+                    snn.get_tensor("d_readout_current"), snn.get_tensor("loss_per_sample")])
         snn.destroy()
-    ref = out[3]
-    for got in out[:3]:
+    ref = out[4]
+    for got in out[:4]:
         same = all(np.array_equal(got[i], ref[i]) for i in (1, 4))
         near = np.abs(ref[0] - wl.theta) <= parity.BAND
         assert np.array_equal(got[1][~near], ref[1][~near])
         if same:
-            for i in (0, 2, 3, 5):
+            for i in (0, 2, 3, 5, 6, 7):
                 assert np.abs(got[i] - ref[i]).max() <= 1e-5 * np.abs(ref[i]).max()
     assert ref[1].mean() > 0.005
 
@@ -248,6 +250,29 @@ def test_layer_launches_thresholds_decays_and_batch_tails(monkeypatch, theta, be
                             rate_lo=0.03, rate_hi=0.12)
     rep = full_step_parity(wl, w_gain=2.0 * theta)
     assert T < 20 or rep["spike_rate"][0] > 0.005
+
+
+@pytest.mark.parametrize("loss,T,classes", [("integral", 300, 20), ("max", 300, 20), ("integral", 50, 5), ("max", 129, 32)])
+def test_last_layer_launch_runs_the_whole_readout(monkeypatch, loss, T, classes):
+    """Last spiking layer of 128 neurons, at most 32 padded classes, bf16 products: its forward
+    launch also forms the readout's currents, runs the readout scan in eight segments per block
+    of 128 steps, and computes logits, first maximising steps, loss and the readout's current
+    gradients.  Both losses, one to three blocks with ragged tails, 5 to 32 classes; an
+    out-of-range label is reported through the same flag as by the separate kernel."""
+    from paper_2402_18994_amd.binding import SnnError
+    monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
+    wl = workloads.Workload(name="whole-readout", index=25, T=T, B=6, sizes=(70, 128, 128, classes),
+                            recurrent=(False, False), beta=(0.9, 0.93, 0.95), theta=1.0, surrogate="superspike",
+                            slope=10.0, precision="bf16", rate_lo=0.03, rate_hi=0.12, loss=loss)
+    full_step_parity(wl, w_gain=2.0, check_sgd=False)
+    inp = workloads.generate(wl, w_gain=2.0)
+    snn = make(wl, inp)
+    bad = inp.labels.copy(); bad[2] = classes
+    with pytest.raises(SnnError) as e:
+        snn.forward(inp.X, bad)
+    assert e.value.status == 2
+    snn.forward(inp.X, inp.labels)                      # the flag was cleared
+    snn.destroy()
 
 
 @pytest.fixture
