@@ -881,4 +881,85 @@ __global__ __launch_bounds__(256) void param_update_kernel(const ParamJobs jobs,
   }
 }
 
+// Reduction of the per-split partial weight gradients and the parameter update in one launch,
+// for the step that goes straight from snn_backward to snn_sgd_step: per matrix W [K][N],
+//   dW = sum over the splits, in the order reduce_partials_kernel adds them (four interleaved
+//        running sums, then ((s0 + s1) + s2) + s3): the same bits as the separate launch;
+//   W <- W - lr dW, Qb and Qf refreshed as param_update_kernel does.
+// A workgroup owns 8 rows x 32 columns (432 workgroups at 700-128-128-20, where 32 x 32 tiles
+// would leave 108 to pull 28 MB of partial sums); every load of a partial is a full 128-byte
+// row piece; the transposed operand leaves through LDS as 16 bytes per column (8 rows).
+// One workgroup beyond the last job takes the mean loss when loss_b != NULL.
+struct ReduceUpdateJobs {
+  int njobs;
+  int first_block[SNN_MAX_JOBS + 1];
+  int blocks_x[SNN_MAX_JOBS];
+  float *W[SNN_MAX_JOBS], *dW[SNN_MAX_JOBS];
+  const float *part[SNN_MAX_JOBS];     // NULL: dW holds the gradient already (a single split)
+  int splits[SNN_MAX_JOBS];
+  int K[SNN_MAX_JOBS], N[SNN_MAX_JOBS];
+  uint16_t *Qf[SNN_MAX_JOBS];
+  uint16_t *Qb[SNN_MAX_JOBS];
+  int ldqf[SNN_MAX_JOBS], ldqb[SNN_MAX_JOBS];
+  long long qf_plane[SNN_MAX_JOBS], qb_plane[SNN_MAX_JOBS];
+};
+
+__global__ __launch_bounds__(256) void reduce_update_kernel(const ReduceUpdateJobs jobs, float lr, int nplanes,
+                                                            const float *__restrict__ loss_b, float *__restrict__ loss,
+                                                            int B) {
+  __shared__ __attribute__((aligned(16))) uint16_t tile[3][32][8];
+  __shared__ float lsum[256];
+  if ((int)blockIdx.x >= jobs.first_block[jobs.njobs]) {
+    loss_mean_block(loss_b, loss, B, lsum);
+    return;
+  }
+  int j = 0;
+  while (j + 1 < jobs.njobs && (int)blockIdx.x >= jobs.first_block[j + 1]) ++j;
+  const int blk = blockIdx.x - jobs.first_block[j];
+  float *__restrict__ W = jobs.W[j];
+  float *__restrict__ dW = jobs.dW[j];
+  const float *__restrict__ part = jobs.part[j];
+  const int splits = jobs.splits[j];
+  const int K = jobs.K[j], N = jobs.N[j];
+  uint16_t *__restrict__ Qf = jobs.Qf[j];
+  uint16_t *__restrict__ Qb = jobs.Qb[j];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int n0 = (blk % jobs.blocks_x[j]) * 32, k0 = (blk / jobs.blocks_x[j]) * 8;
+  const int k = k0 + ty, n = n0 + tx;
+  float w = 0.f;
+  if (k < K && n < N) {
+    const size_t idx = (size_t)k * N + n, kn = (size_t)K * N;
+    float g;
+    if (part) {
+      float acc[4] = {0.f, 0.f, 0.f, 0.f};
+      int s = 0;
+      for (; s + 8 <= splits; s += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = part[(size_t)(s + u) * kn + idx];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc[u & 3] += v[u];
+      }
+      for (; s < splits; ++s) acc[s & 3] += part[(size_t)s * kn + idx];
+      g = ((acc[0] + acc[1]) + acc[2]) + acc[3];
+      dW[idx] = g;
+    } else {
+      g = dW[idx];
+    }
+    w = W[idx] - lr * g;
+    W[idx] = w;
+  }
+  for (int p = 0; p < nplanes; ++p) {
+    const uint16_t bits = (uint16_t)bf16_piece(w, p);
+    tile[p][tx][ty] = bits;
+    if (Qb && k < K && n < N) Qb[(size_t)p * jobs.qb_plane[j] + (size_t)k * jobs.ldqb[j] + n] = bits;
+  }
+  __syncthreads();
+  // Qf[p][n][k0 .. k0+7]: rows beyond K are zeros, as the padding of Qf is
+  if ((int)threadIdx.x < 32 * nplanes) {
+    const int p = threadIdx.x >> 5, nn = n0 + tx;
+    if (nn < N) *(uint4 *)&Qf[(size_t)p * jobs.qf_plane[j] + (size_t)nn * jobs.ldqf[j] + k0] = *(const uint4 *)&tile[p][tx][0];
+  }
+}
+
 }  // namespace snn

@@ -86,6 +86,8 @@ struct snn_ctx {
   bool x_padded = false;           // the caller's raster must be copied into x_buf
   int ldx = 0;                     // row length of x_eff
   const int32_t *labels_dev = nullptr;
+  ReduceJobs pending;             // partial sums of the last backward pass that have not been added yet
+  bool reduce_pending = false;
   std::string err;
   Prof prof;
 };
@@ -539,7 +541,7 @@ int queue_weight_grad(snn_ctx *c, int l, WgradJobs &w, ReduceJobs &jobs) {
 }
 
 // Launches what was queued (largest tiles first) and the reduction of the partial sums.
-int launch_weight_grads(snn_ctx *c, WgradJobs &w, const ReduceJobs &jobs, bool with_loss) {
+int launch_weight_grads(snn_ctx *c, WgradJobs &w, const ReduceJobs &jobs, bool with_loss, bool defer = false) {
   int rc;
   {
   Bracket br(c, SNN_K_WEIGHT_GRAD, 0);
@@ -555,8 +557,23 @@ int launch_weight_grads(snn_ctx *c, WgradJobs &w, const ReduceJobs &jobs, bool w
   for (int which = 2; which >= 0; --which)
     if ((rc = flush_tn(c, w, which))) return rc;
   }
+  if (defer) {                     // snn_sgd_step (or the first reader of a gradient) adds the partial sums
+    c->pending = jobs;
+    c->reduce_pending = true;
+    return SNN_OK;
+  }
+  c->reduce_pending = false;
   Bracket br(c, SNN_K_GRAD_REDUCE, 0);
   return launch_reduce(c, jobs, with_loss);
+}
+
+// Adds partial sums that snn_backward left for snn_sgd_step, for a caller that wants the
+// gradients (or anything else) first.
+int flush_reduce(snn_ctx *c) {
+  if (!c->reduce_pending) return SNN_OK;
+  c->reduce_pending = false;
+  Bracket br(c, SNN_K_GRAD_REDUCE, 0);
+  return launch_reduce(c, c->pending, !c->loss_ready);
 }
 
 // Threads per workgroup of the one-thread-per-chain scans: single wavefronts while that is
@@ -935,6 +952,36 @@ int update_layers(snn_ctx *c, int l0, int l1, bool with_grad, float lr) {
   return SNN_OK;
 }
 
+// snn_sgd_step right after snn_backward: partial sums -> dW -> W and its operand layouts, one launch.
+int reduce_and_update(snn_ctx *c, float lr) {
+  ReduceUpdateJobs jobs;
+  memset(&jobs, 0, sizeof jobs);
+  auto add = [&](float *W, float *dW, int K, int N, uint16_t *Qf, int ldqf, long long qf_plane, uint16_t *Qb, int ldqb,
+                 long long qb_plane) {
+    const int j = jobs.njobs++;
+    jobs.W[j] = W; jobs.dW[j] = dW; jobs.K[j] = K; jobs.N[j] = N;
+    jobs.Qf[j] = Qf; jobs.ldqf[j] = ldqf; jobs.qf_plane[j] = qf_plane;
+    jobs.Qb[j] = Qb; jobs.ldqb[j] = ldqb; jobs.qb_plane[j] = qb_plane;
+    jobs.part[j] = nullptr; jobs.splits[j] = 1;
+    for (int r = 0; r < c->pending.njobs; ++r)
+      if (c->pending.out[r] == dW) { jobs.part[j] = c->pending.part[r]; jobs.splits[j] = c->pending.splits[r]; }
+    jobs.blocks_x[j] = (N + 31) / 32;
+    jobs.first_block[j + 1] = jobs.first_block[j] + jobs.blocks_x[j] * ((K + 7) / 8);
+  };
+  for (int l = 0; l < c->L; ++l) {
+    Layer &y = c->layers[l];
+    add(y.Wm, y.dW, y.K, y.N, y.Qf, y.ldqf, y.qf_plane, y.Qb, y.ldqb, y.qb_plane);
+    if (y.recurrent) add(y.Rm, y.dR, y.N, y.N, y.QRf, y.ldqr, y.qr_plane, y.QRb, y.ldqr, y.qr_plane);
+  }
+  const bool with_loss = !c->loss_ready;
+  hipLaunchKernelGGL(reduce_update_kernel, dim3(jobs.first_block[jobs.njobs] + (with_loss ? 1 : 0)), dim3(256), 0,
+                     c->stream, jobs, lr, c->nplanes, with_loss ? c->loss_b : nullptr, c->loss, c->B);
+  HIPCHK(c, hipGetLastError());
+  if (with_loss) c->loss_ready = true;
+  c->reduce_pending = false;
+  return SNN_OK;
+}
+
 int check_err_flag(snn_ctx *c) {
   int flag = 0;
   HIPCHK(c, hipMemcpyAsync(&flag, c->err_flag, sizeof(int), hipMemcpyDeviceToHost, c->stream));
@@ -1190,7 +1237,11 @@ int32_t snn_backward(snn_ctx *c) {
     HIPCHK(c, hipGetLastError());
     for (int l = 0; l < c->L; ++l) add_reduce_job(jobs, c->layers[l].part_b, c->layers[l].dbeta, c->B, c->layers[l].ld, true);
   }
-  if ((rc = launch_weight_grads(c, wj, jobs, !c->loss_ready))) return rc;
+  // Without trained decays the reduction of the partial sums waits for snn_sgd_step, which does
+  // it in the launch that updates the parameters (SNN_FUSE_SGD=0: reduce here, as before).
+  const char *e = getenv("SNN_FUSE_SGD");
+  const bool defer = !c->learn_beta && !(e && atoi(e) == 0);
+  if ((rc = launch_weight_grads(c, wj, jobs, !c->loss_ready, defer))) return rc;
   c->state = 2;
   return SNN_OK;
 }
@@ -1199,7 +1250,7 @@ int32_t snn_sgd_step(snn_ctx *c, float lr) {
   if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
   if (c->state < 2) return fail(c, SNN_ERR_STATE, "snn_sgd_step needs a preceding snn_backward");
   Bracket br(c, SNN_K_SGD, 0);
-  int rc = update_layers(c, 0, c->L, true, lr);
+  int rc = c->reduce_pending ? reduce_and_update(c, lr) : update_layers(c, 0, c->L, true, lr);
   if (rc) return rc;
   if (c->learn_beta) {
     BetaJobs bj;
@@ -1224,6 +1275,7 @@ int32_t snn_get_tensor(snn_ctx *c, int32_t tensor, int32_t layer, void *dst, siz
   if (rc) return rc;
   if (bytes != v.rows * v.cols * v.esz)
     return fail(c, SNN_ERR_SHAPE, "tensor %d needs %zu bytes, got %zu", tensor, v.rows * v.cols * v.esz, bytes);
+  if ((rc = flush_reduce(c))) return rc;
   if (tensor == SNN_T_LOSS && (rc = ensure_loss(c))) return rc;
   if (tensor == SNN_T_CURRENT && layer >= 1 && layer <= c->L - 1 && !c->layers[layer - 1].i_ready) {
     if ((rc = launch_current_gemm(c, layer - 1))) return rc;   // the layer ran as one launch: materialise I now
@@ -1285,6 +1337,10 @@ int32_t snn_run_step(snn_ctx *c, int32_t step, int32_t layer, const uint8_t *x_d
   if (layer < 1 || layer > c->L) return fail(c, SNN_ERR_ARG, "layer %d out of range", layer);
   const int l = layer - 1;
   const bool spiking = c->layers[l].spiking;
+  {
+    int rc = flush_reduce(c);
+    if (rc) return rc;
+  }
   if (x_dev) {
     int rc = prepare_input(c, x_dev);
     if (rc) return rc;

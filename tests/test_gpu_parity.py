@@ -275,6 +275,44 @@ def test_last_layer_launch_runs_the_whole_readout(monkeypatch, loss, T, classes)
     snn.destroy()
 
 
+@pytest.mark.parametrize("sizes,recurrent,precision", [((70, 128, 128, 10), (False, False), "bf16"),
+                                                        ((45, 29, 13, 3), (False, False), "fp32"),
+                                                        ((50, 40, 24, 5), (True, False), "bf16"),
+                                                        ((61, 150, 66, 10), (False, True), "fp32")])
+def test_sgd_step_straight_after_backward(monkeypatch, sizes, recurrent, precision):
+    """snn_sgd_step right after snn_backward adds the per-split partial sums and updates the
+    parameters in one launch; a caller that reads a gradient first gets the separate reduction.
+    Both orders, and the library with the fusion switched off, must leave the same bits in the
+    weights, in the gradients and in the loss, and the next forward pass (which runs on the
+    refreshed bfloat16 operand layouts) must give the same loss."""
+    wl = workloads.Workload(name="sgd-fused", index=26, T=24, B=40, sizes=sizes, recurrent=recurrent,
+                            beta=(0.9, 0.93, 0.95), theta=1.0, surrogate="superspike", slope=10.0, precision=precision,
+                            rate_lo=0.05, rate_hi=0.2, rec_gain=1.0)
+    inp = workloads.generate(wl, w_gain=2.0)
+    L = len(sizes) - 1
+    out = []
+    for mode in ("straight", "read-first", "off"):
+        monkeypatch.setenv("SNN_FUSE_SGD", "0" if mode == "off" else "1")
+        snn = make(wl, inp)
+        snn.forward(inp.X, inp.labels)
+        snn.backward()
+        if mode == "read-first":
+            snn.get_tensor("grad_w", 1)
+        snn.sgd_step(0.05)
+        res = [snn.get_tensor("loss")]
+        for l in range(1, L + 1):
+            res += [snn.get_tensor("weight", l), snn.get_tensor("grad_w", l)]
+            if l <= L - 1 and recurrent[l - 1]:
+                res += [snn.get_tensor("rweight", l), snn.get_tensor("grad_r", l)]
+        res.append(np.float32(snn.forward(inp.X, inp.labels)))
+        out.append(res)
+        snn.destroy()
+    for got in out[:2]:
+        for a, b in zip(got, out[2]):
+            assert np.array_equal(a, b)
+    assert all(np.abs(g).max() > 0 for g in out[0][2::2][:L])
+
+
 @pytest.fixture
 def large_tensor_paths(monkeypatch):
     """The kernels chosen for tensors that stream past the caches (the streamed current product,
