@@ -199,7 +199,10 @@ int32_t snn_forward_packed(snn_ctx *ctx, const uint8_t *x_packed_dev, const int3
 /* Reverse sweep: readout gradient, per spiking layer the reverse-time scan with the fused
  * surrogate derivative, the weight-gradient products dW^l = S^{l-1}^T dI^l (dR^l =
  * S^l^T dI^l) and the input-gradient products dS^{l-1} = dI^l W^l^T.  Needs a preceding
- * snn_forward on the current weights (else SNN_ERR_STATE). */
+ * snn_forward on the current weights (else SNN_ERR_STATE).
+ * The weight-gradient products are split along the T*B rows; the sum of the splits' partial
+ * results may be left to the next call that needs it (snn_sgd_step, or snn_get_tensor /
+ * snn_run_step, which add them first): the gradients a caller sees are the same either way. */
 int32_t snn_backward(snn_ctx *ctx);
 
 /* W <- W - lr dW, R <- R - lr dR on the fp32 masters, then refresh the bfloat16 operand
