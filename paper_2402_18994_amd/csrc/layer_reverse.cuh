@@ -52,15 +52,6 @@ struct LayerReverseArgs {
 #define SNN_RPROBE(i) do { } while (0)
 #endif
 
-// The surrogates with the hardware reciprocal (1 ulp) instead of an IEEE division: the division
-// alone made step 3 take 1.6 us per block of 64 steps, as much as the rest of the block.
-template <int SURR> __device__ __forceinline__ float surr_rcp(float k, float x) {
-  if (SURR == 0) { const float d = 1.0f + k * fabsf(x); return __builtin_amdgcn_rcpf(d * d); }
-  if (SURR == 1) { const float u = 1.5707963267948966f * k * x; return (0.5f * k) * __builtin_amdgcn_rcpf(1.0f + u * u); }
-  if (SURR == 2) { const float s = __builtin_amdgcn_rcpf(1.0f + __expf(-k * x)); return k * s * (1.0f - s); }
-  return surr<SURR>(k, x);
-}
-
 template <int KS, int SURR, int BN>
 __global__ __launch_bounds__(256, BN == 64 ? 2 : 1) void lif_layer_reverse_kernel(const LayerReverseArgs a) {
   static_assert(BN == 64 || BN == 128, "neurons per workgroup");

@@ -82,6 +82,11 @@ __global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__
 #pragma unroll
     for (int g = 0; g < 4; ++g) cur[d][g] = ld_b128(rI, vo4[g], min(d, T - 1) * row4);
 
+  // One step.  The chain that bounds it is serial - spikes into LDS, barrier, fragment reads, the
+  // MFMAs, the state update - so everything that does not depend on the product is issued
+  // while the MFMAs run: the stores of V_t and S_t sit between the MFMAs and the update, and
+  // the eight products of a step go to two accumulators (even and odd k steps) so that only
+  // four of them depend on each other.
   auto step = [&](u32x4 (&in)[4], int t) {
     uint32_t sp[16];
 #pragma unroll
@@ -89,32 +94,38 @@ __global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__
     char *x = xs[t & 1];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      u32x4 vv;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) vv[i] = __float_as_uint(v[4 * g + i]);
-      st_b128(rV, vo4[g], t * row4, vv);
-      st_b32(rS, vo1[g], t * (row4 >> 2), sp[4 * g] | (sp[4 * g + 1] << 8) | (sp[4 * g + 2] << 16) | (sp[4 * g + 3] << 24));
       u32x2 sx;                                  // four spikes as bfloat16 0.0 / 1.0
       sx[0] = (sp[4 * g] | (sp[4 * g + 1] << 16)) * 0x3F80u;
       sx[1] = (sp[4 * g + 2] | (sp[4 * g + 3] << 16)) * 0x3F80u;
       *(u32x2 *)(x + xo[g]) = sx;
     }
-    f32x16 acc;
+    f32x16 acc, acc1;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    for (int r = 0; r < 16; ++r) acc[r] = acc1[r] = 0.f;
     lds_barrier();
     if (t + 1 < T) {                             // the last state is not used
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
         const bf16x8 sf = *(const bf16x8 *)(x + (lane & 31) * RL_PITCH + (16 * ks + 8 * (lane >> 5)) * 2);
 #pragma unroll
-        for (int p = NP - 1; p >= 0; --p) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[p][ks], sf, acc, 0, 0, 0);
+        for (int p = NP - 1; p >= 0; --p) {
+          if (ks & 1) acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[p][ks], sf, acc1, 0, 0, 0);
+          else acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[p][ks], sf, acc, 0, 0, 0);
+        }
       }
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      u32x4 vv;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) vv[i] = __float_as_uint(v[4 * g + i]);
+      st_b128(rV, vo4[g], t * row4, vv);
+      st_b32(rS, vo1[g], t * (row4 >> 2), sp[4 * g] | (sp[4 * g + 1] << 8) | (sp[4 * g + 2] << 16) | (sp[4 * g + 3] << 24));
     }
     // accumulator register r: neuron 32w + 8*(r/4) + 4*(lane/32) + r%4, i.e. group r/4, element r%4
 #pragma unroll
     for (int i = 0; i < 16; ++i)
-      v[i] = beta[i] * v[i] + __uint_as_float(in[i >> 2][i & 3]) + acc[i] - (sp[i] ? theta : 0.f);
+      v[i] = beta[i] * v[i] + __uint_as_float(in[i >> 2][i & 3]) + (acc[i] + acc1[i]) - (sp[i] ? theta : 0.f);
 #pragma unroll
     for (int g = 0; g < 4; ++g) in[g] = ld_b128(rI, vo4[g], min(t + PF, T - 1) * row4);
   };
@@ -184,27 +195,30 @@ __global__ __launch_bounds__(256) void rlif_reverse_fused_kernel(const float *__
       cv[d][g] = ld_b128(rV, vo4[g], so);
     }
 
+  // One step, ordered like the forward one: the planes of g into LDS, barrier, fragment reads
+  // and MFMAs (two accumulators), and under the MFMAs what does not need the product: the
+  // store of dI_t and the surrogate (with the hardware reciprocal; sixteen IEEE divisions per
+  // lane and step were a third of the step).
   auto step = [&](u32x4 (&ds)[4], u32x4 (&vv)[4], int t) {
     char *x = (char *)xs[t & 1];
+    u32x4 o[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      u32x4 o;
       uint32_t pl[GP][4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const float gg = gv[4 * g + i];
         if (HL) {
           const uint32_t hl = pack_hl(gg);
-          o[i] = hl;
+          o[g][i] = hl;
           pl[0][i] = hl & 0xFFFFu;
           pl[1][i] = hl >> 16;
         } else {
-          o[i] = __float_as_uint(gg);
+          o[g][i] = __float_as_uint(gg);
 #pragma unroll
           for (int q = 0; q < GP; ++q) pl[q][i] = bf16_piece(gg, q);
         }
       }
-      st_b128(rdI, vo4[g], t * row4, o);
 #pragma unroll
       for (int q = 0; q < GP; ++q) {
         u32x2 px;
@@ -213,9 +227,9 @@ __global__ __launch_bounds__(256) void rlif_reverse_fused_kernel(const float *__
         *(u32x2 *)(x + q * 32 * RL_PITCH + xo[g]) = px;
       }
     }
-    f32x16 acc;
+    f32x16 acc, acc1;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    for (int r = 0; r < 16; ++r) acc[r] = acc1[r] = 0.f;
     lds_barrier();
     if (t > 0) {                                 // the g leaving step 0 is not used
 #pragma unroll
@@ -230,17 +244,24 @@ __global__ __launch_bounds__(256) void rlif_reverse_fused_kernel(const float *__
 #pragma unroll
           for (int p = 0; p < NP; ++p) {
             const int q = sum - p;
-            if (q >= 0 && q < GP && (NP == 1 || p + q < 3))
-              acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[p][ks], gf[q], acc, 0, 0, 0);
+            if (q >= 0 && q < GP && (NP == 1 || p + q < 3)) {
+              if (ks & 1) acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[p][ks], gf[q], acc1, 0, 0, 0);
+              else acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[p][ks], gf[q], acc, 0, 0, 0);
+            }
           }
       }
     }
 #pragma unroll
+    for (int g = 0; g < 4; ++g) st_b128(rdI, vo4[g], t * row4, o[g]);
+    float sg[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sg[i] = surr_rcp<SURR>(slope, __uint_as_float(vv[i >> 2][i & 3]) - theta);
+#pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const float q = __uint_as_float(ds[i >> 2][i & 3]) - theta * gv[i] + acc[i];
+      const float q = __uint_as_float(ds[i >> 2][i & 3]) - theta * gv[i] + (acc[i] + acc1[i]);
       const float vt = __uint_as_float(vv[i >> 2][i & 3]);
       db[i] += gv[i] * vt;
-      gv[i] = beta[i] * gv[i] + surr<SURR>(slope, vt - theta) * q;
+      gv[i] = beta[i] * gv[i] + sg[i] * q;
     }
 #pragma unroll
     for (int g = 0; g < 4; ++g) {

@@ -104,6 +104,17 @@ template <int SURR> __device__ __forceinline__ float surr(float k, float x) {
   return 1.0f;                                                   // straight-through
 }
 
+// The surrogates with the hardware reciprocal (1 ulp) instead of an IEEE division: for the
+// kernels where the surrogate's arithmetic, not memory, is what a step waits for (the one-launch
+// layer reverse: the division alone took 1.6 us per block of 64 steps; the recurrent reverse
+// kernel: sixteen divisions per lane and step).
+template <int SURR> __device__ __forceinline__ float surr_rcp(float k, float x) {
+  if (SURR == 0) { const float d = 1.0f + k * fabsf(x); return __builtin_amdgcn_rcpf(d * d); }
+  if (SURR == 1) { const float u = 1.5707963267948966f * k * x; return (0.5f * k) * __builtin_amdgcn_rcpf(1.0f + u * u); }
+  if (SURR == 2) { const float s = __builtin_amdgcn_rcpf(1.0f + __expf(-k * x)); return k * s * (1.0f - s); }
+  return surr<SURR>(k, x);
+}
+
 template <int VEC, int U, int SURR, bool HL, int POL>
 __global__ __launch_bounds__(256) void lif_reverse_kernel(const float *__restrict__ dS, const float *__restrict__ V,
                                                           uint32_t *__restrict__ dI, int T, int stride,
