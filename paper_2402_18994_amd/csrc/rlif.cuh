@@ -556,7 +556,7 @@ __global__ __launch_bounds__(256) void rlif_step_reverse_kernel(const uint32_t *
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const float q = d4[i] - theta * g4[i] + sum[i];
-      gn[i] = b4[i] * g4[i] + surr<SURR>(slope, v4[i] - theta) * q;
+      gn[i] = b4[i] * g4[i] + surr_rcp<SURR>(slope, v4[i] - theta) * q;
       wd[i] = HL ? pack_hl(gn[i]) : __float_as_uint(gn[i]);
     }
     if (db_part) {                                     // dL/dbeta per sample, accumulated over the steps

@@ -150,7 +150,7 @@ __global__ __launch_bounds__(256) void lif_reverse_kernel(const float *__restric
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
       db[i] += g[i] * vv[i];
-      g[i] = beta[i] * g[i] + surr<SURR>(slope, vv[i] - theta) * (ds[i] - theta * g[i]);
+      g[i] = beta[i] * g[i] + surr_rcp<SURR>(slope, vv[i] - theta) * (ds[i] - theta * g[i]);
     }
   };
   fetch(a_ds, a_v, T - 1);
@@ -431,7 +431,7 @@ __global__ __launch_bounds__(256) void lif_reverse_top_kernel(const uint32_t *__
   auto step = [&](float ds, float vv, int t) {
     st_b32(rdI, vo4, t * row4, pack_hl(g));
     db += g * vv;
-    g = beta * g + surr<SURR>(slope, vv - theta) * (ds - theta * g);
+    g = beta * g + surr_rcp<SURR>(slope, vv - theta) * (ds - theta * g);
   };
 
   // The dS block of the next 16 steps is formed before the current 16 are scanned, so that its
