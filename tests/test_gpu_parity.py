@@ -313,6 +313,28 @@ def test_sgd_step_straight_after_backward(monkeypatch, sizes, recurrent, precisi
     assert all(np.abs(g).max() > 0 for g in out[0][2::2][:L])
 
 
+def test_sgd_step_straight_after_backward_headline_shape(monkeypatch):
+    """The training loop bench.py times (forward, backward, step, nothing read in between) at the
+    full headline shape: weights after two steps, their gradients and the loss must have the
+    same bits as with the reduction done inside snn_backward."""
+    wl = workloads.CONFIGS["shd_ff128"]
+    inp = workloads.generate(wl, w_gain=3.0)
+    out = []
+    for knob in ("1", "0"):
+        monkeypatch.setenv("SNN_FUSE_SGD", knob)
+        snn = make(wl, inp)
+        for _ in range(2):
+            snn.forward(inp.X, inp.labels)
+            snn.backward()
+            snn.sgd_step(0.05)
+        out.append([snn.get_tensor("loss")] + [snn.get_tensor("weight", l) for l in (1, 2, 3)]
+                   + [snn.get_tensor("grad_w", l) for l in (1, 2, 3)])
+        snn.destroy()
+    for a, b in zip(*out):
+        assert np.array_equal(a, b)
+    assert all(np.abs(g).max() > 0 for g in out[0][4:])
+
+
 @pytest.fixture
 def large_tensor_paths(monkeypatch):
     """The kernels chosen for tensors that stream past the caches (the streamed current product,
