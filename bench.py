@@ -49,9 +49,10 @@ def algorithmic_bytes(wl, kernel, layer):
     fused_rev = (bf and layer < L and not wl.recurrent[layer - 1] and n_out % 64 == 0
                  and pad8(wl.sizes[layer + 1]) <= 128)
     fused_fwd = fused_rev and layer == L - 1 and n_out in (64, 128, 256) and pad8(wl.sizes[L]) <= 32
-    # a feed-forward layer of 64..256 padded neurons runs product and scan as one launch from 128 samples on
+    # a feed-forward layer of 64..256 padded neurons runs product and scan as one launch (rasters beyond 256
+    # steps: from 64 samples on)
     whole_fwd = (bf and layer < L and not wl.recurrent[layer - 1] and pad8(n_out) % 64 == 0 and pad8(n_out) <= 256
-                 and wl.B >= 128)
+                 and (wl.T <= 256 or wl.B >= 64))
     if kernel == "lif_forward" and whole_fwd:   # read the spikes below (1) and W, write V (4) and S (1) [+ J]
         with_j = layer == L - 1 and pad8(n_out) == 128 and pad8(wl.sizes[L]) <= 32
         return M * n_in + 2 * n_in * n_out + M * n_out * (4 + 1) + (M * pad8(wl.sizes[L]) * 4 if with_j else 0)
@@ -206,6 +207,10 @@ def main():
     # the weight-gradient products of all layers are one launch (layer 0); for the scans, layers of
     # equal width move equal bytes per launch
     blayer = klayer if (klayer or kname == "weight_grad") else 1
+    # The dominant kernel is bracketed by events inside the timed steps, at every 8th step: an
+    # event pair costs the stream about 3 us (calibrated above), which at every step would be
+    # several per cent of a 90 us step.
+    snn.profile_every(max(1, min(8, args.steps // 16)))
     snn.profile_select(kname, klayer)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -214,6 +219,7 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     k_ms, k_n = snn.profile_read()
+    snn.profile_every(1)
     snn.profile_select("none", 0)
     loss = snn.forward(x, y)
 

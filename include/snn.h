@@ -231,6 +231,11 @@ int32_t snn_run_step(snn_ctx *ctx, int32_t step, int32_t layer, const uint8_t *x
  * snn_profile_read waits for the stream and returns the summed elapsed milliseconds and
  * the number of bracketed launches since the last select. */
 int32_t snn_profile_select(snn_ctx *ctx, int32_t kernel_class, int32_t layer);
+/* Bracket only every n-th matching launch (n >= 1, default 1; counted from the next select on):
+ * an event pair costs a few microseconds on the stream, which a timed loop that wants the
+ * kernel's average duration, not every sample of it, need not pay at every step.  For
+ * callers that time whole steps while the timer is on (the bench). */
+int32_t snn_profile_every(snn_ctx *ctx, int32_t n);
 int32_t snn_profile_read(snn_ctx *ctx, double *total_ms, int64_t *launches);
 
 /* Free the host-side context (the workspace stays the caller's).  Waits for the stream. */

@@ -71,12 +71,13 @@ def load_library():
     lib.snn_set_tensor.argtypes = [vp, i32, i32, vp, sz]
     lib.snn_run_step.argtypes = [vp, i32, i32, vp, vp]
     lib.snn_profile_select.argtypes = [vp, i32, i32]
+    lib.snn_profile_every.argtypes = [vp, i32]
     lib.snn_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.snn_destroy.argtypes = [vp]
     lib.snn_last_error.argtypes = [vp]
     lib.snn_last_error.restype = C.c_char_p
     for name in ("snn_workspace_bytes", "snn_init", "snn_forward", "snn_forward_packed", "snn_backward", "snn_sgd_step",
-                 "snn_get_tensor", "snn_set_tensor", "snn_run_step", "snn_profile_select",
+                 "snn_get_tensor", "snn_set_tensor", "snn_run_step", "snn_profile_select", "snn_profile_every",
                  "snn_profile_read", "snn_destroy"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -242,6 +243,9 @@ class SNN:
 
     def profile_select(self, kernel: str, layer: int = 0):
         self._chk(self.lib.snn_profile_select(self.ctx, KERNELS[kernel], layer), self.ctx)
+
+    def profile_every(self, n: int):
+        self._chk(self.lib.snn_profile_every(self.ctx, n), self.ctx)
 
     def profile_read(self):
         ms, n = C.c_double(0), C.c_int64(0)

@@ -56,6 +56,8 @@ struct Prof {
   int cls = SNN_K_NONE, layer = 0;
   std::vector<hipEvent_t> ev;     // start/stop pairs
   size_t used = 0;
+  int every = 1;                  // bracket every n-th matching launch
+  long long seen = 0;             // matching launches since the last select
 };
 
 }  // namespace
@@ -309,6 +311,7 @@ struct Bracket {
   bool on;
   Bracket(snn_ctx *ctx, int cls, int layer1) : c(ctx) {
     on = c->prof.cls == cls && (c->prof.layer == 0 || c->prof.layer == layer1);
+    if (on) on = c->prof.seen++ % c->prof.every == 0;
     if (on) {
       if (c->prof.used + 2 > c->prof.ev.size()) {
         if (c->prof.ev.size() >= (1u << 16)) { on = false; return; }
@@ -717,15 +720,14 @@ int launch_lif_forward_top(snn_ctx *c) {
 }
 
 // The same reverse pass as one workgroup per sample and 64 neurons on LDS
-// (lif_layer_reverse_kernel): layers of 64 to 256 neurons, enough samples to fill the chip,
-// 32-bit byte offsets.  SNN_FUSE_LAYER_REV=0 switches it off; SNN_FUSE_LAYER_MIN_B as for the
+// (lif_layer_reverse_kernel): layers of 64 to 256 neurons, 32-bit byte offsets.  SNN_FUSE_LAYER_REV=0 switches it off; SNN_FUSE_LAYER_MIN_B as for the
 // forward pass.  Both read per call.
 bool layer_reverse_whole(snn_ctx *c, int l) {
   const char *e = getenv("SNN_FUSE_LAYER_REV");
   if (e && atoi(e) == 0) return false;
   const Layer &y = c->layers[l];
   const char *m = getenv("SNN_FUSE_LAYER_MIN_B");
-  const int min_b = m ? atoi(m) : 128;
+  const int min_b = m ? atoi(m) : c->T <= 256 ? 1 : 64;
   return reverse_fusable(c, l) && y.ld <= 256 && c->B >= min_b &&
          (size_t)c->M * y.ld * 4 < ((size_t)1 << 31) && (size_t)c->M * columns_above(c, l) * 4 < ((size_t)1 << 31);
 }
@@ -802,13 +804,15 @@ int launch_lif_reverse_fused(snn_ctx *c, int l) {
 
 // A feed-forward spiking layer of 64, 128, 192 or 256 (padded) neurons on rounded weights runs
 // as ONE launch, product and scan (lif_layer_forward_kernel): I is not stored.  A workgroup
-// owns a sample and 64 or 128 neurons, so it needs enough samples to fill the chip; 32-bit
+// owns a sample and 64 or 128 neurons; 32-bit
 // byte offsets into the spikes below and V; a threshold the scan's compare-free spike
 // decision is exact for.
 // SNN_FUSE_LAYER: 0 never, 1 all but the last spiking layer, 2 every such layer, 3 the last one
 // also forms the readout's currents when it has exactly 128 padded neurons, 4 (default) and runs
 // the readout scan, the loss and the readout's current gradients;
-// SNN_FUSE_LAYER_MIN_B: samples from which it is used (default 128); SNN_LAYER_NEURONS: 64 or
+// SNN_FUSE_LAYER_MIN_B: samples from which it is used (default: any number up to 256 steps, 64
+// for longer rasters: at the headline widths it wins from 4 samples on, having fewer launches,
+// but a workgroup walks its sample's blocks of 128 steps serially); SNN_LAYER_NEURONS: 64 or
 // 128 neurons per workgroup.  All read per call.
 int layer_fuse_mode() {
   const char *e = getenv("SNN_FUSE_LAYER");
@@ -818,7 +822,7 @@ bool layer_forward_fusable(snn_ctx *c, int l) {
   if (l < 0 || l > c->L - 2) return false;
   const Layer &y = c->layers[l];
   const char *e = getenv("SNN_FUSE_LAYER_MIN_B");
-  const int min_b = e ? atoi(e) : 128;
+  const int min_b = e ? atoi(e) : c->T <= 256 ? 1 : 64;   // a workgroup walks a sample's blocks of 128 steps one after the other
   const SpikeSrc s = spikes_below(c, l);
   return c->nplanes == 1 && y.spiking && !y.recurrent && y.ld % 64 == 0 && y.ld <= 256 && c->B >= min_b &&
          s.ld % 4 == 0 && (size_t)c->M * s.ld < ((size_t)1 << 31) && (size_t)c->M * y.ld * 4 < ((size_t)1 << 31) &&
@@ -1374,7 +1378,15 @@ int32_t snn_profile_select(snn_ctx *c, int32_t kernel_class, int32_t layer) {
   if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
   if (kernel_class < SNN_K_NONE || kernel_class >= SNN_K_COUNT) return fail(c, SNN_ERR_ARG, "unknown kernel class");
   HIPCHK(c, hipStreamSynchronize(c->stream));
-  c->prof.cls = kernel_class; c->prof.layer = layer; c->prof.used = 0;
+  c->prof.cls = kernel_class; c->prof.layer = layer; c->prof.used = 0; c->prof.seen = 0;
+  return SNN_OK;
+}
+
+int32_t snn_profile_every(snn_ctx *c, int32_t n) {
+  if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
+  if (n < 1) return fail(c, SNN_ERR_ARG, "n must be at least 1");
+  c->prof.every = n;
+  c->prof.seen = 0;
   return SNN_OK;
 }
 
