@@ -37,7 +37,8 @@
 
 namespace snn {
 
-struct LayerForwardArgs {
+// One layer of the launch: operands and results.
+struct LayerForwardOp {
   const uint8_t *P;        // spikes below [T*B][ldp], bytes 0/1
   int ldp, kc;             // row length, fan-in
   unsigned p_bytes;
@@ -47,6 +48,13 @@ struct LayerForwardArgs {
   float *V;                // [T*B][ld]
   uint8_t *S;              // [T*B][ld]
   const float *beta_v;     // [ld]
+};
+
+struct LayerForwardArgs {
+  // The layers of the launch, bottom up.  More than one (kernel variants NL > 1, layers of
+  // exactly 128 padded neurons): op[i + 1].P is op[i].S, and a workgroup takes its sample
+  // through all of them block by block, reading back the spikes it has just stored.
+  LayerForwardOp op[2];
   float theta;             // in [2^-60, 2^26]
   int T, B, ld;            // ld: a multiple of the workgroup's 64 or 128 neurons
   int nt_store;            // V and S stream past the caches
@@ -81,9 +89,10 @@ struct LayerForwardArgs {
 
 // READOUT: 0 none; 1 the launch also forms the readout's currents J; 2 and the LI scan, the
 // maximum over time, the loss and dJ; 3 the same with the integral loss.
-template <int TN, int NS = 4, int READOUT = 0>
+template <int TN, int NS = 4, int READOUT = 0, int NL = 1>
 __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerForwardArgs a) {
   static_assert(!READOUT || TN == 2, "the readout variants hold the whole layer");
+  static_assert(NL == 1 || (NL == 2 && TN == 2), "a chain of layers: whole layers of 128 neurons");
   constexpr bool LOSS = READOUT >= 2, INTEGRAL = READOUT == 3;
   constexpr int JP = 36;                              // floats between rows of the 128 x 32 readout tile in LDS
   __shared__ float x_e[LOSS ? 2 : 1][8][32], x_best[8][32];
@@ -105,20 +114,14 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
   const int n0 = part * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN, h = lane >> 5;
-  const int nk = (a.kc + 31) >> 5;
-  const u32x4 rp = raw_rsrc(a.P, a.p_bytes), rq = raw_rsrc(a.Q, a.q_bytes);
-  const rsrc_t rV = make_rsrc(a.V, (unsigned)a.T * a.B * a.ld * 4u), rS = make_rsrc(a.S, (unsigned)a.T * a.B * a.ld);
-
-  int qv[QI];
+  float beta[NL], v[NL];                              // decay and potential of neuron n0 + tid % BN, per layer
 #pragma unroll
-  for (int q = 0; q < QI; ++q) {
-    const int row = Tile::q_row(wave, lane, q);
-    qv[q] = ((n0 + row) * a.ldq + Tile::q_chunk(row, lane) * 8) * 2;
+  for (int li = 0; li < NL; ++li) {
+    beta[li] = a.op[li].beta_v[n0 + tid % BN];
+    v[li] = 0.f;
   }
-  const float beta = a.beta_v[n0 + tid % BN];
   const float theta = a.theta;
   const float big = 0x1p100f, mtheta_big = -theta * 0x1p100f, mtheta = -theta;
-  float v = 0.f;                                      // potential of neuron n0 + tid (scanning wavefronts)
 
   // Readout variant: W_out^T as the first MFMA operand, lane -> class (lane & 31), neurons
   // 16 kk + 8 h .. +7; resident.
@@ -139,12 +142,25 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
   int tb = 0, par = 0;
 
   for (int t0 = 0; t0 < a.T; t0 += BM) {
+   static_for<NL>([&](auto LI) {
+    constexpr int li = decltype(LI)::value;
+    constexpr bool last = li == NL - 1;
+    const LayerForwardOp &op = a.op[li];
+    const int nk = (op.kc + 31) >> 5;
+    const u32x4 rp = raw_rsrc(op.P, op.p_bytes), rq = raw_rsrc(op.Q, op.q_bytes);
+    const rsrc_t rV = make_rsrc(op.V, (unsigned)a.T * a.B * a.ld * 4u), rS = make_rsrc(op.S, (unsigned)a.T * a.B * a.ld);
+    int qv[QI];
+#pragma unroll
+    for (int q = 0; q < QI; ++q) {
+      const int row = Tile::q_row(wave, lane, q);
+      qv[q] = ((n0 + row) * op.ldq + Tile::q_chunk(row, lane) * 8) * 2;
+    }
     SNN_PROBE(0);
     // 1. product
     int pv[PI];
     {
       const int row = Tile::p_row(wave, lane, 0);
-      pv[0] = t0 + row < a.T ? ((t0 + row) * a.B + b) * a.ldp + Tile::p_unit(row, lane) * 16 : OOB;
+      pv[0] = t0 + row < a.T ? ((t0 + row) * a.B + b) * op.ldp + Tile::p_unit(row, lane) * 16 : OOB;
     }
     f32x16 acc[TM][TN];
     Tile::run(lds, rp, rq, pv, qv, nk, wave, lane, acc);
@@ -191,10 +207,10 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
         for (int u = 0; u < U; ++u) asm volatile("" : "+v"(cur[u]));
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          cell[(s0 + u) * (CP / 4)] = v;
+          cell[(s0 + u) * (CP / 4)] = v[li];
           float s;                                    // 1 if v > theta, else 0
-          asm("v_fma_f32 %0, %1, %2, %3 clamp" : "=v"(s) : "v"(v), "v"(big), "v"(mtheta_big));
-          v = __builtin_fmaf(mtheta, s, __builtin_fmaf(beta, v, cur[u]));
+          asm("v_fma_f32 %0, %1, %2, %3 clamp" : "=v"(s) : "v"(v[li]), "v"(big), "v"(mtheta_big));
+          v[li] = __builtin_fmaf(mtheta, s, __builtin_fmaf(beta[li], v[li], cur[u]));
         }
       }
     }
@@ -235,7 +251,7 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
     // .. +7, their spikes decided once more from V in the tile (exactly as in the scan) and
     // rounded to bfloat16 pairs.  The lane ends up with its step's currents, four consecutive
     // classes per register quad.
-    if (READOUT) {
+    if (READOUT && last) {
       f32x16 jt;
 #pragma unroll
       for (int r = 0; r < 16; ++r) jt[r] = 0.f;
@@ -311,8 +327,12 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
       }
     }
     SNN_PROBE(4);
-    __syncthreads();                                  // the next block's stages overwrite the tile
+    // A layer above reads the spikes of this block back from memory: they have reached the L2
+    // (nothing of them is in this compute unit's L1) once the stores are acknowledged.
+    if (!last) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                                  // the next product's stages overwrite the tile
     SNN_PROBE(5);
+   });
   }
 
   if (LOSS) {

@@ -840,21 +840,34 @@ int layer_forward_takes_readout(snn_ctx *c) {
   return !ok ? 0 : mode >= 4 && c->hl ? 2 : 1;
 }
 
-int launch_layer_forward(snn_ctx *c, int l, int with_readout, const int32_t *labels) {
+// Layers l .. l + nl - 1 in one launch (nl = 2: both of exactly 128 padded neurons, a workgroup
+// takes its sample through both); with_readout refers to the last of them.
+int launch_layer_forward(snn_ctx *c, int l, int nl, int with_readout, const int32_t *labels) {
   Layer &y = c->layers[l];
-  const SpikeSrc s = spikes_below(c, l);
-  if (!s.p) return fail(c, SNN_ERR_NULL, "input raster is NULL");
   LayerForwardArgs a;
   memset(&a, 0, sizeof a);
-  a.P = s.p; a.ldp = s.ld; a.kc = s.valid; a.p_bytes = s.bytes;
-  a.Q = y.Qf; a.ldq = y.ldqf; a.q_bytes = (unsigned)(y.qf_plane * 2);
-  a.V = y.V; a.S = y.S; a.beta_v = y.beta_v; a.theta = c->theta;
+  for (int i = 0; i < nl; ++i) {
+    Layer &yi = c->layers[l + i];
+    const SpikeSrc s = spikes_below(c, l + i);
+    if (!s.p) return fail(c, SNN_ERR_NULL, "input raster is NULL");
+    LayerForwardOp &op = a.op[i];
+    op.P = s.p; op.ldp = s.ld; op.kc = s.valid; op.p_bytes = s.bytes;
+    op.Q = yi.Qf; op.ldq = yi.ldqf; op.q_bytes = (unsigned)(yi.qf_plane * 2);
+    op.V = yi.V; op.S = yi.S; op.beta_v = yi.beta_v;
+    yi.i_ready = false;
+  }
+  a.theta = c->theta;
   a.T = c->T; a.B = c->B; a.ld = y.ld;
   a.nt_store = streams_past_cache(c->M * y.ld * 4);
   Bracket br(c, SNN_K_LIF_FORWARD, l + 1);
   const char *e = getenv("SNN_LAYER_NEURONS");
   const int bn = y.ld % 128 ? 64 : e ? atoi(e) : 128;   // 128: 108.0 us per step at 700-128-128-20, 64: 109.7
   const dim3 grid((unsigned)(rup(c->B, 8) * (y.ld / bn)));
+#define SNN_LFWD(RO)                                                                                             \
+  do {                                                                                                           \
+    if (nl == 2) hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 2>), grid, dim3(256), 0, c->stream, a);  \
+    else hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 1>), grid, dim3(256), 0, c->stream, a);          \
+  } while (0)
   if (with_readout) {
     Layer &ro = c->layers[c->L - 1];
     a.J = ro.I; a.ldj = c->ldC; a.Qr = ro.Qf; a.ldqr = ro.ldqf; a.qr_bytes = (unsigned)(ro.qf_plane * 2);
@@ -862,18 +875,17 @@ int launch_layer_forward(snn_ctx *c, int l, int with_readout, const int32_t *lab
       if (!labels) return fail(c, SNN_ERR_NULL, "labels are NULL");
       a.Y = ro.V; a.z = c->z; a.tstar = c->tstar; a.labels = labels; a.loss_b = c->loss_b; a.dz = c->dz;
       a.err = c->err_flag; a.dJ = ro.dI; a.beta_r = ro.beta_v; a.C = c->C;
-      if (c->integral) hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, 3>), grid, dim3(256), 0, c->stream, a);
-      else hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, 2>), grid, dim3(256), 0, c->stream, a);
+      if (c->integral) SNN_LFWD(3); else SNN_LFWD(2);
       c->dj_ready = true;
       c->loss_ready = false;
     } else {
-      hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, 1>), grid, dim3(256), 0, c->stream, a);
+      SNN_LFWD(1);
     }
     ro.i_ready = true;
   } else if (bn == 64) hipLaunchKernelGGL((lif_layer_forward_kernel<1, 4>), grid, dim3(256), 0, c->stream, a);
-  else hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4>), grid, dim3(256), 0, c->stream, a);
+  else SNN_LFWD(0);
+#undef SNN_LFWD
   HIPCHK(c, hipGetLastError());
-  y.i_ready = false;
   return SNN_OK;
 }
 
@@ -1162,7 +1174,15 @@ static int32_t forward_layers(snn_ctx *c, const int32_t *labels_dev, float *loss
   const bool fuse_top = !whole_top && top_forward_fusable(c);   // the last spiking layer's scan forms the readout's currents
   for (int l = 0; l < c->L; ++l) {
     if (whole >= 1 && (l < c->L - 2 || whole_top) && layer_forward_fusable(c, l)) {
-      if ((rc = launch_layer_forward(c, l, l == c->L - 2 ? with_readout : 0, labels_dev))) return rc;
+      // this layer and the next in one launch when both hold exactly 128 padded neurons
+      // (SNN_FUSE_LAYER_PAIR=0: one launch each)
+      const char *pe = getenv("SNN_FUSE_LAYER_PAIR");
+      const char *ne = getenv("SNN_LAYER_NEURONS");
+      const bool pair = !(pe && atoi(pe) == 0) && !(ne && atoi(ne) != 128) && c->layers[l].ld == 128 && l + 1 <= c->L - 2 &&
+                        (l + 1 < c->L - 2 || whole_top) && layer_forward_fusable(c, l + 1) && c->layers[l + 1].ld == 128;
+      const int nl = pair ? 2 : 1;
+      if ((rc = launch_layer_forward(c, l, nl, l + nl - 1 == c->L - 2 ? with_readout : 0, labels_dev))) return rc;
+      l += nl - 1;
       continue;
     }
     if (l == c->L - 1 && with_readout) {                // J is there already, perhaps the whole readout

@@ -335,6 +335,32 @@ def test_sgd_step_straight_after_backward_headline_shape(monkeypatch):
     assert all(np.abs(g).max() > 0 for g in out[0][4:])
 
 
+@pytest.mark.parametrize("T,sizes", [(150, (90, 128, 128, 128, 10)), (40, (50, 128, 128, 64, 128, 128, 12))])
+def test_two_layers_per_forward_launch(monkeypatch, T, sizes):
+    """Consecutive one-launch layers of exactly 128 neurons share a launch in pairs: a workgroup
+    takes its sample through the lower layer's block, stores its spikes, and reads them back as
+    the upper layer's input.  Three hidden layers (a pair, then the last one alone with the
+    readout) and five (pair, a 64-wide layer on its own, pair with the readout), two blocks of
+    128 steps; against the oracle, and the same bits as with one launch per layer."""
+    L = len(sizes) - 1
+    wl = workloads.Workload(name="layer-pairs", index=28, T=T, B=6, sizes=sizes, recurrent=(False,) * (L - 1),
+                            beta=(0.9, 0.93, 0.95, 0.9, 0.92, 0.94)[:L], theta=1.0, surrogate="superspike", slope=10.0,
+                            precision="bf16", rate_lo=0.03, rate_hi=0.12)
+    full_step_parity(wl, w_gain=2.0)
+    inp = workloads.generate(wl, w_gain=2.0)
+    out = []
+    for knob in ("1", "0"):
+        monkeypatch.setenv("SNN_FUSE_LAYER_PAIR", knob)
+        snn = make(wl, inp)
+        snn.forward(inp.X, inp.labels)
+        out.append([snn.get_tensor("membrane", l) for l in range(1, L)] + [snn.get_tensor("spikes", l) for l in range(1, L)]
+                   + [snn.get_tensor("readout_trace"), snn.get_tensor("loss")])
+        snn.destroy()
+    for a, b in zip(*out):
+        assert np.array_equal(a, b)
+    assert out[0][L - 1].mean() > 0.005
+
+
 @pytest.fixture
 def large_tensor_paths(monkeypatch):
     """The kernels chosen for tensors that stream past the caches (the streamed current product,
