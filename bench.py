@@ -24,7 +24,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # per dispatch, each scaled by what the same counter reads for the 256 MiB device copy this
 # script issues first: FETCH_SIZE reads half the bytes of that copy, WRITE_SIZE all of them).
 # The runs and their figures are in profiles/train_step_shd_ff128.txt.
-MEASURED_TRAFFIC = {("shd_ff128", "weight_grad"): (33302.9 * 2.0 + 27136.0) * 1024.0}
+MEASURED_TRAFFIC = {("shd_ff128", "weight_grad"): (33302.9 * 2.0 + 27136.0) * 1024.0,
+                    ("shd_ff128", "lif_forward"): (15234.7 * 2.0 + 50256.0) * 1024.0}
 
 # rocprofv3's duration of the calibration kernel that waits CALIBRATE_US on the device clock: the
 # difference is the start and end of a dispatch, which the profiler counts as kernel time.  The
@@ -50,12 +51,18 @@ def algorithmic_bytes(wl, kernel, layer):
                  and pad8(wl.sizes[layer + 1]) <= 128)
     fused_fwd = fused_rev and layer == L - 1 and n_out in (64, 128, 256) and pad8(wl.sizes[L]) <= 32
     # a feed-forward layer of 64..256 padded neurons runs product and scan as one launch (rasters beyond 256
-    # steps: from 64 samples on)
-    whole_fwd = (bf and layer < L and not wl.recurrent[layer - 1] and pad8(n_out) % 64 == 0 and pad8(n_out) <= 256
-                 and (wl.T <= 256 or wl.B >= 64))
-    if kernel == "lif_forward" and whole_fwd:   # read the spikes below (1) and W, write V (4) and S (1) [+ J]
-        with_j = layer == L - 1 and pad8(n_out) == 128 and pad8(wl.sizes[L]) <= 32
-        return M * n_in + 2 * n_in * n_out + M * n_out * (4 + 1) + (M * pad8(wl.sizes[L]) * 4 if with_j else 0)
+    # steps: from 64 samples on); two consecutive such layers of exactly 128 neurons share a launch, and the
+    # last spiking layer's launch (128 neurons, at most 32 padded classes) runs the whole readout
+    chain, with_readout = forward_chain(wl, layer)
+    if kernel == "lif_forward" and chain:
+        # the launch that starts at `layer`: spikes below (1 B) and W (2 B) read; V (4) and S (1) written per
+        # layer; with the readout its currents, its trace and its current gradients (4 B each)
+        total = M * n_in
+        for l in chain:
+            total += 2 * wl.sizes[l - 1] * wl.sizes[l] + M * wl.sizes[l] * (4 + 1)
+        if with_readout:
+            total += 2 * wl.sizes[chain[-1]] * wl.sizes[L] + 3 * M * pad8(wl.sizes[L]) * 4
+        return total
     if kernel == "lif_forward":      # read I (4), write V (4) and S (1 byte) [+ the readout's currents]
         return M * n_out * (4 + 4 + 1) + (M * pad8(wl.sizes[L]) * 4 if fused_fwd else 0)
     if kernel == "lif_reverse":      # read dS (4) [or the current gradients above] and V (4), write dI (4)
@@ -69,6 +76,25 @@ def algorithmic_bytes(wl, kernel, layer):
     if kernel == "input_grad":       # read dI and the weight planes, write dS
         return M * n_out * di + planes * 2 * n_in * n_out + M * n_in * 4
     raise KeyError(kernel)
+
+
+def forward_chain(wl, layer):
+    """The spiking layers that the forward launch starting at text layer `layer` covers, and whether it
+    runs the readout too; ([], False) if that layer runs as separate product and scan launches."""
+    L = len(wl.sizes) - 1
+    pad8 = lambda n: (n + 7) // 8 * 8
+
+    def whole(l):
+        n = pad8(wl.sizes[l])
+        return (wl.precision == "bf16" and 1 <= l < L and not wl.recurrent[l - 1] and n % 64 == 0 and n <= 256
+                and (wl.T <= 256 or wl.B >= 64))
+    if not whole(layer):
+        return [], False
+    chain = [layer]
+    if pad8(wl.sizes[layer]) == 128 and whole(layer + 1) and pad8(wl.sizes[layer + 1]) == 128:
+        chain.append(layer + 1)
+    top = chain[-1]
+    return chain, top == L - 1 and pad8(wl.sizes[top]) == 128 and pad8(wl.sizes[L]) <= 32
 
 
 def gemm_flops(wl):
@@ -119,7 +145,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="shd_ff128")
-    ap.add_argument("--dominant", default="weight_grad:0",
+    ap.add_argument("--dominant", default=None,
                     help="kernel:layer bracketed for the roofline line (layer 0 = every layer)")
     ap.add_argument("--traffic", type=float, default=None,
                     help="measured HBM bytes per launch of the dominant kernel (from the rocprofv3 --pmc runs); "
@@ -202,6 +228,11 @@ def main():
             print(f"[breakdown] {k:16s} {v['us_per_step']:9.1f} us/step over {v['launches_per_step']} launches/step",
                   file=sys.stderr)
 
+    if args.dominant is None:
+        # the launch with the largest share of the step: where the forward pass of all spiking layers and the
+        # readout is one launch, that one; else the merged weight-gradient launch
+        chain, with_readout = forward_chain(wl, 1)
+        args.dominant = "lif_forward:1" if with_readout and len(chain) == len(wl.sizes) - 2 else "weight_grad:0"
     kname, klayer = args.dominant.split(":")
     klayer = int(klayer)
     # the weight-gradient products of all layers are one launch (layer 0); for the scans, layers of
