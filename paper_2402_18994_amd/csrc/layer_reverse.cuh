@@ -83,17 +83,6 @@ __global__ __launch_bounds__(256, BN == 64 ? 2 : 1) void lif_layer_reverse_kerne
   const rsrc_t rX = make_rsrc(a.dX, (unsigned)a.T * a.B * a.ldc * 4u), rW = make_rsrc(a.Wq, a.wq_bytes);
   if (tid < BN) betas[tid] = a.beta_v[n0 + tid];
 
-  // First MFMA operand: W[n][c], lane -> neuron (lane & 31) of the 32-neuron tile, columns
-  // 16 kk + 8 h .. +7.  Resident for the whole kernel.
-  bf16x8 wf[NJ][KK];
-#pragma unroll
-  for (int j = 0; j < NJ; ++j)
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      const int n = n0 + 32 * NJ * wn + 32 * j + (lane & 31), c = 16 * kk + 8 * h;
-      wf[j][kk] = __builtin_bit_cast(bf16x8, ld_b128(rW, c + 7 < a.ldq ? (n * a.ldq + c) * 2 : OOB, 0));
-    }
-
   // A block's global loads: V as 8 x 16 bytes per thread (row = 8 k + tid / 32), dX as KK x 16
   // bytes per thread over rows of 8 KS chunks (chunks beyond ldc read as zero).
   u32x4 xv[NV], xd[KK];
@@ -119,10 +108,22 @@ __global__ __launch_bounds__(256, BN == 64 ? 2 : 1) void lif_layer_reverse_kerne
     }
   };
 
+  int t0 = (a.T - 1) / BM * BM;
+  fetch(t0);                                          // the first block's loads go out before anything else
+
+  // First MFMA operand: W[n][c], lane -> neuron (lane & 31) of the 32-neuron tile, columns
+  // 16 kk + 8 h .. +7.  Resident for the whole kernel.
+  bf16x8 wf[NJ][KK];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j)
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const int n = n0 + 32 * NJ * wn + 32 * j + (lane & 31), c = 16 * kk + 8 * h;
+      wf[j][kk] = __builtin_bit_cast(bf16x8, ld_b128(rW, c + 7 < a.ldq ? (n * a.ldq + c) * 2 : OOB, 0));
+    }
+
   float g = 0.f, db = 0.f;                            // state of neuron n0 + tid (wavefronts 0 and 1)
 
-  int t0 = (a.T - 1) / BM * BM;
-  fetch(t0);
   for (int blk = 0; t0 >= 0; t0 -= BM, ++blk) {
     SNN_RPROBE(0);
     fill();
