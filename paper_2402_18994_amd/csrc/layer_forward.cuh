@@ -19,7 +19,7 @@
 //      2^-24 theta, and the scaling is exact in the fused multiply-add), and V' = (beta V + I)
 //      - theta s is the value the plain scan computes.  Compare, select and subtract cost 57
 //      cycles per step as a dependent chain (the compare's result travels through a scalar
-//      register); the two fused multiply-adds take 20;
+//      register); the two fused multiply-adds take 35;
 //   4. store: all four wavefronts write V as whole rows, 16 bytes per lane, and S as 16
 //      neurons per lane, decided again from the stored V (the same exact comparison);
 //   5. (last spiking layer of 128 neurons, at most 32 padded classes) the readout's currents
@@ -32,6 +32,9 @@
 //      form per segment: no launch for the readout at all.
 // The potential is carried in the scanning lanes' registers from block to block.
 // Rows past T read as zero and are not stored; columns of W past the fan-in are zero.
+// Two consecutive layers of exactly 128 neurons can share the launch (NL = 2): per block the
+// workgroup runs steps 1 to 4 for the lower layer, waits until its spike stores are
+// acknowledged, and runs them again for the upper layer on the rows it has just written.
 #pragma once
 #include "gemm_stream.cuh"
 
