@@ -165,9 +165,9 @@ def test_top_layer_scans_same_as_unfused(monkeypatch):
 def test_layer_forward_in_one_launch(monkeypatch, T, sizes, nt, bn):
     """bf16 products, feed-forward spiking layers of 64 to 256 (padded) neurons: product and scan
     run as one launch per layer, a workgroup per sample and 64 or 128 neurons, and I is never
-    stored (read back, it comes from the product kernel).  The library uses the path from 128
-    samples on; the knob lowers that so that an element-by-element oracle run covers it: one,
-    two and three blocks of 128 steps with ragged tails, fan-ins that are no multiple of 32 or
+    stored (read back, it comes from the product kernel).  For rasters of more than 256 steps the
+    library uses the path from 64 samples on; the knob lowers that so that an element-by-element
+    oracle run covers those too: one, two and three blocks of 128 steps with ragged tails, fan-ins that are no multiple of 32 or
     of 16 bytes, a layer of 121 neurons padded to 128, layers of 64, 192 and 256 neurons, both
     workgroup widths, stores with and without the non-temporal hint."""
     monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
@@ -220,7 +220,7 @@ def test_layer_reverse_in_one_launch(monkeypatch, T, sizes, surrogate, slope):
     128 columns: dS, surrogate, reverse scan and the hi/lo store run as one launch, a workgroup
     per sample and 64 neurons, in blocks of 64 steps from the end.  One to three blocks with
     ragged first blocks, 24 to 128 columns above (one, two and four 32-wide contraction steps),
-    every surrogate; the library uses the path from 128 samples on, the knob lowers that."""
+    every surrogate (the knob lifts the batch-size condition that applies to long rasters)."""
     monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
     wl = workloads.Workload(name="layer-reverse", index=23, T=T, B=5, sizes=sizes, recurrent=(False, False),
                             beta=(0.9, 0.93, 0.95), theta=1.0, surrogate=surrogate, slope=slope, precision="bf16",
