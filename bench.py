@@ -223,6 +223,20 @@ def main():
         if n:
             per_class[name] = {"us_per_step": round((ms * 1e3 - n * ev_overhead_us) / 10, 2), "launches_per_step": n // 10}
     snn.profile_select("none", 0)
+    # where the class is one kind of launch with a byte formula and every spiking layer is feed-forward:
+    # algorithmic GB/s over all its launches of a step
+    L = len(wl.sizes) - 1
+    if not any(wl.recurrent):
+        chain, _ = forward_chain(wl, 1)
+        class_bytes = {"weight_grad": algorithmic_bytes(wl, "weight_grad", 0),
+                       "lif_reverse": sum(algorithmic_bytes(wl, "lif_reverse", l) for l in range(1, L))}
+        if len(chain) == L - 1:
+            class_bytes["lif_forward"] = algorithmic_bytes(wl, "lif_forward", 1)
+        elif not chain:
+            class_bytes["lif_forward"] = sum(algorithmic_bytes(wl, "lif_forward", l) for l in range(1, L))
+        for k, nbytes in class_bytes.items():
+            if k in per_class and per_class[k]["us_per_step"] > 0:
+                per_class[k]["algorithmic_gb_per_s"] = round(nbytes / per_class[k]["us_per_step"] / 1e3, 1)
     if args.breakdown:
         for k, v in per_class.items():
             print(f"[breakdown] {k:16s} {v['us_per_step']:9.1f} us/step over {v['launches_per_step']} launches/step",
