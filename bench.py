@@ -50,7 +50,7 @@ def algorithmic_bytes(wl, kernel, layer):
     fused_rev = (bf and layer < L and not wl.recurrent[layer - 1] and n_out % 64 == 0
                  and pad8(wl.sizes[layer + 1]) <= 128)
     fused_fwd = fused_rev and layer == L - 1 and n_out in (64, 128, 256) and pad8(wl.sizes[L]) <= 32
-    # a feed-forward layer of 64..256 padded neurons runs product and scan as one launch (rasters beyond 256
+    # a feed-forward layer of 64..1024 padded neurons runs product and scan as one launch (rasters beyond 256
     # steps: from 64 samples on); two consecutive such layers of exactly 128 neurons share a launch, and the
     # last spiking layer's launch (128 neurons, at most 32 padded classes) runs the whole readout
     chain, with_readout = forward_chain(wl, layer)
@@ -85,9 +85,9 @@ def forward_chain(wl, layer):
     pad8 = lambda n: (n + 7) // 8 * 8
 
     def whole(l):
-        n = pad8(wl.sizes[l])
-        return (wl.precision == "bf16" and 1 <= l < L and not wl.recurrent[l - 1] and n % 64 == 0 and n <= 256
-                and (wl.T <= 256 or wl.B >= 64))
+        n, k = pad8(wl.sizes[l]), wl.sizes[l - 1] if l >= 1 else 0
+        return (wl.precision == "bf16" and 1 <= l < L and not wl.recurrent[l - 1] and n % 64 == 0 and n <= 1024
+                and pad8(k) <= 1024 and (wl.T <= 256 or wl.B >= 64))
     if not whole(layer):
         return [], False
     chain = [layer]
@@ -227,13 +227,13 @@ def main():
     # algorithmic GB/s over all its launches of a step
     L = len(wl.sizes) - 1
     if not any(wl.recurrent):
-        chain, _ = forward_chain(wl, 1)
         class_bytes = {"weight_grad": algorithmic_bytes(wl, "weight_grad", 0),
-                       "lif_reverse": sum(algorithmic_bytes(wl, "lif_reverse", l) for l in range(1, L))}
-        if len(chain) == L - 1:
-            class_bytes["lif_forward"] = algorithmic_bytes(wl, "lif_forward", 1)
-        elif not chain:
-            class_bytes["lif_forward"] = sum(algorithmic_bytes(wl, "lif_forward", l) for l in range(1, L))
+                       "lif_reverse": sum(algorithmic_bytes(wl, "lif_reverse", l) for l in range(1, L)),
+                       "lif_forward": 0}
+        l = 1
+        while l < L:                                   # one term per forward launch of the class
+            class_bytes["lif_forward"] += algorithmic_bytes(wl, "lif_forward", l)
+            l += max(1, len(forward_chain(wl, l)[0]))
         for k, nbytes in class_bytes.items():
             if k in per_class and per_class[k]["us_per_step"] > 0:
                 per_class[k]["algorithmic_gb_per_s"] = round(nbytes / per_class[k]["us_per_step"] / 1e3, 1)

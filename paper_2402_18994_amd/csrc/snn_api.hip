@@ -720,8 +720,10 @@ int launch_lif_forward_top(snn_ctx *c) {
 }
 
 // The same reverse pass as one workgroup per sample and 64 neurons on LDS
-// (lif_layer_reverse_kernel): layers of 64 to 256 neurons, 32-bit byte offsets.  SNN_FUSE_LAYER_REV=0 switches it off; SNN_FUSE_LAYER_MIN_B as for the
-// forward pass.  Both read per call.
+// (lif_layer_reverse_kernel): layers of 64 to 256 neurons (wider, the scan with a wavefront per
+// 64 chains is faster: 121 against 129 us at 512 neurons, 466 against 492 at 1024), 32-bit byte
+// offsets.  SNN_FUSE_LAYER_REV=0 switches it off; SNN_FUSE_LAYER_MIN_B as for the forward pass.
+// Both read per call.
 bool layer_reverse_whole(snn_ctx *c, int l) {
   const char *e = getenv("SNN_FUSE_LAYER_REV");
   if (e && atoi(e) == 0) return false;
@@ -802,11 +804,15 @@ int launch_lif_reverse_fused(snn_ctx *c, int l) {
   return SNN_OK;
 }
 
-// A feed-forward spiking layer of 64, 128, 192 or 256 (padded) neurons on rounded weights runs
-// as ONE launch, product and scan (lif_layer_forward_kernel): I is not stored.  A workgroup
-// owns a sample and 64 or 128 neurons; 32-bit
+// A feed-forward spiking layer of up to 1024 (padded) neurons, a multiple of 64, on rounded
+// weights runs as ONE launch, product and scan (lif_layer_forward_kernel): I is not stored.
+// A workgroup owns a sample and 64 or 128 neurons; 32-bit
 // byte offsets into the spikes below and V; a threshold the scan's compare-free spike
 // decision is exact for.
+// Width limit (SNN_LAYER_MAX_NEURONS): the parts of a sample each pass its spike rows below
+// through their CU, which the I round trip saved outweighs up to 1024 neurons (product + scan
+// 228 -> 169 us at 700-512-512-20, 982 -> 781 us at 700-1024-1024-20, 256 steps) and no longer
+// at 2048 (1433 -> 1455 us, 512 steps, 128 samples); the same limit holds for the fan-in.
 // SNN_FUSE_LAYER: 0 never, 1 all but the last spiking layer, 2 every such layer, 3 the last one
 // also forms the readout's currents when it has exactly 128 padded neurons, 4 (default) and runs
 // the readout scan, the loss and the readout's current gradients;
@@ -818,14 +824,18 @@ int layer_fuse_mode() {
   const char *e = getenv("SNN_FUSE_LAYER");
   return e ? atoi(e) : 4;
 }
+static int layer_max_neurons() {
+  const char *e = getenv("SNN_LAYER_MAX_NEURONS");
+  return e ? atoi(e) : 1024;
+}
 bool layer_forward_fusable(snn_ctx *c, int l) {
   if (l < 0 || l > c->L - 2) return false;
   const Layer &y = c->layers[l];
   const char *e = getenv("SNN_FUSE_LAYER_MIN_B");
   const int min_b = e ? atoi(e) : c->T <= 256 ? 1 : 64;   // a workgroup walks a sample's blocks of 128 steps one after the other
   const SpikeSrc s = spikes_below(c, l);
-  return c->nplanes == 1 && y.spiking && !y.recurrent && y.ld % 64 == 0 && y.ld <= 256 && c->B >= min_b &&
-         s.ld % 4 == 0 && (size_t)c->M * s.ld < ((size_t)1 << 31) && (size_t)c->M * y.ld * 4 < ((size_t)1 << 31) &&
+  return c->nplanes == 1 && y.spiking && !y.recurrent && y.ld % 64 == 0 && y.ld <= layer_max_neurons() && c->B >= min_b &&
+         s.ld % 4 == 0 && s.ld <= layer_max_neurons() && (size_t)c->M * s.ld < ((size_t)1 << 31) && (size_t)c->M * y.ld * 4 < ((size_t)1 << 31) &&
          y.qf_plane >= (long long)y.ld * y.ldqf && c->theta >= 0x1p-60f && c->theta <= 0x1p26f;
 }
 

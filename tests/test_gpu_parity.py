@@ -159,17 +159,20 @@ def test_top_layer_scans_same_as_unfused(monkeypatch):
 
 @pytest.mark.parametrize("T,sizes,nt,bn", [(37, (90, 128, 128, 10), False, 128), (150, (203, 128, 121, 20), False, 64),
                                            (260, (20, 128, 64, 10), True, 128), (128, (700, 128, 128, 20), False, 128),
-                                           (70, (150, 192, 256, 20), False, 128), (45, (64, 256, 128, 10), True, 64)],
+                                           (70, (150, 192, 256, 20), False, 128), (45, (64, 256, 128, 10), True, 64),
+                                           (150, (90, 512, 384, 10), False, 128), (30, (330, 960, 1024, 20), True, 128)],
                          ids=["one-block", "two-blocks-ragged-fan-in", "three-blocks-nontemporal", "headline-widths",
-                              "192-and-256-neurons", "256-neurons-in-four-parts"])
+                              "192-and-256-neurons", "256-neurons-in-four-parts", "512-and-384-neurons",
+                              "960-and-1024-neurons"])
 def test_layer_forward_in_one_launch(monkeypatch, T, sizes, nt, bn):
-    """bf16 products, feed-forward spiking layers of 64 to 256 (padded) neurons: product and scan
+    """bf16 products, feed-forward spiking layers of 64 to 1024 (padded) neurons: product and scan
     run as one launch per layer, a workgroup per sample and 64 or 128 neurons, and I is never
     stored (read back, it comes from the product kernel).  For rasters of more than 256 steps the
     library uses the path from 64 samples on; the knob lowers that so that an element-by-element
-    oracle run covers those too: one, two and three blocks of 128 steps with ragged tails, fan-ins that are no multiple of 32 or
-    of 16 bytes, a layer of 121 neurons padded to 128, layers of 64, 192 and 256 neurons, both
-    workgroup widths, stores with and without the non-temporal hint."""
+    oracle run covers those too: one, two and three blocks of 128 steps with ragged tails,
+    fan-ins that are no multiple of 32 or of 16 bytes, a layer of 121 neurons padded to 128,
+    layers of 64, 192, 256, 384, 512, 960 (fifteen parts of 64) and 1024 neurons, both workgroup
+    widths, stores with and without the non-temporal hint."""
     monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
     monkeypatch.setenv("SNN_LAYER_NEURONS", str(bn))
     if nt:
@@ -368,6 +371,7 @@ def large_tensor_paths(monkeypatch):
     cover: the library reads these two knobs at every launch."""
     monkeypatch.setenv("SNN_STREAM_MIN_MB", "0")
     monkeypatch.setenv("SNN_TILE_ROWS", "128")
+    monkeypatch.setenv("SNN_FUSE_LAYER", "0")     # product and scan as separate launches: these tests are about them
 
 
 @pytest.mark.parametrize("sizes", [(100, 200, 136, 10), (300, 330, 260, 20)], ids=["narrow-tiles", "wide-tiles"])
@@ -414,9 +418,11 @@ def sampled_parity(wl, w_gain, n_samples=6, **tols):
 
 
 @pytest.mark.parametrize("B", [128, 512])
-def test_wide_layers_vector_scans(B):
+def test_wide_layers_vector_scans(monkeypatch, B):
     """B * N of 2^17 and 2^19 chains: the scan kernels that give two and four adjacent chains
-    to a thread (8- and 16-byte accesses), checked on every element."""
+    to a thread (8- and 16-byte accesses), checked on every element (product and scan as
+    separate launches, as for layers wider than 1024 neurons)."""
+    monkeypatch.setenv("SNN_FUSE_LAYER", "0")
     wl = workloads.Workload(name="widescan", index=13, T=24, B=B, sizes=(64, 1024, 1024, 20),
                             recurrent=(False, False), beta=(0.9, 0.9, 0.9), theta=1.0, surrogate="superspike",
                             slope=25.0, precision="bf16", rate_lo=0.05, rate_hi=0.3)
