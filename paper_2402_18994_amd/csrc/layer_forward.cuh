@@ -81,11 +81,11 @@ struct LayerForwardArgs {
   const float *beta_r;     // [ldj] decays of the readout
   int C;                   // classes
 #ifdef SNN_LAYER_PROBE
-  unsigned long long *probe;   // [B][8] device clock at the phase boundaries of the first block (development builds only)
+  unsigned long long *probe;   // [B][2][8] device clock at the phase boundaries of the first block, per layer of the launch; [B][1][7]: the end (development builds only)
 #endif
 };
 #ifdef SNN_LAYER_PROBE
-#define SNN_PROBE(i) do { if (tid == 0 && t0 == 0 && n0 == 0) a.probe[b * 8 + (i)] = wall_clock64(); } while (0)
+#define SNN_PROBE(i) do { if (tid == 0 && t0 == 0 && n0 == 0) a.probe[b * 16 + li * 8 + (i)] = wall_clock64(); } while (0)
 #else
 #define SNN_PROBE(i) do { } while (0)
 #endif
@@ -404,6 +404,9 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
       }
     }
   }
+#ifdef SNN_LAYER_PROBE
+  if (tid == 0 && n0 == 0) a.probe[b * 16 + 15] = wall_clock64();
+#endif
 }
 
 }  // namespace snn
