@@ -38,7 +38,14 @@ __device__ __forceinline__ bf16x8 rl_weight_frag(rsrc_t r, int row, int ldq, int
   return __builtin_bit_cast(bf16x8, v);
 }
 
-template <int NP>   // weight planes: 1 (bfloat16 weights) or 3 (fp32 as hi + mid + lo)
+// STG (rows of a multiple of 16 neurons): V_t and S_t leave through LDS.  In the accumulator
+// layout a store instruction touches 32 sample rows with 32 bytes each, and the eight of a step
+// cost 0.65 of its 1.40 us; staged, the four wavefronts store whole rows (512 bytes of V per
+// half wavefront, 128 bytes of S per eight lanes), five instructions each.  The stage is written
+// before the step's barrier, next to the spike tile, and double-buffered like it.
+constexpr int RL_VP = 132;                    // floats per sample row of the V stage (128 + pad)
+constexpr int RL_SP = 144;                    // bytes per sample row of the S stage (128 + pad)
+template <int NP, bool STG>   // NP weight planes: 1 (bfloat16 weights) or 3 (fp32 as hi + mid + lo)
 __global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__restrict__ I, float *__restrict__ V,
                                                                  uint8_t *__restrict__ S,
                                                                  const uint16_t *__restrict__ QRf, int ldqr,
@@ -46,11 +53,27 @@ __global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__
                                                                  const float *__restrict__ beta_v, float theta) {
   constexpr int PF = 4;
   __shared__ __align__(16) char xs[2][32 * RL_PITCH];
+  __shared__ __align__(16) float vstage[STG ? 2 : 1][STG ? 32 * RL_VP : 4];
+  __shared__ __align__(16) uint8_t sstage[STG ? 2 : 1][STG ? 32 * RL_SP : 16];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int b = blockIdx.x * 32 + (lane & 31);
   const int row4 = B * ld * 4;
   const unsigned bytes = (unsigned)T * B * ld * 4u;
   const rsrc_t rI = make_rsrc(I, bytes), rV = make_rsrc(V, bytes), rS = make_rsrc(S, bytes / 4);
+  // staged stores: V instruction k of wavefront w takes sample rows 8k + 2w + lane/32, four
+  // neurons per lane; the S instruction rows 8w + lane/8, sixteen neurons per lane
+  int vro[4], vlo[4], sro, slo;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int r = 8 * k + 2 * w + (lane >> 5), c = (lane & 31) * 4, bb = blockIdx.x * 32 + r;
+    vro[k] = bb < B && c < ld ? (bb * ld + c) * 4 : OOB;
+    vlo[k] = r * RL_VP + c;
+  }
+  {
+    const int r = 8 * w + (lane >> 3), c = (lane & 7) * 16, bb = blockIdx.x * 32 + r;
+    sro = bb < B && c < ld ? bb * ld + c : OOB;
+    slo = r * RL_SP + c;
+  }
   const rsrc_t rQ = make_rsrc(QRf, (unsigned)(NP * qr_plane * 2));
 
   bf16x8 wf[NP][8];                             // R^T[32w + (lane&31)][:], all planes, all k steps
@@ -99,6 +122,16 @@ __global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__
       sx[1] = (sp[4 * g + 2] | (sp[4 * g + 3] << 16)) * 0x3F80u;
       *(u32x2 *)(x + xo[g]) = sx;
     }
+    if (STG) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n = 32 * w + 8 * g + 4 * (lane >> 5);
+        f32x4 vv = {v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
+        *(f32x4 *)&vstage[t & 1][(lane & 31) * RL_VP + n] = vv;
+        *(uint32_t *)&sstage[t & 1][(lane & 31) * RL_SP + n] =
+            sp[4 * g] | (sp[4 * g + 1] << 8) | (sp[4 * g + 2] << 16) | (sp[4 * g + 3] << 24);
+      }
+    }
     f32x16 acc, acc1;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = acc1[r] = 0.f;
@@ -114,13 +147,19 @@ __global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__
         }
       }
     }
+    if (STG) {
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      u32x4 vv;
+      for (int k = 0; k < 4; ++k) st_b128(rV, vro[k], t * row4, *(const u32x4 *)&vstage[t & 1][vlo[k]]);
+      st_b128(rS, sro, t * (row4 >> 2), *(const u32x4 *)&sstage[t & 1][slo]);
+    } else {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) vv[i] = __float_as_uint(v[4 * g + i]);
-      st_b128(rV, vo4[g], t * row4, vv);
-      st_b32(rS, vo1[g], t * (row4 >> 2), sp[4 * g] | (sp[4 * g + 1] << 8) | (sp[4 * g + 2] << 16) | (sp[4 * g + 3] << 24));
+      for (int g = 0; g < 4; ++g) {
+        u32x4 vv;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) vv[i] = __float_as_uint(v[4 * g + i]);
+        st_b128(rV, vo4[g], t * row4, vv);
+        st_b32(rS, vo1[g], t * (row4 >> 2), sp[4 * g] | (sp[4 * g + 1] << 8) | (sp[4 * g + 2] << 16) | (sp[4 * g + 3] << 24));
+      }
     }
     // accumulator register r: neuron 32w + 8*(r/4) + 4*(lane/32) + r%4, i.e. group r/4, element r%4
 #pragma unroll
@@ -575,12 +614,14 @@ static hipError_t rlif_forward(hipStream_t st, bool fp32, int T, int B, int N, i
                                float theta) {
   if (ld <= 128) {                              // the whole time loop in one launch
     dim3 grid((B + 31) / 32), block(256);
-    if (fp32)
-      hipLaunchKernelGGL(rlif_forward_fused_kernel<3>, grid, block, 0, st, I, V, S, QRf, ldqr, qr_plane, T, B, N, ld,
-                         beta, theta);
-    else
-      hipLaunchKernelGGL(rlif_forward_fused_kernel<1>, grid, block, 0, st, I, V, S, QRf, ldqr, qr_plane, T, B, N, ld,
-                         beta, theta);
+    const char *se = getenv("SNN_RLIF_STAGE");          // test knob: 0 = stores straight from the accumulator layout
+    const bool stg = ld % 16 == 0 && !(se && atoi(se) == 0);
+#define SNN_RLF(NP_, STG_)                                                                                       \
+  hipLaunchKernelGGL((rlif_forward_fused_kernel<NP_, STG_>), grid, block, 0, st, I, V, S, QRf, ldqr, qr_plane, T, B, \
+                     N, ld, beta, theta)
+    if (fp32) { if (stg) SNN_RLF(3, true); else SNN_RLF(3, false); }
+    else { if (stg) SNN_RLF(1, true); else SNN_RLF(1, false); }
+#undef SNN_RLF
     return hipGetLastError();
   }
   const size_t stride = (size_t)B * ld;
