@@ -456,6 +456,29 @@ def test_shd_ff128_fp32_products():
 
 # ---------------------------------------------------------------- recurrent layers
 @pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_recurrent_forward_row_stores_same_bits(monkeypatch, precision):
+    """Narrow recurrent layers whose rows are a multiple of 16 neurons store V_t and S_t as whole
+    rows through an LDS stage; the knob keeps the stores straight from the accumulator layout.
+    Same arithmetic, so every stored value has the same bits: layers of 96 and 128 neurons, a batch
+    of 45 (a second workgroup with 13 samples), 37 steps (both buffers of the stage, odd tail)."""
+    wl = workloads.Workload(name="rec_rows", index=27, T=37, B=45, sizes=(60, 96, 128, 10), recurrent=(True, True),
+                            beta=(0.9, 0.92, 0.95), theta=1.0, surrogate="superspike", slope=25.0,
+                            precision=precision, rate_lo=0.05, rate_hi=0.2, rec_gain=1.0)
+    inp = workloads.generate(wl, w_gain=2.0)
+    out = []
+    for knob in ("1", "0"):
+        monkeypatch.setenv("SNN_RLIF_STAGE", knob)
+        snn = make(wl, inp)
+        snn.forward(inp.X, inp.labels)
+        out.append([snn.get_tensor("membrane", 1), snn.get_tensor("spikes", 1), snn.get_tensor("membrane", 2),
+                    snn.get_tensor("spikes", 2), snn.get_tensor("readout_trace")])
+        snn.destroy()
+    for a, b in zip(*out):
+        assert np.array_equal(a, b)
+    assert out[0][1].mean() > 0.005 and out[0][3].mean() > 0.005
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
 def test_recurrent_small(precision):
     wl = workloads.Workload(name="rec_small", index=13, T=31, B=40, sizes=(50, 40, 24, 5), recurrent=(True, True),
                             beta=(0.9, 0.9, 0.9), theta=1.0, surrogate="superspike", slope=25.0,
