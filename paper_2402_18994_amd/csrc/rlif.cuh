@@ -178,6 +178,128 @@ __global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__
     if (t + d < T) step(cur[d], t + d);
 }
 
+// The same forward pass on tiles of 16 samples (16x16x32 MFMAs): a lane then carries 8 neurons
+// of one sample instead of 16 - half the compares, packs, updates, loads and LDS traffic in the
+// step's dependent chain - and a batch fills twice as many compute units.  Wavefront w still
+// owns neurons [32w, 32w+32), as two row tiles of 16; in a tile's accumulator the lane holds
+// sample (lane & 15) and the four adjacent neurons 4 (lane / 16) .. +3.  Rows of a multiple of 16
+// neurons only: V_t and S_t always leave through the LDS stage (rows 8k + 2w + lane/32 of the
+// tile for V instruction k = 0, 1; the first two wavefronts store S, rows 8w + lane/8).
+template <int NP>
+__global__ __launch_bounds__(256) void rlif_forward_fused16_kernel(const float *__restrict__ I, float *__restrict__ V,
+                                                                   uint8_t *__restrict__ S,
+                                                                   const uint16_t *__restrict__ QRf, int ldqr,
+                                                                   long long qr_plane, int T, int B, int N, int ld,
+                                                                   const float *__restrict__ beta_v, float theta) {
+  constexpr int PF = 4;
+  __shared__ __align__(16) char xs[2][16 * RL_PITCH];
+  __shared__ __align__(16) float vstage[2][16 * RL_VP];
+  __shared__ __align__(16) uint8_t sstage[2][16 * RL_SP];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int bl = lane & 15, q = lane >> 4;       // sample of the tile, group of four neurons / of eight k
+  const int b = blockIdx.x * 16 + bl;
+  const int row4 = B * ld * 4;
+  const unsigned bytes = (unsigned)T * B * ld * 4u;
+  const rsrc_t rI = make_rsrc(I, bytes), rV = make_rsrc(V, bytes), rS = make_rsrc(S, bytes / 4);
+  const rsrc_t rQ = make_rsrc(QRf, (unsigned)(NP * qr_plane * 2));
+
+  // R^T[32w + 16i + (lane & 15)][32 ks + 8 q .. +7], all planes: resident
+  bf16x8 wf[NP][2][4];
+#pragma unroll
+  for (int p = 0; p < NP; ++p)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const int row = (int)(p * (qr_plane / ldqr)) + 32 * w + 16 * i + bl, k = 32 * ks + 8 * q;
+        wf[p][i][ks] = __builtin_bit_cast(bf16x8, ld_b128(rQ, k < ldqr ? (row * ldqr + k) * 2 : OOB, 0));
+      }
+
+  int vo4[2], xo[2], nn[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    nn[i] = 32 * w + 16 * i + 4 * q;
+    vo4[i] = b < B && nn[i] < ld ? (b * ld + nn[i]) * 4 : OOB;
+    xo[i] = bl * RL_PITCH + nn[i] * 2;
+  }
+  int vro[2], vlo[2], sro, slo;
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int r = 8 * k + 2 * w + (lane >> 5), c = (lane & 31) * 4, bb = blockIdx.x * 16 + r;
+    vro[k] = bb < B && c < ld ? (bb * ld + c) * 4 : OOB;
+    vlo[k] = r * RL_VP + c;
+  }
+  {
+    const int r = 8 * (w & 1) + (lane >> 3), c = (lane & 7) * 16, bb = blockIdx.x * 16 + r;
+    sro = w < 2 && bb < B && c < ld ? bb * ld + c : OOB;
+    slo = r * RL_SP + c;
+  }
+  float v[8], beta[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    v[e] = 0.f;                                  // V_0 = 0
+    const int n = nn[e >> 2] + (e & 3);
+    beta[e] = n < ld ? beta_v[n] : 0.f;
+  }
+  u32x4 cur[PF][2];
+#pragma unroll
+  for (int d = 0; d < PF; ++d)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) cur[d][i] = ld_b128(rI, vo4[i], min(d, T - 1) * row4);
+
+  auto step = [&](u32x4 (&in)[2], int t) {
+    uint32_t sp[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sp[e] = v[e] > theta ? 1u : 0u;
+    char *x = xs[t & 1];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      u32x2 sx;                                  // four spikes as bfloat16 0.0 / 1.0
+      sx[0] = (sp[4 * i] | (sp[4 * i + 1] << 16)) * 0x3F80u;
+      sx[1] = (sp[4 * i + 2] | (sp[4 * i + 3] << 16)) * 0x3F80u;
+      *(u32x2 *)(x + xo[i]) = sx;
+      f32x4 vv = {v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]};
+      *(f32x4 *)&vstage[t & 1][bl * RL_VP + nn[i]] = vv;
+      *(uint32_t *)&sstage[t & 1][bl * RL_SP + nn[i]] =
+          sp[4 * i] | (sp[4 * i + 1] << 8) | (sp[4 * i + 2] << 16) | (sp[4 * i + 3] << 24);
+    }
+    f32x4 acc[2][2];                             // [tile][even / odd k step]
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int o = 0; o < 2; ++o) acc[i][o] = f32x4{0.f, 0.f, 0.f, 0.f};
+    lds_barrier();
+    if (t + 1 < T) {                             // the last state is not used
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const bf16x8 sf = *(const bf16x8 *)(x + bl * RL_PITCH + (32 * ks + 8 * q) * 2);
+#pragma unroll
+        for (int p = NP - 1; p >= 0; --p)
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+            acc[i][ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[p][i][ks], sf, acc[i][ks & 1], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) st_b128(rV, vro[k], t * row4, *(const u32x4 *)&vstage[t & 1][vlo[k]]);
+    st_b128(rS, sro, t * (row4 >> 2), *(const u32x4 *)&sstage[t & 1][slo]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      v[e] = beta[e] * v[e] + __uint_as_float(in[e >> 2][e & 3]) + (acc[e >> 2][0][e & 3] + acc[e >> 2][1][e & 3]) -
+             (sp[e] ? theta : 0.f);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) in[i] = ld_b128(rI, vo4[i], min(t + PF, T - 1) * row4);
+  };
+  int t = 0;
+  for (; t + PF <= T; t += PF) {
+#pragma unroll
+    for (int d = 0; d < PF; ++d) step(cur[d], t + d);
+  }
+#pragma unroll
+  for (int d = 0; d < PF; ++d)
+    if (t + d < T) step(cur[d], t + d);
+}
+
 // Reverse pass of the same layers: g <- beta g + surr(V_t - theta) (dS_t - theta g + g R^T), dI_t = g
 // before the update.  g is real-valued, so it enters the product as bfloat16 planes (hi + lo
 // with bfloat16 weights, hi + mid + lo with fp32 weights); (g R^T)^T = R g^T with R[from][to]
@@ -616,6 +738,17 @@ static hipError_t rlif_forward(hipStream_t st, bool fp32, int T, int B, int N, i
     dim3 grid((B + 31) / 32), block(256);
     const char *se = getenv("SNN_RLIF_STAGE");          // test knob: 0 = stores straight from the accumulator layout
     const bool stg = ld % 16 == 0 && !(se && atoi(se) == 0);
+    const char *te = getenv("SNN_RLIF_TILE");           // 32: tiles of 32 samples also where 16 are possible
+    if (stg && !(te && atoi(te) == 32)) {
+      const dim3 grid16((B + 15) / 16);
+      if (fp32)
+        hipLaunchKernelGGL(rlif_forward_fused16_kernel<3>, grid16, block, 0, st, I, V, S, QRf, ldqr, qr_plane, T, B, N, ld,
+                           beta, theta);
+      else
+        hipLaunchKernelGGL(rlif_forward_fused16_kernel<1>, grid16, block, 0, st, I, V, S, QRf, ldqr, qr_plane, T, B, N, ld,
+                           beta, theta);
+      return hipGetLastError();
+    }
 #define SNN_RLF(NP_, STG_)                                                                                       \
   hipLaunchKernelGGL((rlif_forward_fused_kernel<NP_, STG_>), grid, block, 0, st, I, V, S, QRf, ldqr, qr_plane, T, B, \
                      N, ld, beta, theta)

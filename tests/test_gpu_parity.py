@@ -465,6 +465,7 @@ def test_recurrent_forward_row_stores_same_bits(monkeypatch, precision):
                             beta=(0.9, 0.92, 0.95), theta=1.0, surrogate="superspike", slope=25.0,
                             precision=precision, rate_lo=0.05, rate_hi=0.2, rec_gain=1.0)
     inp = workloads.generate(wl, w_gain=2.0)
+    monkeypatch.setenv("SNN_RLIF_TILE", "32")      # both on tiles of 32 samples (16-sample tiles add in another order)
     out = []
     for knob in ("1", "0"):
         monkeypatch.setenv("SNN_RLIF_STAGE", knob)
@@ -476,6 +477,20 @@ def test_recurrent_forward_row_stores_same_bits(monkeypatch, precision):
     for a, b in zip(*out):
         assert np.array_equal(a, b)
     assert out[0][1].mean() > 0.005 and out[0][3].mean() > 0.005
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+@pytest.mark.parametrize("tile", ["16", "32"])
+def test_recurrent_forward_sample_tiles(monkeypatch, precision, tile):
+    """Narrow recurrent layers with rows of a multiple of 16 neurons run on tiles of 16 samples
+    (default) or 32 (knob): full parity for both, layers of 96 and 128 neurons, a batch of 45 (tails
+    of 13 samples in either tiling), 37 steps."""
+    monkeypatch.setenv("SNN_RLIF_TILE", tile)
+    wl = workloads.Workload(name="rec_tiles", index=28, T=37, B=45, sizes=(60, 96, 128, 10), recurrent=(True, True),
+                            beta=(0.9, 0.92, 0.95), theta=1.0, surrogate="superspike", slope=25.0,
+                            precision=precision, rate_lo=0.05, rate_hi=0.2, rec_gain=1.0)
+    rep = full_step_parity(wl, w_gain=2.0)
+    assert rep["spike_rate"][0] > 0.005 and rep["spike_rate"][1] > 0.005
 
 
 @pytest.mark.parametrize("precision", ["fp32", "bf16"])
