@@ -448,6 +448,154 @@ __global__ __launch_bounds__(256) void rlif_reverse_fused_kernel(const float *__
   }
 }
 
+// The reverse pass on tiles of 16 samples, as rlif_forward_fused16_kernel: a lane carries 8
+// neurons of one sample, wavefront w two row tiles of 16 neurons of R.
+template <int NP, int SURR>
+__global__ __launch_bounds__(256) void rlif_reverse_fused16_kernel(const float *__restrict__ dS,
+                                                                   const float *__restrict__ V,
+                                                                   uint32_t *__restrict__ dI,
+                                                                   const uint16_t *__restrict__ QRb, int ldqr,
+                                                                   long long qr_plane, int T, int B, int N, int ld,
+                                                                   const float *__restrict__ beta_v, float theta, float slope,
+                                                                   float *__restrict__ db_part) {
+  constexpr int PF = 2;
+  constexpr int GP = NP == 1 ? 2 : 3;           // planes of g
+  constexpr bool HL = NP == 1;                  // dI is stored in hi/lo form with bfloat16 weights
+  __shared__ __align__(16) char xs[2][GP][16 * RL_PITCH];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int bl = lane & 15, q4 = lane >> 4;
+  const int b = blockIdx.x * 16 + bl;
+  const int row4 = B * ld * 4;
+  const unsigned bytes = (unsigned)T * B * ld * 4u;
+  const rsrc_t rdS = make_rsrc(dS, bytes), rV = make_rsrc(V, bytes), rdI = make_rsrc(dI, bytes);
+  const rsrc_t rQ = make_rsrc(QRb, (unsigned)(NP * qr_plane * 2));
+
+  bf16x8 wf[NP][2][4];                          // R[32w + 16i + (lane & 15)][32 ks + 8 (lane / 16) .. +7]
+#pragma unroll
+  for (int p = 0; p < NP; ++p)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const int row = (int)(p * (qr_plane / ldqr)) + 32 * w + 16 * i + bl, k = 32 * ks + 8 * q4;
+        wf[p][i][ks] = __builtin_bit_cast(bf16x8, ld_b128(rQ, k < ldqr ? (row * ldqr + k) * 2 : OOB, 0));
+      }
+
+  int vo4[2], xo[2], nn[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    nn[i] = 32 * w + 16 * i + 4 * q4;
+    vo4[i] = b < B && nn[i] < ld ? (b * ld + nn[i]) * 4 : OOB;
+    xo[i] = bl * RL_PITCH + nn[i] * 2;
+  }
+  float gv[8], beta[8], db[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    gv[e] = 0.f;                                 // g_T = 0
+    db[e] = 0.f;                                 // sum over t of g_{t+1} V_t
+    const int n = nn[e >> 2] + (e & 3);
+    beta[e] = n < ld ? beta_v[n] : 0.f;
+  }
+  u32x4 cds[PF][2], cv[PF][2];
+#pragma unroll
+  for (int d = 0; d < PF; ++d)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int so = max(T - 1 - d, 0) * row4;
+      cds[d][i] = ld_b128(rdS, vo4[i], so);
+      cv[d][i] = ld_b128(rV, vo4[i], so);
+    }
+
+  auto step = [&](u32x4 (&ds)[2], u32x4 (&vv)[2], int t) {
+    char *x = (char *)xs[t & 1];
+    u32x4 o[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      uint32_t pl[GP][4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float gg = gv[4 * i + j];
+        if (HL) {
+          const uint32_t hl = pack_hl(gg);
+          o[i][j] = hl;
+          pl[0][j] = hl & 0xFFFFu;
+          pl[1][j] = hl >> 16;
+        } else {
+          o[i][j] = __float_as_uint(gg);
+#pragma unroll
+          for (int q = 0; q < GP; ++q) pl[q][j] = bf16_piece(gg, q);
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < GP; ++q) {
+        u32x2 px;
+        px[0] = pl[q][0] | (pl[q][1] << 16);
+        px[1] = pl[q][2] | (pl[q][3] << 16);
+        *(u32x2 *)(x + q * 16 * RL_PITCH + xo[i]) = px;
+      }
+    }
+    f32x4 acc[2][2];                             // [tile][even / odd k step]
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int o2 = 0; o2 < 2; ++o2) acc[i][o2] = f32x4{0.f, 0.f, 0.f, 0.f};
+    lds_barrier();
+    if (t > 0) {                                 // the g leaving step 0 is not used
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        bf16x8 gf[GP];
+#pragma unroll
+        for (int q = 0; q < GP; ++q)
+          gf[q] = *(const bf16x8 *)(x + q * 16 * RL_PITCH + bl * RL_PITCH + (32 * ks + 8 * q4) * 2);
+        // smallest products first
+#pragma unroll
+        for (int sum = NP + GP - 2; sum >= 0; --sum)
+#pragma unroll
+          for (int p = 0; p < NP; ++p) {
+            const int q = sum - p;
+            if (q >= 0 && q < GP && (NP == 1 || p + q < 3)) {
+#pragma unroll
+              for (int i = 0; i < 2; ++i)
+                acc[i][ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[p][i][ks], gf[q], acc[i][ks & 1], 0, 0, 0);
+            }
+          }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) st_b128(rdI, vo4[i], t * row4, o[i]);
+    float sg[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sg[e] = surr_rcp<SURR>(slope, __uint_as_float(vv[e >> 2][e & 3]) - theta);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float qq = __uint_as_float(ds[e >> 2][e & 3]) - theta * gv[e] + (acc[e >> 2][0][e & 3] + acc[e >> 2][1][e & 3]);
+      const float vt = __uint_as_float(vv[e >> 2][e & 3]);
+      db[e] += gv[e] * vt;
+      gv[e] = beta[e] * gv[e] + sg[e] * qq;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int so = max(t - PF, 0) * row4;
+      ds[i] = ld_b128(rdS, vo4[i], so);
+      vv[i] = ld_b128(rV, vo4[i], so);
+    }
+  };
+  int t = T - 1;
+  for (; t - PF + 1 >= 0; t -= PF) {
+#pragma unroll
+    for (int d = 0; d < PF; ++d) step(cds[d], cv[d], t - d);
+  }
+#pragma unroll
+  for (int d = 0; d < PF; ++d)
+    if (t - d >= 0) step(cds[d], cv[d], t - d);
+  if (db_part) {                                 // per sample; summed over the batch by the reduction launch
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      if (b < B && nn[i] < ld)
+        *(float4 *)(db_part + (size_t)b * ld + nn[i]) = make_float4(db[4 * i], db[4 * i + 1], db[4 * i + 2], db[4 * i + 3]);
+  }
+}
+
 // ---------------------------------------------------------------- wide layers: one launch per step
 // Wider layers do not fit a workgroup, so time is walked on the host side of the stream and
 // stream order is the inter-step barrier.  One step is the transposed product of the fused
@@ -784,10 +932,18 @@ static hipError_t rlif_reverse(hipStream_t st, bool fp32, int T, int B, int N, i
                                uint32_t *dI, float *g0, float *g1, const uint16_t *QRb, int ldqr,
                                long long qr_plane, const float *beta, float theta, int surrogate, float slope, float *db_part) {
   if (ld <= 128) {
-    dim3 grid((B + 31) / 32), block(256);
+    const char *te = getenv("SNN_RLIF_TILE");           // 32: tiles of 32 samples instead of 16
+    const bool t32 = te && atoi(te) == 32;
+    dim3 grid(t32 ? (B + 31) / 32 : (B + 15) / 16), block(256);
 #define SNN_RLR(NP, SU)                                                                                         \
-  hipLaunchKernelGGL((rlif_reverse_fused_kernel<NP, SU>), grid, block, 0, st, dS, V, dI, QRb, ldqr, qr_plane, T, B, \
-                     N, ld, beta, theta, slope, db_part)
+  do {                                                                                                          \
+    if (t32)                                                                                                    \
+      hipLaunchKernelGGL((rlif_reverse_fused_kernel<NP, SU>), grid, block, 0, st, dS, V, dI, QRb, ldqr, qr_plane, T, \
+                         B, N, ld, beta, theta, slope, db_part);                                                \
+    else                                                                                                        \
+      hipLaunchKernelGGL((rlif_reverse_fused16_kernel<NP, SU>), grid, block, 0, st, dS, V, dI, QRb, ldqr, qr_plane, \
+                         T, B, N, ld, beta, theta, slope, db_part);                                             \
+  } while (0)
     if (fp32) {
       switch (surrogate) { case 0: SNN_RLR(3, 0); break; case 1: SNN_RLR(3, 1); break;
                            case 2: SNN_RLR(3, 2); break; case 3: SNN_RLR(3, 3); break;
