@@ -183,10 +183,12 @@ __global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__
 // step's dependent chain - and a batch fills twice as many compute units.  Wavefront w still
 // owns neurons [32w, 32w+32), as two row tiles of 16; in a tile's accumulator the lane holds
 // sample (lane & 15) and the four adjacent neurons 4 (lane / 16) .. +3.  Rows of a multiple of 16
-// neurons only: V_t and S_t always leave through the LDS stage (rows 8k + 2w + lane/32 of the
-// tile for V instruction k = 0, 1; the first two wavefronts store S, rows 8w + lane/8).
-template <int NP>
-__global__ __launch_bounds__(256) void rlif_forward_fused16_kernel(const float *__restrict__ I, float *__restrict__ V,
+// neurons only: V_t and S_t always leave through the LDS stage (rows 2 (NWV k + w) + lane/32 of
+// the tile for V instruction k; the first two wavefronts store S, rows 8w + lane/8).
+// NTW: row tiles per wavefront.  2: four wavefronts; 1: eight wavefronts of 16 neurons each, a
+// lane then carries 4 neurons (half the dependent chain again, two wavefronts per SIMD).
+template <int NP, int NTW>
+__global__ __launch_bounds__(512 / NTW) void rlif_forward_fused16_kernel(const float *__restrict__ I, float *__restrict__ V,
                                                                    uint8_t *__restrict__ S,
                                                                    const uint16_t *__restrict__ QRf, int ldqr,
                                                                    long long qr_plane, int T, int B, int N, int ld,
@@ -203,29 +205,30 @@ __global__ __launch_bounds__(256) void rlif_forward_fused16_kernel(const float *
   const rsrc_t rI = make_rsrc(I, bytes), rV = make_rsrc(V, bytes), rS = make_rsrc(S, bytes / 4);
   const rsrc_t rQ = make_rsrc(QRf, (unsigned)(NP * qr_plane * 2));
 
-  // R^T[32w + 16i + (lane & 15)][32 ks + 8 q .. +7], all planes: resident
-  bf16x8 wf[NP][2][4];
+  // R^T[16 (NTW w + i) + (lane & 15)][32 ks + 8 q .. +7], all planes: resident
+  constexpr int NWV = 8 / NTW;                   // wavefronts
+  bf16x8 wf[NP][NTW][4];
 #pragma unroll
   for (int p = 0; p < NP; ++p)
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NTW; ++i)
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
-        const int row = (int)(p * (qr_plane / ldqr)) + 32 * w + 16 * i + bl, k = 32 * ks + 8 * q;
+        const int row = (int)(p * (qr_plane / ldqr)) + 16 * (NTW * w + i) + bl, k = 32 * ks + 8 * q;
         wf[p][i][ks] = __builtin_bit_cast(bf16x8, ld_b128(rQ, k < ldqr ? (row * ldqr + k) * 2 : OOB, 0));
       }
 
-  int vo4[2], xo[2], nn[2];
+  int vo4[NTW], xo[NTW], nn[NTW];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    nn[i] = 32 * w + 16 * i + 4 * q;
+  for (int i = 0; i < NTW; ++i) {
+    nn[i] = 16 * (NTW * w + i) + 4 * q;
     vo4[i] = b < B && nn[i] < ld ? (b * ld + nn[i]) * 4 : OOB;
     xo[i] = bl * RL_PITCH + nn[i] * 2;
   }
-  int vro[2], vlo[2], sro, slo;
+  int vro[NTW], vlo[NTW], sro, slo;
 #pragma unroll
-  for (int k = 0; k < 2; ++k) {
-    const int r = 8 * k + 2 * w + (lane >> 5), c = (lane & 31) * 4, bb = blockIdx.x * 16 + r;
+  for (int k = 0; k < NTW; ++k) {
+    const int r = 2 * (NWV * k + w) + (lane >> 5), c = (lane & 31) * 4, bb = blockIdx.x * 16 + r;
     vro[k] = bb < B && c < ld ? (bb * ld + c) * 4 : OOB;
     vlo[k] = r * RL_VP + c;
   }
@@ -234,26 +237,26 @@ __global__ __launch_bounds__(256) void rlif_forward_fused16_kernel(const float *
     sro = w < 2 && bb < B && c < ld ? bb * ld + c : OOB;
     slo = r * RL_SP + c;
   }
-  float v[8], beta[8];
+  float v[4 * NTW], beta[4 * NTW];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
+  for (int e = 0; e < 4 * NTW; ++e) {
     v[e] = 0.f;                                  // V_0 = 0
     const int n = nn[e >> 2] + (e & 3);
     beta[e] = n < ld ? beta_v[n] : 0.f;
   }
-  u32x4 cur[PF][2];
+  u32x4 cur[PF][NTW];
 #pragma unroll
   for (int d = 0; d < PF; ++d)
 #pragma unroll
-    for (int i = 0; i < 2; ++i) cur[d][i] = ld_b128(rI, vo4[i], min(d, T - 1) * row4);
+    for (int i = 0; i < NTW; ++i) cur[d][i] = ld_b128(rI, vo4[i], min(d, T - 1) * row4);
 
-  auto step = [&](u32x4 (&in)[2], int t) {
-    uint32_t sp[8];
+  auto step = [&](u32x4 (&in)[NTW], int t) {
+    uint32_t sp[4 * NTW];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) sp[e] = v[e] > theta ? 1u : 0u;
+    for (int e = 0; e < 4 * NTW; ++e) sp[e] = v[e] > theta ? 1u : 0u;
     char *x = xs[t & 1];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < NTW; ++i) {
       u32x2 sx;                                  // four spikes as bfloat16 0.0 / 1.0
       sx[0] = (sp[4 * i] | (sp[4 * i + 1] << 16)) * 0x3F80u;
       sx[1] = (sp[4 * i + 2] | (sp[4 * i + 3] << 16)) * 0x3F80u;
@@ -263,9 +266,9 @@ __global__ __launch_bounds__(256) void rlif_forward_fused16_kernel(const float *
       *(uint32_t *)&sstage[t & 1][bl * RL_SP + nn[i]] =
           sp[4 * i] | (sp[4 * i + 1] << 8) | (sp[4 * i + 2] << 16) | (sp[4 * i + 3] << 24);
     }
-    f32x4 acc[2][2];                             // [tile][even / odd k step]
+    f32x4 acc[NTW][2];                             // [tile][even / odd k step]
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NTW; ++i)
 #pragma unroll
       for (int o = 0; o < 2; ++o) acc[i][o] = f32x4{0.f, 0.f, 0.f, 0.f};
     lds_barrier();
@@ -276,19 +279,19 @@ __global__ __launch_bounds__(256) void rlif_forward_fused16_kernel(const float *
 #pragma unroll
         for (int p = NP - 1; p >= 0; --p)
 #pragma unroll
-          for (int i = 0; i < 2; ++i)
+          for (int i = 0; i < NTW; ++i)
             acc[i][ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[p][i][ks], sf, acc[i][ks & 1], 0, 0, 0);
       }
     }
 #pragma unroll
-    for (int k = 0; k < 2; ++k) st_b128(rV, vro[k], t * row4, *(const u32x4 *)&vstage[t & 1][vlo[k]]);
+    for (int k = 0; k < NTW; ++k) st_b128(rV, vro[k], t * row4, *(const u32x4 *)&vstage[t & 1][vlo[k]]);
     st_b128(rS, sro, t * (row4 >> 2), *(const u32x4 *)&sstage[t & 1][slo]);
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
+    for (int e = 0; e < 4 * NTW; ++e)
       v[e] = beta[e] * v[e] + __uint_as_float(in[e >> 2][e & 3]) + (acc[e >> 2][0][e & 3] + acc[e >> 2][1][e & 3]) -
              (sp[e] ? theta : 0.f);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) in[i] = ld_b128(rI, vo4[i], min(t + PF, T - 1) * row4);
+    for (int i = 0; i < NTW; ++i) in[i] = ld_b128(rI, vo4[i], min(t + PF, T - 1) * row4);
   };
   int t = 0;
   for (; t + PF <= T; t += PF) {
@@ -449,9 +452,10 @@ __global__ __launch_bounds__(256) void rlif_reverse_fused_kernel(const float *__
 }
 
 // The reverse pass on tiles of 16 samples, as rlif_forward_fused16_kernel: a lane carries 8
-// neurons of one sample, wavefront w two row tiles of 16 neurons of R.
-template <int NP, int SURR>
-__global__ __launch_bounds__(256) void rlif_reverse_fused16_kernel(const float *__restrict__ dS,
+// neurons of one sample, wavefront w two row tiles of 16 neurons of R (NTW = 2), or 4 and one
+// on eight wavefronts (NTW = 1).
+template <int NP, int SURR, int NTW>
+__global__ __launch_bounds__(512 / NTW) void rlif_reverse_fused16_kernel(const float *__restrict__ dS,
                                                                    const float *__restrict__ V,
                                                                    uint32_t *__restrict__ dI,
                                                                    const uint16_t *__restrict__ QRb, int ldqr,
@@ -470,47 +474,47 @@ __global__ __launch_bounds__(256) void rlif_reverse_fused16_kernel(const float *
   const rsrc_t rdS = make_rsrc(dS, bytes), rV = make_rsrc(V, bytes), rdI = make_rsrc(dI, bytes);
   const rsrc_t rQ = make_rsrc(QRb, (unsigned)(NP * qr_plane * 2));
 
-  bf16x8 wf[NP][2][4];                          // R[32w + 16i + (lane & 15)][32 ks + 8 (lane / 16) .. +7]
+  bf16x8 wf[NP][NTW][4];                        // R[16 (NTW w + i) + (lane & 15)][32 ks + 8 (lane / 16) .. +7]
 #pragma unroll
   for (int p = 0; p < NP; ++p)
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NTW; ++i)
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
-        const int row = (int)(p * (qr_plane / ldqr)) + 32 * w + 16 * i + bl, k = 32 * ks + 8 * q4;
+        const int row = (int)(p * (qr_plane / ldqr)) + 16 * (NTW * w + i) + bl, k = 32 * ks + 8 * q4;
         wf[p][i][ks] = __builtin_bit_cast(bf16x8, ld_b128(rQ, k < ldqr ? (row * ldqr + k) * 2 : OOB, 0));
       }
 
-  int vo4[2], xo[2], nn[2];
+  int vo4[NTW], xo[NTW], nn[NTW];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    nn[i] = 32 * w + 16 * i + 4 * q4;
+  for (int i = 0; i < NTW; ++i) {
+    nn[i] = 16 * (NTW * w + i) + 4 * q4;
     vo4[i] = b < B && nn[i] < ld ? (b * ld + nn[i]) * 4 : OOB;
     xo[i] = bl * RL_PITCH + nn[i] * 2;
   }
-  float gv[8], beta[8], db[8];
+  float gv[4 * NTW], beta[4 * NTW], db[4 * NTW];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
+  for (int e = 0; e < 4 * NTW; ++e) {
     gv[e] = 0.f;                                 // g_T = 0
     db[e] = 0.f;                                 // sum over t of g_{t+1} V_t
     const int n = nn[e >> 2] + (e & 3);
     beta[e] = n < ld ? beta_v[n] : 0.f;
   }
-  u32x4 cds[PF][2], cv[PF][2];
+  u32x4 cds[PF][NTW], cv[PF][NTW];
 #pragma unroll
   for (int d = 0; d < PF; ++d)
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < NTW; ++i) {
       const int so = max(T - 1 - d, 0) * row4;
       cds[d][i] = ld_b128(rdS, vo4[i], so);
       cv[d][i] = ld_b128(rV, vo4[i], so);
     }
 
-  auto step = [&](u32x4 (&ds)[2], u32x4 (&vv)[2], int t) {
+  auto step = [&](u32x4 (&ds)[NTW], u32x4 (&vv)[NTW], int t) {
     char *x = (char *)xs[t & 1];
-    u32x4 o[2];
+    u32x4 o[NTW];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < NTW; ++i) {
       uint32_t pl[GP][4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -534,9 +538,9 @@ __global__ __launch_bounds__(256) void rlif_reverse_fused16_kernel(const float *
         *(u32x2 *)(x + q * 16 * RL_PITCH + xo[i]) = px;
       }
     }
-    f32x4 acc[2][2];                             // [tile][even / odd k step]
+    f32x4 acc[NTW][2];                             // [tile][even / odd k step]
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NTW; ++i)
 #pragma unroll
       for (int o2 = 0; o2 < 2; ++o2) acc[i][o2] = f32x4{0.f, 0.f, 0.f, 0.f};
     lds_barrier();
@@ -555,26 +559,26 @@ __global__ __launch_bounds__(256) void rlif_reverse_fused16_kernel(const float *
             const int q = sum - p;
             if (q >= 0 && q < GP && (NP == 1 || p + q < 3)) {
 #pragma unroll
-              for (int i = 0; i < 2; ++i)
+              for (int i = 0; i < NTW; ++i)
                 acc[i][ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[p][i][ks], gf[q], acc[i][ks & 1], 0, 0, 0);
             }
           }
       }
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) st_b128(rdI, vo4[i], t * row4, o[i]);
-    float sg[8];
+    for (int i = 0; i < NTW; ++i) st_b128(rdI, vo4[i], t * row4, o[i]);
+    float sg[4 * NTW];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) sg[e] = surr_rcp<SURR>(slope, __uint_as_float(vv[e >> 2][e & 3]) - theta);
+    for (int e = 0; e < 4 * NTW; ++e) sg[e] = surr_rcp<SURR>(slope, __uint_as_float(vv[e >> 2][e & 3]) - theta);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
+    for (int e = 0; e < 4 * NTW; ++e) {
       const float qq = __uint_as_float(ds[e >> 2][e & 3]) - theta * gv[e] + (acc[e >> 2][0][e & 3] + acc[e >> 2][1][e & 3]);
       const float vt = __uint_as_float(vv[e >> 2][e & 3]);
       db[e] += gv[e] * vt;
       gv[e] = beta[e] * gv[e] + sg[e] * qq;
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < NTW; ++i) {
       const int so = max(t - PF, 0) * row4;
       ds[i] = ld_b128(rdS, vo4[i], so);
       vv[i] = ld_b128(rV, vo4[i], so);
@@ -590,7 +594,7 @@ __global__ __launch_bounds__(256) void rlif_reverse_fused16_kernel(const float *
     if (t - d >= 0) step(cds[d], cv[d], t - d);
   if (db_part) {                                 // per sample; summed over the batch by the reduction launch
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NTW; ++i)
       if (b < B && nn[i] < ld)
         *(float4 *)(db_part + (size_t)b * ld + nn[i]) = make_float4(db[4 * i], db[4 * i + 1], db[4 * i + 2], db[4 * i + 3]);
   }
@@ -889,12 +893,14 @@ static hipError_t rlif_forward(hipStream_t st, bool fp32, int T, int B, int N, i
     const char *te = getenv("SNN_RLIF_TILE");           // 32: tiles of 32 samples also where 16 are possible
     if (stg && !(te && atoi(te) == 32)) {
       const dim3 grid16((B + 15) / 16);
-      if (fp32)
-        hipLaunchKernelGGL(rlif_forward_fused16_kernel<3>, grid16, block, 0, st, I, V, S, QRf, ldqr, qr_plane, T, B, N, ld,
-                           beta, theta);
-      else
-        hipLaunchKernelGGL(rlif_forward_fused16_kernel<1>, grid16, block, 0, st, I, V, S, QRf, ldqr, qr_plane, T, B, N, ld,
-                           beta, theta);
+      const char *we = getenv("SNN_RLIF_WAVES");        // 4: four wavefronts of two row tiles instead of eight of one
+      const bool w4 = we && atoi(we) == 4;
+#define SNN_RLF16(NP_, NTW_)                                                                                     \
+  hipLaunchKernelGGL((rlif_forward_fused16_kernel<NP_, NTW_>), grid16, dim3(512 / NTW_), 0, st, I, V, S, QRf, ldqr, \
+                     qr_plane, T, B, N, ld, beta, theta)
+      if (fp32) { if (w4) SNN_RLF16(3, 2); else SNN_RLF16(3, 1); }
+      else { if (w4) SNN_RLF16(1, 2); else SNN_RLF16(1, 1); }
+#undef SNN_RLF16
       return hipGetLastError();
     }
 #define SNN_RLF(NP_, STG_)                                                                                       \
@@ -934,14 +940,19 @@ static hipError_t rlif_reverse(hipStream_t st, bool fp32, int T, int B, int N, i
   if (ld <= 128) {
     const char *te = getenv("SNN_RLIF_TILE");           // 32: tiles of 32 samples instead of 16
     const bool t32 = te && atoi(te) == 32;
+    const char *we = getenv("SNN_RLIF_WAVES");          // 4: four wavefronts of two row tiles instead of eight of one
+    const bool w4 = we && atoi(we) == 4;
     dim3 grid(t32 ? (B + 31) / 32 : (B + 15) / 16), block(256);
 #define SNN_RLR(NP, SU)                                                                                         \
   do {                                                                                                          \
     if (t32)                                                                                                    \
       hipLaunchKernelGGL((rlif_reverse_fused_kernel<NP, SU>), grid, block, 0, st, dS, V, dI, QRb, ldqr, qr_plane, T, \
                          B, N, ld, beta, theta, slope, db_part);                                                \
+    else if (w4)                                                                                                \
+      hipLaunchKernelGGL((rlif_reverse_fused16_kernel<NP, SU, 2>), grid, block, 0, st, dS, V, dI, QRb, ldqr, qr_plane, \
+                         T, B, N, ld, beta, theta, slope, db_part);                                             \
     else                                                                                                        \
-      hipLaunchKernelGGL((rlif_reverse_fused16_kernel<NP, SU>), grid, block, 0, st, dS, V, dI, QRb, ldqr, qr_plane, \
+      hipLaunchKernelGGL((rlif_reverse_fused16_kernel<NP, SU, 1>), grid, dim3(512), 0, st, dS, V, dI, QRb, ldqr, qr_plane, \
                          T, B, N, ld, beta, theta, slope, db_part);                                             \
   } while (0)
     if (fp32) {

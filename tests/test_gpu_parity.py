@@ -480,12 +480,14 @@ def test_recurrent_forward_row_stores_same_bits(monkeypatch, precision):
 
 
 @pytest.mark.parametrize("precision", ["fp32", "bf16"])
-@pytest.mark.parametrize("tile", ["16", "32"])
-def test_recurrent_forward_sample_tiles(monkeypatch, precision, tile):
-    """Narrow recurrent layers with rows of a multiple of 16 neurons run on tiles of 16 samples
-    (default) or 32 (knob): full parity for both, layers of 96 and 128 neurons, a batch of 45 (tails
-    of 13 samples in either tiling), 37 steps."""
+@pytest.mark.parametrize("tile,waves", [("16", "8"), ("16", "4"), ("32", "4")])
+def test_recurrent_sample_tiles(monkeypatch, precision, tile, waves):
+    """Narrow recurrent layers run on tiles of 16 samples with eight wavefronts of 16 neurons
+    (default), with four of 32 neurons, or on tiles of 32 samples (knobs): full parity, forward and
+    reverse, for each; layers of 96 and 128 neurons, a batch of 45 (tails of 13 samples in either
+    tiling), 37 steps."""
     monkeypatch.setenv("SNN_RLIF_TILE", tile)
+    monkeypatch.setenv("SNN_RLIF_WAVES", waves)
     wl = workloads.Workload(name="rec_tiles", index=28, T=37, B=45, sizes=(60, 96, 128, 10), recurrent=(True, True),
                             beta=(0.9, 0.92, 0.95), theta=1.0, surrogate="superspike", slope=25.0,
                             precision=precision, rate_lo=0.05, rate_hi=0.2, rec_gain=1.0)
