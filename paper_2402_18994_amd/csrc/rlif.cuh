@@ -29,6 +29,11 @@ static hipError_t fill_zero(hipStream_t st, void *p, size_t bytes) {
 // neurons in four groups of four adjacent ones, so state, loads and stores are per-lane
 // 16-byte vectors and the LIF update needs no shuffles.  Wavefront w owns neurons
 // [32w, 32w+32).  Rows of I (or dS and V) are fetched PF steps ahead of their use.
+// These 32-sample kernels are followed by the ones in use by default, which tile the batch by
+// 16 samples (16x16x32 MFMAs, eight wavefronts of 16 neurons): the step is a dependent chain -
+// spikes or planes of g into LDS, barrier, fragments, products, update - and its length is the
+// number of values a lane carries: 16 here, 4 there (0.97 -> 0.43 us per forward step,
+// 1.64 -> 0.64 per reverse step at 128 neurons).
 constexpr int RL_PITCH = 272;                 // bytes per sample row of an exchange tile (128 bf16 + pad)
 
 // The sixteen-byte fragment of a weight plane [row][k] (k contiguous, pitch ldq) for MFMA step ks.
