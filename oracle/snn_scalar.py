@@ -1,7 +1,7 @@
 """Scalar brute-force version of the oracle (pure Python floats, nested loops).
 
 TEST INFRASTRUCTURE ONLY; for tiny networks.  It restates Eq. 1-2, the LI
-readout, the max-over-time cross-entropy and the reverse sweep one number at a
+readout, the cross-entropy (max over time or summed over time) and the reverse sweep one number at a
 time, with explicit indices, so that an indexing or transposition slip in the
 vectorised oracle shows up as a mismatch.  Unrounded arithmetic only.
 """
@@ -27,10 +27,13 @@ def _surr(kind, k, x):
     raise ValueError(kind)
 
 
-def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels):
+def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels, loss_kind="max"):
     """Forward + backward.  X[t][b][i] in {0,1}; W[l][i][j]; R[l][i][j] or None.
 
     beta[l] is a number or a list with one decay per neuron of layer l.
+    loss_kind: "max" (logit = largest readout value over time, gradient to the first step
+    that reaches it) or "integral" (logit = the readout trace summed over time, so every
+    step receives the logit's gradient).
 
     Returns a dict with V, S (per spiking layer, [t][b][n]), Y [t][b][c], loss,
     dW (per layer [i][j]), dR and dbeta (per layer, per neuron).
@@ -80,9 +83,17 @@ def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels):
                 Y[t][b][c] = y[c]
 
     # ---------------- loss ----------------
-    z = [[max(Y[t][b][c] for t in range(T)) for c in range(C)] for b in range(B)]
-    tstar = [[min(t for t in range(T) if Y[t][b][c] == z[b][c]) for c in range(C)]
-             for b in range(B)]
+    if loss_kind == "integral":
+        z = [[0.0] * C for _ in range(B)]
+        for b in range(B):
+            for c in range(C):
+                for t in range(T):
+                    z[b][c] += Y[t][b][c]
+        tstar = [[0] * C for _ in range(B)]
+    else:
+        z = [[max(Y[t][b][c] for t in range(T)) for c in range(C)] for b in range(B)]
+        tstar = [[min(t for t in range(T) if Y[t][b][c] == z[b][c]) for c in range(C)]
+                 for b in range(B)]
     loss = 0.0
     dz = [[0.0] * C for _ in range(B)]
     for b in range(B):
@@ -102,7 +113,8 @@ def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels):
         g = [[0.0] * sizes[l + 1] for l in range(H)]          # dL/dV_{t+1}
         for t in range(T - 1, -1, -1):
             for c in range(C):
-                hy[c] = bt(L - 1, c) * hy[c] + (dz[b][c] if tstar[b][c] == t else 0.0)
+                into_y = dz[b][c] if (loss_kind == "integral" or tstar[b][c] == t) else 0.0
+                hy[c] = bt(L - 1, c) * hy[c] + into_y
                 if t >= 1:
                     dbeta[L - 1][c] += hy[c] * Y[t - 1][b][c]
             below = S[H - 1][t][b] if H >= 1 else [float(x) for x in X[t][b]]

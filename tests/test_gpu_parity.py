@@ -97,7 +97,7 @@ def test_multi_tile_fp32_theta_not_one():
 
 @pytest.mark.parametrize("recurrent", [(False, False), (True, False)], ids=["ff", "rec"])
 def test_non_leaky_neurons(recurrent):
-    """beta = 1: integrate-and-fire hidden neurons (Section 2.2 names non-leaking neurons) and a
+    """beta = 1: integrate-and-fire hidden neurons (Section 2.1.2 names non-leaking neurons) and a
     pure integrator as readout; the end of the decay range the library accepts."""
     wl = workloads.Workload(name="if-neurons", index=15, T=33, B=20, sizes=(100, 96, 72, 10),
                             recurrent=recurrent, beta=(1.0, 1.0, 1.0), theta=1.0, surrogate="arctan",

@@ -41,7 +41,7 @@ def test_worked_example_constant_current():
 
 @pytest.mark.parametrize("c_num,c_den,theta_num", [(3, 8, 1), (7, 16, 1), (5, 8, 2), (9, 8, 1), (1, 4, 1)])
 def test_non_leaky_neuron_exact_rational(c_num, c_den, theta_num):
-    """beta = 1 (integrate and fire, Section 2.2's non-leaking neuron): under a constant current
+    """beta = 1 (integrate and fire, Section 2.1.2's non-leaking neuron): under a constant current
     the potential stays a multiple of 1/c_den, so Eq. 1-2 can be iterated in exact rational
     arithmetic; the currents are dyadic, so the float recursion has to agree exactly, ties at the
     threshold (strict inequality: no spike at V = theta, which c = 1/4 reaches) included.  The
@@ -485,6 +485,75 @@ def test_bf16_mode_close_to_fp32_mode():
     Wr = [O.rne_bf16(w) for w in inp.W]
     c = O.forward(net_of(wl, "none"), inp.X, Wr, inp.R, inp.labels)
     assert np.array_equal(b.V[0], c.V[0]) and b.loss == c.loss
+
+
+@pytest.mark.parametrize("recurrent", [(False, False), (True, True)])
+def test_bf16_mode_backward_is_the_unrounded_sweep_on_rounded_weights(recurrent):
+    """The bf16 product mode rounds W and R wherever they enter a product of the reverse sweep
+    too (dS = dI W^T, g R^T), and nothing else: its gradients are bit for bit those of the
+    unrounded sweep run on rne_bf16(W), rne_bf16(R), and they differ from the sweep on the
+    unrounded weights.  A reverse sweep that forgot the rounding in one of its products fails."""
+    rng = np.random.default_rng(61)
+    net, X, W, R, lab = tiny_net(rng, sizes=(9, 7, 6, 4), recurrent=recurrent, T=12, B=3,
+                                 surrogate="superspike", slope=25.0, gain=2.5, gemm_round="bf16")
+    W = [w.astype(np.float32).astype(np.float64) for w in W]          # fp32-valued masters
+    R = [None if r is None else r.astype(np.float32).astype(np.float64) for r in R]
+    betas = _random_betas(rng, net)
+    import dataclasses
+    plain = dataclasses.replace(net, gemm_round="none")
+    Wr = [O.rne_bf16(w) for w in W]
+    Rr = [None if r is None else O.rne_bf16(r) for r in R]
+    assert any(np.any(a != b) for a, b in zip(W, Wr))
+    tr_b = O.forward(net, X, W, R, lab, betas=betas)
+    gr_b = O.backward(net, X, W, R, lab, tr_b, betas=betas)
+    tr_r = O.forward(plain, X, Wr, Rr, lab, betas=betas)
+    gr_r = O.backward(plain, X, Wr, Rr, lab, tr_r, betas=betas)
+    assert tr_b.S[0].sum() > 0 and tr_b.S[1].sum() > 0
+    differs = False
+    # the same forward trace handed to the sweep on unrounded weights: only the products differ
+    gr_u = O.backward(plain, X, W, R, lab, tr_b, betas=betas)
+    for l in range(net.L):
+        assert np.array_equal(gr_b.dW[l], gr_r.dW[l])
+        assert np.array_equal(gr_b.dbeta[l], gr_r.dbeta[l])
+        differs |= bool(np.any(gr_b.dW[l] != gr_u.dW[l]))
+    for l in range(net.L - 1):
+        assert np.array_equal(gr_b.dI[l], gr_r.dI[l])
+        assert np.array_equal(gr_b.dS[l], gr_r.dS[l])
+        if R[l] is not None:
+            assert np.array_equal(gr_b.dR[l], gr_r.dR[l])
+            assert np.any(gr_b.dI[l] != gr_u.dI[l])                   # g R^T saw the rounded R
+    assert differs
+    assert np.any(gr_b.dS[0] != gr_u.dS[0])                           # dS = dI W^T saw the rounded W
+    assert np.any(gr_b.dS[1] != gr_u.dS[1])                           # and so did the readout's
+
+
+@pytest.mark.parametrize("recurrent", [(False, False), (True, True)])
+def test_integral_loss_equals_scalar_brute_force(recurrent):
+    """The integral cross-entropy, forward and reverse, one number at a time."""
+    rng = np.random.default_rng(62)
+    net, X, W, R, lab = tiny_net(rng, sizes=(6, 5, 4, 3), recurrent=recurrent, T=9, B=3,
+                                 surrogate="superspike", slope=25.0, gain=2.5, loss="integral")
+    betas = _random_betas(rng, net)
+    tr = O.forward(net, X, W, R, lab, betas=betas)
+    gr = O.backward(net, X, W, R, lab, tr, betas=betas)
+    assert tr.S[0].sum() > 0 and tr.S[1].sum() > 0
+    ref = snn_scalar.run(net.sizes, net.recurrent, [b.tolist() for b in betas], net.theta, "superspike", 25.0,
+                         X.tolist(), [w.tolist() for w in W],
+                         [None if r is None else r.tolist() for r in R], lab.tolist(), loss_kind="integral")
+    assert np.allclose(tr.z, np.array(ref["z"]), atol=1e-12)
+    assert tr.loss == pytest.approx(ref["loss"], abs=1e-12)
+    assert np.allclose(gr.dz, np.array(ref["dz"]), atol=1e-14)
+    for l in range(3):
+        assert np.allclose(gr.dW[l], np.array(ref["dW"][l]), atol=1e-12)
+        assert np.allclose(gr.dbeta[l], np.array(ref["dbeta"][l]), atol=1e-12)
+    for l in range(2):
+        if R[l] is not None:
+            assert np.allclose(gr.dR[l], np.array(ref["dR"][l]), atol=1e-12)
+    # and the scalar version's two losses differ on this network
+    ref_max = snn_scalar.run(net.sizes, net.recurrent, [b.tolist() for b in betas], net.theta, "superspike", 25.0,
+                             X.tolist(), [w.tolist() for w in W],
+                             [None if r is None else r.tolist() for r in R], lab.tolist())
+    assert abs(ref_max["loss"] - ref["loss"]) > 1e-3
 
 
 def test_workload_generator_statistics():
