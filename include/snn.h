@@ -21,6 +21,14 @@
  *     a non-zero status snn_last_error(ctx) describes it.
  *   - There is no CPU fallback: without a usable HIP device snn_init fails
  *     with SNN_ERR_HIP.
+ *   - Size limit (hard): the kernels address a tensor with 32-bit byte offsets, so
+ *     every [T][B][N_l] tensor must stay below 2 GiB at 4 bytes per element
+ *     (T * B * (N_l + 8) * 4 < 2^31 for every l); larger configurations are
+ *     refused by snn_workspace_bytes / snn_init with SNN_ERR_ARG, not tiled.
+ *     At most SNN_MAX_LAYERS weight matrices.
+ *   - The library reads no environment variable.  Which kernels a context uses
+ *     for a step is decided from its shapes; snn_set_option overrides that
+ *     choice per context (for tests and tuning).
  */
 #ifndef SNN_H_
 #define SNN_H_
@@ -33,6 +41,8 @@ extern "C" {
 #endif
 
 typedef struct snn_ctx snn_ctx;          /* opaque, host side */
+
+#define SNN_MAX_LAYERS 12                /* weight matrices per network (spiking layers + readout) */
 
 typedef enum {
   SNN_OK = 0,
@@ -153,15 +163,61 @@ typedef enum {
                                   kernel it times (launched only while this class is selected) */
   SNN_K_GRAD_REDUCE = 11,      /* the launch that adds the per-split partial sums of the weight
                                   gradients (SNN_K_WEIGHT_GRAD covers the products alone)      */
-  SNN_K_COUNT = 12
+  SNN_K_EVENT_PAIR = 12,       /* once per snn_backward: a bracket around nothing.  Its elapsed time is
+                                  what an event pair itself adds to the stream; a bracketed kernel's
+                                  elapsed time minus this is the kernel's own duration             */
+  SNN_K_COUNT = 13
 } snn_kernel_class;
 #define SNN_CALIBRATE_US 10
+
+/* Kernel-selection options of a context (snn_set_option).  Every choice computes the same step
+ * of the path; results differ only in the order floating-point sums are taken.  The defaults
+ * are the measured best; the tests use the options to reach each kernel on small shapes.
+ *   LAYER_FORWARD     feed-forward spiking layers of 64..LAYER_MAX_NEURONS padded neurons on
+ *                     rounded weights run product and scan as ONE launch (Eq. 1-2 with the
+ *                     preceding Linear layer): 0 never; 1 all but the last spiking layer;
+ *                     2 every such layer; 3 the last one also forms the readout's currents
+ *                     (128 padded neurons, at most 32 padded classes); 4 (default) and runs the
+ *                     readout scan, the loss and the readout's current gradients
+ *   LAYER_PAIR        1 (default): two consecutive one-launch layers of exactly 128 padded
+ *                     neurons share a launch; 0: one launch each
+ *   LAYER_REVERSE     1 (default): the reverse pass of a layer of 64..256 neurons below a layer of
+ *                     at most 128 columns runs as one launch (dS product, surrogate, scan); 0: off
+ *   TOP_SCANS         1 (default): the scans of a layer below at most 128 columns form the
+ *                     narrow products themselves (readout currents forward, dS reverse); 0: off
+ *   DEFER_REDUCE      1 (default): snn_backward leaves the per-split partial sums of the weight
+ *                     gradients to snn_sgd_step (or the first reader); 0: it adds them itself
+ *   LAYER_MIN_BATCH   smallest batch for the one-launch layers; 0 (default) = 1 for rasters of up
+ *                     to 256 steps, else 64
+ *   LAYER_NEURONS     neurons per workgroup of the one-launch forward layers: 128 (default) or 64
+ *   LAYER_MAX_NEURONS widest layer (and fan-in) that runs as one launch: 64..1024 (default 1024)
+ *   STREAM_MIN_MB     tensors of at least this many MiB count as streaming past the caches
+ *                     (non-temporal accesses, the streamed current product); default 128
+ *   STREAM_GEMM       1 (default): such current products use the streamed kernel; 0: the general one
+ *   TILE_ROWS         rows per workgroup tile of the general products: 0 (default) = by shape,
+ *                     or 32, 64, 128 */
+typedef enum {
+  SNN_OPT_LAYER_FORWARD = 0,
+  SNN_OPT_LAYER_PAIR = 1,
+  SNN_OPT_LAYER_REVERSE = 2,
+  SNN_OPT_TOP_SCANS = 3,
+  SNN_OPT_DEFER_REDUCE = 4,
+  SNN_OPT_LAYER_MIN_BATCH = 5,
+  SNN_OPT_LAYER_NEURONS = 6,
+  SNN_OPT_LAYER_MAX_NEURONS = 7,
+  SNN_OPT_STREAM_MIN_MB = 8,
+  SNN_OPT_STREAM_GEMM = 9,
+  SNN_OPT_TILE_ROWS = 10,
+  SNN_OPT_COUNT = 11
+} snn_option;
 
 /* Validate `cfg` and report the device bytes snn_init needs (a multiple of 256).
  * Pure host code.  Errors: SNN_ERR_NULL, SNN_ERR_ARG. */
 int32_t snn_workspace_bytes(const snn_config *cfg, size_t *bytes);
 
-/* Build a network.  `workspace_dev`: device memory, 256-byte aligned, at least
+/* Build a network: the stack Linear(no bias) -> LIF -> ... -> Linear(no bias) -> LI of the
+ * network listing in Section 2.1.2 (initial potentials zero, as its initial_state does),
+ * optionally with recurrent LIF layers.  `workspace_dev`: device memory, 256-byte aligned, at least
  * snn_workspace_bytes(cfg) bytes, owned by the caller, used exclusively by this context
  * until snn_destroy.  `W_host`: L host pointers, W_host[l] row-major [N_l][N_{l+1}]
  * (in, out), i.e. I = S W as in the paper's Linear layers without bias.  `R_host`: L-1
@@ -196,7 +252,10 @@ int32_t snn_forward(snn_ctx *ctx, const uint8_t *x_dev, const int32_t *labels_de
 int32_t snn_forward_packed(snn_ctx *ctx, const uint8_t *x_packed_dev, const int32_t *labels_dev,
                            float *loss_host);
 
-/* Reverse sweep: readout gradient, per spiking layer the reverse-time scan with the fused
+/* Reverse sweep: what reverse-mode differentiation of the unrolled forward loop computes
+ * (Section 2.1.3 takes the gradient of the loss with jax.value_and_grad), with the derivative
+ * of the Heaviside step replaced by the surrogate's backward function (Section 2.1.1): readout
+ * gradient, per spiking layer the reverse-time scan with the fused
  * surrogate derivative, the weight-gradient products dW^l = S^{l-1}^T dI^l (dR^l =
  * S^l^T dI^l) and the input-gradient products dS^{l-1} = dI^l W^l^T.  Needs a preceding
  * snn_forward on the current weights (else SNN_ERR_STATE).
@@ -205,14 +264,17 @@ int32_t snn_forward_packed(snn_ctx *ctx, const uint8_t *x_packed_dev, const int3
  * snn_run_step, which add them first): the gradients a caller sees are the same either way. */
 int32_t snn_backward(snn_ctx *ctx);
 
-/* W <- W - lr dW, R <- R - lr dR on the fp32 masters, then refresh the bfloat16 operand
+/* The optimiser update that the training-loop listing of Section 2.1.4 fuses with the gradient
+ * computation into one compiled step; the paper names no optimiser, this is plain SGD:
+ * W <- W - lr dW, R <- R - lr dR on the fp32 masters, then refresh the bfloat16 operand
  * copies the products read.  Needs a preceding snn_backward (else SNN_ERR_STATE). */
 int32_t snn_sgd_step(snn_ctx *ctx, float lr);
 
 /* Copy a tensor to / from dense host memory.  `bytes` must equal the tensor's dense size
  * (else SNN_ERR_SHAPE).  Both wait for the stream.  snn_set_tensor accepts the tensors
- * marked settable; setting a weight also refreshes its bfloat16 copies and invalidates a
- * previous forward.  snn_get_tensor reports a pending bad-label flag as SNN_ERR_ARG. */
+ * marked settable; setting a weight also refreshes its bfloat16 copies, and setting a weight or
+ * the decays invalidates a previous forward (snn_backward then needs a new one).
+ * snn_get_tensor reports a pending bad-label flag as SNN_ERR_ARG. */
 int32_t snn_get_tensor(snn_ctx *ctx, int32_t tensor, int32_t layer, void *dst_host, size_t bytes);
 int32_t snn_set_tensor(snn_ctx *ctx, int32_t tensor, int32_t layer, const void *src_host,
                        size_t bytes);
@@ -224,6 +286,12 @@ int32_t snn_set_tensor(snn_ctx *ctx, int32_t tensor, int32_t layer, const void *
  * call-order state. */
 int32_t snn_run_step(snn_ctx *ctx, int32_t step, int32_t layer, const uint8_t *x_dev,
                      const int32_t *labels_dev);
+
+/* Set / read a kernel-selection option (snn_option) of this context.  Takes effect from the
+ * next call on.  Errors: SNN_ERR_NULL; SNN_ERR_ARG for an unknown option or a value outside the
+ * range listed with the option (the option keeps its value). */
+int32_t snn_set_option(snn_ctx *ctx, int32_t option, int32_t value);
+int32_t snn_get_option(const snn_ctx *ctx, int32_t option, int32_t *value);
 
 /* Event timer.  snn_profile_select(ctx, k, layer) brackets every later launch of kernel
  * class k (layer = 0: all layers, else that layer only) with a pair of HIP events on the

@@ -25,7 +25,10 @@ STEPS = {"current_gemm": 0, "lif_forward": 1, "readout_forward": 2, "readout_rev
          "lif_reverse": 4, "weight_grad": 5, "input_grad": 6}
 KERNELS = {"none": -1, "current_gemm": 0, "lif_forward": 1, "rlif_forward": 2, "readout_forward": 3,
            "readout_reverse": 4, "lif_reverse": 5, "rlif_reverse": 6, "weight_grad": 7,
-           "input_grad": 8, "sgd": 9, "calibrate": 10, "grad_reduce": 11}
+           "input_grad": 8, "sgd": 9, "calibrate": 10, "grad_reduce": 11, "event_pair": 12}
+OPTIONS = {"layer_forward": 0, "layer_pair": 1, "layer_reverse": 2, "top_scans": 3, "defer_reduce": 4,
+           "layer_min_batch": 5, "layer_neurons": 6, "layer_max_neurons": 7, "stream_min_mb": 8,
+           "stream_gemm": 9, "tile_rows": 10}
 CALIBRATE_US = 10.0
 STATUS = {0: "SNN_OK", 1: "SNN_ERR_NULL", 2: "SNN_ERR_ARG", 3: "SNN_ERR_SHAPE", 4: "SNN_ERR_WORKSPACE",
           5: "SNN_ERR_STATE", 6: "SNN_ERR_HIP", 7: "SNN_ERR_UNSUPPORTED"}
@@ -70,6 +73,8 @@ def load_library():
     lib.snn_get_tensor.argtypes = [vp, i32, i32, vp, sz]
     lib.snn_set_tensor.argtypes = [vp, i32, i32, vp, sz]
     lib.snn_run_step.argtypes = [vp, i32, i32, vp, vp]
+    lib.snn_set_option.argtypes = [vp, i32, i32]
+    lib.snn_get_option.argtypes = [vp, i32, C.POINTER(i32)]
     lib.snn_profile_select.argtypes = [vp, i32, i32]
     lib.snn_profile_every.argtypes = [vp, i32]
     lib.snn_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -77,8 +82,8 @@ def load_library():
     lib.snn_last_error.argtypes = [vp]
     lib.snn_last_error.restype = C.c_char_p
     for name in ("snn_workspace_bytes", "snn_init", "snn_forward", "snn_forward_packed", "snn_backward", "snn_sgd_step",
-                 "snn_get_tensor", "snn_set_tensor", "snn_run_step", "snn_profile_select", "snn_profile_every",
-                 "snn_profile_read", "snn_destroy"):
+                 "snn_get_tensor", "snn_set_tensor", "snn_run_step", "snn_set_option", "snn_get_option",
+                 "snn_profile_select", "snn_profile_every", "snn_profile_read", "snn_destroy"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -116,7 +121,7 @@ class SNN:
 
     def __init__(self, T, B, sizes, recurrent, beta, theta, surrogate, slope, precision,
                  W: Sequence[np.ndarray], R: Optional[Sequence[Optional[np.ndarray]]] = None,
-                 device: str = "cuda:0", loss: str = "max", learn_beta: bool = False):
+                 device: str = "cuda:0", loss: str = "max", learn_beta: bool = False, options=None):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no HIP device: this library has no CPU path")
@@ -147,6 +152,8 @@ class SNN:
         self.ctx = ctx
         self._x = None
         self._labels = None
+        for name, value in (options or {}).items():
+            self.set_option(name, value)
 
     # ------------------------------------------------------------------ helpers
     def _chk(self, rc, ctx):
@@ -241,6 +248,14 @@ class SNN:
         lp = self._labels.data_ptr() if self._labels is not None else None
         self._chk(self.lib.snn_run_step(self.ctx, STEPS[step], layer, xp, lp), self.ctx)
 
+    def set_option(self, name: str, value: int):
+        self._chk(self.lib.snn_set_option(self.ctx, OPTIONS[name], int(value)), self.ctx)
+
+    def get_option(self, name: str) -> int:
+        v = C.c_int32(0)
+        self._chk(self.lib.snn_get_option(self.ctx, OPTIONS[name], C.byref(v)), None)
+        return v.value
+
     def profile_select(self, kernel: str, layer: int = 0):
         self._chk(self.lib.snn_profile_select(self.ctx, KERNELS[kernel], layer), self.ctx)
 
@@ -267,8 +282,8 @@ class SNN:
             pass
 
 
-def from_workload(wl, inputs, device: str = "cuda:0", learn_beta: bool = False) -> SNN:
+def from_workload(wl, inputs, device: str = "cuda:0", learn_beta: bool = False, options=None) -> SNN:
     """Build an SNN for a workloads.Workload and the weights of a workloads.Inputs."""
     return SNN(wl.T, wl.B, wl.sizes, wl.recurrent, wl.beta, wl.theta, wl.surrogate, wl.slope,
                wl.precision, inputs.W, inputs.R, device=device, loss=getattr(wl, "loss", "max"),
-               learn_beta=learn_beta)
+               learn_beta=learn_beta, options=options)

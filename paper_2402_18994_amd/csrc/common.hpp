@@ -62,7 +62,7 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void *base, unsigned bytes) {
 __device__ __forceinline__ uint32_t ld_b8(rsrc_t r, int voff, int soff) {
   return (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(r, voff, soff, 0);
 }
-// POLICY: 0 = default, NT = non-temporal (data streamed once; see scan.cuh).
+// POLICY: 0 = default, NT = non-temporal (data streamed once; see scan.hpp).
 constexpr int NT = 2;
 template <int POLICY = 0> __device__ __forceinline__ uint32_t ld_b32(rsrc_t r, int voff, int soff) {
   return __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, POLICY);

@@ -29,7 +29,7 @@
 // Epilogues: plain store (optionally one partial result per contraction split), or one step
 // of a recurrent LIF layer, forward or reverse, applied to the recurrent product.
 #pragma once
-#include "common.cuh"
+#include "common.hpp"
 
 namespace snn {
 

@@ -29,7 +29,7 @@
 // k nothing is masked on the P side: Q is zero-padded to a multiple of 64 along k, and
 // whatever bytes P yields there are reduced to 0/1 before they meet those zeros.
 #pragma once
-#include "gemm.cuh"
+#include "gemm.hpp"
 #include <type_traits>
 
 namespace snn {

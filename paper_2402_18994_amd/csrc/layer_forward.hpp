@@ -9,7 +9,7 @@
 // spike rows in that L2).  Per block of 128 steps:
 //   1. product: the 128 rows (t, b) of the spike tensor below times the rounded weights, on
 //      the streamed pipeline of the large current products (operands straight into LDS,
-//      four stages, see gemm_stream.cuh); the rows of the tile are the sample's time steps,
+//      four stages, see gemm_stream.hpp); the rows of the tile are the sample's time steps,
 //      so W passes through the workgroup once per block and the spikes once in all;
 //   2. the 128 x BN tile of currents goes to LDS (the stages are free by then);
 //   3. scan: BN / 64 wavefronts hold one neuron per lane and walk the 128 steps on LDS: read
@@ -36,7 +36,7 @@
 // workgroup runs steps 1 to 4 for the lower layer, waits until its spike stores are
 // acknowledged, and runs them again for the upper layer on the rows it has just written.
 #pragma once
-#include "gemm_stream.cuh"
+#include "gemm_stream.hpp"
 
 namespace snn {
 
@@ -80,15 +80,7 @@ struct LayerForwardArgs {
   uint32_t *dJ;            // [T*B][ldj] hi/lo words
   const float *beta_r;     // [ldj] decays of the readout
   int C;                   // classes
-#ifdef SNN_LAYER_PROBE
-  unsigned long long *probe;   // [B][2][8] device clock at the phase boundaries of the first block, per layer of the launch; [B][1][7]: the end (development builds only)
-#endif
 };
-#ifdef SNN_LAYER_PROBE
-#define SNN_PROBE(i) do { if (tid == 0 && t0 == 0 && n0 == 0) a.probe[b * 16 + li * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define SNN_PROBE(i) do { } while (0)
-#endif
 
 // READOUT: 0 none; 1 the launch also forms the readout's currents J; 2 and the LI scan, the
 // maximum over time, the loss and dJ; 3 the same with the integral loss.
@@ -158,7 +150,6 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
       const int row = Tile::q_row(wave, lane, q);
       qv[q] = ((n0 + row) * op.ldq + Tile::q_chunk(row, lane) * 8) * 2;
     }
-    SNN_PROBE(0);
     // 1. product
     int pv[PI];
     {
@@ -167,7 +158,6 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
     }
     f32x16 acc[TM][TN];
     Tile::run(lds, rp, rq, pv, qv, nk, wave, lane, acc);
-    SNN_PROBE(1);
 
     // 2. The MFMAs take Q as their first operand, so a tile comes out transposed: the lane
     // holds time row (lane & 31) and register r neuron 8*(r/4) + 4*(lane/32) + (r%4).
@@ -186,7 +176,6 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
           *(u32x4 *)(lds + row * CP + col * 4) = x;
         }
     __syncthreads();
-    SNN_PROBE(2);
 
     // 3. scan (steps past T run on zero currents; nothing of them is stored, and v is not
     // used after the last block)
@@ -218,7 +207,6 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
       }
     }
     __syncthreads();
-    SNN_PROBE(3);
 
     // 4. store.  V: BN/4 lanes x 16 bytes per row.  S: BN/16 lanes x 16 neurons per row.
     {
@@ -329,12 +317,10 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
         }
       }
     }
-    SNN_PROBE(4);
     // A layer above reads the spikes of this block back from memory: they have reached the L2
     // (nothing of them is in this compute unit's L1) once the stores are acknowledged.
     if (!last) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();                                  // the next product's stages overwrite the tile
-    SNN_PROBE(5);
    });
   }
 
@@ -404,9 +390,6 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
       }
     }
   }
-#ifdef SNN_LAYER_PROBE
-  if (tid == 0 && n0 == 0) a.probe[b * 16 + 15] = wall_clock64();
-#endif
 }
 
 }  // namespace snn

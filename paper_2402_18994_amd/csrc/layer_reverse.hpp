@@ -24,7 +24,7 @@
 // g (and the decay gradient's partial sum) stay in the scanning lanes' registers from block
 // to block.  Rows past T read as zero: c2 = 0 there and g, zero at the start, stays zero.
 #pragma once
-#include "scan.cuh"
+#include "scan.hpp"
 #include <type_traits>
 
 namespace snn {
@@ -42,15 +42,7 @@ struct LayerReverseArgs {
   float *db_part;          // [B][ld] per-sample parts of the decay gradient, or NULL
   int T, B, ld;            // ld: a multiple of the workgroup's neurons
   int nt_store;            // dI streams past the caches
-#ifdef SNN_LAYER_PROBE
-  unsigned long long *probe;   // [B][2][8] device clock at the phase boundaries of the first two blocks (development builds only)
-#endif
 };
-#ifdef SNN_LAYER_PROBE
-#define SNN_RPROBE(i) do { if (tid == 0 && n0 == 0 && blk < 2) a.probe[b * 16 + blk * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define SNN_RPROBE(i) do { } while (0)
-#endif
 
 template <int KS, int SURR, int BN>
 __global__ __launch_bounds__(256, BN == 64 ? 2 : 1) void lif_layer_reverse_kernel(const LayerReverseArgs a) {
@@ -125,11 +117,9 @@ __global__ __launch_bounds__(256, BN == 64 ? 2 : 1) void lif_layer_reverse_kerne
   float g = 0.f, db = 0.f;                            // state of neuron n0 + tid (wavefronts 0 and 1)
 
   for (int blk = 0; t0 >= 0; t0 -= BM, ++blk) {
-    SNN_RPROBE(0);
     fill();
     __syncthreads();
     fetch(t0 - BM);
-    SNN_RPROBE(1);
 
     // 2. dS^T tile: rows = neurons, columns = steps; the lane holds step 32 wm + (lane & 31)
     // and register r neuron 8 (r / 4) + 4 h + (r % 4) of its 32-neuron tile.
@@ -160,7 +150,6 @@ __global__ __launch_bounds__(256, BN == 64 ? 2 : 1) void lif_layer_reverse_kerne
         for (int j = 0; j < NJ; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j][kk], hi[kk], acc[j], 0, 0, 0);
     }
     __syncthreads();                                  // every wavefront has read the dX tile: C1 takes its place
-    SNN_RPROBE(2);
 
     // 3. coefficients
 #pragma unroll
@@ -181,7 +170,6 @@ __global__ __launch_bounds__(256, BN == 64 ? 2 : 1) void lif_layer_reverse_kerne
         *(f32x4 *)(C2 + t * CP + n * 4) = c2;
       }
     __syncthreads();
-    SNN_RPROBE(3);
 
     // 4. scan, steps t0 + 63 down to t0: dI_t = g, then g <- c1 g + c2 (and db += g V_t)
     if (wave < BN / 64) {
@@ -218,7 +206,6 @@ __global__ __launch_bounds__(256, BN == 64 ? 2 : 1) void lif_layer_reverse_kerne
       if (a.db_part) scan(std::true_type()); else scan(std::false_type());
     }
     __syncthreads();
-    SNN_RPROBE(4);
 
     // 5. store: BN/4 lanes x 16 bytes per row
 #pragma unroll
@@ -231,7 +218,6 @@ __global__ __launch_bounds__(256, BN == 64 ? 2 : 1) void lif_layer_reverse_kerne
       if (a.nt_store) __builtin_amdgcn_raw_buffer_store_b128(w, rdI, vo, 0, NT);
       else __builtin_amdgcn_raw_buffer_store_b128(w, rdI, vo, 0, 0);
     }
-    SNN_RPROBE(5);
     // The next block's fill writes V and dX, which takes the place of C1 and, when its rows are
     // longer than a coefficient row, of part of C2, which this store phase is still reading.
     if (XP > CP) __syncthreads();

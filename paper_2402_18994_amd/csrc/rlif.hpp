@@ -6,8 +6,8 @@
 // applies the LIF update (forward) or the surrogate-gradient recursion (reverse); stream
 // order is the inter-step barrier.
 #pragma once
-#include "gemm.cuh"
-#include "scan.cuh"
+#include "gemm.hpp"
+#include "scan.hpp"
 
 namespace snn {
 
@@ -43,14 +43,12 @@ __device__ __forceinline__ bf16x8 rl_weight_frag(rsrc_t r, int row, int ldq, int
   return __builtin_bit_cast(bf16x8, v);
 }
 
-// STG (rows of a multiple of 16 neurons): V_t and S_t leave through LDS.  In the accumulator
-// layout a store instruction touches 32 sample rows with 32 bytes each, and the eight of a step
-// cost 0.65 of its 1.40 us; staged, the four wavefronts store whole rows (512 bytes of V per
-// half wavefront, 128 bytes of S per eight lanes), five instructions each.  The stage is written
-// before the step's barrier, next to the spike tile, and double-buffered like it.
+// Row pitches of the LDS stage through which the 16-sample kernel below stores V_t and S_t as
+// whole rows.  (This 32-sample kernel stores straight from the accumulator layout, 32 sample rows
+// of 32 bytes per instruction, and serves rows that are no multiple of 16 neurons.)
 constexpr int RL_VP = 132;                    // floats per sample row of the V stage (128 + pad)
 constexpr int RL_SP = 144;                    // bytes per sample row of the S stage (128 + pad)
-template <int NP, bool STG>   // NP weight planes: 1 (bfloat16 weights) or 3 (fp32 as hi + mid + lo)
+template <int NP>   // NP weight planes: 1 (bfloat16 weights) or 3 (fp32 as hi + mid + lo)
 __global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__restrict__ I, float *__restrict__ V,
                                                                  uint8_t *__restrict__ S,
                                                                  const uint16_t *__restrict__ QRf, int ldqr,
@@ -58,27 +56,11 @@ __global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__
                                                                  const float *__restrict__ beta_v, float theta) {
   constexpr int PF = 4;
   __shared__ __align__(16) char xs[2][32 * RL_PITCH];
-  __shared__ __align__(16) float vstage[STG ? 2 : 1][STG ? 32 * RL_VP : 4];
-  __shared__ __align__(16) uint8_t sstage[STG ? 2 : 1][STG ? 32 * RL_SP : 16];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int b = blockIdx.x * 32 + (lane & 31);
   const int row4 = B * ld * 4;
   const unsigned bytes = (unsigned)T * B * ld * 4u;
   const rsrc_t rI = make_rsrc(I, bytes), rV = make_rsrc(V, bytes), rS = make_rsrc(S, bytes / 4);
-  // staged stores: V instruction k of wavefront w takes sample rows 8k + 2w + lane/32, four
-  // neurons per lane; the S instruction rows 8w + lane/8, sixteen neurons per lane
-  int vro[4], vlo[4], sro, slo;
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const int r = 8 * k + 2 * w + (lane >> 5), c = (lane & 31) * 4, bb = blockIdx.x * 32 + r;
-    vro[k] = bb < B && c < ld ? (bb * ld + c) * 4 : OOB;
-    vlo[k] = r * RL_VP + c;
-  }
-  {
-    const int r = 8 * w + (lane >> 3), c = (lane & 7) * 16, bb = blockIdx.x * 32 + r;
-    sro = bb < B && c < ld ? bb * ld + c : OOB;
-    slo = r * RL_SP + c;
-  }
   const rsrc_t rQ = make_rsrc(QRf, (unsigned)(NP * qr_plane * 2));
 
   bf16x8 wf[NP][8];                             // R^T[32w + (lane&31)][:], all planes, all k steps
@@ -127,16 +109,6 @@ __global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__
       sx[1] = (sp[4 * g + 2] | (sp[4 * g + 3] << 16)) * 0x3F80u;
       *(u32x2 *)(x + xo[g]) = sx;
     }
-    if (STG) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n = 32 * w + 8 * g + 4 * (lane >> 5);
-        f32x4 vv = {v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
-        *(f32x4 *)&vstage[t & 1][(lane & 31) * RL_VP + n] = vv;
-        *(uint32_t *)&sstage[t & 1][(lane & 31) * RL_SP + n] =
-            sp[4 * g] | (sp[4 * g + 1] << 8) | (sp[4 * g + 2] << 16) | (sp[4 * g + 3] << 24);
-      }
-    }
     f32x16 acc, acc1;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = acc1[r] = 0.f;
@@ -152,19 +124,13 @@ __global__ __launch_bounds__(256) void rlif_forward_fused_kernel(const float *__
         }
       }
     }
-    if (STG) {
 #pragma unroll
-      for (int k = 0; k < 4; ++k) st_b128(rV, vro[k], t * row4, *(const u32x4 *)&vstage[t & 1][vlo[k]]);
-      st_b128(rS, sro, t * (row4 >> 2), *(const u32x4 *)&sstage[t & 1][slo]);
-    } else {
+    for (int g = 0; g < 4; ++g) {
+      u32x4 vv;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        u32x4 vv;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) vv[i] = __float_as_uint(v[4 * g + i]);
-        st_b128(rV, vo4[g], t * row4, vv);
-        st_b32(rS, vo1[g], t * (row4 >> 2), sp[4 * g] | (sp[4 * g + 1] << 8) | (sp[4 * g + 2] << 16) | (sp[4 * g + 3] << 24));
-      }
+      for (int i = 0; i < 4; ++i) vv[i] = __float_as_uint(v[4 * g + i]);
+      st_b128(rV, vo4[g], t * row4, vv);
+      st_b32(rS, vo1[g], t * (row4 >> 2), sp[4 * g] | (sp[4 * g + 1] << 8) | (sp[4 * g + 2] << 16) | (sp[4 * g + 3] << 24));
     }
     // accumulator register r: neuron 32w + 8*(r/4) + 4*(lane/32) + r%4, i.e. group r/4, element r%4
 #pragma unroll
@@ -308,154 +274,10 @@ __global__ __launch_bounds__(512 / NTW) void rlif_forward_fused16_kernel(const f
     if (t + d < T) step(cur[d], t + d);
 }
 
-// Reverse pass of the same layers: g <- beta g + surr(V_t - theta) (dS_t - theta g + g R^T), dI_t = g
+// Reverse pass of these layers: g <- beta g + surr(V_t - theta) (dS_t - theta g + g R^T), dI_t = g
 // before the update.  g is real-valued, so it enters the product as bfloat16 planes (hi + lo
 // with bfloat16 weights, hi + mid + lo with fp32 weights); (g R^T)^T = R g^T with R[from][to]
 // as the row operand.
-template <int NP, int SURR>
-__global__ __launch_bounds__(256) void rlif_reverse_fused_kernel(const float *__restrict__ dS,
-                                                                 const float *__restrict__ V,
-                                                                 uint32_t *__restrict__ dI,
-                                                                 const uint16_t *__restrict__ QRb, int ldqr,
-                                                                 long long qr_plane, int T, int B, int N, int ld,
-                                                                 const float *__restrict__ beta_v, float theta, float slope,
-                                                                 float *__restrict__ db_part) {
-  constexpr int PF = 2;
-  constexpr int GP = NP == 1 ? 2 : 3;           // planes of g
-  constexpr bool HL = NP == 1;                  // dI is stored in hi/lo form with bfloat16 weights
-  __shared__ __align__(16) char xs[2][GP][32 * RL_PITCH];
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int b = blockIdx.x * 32 + (lane & 31);
-  const int row4 = B * ld * 4;
-  const unsigned bytes = (unsigned)T * B * ld * 4u;
-  const rsrc_t rdS = make_rsrc(dS, bytes), rV = make_rsrc(V, bytes), rdI = make_rsrc(dI, bytes);
-  const rsrc_t rQ = make_rsrc(QRb, (unsigned)(NP * qr_plane * 2));
-
-  bf16x8 wf[NP][8];                             // R[32w + (lane&31)][:]
-#pragma unroll
-  for (int p = 0; p < NP; ++p)
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-      wf[p][ks] = rl_weight_frag(rQ, (int)(p * (qr_plane / ldqr)) + 32 * w + (lane & 31), ldqr, ks, lane);
-
-  int vo4[4], xo[4];
-#pragma unroll
-  for (int g = 0; g < 4; ++g) {
-    const int n = 32 * w + 8 * g + 4 * (lane >> 5);
-    const bool ok = b < B && n < ld;
-    vo4[g] = ok ? (b * ld + n) * 4 : OOB;
-    xo[g] = (lane & 31) * RL_PITCH + n * 2;
-  }
-  float gv[16], beta[16], db[16];
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    gv[i] = 0.f;                                 // g_T = 0
-    db[i] = 0.f;                                 // sum over t of g_{t+1} V_t
-    const int n = 32 * w + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-    beta[i] = n < ld ? beta_v[n] : 0.f;
-  }
-  u32x4 cds[PF][4], cv[PF][4];
-#pragma unroll
-  for (int d = 0; d < PF; ++d)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int so = max(T - 1 - d, 0) * row4;
-      cds[d][g] = ld_b128(rdS, vo4[g], so);
-      cv[d][g] = ld_b128(rV, vo4[g], so);
-    }
-
-  // One step, ordered like the forward one: the planes of g into LDS, barrier, fragment reads
-  // and MFMAs (two accumulators), and under the MFMAs what does not need the product: the
-  // store of dI_t and the surrogate (with the hardware reciprocal; sixteen IEEE divisions per
-  // lane and step were a third of the step).
-  auto step = [&](u32x4 (&ds)[4], u32x4 (&vv)[4], int t) {
-    char *x = (char *)xs[t & 1];
-    u32x4 o[4];
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      uint32_t pl[GP][4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float gg = gv[4 * g + i];
-        if (HL) {
-          const uint32_t hl = pack_hl(gg);
-          o[g][i] = hl;
-          pl[0][i] = hl & 0xFFFFu;
-          pl[1][i] = hl >> 16;
-        } else {
-          o[g][i] = __float_as_uint(gg);
-#pragma unroll
-          for (int q = 0; q < GP; ++q) pl[q][i] = bf16_piece(gg, q);
-        }
-      }
-#pragma unroll
-      for (int q = 0; q < GP; ++q) {
-        u32x2 px;
-        px[0] = pl[q][0] | (pl[q][1] << 16);
-        px[1] = pl[q][2] | (pl[q][3] << 16);
-        *(u32x2 *)(x + q * 32 * RL_PITCH + xo[g]) = px;
-      }
-    }
-    f32x16 acc, acc1;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = acc1[r] = 0.f;
-    lds_barrier();
-    if (t > 0) {                                 // the g leaving step 0 is not used
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        bf16x8 gf[GP];
-#pragma unroll
-        for (int q = 0; q < GP; ++q)
-          gf[q] = *(const bf16x8 *)(x + q * 32 * RL_PITCH + (lane & 31) * RL_PITCH + (16 * ks + 8 * (lane >> 5)) * 2);
-        // smallest products first
-#pragma unroll
-        for (int sum = NP + GP - 2; sum >= 0; --sum)
-#pragma unroll
-          for (int p = 0; p < NP; ++p) {
-            const int q = sum - p;
-            if (q >= 0 && q < GP && (NP == 1 || p + q < 3)) {
-              if (ks & 1) acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[p][ks], gf[q], acc1, 0, 0, 0);
-              else acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[p][ks], gf[q], acc, 0, 0, 0);
-            }
-          }
-      }
-    }
-#pragma unroll
-    for (int g = 0; g < 4; ++g) st_b128(rdI, vo4[g], t * row4, o[g]);
-    float sg[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) sg[i] = surr_rcp<SURR>(slope, __uint_as_float(vv[i >> 2][i & 3]) - theta);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float q = __uint_as_float(ds[i >> 2][i & 3]) - theta * gv[i] + (acc[i] + acc1[i]);
-      const float vt = __uint_as_float(vv[i >> 2][i & 3]);
-      db[i] += gv[i] * vt;
-      gv[i] = beta[i] * gv[i] + sg[i] * q;
-    }
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int so = max(t - PF, 0) * row4;
-      ds[g] = ld_b128(rdS, vo4[g], so);
-      vv[g] = ld_b128(rV, vo4[g], so);
-    }
-  };
-  int t = T - 1;
-  for (; t - PF + 1 >= 0; t -= PF) {
-#pragma unroll
-    for (int d = 0; d < PF; ++d) step(cds[d], cv[d], t - d);
-  }
-#pragma unroll
-  for (int d = 0; d < PF; ++d)
-    if (t - d >= 0) step(cds[d], cv[d], t - d);
-  if (db_part) {                                 // per sample; summed over the batch by the reduction launch
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int n = 32 * w + 8 * g + 4 * (lane >> 5);
-      if (b < B && n < ld) *(float4 *)(db_part + (size_t)b * ld + n) = make_float4(db[4 * g], db[4 * g + 1], db[4 * g + 2], db[4 * g + 3]);
-    }
-  }
-}
-
 // The reverse pass on tiles of 16 samples, as rlif_forward_fused16_kernel: a lane carries 8
 // neurons of one sample, wavefront w two row tiles of 16 neurons of R (NTW = 2), or 4 and one
 // on eight wavefronts (NTW = 1).
@@ -892,28 +714,26 @@ static hipError_t rlif_forward(hipStream_t st, bool fp32, int T, int B, int N, i
                                uint8_t *S, const uint16_t *QRf, int ldqr, long long qr_plane, const float *beta,
                                float theta) {
   if (ld <= 128) {                              // the whole time loop in one launch
-    dim3 grid((B + 31) / 32), block(256);
-    const char *se = getenv("SNN_RLIF_STAGE");          // test knob: 0 = stores straight from the accumulator layout
-    const bool stg = ld % 16 == 0 && !(se && atoi(se) == 0);
-    const char *te = getenv("SNN_RLIF_TILE");           // 32: tiles of 32 samples also where 16 are possible
-    if (stg && !(te && atoi(te) == 32)) {
+    // Rows of a multiple of 16 neurons: tiles of 16 samples, eight wavefronts of 16 neurons, V_t
+    // and S_t stored as whole rows.  Other widths: tiles of 32 samples, stores straight from the
+    // accumulator layout.
+    if (ld % 16 == 0) {
       const dim3 grid16((B + 15) / 16);
-      const char *we = getenv("SNN_RLIF_WAVES");        // 4: four wavefronts of two row tiles instead of eight of one
-      const bool w4 = we && atoi(we) == 4;
-#define SNN_RLF16(NP_, NTW_)                                                                                     \
-  hipLaunchKernelGGL((rlif_forward_fused16_kernel<NP_, NTW_>), grid16, dim3(512 / NTW_), 0, st, I, V, S, QRf, ldqr, \
-                     qr_plane, T, B, N, ld, beta, theta)
-      if (fp32) { if (w4) SNN_RLF16(3, 2); else SNN_RLF16(3, 1); }
-      else { if (w4) SNN_RLF16(1, 2); else SNN_RLF16(1, 1); }
-#undef SNN_RLF16
+      if (fp32)
+        hipLaunchKernelGGL((rlif_forward_fused16_kernel<3, 1>), grid16, dim3(512), 0, st, I, V, S, QRf, ldqr, qr_plane, T,
+                           B, N, ld, beta, theta);
+      else
+        hipLaunchKernelGGL((rlif_forward_fused16_kernel<1, 1>), grid16, dim3(512), 0, st, I, V, S, QRf, ldqr, qr_plane, T,
+                           B, N, ld, beta, theta);
       return hipGetLastError();
     }
-#define SNN_RLF(NP_, STG_)                                                                                       \
-  hipLaunchKernelGGL((rlif_forward_fused_kernel<NP_, STG_>), grid, block, 0, st, I, V, S, QRf, ldqr, qr_plane, T, B, \
-                     N, ld, beta, theta)
-    if (fp32) { if (stg) SNN_RLF(3, true); else SNN_RLF(3, false); }
-    else { if (stg) SNN_RLF(1, true); else SNN_RLF(1, false); }
-#undef SNN_RLF
+    const dim3 grid((B + 31) / 32), block(256);
+    if (fp32)
+      hipLaunchKernelGGL((rlif_forward_fused_kernel<3>), grid, block, 0, st, I, V, S, QRf, ldqr, qr_plane, T, B, N,
+                         ld, beta, theta);
+    else
+      hipLaunchKernelGGL((rlif_forward_fused_kernel<1>), grid, block, 0, st, I, V, S, QRf, ldqr, qr_plane, T, B, N,
+                         ld, beta, theta);
     return hipGetLastError();
   }
   const size_t stride = (size_t)B * ld;
@@ -943,23 +763,10 @@ static hipError_t rlif_reverse(hipStream_t st, bool fp32, int T, int B, int N, i
                                uint32_t *dI, float *g0, float *g1, const uint16_t *QRb, int ldqr,
                                long long qr_plane, const float *beta, float theta, int surrogate, float slope, float *db_part) {
   if (ld <= 128) {
-    const char *te = getenv("SNN_RLIF_TILE");           // 32: tiles of 32 samples instead of 16
-    const bool t32 = te && atoi(te) == 32;
-    const char *we = getenv("SNN_RLIF_WAVES");          // 4: four wavefronts of two row tiles instead of eight of one
-    const bool w4 = we && atoi(we) == 4;
-    dim3 grid(t32 ? (B + 31) / 32 : (B + 15) / 16), block(256);
+    const dim3 grid((B + 15) / 16);
 #define SNN_RLR(NP, SU)                                                                                         \
-  do {                                                                                                          \
-    if (t32)                                                                                                    \
-      hipLaunchKernelGGL((rlif_reverse_fused_kernel<NP, SU>), grid, block, 0, st, dS, V, dI, QRb, ldqr, qr_plane, T, \
-                         B, N, ld, beta, theta, slope, db_part);                                                \
-    else if (w4)                                                                                                \
-      hipLaunchKernelGGL((rlif_reverse_fused16_kernel<NP, SU, 2>), grid, block, 0, st, dS, V, dI, QRb, ldqr, qr_plane, \
-                         T, B, N, ld, beta, theta, slope, db_part);                                             \
-    else                                                                                                        \
-      hipLaunchKernelGGL((rlif_reverse_fused16_kernel<NP, SU, 1>), grid, dim3(512), 0, st, dS, V, dI, QRb, ldqr, qr_plane, \
-                         T, B, N, ld, beta, theta, slope, db_part);                                             \
-  } while (0)
+  hipLaunchKernelGGL((rlif_reverse_fused16_kernel<NP, SU, 1>), grid, dim3(512), 0, st, dS, V, dI, QRb, ldqr, qr_plane, \
+                     T, B, N, ld, beta, theta, slope, db_part)
     if (fp32) {
       switch (surrogate) { case 0: SNN_RLR(3, 0); break; case 1: SNN_RLR(3, 1); break;
                            case 2: SNN_RLR(3, 2); break; case 3: SNN_RLR(3, 3); break;

@@ -5,7 +5,7 @@
 // rows.  Loads do not depend on the recurrence, so a block of U steps is fetched while the
 // previous block is being integrated.
 #pragma once
-#include "common.cuh"
+#include "common.hpp"
 
 namespace snn {
 
@@ -750,13 +750,15 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *__restrict__ p
 // of one job; its four wavefronts each add every fourth split (16-byte loads, eight in
 // flight) and the four sums are combined through LDS in a fixed order, so the result does
 // not depend on timing.  Tails that are not a multiple of four floats are done one by one.
+// (Up to three reductions per layer: dW, dR and, with trained decays, the per-sample parts of dbeta.)
+#define SNN_MAX_REDUCE_JOBS 36
 struct ReduceJobs {
   int njobs;
-  int first_block[SNN_MAX_JOBS + 1];
-  const float *part[SNN_MAX_JOBS];
-  float *out[SNN_MAX_JOBS];
-  int splits[SNN_MAX_JOBS];
-  long long n[SNN_MAX_JOBS];          // elements per matrix = stride between splits
+  int first_block[SNN_MAX_REDUCE_JOBS + 1];
+  const float *part[SNN_MAX_REDUCE_JOBS];
+  float *out[SNN_MAX_REDUCE_JOBS];
+  int splits[SNN_MAX_REDUCE_JOBS];
+  long long n[SNN_MAX_REDUCE_JOBS];   // elements per matrix = stride between splits
 };
 
 // Mean of the per-sample losses in a fixed order, by one workgroup of 256 threads.

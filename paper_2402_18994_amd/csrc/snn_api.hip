@@ -12,12 +12,12 @@
 #include <string>
 #include <vector>
 
-#include "gemm.cuh"
-#include "gemm_stream.cuh"
-#include "layer_forward.cuh"
-#include "scan.cuh"
-#include "layer_reverse.cuh"
-#include "rlif.cuh"
+#include "gemm.hpp"
+#include "gemm_stream.hpp"
+#include "layer_forward.hpp"
+#include "scan.hpp"
+#include "layer_reverse.hpp"
+#include "rlif.hpp"
 
 using namespace snn;
 
@@ -90,6 +90,7 @@ struct snn_ctx {
   const int32_t *labels_dev = nullptr;
   ReduceJobs pending;             // partial sums of the last backward pass that have not been added yet
   bool reduce_pending = false;
+  int opt[SNN_OPT_COUNT] = {4, 1, 1, 1, 1, 0, 128, 1024, 128, 1, 0};   // snn_option values, in the enum's order
   std::string err;
   Prof prof;
 };
@@ -120,9 +121,9 @@ int validate(const snn_config *cfg) {
   if (!cfg) return fail(nullptr, SNN_ERR_NULL, "config is NULL");
   if (!cfg->sizes || !cfg->beta) return fail(nullptr, SNN_ERR_NULL, "config.sizes / config.beta is NULL");
   if (cfg->T <= 0 || cfg->B <= 0) return fail(nullptr, SNN_ERR_ARG, "T and B must be positive");
-  if (cfg->n_layers < 2 || cfg->n_layers > SNN_MAX_JOBS / 2)
+  if (cfg->n_layers < 2 || cfg->n_layers > SNN_MAX_LAYERS)
     return fail(nullptr, SNN_ERR_ARG, "n_layers must be in [2, %d] (at least one spiking layer and the readout)",
-                SNN_MAX_JOBS / 2);
+                SNN_MAX_LAYERS);
   for (int i = 0; i <= cfg->n_layers; ++i)
     if (cfg->sizes[i] <= 0 || cfg->sizes[i] > (1 << 20)) return fail(nullptr, SNN_ERR_ARG, "sizes[%d] out of range", i);
   for (int i = 0; i < cfg->n_layers; ++i)
@@ -155,11 +156,7 @@ int validate(const snn_config *cfg) {
 //     (2048 wide: 56 MB per split) more splits cost more than they gain (64 splits: 10.2 ms
 //     against 3.3 ms with 8), and 16 splits never beat 8 at 1024 wide.
 int choose_splits(long long M, int tiles, long long weights, long long row_bytes, long long *per_split) {
-  static const long long target = [] {
-    const char *e = getenv("SNN_WGRAD_WORKGROUPS");      // tuning knob: workgroups resident at once
-    long long v = e ? atoll(e) : 0;
-    return v > 0 ? v : 512;
-  }();
+  const long long target = 512;                          // workgroups resident at once
   if (tiles < 1) tiles = 1;
   const long long max_by_len = M / 256;                  // at least four 64-row tiles per workgroup
   long long want = target / tiles;
@@ -187,9 +184,8 @@ int wgrad_tiles(int rows, int cols, bool tall) {
 
 // Rows of C per workgroup for the products over all T*B rows whose output is wider than 64
 // columns: the tallest tile that still gives every compute unit a few workgroups.
-int pick_rows_per_tile(long long rows, int cols) {
-  const char *e = getenv("SNN_TILE_ROWS");                              // tuning and test knob, read per call
-  const int forced = e ? atoi(e) : 0;
+int pick_rows_per_tile(const snn_ctx *c, long long rows, int cols) {
+  const int forced = c->opt[SNN_OPT_TILE_ROWS];
   if (forced == 32 || forced == 64 || forced == 128) return forced;
   const long long col_tiles = (cols + 127) / 128;
   if ((rows + 127) / 128 * col_tiles >= 512) return 128;
@@ -224,8 +220,7 @@ void carve(snn_ctx &c, Carver &cv) {
     }
     return n;
   };
-  static const int tall_knob = [] { const char *e = getenv("SNN_WGRAD_TALL"); return e ? atoi(e) : -1; }();
-  c.wg_tall = c.precision != SNN_PREC_FP32 && (tall_knob >= 0 ? tall_knob != 0 : count_tiles(false) >= 32);
+  c.wg_tall = c.precision != SNN_PREC_FP32 && count_tiles(false) >= 32;
   const int wg_tiles = count_tiles(c.wg_tall);
   long long wg_weights = 0, wg_row_bytes = 0;             // what the merged launch writes per split / reads per row
   for (int l = 0; l < c.L; ++l) {
@@ -371,16 +366,12 @@ SpikeSrc spikes_below(snn_ctx *c, int l) {
 // again before the next kernel reads it; stored non-temporally it at least leaves the
 // operands of the product that writes it in place.  Smaller results are stored normally: the
 // next kernel finds them warm.
-// (SNN_STREAM_MIN_MB moves the limit; the tests set it to 0 to run these paths on small shapes.)
-static bool streams_past_cache(size_t bytes) {
-  const char *e = getenv("SNN_STREAM_MIN_MB");
-  return bytes >= ((size_t)(e ? atoi(e) : 128) << 20);
+// (SNN_OPT_STREAM_MIN_MB moves the limit; the tests set it to 0 to run these paths on small shapes.)
+static bool streams_past_cache(const snn_ctx *c, size_t bytes) {
+  return bytes >= ((size_t)c->opt[SNN_OPT_STREAM_MIN_MB] << 20);
 }
 
-static bool stream_gemm() {
-  const char *e = getenv("SNN_STREAM_GEMM");
-  return !e || atoi(e) != 0;
-}
+static bool stream_gemm(const snn_ctx *c) { return c->opt[SNN_OPT_STREAM_GEMM] != 0; }
 
 // I^l = S^{l-1} W^l over all T*B rows at once.
 int launch_current_gemm(snn_ctx *c, int l) {
@@ -393,12 +384,12 @@ int launch_current_gemm(snn_ctx *c, int l) {
   a.Q = y.Qf; a.ldq = y.ldqf; a.q_plane_stride = y.qf_plane; a.q_bytes = (unsigned)(c->nplanes * y.qf_plane * 2);
   a.C = y.I; a.ldc = y.ld; a.rows = (int)c->M; a.cols = y.N;
   a.kc_per_split = (int)rup(a.kc, 64);
-  a.nt_store = streams_past_cache(c->M * y.ld * 4);
+  a.nt_store = streams_past_cache(c, c->M * y.ld * 4);
   Bracket br(c, SNN_K_CURRENT_GEMM, l + 1);
   hipError_t e;
-  const int bm = pick_rows_per_tile(c->M, y.N);
+  const int bm = pick_rows_per_tile(c, c->M, y.N);
   // The streamed kernel addresses both P and C with 32-bit byte offsets.
-  const bool streamed = a.nt_store && stream_gemm() && c->M * y.ld * 4 < ((size_t)1 << 31) && (size_t)c->M * s.ld < ((size_t)1 << 31);
+  const bool streamed = a.nt_store && stream_gemm(c) && c->M * y.ld * 4 < ((size_t)1 << 31) && (size_t)c->M * s.ld < ((size_t)1 << 31);
   if (c->precision == SNN_PREC_FP32) {
     if (y.N <= 32) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 4, 1, 1, 1, 3, 1>(a, 1, c->stream);
     else if (y.N <= 64) e = gemm_launch<P_U8, Q_BF16, EPI_STORE, 2, 2, 2, 1, 3, 1>(a, 1, c->stream);
@@ -430,10 +421,10 @@ int launch_input_grad(snn_ctx *c, int l) {
   a.Q = y.Qb; a.ldq = y.ldqb; a.q_plane_stride = y.qb_plane; a.q_bytes = (unsigned)(c->nplanes * y.qb_plane * 2);
   a.C = below.dS; a.ldc = below.ld; a.rows = (int)c->M; a.cols = y.K;
   a.kc_per_split = (int)rup(a.kc, 64);
-  a.nt_store = streams_past_cache(c->M * below.ld * 4);
+  a.nt_store = streams_past_cache(c, c->M * below.ld * 4);
   Bracket br(c, SNN_K_INPUT_GRAD, l + 1);
   hipError_t e;
-  const int bm = pick_rows_per_tile(c->M, y.K);
+  const int bm = pick_rows_per_tile(c, c->M, y.K);
   if (c->precision == SNN_PREC_FP32) {
     if (y.K <= 32) e = gemm_launch<P_F32S, Q_BF16, EPI_STORE, 4, 1, 1, 1, 3, 1>(a, 1, c->stream);
     else e = gemm_launch<P_F32S, Q_BF16, EPI_STORE, 2, 2, 1, 1, 3, 1>(a, 1, c->stream);
@@ -500,11 +491,15 @@ int queue_tn(snn_ctx *c, WgradJobs &w, SpikeSrc s, int rows, const void *G, int 
   return SNN_OK;
 }
 
-void add_reduce_job(ReduceJobs &jobs, const float *part, float *out, int splits, long long n, bool always = false) {
-  if (splits <= 1 && !always) return;       // a single split was written straight to `out`
+static_assert(SNN_MAX_REDUCE_JOBS >= 3 * SNN_MAX_LAYERS, "dW, dR and dbeta of every layer");
+static_assert(SNN_MAX_JOBS >= 2 * SNN_MAX_LAYERS, "W and R of every layer");
+bool add_reduce_job(ReduceJobs &jobs, const float *part, float *out, int splits, long long n, bool always = false) {
+  if (splits <= 1 && !always) return true;  // a single split was written straight to `out`
+  if (jobs.njobs >= SNN_MAX_REDUCE_JOBS) return false;
   const int j = jobs.njobs++;
   jobs.part[j] = part; jobs.out[j] = out; jobs.splits[j] = splits; jobs.n[j] = n;
   jobs.first_block[j + 1] = jobs.first_block[j] + (int)((n + 255) / 256);
+  return true;
 }
 
 // Sums the split partial products; with_loss adds the workgroup that takes the mean loss.
@@ -534,12 +529,13 @@ int queue_weight_grad(snn_ctx *c, int l, WgradJobs &w, ReduceJobs &jobs) {
   if (!s.p) return fail(c, SNN_ERR_NULL, "input raster is NULL");
   int rc = queue_tn(c, w, s, y.K, y.dI, y.ld, y.N, y.dW, y.part_w, y.splits_w, y.per_w);
   if (rc) return rc;
-  add_reduce_job(jobs, y.part_w, y.dW, y.splits_w, (long long)y.K * y.N);
+  bool ok = add_reduce_job(jobs, y.part_w, y.dW, y.splits_w, (long long)y.K * y.N);
   if (y.recurrent) {
     SpikeSrc own = {y.S, y.ld, y.ld, (unsigned)(c->M * y.ld)};
     rc = queue_tn(c, w, own, y.N, y.dI, y.ld, y.N, y.dR, y.part_r, y.splits_r, y.per_r);
-    add_reduce_job(jobs, y.part_r, y.dR, y.splits_r, (long long)y.N * y.N);
+    ok = ok && add_reduce_job(jobs, y.part_r, y.dR, y.splits_r, (long long)y.N * y.N);
   }
+  if (!ok) return fail(c, SNN_ERR_UNSUPPORTED, "more than %d gradient reductions in one backward pass", SNN_MAX_REDUCE_JOBS);
   return rc;
 }
 
@@ -581,11 +577,7 @@ int flush_reduce(snn_ctx *c) {
 
 // Threads per workgroup of the one-thread-per-chain scans: single wavefronts while that is
 // what it takes to give each of the 256 compute units (8 XCDs x 32) something to do.
-int scan_block(long long threads) {
-  static const int forced = [] { const char *e = getenv("SNN_SCAN_BLOCK"); return e ? atoi(e) : 0; }();
-  if (forced == 64 || forced == 128 || forced == 256) return forced;    // tuning knob
-  return threads >= 256 * 1024 ? 256 : 64;
-}
+int scan_block(long long threads) { return threads >= 256 * 1024 ? 256 : 64; }
 
 template <int VEC, int U>
 hipError_t lif_fwd_launch(snn_ctx *c, Layer &y) {
@@ -593,7 +585,7 @@ hipError_t lif_fwd_launch(snn_ctx *c, Layer &y) {
   const int threads = stride / VEC;
   const int bs = scan_block(threads);
   const dim3 grid((unsigned)((threads + bs - 1) / bs)), block(bs);
-  if (streams_past_cache(c->M * y.ld * 4))
+  if (streams_past_cache(c, c->M * y.ld * 4))
     hipLaunchKernelGGL((lif_forward_kernel<VEC, U, NT>), grid, block, 0, c->stream, y.I, y.V, y.S, c->T, stride,
                        y.beta_v, y.ld, c->theta);
   else
@@ -626,7 +618,7 @@ hipError_t lif_rev_launch2(snn_ctx *c, Layer &y) {
   const int threads = stride / VEC;
   const int bs = scan_block(threads);
   dim3 grid((unsigned)((threads + bs - 1) / bs)), block(bs);
-  const bool nt = streams_past_cache(c->M * y.ld * 4);
+  const bool nt = streams_past_cache(c, c->M * y.ld * 4);
 #define SNN_REV(SU)                                                                                              \
   do {                                                                                                           \
     if (nt)                                                                                                      \
@@ -679,8 +671,7 @@ int launch_lif_reverse(snn_ctx *c, int l) {
 // where the four-chains-per-lane scan plus the readout's input-gradient launch took 290 + 100.)
 int columns_above(const snn_ctx *c, int l) { return l + 1 == c->L - 1 ? c->ldC : c->layers[l + 1].ld; }
 bool reverse_fusable(const snn_ctx *c, int l) {
-  const char *e = getenv("SNN_FUSE_TOP");                 // test knob, read per call
-  if (e && atoi(e) == 0) return false;
+  if (!c->opt[SNN_OPT_TOP_SCANS]) return false;
   if (l < 0 || l > c->L - 2) return false;
   const Layer &y = c->layers[l];
   return c->hl && y.spiking && !y.recurrent && y.ld % 64 == 0 && columns_above(c, l) <= 128;
@@ -701,7 +692,7 @@ int launch_lif_forward_top(snn_ctx *c) {
   Bracket br(c, SNN_K_LIF_FORWARD, l + 1);
   const int stride = c->B * y.ld;
   const int q_rows = (int)(ro.qf_plane / ro.ldqf);
-  const bool nt = streams_past_cache(c->M * y.ld * 4);
+  const bool nt = streams_past_cache(c, c->M * y.ld * 4);
 #define SNN_FWDT(NW)                                                                                              \
   do {                                                                                                            \
     if (nt)                                                                                                       \
@@ -722,14 +713,14 @@ int launch_lif_forward_top(snn_ctx *c) {
 // The same reverse pass as one workgroup per sample and 64 neurons on LDS
 // (lif_layer_reverse_kernel): layers of 64 to 256 neurons (wider, the scan with a wavefront per
 // 64 chains is faster: 121 against 129 us at 512 neurons, 466 against 492 at 1024), 32-bit byte
-// offsets.  SNN_FUSE_LAYER_REV=0 switches it off; SNN_FUSE_LAYER_MIN_B as for the forward pass.
-// Both read per call.
+// offsets.  SNN_OPT_LAYER_REVERSE = 0 switches it off; SNN_OPT_LAYER_MIN_BATCH as for the forward pass.
+int layer_min_batch(const snn_ctx *c) {
+  return c->opt[SNN_OPT_LAYER_MIN_BATCH] > 0 ? c->opt[SNN_OPT_LAYER_MIN_BATCH] : c->T <= 256 ? 1 : 64;
+}
 bool layer_reverse_whole(snn_ctx *c, int l) {
-  const char *e = getenv("SNN_FUSE_LAYER_REV");
-  if (e && atoi(e) == 0) return false;
+  if (!c->opt[SNN_OPT_LAYER_REVERSE]) return false;
   const Layer &y = c->layers[l];
-  const char *m = getenv("SNN_FUSE_LAYER_MIN_B");
-  const int min_b = m ? atoi(m) : c->T <= 256 ? 1 : 64;
+  const int min_b = layer_min_batch(c);
   return reverse_fusable(c, l) && y.ld <= 256 && c->B >= min_b &&
          (size_t)c->M * y.ld * 4 < ((size_t)1 << 31) && (size_t)c->M * columns_above(c, l) * 4 < ((size_t)1 << 31);
 }
@@ -743,7 +734,7 @@ int launch_layer_reverse(snn_ctx *c, int l) {
   a.Wq = up.Qb; a.ldq = up.ldqb; a.wq_bytes = (unsigned)(up.qb_plane * 2);
   a.V = y.V; a.dI = y.dI; a.beta_v = y.beta_v; a.theta = c->theta; a.slope = c->slope; a.db_part = y.part_b;
   a.T = c->T; a.B = c->B; a.ld = y.ld;
-  a.nt_store = streams_past_cache(c->M * y.ld * 4);
+  a.nt_store = streams_past_cache(c, c->M * y.ld * 4);
   Bracket br(c, SNN_K_LIF_REVERSE, l + 1);
   // 64 neurons per workgroup (two or three workgroups share a compute unit and overlap each
   // other's phases): 99.8 us per step at 700-128-128-20 against 104.8 with 128 neurons.
@@ -775,7 +766,7 @@ int launch_lif_reverse_fused(snn_ctx *c, int l) {
   const int stride = c->B * y.ld, ldc = columns_above(c, l);
   const int wpg = (y.ld / 64) % 4 == 0 ? 4 : (y.ld / 64) % 2 == 0 ? 2 : 1;   // wavefronts per workgroup: one sample's
   const dim3 grid((unsigned)(stride / 64 / wpg)), block(64 * wpg);
-  const bool nt = streams_past_cache(c->M * y.ld * 4);
+  const bool nt = streams_past_cache(c, c->M * y.ld * 4);
 #define SNN_REVT2(KS, SU)                                                                                        \
   do {                                                                                                           \
     if (nt)                                                                                                      \
@@ -809,44 +800,36 @@ int launch_lif_reverse_fused(snn_ctx *c, int l) {
 // A workgroup owns a sample and 64 or 128 neurons; 32-bit
 // byte offsets into the spikes below and V; a threshold the scan's compare-free spike
 // decision is exact for.
-// Width limit (SNN_LAYER_MAX_NEURONS): the parts of a sample each pass its spike rows below
+// Width limit (SNN_OPT_LAYER_MAX_NEURONS): the parts of a sample each pass its spike rows below
 // through their CU, which the I round trip saved outweighs up to 1024 neurons (product + scan
 // 228 -> 169 us at 700-512-512-20, 982 -> 781 us at 700-1024-1024-20, 256 steps) and no longer
 // at 2048 (1433 -> 1455 us, 512 steps, 128 samples); the same limit holds for the fan-in.
-// SNN_FUSE_LAYER: 0 never, 1 all but the last spiking layer, 2 every such layer, 3 the last one
-// also forms the readout's currents when it has exactly 128 padded neurons, 4 (default) and runs
-// the readout scan, the loss and the readout's current gradients;
-// SNN_FUSE_LAYER_MIN_B: samples from which it is used (default: any number up to 256 steps, 64
+// SNN_OPT_LAYER_FORWARD: 0 never, 1 all but the last spiking layer, 2 every such layer, 3 the last
+// one also forms the readout's currents when it has exactly 128 padded neurons, 4 (default) and
+// runs the readout scan, the loss and the readout's current gradients;
+// SNN_OPT_LAYER_MIN_BATCH: samples from which it is used (default: any number up to 256 steps, 64
 // for longer rasters: at the headline widths it wins from 4 samples on, having fewer launches,
-// but a workgroup walks its sample's blocks of 128 steps serially); SNN_LAYER_NEURONS: 64 or
-// 128 neurons per workgroup.  All read per call.
-int layer_fuse_mode() {
-  const char *e = getenv("SNN_FUSE_LAYER");
-  return e ? atoi(e) : 4;
-}
-static int layer_max_neurons() {
-  const char *e = getenv("SNN_LAYER_MAX_NEURONS");
-  return e ? atoi(e) : 1024;
-}
+// but a workgroup walks its sample's blocks of 128 steps serially); SNN_OPT_LAYER_NEURONS: 64 or
+// 128 neurons per workgroup.
+int layer_fuse_mode(const snn_ctx *c) { return c->opt[SNN_OPT_LAYER_FORWARD]; }
+static int layer_max_neurons(const snn_ctx *c) { return c->opt[SNN_OPT_LAYER_MAX_NEURONS]; }
 bool layer_forward_fusable(snn_ctx *c, int l) {
   if (l < 0 || l > c->L - 2) return false;
   const Layer &y = c->layers[l];
-  const char *e = getenv("SNN_FUSE_LAYER_MIN_B");
-  const int min_b = e ? atoi(e) : c->T <= 256 ? 1 : 64;   // a workgroup walks a sample's blocks of 128 steps one after the other
+  const int min_b = layer_min_batch(c);                  // a workgroup walks a sample's blocks of 128 steps one after the other
   const SpikeSrc s = spikes_below(c, l);
-  return c->nplanes == 1 && y.spiking && !y.recurrent && y.ld % 64 == 0 && y.ld <= layer_max_neurons() && c->B >= min_b &&
-         s.ld % 4 == 0 && s.ld <= layer_max_neurons() && (size_t)c->M * s.ld < ((size_t)1 << 31) && (size_t)c->M * y.ld * 4 < ((size_t)1 << 31) &&
+  return c->nplanes == 1 && y.spiking && !y.recurrent && y.ld % 64 == 0 && y.ld <= layer_max_neurons(c) && c->B >= min_b &&
+         s.ld % 4 == 0 && s.ld <= layer_max_neurons(c) && (size_t)c->M * s.ld < ((size_t)1 << 31) && (size_t)c->M * y.ld * 4 < ((size_t)1 << 31) &&
          y.qf_plane >= (long long)y.ld * y.ldqf && c->theta >= 0x1p-60f && c->theta <= 0x1p26f;
 }
 
 // What the launch of the last spiking layer takes over from the readout: 0 nothing, 1 its
 // currents J, 2 also the LI scan, the loss and dJ (what readout_loss_kernel does).
 int layer_forward_takes_readout(snn_ctx *c) {
-  const char *e = getenv("SNN_LAYER_NEURONS");
   const Layer &ro = c->layers[c->L - 1];
-  const int mode = layer_fuse_mode();
+  const int mode = layer_fuse_mode(c);
   const bool ok = c->L >= 2 && mode >= 3 && layer_forward_fusable(c, c->L - 2) && c->layers[c->L - 2].ld == 128 &&
-                  (!e || atoi(e) == 128) && c->ldC <= 32 && ro.qf_plane >= 32ll * ro.ldqf && ro.ldqf >= 128;
+                  c->opt[SNN_OPT_LAYER_NEURONS] == 128 && c->ldC <= 32 && ro.qf_plane >= 32ll * ro.ldqf && ro.ldqf >= 128;
   return !ok ? 0 : mode >= 4 && c->hl ? 2 : 1;
 }
 
@@ -868,10 +851,9 @@ int launch_layer_forward(snn_ctx *c, int l, int nl, int with_readout, const int3
   }
   a.theta = c->theta;
   a.T = c->T; a.B = c->B; a.ld = y.ld;
-  a.nt_store = streams_past_cache(c->M * y.ld * 4);
+  a.nt_store = streams_past_cache(c, c->M * y.ld * 4);
   Bracket br(c, SNN_K_LIF_FORWARD, l + 1);
-  const char *e = getenv("SNN_LAYER_NEURONS");
-  const int bn = y.ld % 128 ? 64 : e ? atoi(e) : 128;   // 128: 108.0 us per step at 700-128-128-20, 64: 109.7
+  const int bn = y.ld % 128 ? 64 : c->opt[SNN_OPT_LAYER_NEURONS];   // 128: 108.0 us per step at 700-128-128-20, 64: 109.7
   const dim3 grid((unsigned)(rup(c->B, 8) * (y.ld / bn)));
 #define SNN_LFWD(RO)                                                                                             \
   do {                                                                                                           \
@@ -1178,17 +1160,15 @@ int32_t snn_init(const snn_config *cfg, void *workspace_dev, size_t workspace_by
 
 static int32_t forward_layers(snn_ctx *c, const int32_t *labels_dev, float *loss_host) {
   int rc;
-  const int whole = layer_fuse_mode();                  // layers that run as one launch, product and scan
+  const int whole = layer_fuse_mode(c);                 // layers that run as one launch, product and scan
   const bool whole_top = whole >= 2 && layer_forward_fusable(c, c->L - 2);
   const int with_readout = whole_top ? layer_forward_takes_readout(c) : 0;
   const bool fuse_top = !whole_top && top_forward_fusable(c);   // the last spiking layer's scan forms the readout's currents
   for (int l = 0; l < c->L; ++l) {
     if (whole >= 1 && (l < c->L - 2 || whole_top) && layer_forward_fusable(c, l)) {
       // this layer and the next in one launch when both hold exactly 128 padded neurons
-      // (SNN_FUSE_LAYER_PAIR=0: one launch each)
-      const char *pe = getenv("SNN_FUSE_LAYER_PAIR");
-      const char *ne = getenv("SNN_LAYER_NEURONS");
-      const bool pair = !(pe && atoi(pe) == 0) && !(ne && atoi(ne) != 128) && c->layers[l].ld == 128 && l + 1 <= c->L - 2 &&
+      // (SNN_OPT_LAYER_PAIR = 0: one launch each)
+      const bool pair = c->opt[SNN_OPT_LAYER_PAIR] && c->opt[SNN_OPT_LAYER_NEURONS] == 128 && c->layers[l].ld == 128 && l + 1 <= c->L - 2 &&
                         (l + 1 < c->L - 2 || whole_top) && layer_forward_fusable(c, l + 1) && c->layers[l + 1].ld == 128;
       const int nl = pair ? 2 : 1;
       if ((rc = launch_layer_forward(c, l, nl, l + nl - 1 == c->L - 2 ? with_readout : 0, labels_dev))) return rc;
@@ -1248,6 +1228,7 @@ int32_t snn_backward(snn_ctx *c) {
       c->layers[l].ds_ready = !fused;
       if ((rc = fused ? launch_lif_reverse_fused(c, l) : launch_lif_reverse(c, l))) return rc;
     }
+    if (l == 0 && c->prof.cls == SNN_K_EVENT_PAIR) { Bracket br(c, SNN_K_EVENT_PAIR, 0); }
     if (l == 0 && c->prof.cls == SNN_K_CALIBRATE) {
       Bracket br(c, SNN_K_CALIBRATE, 0);
       hipLaunchKernelGGL(wait_ticks_kernel, dim3(1), dim3(64), 0, c->stream,
@@ -1269,12 +1250,13 @@ int32_t snn_backward(snn_ctx *c) {
       hipLaunchKernelGGL(readout_beta_grad_kernel<false>, dim3((stride + 255) / 256), dim3(256), 0, c->stream, ro.dI,
                          ro.V, ro.part_b, c->T, stride);
     HIPCHK(c, hipGetLastError());
-    for (int l = 0; l < c->L; ++l) add_reduce_job(jobs, c->layers[l].part_b, c->layers[l].dbeta, c->B, c->layers[l].ld, true);
+    for (int l = 0; l < c->L; ++l)
+      if (!add_reduce_job(jobs, c->layers[l].part_b, c->layers[l].dbeta, c->B, c->layers[l].ld, true))
+        return fail(c, SNN_ERR_UNSUPPORTED, "more than %d gradient reductions in one backward pass", SNN_MAX_REDUCE_JOBS);
   }
   // Without trained decays the reduction of the partial sums waits for snn_sgd_step, which does
-  // it in the launch that updates the parameters (SNN_FUSE_SGD=0: reduce here, as before).
-  const char *e = getenv("SNN_FUSE_SGD");
-  const bool defer = !c->learn_beta && !(e && atoi(e) == 0);
+  // it in the launch that updates the parameters (SNN_OPT_DEFER_REDUCE = 0: reduce here).
+  const bool defer = !c->learn_beta && c->opt[SNN_OPT_DEFER_REDUCE];
   if ((rc = launch_weight_grads(c, wj, jobs, !c->loss_ready, defer))) return rc;
   c->state = 2;
   return SNN_OK;
@@ -1358,6 +1340,9 @@ int32_t snn_set_tensor(snn_ctx *c, int32_t tensor, int32_t layer, const void *sr
                              c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
   if (tensor == SNN_T_D_LOGITS || tensor == SNN_T_ARGMAX_T) c->dj_ready = false;   // dJ must be recomputed
+  if (tensor == SNN_T_CURRENT) c->layers[layer - 1].i_ready = true;     // what the caller imposed is what a reader gets
+  if (tensor == SNN_T_D_SPIKES) c->layers[layer - 1].ds_ready = true;
+  if (tensor == SNN_T_BETA) c->state = 0;                               // a forward pass on other decays is stale
   if (tensor == SNN_T_WEIGHT || tensor == SNN_T_RWEIGHT) {
     if ((rc = update_layers(c, layer - 1, layer, false, 0.f))) return rc;
     HIPCHK(c, hipStreamSynchronize(c->stream));
@@ -1402,6 +1387,35 @@ int32_t snn_run_step(snn_ctx *c, int32_t step, int32_t layer, const uint8_t *x_d
       return launch_input_grad(c, l);
     default: return fail(c, SNN_ERR_ARG, "unknown step %d", step);
   }
+}
+
+int32_t snn_set_option(snn_ctx *c, int32_t option, int32_t value) {
+  if (!c) return fail(nullptr, SNN_ERR_NULL, "context is NULL");
+  bool ok;
+  switch (option) {
+    case SNN_OPT_LAYER_FORWARD: ok = value >= 0 && value <= 4; break;
+    case SNN_OPT_LAYER_PAIR:
+    case SNN_OPT_LAYER_REVERSE:
+    case SNN_OPT_TOP_SCANS:
+    case SNN_OPT_DEFER_REDUCE:
+    case SNN_OPT_STREAM_GEMM: ok = value == 0 || value == 1; break;
+    case SNN_OPT_LAYER_MIN_BATCH: ok = value >= 0; break;
+    case SNN_OPT_LAYER_NEURONS: ok = value == 64 || value == 128; break;
+    case SNN_OPT_LAYER_MAX_NEURONS: ok = value >= 64 && value <= 1024; break;
+    case SNN_OPT_STREAM_MIN_MB: ok = value >= 0 && value <= (1 << 20); break;
+    case SNN_OPT_TILE_ROWS: ok = value == 0 || value == 32 || value == 64 || value == 128; break;
+    default: return fail(c, SNN_ERR_ARG, "unknown option %d", option);
+  }
+  if (!ok) return fail(c, SNN_ERR_ARG, "value %d is out of range for option %d", value, option);
+  c->opt[option] = value;
+  return SNN_OK;
+}
+
+int32_t snn_get_option(const snn_ctx *c, int32_t option, int32_t *value) {
+  if (!c || !value) return fail(nullptr, SNN_ERR_NULL, "context or value is NULL");
+  if (option < 0 || option >= SNN_OPT_COUNT) return fail(nullptr, SNN_ERR_ARG, "unknown option %d", option);
+  *value = c->opt[option];
+  return SNN_OK;
 }
 
 int32_t snn_profile_select(snn_ctx *c, int32_t kernel_class, int32_t layer) {

@@ -81,9 +81,15 @@ def reconciled_forward(net: O.Net, X, W, R, labels, S_gpu, max_rounds: int = 200
     raise ParityError("spike reconciliation did not converge")
 
 
-def close_state(name, a, b, tol=TOL_STATE):
+def close_state(name, a, b, tol=TOL_STATE, count_above=None):
+    """|a - b| <= tol max(1, |b|) element by element; returns the largest scaled error.
+    `count_above`: a dict that receives, under `name`, how many elements exceed TOL_STATE (for
+    cases that are held to a wider band and report how often the standard one is passed)."""
     a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
     err = np.abs(a - b) / np.maximum(1.0, np.abs(b))
+    if count_above is not None:
+        count_above[name] = int((err > TOL_STATE).sum())
+        count_above["_elements"] = count_above.get("_elements", 0) + err.size
     if not (err.max() <= tol):
         i = np.unravel_index(np.argmax(err), err.shape)
         raise ParityError(f"{name}: max scaled error {err.max():.3e} > {tol:g} at {i}: device {a[i]!r} oracle {b[i]!r}")
@@ -190,12 +196,15 @@ def sampled_step_parity(net: O.Net, inp, snn, loss_gpu, idx, n_rows=48, seed=0, 
     tr, imposed = reconciled_forward(net, Xs, inp.W, inp.R, ls, [s[:, idx] for s in S_full], band=band)
     rep["imposed_decisions"] = imposed
     rep["spike_rate"] = [float(s.mean()) for s in S_full]
+    above = {}
     for l in range(Lh):
         assert np.array_equal(S_full[l][:, idx], tr.S[l].astype(np.uint8))
-        rep[f"V{l + 1}"] = close_state(f"V^{l + 1}", snn.get_tensor("membrane", l + 1)[:, idx], tr.V[l], tol_state)
-        rep[f"I{l + 1}"] = close_state(f"I^{l + 1}", snn.get_tensor("current", l + 1)[:, idx], tr.I[l], tol_state)
-    rep["Y"] = close_state("Y", snn.get_tensor("readout_trace")[:, idx], tr.Y, tol_state)
-    rep["z"] = close_state("z", snn.get_tensor("logits")[idx], tr.z, tol_state)
+        rep[f"V{l + 1}"] = close_state(f"V^{l + 1}", snn.get_tensor("membrane", l + 1)[:, idx], tr.V[l], tol_state, above)
+        rep[f"I{l + 1}"] = close_state(f"I^{l + 1}", snn.get_tensor("current", l + 1)[:, idx], tr.I[l], tol_state, above)
+    rep["Y"] = close_state("Y", snn.get_tensor("readout_trace")[:, idx], tr.Y, tol_state, above)
+    rep["z"] = close_state("z", snn.get_tensor("logits")[idx], tr.z, tol_state, above)
+    rep["state_elements"] = above.pop("_elements")
+    rep["above_1e-5"] = above
     ts = snn.get_tensor("argmax_t")[idx]
     bad = np.argwhere(ts != tr.tstar)
     for b, c in bad:

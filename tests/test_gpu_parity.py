@@ -17,22 +17,29 @@ from tests.helpers import net_of
 pytestmark = pytest.mark.gpu
 
 
-def make(wl, inp):
+def make(wl, inp, options=None):
+    """A context for the workload; `options`: snn_set_option values by name (kernel selection)."""
     from paper_2402_18994_amd.binding import from_workload
-    return from_workload(wl, inp)
+    return from_workload(wl, inp, options=options)
 
 
-def full_step_parity(wl, w_gain=1.0, lr=0.1, seed=None, grad_tol=parity.TOL_GRAD, check_sgd=True):
+def full_step_parity(wl, w_gain=1.0, lr=0.1, seed=None, grad_tol=parity.TOL_GRAD, check_sgd=True, options=None,
+                     say=lambda text: None):
+    """`say`: progress lines of a long case (a run that stays silent for minutes is taken for hung)."""
     inp = workloads.generate(wl, w_gain=w_gain, seed=seed)
     net = net_of(wl)
-    snn = make(wl, inp)
+    snn = make(wl, inp, options)
     print(f"\n[case] {wl.name} T={wl.T} B={wl.B} sizes={wl.sizes} rec={wl.recurrent} "
           f"{wl.precision} {wl.surrogate} gain={w_gain}", flush=True)
     rep = {}
     loss = snn.forward(inp.X, inp.labels)
+    say("device forward done; oracle forward")
     tr = parity.compare_forward(net, inp, snn, loss, rep)
+    say(f"forward tensors agree ({rep['imposed_decisions']} imposed decisions); device backward")
     snn.backward()
+    say("oracle backward")
     gr = parity.compare_backward(net, inp, snn, tr, rep, tol=grad_tol)
+    say("gradients agree")
     if check_sgd:
         snn.sgd_step(lr)
         Wn, Rn = O.sgd_step(inp.W, inp.R, gr, lr)
@@ -136,15 +143,14 @@ def test_reverse_scan_below_a_narrow_layer(above, rec_above):
     assert rep["spike_rate"][1] > 0.005
 
 
-def test_top_layer_scans_same_as_unfused(monkeypatch):
+def test_top_layer_scans_same_as_unfused():
     """The same step with and without the two fusions: readout currents, current gradients and
     weight gradients agree to rounding (the paths add their terms in different orders)."""
     wl = workloads.CONFIGS["shd_ff128"].scaled(T=48, B=16)
     inp = workloads.generate(wl, w_gain=3.0)
     out = []
-    for knob in ("1", "0"):
-        monkeypatch.setenv("SNN_FUSE_TOP", knob)
-        snn = make(wl, inp)
+    for knob in (1, 0):
+        snn = make(wl, inp, {"top_scans": knob})
         snn.forward(inp.X, inp.labels)
         snn.backward()
         out.append([snn.get_tensor("d_current", 1), snn.get_tensor("d_spikes", 1),
@@ -164,37 +170,34 @@ def test_top_layer_scans_same_as_unfused(monkeypatch):
                          ids=["one-block", "two-blocks-ragged-fan-in", "three-blocks-nontemporal", "headline-widths",
                               "192-and-256-neurons", "256-neurons-in-four-parts", "512-and-384-neurons",
                               "960-and-1024-neurons"])
-def test_layer_forward_in_one_launch(monkeypatch, T, sizes, nt, bn):
+def test_layer_forward_in_one_launch(T, sizes, nt, bn):
     """bf16 products, feed-forward spiking layers of 64 to 1024 (padded) neurons: product and scan
     run as one launch per layer, a workgroup per sample and 64 or 128 neurons, and I is never
     stored (read back, it comes from the product kernel).  For rasters of more than 256 steps the
-    library uses the path from 64 samples on; the knob lowers that so that an element-by-element
+    library uses the path from 64 samples on; the option lowers that so that an element-by-element
     oracle run covers those too: one, two and three blocks of 128 steps with ragged tails,
     fan-ins that are no multiple of 32 or of 16 bytes, a layer of 121 neurons padded to 128,
     layers of 64, 192, 256, 384, 512, 960 (fifteen parts of 64) and 1024 neurons, both workgroup
     widths, stores with and without the non-temporal hint."""
-    monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
-    monkeypatch.setenv("SNN_LAYER_NEURONS", str(bn))
+    options = {"layer_min_batch": 1, "layer_neurons": bn}
     if nt:
-        monkeypatch.setenv("SNN_STREAM_MIN_MB", "0")
+        options["stream_min_mb"] = 0
     wl = workloads.Workload(name="layer-launch", index=18, T=T, B=5, sizes=sizes, recurrent=(False, False),
                             beta=(0.9, 0.93, 0.95), theta=1.0, surrogate="superspike", slope=10.0, precision="bf16",
                             rate_lo=0.03, rate_hi=0.12)
-    rep = full_step_parity(wl, w_gain=2.0)
+    rep = full_step_parity(wl, w_gain=2.0, options=options)
     assert rep["spike_rate"][0] > 0.005
 
 
-def test_layer_forward_in_one_launch_same_as_separate_launches(monkeypatch):
+def test_layer_forward_in_one_launch_same_as_separate_launches():
     """The same forward pass with and without the one-launch layers: potentials and readout
     agree to rounding, spikes are identical away from the threshold."""
     wl = workloads.CONFIGS["shd_ff128"].scaled(T=140, B=12)
     inp = workloads.generate(wl, w_gain=3.0)
-    monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
     out = []
     # 3: the last layer's launch also forms the readout's currents; 4: and runs the whole readout
-    for knob in ("4", "3", "2", "1", "0"):
-        monkeypatch.setenv("SNN_FUSE_LAYER", knob)
-        snn = make(wl, inp)
+    for knob in (4, 3, 2, 1, 0):
+        snn = make(wl, inp, {"layer_min_batch": 1, "layer_forward": knob})
         snn.forward(inp.X, inp.labels)
         out.append([snn.get_tensor("membrane", 1), snn.get_tensor("spikes", 1), snn.get_tensor("current", 1),
                     snn.get_tensor("membrane", 2), snn.get_tensor("spikes", 2), snn.get_tensor("readout_trace"),
@@ -218,58 +221,53 @@ def test_layer_forward_in_one_launch_same_as_separate_launches(monkeypatch):
                                                       (70, (70, 128, 128, 3), "boxcar", 1.0),
                                                       (33, (70, 256, 64, 12), "ste", 1.0),
                                                       (50, (40, 192, 64, 10), "superspike", 25.0)])
-def test_layer_reverse_in_one_launch(monkeypatch, T, sizes, surrogate, slope):
+def test_layer_reverse_in_one_launch(T, sizes, surrogate, slope):
     """bf16 products, feed-forward spiking layers of 64 to 256 neurons below a layer of at most
     128 columns: dS, surrogate, reverse scan and the hi/lo store run as one launch, a workgroup
     per sample and 64 neurons, in blocks of 64 steps from the end.  One to three blocks with
     ragged first blocks, 24 to 128 columns above (one, two and four 32-wide contraction steps),
-    every surrogate (the knob lifts the batch-size condition that applies to long rasters)."""
-    monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
+    every surrogate (the option lifts the batch-size condition that applies to long rasters)."""
     wl = workloads.Workload(name="layer-reverse", index=23, T=T, B=5, sizes=sizes, recurrent=(False, False),
                             beta=(0.9, 0.93, 0.95), theta=1.0, surrogate=surrogate, slope=slope, precision="bf16",
                             rate_lo=0.03, rate_hi=0.12)
-    rep = full_step_parity(wl, w_gain=2.0)
+    rep = full_step_parity(wl, w_gain=2.0, options={"layer_min_batch": 1})
     assert rep["spike_rate"][0] > 0.005
 
 
-def test_layer_reverse_in_one_launch_with_trainable_decays(monkeypatch):
+def test_layer_reverse_in_one_launch_with_trainable_decays():
     """The same path with the decay gradients' partial sums taken inside the scan."""
-    monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
-    beta_step_parity(workloads.CONFIGS["shd_ff128"].scaled(T=100, B=12), w_gain=3.0)
+    beta_step_parity(workloads.CONFIGS["shd_ff128"].scaled(T=100, B=12), w_gain=3.0, options={"layer_min_batch": 1})
 
 
 @pytest.mark.parametrize("theta,beta,T,B", [(0.37, (0.9, 0.93, 0.95), 40, 5), (2.5, (1.0, 0.0, 0.9), 70, 6),
                                             (1.0, (0.9, 0.9, 0.9), 1, 9), (1.0, (0.9, 0.9, 0.9), 2, 9),
                                             (0.8, (0.95, 0.9, 0.9), 21, 131)])
-def test_layer_launches_thresholds_decays_and_batch_tails(monkeypatch, theta, beta, T, B):
+def test_layer_launches_thresholds_decays_and_batch_tails(theta, beta, T, B):
     """The one-launch layer kernels away from theta = 1 (their scan decides spikes without a
     compare, exactly for any threshold in [2^-60, 2^26]), with non-leaky (beta = 1) and
     memoryless (beta = 0) layers, one and two time steps, and a batch of 131 samples, which takes
-    the path without the test knob and leaves five of the launched workgroups without a sample."""
-    if B < 128:
-        monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
+    the path without the option and leaves five of the launched workgroups without a sample."""
     wl = workloads.Workload(name="layer-edge", index=24, T=T, B=B, sizes=(60, 128, 128, 10), recurrent=(False, False),
                             beta=beta, theta=theta, surrogate="superspike", slope=10.0, precision="bf16",
                             rate_lo=0.03, rate_hi=0.12)
-    rep = full_step_parity(wl, w_gain=2.0 * theta)
+    rep = full_step_parity(wl, w_gain=2.0 * theta, options={"layer_min_batch": 1} if B < 128 else None)
     assert T < 20 or rep["spike_rate"][0] > 0.005
 
 
 @pytest.mark.parametrize("loss,T,classes", [("integral", 300, 20), ("max", 300, 20), ("integral", 50, 5), ("max", 129, 32)])
-def test_last_layer_launch_runs_the_whole_readout(monkeypatch, loss, T, classes):
+def test_last_layer_launch_runs_the_whole_readout(loss, T, classes):
     """Last spiking layer of 128 neurons, at most 32 padded classes, bf16 products: its forward
     launch also forms the readout's currents, runs the readout scan in eight segments per block
     of 128 steps, and computes logits, first maximising steps, loss and the readout's current
     gradients.  Both losses, one to three blocks with ragged tails, 5 to 32 classes; an
     out-of-range label is reported through the same flag as by the separate kernel."""
     from paper_2402_18994_amd.binding import SnnError
-    monkeypatch.setenv("SNN_FUSE_LAYER_MIN_B", "1")
     wl = workloads.Workload(name="whole-readout", index=25, T=T, B=6, sizes=(70, 128, 128, classes),
                             recurrent=(False, False), beta=(0.9, 0.93, 0.95), theta=1.0, surrogate="superspike",
                             slope=10.0, precision="bf16", rate_lo=0.03, rate_hi=0.12, loss=loss)
-    full_step_parity(wl, w_gain=2.0, check_sgd=False)
+    full_step_parity(wl, w_gain=2.0, check_sgd=False, options={"layer_min_batch": 1})
     inp = workloads.generate(wl, w_gain=2.0)
-    snn = make(wl, inp)
+    snn = make(wl, inp, {"layer_min_batch": 1})
     bad = inp.labels.copy(); bad[2] = classes
     with pytest.raises(SnnError) as e:
         snn.forward(inp.X, bad)
@@ -282,7 +280,7 @@ def test_last_layer_launch_runs_the_whole_readout(monkeypatch, loss, T, classes)
                                                         ((45, 29, 13, 3), (False, False), "fp32"),
                                                         ((50, 40, 24, 5), (True, False), "bf16"),
                                                         ((61, 150, 66, 10), (False, True), "fp32")])
-def test_sgd_step_straight_after_backward(monkeypatch, sizes, recurrent, precision):
+def test_sgd_step_straight_after_backward(sizes, recurrent, precision):
     """snn_sgd_step right after snn_backward adds the per-split partial sums and updates the
     parameters in one launch; a caller that reads a gradient first gets the separate reduction.
     Both orders, and the library with the fusion switched off, must leave the same bits in the
@@ -295,8 +293,7 @@ def test_sgd_step_straight_after_backward(monkeypatch, sizes, recurrent, precisi
     L = len(sizes) - 1
     out = []
     for mode in ("straight", "read-first", "off"):
-        monkeypatch.setenv("SNN_FUSE_SGD", "0" if mode == "off" else "1")
-        snn = make(wl, inp)
+        snn = make(wl, inp, {"defer_reduce": 0 if mode == "off" else 1})
         snn.forward(inp.X, inp.labels)
         snn.backward()
         if mode == "read-first":
@@ -316,16 +313,15 @@ def test_sgd_step_straight_after_backward(monkeypatch, sizes, recurrent, precisi
     assert all(np.abs(g).max() > 0 for g in out[0][2::2][:L])
 
 
-def test_sgd_step_straight_after_backward_headline_shape(monkeypatch):
+def test_sgd_step_straight_after_backward_headline_shape():
     """The training loop bench.py times (forward, backward, step, nothing read in between) at the
     full headline shape: weights after two steps, their gradients and the loss must have the
     same bits as with the reduction done inside snn_backward."""
     wl = workloads.CONFIGS["shd_ff128"]
     inp = workloads.generate(wl, w_gain=3.0)
     out = []
-    for knob in ("1", "0"):
-        monkeypatch.setenv("SNN_FUSE_SGD", knob)
-        snn = make(wl, inp)
+    for knob in (1, 0):
+        snn = make(wl, inp, {"defer_reduce": knob})
         for _ in range(2):
             snn.forward(inp.X, inp.labels)
             snn.backward()
@@ -339,7 +335,7 @@ def test_sgd_step_straight_after_backward_headline_shape(monkeypatch):
 
 
 @pytest.mark.parametrize("T,sizes", [(150, (90, 128, 128, 128, 10)), (40, (50, 128, 128, 64, 128, 128, 12))])
-def test_two_layers_per_forward_launch(monkeypatch, T, sizes):
+def test_two_layers_per_forward_launch(T, sizes):
     """Consecutive one-launch layers of exactly 128 neurons share a launch in pairs: a workgroup
     takes its sample through the lower layer's block, stores its spikes, and reads them back as
     the upper layer's input.  Three hidden layers (a pair, then the last one alone with the
@@ -352,9 +348,8 @@ def test_two_layers_per_forward_launch(monkeypatch, T, sizes):
     full_step_parity(wl, w_gain=2.0)
     inp = workloads.generate(wl, w_gain=2.0)
     out = []
-    for knob in ("1", "0"):
-        monkeypatch.setenv("SNN_FUSE_LAYER_PAIR", knob)
-        snn = make(wl, inp)
+    for knob in (1, 0):
+        snn = make(wl, inp, {"layer_pair": knob})
         snn.forward(inp.X, inp.labels)
         out.append([snn.get_tensor("membrane", l) for l in range(1, L)] + [snn.get_tensor("spikes", l) for l in range(1, L)]
                    + [snn.get_tensor("readout_trace"), snn.get_tensor("loss")])
@@ -364,34 +359,30 @@ def test_two_layers_per_forward_launch(monkeypatch, T, sizes):
     assert out[0][L - 1].mean() > 0.005
 
 
-@pytest.fixture
-def large_tensor_paths(monkeypatch):
-    """The kernels chosen for tensors that stream past the caches (the streamed current product,
-    non-temporal scan loads and product stores) on shapes an element-by-element oracle run can
-    cover: the library reads these two knobs at every launch."""
-    monkeypatch.setenv("SNN_STREAM_MIN_MB", "0")
-    monkeypatch.setenv("SNN_TILE_ROWS", "128")
-    monkeypatch.setenv("SNN_FUSE_LAYER", "0")     # product and scan as separate launches: these tests are about them
+# The kernels chosen for tensors that stream past the caches (the streamed current product,
+# non-temporal scan loads and product stores) on shapes an element-by-element oracle run can
+# cover; product and scan as separate launches: these tests are about them.
+LARGE_TENSOR_PATHS = {"stream_min_mb": 0, "tile_rows": 128, "layer_forward": 0}
 
 
 @pytest.mark.parametrize("sizes", [(100, 200, 136, 10), (300, 330, 260, 20)], ids=["narrow-tiles", "wide-tiles"])
-def test_large_tensor_paths_ragged(large_tensor_paths, sizes):
+def test_large_tensor_paths_ragged(sizes):
     """Streamed current product with partial row tiles (T*B = 437), partial column tiles, a
     contraction that is neither a multiple of 32 nor of 16 bytes per row, and both tile widths;
     scans with non-temporal loads."""
     wl = workloads.Workload(name="streamed-ragged", index=13, T=19, B=23, sizes=sizes,
                             recurrent=(False, False), beta=(0.92, 0.9, 0.95), theta=1.0, surrogate="superspike",
                             slope=10.0, precision="bf16", rate_lo=0.02, rate_hi=0.1)
-    rep = full_step_parity(wl, w_gain=2.0)
+    rep = full_step_parity(wl, w_gain=2.0, options=LARGE_TENSOR_PATHS)
     assert rep["spike_rate"][1] > 0.005
 
 
-def test_large_tensor_paths_single_stage(large_tensor_paths):
+def test_large_tensor_paths_single_stage():
     """Contractions shorter than the pipeline: 20 inputs (one stage of the four) and 40 (two)."""
     wl = workloads.Workload(name="streamed-short", index=14, T=16, B=16, sizes=(20, 130, 40, 140, 5),
                             recurrent=(False, False, False), beta=(0.9, 0.9, 0.9, 0.9), theta=1.0,
                             surrogate="arctan", slope=2.0, precision="bf16", rate_lo=0.1, rate_hi=0.3)
-    full_step_parity(wl, w_gain=2.5)
+    full_step_parity(wl, w_gain=2.5, options=LARGE_TENSOR_PATHS)
 
 
 def sampled_parity(wl, w_gain, n_samples=6, **tols):
@@ -418,15 +409,14 @@ def sampled_parity(wl, w_gain, n_samples=6, **tols):
 
 
 @pytest.mark.parametrize("B", [128, 512])
-def test_wide_layers_vector_scans(monkeypatch, B):
+def test_wide_layers_vector_scans(B):
     """B * N of 2^17 and 2^19 chains: the scan kernels that give two and four adjacent chains
     to a thread (8- and 16-byte accesses), checked on every element (product and scan as
     separate launches, as for layers wider than 1024 neurons)."""
-    monkeypatch.setenv("SNN_FUSE_LAYER", "0")
     wl = workloads.Workload(name="widescan", index=13, T=24, B=B, sizes=(64, 1024, 1024, 20),
                             recurrent=(False, False), beta=(0.9, 0.9, 0.9), theta=1.0, surrogate="superspike",
                             slope=25.0, precision="bf16", rate_lo=0.05, rate_hi=0.3)
-    rep = full_step_parity(wl, w_gain=3.0, check_sgd=False)
+    rep = full_step_parity(wl, w_gain=3.0, check_sgd=False, options={"layer_forward": 0})
     assert rep["spike_rate"][0] > 0.01 and rep["spike_rate"][1] > 0.01
 
 
@@ -456,43 +446,18 @@ def test_shd_ff128_fp32_products():
 
 # ---------------------------------------------------------------- recurrent layers
 @pytest.mark.parametrize("precision", ["fp32", "bf16"])
-def test_recurrent_forward_row_stores_same_bits(monkeypatch, precision):
-    """Narrow recurrent layers whose rows are a multiple of 16 neurons store V_t and S_t as whole
-    rows through an LDS stage; the knob keeps the stores straight from the accumulator layout.
-    Same arithmetic, so every stored value has the same bits: layers of 96 and 128 neurons, a batch
-    of 45 (a second workgroup with 13 samples), 37 steps (both buffers of the stage, odd tail)."""
-    wl = workloads.Workload(name="rec_rows", index=27, T=37, B=45, sizes=(60, 96, 128, 10), recurrent=(True, True),
-                            beta=(0.9, 0.92, 0.95), theta=1.0, surrogate="superspike", slope=25.0,
-                            precision=precision, rate_lo=0.05, rate_hi=0.2, rec_gain=1.0)
-    inp = workloads.generate(wl, w_gain=2.0)
-    monkeypatch.setenv("SNN_RLIF_TILE", "32")      # both on tiles of 32 samples (16-sample tiles add in another order)
-    out = []
-    for knob in ("1", "0"):
-        monkeypatch.setenv("SNN_RLIF_STAGE", knob)
-        snn = make(wl, inp)
-        snn.forward(inp.X, inp.labels)
-        out.append([snn.get_tensor("membrane", 1), snn.get_tensor("spikes", 1), snn.get_tensor("membrane", 2),
-                    snn.get_tensor("spikes", 2), snn.get_tensor("readout_trace")])
-        snn.destroy()
-    for a, b in zip(*out):
-        assert np.array_equal(a, b)
-    assert out[0][1].mean() > 0.005 and out[0][3].mean() > 0.005
-
-
-@pytest.mark.parametrize("precision", ["fp32", "bf16"])
-@pytest.mark.parametrize("tile,waves", [("16", "8"), ("16", "4"), ("32", "4")])
-def test_recurrent_sample_tiles(monkeypatch, precision, tile, waves):
-    """Narrow recurrent layers run on tiles of 16 samples with eight wavefronts of 16 neurons
-    (default), with four of 32 neurons, or on tiles of 32 samples (knobs): full parity, forward and
-    reverse, for each; layers of 96 and 128 neurons, a batch of 45 (tails of 13 samples in either
-    tiling), 37 steps."""
-    monkeypatch.setenv("SNN_RLIF_TILE", tile)
-    monkeypatch.setenv("SNN_RLIF_WAVES", waves)
-    wl = workloads.Workload(name="rec_tiles", index=28, T=37, B=45, sizes=(60, 96, 128, 10), recurrent=(True, True),
-                            beta=(0.9, 0.92, 0.95), theta=1.0, surrogate="superspike", slope=25.0,
-                            precision=precision, rate_lo=0.05, rate_hi=0.2, rec_gain=1.0)
-    rep = full_step_parity(wl, w_gain=2.0)
-    assert rep["spike_rate"][0] > 0.005 and rep["spike_rate"][1] > 0.005
+def test_recurrent_both_sample_tilings(precision):
+    """Narrow recurrent layers whose rows are a multiple of 16 neurons run on tiles of 16 samples
+    (eight wavefronts of 16 neurons, V_t and S_t stored as whole rows through LDS); other widths
+    run the forward pass on tiles of 32 samples with stores from the accumulator layout.  Layers
+    of 96 and 128 neurons, then 72 and 40; a batch of 45 (tails of 13 samples in either tiling),
+    37 steps (both buffers of the stage, odd tail)."""
+    for sizes in ((60, 96, 128, 10), (60, 72, 40, 10)):
+        wl = workloads.Workload(name="rec_tiles", index=28, T=37, B=45, sizes=sizes, recurrent=(True, True),
+                                beta=(0.9, 0.92, 0.95), theta=1.0, surrogate="superspike", slope=25.0,
+                                precision=precision, rate_lo=0.05, rate_hi=0.2, rec_gain=1.0)
+        rep = full_step_parity(wl, w_gain=2.0)
+        assert rep["spike_rate"][0] > 0.005 and rep["spike_rate"][1] > 0.005
 
 
 @pytest.mark.parametrize("precision", ["fp32", "bf16"])
@@ -662,6 +627,26 @@ def test_error_paths():
     assert snn.lib.snn_set_tensor(snn.ctx, 17, 1, b.ctypes.data, b.nbytes - 4) == 3
     assert snn.lib.snn_get_tensor(snn.ctx, 18, 1, b.ctypes.data, b.nbytes) == 5          # learn_beta = 0
     assert snn.lib.snn_set_tensor(snn.ctx, 18, 1, b.ctypes.data, b.nbytes) in (2, 5)     # never settable
+    # kernel-selection options: unknown ids and values outside the documented range are refused
+    assert snn.get_option("layer_forward") == 4 and snn.get_option("stream_min_mb") == 128
+    assert snn.lib.snn_set_option(snn.ctx, 99, 0) == 2
+    assert snn.lib.snn_set_option(snn.ctx, -1, 0) == 2
+    for name, bad_value in (("layer_forward", 5), ("layer_pair", 2), ("layer_neurons", 96), ("tile_rows", 48),
+                            ("layer_max_neurons", 2048), ("stream_min_mb", -1), ("layer_min_batch", -3)):
+        before = snn.get_option(name)
+        with pytest.raises(SnnError) as e:
+            snn.set_option(name, bad_value)
+        assert e.value.status == 2 and snn.get_option(name) == before
+    snn.set_option("tile_rows", 64)
+    assert snn.get_option("tile_rows") == 64
+    assert snn.lib.snn_set_option(None, 0, 0) == 1
+    # setting the decays makes a previous forward pass stale
+    snn.forward(inp.X, inp.labels)
+    snn.set_tensor("beta", 1, np.full(wl.sizes[1], 0.5, np.float32))
+    with pytest.raises(SnnError) as e:
+        snn.backward()
+    assert e.value.status == 5
+    snn.forward(inp.X, inp.labels)
     # a workspace that is too small or misaligned is refused
     import torch
     from paper_2402_18994_amd import binding
@@ -686,6 +671,18 @@ def test_wide_ff1024_full_size_sampled():
     assert rep["spike_rate"][0] > 0.005 and rep["spike_rate"][1] > 0.005
 
 
+def test_wide_ff1024_full_size_whole_batch(capsys):
+    """700-1024-1024-20 at T = 256, B = 512, every sample: all forward tensors, all current and
+    spike gradients and the weight gradients against the oracle's own contraction over all
+    131 072 rows (the oracle holds about 11 GB of float64 traces for this and takes a minute or
+    two on the host cores, so the case reports its phases as it goes)."""
+    def say(text):
+        with capsys.disabled():
+            print(f"[wide_ff1024 whole batch] {text}", flush=True)
+    rep = full_step_parity(workloads.CONFIGS["wide_ff1024"], w_gain=3.0, check_sgd=False, say=say)
+    assert rep["spike_rate"][0] > 0.005 and rep["spike_rate"][1] > 0.005
+
+
 @pytest.mark.parametrize("name", ["table1_ff128", "table1_ff512"])
 def test_table1_shapes_full_size_sampled(name):
     """The shapes of the paper's timing runs (Table 1); at width 512 the tensors are 134 MB, the
@@ -695,12 +692,14 @@ def test_table1_shapes_full_size_sampled(name):
 
 
 def test_deep_rec2048_full_size_sampled():
-    """fp32 state with a fan-in of 2048 (+2048 recurrent) and a memory of 1/(1-beta) = 33 steps:
-    the rounding of the device's fp32 sums against the fp64 oracle reaches 1.3e-5 on a few of
-    the 3e6 sampled potentials, so potentials and the decision band are held to 5e-5 here
-    (the bound stated for bf16-product modes is 2e-2)."""
-    rep = sampled_parity(workloads.CONFIGS["deep_rec2048"], w_gain=3.0, n_samples=3, tol_state=5e-5, band=5e-5)
+    """16 of the 128 samples.  fp32 state with a fan-in of 2048 (+2048 recurrent) and a memory of
+    1/(1-beta) = 33 steps: the rounding of the device's fp32 sums against the fp64 oracle passes
+    1e-5 on a few of the sampled potentials, so potentials and the decision band are held to 5e-5
+    here (the bound stated for bf16-product modes is 2e-2); the report counts, per tensor, the
+    elements whose scaled error is above 1e-5."""
+    rep = sampled_parity(workloads.CONFIGS["deep_rec2048"], w_gain=3.0, n_samples=16, tol_state=5e-5, band=5e-5)
     assert rep["spike_rate"][0] > 0.005
+    assert sum(rep["above_1e-5"].values()) <= 1e-3 * rep["state_elements"]      # a few per ten thousand
 
 
 # ---------------------------------------------------------------- input packed along time
@@ -755,7 +754,7 @@ def test_integral_loss_headline_shape_long_horizon():
 
 
 # ---------------------------------------------------------------- per-neuron, trainable decay
-def beta_step_parity(wl, w_gain=2.5, lr=0.05):
+def beta_step_parity(wl, w_gain=2.5, lr=0.05, options=None):
     """Random per-neuron decays set through SNN_T_BETA; forward, backward with dL/dbeta, and
     the clipped update, against the oracle."""
     inp = workloads.generate(wl, w_gain=w_gain)
@@ -764,7 +763,7 @@ def beta_step_parity(wl, w_gain=2.5, lr=0.05):
     betas = [rng.uniform(0.7, 0.99, size=n).astype(np.float32) for n in wl.sizes[1:]]
     betas[0][:2] = (0.0, 1.0)                              # the ends of the interval
     from paper_2402_18994_amd.binding import from_workload
-    snn = from_workload(wl, inp, learn_beta=True)
+    snn = from_workload(wl, inp, learn_beta=True, options=options)
     print(f"\n[case] trainable beta {wl.name} T={wl.T} B={wl.B} sizes={wl.sizes} rec={wl.recurrent} {wl.precision} {wl.loss}",
           flush=True)
     for l, b in enumerate(betas):
@@ -805,6 +804,18 @@ def test_trainable_beta_recurrent_narrow_and_wide(precision):
                                 beta=(0.9,) * (len(sizes) - 1), theta=1.0, surrogate="arctan", slope=2.0,
                                 precision=precision, rate_lo=0.05, rate_hi=0.2, rec_gain=1.0)
         beta_step_parity(wl)
+
+
+def test_most_layers_with_trained_decays_and_recurrence():
+    """The largest admitted network (SNN_MAX_LAYERS = 12 weight matrices) with every hidden layer
+    recurrent and the decays trained: 35 gradient reductions (dW, dR and dbeta of every layer) in
+    one backward pass."""
+    sizes = (30,) + (24, 16) * 5 + (24,) + (6,)
+    assert len(sizes) == 13
+    wl = workloads.Workload(name="beta_deep", index=29, T=12, B=6, sizes=sizes, recurrent=(True,) * 11,
+                            beta=(0.9,) * 12, theta=1.0, surrogate="superspike", slope=25.0, precision="bf16",
+                            rate_lo=0.1, rate_hi=0.3, rec_gain=1.0)
+    beta_step_parity(wl, w_gain=3.0)
 
 
 def test_trainable_beta_large_update_is_clipped():

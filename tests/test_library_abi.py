@@ -72,6 +72,22 @@ def test_workspace_size_and_validation(lib):
     assert lib.snn_destroy(None) == 0
 
 
+def test_layer_count_limit(lib):
+    """SNN_MAX_LAYERS = 12 weight matrices are admitted (with recurrent layers and trained decays
+    that is 35 gradient reductions per backward pass, which the job lists hold), 13 are not."""
+    hdr = open(os.path.join(ROOT, "include", "snn.h")).read()
+    assert int(re.search(r"#define SNN_MAX_LAYERS (\d+)", hdr).group(1)) == 12
+    for L, ok in ((12, True), (13, False)):
+        kw = dict(sizes=(10,) + (8,) * (L - 1) + (3,), recurrent=(1,) * (L - 1), beta=(0.9,) * L)
+        if ok:
+            assert ws(lib, **kw) > 0
+        else:
+            with pytest.raises(binding.SnnError) as e:
+                ws(lib, **kw)
+            assert e.value.status == 2
+    assert lib.snn_set_option(None, 0, 0) == 1 and lib.snn_get_option(None, 0, None) == 1
+
+
 def test_headline_workspace_fits_one_gpu(lib):
     import workloads
     for name in workloads.CONFIG_ORDER:
