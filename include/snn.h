@@ -293,6 +293,28 @@ int32_t snn_run_step(snn_ctx *ctx, int32_t step, int32_t layer, const uint8_t *x
 int32_t snn_set_option(snn_ctx *ctx, int32_t option, int32_t value);
 int32_t snn_get_option(const snn_ctx *ctx, int32_t option, int32_t *value);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc) and have no workspace to hand over: the weight-gradient
+ * product of one layer, the step snn_run_step(SNN_STEP_WEIGHT_GRAD) runs inside a context, with
+ * the per-split partial sums in a static device array of SNN_STATIC_SCRATCH_BYTES that every GPU
+ * the library runs on holds until the process ends.  Allocates nothing, on the device or through
+ * any library.
+ *   S_dev   device, uint8 [M][K], values 0 or 1: the spikes below the layer, M = T*B rows
+ *   G_dev   device, float [M][N]: the layer's current gradients dL/dI
+ *   dW_dev  device, float [K][N]: receives S^T G (every element written; fp32-exact products,
+ *           fixed summation order, so the result is bit-repeatable)
+ * K and N multiples of 4; S_dev 4-byte aligned, G_dev and dW_dev 16-byte aligned (else
+ * SNN_ERR_ARG).  Sizes beyond the scratch are refused with SNN_ERR_UNSUPPORTED: M <=
+ * SNN_STATIC_MAX_ROWS, K*N <= SNN_STATIC_MAX_WEIGHTS, M*K < 2^31, M*N*4 < 2^31.  Enqueues on
+ * `hip_stream` (NULL = the default stream) and returns; runs on the current device.  All calls on
+ * one GPU share that GPU's array: calls that may overlap on one GPU (different streams, several
+ * threads) race and must be ordered by the caller.  Error text: snn_last_error(NULL). */
+#define SNN_STATIC_SCRATCH_BYTES (16u << 20)
+#define SNN_STATIC_MAX_ROWS (1 << 24)
+#define SNN_STATIC_MAX_WEIGHTS (1 << 21)
+int32_t snn_weight_grad_static(const uint8_t *S_dev, const float *G_dev, float *dW_dev, int64_t M,
+                               int32_t K, int32_t N, void *hip_stream);
+
 /* Event timer.  snn_profile_select(ctx, k, layer) brackets every later launch of kernel
  * class k (layer = 0: all layers, else that layer only) with a pair of HIP events on the
  * library's stream; k = SNN_K_NONE switches it off and clears the totals.

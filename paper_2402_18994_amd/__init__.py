@@ -5,4 +5,4 @@ The package is a thin ctypes binding over the C ABI declared in include/snn.h
 runs in the library's HIP kernels; Python only marshals arguments.
 """
 from .binding import (SNN, SnnError, load_library, library_path, SURROGATES, PRECISIONS,  # noqa: F401
-                      TENSORS, STEPS, KERNELS, OPTIONS)
+                      TENSORS, STEPS, KERNELS, OPTIONS, weight_grad_static)

@@ -30,6 +30,7 @@ OPTIONS = {"layer_forward": 0, "layer_pair": 1, "layer_reverse": 2, "top_scans":
            "layer_min_batch": 5, "layer_neurons": 6, "layer_max_neurons": 7, "stream_min_mb": 8,
            "stream_gemm": 9, "tile_rows": 10}
 CALIBRATE_US = 10.0
+STATIC_SCRATCH_BYTES = 16 << 20
 STATUS = {0: "SNN_OK", 1: "SNN_ERR_NULL", 2: "SNN_ERR_ARG", 3: "SNN_ERR_SHAPE", 4: "SNN_ERR_WORKSPACE",
           5: "SNN_ERR_STATE", 6: "SNN_ERR_HIP", 7: "SNN_ERR_UNSUPPORTED"}
 
@@ -75,6 +76,7 @@ def load_library():
     lib.snn_run_step.argtypes = [vp, i32, i32, vp, vp]
     lib.snn_set_option.argtypes = [vp, i32, i32]
     lib.snn_get_option.argtypes = [vp, i32, C.POINTER(i32)]
+    lib.snn_weight_grad_static.argtypes = [vp, vp, vp, C.c_int64, i32, i32, vp]
     lib.snn_profile_select.argtypes = [vp, i32, i32]
     lib.snn_profile_every.argtypes = [vp, i32]
     lib.snn_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -83,7 +85,7 @@ def load_library():
     lib.snn_last_error.restype = C.c_char_p
     for name in ("snn_workspace_bytes", "snn_init", "snn_forward", "snn_forward_packed", "snn_backward", "snn_sgd_step",
                  "snn_get_tensor", "snn_set_tensor", "snn_run_step", "snn_set_option", "snn_get_option",
-                 "snn_profile_select", "snn_profile_every", "snn_profile_read", "snn_destroy"):
+                 "snn_weight_grad_static", "snn_profile_select", "snn_profile_every", "snn_profile_read", "snn_destroy"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -280,6 +282,23 @@ class SNN:
             self.destroy()
         except Exception:
             pass
+
+
+def weight_grad_static(S, G, dW, stream=None):
+    """snn_weight_grad_static: dW [K,N] = S^T G for S uint8 [M,K] and G float32 [M,N], all cuda
+    tensors the caller owns; nothing is allocated."""
+    import torch
+    lib = load_library()
+    assert S.dtype == torch.uint8 and G.dtype == torch.float32 and dW.dtype == torch.float32
+    assert S.is_contiguous() and G.is_contiguous() and dW.is_contiguous()
+    M, K = S.shape
+    N = G.shape[1]
+    assert G.shape[0] == M and tuple(dW.shape) == (K, N)
+    st = stream if stream is not None else torch.cuda.current_stream(S.device)
+    with torch.cuda.device(S.device):
+        rc = lib.snn_weight_grad_static(S.data_ptr(), G.data_ptr(), dW.data_ptr(), M, K, N, C.c_void_p(st.cuda_stream))
+    if rc:
+        raise SnnError(rc, lib.snn_last_error(None).decode())
 
 
 def from_workload(wl, inputs, device: str = "cuda:0", learn_beta: bool = False, options=None) -> SNN:

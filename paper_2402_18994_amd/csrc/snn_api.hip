@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -20,6 +21,12 @@
 #include "rlif.hpp"
 
 using namespace snn;
+
+// Scratch of snn_weight_grad_static: the per-split partial sums of one weight-gradient product.
+// One copy per GPU, held from the moment the library is loaded on it until the process ends.
+// Host code never uses this name as an address: it asks for the device address once per device
+// (static_scratch) and passes that pointer on.
+static __device__ __align__(256) unsigned char scratch[SNN_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -139,6 +146,27 @@ int validate(const snn_config *cfg) {
     if ((long long)cfg->T * cfg->B * (cfg->sizes[i] + 8) * 4 >= (1ll << 31))
       return fail(nullptr, SNN_ERR_ARG, "T*B*sizes[%d] too large: a tensor must stay below 2 GiB", i);
   return SNN_OK;
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES] = {};
+hipError_t static_scratch(void **out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
 }
 
 // Contraction splits of the weight-gradient products, which share one launch with `tiles`
@@ -1138,6 +1166,10 @@ int32_t snn_init(const snn_config *cfg, void *workspace_dev, size_t workspace_by
         hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
       c->wall_khz = khz;
   }
+  {
+    void *unused = nullptr;                              // set-up of snn_weight_grad_static on this device
+    if ((e = static_scratch(&unused)) != hipSuccess) return bail(e, "hipGetSymbolAddress(scratch)");
+  }
   if ((e = hipMemsetAsync(c->ws, 0, c->ws_bytes, c->stream)) != hipSuccess) return bail(e, "hipMemsetAsync(workspace)");
   std::vector<std::vector<float>> beta_host(c->L);        // alive until the synchronisation below
   for (int l = 0; l < c->L; ++l) {
@@ -1387,6 +1419,64 @@ int32_t snn_run_step(snn_ctx *c, int32_t step, int32_t layer, const uint8_t *x_d
       return launch_input_grad(c, l);
     default: return fail(c, SNN_ERR_ARG, "unknown step %d", step);
   }
+}
+
+int32_t snn_weight_grad_static(const uint8_t *S_dev, const float *G_dev, float *dW_dev, int64_t M, int32_t K, int32_t N,
+                               void *hip_stream) {
+  if (!S_dev || !G_dev || !dW_dev) return fail(nullptr, SNN_ERR_NULL, "S_dev, G_dev or dW_dev is NULL");
+  if (M <= 0 || K <= 0 || N <= 0) return fail(nullptr, SNN_ERR_ARG, "M, K and N must be positive");
+  if (K % 4 || N % 4) return fail(nullptr, SNN_ERR_ARG, "K and N must be multiples of 4");
+  if ((uintptr_t)S_dev % 4 || (uintptr_t)G_dev % 16 || (uintptr_t)dW_dev % 16)
+    return fail(nullptr, SNN_ERR_ARG, "S_dev must be 4-byte aligned, G_dev and dW_dev 16-byte aligned");
+  if (M > SNN_STATIC_MAX_ROWS || (long long)K * N > SNN_STATIC_MAX_WEIGHTS || M * K >= (1ll << 31) || M * N * 4 >= (1ll << 31))
+    return fail(nullptr, SNN_ERR_UNSUPPORTED,
+                "beyond the static scratch: M <= %d, K * N <= %d, M * K < 2^31 and M * N * 4 < 2^31 are required",
+                SNN_STATIC_MAX_ROWS, SNN_STATIC_MAX_WEIGHTS);
+  hipStream_t st = (hipStream_t)hip_stream;
+  void *scr = nullptr;
+  hipError_t e = static_scratch(&scr);
+  if (e != hipSuccess) return fail(nullptr, SNN_ERR_HIP, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+  // Splits as for a context's products, but no more than fit the scratch (a single split needs
+  // none: it writes dW itself).  Every split writes its whole K x N slice before the reduction
+  // reads it, so nothing has to be cleared between calls.
+  const long long weights = (long long)K * N;
+  long long per = 0;
+  int splits = choose_splits(M, wgrad_tiles(K, N, false), weights, K + 4ll * N, &per);
+  const long long fit = (long long)SNN_STATIC_SCRATCH_BYTES / (weights * 4);
+  if (splits > fit) {
+    per = (long long)rup((size_t)((M + fit - 1) / fit), 64);
+    splits = (int)((M + per - 1) / per);
+  }
+  GemmArgs a;
+  memset(&a, 0, sizeof a);
+  a.P = S_dev; a.ldp = K; a.p_ivalid = K; a.p_bytes = (unsigned)(M * K);
+  a.Q = G_dev; a.ldq = N; a.q_bytes = (unsigned)(M * N * 4);
+  a.rows = K; a.cols = N; a.ldc = N; a.kc = (int)M;
+  a.kc_per_split = (int)per;
+  a.c_split_stride = weights;
+  a.C = splits > 1 ? (float *)scr : dW_dev;
+  GemmJobs jobs;
+  memset(&jobs, 0, sizeof jobs);
+  if (N <= 32) {
+    gemm_jobs_add<4, 1, 1, 1>(jobs, a, splits);
+    e = gemm_jobs_launch<P_T_U8, Q_T_F32S, EPI_STORE, 4, 1, 1, 1, 3, 1>(jobs, st);
+  } else if (N <= 64) {
+    gemm_jobs_add<2, 2, 2, 1>(jobs, a, splits);
+    e = gemm_jobs_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 1, 3, 1>(jobs, st);
+  } else {
+    gemm_jobs_add<2, 2, 2, 2>(jobs, a, splits);
+    e = gemm_jobs_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 2, 3, 1>(jobs, st);
+  }
+  if (e != hipSuccess) return fail(nullptr, SNN_ERR_HIP, "weight-gradient launch failed: %s", hipGetErrorString(e));
+  if (splits > 1) {
+    ReduceJobs red;
+    memset(&red, 0, sizeof red);
+    add_reduce_job(red, (const float *)scr, dW_dev, splits, weights);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(red.first_block[1]), dim3(256), 0, st, red, nullptr, nullptr, 0);
+    if ((e = hipGetLastError()) != hipSuccess)
+      return fail(nullptr, SNN_ERR_HIP, "reduction launch failed: %s", hipGetErrorString(e));
+  }
+  return SNN_OK;
 }
 
 int32_t snn_set_option(snn_ctx *c, int32_t option, int32_t value) {

@@ -85,6 +85,8 @@ def test_layer_count_limit(lib):
             with pytest.raises(binding.SnnError) as e:
                 ws(lib, **kw)
             assert e.value.status == 2
+    # the entry point without allocation validates its arguments before touching a device
+    assert lib.snn_weight_grad_static(None, None, None, C.c_int64(8), 8, 8, None) == 1
     assert lib.snn_set_option(None, 0, 0) == 1 and lib.snn_get_option(None, 0, None) == 1
 
 
