@@ -40,6 +40,15 @@ notes of this repository):
   * Recurrent LIF: V_{t+1} = beta V_t + I_t + S_t R - theta S_t with S_t the
     spikes just emitted from V_t; R is [from, to].  The paper only mentions
     recurrent models.
+  * Neurons with an adaptive firing threshold (Section 2.1.2 names them and gives no
+    equations): every neuron carries a second state A_t >= 0, A_0 = 0, that raises its
+    threshold, theta_t = theta + A_t.  Eq. 1-2 are applied with the threshold in force:
+        S_t = H(V_t - theta_t),   V_{t+1} = beta V_t + X_t - theta_t S_t,
+    and each spike raises the threshold by `adapt_step`, which then decays:
+        A_{t+1} = adapt_decay A_t + adapt_step S_t.
+    adapt_step = 0 is the plain LIF neuron.  The reverse sweep differentiates through both
+    states (A_t reaches the loss through the spike decision, the reset magnitude and
+    A_{t+1}); neither term is detached.  adapt_decay and adapt_step are fixed per layer.
   * "bf16" GEMM mode: the weight matrices (W and R) are rounded to bfloat16
     (round to nearest even) wherever they enter a product, forward and
     backward; 0/1 spikes are exact; all state, the surrogate, the loss, the
@@ -52,7 +61,7 @@ notes of this repository):
 
 parity unpinned (fixed by this file, nothing in the paper to check against):
 the arctan constant, the boxcar's width and height, the loss reduction (mean),
-the readout equation and the form of the integral loss.
+the readout equation, the form of the integral loss and the adaptive-threshold equations.
 """
 from __future__ import annotations
 
@@ -72,6 +81,8 @@ class Net:
     slope: float
     gemm_round: str = "none"          # "none" | "bf16"
     loss: str = "max"                 # "max" | "integral": how the readout trace is reduced over time
+    adapt_decay: Optional[Tuple[float, ...]] = None   # L-1 values in [0, 1]: decay of the threshold adaptation
+    adapt_step: Optional[Tuple[float, ...]] = None    # L-1 values >= 0: rise of the threshold per spike (0: plain LIF)
 
     @property
     def L(self) -> int:
@@ -145,6 +156,7 @@ class Trace:
     I: List[np.ndarray] = field(default_factory=list)   # per spiking layer [T,B,N]
     V: List[np.ndarray] = field(default_factory=list)   # potential the spike decision used
     S: List[np.ndarray] = field(default_factory=list)   # spikes (0/1, or smooth values)
+    A: List[np.ndarray] = field(default_factory=list)   # threshold adaptation in force at each step (zeros: plain LIF)
     J: Optional[np.ndarray] = None                      # readout currents [T,B,C]
     Y: Optional[np.ndarray] = None                      # readout trace    [T,B,C]
     z: Optional[np.ndarray] = None                      # max over time    [B,C]
@@ -167,6 +179,15 @@ def _betas(net: Net, betas):
     return out
 
 
+def _adaptation(net: Net):
+    """Per spiking layer (decay, step) of the threshold adaptation; (0, 0) for plain LIF layers."""
+    n = net.L - 1
+    dec = net.adapt_decay if net.adapt_decay is not None else (0.0,) * n
+    stp = net.adapt_step if net.adapt_step is not None else (0.0,) * n
+    assert len(dec) == n and len(stp) == n
+    return [(float(d), float(k)) for d, k in zip(dec, stp)]
+
+
 def forward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
             R: Sequence[Optional[np.ndarray]], labels: np.ndarray,
             forced: Optional[Forced] = None, smooth: bool = False,
@@ -184,36 +205,42 @@ def forward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
     Rq = [None if r is None else _q(net, np.asarray(r, np.float64)) for r in R]
     th = net.theta
     be = _betas(net, betas)
+    ad = _adaptation(net)
     tr = Trace()
     for l in range(L - 1):
         n = net.sizes[l + 1]
         tr.I.append(np.zeros((T, B, n)))
         tr.V.append(np.zeros((T, B, n)))
         tr.S.append(np.zeros((T, B, n)))
+        tr.A.append(np.zeros((T, B, n)))
     C = net.sizes[L]
     tr.J = np.zeros((T, B, C))
     tr.Y = np.zeros((T, B, C))
     v = [np.zeros((B, net.sizes[l + 1])) for l in range(L - 1)]   # V_0 = 0
+    a = [np.zeros((B, net.sizes[l + 1])) for l in range(L - 1)]   # A_0 = 0
     y = np.zeros((B, C))                                          # y_{-1} = 0
     Xf = X.astype(np.float64)
     for t in range(T):
         s_in = Xf[t]
         for l in range(L - 1):
             cur = s_in @ Wq[l]                       # Linear, no bias
+            th_t = th + a[l]                         # threshold in force (plain LIF: a = 0)
             if smooth:
-                s = smooth_step(net.surrogate, net.slope, v[l] - th)
+                s = smooth_step(net.surrogate, net.slope, v[l] - th_t)
             else:
-                s = (v[l] - th > 0.0).astype(np.float64)          # Eq. 1
+                s = (v[l] - th_t > 0.0).astype(np.float64)        # Eq. 1
             if forced and (l, t) in forced:
                 for (b, nn, val) in forced[(l, t)]:
                     s[b, nn] = float(val)
             tr.I[l][t] = cur
             tr.V[l][t] = v[l]
             tr.S[l][t] = s
-            nxt = be[l] * v[l] + cur - th * s                     # Eq. 2
+            tr.A[l][t] = a[l]
+            nxt = be[l] * v[l] + cur - th_t * s                   # Eq. 2
             if Rq[l] is not None:
                 nxt = nxt + s @ Rq[l]
             v[l] = nxt
+            a[l] = ad[l][0] * a[l] + ad[l][1] * s                 # each spike raises the threshold, which then decays
             s_in = s
         jt = s_in @ Wq[L - 1]
         y = be[L - 1] * y + jt
@@ -256,8 +283,10 @@ def backward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
     g[l] is dL/dV_{t+1} of spiking layer l while step t is processed.  A
     potential V_t reaches the loss through beta*V_t into V_{t+1} and through
     the spike S_t, which feeds the next layer at step t, the reset
-    -theta*S_t and (if recurrent) S_t R into V_{t+1}.  dS_t/dV_t is the
-    surrogate at V_t - theta.  beta_n multiplies V_t[:, n] on the way to
+    -theta_t*S_t, (if recurrent) S_t R into V_{t+1} and (if the threshold
+    adapts) adapt_step*S_t into A_{t+1}.  dS_t/dV_t is the surrogate at
+    V_t - theta_t, dS_t/dA_t its negative; A_t also scales the reset
+    (-S_t g) and decays into A_{t+1}.  ga[l] is dL/dA_{t+1}.  beta_n multiplies V_t[:, n] on the way to
     V_{t+1}[:, n], so dL/dbeta_n = sum over t and b of g_{t+1} V_t (readout:
     h_t y_{t-1}).
     """
@@ -267,6 +296,7 @@ def backward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
     Rq = [None if r is None else _q(net, np.asarray(r, np.float64)) for r in R]
     th = net.theta
     be = _betas(net, betas)
+    ad = _adaptation(net)
     Bn = B if batch_norm is None else batch_norm
     C = net.sizes[L]
 
@@ -290,6 +320,7 @@ def backward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
     Xf = X.astype(np.float64)
     h = np.zeros((B, C))                                   # dL/dy_{t+1} carried back
     g = [np.zeros((B, net.sizes[l + 1])) for l in range(L - 1)]
+    ga = [np.zeros((B, net.sizes[l + 1])) for l in range(L - 1)]
     tgrid = tr.tstar
     for t in range(T - 1, -1, -1):
         # readout: y_t = beta y_{t-1} + J_t; z picks y at tstar, or sums y over all steps
@@ -309,11 +340,13 @@ def backward(net: Net, X: np.ndarray, W: Sequence[np.ndarray],
             gr.dW[l] += s_in.T @ dIt
             if Rq[l] is not None:
                 gr.dR[l] += tr.S[l][t].T @ dIt
-            q = d_s - th * g[l]
+            A_t = tr.A[l][t] if tr.A else 0.0
+            q = d_s - (th + A_t) * g[l] + ad[l][1] * ga[l]     # dL/dS_t
             if Rq[l] is not None:
                 q = q + dIt @ Rq[l].T
-            sg = surrogate_grad(net.surrogate, net.slope, tr.V[l][t] - th)
+            sg = surrogate_grad(net.surrogate, net.slope, tr.V[l][t] - th - A_t)
             gr.dbeta[l] += (g[l] * tr.V[l][t]).sum(axis=0)      # V_{t+1} = beta V_t + ..
+            ga[l] = ad[l][0] * ga[l] - tr.S[l][t] * g[l] - sg * q
             g[l] = be[l] * g[l] + sg * q
             if l >= 1:
                 d_s = dIt @ Wq[l].T

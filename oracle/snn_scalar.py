@@ -27,13 +27,16 @@ def _surr(kind, k, x):
     raise ValueError(kind)
 
 
-def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels, loss_kind="max"):
+def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels, loss_kind="max",
+        adapt_decay=None, adapt_step=None):
     """Forward + backward.  X[t][b][i] in {0,1}; W[l][i][j]; R[l][i][j] or None.
 
     beta[l] is a number or a list with one decay per neuron of layer l.
     loss_kind: "max" (logit = largest readout value over time, gradient to the first step
     that reaches it) or "integral" (logit = the readout trace summed over time, so every
     step receives the logit's gradient).
+    adapt_decay, adapt_step: per spiking layer, the adaptive threshold theta + A with
+    A' = adapt_decay * A + adapt_step * spike (None: plain LIF).
 
     Returns a dict with V, S (per spiking layer, [t][b][n]), Y [t][b][c], loss,
     dW (per layer [i][j]), dR and dbeta (per layer, per neuron).
@@ -48,19 +51,23 @@ def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels, loss_k
     C = sizes[L]
     H = L - 1                                    # number of spiking layers
 
+    gam = list(adapt_decay) if adapt_decay is not None else [0.0] * H
+    kap = list(adapt_step) if adapt_step is not None else [0.0] * H
     V = [[[[0.0] * sizes[l + 1] for _ in range(B)] for _ in range(T)] for l in range(H)]
     S = [[[[0.0] * sizes[l + 1] for _ in range(B)] for _ in range(T)] for l in range(H)]
+    A = [[[[0.0] * sizes[l + 1] for _ in range(B)] for _ in range(T)] for l in range(H)]
     Y = [[[0.0] * C for _ in range(B)] for _ in range(T)]
 
     # ---------------- forward, one sample at a time ----------------
     for b in range(B):
         v = [[0.0] * sizes[l + 1] for l in range(H)]
+        adp = [[0.0] * sizes[l + 1] for l in range(H)]
         y = [0.0] * C
         for t in range(T):
             below = [float(X[t][b][i]) for i in range(sizes[0])]
             for l in range(H):
                 n_out = sizes[l + 1]
-                spikes = [1.0 if v[l][n] - theta > 0.0 else 0.0 for n in range(n_out)]
+                spikes = [1.0 if v[l][n] - (theta + adp[l][n]) > 0.0 else 0.0 for n in range(n_out)]
                 new_v = [0.0] * n_out
                 for n in range(n_out):
                     cur = 0.0
@@ -70,10 +77,12 @@ def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels, loss_k
                     if R[l] is not None:
                         for i in range(n_out):
                             rec += spikes[i] * R[l][i][n]
-                    new_v[n] = bt(l, n) * v[l][n] + cur + rec - theta * spikes[n]
+                    new_v[n] = bt(l, n) * v[l][n] + cur + rec - (theta + adp[l][n]) * spikes[n]
                     V[l][t][b][n] = v[l][n]
                     S[l][t][b][n] = spikes[n]
+                    A[l][t][b][n] = adp[l][n]
                 v[l] = new_v
+                adp[l] = [gam[l] * adp[l][n] + kap[l] * spikes[n] for n in range(n_out)]
                 below = spikes
             for c in range(C):
                 j = 0.0
@@ -111,6 +120,7 @@ def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels, loss_k
     for b in range(B):
         hy = [0.0] * C
         g = [[0.0] * sizes[l + 1] for l in range(H)]          # dL/dV_{t+1}
+        ga = [[0.0] * sizes[l + 1] for l in range(H)]         # dL/dA_{t+1}
         for t in range(T - 1, -1, -1):
             for c in range(C):
                 into_y = dz[b][c] if (loss_kind == "integral" or tstar[b][c] == t) else 0.0
@@ -130,8 +140,10 @@ def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels, loss_k
                     for n in range(n_out):
                         dW[l][i][n] += src[i] * d_i[n]
                 new_g = [0.0] * n_out
+                new_ga = [0.0] * n_out
                 for n in range(n_out):
-                    q = d_s[n] - theta * g[l][n]
+                    thr = theta + A[l][t][b][n]
+                    q = d_s[n] - thr * g[l][n] + kap[l] * ga[l][n]
                     if R[l] is not None:
                         for m_ in range(n_out):
                             q += g[l][m_] * R[l][n][m_]
@@ -139,8 +151,11 @@ def run(sizes, recurrent, beta, theta, surrogate, slope, X, W, R, labels, loss_k
                         for m_ in range(n_out):
                             dR[l][n][m_] += S[l][t][b][n] * d_i[m_]
                     dbeta[l][n] += g[l][n] * V[l][t][b][n]
-                    new_g[n] = bt(l, n) * g[l][n] + _surr(surrogate, slope, V[l][t][b][n] - theta) * q
+                    sg = _surr(surrogate, slope, V[l][t][b][n] - thr)
+                    new_g[n] = bt(l, n) * g[l][n] + sg * q
+                    new_ga[n] = gam[l] * ga[l][n] - S[l][t][b][n] * g[l][n] - sg * q
                 if l >= 1:
                     d_s = [sum(d_i[n] * W[l][i][n] for n in range(n_out)) for i in range(sizes[l])]
                 g[l] = new_g
-    return dict(V=V, S=S, Y=Y, z=z, tstar=tstar, loss=loss, dz=dz, dW=dW, dR=dR, dbeta=dbeta)
+                ga[l] = new_ga
+    return dict(V=V, S=S, A=A, Y=Y, z=z, tstar=tstar, loss=loss, dz=dz, dW=dW, dR=dR, dbeta=dbeta)

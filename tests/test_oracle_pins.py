@@ -422,6 +422,127 @@ def test_readout_dbeta_of_the_real_spiking_network_and_clip():
     assert np.allclose(same[0], betas[0] - 1e-3 * gr.dbeta[0], atol=0, rtol=0)
 
 
+# ---------------------------------------------------------------- adaptive threshold
+def adaptive_neuron(beta, theta, c, T, decay, step):
+    net = O.Net(sizes=(1, 1, 1), recurrent=(False,), beta=(beta, 0.5), theta=theta, surrogate="superspike",
+                slope=25.0, adapt_decay=(decay,), adapt_step=(step,))
+    return net, np.ones((T, 1, 1), np.uint8), [np.array([[c]]), np.array([[1.0]])], [None], np.array([0])
+
+
+@pytest.mark.parametrize("c_num,c_den,k_num,k_den", [(1, 2, 1, 2), (3, 4, 1, 4), (5, 8, 1, 8), (7, 4, 3, 8)])
+def test_adaptive_threshold_exact_rational(c_num, c_den, k_num, k_den):
+    """No leak, no decay of the adaptation (beta = 1, adapt_decay = 1), constant dyadic current:
+    everything is exactly representable, so Eq. 1-2 with the threshold in force can be iterated
+    in rational arithmetic and the float recursion must agree exactly.  The k-th spike is taken
+    at threshold theta + (k-1) step and removes that much charge, so after n spikes the charge
+    balance reads V_T = T c - n theta - step n (n-1) / 2, and the intervals between spikes do
+    not shrink (the neuron adapts)."""
+    from fractions import Fraction
+    T = 160
+    c, kappa, theta = Fraction(c_num, c_den), Fraction(k_num, k_den), Fraction(1)
+    net, X, W, R, lab = adaptive_neuron(1.0, 1.0, float(c), T, 1.0, float(kappa))
+    tr = O.forward(net, X, W, R, lab)
+    v, a, times = Fraction(0), Fraction(0), []
+    for t in range(T):
+        s = 1 if v > theta + a else 0
+        assert tr.S[0][t, 0, 0] == s and tr.V[0][t, 0, 0] == float(v) and tr.A[0][t, 0, 0] == float(a)
+        if s:
+            times.append(t)
+        v, a = v + c - (theta + a) * s, a + kappa * s
+    n = len(times)
+    assert n >= 5
+    assert tr.v_final[0][0, 0] == float(T * c - n * theta - kappa * n * (n - 1) / 2)
+    gaps = np.diff(times)
+    assert np.all(np.diff(gaps) >= -1) and gaps[-1] > gaps[0]      # slows down (up to the grid of whole steps)
+
+
+def test_adaptation_is_a_filter_of_the_spikes_and_charge_balance():
+    """A_t is a first-order filter of the layer's own spike train, one step delayed (library
+    filter), the spike decision is V_t > theta + A_t, and the potential at the end balances the
+    currents against the resets at the threshold in force."""
+    rng = np.random.default_rng(71)
+    net, X, W, R, lab = tiny_net(rng, sizes=(12, 9, 7, 4), recurrent=(True, False), T=40, B=3, surrogate="superspike",
+                                 slope=25.0, gain=3.0, adapt_decay=(0.9, 0.7), adapt_step=(0.4, 0.25))
+    tr = O.forward(net, X, W, R, lab)
+    T = X.shape[0]
+    for l in range(2):
+        assert tr.S[l].sum() > 10
+        filt = scipy.signal.lfilter([0.0, net.adapt_step[l]], [1.0, -net.adapt_decay[l]], tr.S[l], axis=0)
+        assert np.allclose(tr.A[l], filt, atol=1e-13)
+        assert np.array_equal(tr.S[l], (tr.V[l] > net.theta + tr.A[l]).astype(float))
+        drive = tr.I[l] - (net.theta + tr.A[l]) * tr.S[l]
+        if R[l] is not None:
+            drive = drive + tr.S[l] @ R[l]
+        w = net.beta[l] ** (T - 1 - np.arange(T))
+        assert np.allclose(np.tensordot(w, drive, axes=(0, 0)), tr.v_final[l], atol=1e-12)
+    # the adaptation lowers the firing rate of the same network
+    import dataclasses
+    plain = O.forward(dataclasses.replace(net, adapt_step=(0.0, 0.0)), X, W, R, lab)
+    assert plain.S[0].sum() > tr.S[0].sum()
+
+
+def test_zero_adaptation_step_is_the_plain_neuron():
+    rng = np.random.default_rng(72)
+    net, X, W, R, lab = tiny_net(rng, sizes=(9, 7, 6, 4), recurrent=(False, True), T=14, B=4, surrogate="arctan",
+                                 slope=2.0, gain=2.5)
+    import dataclasses
+    zero = dataclasses.replace(net, adapt_decay=(0.8, 0.9), adapt_step=(0.0, 0.0))
+    a, b = O.forward(net, X, W, R, lab), O.forward(zero, X, W, R, lab)
+    assert all(np.array_equal(x, y) for x, y in zip(a.V, b.V)) and a.loss == b.loss
+    ga, gb = O.backward(net, X, W, R, lab, a), O.backward(zero, X, W, R, lab, b)
+    assert all(np.array_equal(x, y) for x, y in zip(ga.dW, gb.dW))
+    assert np.array_equal(ga.dR[1], gb.dR[1])
+
+
+@pytest.mark.parametrize("surrogate,slope", [("sigmoid", 3.0), ("superspike", 4.0), ("arctan", 2.0)])
+@pytest.mark.parametrize("recurrent", [(False, False), (True, True)])
+def test_adaptive_backward_is_exact_gradient_of_smoothed_network(surrogate, slope, recurrent):
+    """Central differences on every weight of the smoothed network with adapting thresholds: the
+    paths through the spike decision (-surrogate), through the reset magnitude (-S g) and through
+    the adaptation's own memory must all be in the reverse sweep, with the right signs."""
+    rng = np.random.default_rng(73)
+    net, X, W, R, lab = tiny_net(rng, recurrent=recurrent, surrogate=surrogate, slope=slope,
+                                 adapt_decay=(0.85, 0.6), adapt_step=(0.5, 0.3))
+    tr = O.forward(net, X, W, R, lab, smooth=True)
+    assert np.abs(tr.A[0]).max() > 0.1
+    gr = O.backward(net, X, W, R, lab, tr)
+    dW, dR = fd_grads(net, X, W, R, lab)
+    for l in range(net.L):
+        assert np.abs(gr.dW[l]).max() > 1e-4
+        assert np.allclose(gr.dW[l], dW[l], rtol=2e-6, atol=2e-9), (l, np.abs(gr.dW[l] - dW[l]).max())
+    for l in range(net.L - 1):
+        if R[l] is not None:
+            assert np.allclose(gr.dR[l], dR[l], rtol=2e-6, atol=2e-9)
+    # the sweep that ignores the adaptation is a different (wrong) gradient here
+    import dataclasses
+    wrong = O.backward(dataclasses.replace(net, adapt_step=(0.0, 0.0)), X, W, R, lab, tr)
+    assert not np.allclose(wrong.dW[0], dW[0], rtol=1e-3, atol=1e-6)
+
+
+@pytest.mark.parametrize("recurrent", [(False, False), (True, False)])
+def test_adaptive_vectorised_oracle_equals_scalar_brute_force(recurrent):
+    rng = np.random.default_rng(74)
+    net, X, W, R, lab = tiny_net(rng, sizes=(6, 5, 4, 3), recurrent=recurrent, T=12, B=3, surrogate="superspike",
+                                 slope=25.0, gain=3.0, adapt_decay=(0.9, 0.5), adapt_step=(0.3, 0.6))
+    betas = _random_betas(rng, net)
+    tr = O.forward(net, X, W, R, lab, betas=betas)
+    gr = O.backward(net, X, W, R, lab, tr, betas=betas)
+    assert tr.S[0].sum() > 0 and tr.S[1].sum() > 0
+    ref = snn_scalar.run(net.sizes, net.recurrent, [b.tolist() for b in betas], net.theta, "superspike", 25.0,
+                         X.tolist(), [w.tolist() for w in W], [None if r is None else r.tolist() for r in R],
+                         lab.tolist(), adapt_decay=net.adapt_decay, adapt_step=net.adapt_step)
+    for l in range(2):
+        assert np.allclose(tr.V[l], np.array(ref["V"][l]), atol=1e-12)
+        assert np.allclose(tr.A[l], np.array(ref["A"][l]), atol=1e-12)
+        assert np.array_equal(tr.S[l], np.array(ref["S"][l]))
+    assert tr.loss == pytest.approx(ref["loss"], abs=1e-12)
+    for l in range(3):
+        assert np.allclose(gr.dW[l], np.array(ref["dW"][l]), atol=1e-12)
+        assert np.allclose(gr.dbeta[l], np.array(ref["dbeta"][l]), atol=1e-12)
+    if R[0] is not None:
+        assert np.allclose(gr.dR[0], np.array(ref["dR"][0]), atol=1e-12)
+
+
 # ---------------------------------------------------------------- invariants
 def test_batch_permutation_duplication_and_time_shift():
     rng = np.random.default_rng(41)
