@@ -113,6 +113,18 @@ typedef struct {
                                 dL/dbeta, snn_sgd_step also does beta <- clip(beta - lr
                                 dbeta, 0, 1).  Either way every neuron (and readout class)
                                 has its own decay, initialised from `beta` and settable   */
+  const float *adapt_decay;  /* host, L-1 entries in [0,1], or NULL                      */
+  const float *adapt_step;   /* host, L-1 entries >= 0, or NULL (both NULL: no layer adapts).
+                                Neurons with an adaptive firing threshold (named in Section
+                                2.1.2, which gives no equations; this is the reading built
+                                here): a spiking layer with adapt_step > 0 carries a second
+                                state A_t >= 0, A_0 = 0, and Eq. 1-2 take the threshold in
+                                force theta_t = theta + A_t:
+                                  S_t = H(V_t - theta_t), V_{t+1} = beta V_t + X_t - theta_t S_t,
+                                  A_{t+1} = adapt_decay A_t + adapt_step S_t.
+                                The reverse sweep runs through both states.  adapt_step = 0:
+                                plain LIF.  Feed-forward layers only: a layer that is both
+                                recurrent and adaptive is refused with SNN_ERR_UNSUPPORTED.  */
 } snn_config;
 
 /* Tensors that snn_get_tensor / snn_set_tensor move.  `layer` is 1-based as in the text:
@@ -137,16 +149,18 @@ typedef enum {
   SNN_T_LOSS = 15,       /* 1 float                                                        */
   SNN_T_LOSS_PER_SAMPLE = 16, /* [B]                                                       */
   SNN_T_BETA = 17,       /* [N_l] decays of layer l (1..L, L = readout), in [0,1] (settable)   */
-  SNN_T_GRAD_BETA = 18   /* [N_l] dL/dbeta of layer l; needs learn_beta (else SNN_ERR_STATE)   */
+  SNN_T_GRAD_BETA = 18,  /* [N_l] dL/dbeta of layer l; needs learn_beta (else SNN_ERR_STATE)   */
+  SNN_T_ADAPTATION = 19  /* A^l [T][B][N_l]: threshold adaptation in force at each step, layers
+                            with adapt_step > 0 only (else SNN_ERR_ARG) (settable)            */
 } snn_tensor;
 
 /* Single steps of the path, for kernel-level tests on imposed inputs (snn_run_step). */
 typedef enum {
   SNN_STEP_CURRENT_GEMM = 0,   /* I^l = S^{l-1} W^l (layer L: J = S^{L-1} W^L)             */
-  SNN_STEP_LIF_FORWARD = 1,    /* I^l -> V^l, S^l (recurrent layers: includes S R)         */
+  SNN_STEP_LIF_FORWARD = 1,    /* I^l -> V^l, S^l (recurrent layers: includes S R; adaptive: A^l) */
   SNN_STEP_READOUT_FORWARD = 2,/* J -> Y, z, t*, loss, dz                                  */
   SNN_STEP_READOUT_REVERSE = 3,/* dz, t* -> dJ                                             */
-  SNN_STEP_LIF_REVERSE = 4,    /* dS^l, V^l -> dI^l                                        */
+  SNN_STEP_LIF_REVERSE = 4,    /* dS^l, V^l (adaptive layers: and A^l) -> dI^l             */
   SNN_STEP_WEIGHT_GRAD = 5,    /* dW^l = S^{l-1}^T dI^l (and dR^l); layer L uses dJ        */
   SNN_STEP_INPUT_GRAD = 6      /* dS^{l-1} = dI^l W^l^T, l >= 2                            */
 } snn_step;

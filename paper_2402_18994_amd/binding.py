@@ -20,7 +20,7 @@ LOSSES = {"max": 0, "integral": 1}
 TENSORS = {"weight": 0, "rweight": 1, "grad_w": 2, "grad_r": 3, "current": 4, "membrane": 5,
            "spikes": 6, "d_spikes": 7, "d_current": 8, "readout_current": 9, "readout_trace": 10,
            "logits": 11, "argmax_t": 12, "d_logits": 13, "d_readout_current": 14, "loss": 15,
-           "loss_per_sample": 16, "beta": 17, "grad_beta": 18}
+           "loss_per_sample": 16, "beta": 17, "grad_beta": 18, "adaptation": 19}
 STEPS = {"current_gemm": 0, "lif_forward": 1, "readout_forward": 2, "readout_reverse": 3,
          "lif_reverse": 4, "weight_grad": 5, "input_grad": 6}
 KERNELS = {"none": -1, "current_gemm": 0, "lif_forward": 1, "rlif_forward": 2, "readout_forward": 3,
@@ -45,7 +45,8 @@ class snn_config(C.Structure):
     _fields_ = [("T", C.c_int32), ("B", C.c_int32), ("n_layers", C.c_int32),
                 ("sizes", C.POINTER(C.c_int32)), ("recurrent", C.POINTER(C.c_uint8)),
                 ("beta", C.POINTER(C.c_float)), ("threshold", C.c_float), ("surrogate", C.c_int32),
-                ("slope", C.c_float), ("precision", C.c_int32), ("loss", C.c_int32), ("learn_beta", C.c_int32)]
+                ("slope", C.c_float), ("precision", C.c_int32), ("loss", C.c_int32), ("learn_beta", C.c_int32),
+                ("adapt_decay", C.POINTER(C.c_float)), ("adapt_step", C.POINTER(C.c_float))]
 
 
 def library_path() -> str:
@@ -95,8 +96,12 @@ class _Cfg:
     """Keeps the arrays a snn_config points to alive."""
 
     def __init__(self, T, B, sizes, recurrent, beta, theta, surrogate, slope, precision, loss="max",
-                 learn_beta=False):
+                 learn_beta=False, adapt_decay=None, adapt_step=None):
         L = len(sizes) - 1
+        self.adapt_decay = self.adapt_step = None
+        if adapt_step is not None:
+            self.adapt_decay = (C.c_float * max(1, L - 1))(*[float(x) for x in adapt_decay])
+            self.adapt_step = (C.c_float * max(1, L - 1))(*[float(x) for x in adapt_step])
         self.sizes = (C.c_int32 * (L + 1))(*[int(s) for s in sizes])
         rec = list(recurrent) if recurrent is not None else [0] * (L - 1)
         self.rec = (C.c_uint8 * max(1, L - 1))(*[int(bool(r)) for r in rec])
@@ -105,12 +110,15 @@ class _Cfg:
                             SURROGATES[surrogate] if isinstance(surrogate, str) else int(surrogate),
                             float(slope),
                             PRECISIONS[precision] if isinstance(precision, str) else int(precision),
-                            LOSSES[loss] if isinstance(loss, str) else int(loss), int(bool(learn_beta)))
+                            LOSSES[loss] if isinstance(loss, str) else int(loss), int(bool(learn_beta)),
+                            self.adapt_decay, self.adapt_step)
 
 
-def workspace_bytes(T, B, sizes, recurrent, beta, theta, surrogate, slope, precision, loss="max") -> int:
+def workspace_bytes(T, B, sizes, recurrent, beta, theta, surrogate, slope, precision, loss="max",
+                    adapt_decay=None, adapt_step=None) -> int:
     lib = load_library()
-    cfg = _Cfg(T, B, sizes, recurrent, beta, theta, surrogate, slope, precision, loss)
+    cfg = _Cfg(T, B, sizes, recurrent, beta, theta, surrogate, slope, precision, loss,
+               adapt_decay=adapt_decay, adapt_step=adapt_step)
     n = C.c_size_t(0)
     rc = lib.snn_workspace_bytes(C.byref(cfg.c), C.byref(n))
     if rc:
@@ -123,7 +131,8 @@ class SNN:
 
     def __init__(self, T, B, sizes, recurrent, beta, theta, surrogate, slope, precision,
                  W: Sequence[np.ndarray], R: Optional[Sequence[Optional[np.ndarray]]] = None,
-                 device: str = "cuda:0", loss: str = "max", learn_beta: bool = False, options=None):
+                 device: str = "cuda:0", loss: str = "max", learn_beta: bool = False, options=None,
+                 adapt_decay=None, adapt_step=None):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no HIP device: this library has no CPU path")
@@ -134,7 +143,8 @@ class SNN:
         self.L = len(self.sizes) - 1
         self.recurrent = [bool(r) for r in (recurrent if recurrent is not None else [0] * (self.L - 1))]
         self.precision = precision
-        self._cfg = _Cfg(T, B, sizes, self.recurrent, beta, theta, surrogate, slope, precision, loss, learn_beta)
+        self._cfg = _Cfg(T, B, sizes, self.recurrent, beta, theta, surrogate, slope, precision, loss, learn_beta,
+                         adapt_decay, adapt_step)
         n = C.c_size_t(0)
         self._chk(self.lib.snn_workspace_bytes(C.byref(self._cfg.c), C.byref(n)), None)
         self.workspace = torch.empty(n.value, dtype=torch.uint8, device=self.device)
@@ -182,7 +192,7 @@ class SNN:
             return (s[layer - 1], s[layer]), np.float32
         if name in ("rweight", "grad_r"):
             return (s[layer], s[layer]), np.float32
-        if name in ("current", "membrane", "d_spikes", "d_current"):
+        if name in ("current", "membrane", "d_spikes", "d_current", "adaptation"):
             return (T, B, s[layer]), np.float32
         if name == "spikes":
             return (T, B, s[layer]), np.uint8
@@ -305,4 +315,5 @@ def from_workload(wl, inputs, device: str = "cuda:0", learn_beta: bool = False, 
     """Build an SNN for a workloads.Workload and the weights of a workloads.Inputs."""
     return SNN(wl.T, wl.B, wl.sizes, wl.recurrent, wl.beta, wl.theta, wl.surrogate, wl.slope,
                wl.precision, inputs.W, inputs.R, device=device, loss=getattr(wl, "loss", "max"),
-               learn_beta=learn_beta, options=options)
+               learn_beta=learn_beta, options=options, adapt_decay=getattr(wl, "adapt_decay", None),
+               adapt_step=getattr(wl, "adapt_step", None))

@@ -42,10 +42,14 @@ template <int VEC> __device__ __forceinline__ void st_spikes(rsrc_t r, int voff,
 // memory-side) are read non-temporally: 8 % (forward) and 11 % (reverse) faster at 537 MB per
 // tensor.  Smaller ones are still warm from the kernel that wrote them, and the same hint
 // costs 10 % there.
-template <int VEC, int U, int POL>
+// ADAPT: neurons with an adaptive firing threshold.  A second state A (A_0 = 0) raises the
+// threshold, theta_t = theta + A_t; the spike and the reset take theta_t, then
+// A_{t+1} = gamma A_t + kappa S_t.  A_t is stored beside V_t (the reverse scan needs both).
+template <int VEC, int U, int POL, bool ADAPT>
 __global__ __launch_bounds__(256) void lif_forward_kernel(const float *__restrict__ I, float *__restrict__ V,
                                                           uint8_t *__restrict__ S, int T, int stride,
-                                                          const float *__restrict__ beta_v, int ld, float theta) {
+                                                          const float *__restrict__ beta_v, int ld, float theta,
+                                                          float *__restrict__ A, float gamma, float kappa) {
   const int p = (blockIdx.x * blockDim.x + threadIdx.x) * VEC;
   if (p >= stride) return;
   float beta[VEC];                                   // one decay per neuron (column p % ld)
@@ -53,10 +57,11 @@ __global__ __launch_bounds__(256) void lif_forward_kernel(const float *__restric
   for (int i = 0; i < VEC; ++i) beta[i] = beta_v[p % ld + i];
   const rsrc_t rI = make_rsrc(I, (unsigned)T * stride * 4u), rV = make_rsrc(V, (unsigned)T * stride * 4u);
   const rsrc_t rS = make_rsrc(S, (unsigned)T * stride);
+  const rsrc_t rA = make_rsrc(A, ADAPT ? (unsigned)T * stride * 4u : 0u);
   const int vo4 = p * 4, vo1 = p, row4 = stride * 4;
-  float v[VEC];
+  float v[VEC], ad[VEC];
 #pragma unroll
-  for (int i = 0; i < VEC; ++i) v[i] = 0.f;
+  for (int i = 0; i < VEC; ++i) v[i] = ad[i] = 0.f;
   float a[U][VEC], b[U][VEC];
 
   auto fetch = [&](float (&buf)[U][VEC], int t0) {
@@ -65,12 +70,25 @@ __global__ __launch_bounds__(256) void lif_forward_kernel(const float *__restric
   };
   auto step = [&](const float (&cur)[VEC], int t) {
     uint32_t s[VEC], w[VEC];
+    float thr[VEC];
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) { s[i] = v[i] > theta ? 1u : 0u; w[i] = __float_as_uint(v[i]); }
+    for (int i = 0; i < VEC; ++i) {
+      thr[i] = ADAPT ? theta + ad[i] : theta;
+      s[i] = v[i] > thr[i] ? 1u : 0u;
+      w[i] = __float_as_uint(v[i]);
+    }
     stv<VEC>(rV, vo4, t * row4, w);
     st_spikes<VEC>(rS, vo1, t * stride, s);
+    if (ADAPT) {
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) v[i] = beta[i] * v[i] + cur[i] - (s[i] ? theta : 0.f);
+      for (int i = 0; i < VEC; ++i) w[i] = __float_as_uint(ad[i]);
+      stv<VEC>(rA, vo4, t * row4, w);
+    }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+      v[i] = beta[i] * v[i] + cur[i] - (s[i] ? thr[i] : 0.f);
+      if (ADAPT) ad[i] = gamma * ad[i] + (s[i] ? kappa : 0.f);
+    }
   };
   fetch(a, 0);
   int t0 = 0;
@@ -95,6 +113,11 @@ __global__ __launch_bounds__(256) void lif_forward_kernel(const float *__restric
 // g = 0; for t = T-1..0: dI_t = g; g = beta g + surr(V_t - theta) (dS_t - theta g).
 // With db_part: also dL/dbeta per chain, sum_t g_{t+1} V_t (V_{t+1} = beta V_t + ..).
 // dI is written as fp32 or, when HL, in the hi/lo form the bfloat16 products read.
+// ADAPT (adaptive threshold, see lif_forward_kernel): with theta_t = theta + A_t and ga the
+// gradient of A_{t+1}: q = dS_t - theta_t g + kappa ga; the spike decision's derivative is the
+// surrogate at V_t - theta_t with respect to V_t and its negative with respect to A_t, so
+// ga <- gamma ga - S_t g - surr q (S_t = [V_t > theta_t], the reset's factor) and
+// g <- beta g + surr q.
 template <int SURR> __device__ __forceinline__ float surr(float k, float x) {
   if (SURR == 0) { float d = 1.0f + k * fabsf(x); return 1.0f / (d * d); }
   if (SURR == 1) { float u = 1.5707963267948966f * k * x; return (0.5f * k) / (1.0f + u * u); }
@@ -115,11 +138,12 @@ template <int SURR> __device__ __forceinline__ float surr_rcp(float k, float x) 
   return surr<SURR>(k, x);
 }
 
-template <int VEC, int U, int SURR, bool HL, int POL>
+template <int VEC, int U, int SURR, bool HL, int POL, bool ADAPT>
 __global__ __launch_bounds__(256) void lif_reverse_kernel(const float *__restrict__ dS, const float *__restrict__ V,
                                                           uint32_t *__restrict__ dI, int T, int stride,
                                                           const float *__restrict__ beta_v, int ld, float theta,
-                                                          float slope, float *__restrict__ db_part) {
+                                                          float slope, float *__restrict__ db_part,
+                                                          const float *__restrict__ A, float gamma, float kappa) {
   const int p = (blockIdx.x * blockDim.x + threadIdx.x) * VEC;
   if (p >= stride) return;
   float beta[VEC], db[VEC];                          // decay per neuron; sum over t of g_{t+1} V_t
@@ -127,22 +151,25 @@ __global__ __launch_bounds__(256) void lif_reverse_kernel(const float *__restric
   for (int i = 0; i < VEC; ++i) { beta[i] = beta_v[p % ld + i]; db[i] = 0.f; }
   const unsigned bytes = (unsigned)T * stride * 4u;
   const rsrc_t rdS = make_rsrc(dS, bytes), rV = make_rsrc(V, bytes), rdI = make_rsrc(dI, bytes);
+  const rsrc_t rA = make_rsrc(A, ADAPT ? bytes : 0u);
   const int vo4 = p * 4, row4 = stride * 4;
-  float g[VEC];
+  constexpr int UA = ADAPT ? U : 1;                  // the adaptation's rows are only fetched when it exists
+  float g[VEC], ga[VEC];
 #pragma unroll
-  for (int i = 0; i < VEC; ++i) g[i] = 0.f;
-  float a_ds[U][VEC], a_v[U][VEC], b_ds[U][VEC], b_v[U][VEC];
+  for (int i = 0; i < VEC; ++i) g[i] = ga[i] = 0.f;
+  float a_ds[U][VEC], a_v[U][VEC], b_ds[U][VEC], b_v[U][VEC], a_a[UA][VEC], b_a[UA][VEC];
 
   // a block covers steps thi, thi-1, .., thi-U+1 (clamped at 0: re-reads, never used)
-  auto fetch = [&](float (&bds)[U][VEC], float (&bv)[U][VEC], int thi) {
+  auto fetch = [&](float (&bds)[U][VEC], float (&bv)[U][VEC], float (&ba)[UA][VEC], int thi) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int so = max(thi - u, 0) * row4;
       ldv<VEC, POL>(bds[u], rdS, vo4, so);
       ldv<VEC, POL>(bv[u], rV, vo4, so);
+      if (ADAPT) ldv<VEC, POL>(ba[u % UA], rA, vo4, so);
     }
   };
-  auto step = [&](const float (&ds)[VEC], const float (&vv)[VEC], int t) {
+  auto step = [&](const float (&ds)[VEC], const float (&vv)[VEC], const float (&aa)[VEC], int t) {
     uint32_t w[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; ++i) w[i] = HL ? pack_hl(g[i]) : __float_as_uint(g[i]);
@@ -150,25 +177,32 @@ __global__ __launch_bounds__(256) void lif_reverse_kernel(const float *__restric
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
       db[i] += g[i] * vv[i];
-      g[i] = beta[i] * g[i] + surr_rcp<SURR>(slope, vv[i] - theta) * (ds[i] - theta * g[i]);
+      if (ADAPT) {
+        const float thr = theta + aa[i], x = vv[i] - thr;
+        const float sq = surr_rcp<SURR>(slope, x) * (ds[i] - thr * g[i] + kappa * ga[i]);
+        ga[i] = gamma * ga[i] - (x > 0.f ? g[i] : 0.f) - sq;
+        g[i] = beta[i] * g[i] + sq;
+      } else {
+        g[i] = beta[i] * g[i] + surr_rcp<SURR>(slope, vv[i] - theta) * (ds[i] - theta * g[i]);
+      }
     }
   };
-  fetch(a_ds, a_v, T - 1);
+  fetch(a_ds, a_v, a_a, T - 1);
   int thi = T - 1;
   for (; thi - 2 * U + 1 >= 0; thi -= 2 * U) {
-    fetch(b_ds, b_v, thi - U);
+    fetch(b_ds, b_v, b_a, thi - U);
 #pragma unroll
-    for (int u = 0; u < U; ++u) step(a_ds[u], a_v[u], thi - u);
-    fetch(a_ds, a_v, thi - 2 * U);
+    for (int u = 0; u < U; ++u) step(a_ds[u], a_v[u], a_a[u % UA], thi - u);
+    fetch(a_ds, a_v, a_a, thi - 2 * U);
 #pragma unroll
-    for (int u = 0; u < U; ++u) step(b_ds[u], b_v[u], thi - U - u);
+    for (int u = 0; u < U; ++u) step(b_ds[u], b_v[u], b_a[u % UA], thi - U - u);
   }
   if (thi >= 0) {
-    fetch(b_ds, b_v, thi - U);
+    fetch(b_ds, b_v, b_a, thi - U);
 #pragma unroll
-    for (int u = 0; u < U; ++u) if (thi - u >= 0) step(a_ds[u], a_v[u], thi - u);
+    for (int u = 0; u < U; ++u) if (thi - u >= 0) step(a_ds[u], a_v[u], a_a[u % UA], thi - u);
 #pragma unroll
-    for (int u = 0; u < U; ++u) if (thi - U - u >= 0) step(b_ds[u], b_v[u], thi - U - u);
+    for (int u = 0; u < U; ++u) if (thi - U - u >= 0) step(b_ds[u], b_v[u], b_a[u % UA], thi - U - u);
   }
   if (db_part) {                                     // per sample; summed over the batch by the reduction launch
 #pragma unroll

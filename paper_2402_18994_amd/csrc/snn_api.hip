@@ -36,6 +36,9 @@ struct Layer {
   int K = 0, N = 0;        // fan-in, fan-out
   int ld = 0;              // padded fan-out of the activation tensors (multiple of 8)
   bool recurrent = false, spiking = false;
+  bool adaptive = false;   // adaptive firing threshold: theta + A_t, A' = gamma A + kappa S
+  float gamma = 0.f, kappa = 0.f;
+  float *A = nullptr;      // [M][ld] adaptation in force at each step (adaptive layers only)
   float beta = 0.f;        // initial decay of the layer (config); the live values are beta_v
   float *beta_v = nullptr; // [ld] one decay per neuron / class (padding 0)
   float *dbeta = nullptr;  // [ld] gradient of the decays (only with learn_beta)
@@ -141,6 +144,15 @@ int validate(const snn_config *cfg) {
   if (cfg->precision < 0 || cfg->precision > 1) return fail(nullptr, SNN_ERR_ARG, "unknown precision");
   if (cfg->loss < 0 || cfg->loss > 1) return fail(nullptr, SNN_ERR_ARG, "unknown loss");
   if (cfg->learn_beta < 0 || cfg->learn_beta > 1) return fail(nullptr, SNN_ERR_ARG, "learn_beta must be 0 or 1");
+  if ((cfg->adapt_decay == nullptr) != (cfg->adapt_step == nullptr))
+    return fail(nullptr, SNN_ERR_NULL, "adapt_decay and adapt_step must both be given or both be NULL");
+  if (cfg->adapt_step)
+    for (int i = 0; i < cfg->n_layers - 1; ++i) {
+      if (!(cfg->adapt_decay[i] >= 0.f && cfg->adapt_decay[i] <= 1.f)) return fail(nullptr, SNN_ERR_ARG, "adapt_decay[%d] outside [0,1]", i);
+      if (!(cfg->adapt_step[i] >= 0.f)) return fail(nullptr, SNN_ERR_ARG, "adapt_step[%d] is negative", i);
+      if (cfg->adapt_step[i] > 0.f && cfg->recurrent && cfg->recurrent[i])
+        return fail(nullptr, SNN_ERR_UNSUPPORTED, "layer %d is recurrent and adaptive: adaptive thresholds are built for feed-forward layers", i + 1);
+    }
   if ((long long)cfg->T * cfg->B > (1ll << 30)) return fail(nullptr, SNN_ERR_ARG, "T*B too large");
   for (int i = 0; i <= cfg->n_layers; ++i)      // byte offsets into one tensor are 31-bit
     if ((long long)cfg->T * cfg->B * (cfg->sizes[i] + 8) * 4 >= (1ll << 31))
@@ -293,6 +305,7 @@ void carve(snn_ctx &c, Carver &cv) {
       y.S = cv.take<uint8_t>(M * y.ld);
       y.dS = cv.take<float>(M * y.ld);
     }
+    if (y.adaptive) y.A = cv.take<float>(M * y.ld);
   }
   c.ldx = c.sizes[0] % 4 == 0 ? c.sizes[0] : (int)rup(c.sizes[0], 8);
   c.x_padded = c.ldx != c.sizes[0];
@@ -323,6 +336,8 @@ void configure(snn_ctx &c, const snn_config *cfg) {
     y.spiking = l < c.L - 1;
     y.recurrent = y.spiking && cfg->recurrent && cfg->recurrent[l];
     y.beta = cfg->beta[l];
+    y.adaptive = y.spiking && cfg->adapt_step && cfg->adapt_step[l] > 0.f;
+    if (y.adaptive) { y.gamma = cfg->adapt_decay[l]; y.kappa = cfg->adapt_step[l]; }
   }
   c.C = c.sizes[c.L];
   c.ldC = c.layers[c.L - 1].ld;
@@ -613,12 +628,13 @@ hipError_t lif_fwd_launch(snn_ctx *c, Layer &y) {
   const int threads = stride / VEC;
   const int bs = scan_block(threads);
   const dim3 grid((unsigned)((threads + bs - 1) / bs)), block(bs);
-  if (streams_past_cache(c, c->M * y.ld * 4))
-    hipLaunchKernelGGL((lif_forward_kernel<VEC, U, NT>), grid, block, 0, c->stream, y.I, y.V, y.S, c->T, stride,
-                       y.beta_v, y.ld, c->theta);
-  else
-    hipLaunchKernelGGL((lif_forward_kernel<VEC, U, 0>), grid, block, 0, c->stream, y.I, y.V, y.S, c->T, stride,
-                       y.beta_v, y.ld, c->theta);
+  const bool nt = streams_past_cache(c, c->M * y.ld * 4);
+#define SNN_FWD(POL_, AD_)                                                                                       \
+  hipLaunchKernelGGL((lif_forward_kernel<VEC, U, POL_, AD_>), grid, block, 0, c->stream, y.I, y.V, y.S, c->T, stride, \
+                     y.beta_v, y.ld, c->theta, y.A, y.gamma, y.kappa)
+  if (y.adaptive) { if (nt) SNN_FWD(NT, true); else SNN_FWD(0, true); }
+  else { if (nt) SNN_FWD(NT, false); else SNN_FWD(0, false); }
+#undef SNN_FWD
   return hipGetLastError();
 }
 
@@ -647,14 +663,13 @@ hipError_t lif_rev_launch2(snn_ctx *c, Layer &y) {
   const int bs = scan_block(threads);
   dim3 grid((unsigned)((threads + bs - 1) / bs)), block(bs);
   const bool nt = streams_past_cache(c, c->M * y.ld * 4);
+#define SNN_REV2(SU, POL_, AD_)                                                                                  \
+  hipLaunchKernelGGL((lif_reverse_kernel<VEC, U, SU, HL, POL_, AD_>), grid, block, 0, c->stream, y.dS, y.V, y.dI, c->T, \
+                     stride, y.beta_v, y.ld, c->theta, c->slope, y.part_b, y.A, y.gamma, y.kappa)
 #define SNN_REV(SU)                                                                                              \
   do {                                                                                                           \
-    if (nt)                                                                                                      \
-      hipLaunchKernelGGL((lif_reverse_kernel<VEC, U, SU, HL, NT>), grid, block, 0, c->stream, y.dS, y.V, y.dI, c->T, \
-                         stride, y.beta_v, y.ld, c->theta, c->slope, y.part_b);                                  \
-    else                                                                                                         \
-      hipLaunchKernelGGL((lif_reverse_kernel<VEC, U, SU, HL, 0>), grid, block, 0, c->stream, y.dS, y.V, y.dI, c->T,  \
-                         stride, y.beta_v, y.ld, c->theta, c->slope, y.part_b);                                  \
+    if (y.adaptive) { if (nt) SNN_REV2(SU, NT, true); else SNN_REV2(SU, 0, true); }                              \
+    else { if (nt) SNN_REV2(SU, NT, false); else SNN_REV2(SU, 0, false); }                                       \
   } while (0)
   switch (c->surrogate) {
     case 0: SNN_REV(0); break;
@@ -665,6 +680,7 @@ hipError_t lif_rev_launch2(snn_ctx *c, Layer &y) {
     default: SNN_REV(5); break;
   }
 #undef SNN_REV
+#undef SNN_REV2
   return hipGetLastError();
 }
 template <int VEC, int U>
@@ -702,7 +718,7 @@ bool reverse_fusable(const snn_ctx *c, int l) {
   if (!c->opt[SNN_OPT_TOP_SCANS]) return false;
   if (l < 0 || l > c->L - 2) return false;
   const Layer &y = c->layers[l];
-  return c->hl && y.spiking && !y.recurrent && y.ld % 64 == 0 && columns_above(c, l) <= 128;
+  return c->hl && y.spiking && !y.recurrent && !y.adaptive && y.ld % 64 == 0 && columns_above(c, l) <= 128;
 }
 
 // Forward counterpart: the last spiking layer's scan also forms the readout's currents
@@ -846,7 +862,7 @@ bool layer_forward_fusable(snn_ctx *c, int l) {
   const Layer &y = c->layers[l];
   const int min_b = layer_min_batch(c);                  // a workgroup walks a sample's blocks of 128 steps one after the other
   const SpikeSrc s = spikes_below(c, l);
-  return c->nplanes == 1 && y.spiking && !y.recurrent && y.ld % 64 == 0 && y.ld <= layer_max_neurons(c) && c->B >= min_b &&
+  return c->nplanes == 1 && y.spiking && !y.recurrent && !y.adaptive && y.ld % 64 == 0 && y.ld <= layer_max_neurons(c) && c->B >= min_b &&
          s.ld % 4 == 0 && s.ld <= layer_max_neurons(c) && (size_t)c->M * s.ld < ((size_t)1 << 31) && (size_t)c->M * y.ld * 4 < ((size_t)1 << 31) &&
          y.qf_plane >= (long long)y.ld * y.ldqf && c->theta >= 0x1p-60f && c->theta <= 0x1p26f;
 }
@@ -1079,6 +1095,10 @@ int view_of(snn_ctx *c, int tensor, int layer, TensorView *v, bool for_set) {
     case SNN_T_SPIKES:
       if ((rc = spiking_layer(&y))) return rc;
       *v = {y->S, M, (size_t)y->N, (size_t)y->ld, 1, false}; break;
+    case SNN_T_ADAPTATION:
+      if ((rc = spiking_layer(&y))) return rc;
+      if (!y->adaptive) return fail(c, SNN_ERR_ARG, "layer %d has no adaptive threshold", layer);
+      *v = {y->A, M, (size_t)y->N, (size_t)y->ld, 4, false}; break;
     case SNN_T_D_SPIKES:
       if ((rc = spiking_layer(&y))) return rc;
       *v = {y->dS, M, (size_t)y->N, (size_t)y->ld, 4, false}; break;

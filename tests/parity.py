@@ -28,6 +28,7 @@ def _splice(tr: O.Trace, sub: O.Trace, idx: np.ndarray, B: int):
         tr.I[l][:, idx] = sub.I[l]
         tr.V[l][:, idx] = sub.V[l]
         tr.S[l][:, idx] = sub.S[l]
+        tr.A[l][:, idx] = sub.A[l]
         tr.v_final[l][idx] = sub.v_final[l]
     tr.J[:, idx] = sub.J
     tr.Y[:, idx] = sub.Y
@@ -65,7 +66,7 @@ def reconciled_forward(net: O.Net, X, W, R, labels, S_gpu, max_rounds: int = 200
         for b, l, t in todo:
             ns = np.flatnonzero(tr.S[l][t, b] != S_gpu[l][t, b])
             for n in ns:
-                dist = abs(tr.V[l][t, b, n] - net.theta)
+                dist = abs(tr.V[l][t, b, n] - net.theta - tr.A[l][t, b, n])      # to the threshold in force
                 if dist > band:
                     raise ParityError(f"spike mismatch outside the band: layer {l + 1} t={t} b={b} n={n} "
                                       f"|V-theta|={dist:.3e} oracle V={tr.V[l][t, b, n]!r} "
@@ -121,6 +122,8 @@ def compare_forward(net: O.Net, inp, snn, loss_gpu, report=None, betas=None):
         assert np.array_equal(S_gpu[l], tr.S[l].astype(np.uint8))
         rep[f"V{l + 1}"] = close_state(f"V^{l + 1}", snn.get_tensor("membrane", l + 1), tr.V[l])
         rep[f"I{l + 1}"] = close_state(f"I^{l + 1}", snn.get_tensor("current", l + 1), tr.I[l])
+        if net.adapt_step is not None and net.adapt_step[l] > 0:
+            rep[f"A{l + 1}"] = close_state(f"A^{l + 1}", snn.get_tensor("adaptation", l + 1), tr.A[l])
     rep["Y"] = close_state("Y", snn.get_tensor("readout_trace"), tr.Y)
     rep["z"] = close_state("z", snn.get_tensor("logits"), tr.z)
     # first maximiser: must agree unless two steps tie within tolerance; then follow the device

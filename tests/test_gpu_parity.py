@@ -753,6 +753,96 @@ def test_integral_loss_headline_shape_long_horizon():
     full_step_parity(wl, w_gain=3.0, check_sgd=False)
 
 
+# ---------------------------------------------------------------- adaptive firing thresholds
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_adaptive_threshold_ragged_shapes(precision):
+    """Neurons whose threshold rises with every spike and decays (Section 2.1.2 names them): the
+    extra state in the forward and reverse scans, on shapes that are multiples of nothing; one
+    case with both layers adapting, one with an adapting layer below a plain one."""
+    for step in ((0.3, 0.2), (0.4, 0.0)):
+        wl = workloads.Workload(name="adaptive", index=30, T=37, B=7, sizes=(45, 29, 13, 3), recurrent=(False, False),
+                                beta=(0.9, 0.85, 0.8), theta=1.0, surrogate="superspike", slope=10.0,
+                                precision=precision, rate_lo=0.1, rate_hi=0.3, adapt_decay=(0.9, 0.7), adapt_step=step)
+        rep = full_step_parity(wl, w_gain=3.0)
+        assert rep["spike_rate"][0] > 0.01 and rep["spike_rate"][1] > 0.001
+        assert "A1" in rep and ("A2" in rep) == (step[1] > 0)
+
+
+@pytest.mark.parametrize("adaptive", [(True, False), (False, True), (True, True)], ids=["lower", "upper", "both"])
+def test_adaptive_threshold_headline_widths(adaptive):
+    """700-128-128-20 on bf16 products with one or both hidden layers adapting: an adapting layer
+    runs as product + scan launches between (or below, or above) layers that run as one launch."""
+    wl = workloads.CONFIGS["shd_ff128"].scaled(T=70, B=24, adapt_decay=(0.95, 0.9),
+                                               adapt_step=tuple(0.25 if a else 0.0 for a in adaptive))
+    rep = full_step_parity(wl, w_gain=3.0)
+    assert rep["spike_rate"][0] > 0.01 and rep["spike_rate"][1] > 0.005
+
+
+@pytest.mark.parametrize("B,nt", [(128, False), (512, True)])
+def test_adaptive_threshold_vector_scans(B, nt):
+    """2^17 and 2^19 chains: the scans that give two and four adjacent chains to a thread, with
+    the adaptation as a third stream; once with the non-temporal loads of large tensors."""
+    wl = workloads.Workload(name="adaptive_wide", index=31, T=24, B=B, sizes=(64, 1024, 20), recurrent=(False,),
+                            beta=(0.9, 0.9), theta=1.0, surrogate="arctan", slope=2.0, precision="bf16",
+                            rate_lo=0.05, rate_hi=0.3, adapt_decay=(0.8,), adapt_step=(0.5,))
+    rep = full_step_parity(wl, w_gain=3.0, check_sgd=False, options={"stream_min_mb": 0} if nt else None)
+    assert rep["spike_rate"][0] > 0.01
+
+
+def test_adaptive_threshold_with_trained_decays_and_integral_loss():
+    wl = workloads.Workload(name="adaptive_beta", index=32, T=33, B=9, sizes=(50, 40, 24, 5), recurrent=(False, False),
+                            beta=(0.9, 0.9, 0.9), theta=1.0, surrogate="sigmoid", slope=4.0, precision="fp32",
+                            rate_lo=0.1, rate_hi=0.3, loss="integral", adapt_decay=(0.9, 0.8), adapt_step=(0.3, 0.3))
+    rep, gr, new = beta_step_parity(wl, w_gain=3.0)
+    assert all(np.abs(d).max() > 0 for d in gr.dbeta)
+
+
+def test_adaptive_threshold_single_steps_and_errors():
+    """The adaptive scans alone on the oracle's tensors (teacher forcing), and what the library
+    refuses: a layer that is recurrent and adaptive, the adaptation of a layer that has none."""
+    import ctypes as C
+    from paper_2402_18994_amd import binding
+    wl = workloads.Workload(name="adaptive_steps", index=33, T=29, B=6, sizes=(40, 72, 5), recurrent=(False,),
+                            beta=(0.9, 0.9), theta=0.8, surrogate="arctan", slope=2.0, precision="fp32",
+                            rate_lo=0.1, rate_hi=0.3, adapt_decay=(0.85,), adapt_step=(0.35,))
+    inp = workloads.generate(wl, w_gain=3.0)
+    net = net_of(wl)
+    tr = O.forward(net, inp.X, inp.W, inp.R, inp.labels)
+    gr = O.backward(net, inp.X, inp.W, inp.R, inp.labels, tr)
+    assert tr.S[0].mean() > 0.01
+    snn = make(wl, inp)
+    snn.set_tensor("current", 1, tr.I[0])
+    snn.run_step("lif_forward", 1)
+    near = np.abs(tr.V[0] - net.theta - tr.A[0]) <= parity.BAND
+    S1 = snn.get_tensor("spikes", 1)
+    assert np.array_equal(S1[~near], tr.S[0].astype(np.uint8)[~near])
+    if np.array_equal(S1, tr.S[0].astype(np.uint8)):
+        parity.close_state("V1", snn.get_tensor("membrane", 1), tr.V[0])
+        parity.close_state("A1", snn.get_tensor("adaptation", 1), tr.A[0])
+    snn.set_tensor("d_spikes", 1, gr.dS[0])
+    snn.set_tensor("membrane", 1, tr.V[0])
+    snn.set_tensor("adaptation", 1, tr.A[0])
+    snn.run_step("lif_reverse", 1)
+    parity.close_grad("dI1", snn.get_tensor("d_current", 1), gr.dI[0])
+    snn.destroy()
+    plain = make(wl.scaled(adapt_decay=None, adapt_step=None), inp)
+    buf = np.zeros((wl.T, wl.B, 72), np.float32)
+    assert plain.lib.snn_get_tensor(plain.ctx, 19, 1, buf.ctypes.data, buf.nbytes) == 2
+    plain.destroy()
+    n = C.c_size_t(0)
+    lib = binding.load_library()
+    for kw, status in ((dict(recurrent=(1,)), 7), (dict(adapt_decay=(1.5,)), 2), (dict(adapt_step=(-0.1,)), 2)):
+        d = dict(T=8, B=4, sizes=(10, 6, 3), recurrent=(0,), beta=(0.9, 0.9), theta=1.0, surrogate="superspike",
+                 slope=25.0, precision="fp32", adapt_decay=(0.9,), adapt_step=(0.5,))
+        d.update(kw)
+        cfg = binding._Cfg(**d)
+        assert lib.snn_workspace_bytes(C.byref(cfg.c), C.byref(n)) == status, kw
+    cfg = binding._Cfg(T=8, B=4, sizes=(10, 6, 3), recurrent=(0,), beta=(0.9, 0.9), theta=1.0, surrogate="superspike",
+                       slope=25.0, precision="fp32", adapt_decay=(0.9,), adapt_step=(0.5,))
+    cfg.c.adapt_decay = None                                   # one of the two arrays missing
+    assert lib.snn_workspace_bytes(C.byref(cfg.c), C.byref(n)) == 1
+
+
 # ---------------------------------------------------------------- per-neuron, trainable decay
 def beta_step_parity(wl, w_gain=2.5, lr=0.05, options=None):
     """Random per-neuron decays set through SNN_T_BETA; forward, backward with dL/dbeta, and

@@ -38,6 +38,8 @@ class Workload:
     rate_hi: float
     rec_gain: float = 0.5           # recurrent weights ~ N(0, rec_gain / sqrt(N))
     loss: str = "max"               # "max" (over time) | "integral" (sum over time) of the readout trace
+    adapt_decay: Optional[Tuple[float, ...]] = None   # per spiking layer: decay of the threshold adaptation
+    adapt_step: Optional[Tuple[float, ...]] = None    # per spiking layer: rise of the threshold per spike (0: plain LIF)
 
     @property
     def n_layers(self) -> int:
