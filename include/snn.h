@@ -260,9 +260,13 @@ int32_t snn_forward(snn_ctx *ctx, const uint8_t *x_dev, const int32_t *labels_de
  *   x_packed_dev  device, uint8 [ceil(T/8)][B][N_0]; bit 7-(t%8) of byte [t/8][b][n] is
  *                 the spike at step t (the first step in the most significant bit; bits
  *                 of steps >= T are ignored)
- * The raster is unpacked into the workspace by a pre-pass; x_packed_dev may be released
- * when the call returns only after the stream has passed that pre-pass (it is not read by
- * snn_backward).  Everything else as for snn_forward. */
+ * Where layer 1 runs as one launch (feed-forward, a multiple of 64 neurons wide, rounded
+ * weights, at most 1024 input channels in rows of a multiple of 4 bytes) that launch reads the
+ * packed raster itself and unpacks between its LDS read and the MFMA, and so does the weight-
+ * gradient product of layer 1 in snn_backward when B is a multiple of 8; nothing is unpacked in
+ * memory then.  Other shapes are unpacked into the workspace by a pre-pass.  x_packed_dev must
+ * stay valid until the following snn_backward has finished.  Everything else as for
+ * snn_forward. */
 int32_t snn_forward_packed(snn_ctx *ctx, const uint8_t *x_packed_dev, const int32_t *labels_dev,
                            float *loss_host);
 

@@ -10,6 +10,11 @@
 //   transposed  the contraction index is the slowest axis (contraction over the T*B rows)
 //                 weight gradient   dW = S^T dI      P = S [m][i] (0/1 bytes)  Q = dI [m][j]
 //               8x4 / 8x2 element blocks are transposed in registers on their way to LDS.
+//               With the input raster packed along time (Section 2.1.4: eight steps of a channel
+//               per byte) the weight gradient of layer 1 walks the contraction in another order,
+//               which a sum does not mind: a 64-wide tile is one packed row (eight steps) of eight
+//               consecutive samples, so that a byte of P is exactly one 16-byte chunk of a tile row
+//               (P_T_BITS) and the rows of dI follow the same order (Q_T_*_PK).
 //
 // "Planes": a real operand enters as bfloat16 pieces of the split x = hi + mid + lo.
 //   weights            pre-split in memory: one plane when rounded to bfloat16, three for
@@ -33,8 +38,8 @@
 
 namespace snn {
 
-enum { P_U8 = 0, P_HL = 1, P_F32S = 2, P_T_U8 = 3 };
-enum { Q_BF16 = 0, Q_T_HL = 1, Q_T_F32S = 2 };
+enum { P_U8 = 0, P_HL = 1, P_F32S = 2, P_T_U8 = 3, P_T_BITS = 4 };
+enum { Q_BF16 = 0, Q_T_HL = 1, Q_T_F32S = 2, Q_T_HL_PK = 3, Q_T_F32S_PK = 4 };
 enum { EPI_STORE = 0 };
 
 struct GemmArgs {
@@ -52,6 +57,8 @@ struct GemmArgs {
   long long c_split_stride;  // elements between partial results
   int tiles_m, tiles_n;
   int nt_store;              // store C non-temporally (large results that a later kernel streams once)
+  int packed;                // P_T_U8 jobs: P is the raster packed along time; contraction in packed order
+  int pk_T, pk_B;            // time steps and batch of the packed raster (B a multiple of 8)
 };
 
 // ------------------------------------------------------------------ operand loaders
@@ -217,6 +224,55 @@ template <int ROWS> struct LoaderP<P_T_U8, ROWS> {
   }
 };
 
+// P packed along time: bytes [ceil(T/8) * B][i], bit 7 - r of byte (tp, b, i) = the spike of channel
+// i, sample b at step 8 tp + r.  Contraction in packed order: tile q covers packed rows 8q .. 8q+7
+// (one tp, eight consecutive samples: B is a multiple of 8), k = 8 mg + r for sample mg of the
+// eight and step r of the byte.  One unit = one sample x 8 consecutive i: a single 8-byte load,
+// each byte expanded to the eight bfloat16 of one 16-byte chunk.  Bits of steps beyond T may hold
+// anything: the rows of Q they meet read as zero.
+template <int ROWS> struct LoaderP<P_T_BITS, ROWS> {
+  static constexpr int PLANES = 1;
+  static constexpr int UNITS = ROWS;                      // (ROWS/8) channel groups x 8 samples
+  static constexpr int UP = (UNITS + 255) / 256;
+  int voff[UP], loff[UP][8];
+  u32x2 raw[UP];
+  __device__ __forceinline__ void setup(const GemmArgs &a, int row0, int tid) {
+#pragma unroll
+    for (int c = 0; c < UP; ++c) {
+      const int u = tid + 256 * c;
+      const int ig = u % (ROWS / 8), mg = u / (ROWS / 8);
+      const int i = row0 + 8 * ig;
+      voff[c] = (u < UNITS && i < a.p_ivalid) ? mg * a.ldp + i : OOB;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) loff[c][e] = tile_off((8 * ig + e) & (ROWS - 1), mg & 7);
+    }
+  }
+  __device__ __forceinline__ void load(const GemmArgs &a, rsrc_t rs, int k0, int kend) {
+#pragma unroll
+    for (int c = 0; c < UP; ++c) raw[c] = ld_b64(rs, k0 >= kend ? OOB : voff[c], (k0 >> 3) * a.ldp);
+  }
+  __device__ __forceinline__ void store(char *tile, int tid) {
+#pragma unroll
+    for (int c = 0; c < UP; ++c) {
+      if (tid + 256 * c < UNITS) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          // z holds the byte at bits 0..7 and again at bits 17..24: shifted right by 7 - 2j, bit 0 is
+          // step 2j and bit 16 is step 2j + 1
+          const uint32_t v = (raw[c][e >> 2] >> (8 * (e & 3))) & 0xFFu;
+          const uint32_t z = v | (v << 17);
+          uint4 d;
+          d.x = ((z >> 7) & 0x00010001u) * 0x3F80u;
+          d.y = ((z >> 5) & 0x00010001u) * 0x3F80u;
+          d.z = ((z >> 3) & 0x00010001u) * 0x3F80u;
+          d.w = ((z >> 1) & 0x00010001u) * 0x3F80u;
+          *(uint4 *)(tile + loff[c][e]) = d;
+        }
+      }
+    }
+  }
+};
+
 template <int MODE, int ROWS, int NPL> struct LoaderQ;
 
 // Q[plane][j][k] bfloat16, allocated with rows padded to 128 and k padded to 64 (zeros).
@@ -254,7 +310,10 @@ template <int ROWS, int NPL> struct LoaderQ<Q_BF16, ROWS, NPL> {
 // Q[m][j] dwords, contraction index m slowest, ld a multiple of 8 with zero padding: HL words
 // (two planes) or fp32 (three planes, split here).  One unit = 8 consecutive m x 4
 // consecutive j: eight 16-byte loads, transposed into four 16-byte LDS writes per plane.
-template <int ROWS, bool HL> struct LoaderQTWord {
+// PK: the contraction runs in the packed order of LoaderP<P_T_BITS>: tile q = k0 / 64 is packed row
+// tp = q / (B/8) and samples 8 (q % (B/8)) .. +7; element 8 mg + r of the tile is row
+// (8 tp + r) B + 8 (q % (B/8)) + mg of Q, and rows of steps beyond T read as zero.
+template <int ROWS, bool HL, bool PK = false> struct LoaderQTWord {
   static constexpr int PLANES = HL ? 2 : 3;
   static constexpr int UNITS = ROWS * 2;
   static constexpr int UQ = (UNITS + 255) / 256;
@@ -266,13 +325,24 @@ template <int ROWS, bool HL> struct LoaderQTWord {
       const int u = tid + 256 * c;
       const int jg = u % (ROWS / 4), mg = u / (ROWS / 4);
       const int j = col0 + 4 * jg;
-      voff[c] = (u < UNITS && j < a.ldq) ? (8 * mg * a.ldq + j) * 4 : OOB;
+      voff[c] = (u < UNITS && j < a.ldq) ? ((PK ? mg : 8 * mg) * a.ldq + j) * 4 : OOB;
       mrow[c] = 8 * mg;
 #pragma unroll
       for (int e = 0; e < 4; ++e) loff[c][e] = tile_off((4 * jg + e) & (ROWS - 1), mg & 7);
     }
   }
   __device__ __forceinline__ void load(const GemmArgs &a, rsrc_t rs, int k0, int kend) {
+    if (PK) {
+      const int groups = a.pk_B >> 3, q = k0 >> 6;
+      const int tp = q / groups, bg = q - tp * groups;
+      const int row0 = 8 * tp * a.pk_B + 8 * bg;
+#pragma unroll
+      for (int c = 0; c < UQ; ++c)
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+          raw[c][r] = ld_b128(rs, k0 >= kend || 8 * tp + r >= a.pk_T ? OOB : voff[c], (row0 + r * a.pk_B) * a.ldq * 4);
+      return;
+    }
 #pragma unroll
     for (int c = 0; c < UQ; ++c)
 #pragma unroll
@@ -312,14 +382,26 @@ template <int ROWS, int NPL> struct LoaderQ<Q_T_HL, ROWS, NPL> : LoaderQTWord<RO
 template <int ROWS, int NPL> struct LoaderQ<Q_T_F32S, ROWS, NPL> : LoaderQTWord<ROWS, false> {
   static_assert(NPL == 3, "hi, mid and lo");
 };
+template <int ROWS, int NPL> struct LoaderQ<Q_T_HL_PK, ROWS, NPL> : LoaderQTWord<ROWS, true, true> {
+  static_assert(NPL == 2, "hi and lo");
+};
+template <int ROWS, int NPL> struct LoaderQ<Q_T_F32S_PK, ROWS, NPL> : LoaderQTWord<ROWS, false, true> {
+  static_assert(NPL == 3, "hi, mid and lo");
+};
 
 // ------------------------------------------------------------------ the kernel
 // 256 threads = WM x WN wavefronts, each owning TM x TN MFMA tiles of 32x32.  One LDS stage.
 // D register sets form a ring: the global loads of the next D tiles are always in flight, so
 // that a workgroup alone keeps enough bytes outstanding to cover HBM/L2 latency even when
 // few workgroups fit a compute unit.
+// Bytes of the one LDS stage: every plane of both operand tiles.
+template <int PM, int QM, int WM, int WN, int TM, int TN, int NQP>
+constexpr int gemm_lds_bytes() {
+  return LoaderP<PM, WM * TM * 32>::PLANES * WM * TM * 32 * 128 + NQP * WN * TN * 32 * 128;
+}
+
 template <int PM, int QM, int EPI, int WM, int WN, int TM, int TN, int NQP, int D>
-__device__ __forceinline__ void gemm_body(const GemmArgs &a, const int block) {
+__device__ __forceinline__ void gemm_body(const GemmArgs &a, const int block, char *lds) {
   static_assert(WM * WN == 4, "four wavefronts per workgroup");
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   typedef LoaderP<PM, BM> LP;
@@ -329,7 +411,6 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, const int block) {
   constexpr int PT = BM * 128, QT = BN * 128;       // bytes of one plane of a tile
   constexpr int DR = D;
   static_assert(NPP * PT + NQP * QT <= 81920, "one stage, at least two workgroups per compute unit");
-  __shared__ __attribute__((aligned(16))) char lds[NPP * PT + NQP * QT];
 
   // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Without
   // contraction splits an XCD gets a contiguous run of tiles (column tiles fastest), so tiles
@@ -454,7 +535,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, const int block) {
 
 template <int PM, int QM, int EPI, int WM, int WN, int TM, int TN, int NQP, int D>
 __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a) {
-  gemm_body<PM, QM, EPI, WM, WN, TM, TN, NQP, D>(a, blockIdx.x);
+  __shared__ __attribute__((aligned(16))) char lds[gemm_lds_bytes<PM, QM, WM, WN, TM, TN, NQP>()];
+  gemm_body<PM, QM, EPI, WM, WN, TM, TN, NQP, D>(a, blockIdx.x, lds);
 }
 
 // Several independent products of one kind in a single launch: a small product cannot fill
@@ -469,9 +551,18 @@ struct GemmJobs {
 
 template <int PM, int QM, int EPI, int WM, int WN, int TM, int TN, int NQP, int D>
 __global__ __launch_bounds__(256, 2) void gemm_jobs_kernel(const GemmJobs jobs) {
+  __shared__ __attribute__((aligned(16))) char lds[gemm_lds_bytes<PM, QM, WM, WN, TM, TN, NQP>()];
   int j = 0;
   while (j + 1 < jobs.njobs && (int)blockIdx.x >= jobs.first_block[j + 1]) ++j;
-  gemm_body<PM, QM, EPI, WM, WN, TM, TN, NQP, D>(jobs.job[j], blockIdx.x - jobs.first_block[j]);
+  if constexpr (PM == P_T_U8) {
+    // a weight-gradient job on the raster packed along time: same tiles and stage, other loaders
+    if (jobs.job[j].packed) {
+      gemm_body<P_T_BITS, QM == Q_T_HL ? Q_T_HL_PK : Q_T_F32S_PK, EPI, WM, WN, TM, TN, NQP, D>(
+          jobs.job[j], blockIdx.x - jobs.first_block[j], lds);
+      return;
+    }
+  }
+  gemm_body<PM, QM, EPI, WM, WN, TM, TN, NQP, D>(jobs.job[j], blockIdx.x - jobs.first_block[j], lds);
 }
 
 // Fills in the tile counts; returns the number of workgroups.

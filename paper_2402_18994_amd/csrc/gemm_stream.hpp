@@ -69,6 +69,17 @@ __device__ __forceinline__ void static_for(F &&f) {
   }
 }
 
+// P operand packed along time (the storage format of Section 2.1.4: eight consecutive steps of one
+// channel in a byte, first step in the most significant bit), for tiles whose 128 rows are
+// consecutive time steps of one sample: the 16 packed rows of the block.
+struct PackedRows {
+  rsrc_t rsrc;         // the packed raster
+  int base;            // byte offset of the block's first packed row for this sample
+  int row_stride;      // bytes between packed rows of the sample (B x row length)
+  int rows;            // packed rows that exist from there on (others read as zero)
+  int kbytes;          // row length in bytes (= fan-in), at most 1024, a multiple of 4
+};
+
 // Geometry and main loop of one tile, shared by the kernels built on this pipeline.  `run`
 // expects the per-lane global offsets of the wavefront's load instructions (pv: P, row-major
 // bytes; qv: Q, bfloat16), takes the stages through `lds` (NS * ST bytes) and leaves the
@@ -84,6 +95,12 @@ struct SpikeTile {
   static_assert(BM % 128 == 0 && BN % 64 == 0, "whole KiB per wavefront");
   static_assert(NS >= 4, "the waits assume at least four stages");
   typedef u32x4 frag_t;
+  // Packed P operand: the whole block of the sample (BM / 8 packed rows of up to 1024 bytes) sits
+  // in LDS for all stages, ahead of the stages, which then hold Q alone.  A row pitch of 1088 bytes
+  // puts the four packed rows a fragment read touches on different banks.
+  static constexpr int PKP = 1088, PKB = (BM / 8) * PKP;
+  static_assert(PKB % 1024 == 0, "the stages behind the packed block start on a KiB");
+  static constexpr int lds_bytes(bool pk) { return pk ? PKB + NS * QT : NS * ST; }
 
   // Global side of the loads.  P instruction q of a wavefront fills rows 32 (wave + 4 q) ..
   // +31 of the stage, 32 bytes each: lane -> row lane/2, slot lane%2, which holds the 16-byte
@@ -96,22 +113,43 @@ struct SpikeTile {
   static __device__ __forceinline__ int q_row(int wave, int lane, int q) { return 16 * (wave + 4 * q) + (lane >> 2); }
   static __device__ __forceinline__ int q_chunk(int row, int lane) { return (lane & 3) ^ ((row >> 2) & 3); }
 
+  // PK: P comes from `pk` (packed along time; BM == 128 rows = time steps of one sample) instead
+  // of rp / pv: a lane's 16 bytes of row r, columns 16 h .. +15 of a stage, are bit 7 - r % 8 of
+  // the 16 packed bytes at packed row r / 8; no P loads per stage.
+  template <bool PK = false>
   static __device__ __forceinline__ void run(char *lds, const u32x4 rp, const u32x4 rq, const int (&pv)[PI],
                                              const int (&qv)[QI], const int nk, const int wave, const int lane,
-                                             f32x16 (&acc)[TM][TN]) {
+                                             f32x16 (&acc)[TM][TN], const PackedRows *pk = nullptr) {
     const int wm = wave / WN, wn = wave % WN;
-    const unsigned lds0 = (unsigned)(uintptr_t)(lds_ptr_t)lds;
+    constexpr int STQ = PK ? QT : ST;               // bytes of a stage
+    constexpr int QOFF = PK ? 0 : PT;               // where Q starts inside a stage
+    constexpr int NLK = PK ? QI : NL;               // load instructions per wavefront and stage
+    char *const stages = lds + (PK ? PKB : 0);
+    const unsigned lds0 = (unsigned)(uintptr_t)(lds_ptr_t)stages;
+    u32x4 pkx[4];
+    if (PK) {
+      // the block's packed rows: 16 rows x 64 pieces of 16 bytes, four pieces per thread; pieces
+      // beyond the last packed row or the row length read as zero
+      const int tid = 64 * wave + lane;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int piece = tid + 256 * j, r = piece >> 6, c = (piece & 63) * 16;
+        pkx[j] = ld_b128(pk->rsrc, r < pk->rows && c < pk->kbytes ? r * pk->row_stride + c : OOB, pk->base);
+      }
+    }
     // Stage kt into buffer `buf`.  Beyond the contraction range the descriptors get size 0:
     // the instruction count (which the vmcnt waits rely on) stays the same, nothing is fetched.
     auto issue = [&](int kt_any, int buf) {
       const int kt = __builtin_amdgcn_readfirstlane(kt_any);   // uniform; keeps the offsets scalar
       u32x4 p = rp, qr = rq;
       if (kt >= nk) p.z = qr.z = 0;
-      const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + buf * ST + 1024 * wave);
+      const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + buf * STQ + 1024 * wave);
+      if (!PK) {
 #pragma unroll
-      for (int q = 0; q < PI; ++q) load_to_lds_b128(p, dst + 4096 * q, pv[q], kt * 32);
+        for (int q = 0; q < PI; ++q) load_to_lds_b128(p, dst + 4096 * q, pv[q], kt * 32);
+      }
 #pragma unroll
-      for (int q = 0; q < QI; ++q) load_to_lds_b128(qr, dst + PT + 4096 * q, qv[q], kt * 64);
+      for (int q = 0; q < QI; ++q) load_to_lds_b128(qr, dst + QOFF + 4096 * q, qv[q], kt * 64);
     };
 
     // LDS side of the fragment reads: lane half h reads P unit h (16 k, two MFMA steps' worth)
@@ -120,10 +158,11 @@ struct SpikeTile {
     int fa, fb[2];
     {
       const int ra = wm * TM * 32 + (lane & 31), rb = wn * TN * 32 + (lane & 31);
-      fa = ra * 32 + ((h ^ ((ra >> 3) & 1)) << 4);
+      fa = PK ? (ra >> 3) * PKP + 16 * h : ra * 32 + ((h ^ ((ra >> 3) & 1)) << 4);
 #pragma unroll
-      for (int st = 0; st < 2; ++st) fb[st] = PT + rb * 64 + (((2 * h + st) ^ ((rb >> 2) & 3)) << 4);
+      for (int st = 0; st < 2; ++st) fb[st] = QOFF + rb * 64 + (((2 * h + st) ^ ((rb >> 2) & 3)) << 4);
     }
+    const unsigned pk_shift = 7 - (lane & 7);       // the lane's time step inside its packed byte (first step: bit 7)
 
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -132,10 +171,18 @@ struct SpikeTile {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    auto read_first = [&](int buf, frag_t (&pa)[TM], frag_t (&qb)[TN]) {   // P bytes of a stage, Q of its step 0
-      const char *st = lds + buf * ST;
+    auto read_first = [&](int buf, int kt, frag_t (&pa)[TM], frag_t (&qb)[TN]) {   // P bytes of stage kt, Q of its step 0
+      const char *st = stages + buf * STQ;
 #pragma unroll
-      for (int i = 0; i < TM; ++i) pa[i] = *(const frag_t *)(st + fa + i * 1024);
+      for (int i = 0; i < TM; ++i) {
+        if (PK) {
+          const frag_t w = *(const frag_t *)(lds + fa + i * 4 * PKP + kt * 32);
+#pragma unroll
+          for (int d = 0; d < 4; ++d) pa[i][d] = (w[d] >> pk_shift) & 0x01010101u;
+        } else {
+          pa[i] = *(const frag_t *)(st + fa + i * 1024);
+        }
+      }
 #pragma unroll
       for (int j = 0; j < TN; ++j) qb[j] = *(const frag_t *)(st + fb[0] + j * 2048);
     };
@@ -165,7 +212,7 @@ struct SpikeTile {
     auto stage = [&](int u, int kt, frag_t (&pa)[TM], frag_t (&qb)[TN], frag_t (&pa_next)[TM], frag_t (&qb_next)[TN]) {
       frag_t q1[TN];
 #pragma unroll
-      for (int j = 0; j < TN; ++j) q1[j] = *(const frag_t *)(lds + u * ST + fb[1] + j * 2048);
+      for (int j = 0; j < TN; ++j) q1[j] = *(const frag_t *)(stages + u * STQ + fb[1] + j * 2048);
       products(pa, qb, 0);
       // (ties the accumulators to this point: the MFMAs of step 0 are issued before the waits,
       // not moved behind the barrier by the scheduler)
@@ -173,19 +220,29 @@ struct SpikeTile {
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(acc[i][j]));
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 3) * NL) : "memory");   // younger stages may still be in flight
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 3) * NLK) : "memory");   // younger stages may still be in flight
       lds_barrier();
       issue(kt + NS - 1, (u + NS - 1) % NS);
-      read_first((u + 1) % NS, pa_next, qb_next);
+      read_first((u + 1) % NS, kt + 1, pa_next, qb_next);
       products(pa, q1, 1);
     };
 
 #pragma unroll
     for (int t = 0; t < NS - 1; ++t) issue(t, t);
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NL) : "memory");
+    if (PK) {
+      // (the wait the compiler puts before these writes covers the stage loads issued above as
+      // well: memory returns loads in order)
+      const int tid = 64 * wave + lane;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int piece = tid + 256 * j;
+        *(u32x4 *)(lds + (piece >> 6) * PKP + (piece & 63) * 16) = pkx[j];
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NLK) : "memory");
     lds_barrier();
     frag_t pa0[TM], qb0[TN], pa1[TM], qb1[TN];
-    read_first(0, pa0, qb0);
+    read_first(0, 0, pa0, qb0);
     // Unrolled over the buffers (twice when their number is odd, so that the two fragment
     // register sets alternate consistently).
     constexpr int UN = NS % 2 ? 2 * NS : NS;

@@ -35,6 +35,9 @@
 // Two consecutive layers of exactly 128 neurons can share the launch (NL = 2): per block the
 // workgroup runs steps 1 to 4 for the lower layer, waits until its spike stores are
 // acknowledged, and runs them again for the upper layer on the rows it has just written.
+// PACKED: the bottom layer of the launch reads the input raster packed along time (eight steps
+// per byte, Section 2.1.4): the 16 packed rows of the sample's block sit in LDS for the whole
+// product and are unpacked between the fragment read and the MFMA; the stages carry W alone.
 #pragma once
 #include "gemm_stream.hpp"
 
@@ -42,7 +45,7 @@ namespace snn {
 
 // One layer of the launch: operands and results.
 struct LayerForwardOp {
-  const uint8_t *P;        // spikes below [T*B][ldp], bytes 0/1
+  const uint8_t *P;        // spikes below [T*B][ldp], bytes 0/1 (PACKED, bottom layer: [ceil(T/8)*B][ldp], eight steps per byte)
   int ldp, kc;             // row length, fan-in
   unsigned p_bytes;
   const uint16_t *Q;       // rounded W^T [ld or more][ldq] bfloat16, zero beyond the fan-in and fan-out
@@ -84,7 +87,7 @@ struct LayerForwardArgs {
 
 // READOUT: 0 none; 1 the launch also forms the readout's currents J; 2 and the LI scan, the
 // maximum over time, the loss and dJ; 3 the same with the integral loss.
-template <int TN, int NS = 4, int READOUT = 0, int NL = 1>
+template <int TN, int NS = 4, int READOUT = 0, int NL = 1, bool PACKED = false>
 __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerForwardArgs a) {
   static_assert(!READOUT || TN == 2, "the readout variants hold the whole layer");
   static_assert(NL == 1 || (NL == 2 && TN == 2), "a chain of layers: whole layers of 128 neurons");
@@ -97,7 +100,8 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
   static_assert(BM == 128 && PI == 1 && (BN == 64 || BN == 128), "128 steps x 64 or 128 neurons");
   constexpr int CP = BN * 4 + 16;                     // bytes between time rows of the current tile in LDS
   constexpr int TILE = BM * CP;
-  constexpr int LDS_BYTES = NS * Tile::ST > TILE ? NS * Tile::ST : TILE;   // the stages share the tile's space
+  constexpr int STAGES = Tile::lds_bytes(false) > Tile::lds_bytes(PACKED) ? Tile::lds_bytes(false) : Tile::lds_bytes(PACKED);
+  constexpr int LDS_BYTES = STAGES > TILE ? STAGES : TILE;                 // the stages share the tile's space
   static_assert(LDS_BYTES <= 80 * 1024, "two workgroups per compute unit");
   __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
 
@@ -157,7 +161,17 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
       pv[0] = t0 + row < a.T ? ((t0 + row) * a.B + b) * op.ldp + Tile::p_unit(row, lane) * 16 : OOB;
     }
     f32x16 acc[TM][TN];
-    Tile::run(lds, rp, rq, pv, qv, nk, wave, lane, acc);
+    if constexpr (PACKED && li == 0) {
+      PackedRows pk;
+      pk.rsrc = make_rsrc(op.P, op.p_bytes);
+      pk.base = ((t0 >> 3) * a.B + b) * op.ldp;
+      pk.row_stride = a.B * op.ldp;
+      pk.rows = ((a.T + 7) >> 3) - (t0 >> 3);
+      pk.kbytes = op.ldp;
+      Tile::template run<true>(lds, rp, rq, pv, qv, nk, wave, lane, acc, &pk);
+    } else {
+      Tile::run(lds, rp, rq, pv, qv, nk, wave, lane, acc);
+    }
 
     // 2. The MFMAs take Q as their first operand, so a tile comes out transposed: the lane
     // holds time row (lane & 31) and register r neuron 8*(r/4) + 4*(lane/32) + (r%4).

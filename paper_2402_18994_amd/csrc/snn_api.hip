@@ -96,6 +96,9 @@ struct snn_ctx {
   const uint8_t *x_eff = nullptr;  // raster the products read: the caller's, or x_buf
   uint8_t *x_buf = nullptr;        // [T*B][ldx]: zero-padded copy (N_0 not a multiple of 4) or unpacked input
   bool x_padded = false;           // the caller's raster must be copied into x_buf
+  const uint8_t *x_packed = nullptr;  // the caller's raster packed along time (snn_forward_packed)
+  bool x_direct = false;           // layer 1's launches read x_packed themselves; x_eff exists only once x_unpacked
+  bool x_unpacked = false;
   int ldx = 0;                     // row length of x_eff
   const int32_t *labels_dev = nullptr;
   ReduceJobs pending;             // partial sums of the last backward pass that have not been added yet
@@ -281,7 +284,9 @@ void carve(snn_ctx &c, Carver &cv) {
       y.qb_plane = (long long)rup(K, 128) * y.ldqb;
       y.Qb = cv.take<uint16_t>((size_t)np * y.qb_plane);
     }
-    y.splits_w = choose_splits(c.M, wg_tiles, wg_weights, wg_row_bytes, &y.per_w);
+    // (layer 1: from the length of the contraction in packed order, T rounded up to whole bytes of
+    // eight steps, so that the same splits serve a raster packed along time)
+    y.splits_w = choose_splits(l == 0 ? (long long)((c.T + 7) / 8 * 8) * c.B : c.M, wg_tiles, wg_weights, wg_row_bytes, &y.per_w);
     if (y.splits_w > 1) y.part_w = cv.take<float>((size_t)y.splits_w * K * N);
     if (y.recurrent) {
       y.Rm = cv.take<float>(N * N);
@@ -369,7 +374,8 @@ struct Bracket {
 };
 
 // ------------------------------------------------------------------ launches
-// Dynamic decompression of a raster packed along time (Section 2.1.4) into the workspace.
+// Dynamic decompression of a raster packed along time (Section 2.1.4) into the workspace: for the
+// launches that have no loader for the packed form (and for shapes the packed loaders do not take).
 int prepare_packed_input(snn_ctx *c, const uint8_t *xp) {
   if (!xp) return fail(c, SNN_ERR_NULL, "packed input raster is NULL");
   const long long n = (long long)((c->T + 7) / 8) * c->B * c->sizes[0];
@@ -377,7 +383,15 @@ int prepare_packed_input(snn_ctx *c, const uint8_t *xp) {
                      c->T, c->B, c->sizes[0], c->ldx);
   HIPCHK(c, hipGetLastError());
   c->x_eff = c->x_buf;
+  c->x_unpacked = true;
   return SNN_OK;
+}
+
+// Before a launch that reads the input raster as bytes: when the last forward pass consumed the
+// packed raster directly, unpack it now (a reader of I^1, a single step on imposed inputs).
+int ensure_unpacked_input(snn_ctx *c) {
+  if (!c->x_direct || c->x_unpacked) return SNN_OK;
+  return prepare_packed_input(c, c->x_packed);
 }
 
 // The product kernels read spike rows with 4-byte loads.  A raster whose row length is not a
@@ -385,6 +399,8 @@ int prepare_packed_input(snn_ctx *c, const uint8_t *xp) {
 // only for such sizes); otherwise it is read in place.
 int prepare_input(snn_ctx *c, const uint8_t *x) {
   if (!x) return fail(c, SNN_ERR_NULL, "input raster is NULL");
+  c->x_direct = false;
+  c->x_packed = nullptr;
   if (c->x_padded) {
     const long long n = c->M * c->ldx;
     hipLaunchKernelGGL(pad_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, x, c->x_buf,
@@ -419,6 +435,7 @@ static bool stream_gemm(const snn_ctx *c) { return c->opt[SNN_OPT_STREAM_GEMM] !
 // I^l = S^{l-1} W^l over all T*B rows at once.
 int launch_current_gemm(snn_ctx *c, int l) {
   Layer &y = c->layers[l];
+  if (l == 0) { int rc = ensure_unpacked_input(c); if (rc) return rc; }
   SpikeSrc s = spikes_below(c, l);
   if (!s.p) return fail(c, SNN_ERR_NULL, "input raster is NULL");
   GemmArgs a;
@@ -512,12 +529,16 @@ int flush_tn(snn_ctx *c, WgradJobs &w, int which) {
 }
 
 int queue_tn(snn_ctx *c, WgradJobs &w, SpikeSrc s, int rows, const void *G, int ldg, int cols, float *out,
-             float *part, int splits, long long per) {
+             float *part, int splits, long long per, bool packed = false) {
   GemmArgs a;
   memset(&a, 0, sizeof a);
   a.P = s.p; a.ldp = s.ld; a.p_ivalid = s.valid; a.p_bytes = s.bytes;
   a.Q = G; a.ldq = ldg; a.q_bytes = (unsigned)(c->M * ldg * 4);
   a.rows = rows; a.cols = cols; a.ldc = cols; a.kc = (int)c->M;
+  if (packed) {                    // P packed along time: the contraction in packed order, whole bytes of eight steps
+    a.packed = 1; a.pk_T = c->T; a.pk_B = c->B;
+    a.kc = (c->T + 7) / 8 * 8 * c->B;
+  }
   a.kc_per_split = (int)per;
   a.c_split_stride = (long long)rows * cols;
   a.C = splits > 1 ? part : out;
@@ -568,9 +589,14 @@ int ensure_loss(snn_ctx *c) {
 // are queued on `w`, their partial sums on `jobs` (one reduction launch for all layers).
 int queue_weight_grad(snn_ctx *c, int l, WgradJobs &w, ReduceJobs &jobs) {
   Layer &y = c->layers[l];
+  // Layer 1 after a forward pass on the packed raster: the product reads the bits itself when the
+  // batch is a multiple of 8 (its contraction tiles are eight samples wide); else unpack first.
+  const bool packed = l == 0 && c->x_direct && !c->x_unpacked && c->B % 8 == 0;
+  if (l == 0 && !packed) { int rc = ensure_unpacked_input(c); if (rc) return rc; }
   SpikeSrc s = spikes_below(c, l);
+  if (packed) s = {c->x_packed, c->sizes[0], c->sizes[0], (unsigned)((long long)((c->T + 7) / 8) * c->B * c->sizes[0])};
   if (!s.p) return fail(c, SNN_ERR_NULL, "input raster is NULL");
-  int rc = queue_tn(c, w, s, y.K, y.dI, y.ld, y.N, y.dW, y.part_w, y.splits_w, y.per_w);
+  int rc = queue_tn(c, w, s, y.K, y.dI, y.ld, y.N, y.dW, y.part_w, y.splits_w, y.per_w, packed);
   if (rc) return rc;
   bool ok = add_reduce_job(jobs, y.part_w, y.dW, y.splits_w, (long long)y.K * y.N);
   if (y.recurrent) {
@@ -883,9 +909,11 @@ int launch_layer_forward(snn_ctx *c, int l, int nl, int with_readout, const int3
   Layer &y = c->layers[l];
   LayerForwardArgs a;
   memset(&a, 0, sizeof a);
+  const bool packed = l == 0 && c->x_direct;           // the bottom layer reads the raster packed along time
   for (int i = 0; i < nl; ++i) {
     Layer &yi = c->layers[l + i];
-    const SpikeSrc s = spikes_below(c, l + i);
+    SpikeSrc s = spikes_below(c, l + i);
+    if (packed && i == 0) s = {c->x_packed, c->sizes[0], c->sizes[0], (unsigned)((long long)((c->T + 7) / 8) * c->B * c->sizes[0])};
     if (!s.p) return fail(c, SNN_ERR_NULL, "input raster is NULL");
     LayerForwardOp &op = a.op[i];
     op.P = s.p; op.ldp = s.ld; op.kc = s.valid; op.p_bytes = s.bytes;
@@ -899,11 +927,12 @@ int launch_layer_forward(snn_ctx *c, int l, int nl, int with_readout, const int3
   Bracket br(c, SNN_K_LIF_FORWARD, l + 1);
   const int bn = y.ld % 128 ? 64 : c->opt[SNN_OPT_LAYER_NEURONS];   // 128: 108.0 us per step at 700-128-128-20, 64: 109.7
   const dim3 grid((unsigned)(rup(c->B, 8) * (y.ld / bn)));
-#define SNN_LFWD(RO)                                                                                             \
+#define SNN_LFWD2(RO, PK)                                                                                        \
   do {                                                                                                           \
-    if (nl == 2) hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 2>), grid, dim3(256), 0, c->stream, a);  \
-    else hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 1>), grid, dim3(256), 0, c->stream, a);          \
+    if (nl == 2) hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 2, PK>), grid, dim3(256), 0, c->stream, a); \
+    else hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 1, PK>), grid, dim3(256), 0, c->stream, a);      \
   } while (0)
+#define SNN_LFWD(RO) do { if (packed) SNN_LFWD2(RO, true); else SNN_LFWD2(RO, false); } while (0)
   if (with_readout) {
     Layer &ro = c->layers[c->L - 1];
     a.J = ro.I; a.ldj = c->ldC; a.Qr = ro.Qf; a.ldqr = ro.ldqf; a.qr_bytes = (unsigned)(ro.qf_plane * 2);
@@ -918,9 +947,12 @@ int launch_layer_forward(snn_ctx *c, int l, int nl, int with_readout, const int3
       SNN_LFWD(1);
     }
     ro.i_ready = true;
-  } else if (bn == 64) hipLaunchKernelGGL((lif_layer_forward_kernel<1, 4>), grid, dim3(256), 0, c->stream, a);
-  else SNN_LFWD(0);
+  } else if (bn == 64) {
+    if (packed) hipLaunchKernelGGL((lif_layer_forward_kernel<1, 4, 0, 1, true>), grid, dim3(256), 0, c->stream, a);
+    else hipLaunchKernelGGL((lif_layer_forward_kernel<1, 4>), grid, dim3(256), 0, c->stream, a);
+  } else SNN_LFWD(0);
 #undef SNN_LFWD
+#undef SNN_LFWD2
   HIPCHK(c, hipGetLastError());
   return SNN_OK;
 }
@@ -1210,6 +1242,13 @@ int32_t snn_init(const snn_config *cfg, void *workspace_dev, size_t workspace_by
   return SNN_OK;
 }
 
+// Whether the forward pass runs layer 1 as one launch (the rule of forward_layers below).
+static bool first_layer_runs_whole(snn_ctx *c) {
+  const int whole = layer_fuse_mode(c);
+  const bool whole_top = whole >= 2 && layer_forward_fusable(c, c->L - 2);
+  return whole >= 1 && (0 < c->L - 2 || whole_top) && layer_forward_fusable(c, 0);
+}
+
 static int32_t forward_layers(snn_ctx *c, const int32_t *labels_dev, float *loss_host) {
   int rc;
   const int whole = layer_fuse_mode(c);                 // layers that run as one launch, product and scan
@@ -1261,7 +1300,14 @@ int32_t snn_forward_packed(snn_ctx *c, const uint8_t *x_packed_dev, const int32_
   if (!x_packed_dev || !labels_dev) return fail(c, SNN_ERR_NULL, "x_packed_dev or labels_dev is NULL");
   c->labels_dev = labels_dev;
   int rc;
-  if ((rc = prepare_packed_input(c, x_packed_dev))) return rc;
+  // Where layer 1 runs as one launch, that launch (and the weight-gradient launch) reads the packed
+  // raster itself: rows of a multiple of 4 bytes, at most 1024 channels.  Otherwise the raster is
+  // unpacked into the workspace first.
+  c->x_packed = x_packed_dev;
+  c->x_direct = c->sizes[0] % 4 == 0 && c->sizes[0] <= 1024 && (uintptr_t)x_packed_dev % 4 == 0 && first_layer_runs_whole(c);
+  c->x_unpacked = false;
+  if (c->x_direct) c->x_eff = nullptr;
+  else if ((rc = prepare_packed_input(c, x_packed_dev))) return rc;
   return forward_layers(c, labels_dev, loss_host);
 }
 

@@ -703,32 +703,57 @@ def test_deep_rec2048_full_size_sampled():
 
 
 # ---------------------------------------------------------------- input packed along time
-@pytest.mark.parametrize("T", [37, 40])
-def test_packed_input_matches_plain_input(T):
+PACKED_SHAPES = [((45, 29, 13, 3), 7), ((64, 40, 10), 7),                 # unpacked by the pre-pass (narrow layers)
+                 ((64, 128, 128, 10), 8), ((700, 128, 128, 20), 16),       # layer 1 and the weight gradients read the bits
+                 ((100, 256, 64, 10), 24), ((60, 128, 10), 5)]             # (batch not a multiple of 8: bits forward only)
+
+
+@pytest.mark.parametrize("T", [37, 40, 130])
+@pytest.mark.parametrize("sizes,B", PACKED_SHAPES, ids=[f"{'-'.join(map(str, s))}-B{b}" for s, b in PACKED_SHAPES])
+def test_packed_input_matches_plain_input(T, sizes, B):
     """snn_forward_packed on numpy.packbits(X, axis=0) (the paper's storage format, Section
-    2.1.4) must give bit-identical tensors to snn_forward on X, for T a multiple of 8 and
-    not, and row lengths that are and are not multiples of 4; the plain path is the one
-    held against the oracle by the other tests (and once more here)."""
-    for sizes in ((45, 29, 13, 3), (64, 40, 10)):
-        wl = workloads.Workload(name="packed", index=16, T=T, B=7, sizes=sizes, recurrent=(False,) * (len(sizes) - 2),
-                                beta=(0.9,) * (len(sizes) - 1), theta=1.0, surrogate="superspike", slope=25.0,
-                                precision="bf16", rate_lo=0.1, rate_hi=0.3)
-        inp = workloads.generate(wl, w_gain=2.5)
-        net = net_of(wl)
-        snn = make(wl, inp)
-        loss = snn.forward(inp.X, inp.labels)
-        parity.compare_forward(net, inp, snn, loss, {})
-        names = [("spikes", 1), ("membrane", 1), ("readout_trace", 0), ("logits", 0), ("loss_per_sample", 0)]
-        plain = [snn.get_tensor(n, l) if l else snn.get_tensor(n) for n, l in names]
-        xp = np.packbits(inp.X, axis=0)
-        assert xp.shape == ((T + 7) // 8, wl.B, sizes[0])
-        loss_p = snn.forward_packed(xp, inp.labels)
-        assert loss_p == loss
-        for (n, l), ref in zip(names, plain):
-            got = snn.get_tensor(n, l) if l else snn.get_tensor(n)
-            assert np.array_equal(got, ref), n
-        snn.backward()
-        snn.destroy()
+    2.1.4) must give bit-identical tensors to snn_forward on X, forward and backward, for T a
+    multiple of 8 and not, one and two blocks of 128 steps, row lengths that are and are not
+    multiples of 4, layers that run as one launch (whose product loader and the weight-gradient
+    loader then read the bits themselves) and layers that do not (unpacked by a pre-pass); the
+    plain path is the one held against the oracle by the other tests (and once more here)."""
+    wl = workloads.Workload(name="packed", index=16, T=T, B=B, sizes=sizes, recurrent=(False,) * (len(sizes) - 2),
+                            beta=(0.9,) * (len(sizes) - 1), theta=1.0, surrogate="superspike", slope=25.0,
+                            precision="bf16", rate_lo=0.1, rate_hi=0.3)
+    inp = workloads.generate(wl, w_gain=2.5)
+    net = net_of(wl)
+    L = len(sizes) - 1
+    snn = make(wl, inp, {"layer_min_batch": 1})
+    loss = snn.forward(inp.X, inp.labels)
+    parity.compare_forward(net, inp, snn, loss, {})
+    fwd_names = [("spikes", 1), ("membrane", 1), ("readout_trace", 0), ("logits", 0), ("loss_per_sample", 0)]
+    bwd_names = [("grad_w", l) for l in range(1, L + 1)] + [("d_current", 1), ("current", 1)]
+    fetch = lambda names: [snn.get_tensor(n, l) if l else snn.get_tensor(n) for n, l in names]
+    plain = fetch(fwd_names)
+    snn.backward()
+    plain += fetch(bwd_names)
+    xp = np.packbits(inp.X, axis=0)
+    assert xp.shape == ((T + 7) // 8, wl.B, sizes[0])
+    if T % 8:
+        xp[-1] |= np.uint8((1 << (8 - T % 8)) - 1)           # bits of steps beyond T are to be ignored: set them all
+    loss_p = snn.forward_packed(xp, inp.labels)
+    assert loss_p == loss
+    got = fetch(fwd_names)
+    snn.backward()
+    got += fetch(bwd_names)
+    for (n, l), ref, g in zip(fwd_names + bwd_names, plain, got):
+        if (n, l) == ("grad_w", 1):
+            # read from the bits, the product walks the T*B rows in another order (a packed row of eight
+            # samples per tile): the same sum to fp32 rounding, and the oracle's to the usual bound
+            assert np.abs(g - ref).max() <= 2e-6 * np.abs(ref).max(), (n, l)
+        else:
+            assert np.array_equal(g, ref), (n, l)
+    assert np.abs(plain[5]).max() > 0
+    tr = O.forward(net, inp.X, inp.W, inp.R, inp.labels)
+    if all(np.array_equal(t.astype(np.uint8), snn.get_tensor("spikes", l + 1)) for l, t in enumerate(tr.S)):
+        gr = O.backward(net, inp.X, inp.W, inp.R, inp.labels, tr)
+        parity.close_grad("dW^1 from the packed raster", got[5], gr.dW[0])
+    snn.destroy()
 
 
 # ---------------------------------------------------------------- integral cross-entropy
