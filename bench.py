@@ -61,8 +61,9 @@ def reverse_forms_ds(wl, layer):
     """Whether the reverse scan of text layer `layer` forms dS from the current gradients above itself
     (bf16 products, feed-forward, a multiple of 64 wide, at most 128 padded columns above)."""
     L = len(wl.sizes) - 1
-    return (wl.precision == "bf16" and 1 <= layer < L and not wl.recurrent[layer - 1] and wl.sizes[layer] % 64 == 0
-            and pad8(wl.sizes[layer + 1]) <= 128)
+    if not (wl.precision == "bf16" and 1 <= layer < L and not wl.recurrent[layer - 1]):
+        return False
+    return wl.sizes[layer] % 64 == 0 and pad8(wl.sizes[layer + 1]) <= 128
 
 
 def algorithmic_bytes(wl, kernel, layer):

@@ -196,7 +196,10 @@ typedef enum {
  *   LAYER_PAIR        1 (default): two consecutive one-launch layers of exactly 128 padded
  *                     neurons share a launch; 0: one launch each
  *   LAYER_REVERSE     1 (default): the reverse pass of a layer of 64..256 neurons below a layer of
- *                     at most 128 columns runs as one launch (dS product, surrogate, scan); 0: off
+ *                     at most 128 columns runs as one launch (dS product, surrogate, scan; dS is
+ *                     not stored); 2: so does that of a layer that is a multiple of 128 wide below a
+ *                     wider layer (measured slower than product + scan, hence not the default);
+ *                     0: off
  *   TOP_SCANS         1 (default): the scans of a layer below at most 128 columns form the
  *                     narrow products themselves (readout currents forward, dS reverse); 0: off
  *   DEFER_REDUCE      1 (default): snn_backward leaves the per-split partial sums of the weight

@@ -740,9 +740,26 @@ int launch_lif_reverse(snn_ctx *c, int l) {
 // lane also at large widths: at 1024 neurons below the readout the fused scan takes 216 us
 // where the four-chains-per-lane scan plus the readout's input-gradient launch took 290 + 100.)
 int columns_above(const snn_ctx *c, int l) { return l + 1 == c->L - 1 ? c->ldC : c->layers[l + 1].ld; }
+// Below a WIDER layer (more than 128 columns) the whole reverse layer can run as one launch whose
+// dS product walks the long contraction on the streamed pipeline (lif_layer_reverse_kernel, WIDE):
+// layers that are a multiple of 128 wide, as many samples as the one-launch layers ask for.
+// Only on request (SNN_OPT_LAYER_REVERSE = 2): measured, it is slower than the input-gradient
+// product followed by the scan at every width tried (700-512-512-20, 256 steps, 256 samples: 195 us
+// against 84 + 69; 700-1024-1024-20, 256 steps, 512 samples: 1421 us against 526 + 270).  A
+// workgroup walks one sample through time, so the 64 rows of a block lie B x columns x 4 bytes
+// apart (2 MiB at the second shape), every stage waits out a full memory latency with three stages
+// (48 KiB) in flight per compute unit, and the weights of its 128 neurons (256 KiB) pass through
+// the compute unit again for every 64 steps.
+bool reverse_wide(const snn_ctx *c, int l) {
+  if (c->opt[SNN_OPT_LAYER_REVERSE] != 2 || l < 0 || l > c->L - 2) return false;
+  const Layer &y = c->layers[l];
+  const int min_b = c->opt[SNN_OPT_LAYER_MIN_BATCH] > 0 ? c->opt[SNN_OPT_LAYER_MIN_BATCH] : c->T <= 256 ? 1 : 64;
+  return c->hl && y.spiking && !y.recurrent && !y.adaptive && y.ld % 128 == 0 && columns_above(c, l) > 128 && c->B >= min_b;
+}
 bool reverse_fusable(const snn_ctx *c, int l) {
-  if (!c->opt[SNN_OPT_TOP_SCANS]) return false;
   if (l < 0 || l > c->L - 2) return false;
+  if (reverse_wide(c, l)) return true;
+  if (!c->opt[SNN_OPT_TOP_SCANS]) return false;
   const Layer &y = c->layers[l];
   return c->hl && y.spiking && !y.recurrent && !y.adaptive && y.ld % 64 == 0 && columns_above(c, l) <= 128;
 }
@@ -791,7 +808,7 @@ bool layer_reverse_whole(snn_ctx *c, int l) {
   if (!c->opt[SNN_OPT_LAYER_REVERSE]) return false;
   const Layer &y = c->layers[l];
   const int min_b = layer_min_batch(c);
-  return reverse_fusable(c, l) && y.ld <= 256 && c->B >= min_b &&
+  return reverse_fusable(c, l) && !reverse_wide(c, l) && y.ld <= 256 && c->B >= min_b &&
          (size_t)c->M * y.ld * 4 < ((size_t)1 << 31) && (size_t)c->M * columns_above(c, l) * 4 < ((size_t)1 << 31);
 }
 
@@ -828,7 +845,32 @@ int launch_layer_reverse(snn_ctx *c, int l) {
   return SNN_OK;
 }
 
+int launch_layer_reverse_wide(snn_ctx *c, int l) {
+  Layer &y = c->layers[l];
+  Layer &up = c->layers[l + 1];
+  LayerReverseArgs a;
+  memset(&a, 0, sizeof a);
+  a.dX = up.dI; a.ldc = columns_above(c, l);
+  a.Wq = up.Qb; a.ldq = up.ldqb; a.wq_bytes = (unsigned)(up.qb_plane * 2);
+  a.V = y.V; a.dI = y.dI; a.beta_v = y.beta_v; a.theta = c->theta; a.slope = c->slope; a.db_part = y.part_b;
+  a.T = c->T; a.B = c->B; a.ld = y.ld;
+  a.nt_store = streams_past_cache(c, c->M * y.ld * 4);
+  Bracket br(c, SNN_K_LIF_REVERSE, l + 1);
+  const dim3 grid((unsigned)(rup(c->B, 8) * (y.ld / 128))), block(256);
+  switch (c->surrogate) {
+    case 0: hipLaunchKernelGGL((lif_layer_reverse_kernel<1, 0, 128, true>), grid, block, 0, c->stream, a); break;
+    case 1: hipLaunchKernelGGL((lif_layer_reverse_kernel<1, 1, 128, true>), grid, block, 0, c->stream, a); break;
+    case 2: hipLaunchKernelGGL((lif_layer_reverse_kernel<1, 2, 128, true>), grid, block, 0, c->stream, a); break;
+    case 3: hipLaunchKernelGGL((lif_layer_reverse_kernel<1, 3, 128, true>), grid, block, 0, c->stream, a); break;
+    case 4: hipLaunchKernelGGL((lif_layer_reverse_kernel<1, 4, 128, true>), grid, block, 0, c->stream, a); break;
+    default: hipLaunchKernelGGL((lif_layer_reverse_kernel<1, 5, 128, true>), grid, block, 0, c->stream, a); break;
+  }
+  HIPCHK(c, hipGetLastError());
+  return SNN_OK;
+}
+
 int launch_lif_reverse_fused(snn_ctx *c, int l) {
+  if (reverse_wide(c, l)) return launch_layer_reverse_wide(c, l);
   if (layer_reverse_whole(c, l)) return launch_layer_reverse(c, l);
   Layer &y = c->layers[l];
   Layer &up = c->layers[l + 1];
@@ -1550,8 +1592,8 @@ int32_t snn_set_option(snn_ctx *c, int32_t option, int32_t value) {
   bool ok;
   switch (option) {
     case SNN_OPT_LAYER_FORWARD: ok = value >= 0 && value <= 4; break;
+    case SNN_OPT_LAYER_REVERSE: ok = value >= 0 && value <= 2; break;
     case SNN_OPT_LAYER_PAIR:
-    case SNN_OPT_LAYER_REVERSE:
     case SNN_OPT_TOP_SCANS:
     case SNN_OPT_DEFER_REDUCE:
     case SNN_OPT_STREAM_GEMM: ok = value == 0 || value == 1; break;

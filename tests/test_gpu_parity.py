@@ -234,6 +234,55 @@ def test_layer_reverse_in_one_launch(T, sizes, surrogate, slope):
     assert rep["spike_rate"][0] > 0.005
 
 
+@pytest.mark.parametrize("T,sizes,surrogate,slope,nt", [(150, (90, 128, 256, 20), "superspike", 10.0, False),
+                                                         (64, (60, 512, 384, 10), "arctan", 2.0, False),
+                                                         (30, (330, 1024, 960, 20), "sigmoid", 4.0, True),
+                                                         (70, (50, 256, 200, 12), "triangular", 1.0, False),
+                                                         (129, (40, 128, 136, 256, 5), "boxcar", 1.0, False),
+                                                         (33, (70, 384, 1024, 3), "ste", 1.0, True)],
+                         ids=["128-below-256", "512-below-384", "1024-below-960", "256-below-200-columns",
+                              "128-below-136-below-256", "384-below-1024"])
+def test_layer_reverse_in_one_launch_below_a_wide_layer(T, sizes, surrogate, slope, nt):
+    """bf16 products, a feed-forward layer that is a multiple of 128 wide below a layer of more
+    than 128 columns: on request the reverse layer runs as one launch whose dS = dI W^T product streams the
+    hi/lo words of the layer above and its weights through LDS in stages of 32 columns (dS read
+    back afterwards comes from the product kernel and must agree with the oracle as well).  One
+    to three blocks of 64 steps with ragged first blocks, 136 to 1024 columns above (five to 32
+    stages, with and without a ragged last one), every surrogate, stores with and without the
+    non-temporal hint, five samples (three of the eight launched workgroups have none)."""
+    L = len(sizes) - 1
+    wl = workloads.Workload(name="layer-reverse-wide", index=34, T=T, B=5, sizes=sizes, recurrent=(False,) * (L - 1),
+                            beta=(0.9, 0.93, 0.95, 0.9)[:L], theta=1.0, surrogate=surrogate, slope=slope, precision="bf16",
+                            rate_lo=0.03, rate_hi=0.12)
+    options = {"layer_min_batch": 1, "layer_reverse": 2}
+    if nt:
+        options["stream_min_mb"] = 0
+    rep = full_step_parity(wl, w_gain=2.0, options=options)
+    assert rep["spike_rate"][0] > 0.005
+
+
+def test_layer_reverse_below_a_wide_layer_same_as_separate_launches():
+    """The same backward pass with the one-launch reverse layers switched off (input-gradient
+    product, then scan): current gradients and weight gradients agree to rounding; and with the
+    decays trained, whose gradient the one-launch scan accumulates itself."""
+    wl = workloads.Workload(name="layer-reverse-wide-cmp", index=35, T=100, B=12, sizes=(80, 256, 512, 10),
+                            recurrent=(False, False), beta=(0.9, 0.93, 0.95), theta=1.0, surrogate="superspike", slope=25.0,
+                            precision="bf16", rate_lo=0.03, rate_hi=0.12)
+    inp = workloads.generate(wl, w_gain=2.0)
+    out = []
+    for knob in (2, 1):
+        snn = make(wl, inp, {"layer_min_batch": 1, "layer_reverse": knob})
+        snn.forward(inp.X, inp.labels)
+        snn.backward()
+        out.append([snn.get_tensor("d_current", 1), snn.get_tensor("d_spikes", 1), snn.get_tensor("grad_w", 1),
+                    snn.get_tensor("grad_w", 2)])
+        snn.destroy()
+    for a, b in zip(*out):
+        assert np.abs(a - b).max() <= 1e-5 * np.abs(b).max()
+    assert np.abs(out[0][0]).max() > 0
+    beta_step_parity(wl, w_gain=2.0, options={"layer_min_batch": 1, "layer_reverse": 2})
+
+
 def test_layer_reverse_in_one_launch_with_trainable_decays():
     """The same path with the decay gradients' partial sums taken inside the scan."""
     beta_step_parity(workloads.CONFIGS["shd_ff128"].scaled(T=100, B=12), w_gain=3.0, options={"layer_min_batch": 1})
@@ -632,7 +681,7 @@ def test_error_paths():
     assert snn.lib.snn_set_option(snn.ctx, 99, 0) == 2
     assert snn.lib.snn_set_option(snn.ctx, -1, 0) == 2
     for name, bad_value in (("layer_forward", 5), ("layer_pair", 2), ("layer_neurons", 96), ("tile_rows", 48),
-                            ("layer_max_neurons", 2048), ("stream_min_mb", -1), ("layer_min_batch", -3)):
+                            ("layer_max_neurons", 2048), ("stream_min_mb", -1), ("layer_min_batch", -3), ("layer_reverse", 3)):
         before = snn.get_option(name)
         with pytest.raises(SnnError) as e:
             snn.set_option(name, bad_value)
