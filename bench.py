@@ -209,6 +209,8 @@ def main():
                     help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs of this command")
     ap.add_argument("--packed", action="store_true",
                     help="feed the raster packed along time (eight spikes per byte) through snn_forward_packed")
+    ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
+                    help="kernel-selection option of the context (binding.OPTIONS), repeatable")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the per-launch table and the fp32-products run (profiler runs)")
@@ -228,7 +230,8 @@ def main():
     wl = workloads.CONFIGS[args.workload]
     inp = workloads.generate(wl)
     dev = torch.device("cuda:0")
-    snn = from_workload(wl, inp, device="cuda:0")
+    options = {k: int(v) for k, v in (o.split("=", 1) for o in args.option)}
+    snn = from_workload(wl, inp, device="cuda:0", options=options or None)
     x = torch.from_numpy(inp.X).to(dev)
     y = torch.from_numpy(inp.labels).to(dev)
     lr = 1e-3
@@ -347,7 +350,7 @@ def main():
                                f"bf16 products / fp32 state" + (", input packed along time" if args.packed else "")
                                if wl.precision == "bf16" else
                                f"{wl.name}: {'-'.join(map(str, wl.sizes))}, T={wl.T}, B={wl.B}, fp32",
-                   "final_loss": loss, "spike_rate": spike_rate,
+                   "options": options, "final_loss": loss, "spike_rate": spike_rate,
                    "note": "weights N(0, 1/sqrt(fan_in)) as the configuration states them: the hidden layers are "
                            "almost silent; no kernel branches on a spike, so the time per step does not depend on it"},
         "roofline": {"bound": "hbm", "kernel": f"{kname}" + (f" layer {klayer}" if klayer else " (all layers)"),

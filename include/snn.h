@@ -212,7 +212,13 @@ typedef enum {
  *                     (non-temporal accesses, the streamed current product); default 128
  *   STREAM_GEMM       1 (default): such current products use the streamed kernel; 0: the general one
  *   TILE_ROWS         rows per workgroup tile of the general products: 0 (default) = by shape,
- *                     or 32, 64, 128 */
+ *                     or 32, 64, 128
+ *   LAYER_TIME_SPLIT  0 (default): one workgroup per sample, blocks of 128 steps; 1: a one-launch
+ *                     forward layer of 128 neurons per workgroup gives each sample to two workgroups
+ *                     that take its blocks of 64 steps in turn (the product of the next block runs
+ *                     while this one is scanned; the state is handed over through memory).  Measured
+ *                     no faster at 700-128-128-20, T = 128, B = 256 (each workgroup still loads all of
+ *                     W per block, and the loads are what bounds the product): on request only */
 typedef enum {
   SNN_OPT_LAYER_FORWARD = 0,
   SNN_OPT_LAYER_PAIR = 1,
@@ -225,7 +231,8 @@ typedef enum {
   SNN_OPT_STREAM_MIN_MB = 8,
   SNN_OPT_STREAM_GEMM = 9,
   SNN_OPT_TILE_ROWS = 10,
-  SNN_OPT_COUNT = 11
+  SNN_OPT_LAYER_TIME_SPLIT = 11,
+  SNN_OPT_COUNT = 12
 } snn_option;
 
 /* Validate `cfg` and report the device bytes snn_init needs (a multiple of 256).

@@ -89,17 +89,18 @@ template <int WM, int WN, int TM, int TN, int NS>
 struct SpikeTile {
   static_assert(WM * WN == 4, "four wavefronts per workgroup");
   static constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-  static constexpr int PT = BM * 32, QT = BN * 64, ST = PT + QT;   // bytes: P part, Q part, stage (32 k)
-  static constexpr int PI = BM / 128, QI = BN / 64;                 // load instructions per wavefront and stage
+  // (a tile of 64 rows still gives P a whole KiB per wavefront and stage: the rows beyond the tile
+  // are loaded as rows outside the product, i.e. as zeros, and never read)
+  static constexpr int PT = (BM < 128 ? 128 : BM) * 32, QT = BN * 64, ST = PT + QT;   // bytes: P part, Q part, stage (32 k)
+  static constexpr int PI = PT / 4096, QI = BN / 64;                // load instructions per wavefront and stage
   static constexpr int NL = PI + QI;
-  static_assert(BM % 128 == 0 && BN % 64 == 0, "whole KiB per wavefront");
+  static_assert(BM % 64 == 0 && BN % 64 == 0, "whole KiB per wavefront");
   static_assert(NS >= 4, "the waits assume at least four stages");
   typedef u32x4 frag_t;
   // Packed P operand: the whole block of the sample (BM / 8 packed rows of up to 1024 bytes) sits
   // in LDS for all stages, ahead of the stages, which then hold Q alone.  A row pitch of 1088 bytes
   // puts the four packed rows a fragment read touches on different banks.
-  static constexpr int PKP = 1088, PKB = (BM / 8) * PKP;
-  static_assert(PKB % 1024 == 0, "the stages behind the packed block start on a KiB");
+  static constexpr int PKP = 1088, PKB = ((BM / 8) * PKP + 1023) / 1024 * 1024;   // (the stages behind it start on a KiB)
   static constexpr int lds_bytes(bool pk) { return pk ? PKB + NS * QT : NS * ST; }
 
   // Global side of the loads.  P instruction q of a wavefront fills rows 32 (wave + 4 q) ..
@@ -126,30 +127,42 @@ struct SpikeTile {
     constexpr int NLK = PK ? QI : NL;               // load instructions per wavefront and stage
     char *const stages = lds + (PK ? PKB : 0);
     const unsigned lds0 = (unsigned)(uintptr_t)(lds_ptr_t)stages;
-    u32x4 pkx[4];
+    constexpr int PKN = BM / 32;                    // 16-byte pieces of the packed block per thread
+    u32x4 pkx[PKN];
     if (PK) {
-      // the block's packed rows: 16 rows x 64 pieces of 16 bytes, four pieces per thread; pieces
-      // beyond the last packed row or the row length read as zero
+      // the block's packed rows: BM / 8 rows x 64 pieces of 16 bytes, BM / 32 pieces per thread;
+      // pieces beyond the last packed row or the row length read as zero
       const int tid = 64 * wave + lane;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < PKN; ++j) {
         const int piece = tid + 256 * j, r = piece >> 6, c = (piece & 63) * 16;
         pkx[j] = ld_b128(pk->rsrc, r < pk->rows && c < pk->kbytes ? r * pk->row_stride + c : OOB, pk->base);
       }
     }
     // Stage kt into buffer `buf`.  Beyond the contraction range the descriptors get size 0:
     // the instruction count (which the vmcnt waits rely on) stays the same, nothing is fetched.
+    struct IssueRegs {                                  // scalar operands of one stage's loads
+      u32x4 p, q;
+      unsigned dst;
+      int kt;
+    };
+    auto issue_prepare = [&](int kt_any, int buf) {
+      IssueRegs r;
+      r.kt = __builtin_amdgcn_readfirstlane(kt_any);          // uniform; keeps the offsets scalar
+      r.p = rp; r.q = rq;
+      if (r.kt >= nk) r.p.z = r.q.z = 0;
+      r.dst = __builtin_amdgcn_readfirstlane(lds0 + buf * STQ + 1024 * wave);
+      asm volatile("" : "+s"(r.p.z), "+s"(r.q.z), "+s"(r.dst), "+s"(r.kt));   // formed here, not next to the loads
+      return r;
+    };
+    auto issue_load = [&](const IssueRegs &r, int n) {        // load instruction n of the stage (P first)
+      if (n < NLK - QI) load_to_lds_b128(r.p, r.dst + 4096 * n, pv[n < PI ? n : 0], r.kt * 32);
+      else load_to_lds_b128(r.q, r.dst + QOFF + 4096 * (n - (NLK - QI)), qv[n - (NLK - QI)], r.kt * 64);
+    };
     auto issue = [&](int kt_any, int buf) {
-      const int kt = __builtin_amdgcn_readfirstlane(kt_any);   // uniform; keeps the offsets scalar
-      u32x4 p = rp, qr = rq;
-      if (kt >= nk) p.z = qr.z = 0;
-      const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + buf * STQ + 1024 * wave);
-      if (!PK) {
+      const IssueRegs r = issue_prepare(kt_any, buf);
 #pragma unroll
-        for (int q = 0; q < PI; ++q) load_to_lds_b128(p, dst + 4096 * q, pv[q], kt * 32);
-      }
-#pragma unroll
-      for (int q = 0; q < QI; ++q) load_to_lds_b128(qr, dst + QOFF + 4096 * q, qv[q], kt * 64);
+      for (int n = 0; n < NLK; ++n) issue_load(r, n);
     };
 
     // LDS side of the fragment reads: lane half h reads P unit h (16 k, two MFMA steps' worth)
@@ -162,7 +175,6 @@ struct SpikeTile {
 #pragma unroll
       for (int st = 0; st < 2; ++st) fb[st] = QOFF + rb * 64 + (((2 * h + st) ^ ((rb >> 2) & 3)) << 4);
     }
-    const unsigned pk_shift = 7 - (lane & 7);       // the lane's time step inside its packed byte (first step: bit 7)
 
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -171,60 +183,115 @@ struct SpikeTile {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    auto read_first = [&](int buf, int kt, frag_t (&pa)[TM], frag_t (&qb)[TN]) {   // P bytes of stage kt, Q of its step 0
+    // Registers of one stage: its P bytes, spread (a spike is 0x40 in its byte), the Q fragments of
+    // its MFMA step 0, and the P fragments of step 0.
+    struct StageRegs {
+      frag_t pa[TM], qb[TN];
+      bf16x8 af[TM];
+    };
+    // Spike bytes to bfloat16 with two instructions per four spikes.  0x40 in the upper byte of a
+    // bfloat16 is 2.0, so a spike byte becomes an operand by one shift of its dword (0/1 -> 0x00/0x40
+    // in each byte; from the packed form: a rotation that brings the lane's bit to bit 6 of every
+    // byte, and a mask) and one byte permutation per pair.  The products come out doubled, exactly
+    // (a power of two), and are halved after the last stage.
+    // (the lane's step is bit 7 - lane % 8 of a packed byte: a rotation to the right by that minus 6, mod 32)
+    const unsigned pk_rot = (unsigned)(1 - (lane & 7)) & 31u;
+    auto spread = [&](frag_t &w) {
+#pragma unroll
+      for (int d = 0; d < 4; ++d)
+        w[d] = PK ? (__builtin_amdgcn_alignbit(w[d], w[d], pk_rot) & 0x40404040u) : (w[d] << 6);
+    };
+    auto convert = [&](uint32_t t0, uint32_t t1) {
+      u32x4 d;
+      d.x = __builtin_amdgcn_perm(0u, t0, 0x010C000Cu);
+      d.y = __builtin_amdgcn_perm(0u, t0, 0x030C020Cu);
+      d.z = __builtin_amdgcn_perm(0u, t1, 0x010C000Cu);
+      d.w = __builtin_amdgcn_perm(0u, t1, 0x030C020Cu);
+      return __builtin_bit_cast(bf16x8, d);
+    };
+    auto read_first = [&](int buf, int kt, StageRegs &r) {    // P bytes of stage kt (as stored), Q of its step 0
       const char *st = stages + buf * STQ;
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        if (PK) {
-          const frag_t w = *(const frag_t *)(lds + fa + i * 4 * PKP + kt * 32);
+      for (int i = 0; i < TM; ++i)
+        r.pa[i] = PK ? *(const frag_t *)(lds + fa + i * 4 * PKP + kt * 32) : *(const frag_t *)(st + fa + i * 1024);
 #pragma unroll
-          for (int d = 0; d < 4; ++d) pa[i][d] = (w[d] >> pk_shift) & 0x01010101u;
-        } else {
-          pa[i] = *(const frag_t *)(st + fa + i * 1024);
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < TN; ++j) qb[j] = *(const frag_t *)(st + fb[0] + j * 2048);
+      for (int j = 0; j < TN; ++j) r.qb[j] = *(const frag_t *)(st + fb[0] + j * 2048);
     };
-    auto products = [&](const frag_t (&pa)[TM], const frag_t (&qb)[TN], int st) {
-      bf16x8 af[TM];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const uint32_t w0 = pa[i][2 * st], w1 = pa[i][2 * st + 1];
-        u32x4 d;
-        d.x = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w0, 0x0C010C00u));
-        d.y = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w0, 0x0C030C02u));
-        d.z = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w1, 0x0C010C00u));
-        d.w = spikes2_to_bf16(__builtin_amdgcn_perm(0u, w1, 0x0C030C02u));
-        af[i] = __builtin_bit_cast(bf16x8, d);
-      }
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, qb[j]), af[i], acc[i][j], 0, 0, 0);
+    // One stage in buffer u.  On entry the stage's P bytes, its step-0 Q fragments and its converted
+    // step-0 P fragments are in registers (or on their way).  The barrier sits between the two MFMA
+    // steps: past it, every wavefront has left stage kt-1 (its buffer, u+NS-1, may be overwritten:
+    // the loads of stage kt+NS-1 go there) and has seen its own loads of stage kt+1 land (so buffer
+    // u+1 is complete and its first fragments can be read under the MFMAs of step 1).
+    //
+    // One wavefront per SIMD: nothing but this wavefront's own independent instructions fills the
+    // 32 cycles an MFMA keeps the matrix unit.  The order is therefore fixed by hand (scheduling
+    // barriers), one MFMA, then the few conversion instructions of a fragment needed later:
+    // step 1's fragments under the MFMAs of step 0, the next stage's step-0 fragments under the last
+    // MFMAs of step 1, the fragment reads and the load issue right behind the barrier under the
+    // first ones.  Left to the scheduler, the conversions of a whole stage sit in front of its first
+    // MFMA and the fragment reads of a stage at its top, each followed by its wait.
+    auto pin = [&](bf16x8 &f) {                             // the fragment is formed here, not next to its use
+      u32x4 x = __builtin_bit_cast(u32x4, f);
+      asm volatile("" : "+v"(x));
+      f = __builtin_bit_cast(bf16x8, x);
     };
-    // One stage in buffer u.  On entry the stage's P bytes (pa) and step-0 Q fragments (qb) are
-    // in registers (or on their way).  The barrier sits between the two MFMA steps: past it,
-    // every wavefront has left stage kt-1 (its buffer, u+3, may be overwritten: the loads of
-    // stage kt+3 go there) and has seen its own loads of stage kt+1 land (so buffer u+1 is
-    // complete and its first fragments can be read under the MFMAs of step 1).
-    auto stage = [&](int u, int kt, frag_t (&pa)[TM], frag_t (&qb)[TN], frag_t (&pa_next)[TM], frag_t (&qb_next)[TN]) {
+    auto stage = [&](int u, int kt, StageRegs &cur, StageRegs &nxt) {
+      constexpr int M = TM * TN;                        // MFMAs per step
       frag_t q1[TN];
 #pragma unroll
       for (int j = 0; j < TN; ++j) q1[j] = *(const frag_t *)(stages + u * STQ + fb[1] + j * 2048);
-      products(pa, qb, 0);
-      // (ties the accumulators to this point: the MFMAs of step 0 are issued before the waits,
-      // not moved behind the barrier by the scheduler)
+      bf16x8 a1[TM];
+      IssueRegs ir;
+      __builtin_amdgcn_sched_barrier(0);
+      static_for<M>([&](auto X) {
+        constexpr int x = decltype(X)::value, i = x / TN, j = x % TN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cur.qb[j]), cur.af[i], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (x < TM) {
+          a1[x] = convert(cur.pa[x][2], cur.pa[x][3]);
+          pin(a1[x]);
+        }
+        if constexpr (x == (TM < M - 1 ? TM : M - 1)) ir = issue_prepare(kt + NS - 1, (u + NS - 1) % NS);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      // (ties the accumulators to this point: the MFMAs of step 0 are issued before the waits)
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(acc[i][j]));
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 3) * NLK) : "memory");   // younger stages may still be in flight
       lds_barrier();
-      issue(kt + NS - 1, (u + NS - 1) % NS);
-      read_first((u + 1) % NS, kt + 1, pa_next, qb_next);
-      products(pa, q1, 1);
+      {
+        const char *st = stages + ((u + 1) % NS) * STQ;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+          nxt.pa[i] = PK ? *(const frag_t *)(lds + fa + i * 4 * PKP + (kt + 1) * 32) : *(const frag_t *)(st + fa + i * 1024);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      constexpr int L0 = M - TM >= 2 ? (NLK < 2 ? NLK : 2) : NLK;   // load instructions behind the first MFMA
+      static_for<M>([&](auto X) {
+        constexpr int x = decltype(X)::value, i = x / TN, j = x % TN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, q1[j]), a1[i], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (x == 0) {
+#pragma unroll
+          for (int n = 0; n < L0; ++n) issue_load(ir, n);
+        }
+        if constexpr (x == (L0 < NLK ? 1 : 0)) {
+#pragma unroll
+          for (int n = L0; n < NLK; ++n) issue_load(ir, n);
+          const char *st = stages + ((u + 1) % NS) * STQ;
+#pragma unroll
+          for (int jj = 0; jj < TN; ++jj) nxt.qb[jj] = *(const frag_t *)(st + fb[0] + jj * 2048);
+        }
+        if constexpr (x >= M - TM) {
+          constexpr int i2 = x - (M - TM);
+          spread(nxt.pa[i2]);
+          nxt.af[i2] = convert(nxt.pa[i2][0], nxt.pa[i2][1]);
+          pin(nxt.af[i2]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      });
     };
 
 #pragma unroll
@@ -234,33 +301,48 @@ struct SpikeTile {
       // well: memory returns loads in order)
       const int tid = 64 * wave + lane;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < PKN; ++j) {
         const int piece = tid + 256 * j;
         *(u32x4 *)(lds + (piece >> 6) * PKP + (piece & 63) * 16) = pkx[j];
       }
     }
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NLK) : "memory");
     lds_barrier();
-    frag_t pa0[TM], qb0[TN], pa1[TM], qb1[TN];
-    read_first(0, 0, pa0, qb0);
+    StageRegs r0, r1;
+    read_first(0, 0, r0);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      spread(r0.pa[i]);
+      r0.af[i] = convert(r0.pa[i][0], r0.pa[i][1]);
+    }
     // Unrolled over the buffers (twice when their number is odd, so that the two fragment
-    // register sets alternate consistently).
+    // register sets alternate consistently): whole rounds in one block of straight-line code, the
+    // stages left over (fewer than a round) behind it.
     constexpr int UN = NS % 2 ? 2 * NS : NS;
-    for (int kt = 0; kt < nk; kt += UN) {
-      bool done = false;
+    int kt = 0;
+    for (; kt + UN <= nk; kt += UN) {
       static_for<UN>([&](auto U) {
         constexpr int u = decltype(U)::value;
-        if (!done) {
-          if constexpr (u % 2 == 0) stage(u % NS, kt + u, pa0, qb0, pa1, qb1);
-          else stage(u % NS, kt + u, pa1, qb1, pa0, qb0);
-          if (kt + u + 1 >= nk) done = true;
-        }
+        if constexpr (u % 2 == 0) stage(u % NS, kt + u, r0, r1);
+        else stage(u % NS, kt + u, r1, r0);
       });
-      if (done) break;
     }
+    static_for<UN - 1>([&](auto U) {
+      constexpr int u = decltype(U)::value;
+      if (kt + u < nk) {
+        if constexpr (u % 2 == 0) stage(u % NS, kt + u, r0, r1);
+        else stage(u % NS, kt + u, r1, r0);
+      }
+    });
     // The loads beyond the range wrote zeros: they too are over before the buffers are reused.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     lds_barrier();
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] *= 0.5f;
   }
 };
 

@@ -38,6 +38,16 @@
 // PACKED: the bottom layer of the launch reads the input raster packed along time (eight steps
 // per byte, Section 2.1.4): the 16 packed rows of the sample's block sit in LDS for the whole
 // product and are unpacked between the fragment read and the MFMA; the stages carry W alone.
+// TS = 2 (blocks of 64 steps, TMV = 1): two workgroups share a sample and take its blocks in turn.
+// Only the scan needs the block before it; the product of block k + 1 (most of a block's time)
+// does not, so it runs on the other workgroup while block k is still being scanned.  What the
+// scan of block k + 1 needs - the potentials after block k, and for the readout its state, the
+// running maximum, its step and the running sum - goes through a small buffer in memory: written
+// with device-scope accesses, the writer waits for its stores to be acknowledged and then raises
+// a flag, the reader polls the flag (a bounded number of times: if the flag never comes, the
+// error bit 1 is set and the kernel still ends) and reads with device-scope loads.  The workgroup
+// of a sample's first block has the lower id, so it is never dispatched after the one that
+// waits for it.
 #pragma once
 #include "gemm_stream.hpp"
 
@@ -83,21 +93,49 @@ struct LayerForwardArgs {
   uint32_t *dJ;            // [T*B][ldj] hi/lo words
   const float *beta_r;     // [ldj] decays of the readout
   int C;                   // classes
+  // Time-split variants (TS = 2): per sample SNN_HAND_BYTES of hand-over space.  Dwords 0..15:
+  // flags (one per layer of the launch, [2]: the readout), each holding epoch * 1024 + the number of
+  // blocks whose state has been published; then per layer two slots of 128 potentials; then two
+  // slots of 256 x 4 dwords of readout state (state, running maximum, its step, running sum per
+  // thread).  `epoch` grows with every launch, so flags never have to be cleared.
+  uint32_t *hand;
+  int epoch;
 };
+#define SNN_HAND_BYTES 12288
+constexpr int HAND_V = 16, HAND_R = 16 + 2 * 2 * 128;      // dword offsets of the potential slots and the readout slots
+
+__device__ __forceinline__ void hand_store(uint32_t *p, uint32_t x) {
+  __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t hand_load(const uint32_t *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// One thread polls until the flag has reached `want` (wrap-safe), at most 2^20 times (about a
+// second); then sets bit 1 of the error word and goes on, so that the grid always drains.
+__device__ __forceinline__ void hand_wait(const uint32_t *flag, uint32_t want, int *err) {
+  int n = 0;
+  while ((int)(hand_load(flag) - want) < 0) {
+    if (++n >= (1 << 20)) { atomicOr(err, 2); break; }
+    __builtin_amdgcn_s_sleep(2);
+  }
+}
 
 // READOUT: 0 none; 1 the launch also forms the readout's currents J; 2 and the LI scan, the
 // maximum over time, the loss and dJ; 3 the same with the integral loss.
-template <int TN, int NS = 4, int READOUT = 0, int NL = 1, bool PACKED = false>
+template <int TN, int NS = 4, int READOUT = 0, int NL = 1, bool PACKED = false, int TS = 1>
 __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerForwardArgs a) {
   static_assert(!READOUT || TN == 2, "the readout variants hold the whole layer");
   static_assert(NL == 1 || (NL == 2 && TN == 2), "a chain of layers: whole layers of 128 neurons");
+  static_assert(TS == 1 || (TS == 2 && TN == 2), "two workgroups per sample: whole layers of 128 neurons");
   constexpr bool LOSS = READOUT >= 2, INTEGRAL = READOUT == 3;
-  constexpr int JP = 36;                              // floats between rows of the 128 x 32 readout tile in LDS
+  constexpr int JP = 36;                              // floats between rows of the BM x 32 readout tile in LDS
   __shared__ float x_e[LOSS ? 2 : 1][8][32], x_best[8][32];
   __shared__ int x_tb[8][32];
-  typedef SpikeTile<2, 2, 2, TN, NS> Tile;
-  constexpr int TM = 2, WN = 2, BM = Tile::BM, BN = Tile::BN, PI = Tile::PI, QI = Tile::QI;
-  static_assert(BM == 128 && PI == 1 && (BN == 64 || BN == 128), "128 steps x 64 or 128 neurons");
+  constexpr int TM = TS == 2 ? 1 : 2;                 // blocks of 64 steps when two workgroups share a sample
+  typedef SpikeTile<2, 2, TM, TN, NS> Tile;
+  constexpr int WN = 2, BM = Tile::BM, BN = Tile::BN, PI = Tile::PI, QI = Tile::QI;
+  constexpr int SEG = BM / 8;                         // steps per segment of the readout scan (eight segments per block)
+  static_assert((BM == 128 || BM == 64) && PI == 1 && (BN == 64 || BN == 128), "128 or 64 steps x 64 or 128 neurons");
   constexpr int CP = BN * 4 + 16;                     // bytes between time rows of the current tile in LDS
   constexpr int TILE = BM * CP;
   constexpr int STAGES = Tile::lds_bytes(false) > Tile::lds_bytes(PACKED) ? Tile::lds_bytes(false) : Tile::lds_bytes(PACKED);
@@ -106,10 +144,16 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
   __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
 
   // Workgroup ids are dealt round-robin to the 8 XCDs: the parts of a sample take ids 8 apart.
+  // With TS = 2 the two workgroups of a sample part take ids 8 x parts apart, the one of the first
+  // block first.
   const int parts = a.ld / BN;
   const int part = (blockIdx.x >> 3) % parts;
-  const int b = (blockIdx.x >> 3) / parts * 8 + (blockIdx.x & 7);
+  const int half = TS == 1 ? 0 : ((blockIdx.x >> 3) / parts) % TS;
+  const int b = (blockIdx.x >> 3) / (parts * TS) * 8 + (blockIdx.x & 7);
   if (b >= a.B) return;
+  const int nblocks = (a.T + BM - 1) / BM;
+  uint32_t *const hand = TS == 2 ? a.hand + ((size_t)b * parts + part) * (SNN_HAND_BYTES / 4) : nullptr;
+  const uint32_t hand_base = (uint32_t)a.epoch * 1024u;
   const int n0 = part * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN, h = lane >> 5;
@@ -134,13 +178,14 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
 
   // Readout state of class tid % 32 (variants with the loss)
   const float beta_r = LOSS && (tid & 31) < a.ldj ? a.beta_r[tid & 31] : 0.f;
-  float bseg = beta_r;                                // beta^16
+  float bseg = beta_r;                                // beta^SEG
 #pragma unroll
-  for (int i = 0; i < 4; ++i) bseg *= bseg;
+  for (int i = 1; i < SEG; i *= 2) bseg *= bseg;
   float y_in = 0.f, best = -INFINITY, ysum = 0.f;
   int tb = 0, par = 0;
 
-  for (int t0 = 0; t0 < a.T; t0 += BM) {
+  for (int blk = half; blk < nblocks; blk += TS) {
+   const int t0 = blk * BM;
    static_for<NL>([&](auto LI) {
     constexpr int li = decltype(LI)::value;
     constexpr bool last = li == NL - 1;
@@ -158,7 +203,7 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
     int pv[PI];
     {
       const int row = Tile::p_row(wave, lane, 0);
-      pv[0] = t0 + row < a.T ? ((t0 + row) * a.B + b) * op.ldp + Tile::p_unit(row, lane) * 16 : OOB;
+      pv[0] = row < BM && t0 + row < a.T ? ((t0 + row) * a.B + b) * op.ldp + Tile::p_unit(row, lane) * 16 : OOB;
     }
     f32x16 acc[TM][TN];
     if constexpr (PACKED && li == 0) {
@@ -189,13 +234,19 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
           const int row = (wm * TM + i) * 32 + (lane & 31), col = (wn * TN + j) * 32 + 8 * q + 4 * h;
           *(u32x4 *)(lds + row * CP + col * 4) = x;
         }
+    if (TS == 2 && blk > 0 && tid == 0) hand_wait(hand + li, hand_base + blk, a.err);   // the block before has been scanned
     __syncthreads();
 
-    // 3. scan (steps past T run on zero currents; nothing of them is stored, and v is not
-    // used after the last block)
+    // 3. scan and store.  The wavefronts that hold no neuron (256 - BN threads) store what the scan
+    // has finished, 16 steps behind it: after every 16 steps a barrier, behind which they read the
+    // 16 rows of potentials back from the tile and write V (BN/4 pieces of 16 bytes per row) and S
+    // (BN/16 pieces of 16 neurons per row, decided from V as in the scan) while the scan goes on
+    // with the next rows.  (Steps past T run on zero currents; nothing of them is stored, and v is
+    // not used after the last block.)
+    constexpr int U = 16;
     if (wave < BN / 64) {
+      if (TS == 2 && blk > 0) v[li] = __uint_as_float(hand_load(hand + HAND_V + (li * 2 + ((blk - 1) & 1)) * 128 + tid));
       float *cell = (float *)(lds + tid * 4);
-      constexpr int U = 16;
       float nxt[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) nxt[u] = cell[u * (CP / 4)];
@@ -218,39 +269,48 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
           asm("v_fma_f32 %0, %1, %2, %3 clamp" : "=v"(s) : "v"(v[li]), "v"(big), "v"(mtheta_big));
           v[li] = __builtin_fmaf(mtheta, s, __builtin_fmaf(beta[li], v[li], cur[u]));
         }
+        __syncthreads();                              // rows s0 .. s0+15 hold potentials
+      }
+      if (TS == 2 && blk + 1 < nblocks) {             // hand the potentials on to the workgroup of the next block
+        hand_store(hand + HAND_V + (li * 2 + (blk & 1)) * 128 + tid, __float_as_uint(v[li]));
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      }
+    } else {
+      constexpr int NT_ = 256 - BN, VL = BN / 4, SL = BN / 16;   // storing threads; pieces per row of V and of S
+      const int st = tid - BN;
+      for (int s0 = 0; s0 < BM; s0 += U) {
+        __syncthreads();
+#pragma unroll
+        for (int p0 = 0; p0 < U * VL; p0 += NT_) {
+          const int p = p0 + st, row = s0 + p / VL, col = (p % VL) * 4;
+          if (U * VL % NT_ == 0 || p < U * VL) {
+            const u32x4 x = *(const u32x4 *)(lds + row * CP + col * 4);
+            const int vo = t0 + row < a.T ? (((t0 + row) * a.B + b) * a.ld + n0 + col) * 4 : OOB;
+            if (a.nt_store) __builtin_amdgcn_raw_buffer_store_b128(x, rV, vo, 0, NT);
+            else __builtin_amdgcn_raw_buffer_store_b128(x, rV, vo, 0, 0);
+          }
+        }
+#pragma unroll
+        for (int p0 = 0; p0 < U * SL; p0 += NT_) {
+          const int p = p0 + st, row = s0 + p / SL, col = (p % SL) * 16;
+          if (p < U * SL) {
+            u32x4 x;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const f32x4 f = *(const f32x4 *)(lds + row * CP + (col + 4 * q) * 4);
+              x[q] = (f[0] > theta ? 1u : 0u) | (f[1] > theta ? 0x100u : 0u) | (f[2] > theta ? 0x10000u : 0u) |
+                     (f[3] > theta ? 0x1000000u : 0u);
+            }
+            const int so = t0 + row < a.T ? ((t0 + row) * a.B + b) * a.ld + n0 + col : OOB;
+            if (a.nt_store) __builtin_amdgcn_raw_buffer_store_b128(x, rS, so, 0, NT);
+            else __builtin_amdgcn_raw_buffer_store_b128(x, rS, so, 0, 0);
+          }
+        }
       }
     }
     __syncthreads();
+    if (TS == 2 && blk + 1 < nblocks && tid == 0) hand_store(hand + li, hand_base + blk + 1);
 
-    // 4. store.  V: BN/4 lanes x 16 bytes per row.  S: BN/16 lanes x 16 neurons per row.
-    {
-      constexpr int LPR = BN / 4, RPI = 256 / LPR;
-#pragma unroll
-      for (int k = 0; k < BM / RPI; ++k) {
-        const int row = RPI * k + tid / LPR, col = (tid % LPR) * 4;
-        const u32x4 x = *(const u32x4 *)(lds + row * CP + col * 4);
-        const int vo = t0 + row < a.T ? (((t0 + row) * a.B + b) * a.ld + n0 + col) * 4 : OOB;
-        if (a.nt_store) __builtin_amdgcn_raw_buffer_store_b128(x, rV, vo, 0, NT);
-        else __builtin_amdgcn_raw_buffer_store_b128(x, rV, vo, 0, 0);
-      }
-    }
-    {
-      constexpr int LPR = BN / 16, RPI = 256 / LPR;
-#pragma unroll
-      for (int k = 0; k < BM / RPI; ++k) {
-        const int row = RPI * k + tid / LPR, col = (tid % LPR) * 16;
-        u32x4 x;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const f32x4 p = *(const f32x4 *)(lds + row * CP + (col + 4 * q) * 4);
-          x[q] = (p[0] > theta ? 1u : 0u) | (p[1] > theta ? 0x100u : 0u) | (p[2] > theta ? 0x10000u : 0u) |
-                 (p[3] > theta ? 0x1000000u : 0u);
-        }
-        const int so = t0 + row < a.T ? ((t0 + row) * a.B + b) * a.ld + n0 + col : OOB;
-        if (a.nt_store) __builtin_amdgcn_raw_buffer_store_b128(x, rS, so, 0, NT);
-        else __builtin_amdgcn_raw_buffer_store_b128(x, rS, so, 0, 0);
-      }
-    }
     // 5. readout currents of the block: J^T (32 classes x 128 steps) = W_out^T S^T, a wavefront
     // takes 32 steps.  Second operand: lane -> step 32 wave + (lane & 31), neurons 16 kk + 8 h
     // .. +7, their spikes decided once more from V in the tile (exactly as in the scan) and
@@ -260,7 +320,8 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
       f32x16 jt;
 #pragma unroll
       for (int r = 0; r < 16; ++r) jt[r] = 0.f;
-      const int row = 32 * wave + (lane & 31);
+      const int row = 32 * wave + (lane & 31);          // (blocks of 64 steps: the first two wavefronts)
+      if (row < BM) {
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
         const f32x4 p0 = *(const f32x4 *)(lds + row * CP + (16 * kk + 8 * h) * 4);
@@ -282,26 +343,37 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
         const int jo = t0 + row < a.T && c + 3 < a.ldj ? (((t0 + row) * a.B + b) * a.ldj + c) * 4 : OOB;
         __builtin_amdgcn_raw_buffer_store_b128(x, rJ, jo, 0, 0);
       }
+      }
       if (LOSS) {
-        // 6. readout scan of the block.  The LI readout is linear in its state, so the 128 steps
-        // are cut in eight segments of 16: thread -> (segment tid / 32, class tid % 32).  A
+        // 6. readout scan of the block.  The LI readout is linear in its state, so the block's steps
+        // are cut in eight segments of SEG: thread -> (segment tid / 32, class tid % 32).  A
         // segment is first integrated from a zero state, the results are exchanged, the state
         // entering each segment follows, and the segment is integrated again from it, step by
         // step as the sequential scan would (the scheme of readout_loss_kernel, which has the
         // eight wavefronts of a workgroup where this has the eight 32-lane groups).
+        if (TS == 2 && blk > 0 && tid == 0) hand_wait(hand + 2, hand_base + blk, a.err);   // the readout has passed the block before
         __syncthreads();                              // V has been stored: the tile's space is free
+        if (TS == 2 && blk > 0) {
+          const uint32_t *src = hand + HAND_R + (((blk - 1) & 1) * 256 + tid) * 4;
+          y_in = __uint_as_float(hand_load(src));
+          best = __uint_as_float(hand_load(src + 1));
+          tb = (int)hand_load(src + 2);
+          ysum = __uint_as_float(hand_load(src + 3));
+        }
         float *Jt = (float *)lds;
+        if (row < BM) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          f32x4 x = {jt[4 * q], jt[4 * q + 1], jt[4 * q + 2], jt[4 * q + 3]};
-          *(f32x4 *)&Jt[row * JP + 8 * q + 4 * h] = x;
+          for (int q = 0; q < 4; ++q) {
+            f32x4 x = {jt[4 * q], jt[4 * q + 1], jt[4 * q + 2], jt[4 * q + 3]};
+            *(f32x4 *)&Jt[row * JP + 8 * q + 4 * h] = x;
+          }
         }
         __syncthreads();
-        const int g = tid >> 5, c = tid & 31, ts0 = t0 + 16 * g;
-        float j[16], e = 0.f;
+        const int g = tid >> 5, c = tid & 31, ts0 = t0 + SEG * g;
+        float j[SEG], e = 0.f;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
-          j[k] = Jt[(16 * g + k) * JP + c];
+        for (int k = 0; k < SEG; ++k) {
+          j[k] = Jt[(SEG * g + k) * JP + c];
           e = beta_r * e + j[k];
         }
         x_e[par][g][c] = e;
@@ -314,17 +386,26 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
         }
         y_in = cst;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
+        for (int k = 0; k < SEG; ++k) {
           y = beta_r * y + j[k];
-          Jt[(16 * g + k) * JP + c] = y;
+          Jt[(SEG * g + k) * JP + c] = y;
           if (INTEGRAL) { if (ts0 + k < a.T) ysum += y; }
           else if (ts0 + k < a.T && y > best) { best = y; tb = ts0 + k; }
         }
         par ^= 1;
+        if (TS == 2 && blk + 1 < nblocks) {           // hand the readout's state on
+          uint32_t *dst = hand + HAND_R + ((blk & 1) * 256 + tid) * 4;
+          hand_store(dst, __float_as_uint(y_in));
+          hand_store(dst + 1, __float_as_uint(best));
+          hand_store(dst + 2, (uint32_t)tb);
+          hand_store(dst + 3, __float_as_uint(ysum));
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
         __syncthreads();
+        if (TS == 2 && blk + 1 < nblocks && tid == 0) hand_store(hand + 2, hand_base + blk + 1);
         const rsrc_t rY = make_rsrc(a.Y, (unsigned)a.T * a.B * a.ldj * 4u);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {                 // 8 lanes x 16 bytes per row, 32 rows per instruction
+        for (int k = 0; k < BM / 32; ++k) {           // 8 lanes x 16 bytes per row, 32 rows per instruction
           const int r = 32 * k + (tid >> 3), cc = (tid & 7) * 4;
           const u32x4 x = *(const u32x4 *)&Jt[r * JP + cc];
           st_b128(rY, t0 + r < a.T && cc + 3 < a.ldj ? (((t0 + r) * a.B + b) * a.ldj + cc) * 4 : OOB, 0, x);
@@ -338,7 +419,7 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
    });
   }
 
-  if (LOSS) {
+  if (LOSS && (TS == 1 || half == (nblocks - 1) % TS)) {   // (two workgroups per sample: the one of the last block)
     // first maximiser over the segments (integral loss: the sum of the segments' sums, in order)
     const int g = tid >> 5, c = tid & 31;
     x_best[g][c] = INTEGRAL ? ysum : best;
@@ -379,7 +460,7 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
     const float l2b = log2f(beta_r);
     const rsrc_t rdJ = make_rsrc(a.dJ, (unsigned)a.T * a.B * a.ldj * 4u);
     uint32_t *Ht = (uint32_t *)lds;
-    for (int t0 = 0; t0 < a.T; t0 += BM) {
+    for (int t0 = 0; t0 < a.T; t0 += 128) {             // (128 steps at a time, whatever the block size above)
       const int ts0 = t0 + 16 * g;
       float hh;
       if (INTEGRAL) {

@@ -103,7 +103,10 @@ struct snn_ctx {
   const int32_t *labels_dev = nullptr;
   ReduceJobs pending;             // partial sums of the last backward pass that have not been added yet
   bool reduce_pending = false;
-  int opt[SNN_OPT_COUNT] = {4, 1, 1, 1, 1, 0, 128, 1024, 128, 1, 0};   // snn_option values, in the enum's order
+  int opt[SNN_OPT_COUNT] = {4, 1, 1, 1, 1, 0, 128, 1024, 128, 1, 0, 0};   // snn_option values, in the enum's order
+  uint32_t *hand = nullptr;       // hand-over space of the forward launches that give a sample to two workgroups
+  int hand_parts = 1;             // hand-over regions per sample (one per column block of a layer)
+  int fwd_epoch = 0;              // number of such launches so far (their flags count from epoch * 1024)
   std::string err;
   Prof prof;
 };
@@ -318,6 +321,9 @@ void carve(snn_ctx &c, Carver &cv) {
   c.z = cv.take<float>((size_t)c.B * c.ldC);
   c.dz = cv.take<float>((size_t)c.B * c.ldC);
   c.tstar = cv.take<int>((size_t)c.B * c.ldC);
+  c.hand_parts = 1;                                    // column blocks of the widest layer (64 neurons at least each)
+  for (const Layer &y : c.layers) c.hand_parts = std::max(c.hand_parts, y.ld / 64);
+  c.hand = cv.take<uint32_t>(rup(c.B, 8) * c.hand_parts * (SNN_HAND_BYTES / 4));
   c.loss_b = cv.take<float>((size_t)c.B);
   c.loss = cv.take<float>(64);
   c.err_flag = cv.take<int>(64);
@@ -966,14 +972,28 @@ int launch_layer_forward(snn_ctx *c, int l, int nl, int with_readout, const int3
   a.theta = c->theta;
   a.T = c->T; a.B = c->B; a.ld = y.ld;
   a.nt_store = streams_past_cache(c, c->M * y.ld * 4);
-  Bracket br(c, SNN_K_LIF_FORWARD, l + 1);
+  a.err = c->err_flag;
   const int bn = y.ld % 128 ? 64 : c->opt[SNN_OPT_LAYER_NEURONS];   // 128: 108.0 us per step at 700-128-128-20, 64: 109.7
-  const dim3 grid((unsigned)(rup(c->B, 8) * (y.ld / bn)));
-#define SNN_LFWD2(RO, PK)                                                                                        \
+  // Two workgroups per sample, taking its blocks of 64 steps in turn (SNN_OPT_LAYER_TIME_SPLIT, on
+  // request: 29.3 us against 28.8 at 700-128-128-20, T = 128, B = 256): from two blocks on, and while a
+  // block count fits the flags' 10 bits.
+  const bool split = c->opt[SNN_OPT_LAYER_TIME_SPLIT] && bn == 128 && c->T > 64 && c->T <= 64 * 1000;
+  if (split) {
+    if (++c->fwd_epoch >= (1 << 21)) {                // long before the flags' counter wraps: start over
+      HIPCHK(c, fill_zero(c->stream, c->hand, rup(c->B, 8) * c->hand_parts * SNN_HAND_BYTES));
+      c->fwd_epoch = 1;
+    }
+    a.hand = c->hand;
+    a.epoch = c->fwd_epoch;
+  }
+  Bracket br(c, SNN_K_LIF_FORWARD, l + 1);
+  const dim3 grid((unsigned)(rup(c->B, 8) * (y.ld / bn) * (split ? 2 : 1)));
+#define SNN_LFWD3(RO, PK, TS_)                                                                                   \
   do {                                                                                                           \
-    if (nl == 2) hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 2, PK>), grid, dim3(256), 0, c->stream, a); \
-    else hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 1, PK>), grid, dim3(256), 0, c->stream, a);      \
+    if (nl == 2) hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 2, PK, TS_>), grid, dim3(256), 0, c->stream, a); \
+    else hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 1, PK, TS_>), grid, dim3(256), 0, c->stream, a); \
   } while (0)
+#define SNN_LFWD2(RO, PK) do { if (split) SNN_LFWD3(RO, PK, 2); else SNN_LFWD3(RO, PK, 1); } while (0)
 #define SNN_LFWD(RO) do { if (packed) SNN_LFWD2(RO, true); else SNN_LFWD2(RO, false); } while (0)
   if (with_readout) {
     Layer &ro = c->layers[c->L - 1];
@@ -981,7 +1001,7 @@ int launch_layer_forward(snn_ctx *c, int l, int nl, int with_readout, const int3
     if (with_readout == 2) {
       if (!labels) return fail(c, SNN_ERR_NULL, "labels are NULL");
       a.Y = ro.V; a.z = c->z; a.tstar = c->tstar; a.labels = labels; a.loss_b = c->loss_b; a.dz = c->dz;
-      a.err = c->err_flag; a.dJ = ro.dI; a.beta_r = ro.beta_v; a.C = c->C;
+      a.dJ = ro.dI; a.beta_r = ro.beta_v; a.C = c->C;
       if (c->integral) SNN_LFWD(3); else SNN_LFWD(2);
       c->dj_ready = true;
       c->loss_ready = false;
@@ -995,6 +1015,7 @@ int launch_layer_forward(snn_ctx *c, int l, int nl, int with_readout, const int3
   } else SNN_LFWD(0);
 #undef SNN_LFWD
 #undef SNN_LFWD2
+#undef SNN_LFWD3
   HIPCHK(c, hipGetLastError());
   return SNN_OK;
 }
@@ -1114,6 +1135,7 @@ int check_err_flag(snn_ctx *c) {
   HIPCHK(c, hipStreamSynchronize(c->stream));
   if (flag) {
     HIPCHK(c, fill_zero(c->stream, c->err_flag, 256));
+    if (flag & 2) return fail(c, SNN_ERR_HIP, "a forward launch gave up waiting for the workgroup that shares its sample");
     return fail(c, SNN_ERR_ARG, "a label was outside [0, C)");
   }
   return SNN_OK;
@@ -1594,6 +1616,7 @@ int32_t snn_set_option(snn_ctx *c, int32_t option, int32_t value) {
     case SNN_OPT_LAYER_FORWARD: ok = value >= 0 && value <= 4; break;
     case SNN_OPT_LAYER_REVERSE: ok = value >= 0 && value <= 2; break;
     case SNN_OPT_LAYER_PAIR:
+    case SNN_OPT_LAYER_TIME_SPLIT:
     case SNN_OPT_TOP_SCANS:
     case SNN_OPT_DEFER_REDUCE:
     case SNN_OPT_STREAM_GEMM: ok = value == 0 || value == 1; break;

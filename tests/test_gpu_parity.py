@@ -189,6 +189,40 @@ def test_layer_forward_in_one_launch(T, sizes, nt, bn):
     assert rep["spike_rate"][0] > 0.005
 
 
+@pytest.mark.parametrize("T,sizes,loss,packed", [(70, (150, 192, 256, 20), "max", False), (150, (203, 128, 128, 20), "max", False),
+                                                  (260, (90, 128, 128, 10), "integral", False), (200, (64, 128, 10), "max", True),
+                                                  (128, (700, 128, 128, 20), "max", True)],
+                         ids=["two-blocks-two-parts", "three-blocks-readout", "five-blocks-integral", "four-blocks-packed",
+                              "headline-packed"])
+def test_layer_forward_two_workgroups_per_sample(T, sizes, loss, packed):
+    """The one-launch forward layer with each sample given to two workgroups that take its blocks
+    of 64 steps in turn (on request): potentials, the readout's state and the running maximum
+    are handed from block to block through memory.  Two to five blocks with ragged tails, a
+    layer in two column parts (each part its own hand-over), both losses, plain and packed
+    input; run three times in a row on one context (the hand-over flags count launches)."""
+    L = len(sizes) - 1
+    wl = workloads.Workload(name="time-split", index=19, T=T, B=6, sizes=sizes, recurrent=(False,) * (L - 1),
+                            beta=(0.9, 0.93, 0.95)[:L], theta=1.0, surrogate="superspike", slope=10.0, precision="bf16",
+                            rate_lo=0.03, rate_hi=0.12, loss=loss)
+    options = {"layer_min_batch": 1, "layer_time_split": 1}
+    rep = full_step_parity(wl, w_gain=2.0, options=options)
+    assert rep["spike_rate"][0] > 0.005
+    inp = workloads.generate(wl, w_gain=2.0)
+    snn = make(wl, inp, options)
+    xp = np.packbits(inp.X, axis=0)
+    outs = []
+    for k in range(3):
+        if packed and k == 1:
+            snn.forward_packed(xp, inp.labels)
+        else:
+            snn.forward(inp.X, inp.labels)
+        outs.append([snn.get_tensor("spikes", L - 1), snn.get_tensor("membrane", L - 1), snn.get_tensor("loss_per_sample")])
+    snn.destroy()
+    for o in outs[1:]:
+        for a, b in zip(o, outs[0]):
+            assert np.array_equal(a, b)
+
+
 def test_layer_forward_in_one_launch_same_as_separate_launches():
     """The same forward pass with and without the one-launch layers: potentials and readout
     agree to rounding, spikes are identical away from the threshold."""
@@ -209,8 +243,8 @@ def test_layer_forward_in_one_launch_same_as_separate_launches():
         near = np.abs(ref[0] - wl.theta) <= parity.BAND
         assert np.array_equal(got[1][~near], ref[1][~near])
         if same:
-            for i in (0, 2, 3, 5, 6, 7):
-                assert np.abs(got[i] - ref[i]).max() <= 1e-5 * np.abs(ref[i]).max()
+            for i in (0, 2, 3, 5, 6, 7):      # 6 is a gradient (softmax of the readout): the gradients' tolerance
+                assert np.abs(got[i] - ref[i]).max() <= (1e-4 if i == 6 else 1e-5) * np.abs(ref[i]).max()
     assert ref[1].mean() > 0.005
 
 
