@@ -182,6 +182,7 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
 #pragma unroll
   for (int i = 1; i < SEG; i *= 2) bseg *= bseg;
   float y_in = 0.f, best = -INFINITY, ysum = 0.f;
+  int lab = LOSS ? a.labels[b] : 0;                   // (asked for here: the epilogue would wait a memory round trip for it)
   int tb = 0, par = 0;
 
   for (int blk = half; blk < nblocks; blk += TS) {
@@ -445,7 +446,6 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
     float sum = ex;
 #pragma unroll
     for (int o = 16; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-    int lab = a.labels[b];
     if (lab < 0 || lab >= a.C) { if (tid == 0) atomicOr(a.err, 1); lab = 0; }
     float zl = (live && c == lab) ? best : 0.f;
 #pragma unroll

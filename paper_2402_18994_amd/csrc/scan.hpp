@@ -980,6 +980,15 @@ __global__ __launch_bounds__(256) void reduce_update_kernel(const ReduceUpdateJo
     if (part) {
       float acc[4] = {0.f, 0.f, 0.f, 0.f};
       int s = 0;
+      // (all loads of a round are in flight before the first sum: the kernel is a few memory round
+      // trips long, and 32 splits are one round instead of four)
+      for (; s + 32 <= splits; s += 32) {
+        float v[32];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) v[u] = part[(size_t)(s + u) * kn + idx];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) acc[u & 3] += v[u];
+      }
       for (; s + 8 <= splits; s += 8) {
         float v[8];
 #pragma unroll
