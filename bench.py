@@ -30,8 +30,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 # device copy this script issues first: FETCH_SIZE reads half the bytes of that copy, WRITE_SIZE
 # all of them).  Not measured by this run: the figure is the one in the named summary, which the
 # same command produced under the profiler; --traffic replaces it.
-PROFILED_TRAFFIC = {
-    ("shd_ff128", "lif_forward"): ((15234.7 * 2.0 + 50256.0) * 1024.0, "profiles/train_step_shd_ff128.txt"),
+PROFILED_TRAFFIC = {           # (workload, kernel, input packed along time)
+    ("shd_ff128", "lif_forward", False): ((16129.8 * 2.0 + 50256.0) * 1024.0, "profiles/train_step_shd_ff128.txt"),
+    ("shd_ff128", "lif_forward", True): ((5373.2 * 2.0 + 51792.0) * 1024.0, "profiles/train_step_shd_ff128.txt"),
 }
 
 
@@ -66,16 +67,20 @@ def reverse_forms_ds(wl, layer):
     return wl.sizes[layer] % 64 == 0 and pad8(wl.sizes[layer + 1]) <= 128
 
 
-def algorithmic_bytes(wl, kernel, layer):
+def algorithmic_bytes(wl, kernel, layer, packed=False):
     """HBM bytes one launch of `kernel` for text layer `layer` has to move (compulsory traffic
-    of its operands and results, each touched once), in the formats this build stores."""
+    of its operands and results, each touched once), in the formats this build stores; `packed`:
+    the input raster is read as eight steps per byte."""
     M = wl.T * wl.B
+    # rows of the raster as the launches of layer 1 read it (they read the bits themselves where layer 1
+    # runs as one launch and, for the weight gradient, the batch is a multiple of 8; else a pre-pass unpacks)
+    x_rows = (wl.T + 7) // 8 * wl.B if packed and forward_chain(wl, 1)[0] and wl.B % 8 == 0 else M
     bf = wl.precision == "bf16"
     di = 4                           # current gradients are 4 bytes in memory in both modes
     planes = 1 if bf else 3
     L = len(wl.sizes) - 1
     if kernel == "weight_grad" and layer == 0:   # the merged launch: every layer's spikes below, dI and dW (+ dR)
-        return sum(algorithmic_bytes(wl, kernel, l) for l in range(1, L + 1))
+        return sum(algorithmic_bytes(wl, kernel, l, packed) for l in range(1, L + 1))
     n_in, n_out = wl.sizes[layer - 1], wl.sizes[layer]
     fused_rev = reverse_forms_ds(wl, layer)
     fused_fwd = fused_rev and layer == L - 1 and n_out in (64, 128, 256) and pad8(wl.sizes[L]) <= 32
@@ -83,7 +88,7 @@ def algorithmic_bytes(wl, kernel, layer):
     if kernel == "lif_forward" and chain:
         # the launch that starts at `layer`: spikes below (1 B) and W (2 B) read; V (4) and S (1) written per
         # layer; with the readout its currents, its trace and its current gradients (4 B each)
-        total = M * n_in
+        total = (x_rows if layer == 1 else M) * n_in
         for l in chain:
             total += 2 * wl.sizes[l - 1] * wl.sizes[l] + M * wl.sizes[l] * (4 + 1)
         if with_readout:
@@ -98,7 +103,7 @@ def algorithmic_bytes(wl, kernel, layer):
         return M * n_in + planes * 2 * n_in * n_out + M * n_out * 4
     if kernel == "weight_grad":      # read spikes and dI, write dW (recurrent: own spikes too, and dR)
         rec = layer < L and wl.recurrent[layer - 1]
-        return M * n_in + M * n_out * di + n_in * n_out * 4 + (M * n_out + n_out * n_out * 4 if rec else 0)
+        return (x_rows if layer == 1 else M) * n_in + M * n_out * di + n_in * n_out * 4 + (M * n_out + n_out * n_out * 4 if rec else 0)
     if kernel == "input_grad":       # read dI and the weight planes, write dS
         return M * n_out * di + planes * 2 * n_in * n_out + M * n_in * 4
     if kernel == "readout_forward":  # J read, Y and dJ written (4 B per padded class)
@@ -306,7 +311,7 @@ def main():
     k_us, k_n = bracketed(kname, klayer, args.steps)   # the same number of steps as the timed region
     k_raw_us = k_us / max(1, k_n)
     k_avg_us = max(k_raw_us - pair_us, 1e-3)
-    abytes = algorithmic_bytes(wl, kname, blayer)
+    abytes = algorithmic_bytes(wl, kname, blayer, args.packed)
     achieved = abytes / k_avg_us / 1e3 if k_n else 0.0
 
     kernels = []
@@ -323,7 +328,7 @@ def main():
             per_launch = us / n - pair_us
             nb = fl = 0
             try:
-                nb = algorithmic_bytes(wl, name, layer if layer else 0) if name not in ("rlif_forward", "rlif_reverse", "grad_reduce", "sgd") else 0
+                nb = algorithmic_bytes(wl, name, layer if layer else 0, args.packed) if name not in ("rlif_forward", "rlif_reverse", "grad_reduce", "sgd") else 0
             except KeyError:
                 nb = 0
             fl = method_flops(wl, name, layer)
@@ -368,8 +373,8 @@ def main():
     if args.traffic is not None:
         out["roofline"]["traffic"] = args.traffic
         out["roofline"]["traffic_source"] = "--traffic"
-    elif (wl.name, kname) in PROFILED_TRAFFIC and not args.packed:
-        out["roofline"]["traffic"], out["roofline"]["traffic_source"] = PROFILED_TRAFFIC[(wl.name, kname)]
+    elif (wl.name, kname, args.packed) in PROFILED_TRAFFIC and not options:
+        out["roofline"]["traffic"], out["roofline"]["traffic_source"] = PROFILED_TRAFFIC[(wl.name, kname, args.packed)]
 
     if not args.no_extras and wl.precision == "bf16":
         # The same shape with fp32 products (the arithmetic of the paper's timing runs, Section 3.1): every
