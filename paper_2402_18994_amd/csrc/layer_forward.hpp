@@ -122,37 +122,28 @@ __device__ __forceinline__ void hand_wait(const uint32_t *flag, uint32_t want, i
 
 // READOUT: 0 none; 1 the launch also forms the readout's currents J; 2 and the LI scan, the
 // maximum over time, the loss and dJ; 3 the same with the integral loss.
-template <int TN, int NS = 4, int READOUT = 0, int NL = 1, bool PACKED = false, int TS = 1>
-__global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerForwardArgs a) {
-  static_assert(!READOUT || TN == 2, "the readout variants hold the whole layer");
-  static_assert(NL == 1 || (NL == 2 && TN == 2), "a chain of layers: whole layers of 128 neurons");
-  static_assert(TS == 1 || (TS == 2 && TN == 2), "two workgroups per sample: whole layers of 128 neurons");
+//
+// The work of one workgroup: NL layers of the launch from layer LI0 on, for the blocks half, half +
+// TS, ... of sample b (TM: 64 TM steps per block).  ROLE: 0 the workgroup depends on no other (or,
+// TS = 2, on the one that takes the sample's other blocks); 1 it runs the lower layer of a pair and
+// tells the workgroup of the upper layer how many 64-step chunks of its spikes have reached memory;
+// 2 it runs the upper layer and waits for the chunk of each of its blocks (see the kernel below).
+template <int TN, int NS, int READOUT, int NL, bool PACKED, int TS, int TM, int LI0, int ROLE>
+__device__ __forceinline__ void lif_layer_forward_body(const LayerForwardArgs &a, char *lds, float (*x_e)[8][32],
+                                                       float (*x_best)[32], int (*x_tb)[32], const int b,
+                                                       const int part, const int parts, const int half) {
   constexpr bool LOSS = READOUT >= 2, INTEGRAL = READOUT == 3;
   constexpr int JP = 36;                              // floats between rows of the BM x 32 readout tile in LDS
-  __shared__ float x_e[LOSS ? 2 : 1][8][32], x_best[8][32];
-  __shared__ int x_tb[8][32];
-  constexpr int TM = TS == 2 ? 1 : 2;                 // blocks of 64 steps when two workgroups share a sample
   typedef SpikeTile<2, 2, TM, TN, NS> Tile;
   constexpr int WN = 2, BM = Tile::BM, BN = Tile::BN, PI = Tile::PI, QI = Tile::QI;
   constexpr int SEG = BM / 8;                         // steps per segment of the readout scan (eight segments per block)
   static_assert((BM == 128 || BM == 64) && PI == 1 && (BN == 64 || BN == 128), "128 or 64 steps x 64 or 128 neurons");
+  static_assert(ROLE == 0 || (TS == 1 && NL == 1 && BM == (ROLE == 1 ? 128 : 64)), "a pair of layers on two workgroups");
   constexpr int CP = BN * 4 + 16;                     // bytes between time rows of the current tile in LDS
-  constexpr int TILE = BM * CP;
-  constexpr int STAGES = Tile::lds_bytes(false) > Tile::lds_bytes(PACKED) ? Tile::lds_bytes(false) : Tile::lds_bytes(PACKED);
-  constexpr int LDS_BYTES = STAGES > TILE ? STAGES : TILE;                 // the stages share the tile's space
-  static_assert(LDS_BYTES <= 80 * 1024, "two workgroups per compute unit");
-  __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+  constexpr int HAND_PAIR = 3;                        // flag of a pair of layers on two workgroups: chunks of 64 steps stored
 
-  // Workgroup ids are dealt round-robin to the 8 XCDs: the parts of a sample take ids 8 apart.
-  // With TS = 2 the two workgroups of a sample part take ids 8 x parts apart, the one of the first
-  // block first.
-  const int parts = a.ld / BN;
-  const int part = (blockIdx.x >> 3) % parts;
-  const int half = TS == 1 ? 0 : ((blockIdx.x >> 3) / parts) % TS;
-  const int b = (blockIdx.x >> 3) / (parts * TS) * 8 + (blockIdx.x & 7);
-  if (b >= a.B) return;
   const int nblocks = (a.T + BM - 1) / BM;
-  uint32_t *const hand = TS == 2 ? a.hand + ((size_t)b * parts + part) * (SNN_HAND_BYTES / 4) : nullptr;
+  uint32_t *const hand = TS == 2 || ROLE ? a.hand + ((size_t)b * parts + part) * (SNN_HAND_BYTES / 4) : nullptr;
   const uint32_t hand_base = (uint32_t)a.epoch * 1024u;
   const int n0 = part * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -160,7 +151,7 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
   float beta[NL], v[NL];                              // decay and potential of neuron n0 + tid % BN, per layer
 #pragma unroll
   for (int li = 0; li < NL; ++li) {
-    beta[li] = a.op[li].beta_v[n0 + tid % BN];
+    beta[li] = a.op[li + LI0].beta_v[n0 + tid % BN];
     v[li] = 0.f;
   }
   const float theta = a.theta;
@@ -190,7 +181,7 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
    static_for<NL>([&](auto LI) {
     constexpr int li = decltype(LI)::value;
     constexpr bool last = li == NL - 1;
-    const LayerForwardOp &op = a.op[li];
+    const LayerForwardOp &op = a.op[li + LI0];
     const int nk = (op.kc + 31) >> 5;
     const u32x4 rp = raw_rsrc(op.P, op.p_bytes), rq = raw_rsrc(op.Q, op.q_bytes);
     const rsrc_t rV = make_rsrc(op.V, (unsigned)a.T * a.B * a.ld * 4u), rS = make_rsrc(op.S, (unsigned)a.T * a.B * a.ld);
@@ -200,14 +191,18 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
       const int row = Tile::q_row(wave, lane, q);
       qv[q] = ((n0 + row) * op.ldq + Tile::q_chunk(row, lane) * 8) * 2;
     }
-    // 1. product
+    // 1. product (the upper layer of a pair on two workgroups: once the block's rows below are in memory)
+    if (ROLE == 2) {
+      if (tid == 0) hand_wait(hand + HAND_PAIR, hand_base + blk + 1, a.err);
+      __syncthreads();
+    }
     int pv[PI];
     {
       const int row = Tile::p_row(wave, lane, 0);
       pv[0] = row < BM && t0 + row < a.T ? ((t0 + row) * a.B + b) * op.ldp + Tile::p_unit(row, lane) * 16 : OOB;
     }
     f32x16 acc[TM][TN];
-    if constexpr (PACKED && li == 0) {
+    if constexpr (PACKED && li + LI0 == 0) {
       PackedRows pk;
       pk.rsrc = make_rsrc(op.P, op.p_bytes);
       pk.base = ((t0 >> 3) * a.B + b) * op.ldp;
@@ -271,6 +266,9 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
           v[li] = __builtin_fmaf(mtheta, s, __builtin_fmaf(beta[li], v[li], cur[u]));
         }
         __syncthreads();                              // rows s0 .. s0+15 hold potentials
+        // (the storing wavefronts pass this barrier after the rows before s0 and, at the end of a
+        // 64-step chunk, after the acknowledgement of their stores)
+        if (ROLE == 1 && s0 > 0 && s0 % 64 == 0 && tid == 0) hand_store(hand + HAND_PAIR, hand_base + (t0 + s0) / 64);
       }
       if (TS == 2 && blk + 1 < nblocks) {             // hand the potentials on to the workgroup of the next block
         hand_store(hand + HAND_V + (li * 2 + (blk & 1)) * 128 + tid, __float_as_uint(v[li]));
@@ -307,9 +305,11 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
             else __builtin_amdgcn_raw_buffer_store_b128(x, rS, so, 0, 0);
           }
         }
+        if (ROLE == 1 && (s0 + U) % 64 == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // a chunk's spikes are in the L2
       }
     }
     __syncthreads();
+    if (ROLE == 1 && tid == 0) hand_store(hand + HAND_PAIR, hand_base + (t0 + BM) / 64);
     if (TS == 2 && blk + 1 < nblocks && tid == 0) hand_store(hand + li, hand_base + blk + 1);
 
     // 5. readout currents of the block: J^T (32 classes x 128 steps) = W_out^T S^T, a wavefront
@@ -484,6 +484,47 @@ __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerFo
         st_b128(rdJ, t0 + r < a.T && cc + 3 < a.ldj ? (((t0 + r) * a.B + b) * a.ldj + cc) * 4 : OOB, 0, x);
       }
     }
+  }
+}
+
+// LS = 2 (a pair of 128-neuron layers, NL = 2): the two layers of a sample run on two workgroups.
+// The first takes the lower layer through the sample's blocks of 128 steps and, whenever the
+// wavefronts that store V and S have another 64 steps acknowledged (the spikes are then in the L2
+// the two workgroups share: ids 8 x parts apart run on the same XCD), raises a count in memory; the
+// second takes the upper layer (and the readout) through blocks of 64 steps and waits for the count
+// before each block's product, which reads those spikes.  The upper layer's product, scan and
+// stores thereby run while the lower layer is still being scanned.  Only the second workgroup
+// waits, and the first has the lower id, so it is never dispatched after the one waiting for it.
+template <int TN, int NS = 4, int READOUT = 0, int NL = 1, bool PACKED = false, int TS = 1, int LS = 1>
+__global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerForwardArgs a) {
+  static_assert(!READOUT || TN == 2, "the readout variants hold the whole layer");
+  static_assert(NL == 1 || (NL == 2 && TN == 2), "a chain of layers: whole layers of 128 neurons");
+  static_assert(TS == 1 || (TS == 2 && TN == 2), "two workgroups per sample: whole layers of 128 neurons");
+  static_assert(LS == 1 || (LS == 2 && NL == 2 && TS == 1), "a pair of layers on two workgroups");
+  constexpr int TM = TS == 2 ? 1 : 2;                 // blocks of 64 steps when two workgroups share a sample's blocks
+  typedef SpikeTile<2, 2, TM, TN, NS> Tile;
+  constexpr int BN = Tile::BN, CP = BN * 4 + 16, TILE = Tile::BM * CP;
+  constexpr int STAGES = Tile::lds_bytes(false) > Tile::lds_bytes(PACKED) ? Tile::lds_bytes(false) : Tile::lds_bytes(PACKED);
+  constexpr int LDS_BYTES = STAGES > TILE ? STAGES : TILE;                 // the stages share the tile's space
+  static_assert(LDS_BYTES <= 80 * 1024, "two workgroups per compute unit");
+  __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+  __shared__ float x_e[2][8][32], x_best[8][32];
+  __shared__ int x_tb[8][32];
+
+  // Workgroup ids are dealt round-robin to the 8 XCDs: the parts of a sample take ids 8 apart.
+  // The two workgroups of a sample part (TS = 2 or LS = 2) take ids 8 x parts apart, the one that
+  // never waits for the other first.
+  constexpr int WGS = TS * LS;
+  const int parts = a.ld / BN;
+  const int part = (blockIdx.x >> 3) % parts;
+  const int half = WGS == 1 ? 0 : ((blockIdx.x >> 3) / parts) % WGS;
+  const int b = (blockIdx.x >> 3) / (parts * WGS) * 8 + (blockIdx.x & 7);
+  if (b >= a.B) return;
+  if constexpr (LS == 2) {
+    if (half == 0) lif_layer_forward_body<TN, NS, 0, 1, PACKED, 1, 2, 0, 1>(a, lds, x_e, x_best, x_tb, b, part, parts, 0);
+    else lif_layer_forward_body<TN, NS, READOUT, 1, false, 1, 1, 1, 2>(a, lds, x_e, x_best, x_tb, b, part, parts, 0);
+  } else {
+    lif_layer_forward_body<TN, NS, READOUT, NL, PACKED, TS, TM, 0, 0>(a, lds, x_e, x_best, x_tb, b, part, parts, half);
   }
 }
 

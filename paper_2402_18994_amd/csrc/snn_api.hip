@@ -978,7 +978,11 @@ int launch_layer_forward(snn_ctx *c, int l, int nl, int with_readout, const int3
   // request: 29.3 us against 28.8 at 700-128-128-20, T = 128, B = 256): from two blocks on, and while a
   // block count fits the flags' 10 bits.
   const bool split = c->opt[SNN_OPT_LAYER_TIME_SPLIT] && bn == 128 && c->T > 64 && c->T <= 64 * 1000;
-  if (split) {
+  // A pair of layers on two workgroups per sample (SNN_OPT_LAYER_PAIR = 2, on request: 32.9 us against
+  // 27.7 at 700-128-128-20, T = 128, B = 256): the upper layer's workgroup follows the lower layer's,
+  // 64 steps at a time.
+  const bool lsplit = nl == 2 && c->opt[SNN_OPT_LAYER_PAIR] == 2 && !split && c->T <= 64 * 1000;
+  if (split || lsplit) {
     if (++c->fwd_epoch >= (1 << 21)) {                // long before the flags' counter wraps: start over
       HIPCHK(c, fill_zero(c->stream, c->hand, rup(c->B, 8) * c->hand_parts * SNN_HAND_BYTES));
       c->fwd_epoch = 1;
@@ -987,10 +991,11 @@ int launch_layer_forward(snn_ctx *c, int l, int nl, int with_readout, const int3
     a.epoch = c->fwd_epoch;
   }
   Bracket br(c, SNN_K_LIF_FORWARD, l + 1);
-  const dim3 grid((unsigned)(rup(c->B, 8) * (y.ld / bn) * (split ? 2 : 1)));
+  const dim3 grid((unsigned)(rup(c->B, 8) * (y.ld / bn) * (split || lsplit ? 2 : 1)));
 #define SNN_LFWD3(RO, PK, TS_)                                                                                   \
   do {                                                                                                           \
-    if (nl == 2) hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 2, PK, TS_>), grid, dim3(256), 0, c->stream, a); \
+    if (lsplit) hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 2, PK, 1, 2>), grid, dim3(256), 0, c->stream, a); \
+    else if (nl == 2) hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 2, PK, TS_>), grid, dim3(256), 0, c->stream, a); \
     else hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 1, PK, TS_>), grid, dim3(256), 0, c->stream, a); \
   } while (0)
 #define SNN_LFWD2(RO, PK) do { if (split) SNN_LFWD3(RO, PK, 2); else SNN_LFWD3(RO, PK, 1); } while (0)
@@ -1614,8 +1619,8 @@ int32_t snn_set_option(snn_ctx *c, int32_t option, int32_t value) {
   bool ok;
   switch (option) {
     case SNN_OPT_LAYER_FORWARD: ok = value >= 0 && value <= 4; break;
-    case SNN_OPT_LAYER_REVERSE: ok = value >= 0 && value <= 2; break;
-    case SNN_OPT_LAYER_PAIR:
+    case SNN_OPT_LAYER_REVERSE:
+    case SNN_OPT_LAYER_PAIR: ok = value >= 0 && value <= 2; break;
     case SNN_OPT_LAYER_TIME_SPLIT:
     case SNN_OPT_TOP_SCANS:
     case SNN_OPT_DEFER_REDUCE:

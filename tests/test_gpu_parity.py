@@ -223,6 +223,49 @@ def test_layer_forward_two_workgroups_per_sample(T, sizes, loss, packed):
             assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("T,sizes,loss,packed", [(37, (64, 128, 128, 10), "max", False), (64, (90, 128, 128, 10), "max", False),
+                                                  (65, (90, 128, 128, 10), "integral", False), (150, (203, 128, 128, 20), "max", False),
+                                                  (260, (90, 128, 128, 10), "integral", True), (128, (700, 128, 128, 20), "max", True),
+                                                  (200, (50, 128, 128, 128, 10), "max", False)],
+                         ids=["one-short-block", "one-chunk", "one-chunk-and-a-step", "three-chunks-ragged", "five-chunks-integral-packed",
+                              "headline-packed", "three-layers-pair-below"])
+def test_layer_pair_on_two_workgroups(T, sizes, loss, packed):
+    """Two consecutive 128-neuron layers in one launch with a workgroup per layer and sample
+    (SNN_OPT_LAYER_PAIR = 2): the upper layer's workgroup follows the lower layer's through
+    memory, 64 steps at a time.  One to five chunks with ragged tails, both losses, plain and
+    packed input, a pair below a third spiking layer (no readout in the pair's launch); three
+    forward passes in a row on one context (the flag counts launches), the second one packed."""
+    L = len(sizes) - 1
+    wl = workloads.Workload(name="layer-pair-split", index=20, T=T, B=6, sizes=sizes, recurrent=(False,) * (L - 1),
+                            beta=(0.9, 0.93, 0.95, 0.9)[:L], theta=1.0, surrogate="superspike", slope=10.0, precision="bf16",
+                            rate_lo=0.03, rate_hi=0.12, loss=loss)
+    options = {"layer_min_batch": 1, "layer_pair": 2}
+    rep = full_step_parity(wl, w_gain=2.0, options=options)
+    assert rep["spike_rate"][0] > 0.005
+    inp = workloads.generate(wl, w_gain=2.0)
+    snn = make(wl, inp, options)
+    xp = np.packbits(inp.X, axis=0)
+    outs = []
+    for k in range(3):
+        if packed and k == 1:
+            snn.forward_packed(xp, inp.labels)
+        else:
+            snn.forward(inp.X, inp.labels)
+        outs.append([snn.get_tensor("spikes", 2), snn.get_tensor("membrane", 2), snn.get_tensor("spikes", 1),
+                     snn.get_tensor("loss_per_sample")])
+    snn.destroy()
+    for o in outs[1:]:
+        for a, b in zip(o, outs[0]):
+            assert np.array_equal(a, b)
+    # the same bits as the pair on one workgroup per sample
+    snn = make(wl, inp, {"layer_min_batch": 1, "layer_pair": 1})
+    snn.forward(inp.X, inp.labels)
+    ref = [snn.get_tensor("spikes", 2), snn.get_tensor("membrane", 2), snn.get_tensor("spikes", 1)]
+    snn.destroy()
+    for a, b in zip(outs[0][:3], ref):
+        assert np.array_equal(a, b)
+
+
 def test_layer_forward_in_one_launch_same_as_separate_launches():
     """The same forward pass with and without the one-launch layers: potentials and readout
     agree to rounding, spikes are identical away from the threshold."""
@@ -714,7 +757,7 @@ def test_error_paths():
     assert snn.get_option("layer_forward") == 4 and snn.get_option("stream_min_mb") == 128
     assert snn.lib.snn_set_option(snn.ctx, 99, 0) == 2
     assert snn.lib.snn_set_option(snn.ctx, -1, 0) == 2
-    for name, bad_value in (("layer_forward", 5), ("layer_pair", 2), ("layer_neurons", 96), ("tile_rows", 48),
+    for name, bad_value in (("layer_forward", 5), ("layer_pair", 3), ("layer_time_split", 2), ("layer_neurons", 96), ("tile_rows", 48),
                             ("layer_max_neurons", 2048), ("stream_min_mb", -1), ("layer_min_batch", -3), ("layer_reverse", 3)):
         before = snn.get_option(name)
         with pytest.raises(SnnError) as e:
