@@ -9,8 +9,9 @@ Prints ONE JSON line on stdout; diagnostics go to stderr.
 
 Order of the run: warm-up; the timed region (K steps, nothing bracketed: `value`); then, outside
 it, K more steps with the dominant kernel bracketed by HIP events on the library's stream
-(`roofline`), a few steps per kernel class and layer (`kernels`), the same shape with fp32
-products (`fp32_products`), and the oracle on the host cores (`cpu_baseline`).
+(`roofline`), a few steps per kernel class and layer (`kernels`), forward + backward without the
+optimiser step (`forward_backward_only`), the same shape with fp32 products (`fp32_products`), and
+the oracle on the host cores (`cpu_baseline`).
 """
 import argparse
 import json
@@ -341,6 +342,32 @@ def main():
             kernels.append(e)
     snn.profile_select("none", 0)
 
+    # Forward + backward alone (the metric as BASELINE words it, without the optimiser step): the
+    # backward pass then adds the weight gradients' partial sums itself instead of leaving them to
+    # snn_sgd_step, so the gradients are complete when it returns.
+    fwd_bwd = None
+    if not args.no_extras:
+        snn.set_option("defer_reduce", 0)
+        nfb = max(20, args.steps // 2)
+
+        def fb():
+            if args.packed:
+                snn.forward_packed(xp, y, want_loss=False)
+            else:
+                snn.forward(x, y, want_loss=False)
+            snn.backward()
+        for _ in range(5):
+            fb()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(nfb):
+            fb()
+        torch.cuda.synchronize()
+        dfb = time.perf_counter() - t0
+        fwd_bwd = {"value": wl.B * nfb / dfb, "unit": "samples/s", "ms_per_step": dfb / nfb * 1e3, "steps": nfb,
+                   "what": "snn_forward + snn_backward, gradients reduced, no snn_sgd_step"}
+        snn.set_option("defer_reduce", options.get("defer_reduce", 1))
+
     loss = snn.forward(x, y)
     spike_rate = [float(snn.get_tensor("spikes", l).mean()) for l in range(1, L)]
     snn.destroy()
@@ -370,6 +397,8 @@ def main():
         "gemm_tflops_whole_step": gemm_flops(wl) / (dt / args.steps) / 1e12,
         "kernels": kernels,
     }
+    if fwd_bwd:
+        out["forward_backward_only"] = fwd_bwd
     if args.traffic is not None:
         out["roofline"]["traffic"] = args.traffic
         out["roofline"]["traffic_source"] = "--traffic"
