@@ -13,21 +13,20 @@
 //     applied on the global side: each lane fetches the 16-byte unit that belongs at its slot;
 //   * the spikes stay bytes in LDS (half the LDS traffic of the P operand) and become
 //     bfloat16 in registers, after the fragment read, between the MFMAs;
-//   * four LDS stages of 32 contraction elements and one barrier per stage: the loads of
-//     stage t+3 are issued during stage t and have almost three stages to land (the P operand
-//     comes from HBM on first touch; two stages of 64 left a third of a microsecond of wait
-//     per tile);
-//   * fragments are read one MFMA step ahead of their use, across the stage boundary too:
-//     the barrier sits between the two steps of a stage.
+//   * three or four LDS stages of 64 or 32 contraction elements and one barrier per stage, at its
+//     start: behind it the loads of stage t + NS - 1 are issued into the buffer stage t - 1 has
+//     left, so a load has NS - 2 stages to land (the P operand comes from HBM on first touch);
+//   * the last MFMA step of a stage is carried over the next stage's barrier (its operands are in
+//     registers) and covers the arrival of that stage's first fragments.
 //
 // Contraction order inside a stage.  A lane holds 8 consecutive k per MFMA.  Reading a lane's
-// P bytes 16 at a time (two steps' worth) fixes which k a step covers: step s of lane half
-// h = lane/32 covers k = 16h + 8s .. +7, and the Q fragment of that step is read from the
-// matching 16-byte chunk 2h + s of the row.
+// P bytes 16 at a time (two steps' worth) fixes which k a step covers: with SPS steps per stage,
+// step s of lane half h = lane/32 covers k = 8 SPS h + 8s .. +7, and the Q fragment of that step is
+// read from the matching 16-byte chunk SPS h + s of the row.
 //
 // Tails.  Rows of P beyond the product read as zero (lane offset beyond the buffer).  Along
 // k nothing is masked on the P side: Q is zero-padded to a multiple of 64 along k, and
-// whatever bytes P yields there are reduced to 0/1 before they meet those zeros.
+// whatever P yields there (bytes of the next row, 0 or 1 like all others) meets those zeros.
 #pragma once
 #include "gemm.hpp"
 #include <type_traits>
@@ -82,20 +81,33 @@ struct PackedRows {
 
 // Geometry and main loop of one tile, shared by the kernels built on this pipeline.  `run`
 // expects the per-lane global offsets of the wavefront's load instructions (pv: P, row-major
-// bytes; qv: Q, bfloat16), takes the stages through `lds` (NS * ST bytes) and leaves the
+// bytes; qv: Q, bfloat16), takes the stages through `lds` (lds_bytes(pk) bytes) and leaves the
 // products in acc; on return every load has landed and every wavefront is past its last
 // fragment read, so the caller may reuse the LDS.
-template <int WM, int WN, int TM, int TN, int NS>
+//
+// KS: contraction elements per stage, 32 or 64.  What a stage costs a compute unit is the number of
+// cache lines its loads touch, not their bytes (a line per clock through the L1, and every line is
+// a miss): a stage of 64 brings 64-byte pieces of the spike rows and whole 128-byte lines of the
+// weight rows where a stage of 32 brings 32- and 64-byte pieces of the same lines twice.  Loads
+// alone, on this pipeline (128 x 128 tile, K = 700, one workgroup per compute unit): 660 cycles per
+// 32 contraction elements with stages of 32, 486 with stages of 64.
+template <int WM, int WN, int TM, int TN, int NS, int KS = 64>
 struct SpikeTile {
   static_assert(WM * WN == 4, "four wavefronts per workgroup");
+  static_assert(KS == 32 || KS == 64, "stages of 32 or 64 contraction elements");
   static constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-  // (a tile of 64 rows still gives P a whole KiB per wavefront and stage: the rows beyond the tile
+  static constexpr int KSTAGE = KS;
+  static constexpr int SPS = KS / 16;                 // MFMA steps per stage
+  static constexpr int PU = KS / 16, QC = KS / 8;     // 16-byte units per row of P, chunks per row of Q, in a stage
+  static constexpr int UPL = KS / 32;                 // units of its row a lane reads per stage (8 bytes per step)
+  // (a tile of few rows still gives P a whole KiB per wavefront and stage: the rows beyond the tile
   // are loaded as rows outside the product, i.e. as zeros, and never read)
-  static constexpr int PT = (BM < 128 ? 128 : BM) * 32, QT = BN * 64, ST = PT + QT;   // bytes: P part, Q part, stage (32 k)
-  static constexpr int PI = PT / 4096, QI = BN / 64;                // load instructions per wavefront and stage
+  static constexpr int PROWS = BM * KS < 4096 ? 4096 / KS : BM;
+  static constexpr int PT = PROWS * KS, QT = BN * 2 * KS, ST = PT + QT;   // bytes: P part, Q part, stage
+  static constexpr int PI = PT / 4096, QI = QT / 4096;                    // load instructions per wavefront and stage
   static constexpr int NL = PI + QI;
-  static_assert(BM % 64 == 0 && BN % 64 == 0, "whole KiB per wavefront");
-  static_assert(NS >= 4, "the waits assume at least four stages");
+  static_assert(PT % 4096 == 0 && QT % 4096 == 0, "whole KiB per wavefront");
+  static_assert(NS >= 3, "a stage in use, one landing, one being asked for");
   typedef u32x4 frag_t;
   // Packed P operand: the whole block of the sample (BM / 8 packed rows of up to 1024 bytes) sits
   // in LDS for all stages, ahead of the stages, which then hold Q alone.  A row pitch of 1088 bytes
@@ -103,20 +115,26 @@ struct SpikeTile {
   static constexpr int PKP = 1088, PKB = ((BM / 8) * PKP + 1023) / 1024 * 1024;   // (the stages behind it start on a KiB)
   static constexpr int lds_bytes(bool pk) { return pk ? PKB + NS * QT : NS * ST; }
 
-  // Global side of the loads.  P instruction q of a wavefront fills rows 32 (wave + 4 q) ..
-  // +31 of the stage, 32 bytes each: lane -> row lane/2, slot lane%2, which holds the 16-byte
-  // unit slot ^ ((row / 8) % 2).  Q instruction q fills rows 16 (wave + 4 q) .. +15, 64 bytes
-  // each: lane -> row lane/4, slot lane%4, holding the 16-byte chunk slot ^ ((row / 4) % 4).
-  // With these permutations the fragment reads (32 consecutive rows, one unit or chunk)
-  // touch every bank equally.
-  static __device__ __forceinline__ int p_row(int wave, int lane, int q) { return 32 * (wave + 4 * q) + (lane >> 1); }
-  static __device__ __forceinline__ int p_unit(int row, int lane) { return (lane & 1) ^ ((row >> 3) & 1); }
-  static __device__ __forceinline__ int q_row(int wave, int lane, int q) { return 16 * (wave + 4 * q) + (lane >> 2); }
-  static __device__ __forceinline__ int q_chunk(int row, int lane) { return (lane & 3) ^ ((row >> 2) & 3); }
+  // Where a row's 16-byte pieces sit inside the row in LDS: piece c of row r at slot c ^ swz(r), so
+  // that the fragment reads (32 consecutive rows, the same piece) touch every bank equally: the LDS
+  // takes a 16-byte read 16 lanes at a time over its 64 banks, so among 16 consecutive rows those
+  // that start on the same bank (every 256 / row bytes-th) must differ in their slot.  (Rows of 128
+  // bytes with slot c ^ (r % 8) measured 48 conflict cycles per stage and wavefront.)
+  static __device__ __forceinline__ int swz_p(int r) { return KS == 32 ? (r >> 3) & 1 : (r >> 2) & 3; }
+  static __device__ __forceinline__ int swz_q(int r) { return KS == 32 ? (r >> 2) & 3 : (r >> 1) & 7; }
+  // Global side of the loads: a wavefront's 64 lanes fill 1 KiB of consecutive LDS, so the
+  // permutation is applied here: each lane fetches the piece that belongs at its slot.  P
+  // instruction q of a wavefront fills rows (1024 / KS)(wave + 4 q) .. of the stage, KS bytes each:
+  // lane -> row lane / PU, slot lane % PU.  Q instruction q fills rows (512 / KS)(wave + 4 q) ..,
+  // 2 KS bytes each: lane -> row lane / QC, slot lane % QC.
+  static __device__ __forceinline__ int p_row(int wave, int lane, int q) { return (1024 / KS) * (wave + 4 * q) + lane / PU; }
+  static __device__ __forceinline__ int p_unit(int row, int lane) { return (lane % PU) ^ swz_p(row); }
+  static __device__ __forceinline__ int q_row(int wave, int lane, int q) { return (512 / KS) * (wave + 4 * q) + lane / QC; }
+  static __device__ __forceinline__ int q_chunk(int row, int lane) { return (lane % QC) ^ swz_q(row); }
 
-  // PK: P comes from `pk` (packed along time; BM == 128 rows = time steps of one sample) instead
-  // of rp / pv: a lane's 16 bytes of row r, columns 16 h .. +15 of a stage, are bit 7 - r % 8 of
-  // the 16 packed bytes at packed row r / 8; no P loads per stage.
+  // PK: P comes from `pk` (packed along time; BM rows = time steps of one sample) instead of rp /
+  // pv: a lane's KS / 2 bytes of row r, columns (KS / 2) h .. of a stage, are bit 7 - r % 8 of the
+  // packed bytes at packed row r / 8; no P loads per stage.
   template <bool PK = false>
   static __device__ __forceinline__ void run(char *lds, const u32x4 rp, const u32x4 rq, const int (&pv)[PI],
                                              const int (&qv)[QI], const int nk, const int wave, const int lane,
@@ -124,7 +142,9 @@ struct SpikeTile {
     const int wm = wave / WN, wn = wave % WN;
     constexpr int STQ = PK ? QT : ST;               // bytes of a stage
     constexpr int QOFF = PK ? 0 : PT;               // where Q starts inside a stage
-    constexpr int NLK = PK ? QI : NL;               // load instructions per wavefront and stage
+    constexpr int PIK = PK ? 0 : PI;                // P load instructions per wavefront and stage
+    constexpr int NLK = PIK + QI;                   // load instructions per wavefront and stage
+    constexpr int M = TM * TN;                      // MFMAs per step
     char *const stages = lds + (PK ? PKB : 0);
     const unsigned lds0 = (unsigned)(uintptr_t)(lds_ptr_t)stages;
     constexpr int PKN = BM / 32;                    // 16-byte pieces of the packed block per thread
@@ -152,12 +172,11 @@ struct SpikeTile {
       r.p = rp; r.q = rq;
       if (r.kt >= nk) r.p.z = r.q.z = 0;
       r.dst = __builtin_amdgcn_readfirstlane(lds0 + buf * STQ + 1024 * wave);
-      asm volatile("" : "+s"(r.p.z), "+s"(r.q.z), "+s"(r.dst), "+s"(r.kt));   // formed here, not next to the loads
       return r;
     };
     auto issue_load = [&](const IssueRegs &r, int n) {        // load instruction n of the stage (P first)
-      if (n < NLK - QI) load_to_lds_b128(r.p, r.dst + 4096 * n, pv[n < PI ? n : 0], r.kt * 32);
-      else load_to_lds_b128(r.q, r.dst + QOFF + 4096 * (n - (NLK - QI)), qv[n - (NLK - QI)], r.kt * 64);
+      if (n < PIK) load_to_lds_b128(r.p, r.dst + 4096 * n, pv[n < PI ? n : 0], r.kt * KS);
+      else load_to_lds_b128(r.q, r.dst + QOFF + 4096 * (n - PIK), qv[n - PIK], r.kt * 2 * KS);
     };
     auto issue = [&](int kt_any, int buf) {
       const IssueRegs r = issue_prepare(kt_any, buf);
@@ -165,15 +184,18 @@ struct SpikeTile {
       for (int n = 0; n < NLK; ++n) issue_load(r, n);
     };
 
-    // LDS side of the fragment reads: lane half h reads P unit h (16 k, two MFMA steps' worth)
-    // and, for step s, Q chunk 2h + s.  Rows 32 apart share the permutation.
+    // LDS side of the fragment reads: lane half h = lane / 32 reads the UPL units UPL h .. of its P
+    // row (8 bytes per MFMA step: step s of a stage covers k = (KS / 2) h + 8 s .. + 7) and, for
+    // step s, chunk SPS h + s of its Q row.  Rows 32 apart share the permutation.
     const int h = lane >> 5;
-    int fa, fb[2];
+    int fa[UPL], fb[SPS];
     {
       const int ra = wm * TM * 32 + (lane & 31), rb = wn * TN * 32 + (lane & 31);
-      fa = PK ? (ra >> 3) * PKP + 16 * h : ra * 32 + ((h ^ ((ra >> 3) & 1)) << 4);
 #pragma unroll
-      for (int st = 0; st < 2; ++st) fb[st] = QOFF + rb * 64 + (((2 * h + st) ^ ((rb >> 2) & 3)) << 4);
+      for (int e = 0; e < UPL; ++e)
+        fa[e] = PK ? (ra >> 3) * PKP + (KS / 2) * h + 16 * e : ra * KS + (((UPL * h + e) ^ swz_p(ra)) << 4);
+#pragma unroll
+      for (int st = 0; st < SPS; ++st) fb[st] = QOFF + rb * 2 * KS + (((SPS * h + st) ^ swz_q(rb)) << 4);
     }
 
 #pragma unroll
@@ -183,12 +205,6 @@ struct SpikeTile {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // Registers of one stage: its P bytes, spread (a spike is 0x40 in its byte), the Q fragments of
-    // its MFMA step 0, and the P fragments of step 0.
-    struct StageRegs {
-      frag_t pa[TM], qb[TN];
-      bf16x8 af[TM];
-    };
     // Spike bytes to bfloat16 with two instructions per four spikes.  0x40 in the upper byte of a
     // bfloat16 is 2.0, so a spike byte becomes an operand by one shift of its dword (0/1 -> 0x00/0x40
     // in each byte; from the packed form: a rotation that brings the lane's bit to bit 6 of every
@@ -207,91 +223,107 @@ struct SpikeTile {
       d.y = __builtin_amdgcn_perm(0u, t0, 0x030C020Cu);
       d.z = __builtin_amdgcn_perm(0u, t1, 0x010C000Cu);
       d.w = __builtin_amdgcn_perm(0u, t1, 0x030C020Cu);
-      return __builtin_bit_cast(bf16x8, d);
+      u32x4 x = d;
+      asm volatile("" : "+v"(x));                             // the fragment is formed here, not next to its use
+      return __builtin_bit_cast(bf16x8, x);
     };
-    auto read_first = [&](int buf, int kt, StageRegs &r) {    // P bytes of stage kt (as stored), Q of its step 0
-      const char *st = stages + buf * STQ;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-        r.pa[i] = PK ? *(const frag_t *)(lds + fa + i * 4 * PKP + kt * 32) : *(const frag_t *)(st + fa + i * 1024);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) r.qb[j] = *(const frag_t *)(st + fb[0] + j * 2048);
+    // Operands of a stage's last MFMA step: issued behind the next stage's barrier (they are in
+    // registers), so that the matrix units have work while that stage's first fragments arrive.
+    struct Pending {
+      frag_t q[TN];
+      bf16x8 af[TM];
     };
-    // One stage in buffer u.  On entry the stage's P bytes, its step-0 Q fragments and its converted
-    // step-0 P fragments are in registers (or on their way).  The barrier sits between the two MFMA
-    // steps: past it, every wavefront has left stage kt-1 (its buffer, u+NS-1, may be overwritten:
-    // the loads of stage kt+NS-1 go there) and has seen its own loads of stage kt+1 land (so buffer
-    // u+1 is complete and its first fragments can be read under the MFMAs of step 1).
+    // One stage in buffer u.  At its barrier every wavefront has seen its own loads of the stage
+    // land (so the buffer is complete) and has left stage kt - 1, whose buffer, u + NS - 1, takes the
+    // loads of stage kt + NS - 1.
     //
     // One wavefront per SIMD: nothing but this wavefront's own independent instructions fills the
     // 32 cycles an MFMA keeps the matrix unit.  The order is therefore fixed by hand (scheduling
-    // barriers), one MFMA, then the few conversion instructions of a fragment needed later:
-    // step 1's fragments under the MFMAs of step 0, the next stage's step-0 fragments under the last
-    // MFMAs of step 1, the fragment reads and the load issue right behind the barrier under the
-    // first ones.  Left to the scheduler, the conversions of a whole stage sit in front of its first
-    // MFMA and the fragment reads of a stage at its top, each followed by its wait.
-    auto pin = [&](bf16x8 &f) {                             // the fragment is formed here, not next to its use
-      u32x4 x = __builtin_bit_cast(u32x4, f);
-      asm volatile("" : "+v"(x));
-      f = __builtin_bit_cast(bf16x8, x);
-    };
-    auto stage = [&](int u, int kt, StageRegs &cur, StageRegs &nxt) {
-      constexpr int M = TM * TN;                        // MFMAs per step
-      frag_t q1[TN];
-#pragma unroll
-      for (int j = 0; j < TN; ++j) q1[j] = *(const frag_t *)(stages + u * STQ + fb[1] + j * 2048);
-      bf16x8 a1[TM];
-      IssueRegs ir;
-      __builtin_amdgcn_sched_barrier(0);
-      static_for<M>([&](auto X) {
-        constexpr int x = decltype(X)::value, i = x / TN, j = x % TN;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cur.qb[j]), cur.af[i], acc[i][j], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (x < TM) {
-          a1[x] = convert(cur.pa[x][2], cur.pa[x][3]);
-          pin(a1[x]);
-        }
-        if constexpr (x == (TM < M - 1 ? TM : M - 1)) ir = issue_prepare(kt + NS - 1, (u + NS - 1) % NS);
-        __builtin_amdgcn_sched_barrier(0);
-      });
-      // (ties the accumulators to this point: the MFMAs of step 0 are issued before the waits)
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(acc[i][j]));
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 3) * NLK) : "memory");   // younger stages may still be in flight
+    // barriers): behind the barrier the fragment reads and the load issue, then the previous
+    // stage's last step, and from there one MFMA, then the few conversion instructions of a fragment
+    // needed a step later.  Left to the scheduler, the conversions of a whole stage sit in front of
+    // its first MFMA and the fragment reads next to their use, each followed by its wait.
+    auto stage = [&](int u, int kt, Pending &pend) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NLK) : "memory");   // younger stages may still be in flight
       lds_barrier();
-      {
-        const char *st = stages + ((u + 1) % NS) * STQ;
+      const char *st = stages + u * STQ;
+      frag_t pa[TM][UPL], q[2][TN];
+      bf16x8 af[2][TM];
+      auto read_p = [&]() {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
-          nxt.pa[i] = PK ? *(const frag_t *)(lds + fa + i * 4 * PKP + (kt + 1) * 32) : *(const frag_t *)(st + fa + i * 1024);
+#pragma unroll
+          for (int e = 0; e < UPL; ++e)
+            pa[i][e] = PK ? *(const frag_t *)(lds + fa[e] + i * 4 * PKP + kt * KS) : *(const frag_t *)(st + fa[e] + i * 32 * KS);
+      };
+      auto read_q = [&](int sp) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) q[sp & 1][j] = *(const frag_t *)(st + fb[sp] + j * 64 * KS);
+      };
+      auto conv = [&](int sp, int i) {                  // the P fragment of row tile i for step sp
+        af[sp & 1][i] = convert(pa[i][sp >> 1][2 * (sp & 1)], pa[i][sp >> 1][2 * (sp & 1) + 1]);
+      };
+      if constexpr (TM == 2 && TN == 2 && KS == 64) {
+        // 16 MFMAs: the step left over from the stage before (operands in registers), then steps 0 to
+        // 2; behind MFMA k the work of slot k, at most about seven instructions each.
+        IssueRegs ir;
+        static_for<16>([&](auto K) {
+          constexpr int k = decltype(K)::value, sp = k / 4 - 1, i = (k % 4) / 2, j = k % 2;
+          if constexpr (k < 4) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pend.q[j]), pend.af[i], acc[i][j], 0, 0, 0);
+          else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, q[sp & 1][j]), af[sp & 1][i], acc[i][j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if constexpr (k == 0) { read_p(); read_q(0); }
+          if constexpr (k == 1) { ir = issue_prepare(kt + NS - 1, (u + NS - 1) % NS); issue_load(ir, 0); }
+          if constexpr (k == 2) { issue_load(ir, 1); if (NLK > 2) issue_load(ir, 2); }
+          if constexpr (k == 3) { spread(pa[0][0]); conv(0, 0); }
+          if constexpr (k == 4) { spread(pa[1][0]); conv(0, 1); }
+          if constexpr (k == 5) { if (NLK > 3) issue_load(ir, 3); read_q(1); }
+          if constexpr (k == 6) { conv(1, 0); if (NLK > 4) issue_load(ir, 4); }
+          if constexpr (k == 7) { conv(1, 1); if (NLK > 5) issue_load(ir, 5); }
+          if constexpr (k == 8) { read_q(2); spread(pa[0][1]); }
+          if constexpr (k == 9) conv(2, 0);
+          if constexpr (k == 10) { spread(pa[1][1]); conv(2, 1); }
+          if constexpr (k == 11) read_q(3);
+          if constexpr (k == 12) conv(3, 0);
+          if constexpr (k == 13) conv(3, 1);
+          __builtin_amdgcn_sched_barrier(0);
+        });
+        static_assert(NLK <= 6, "slots for six load instructions");
+      } else {
+        read_p();
+        read_q(0);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(kt + NS - 1, (u + NS - 1) % NS);
+        __builtin_amdgcn_sched_barrier(0);
+        // the step left over from the stage before, with this stage's first conversions behind its MFMAs
+        static_for<M>([&](auto X) {
+          constexpr int x = decltype(X)::value, i = x / TN, j = x % TN;
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pend.q[j]), pend.af[i], acc[i][j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if constexpr (x < TM) {
+#pragma unroll
+            for (int e = 0; e < UPL; ++e) spread(pa[x][e]);
+            conv(0, x);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        });
+        static_for<SPS - 1>([&](auto S) {
+          constexpr int sp = decltype(S)::value;          // this step; the fragments of step sp + 1 are formed under it
+          read_q(sp + 1);
+          __builtin_amdgcn_sched_barrier(0);
+          static_for<M>([&](auto X) {
+            constexpr int x = decltype(X)::value, i = x / TN, j = x % TN;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, q[sp & 1][j]), af[sp & 1][i], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (x < TM) conv(sp + 1, x);
+            __builtin_amdgcn_sched_barrier(0);
+          });
+        });
       }
-      __builtin_amdgcn_sched_barrier(0);
-      constexpr int L0 = M - TM >= 2 ? (NLK < 2 ? NLK : 2) : NLK;   // load instructions behind the first MFMA
-      static_for<M>([&](auto X) {
-        constexpr int x = decltype(X)::value, i = x / TN, j = x % TN;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, q1[j]), a1[i], acc[i][j], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (x == 0) {
 #pragma unroll
-          for (int n = 0; n < L0; ++n) issue_load(ir, n);
-        }
-        if constexpr (x == (L0 < NLK ? 1 : 0)) {
+      for (int j = 0; j < TN; ++j) pend.q[j] = q[(SPS - 1) & 1][j];
 #pragma unroll
-          for (int n = L0; n < NLK; ++n) issue_load(ir, n);
-          const char *st = stages + ((u + 1) % NS) * STQ;
-#pragma unroll
-          for (int jj = 0; jj < TN; ++jj) nxt.qb[jj] = *(const frag_t *)(st + fb[0] + jj * 2048);
-        }
-        if constexpr (x >= M - TM) {
-          constexpr int i2 = x - (M - TM);
-          spread(nxt.pa[i2]);
-          nxt.af[i2] = convert(nxt.pa[i2][0], nxt.pa[i2][1]);
-          pin(nxt.af[i2]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      });
+      for (int i = 0; i < TM; ++i) pend.af[i] = af[(SPS - 1) & 1][i];
     };
 
 #pragma unroll
@@ -306,33 +338,27 @@ struct SpikeTile {
         *(u32x4 *)(lds + (piece >> 6) * PKP + (piece & 63) * 16) = pkx[j];
       }
     }
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NLK) : "memory");
-    lds_barrier();
-    StageRegs r0, r1;
-    read_first(0, 0, r0);
+    Pending pend;                                     // nothing is left over before the first stage: zeros
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      spread(r0.pa[i]);
-      r0.af[i] = convert(r0.pa[i][0], r0.pa[i][1]);
-    }
-    // Unrolled over the buffers (twice when their number is odd, so that the two fragment
-    // register sets alternate consistently): whole rounds in one block of straight-line code, the
-    // stages left over (fewer than a round) behind it.
-    constexpr int UN = NS % 2 ? 2 * NS : NS;
+    for (int j = 0; j < TN; ++j) pend.q[j] = frag_t{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < TM; ++i) pend.af[i] = __builtin_bit_cast(bf16x8, frag_t{0u, 0u, 0u, 0u});
+    // Unrolled over the buffers: whole rounds in one block of straight-line code, the stages left
+    // over (fewer than a round) behind it.
     int kt = 0;
-    for (; kt + UN <= nk; kt += UN) {
-      static_for<UN>([&](auto U) {
+    for (; kt + NS <= nk; kt += NS) {
+      static_for<NS>([&](auto U) {
         constexpr int u = decltype(U)::value;
-        if constexpr (u % 2 == 0) stage(u % NS, kt + u, r0, r1);
-        else stage(u % NS, kt + u, r1, r0);
+        stage(u, kt + u, pend);
       });
     }
-    static_for<UN - 1>([&](auto U) {
+    static_for<NS - 1>([&](auto U) {
       constexpr int u = decltype(U)::value;
-      if (kt + u < nk) {
-        if constexpr (u % 2 == 0) stage(u % NS, kt + u, r0, r1);
-        else stage(u % NS, kt + u, r1, r0);
-      }
+      if (kt + u < nk) stage(u, kt + u, pend);
+    });
+    static_for<M>([&](auto X) {                        // the last stage's last step
+      constexpr int x = decltype(X)::value, i = x / TN, j = x % TN;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pend.q[j]), pend.af[i], acc[i][j], 0, 0, 0);
     });
     // The loads beyond the range wrote zeros: they too are over before the buffers are reused.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -348,7 +374,7 @@ struct SpikeTile {
 
 template <int WM, int WN, int TM, int TN, int NS = 4>
 __global__ __launch_bounds__(256, 2) void spike_gemm_kernel(const GemmArgs a) {
-  typedef SpikeTile<WM, WN, TM, TN, NS> Tile;
+  typedef SpikeTile<WM, WN, TM, TN, NS, 32> Tile;     // (stages of 64 would leave this tile two buffers)
   constexpr int BM = Tile::BM, BN = Tile::BN, ST = Tile::ST, PI = Tile::PI, QI = Tile::QI;
   static_assert(NS * ST <= 81920, "two workgroups per compute unit");
   __shared__ __attribute__((aligned(16))) char lds[NS * ST];

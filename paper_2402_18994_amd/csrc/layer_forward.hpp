@@ -9,7 +9,7 @@
 // spike rows in that L2).  Per block of 128 steps:
 //   1. product: the 128 rows (t, b) of the spike tensor below times the rounded weights, on
 //      the streamed pipeline of the large current products (operands straight into LDS,
-//      four stages, see gemm_stream.hpp); the rows of the tile are the sample's time steps,
+//      three stages of 64, see gemm_stream.hpp); the rows of the tile are the sample's time steps,
 //      so W passes through the workgroup once per block and the spikes once in all;
 //   2. the 128 x BN tile of currents goes to LDS (the stages are free by then);
 //   3. scan: BN / 64 wavefronts hold one neuron per lane and walk the 128 steps on LDS: read
@@ -135,9 +135,9 @@ __device__ __forceinline__ void lif_layer_forward_body(const LayerForwardArgs &a
   constexpr bool LOSS = READOUT >= 2, INTEGRAL = READOUT == 3;
   constexpr int JP = 36;                              // floats between rows of the BM x 32 readout tile in LDS
   typedef SpikeTile<2, 2, TM, TN, NS> Tile;
-  constexpr int WN = 2, BM = Tile::BM, BN = Tile::BN, PI = Tile::PI, QI = Tile::QI;
+  constexpr int WN = 2, BM = Tile::BM, BN = Tile::BN, PI = Tile::PI, QI = Tile::QI, KS = Tile::KSTAGE;
   constexpr int SEG = BM / 8;                         // steps per segment of the readout scan (eight segments per block)
-  static_assert((BM == 128 || BM == 64) && PI == 1 && (BN == 64 || BN == 128), "128 or 64 steps x 64 or 128 neurons");
+  static_assert((BM == 128 || BM == 64) && (BN == 64 || BN == 128), "128 or 64 steps x 64 or 128 neurons");
   static_assert(ROLE == 0 || (TS == 1 && NL == 1 && BM == (ROLE == 1 ? 128 : 64)), "a pair of layers on two workgroups");
   constexpr int CP = BN * 4 + 16;                     // bytes between time rows of the current tile in LDS
   constexpr int HAND_PAIR = 3;                        // flag of a pair of layers on two workgroups: chunks of 64 steps stored
@@ -157,16 +157,6 @@ __device__ __forceinline__ void lif_layer_forward_body(const LayerForwardArgs &a
   const float theta = a.theta;
   const float big = 0x1p100f, mtheta_big = -theta * 0x1p100f, mtheta = -theta;
 
-  // Readout variant: W_out^T as the first MFMA operand, lane -> class (lane & 31), neurons
-  // 16 kk + 8 h .. +7; resident.
-  bf16x8 wr[READOUT ? 8 : 1];
-  if (READOUT) {
-    const rsrc_t rQ = make_rsrc(a.Qr, a.qr_bytes);
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk)
-      wr[kk] = __builtin_bit_cast(bf16x8, ld_b128(rQ, ((lane & 31) * a.ldqr + 16 * kk + 8 * h) * 2, 0));
-  }
-
   // Readout state of class tid % 32 (variants with the loss)
   const float beta_r = LOSS && (tid & 31) < a.ldj ? a.beta_r[tid & 31] : 0.f;
   float bseg = beta_r;                                // beta^SEG
@@ -182,7 +172,7 @@ __device__ __forceinline__ void lif_layer_forward_body(const LayerForwardArgs &a
     constexpr int li = decltype(LI)::value;
     constexpr bool last = li == NL - 1;
     const LayerForwardOp &op = a.op[li + LI0];
-    const int nk = (op.kc + 31) >> 5;
+    const int nk = (op.kc + KS - 1) / KS;
     const u32x4 rp = raw_rsrc(op.P, op.p_bytes), rq = raw_rsrc(op.Q, op.q_bytes);
     const rsrc_t rV = make_rsrc(op.V, (unsigned)a.T * a.B * a.ld * 4u), rS = make_rsrc(op.S, (unsigned)a.T * a.B * a.ld);
     int qv[QI];
@@ -197,9 +187,10 @@ __device__ __forceinline__ void lif_layer_forward_body(const LayerForwardArgs &a
       __syncthreads();
     }
     int pv[PI];
-    {
-      const int row = Tile::p_row(wave, lane, 0);
-      pv[0] = row < BM && t0 + row < a.T ? ((t0 + row) * a.B + b) * op.ldp + Tile::p_unit(row, lane) * 16 : OOB;
+#pragma unroll
+    for (int q = 0; q < PI; ++q) {
+      const int row = Tile::p_row(wave, lane, q);
+      pv[q] = row < BM && t0 + row < a.T ? ((t0 + row) * a.B + b) * op.ldp + Tile::p_unit(row, lane) * 16 : OOB;
     }
     f32x16 acc[TM][TN];
     if constexpr (PACKED && li + LI0 == 0) {
@@ -232,6 +223,17 @@ __device__ __forceinline__ void lif_layer_forward_body(const LayerForwardArgs &a
         }
     if (TS == 2 && blk > 0 && tid == 0) hand_wait(hand + li, hand_base + blk, a.err);   // the block before has been scanned
     __syncthreads();
+
+    // Readout variant: W_out^T as the first MFMA operand, lane -> class (lane & 31), neurons
+    // 16 kk + 8 h .. +7.  Asked for here, once per block, so that the fragments arrive under the scan
+    // and do not occupy 32 registers during the products.
+    bf16x8 wr[READOUT && last ? 8 : 1];
+    if constexpr (READOUT && last) {
+      const rsrc_t rQ = make_rsrc(a.Qr, a.qr_bytes);
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk)
+        wr[kk] = __builtin_bit_cast(bf16x8, ld_b128(rQ, ((lane & 31) * a.ldqr + 16 * kk + 8 * h) * 2, 0));
+    }
 
     // 3. scan and store.  The wavefronts that hold no neuron (256 - BN threads) store what the scan
     // has finished, 16 steps behind it: after every 16 steps a barrier, behind which they read the
@@ -495,7 +497,7 @@ __device__ __forceinline__ void lif_layer_forward_body(const LayerForwardArgs &a
 // before each block's product, which reads those spikes.  The upper layer's product, scan and
 // stores thereby run while the lower layer is still being scanned.  Only the second workgroup
 // waits, and the first has the lower id, so it is never dispatched after the one waiting for it.
-template <int TN, int NS = 4, int READOUT = 0, int NL = 1, bool PACKED = false, int TS = 1, int LS = 1>
+template <int TN, int NS = 3, int READOUT = 0, int NL = 1, bool PACKED = false, int TS = 1, int LS = 1>
 __global__ __launch_bounds__(256, 2) void lif_layer_forward_kernel(const LayerForwardArgs a) {
   static_assert(!READOUT || TN == 2, "the readout variants hold the whole layer");
   static_assert(NL == 1 || (NL == 2 && TN == 2), "a chain of layers: whole layers of 128 neurons");

@@ -39,7 +39,8 @@ namespace snn {
 // Streamed product for the reverse layer: acc^T (TN x 32 neurons by 32 steps per wavefront) =
 // Q (rounded weights, rows = neurons n, bfloat16 [n][k]) times P^T (hi/lo words [row = step][k]),
 // k = the columns of the layer above, for a tile of 64 steps x 64 TN neurons on 2 x 2 wavefronts.
-// The pipeline is SpikeTile's (four stages of 32 k, one barrier per stage, loads issued three
+// The pipeline is an earlier form of SpikeTile's (four stages of 32 k, one barrier per stage between
+// a stage's two MFMA steps, loads issued three
 // stages ahead as asm so that the compiler does not wait for them); what differs is the P
 // operand: 128 bytes per row and stage, in eight 16-byte units; unit u of row r sits at slot
 // u ^ (r % 8) (the permutation is applied on the global side of the direct-to-LDS loads) so

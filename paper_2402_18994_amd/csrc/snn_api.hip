@@ -994,9 +994,9 @@ int launch_layer_forward(snn_ctx *c, int l, int nl, int with_readout, const int3
   const dim3 grid((unsigned)(rup(c->B, 8) * (y.ld / bn) * (split || lsplit ? 2 : 1)));
 #define SNN_LFWD3(RO, PK, TS_)                                                                                   \
   do {                                                                                                           \
-    if (lsplit) hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 2, PK, 1, 2>), grid, dim3(256), 0, c->stream, a); \
-    else if (nl == 2) hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 2, PK, TS_>), grid, dim3(256), 0, c->stream, a); \
-    else hipLaunchKernelGGL((lif_layer_forward_kernel<2, 4, RO, 1, PK, TS_>), grid, dim3(256), 0, c->stream, a); \
+    if (lsplit) hipLaunchKernelGGL((lif_layer_forward_kernel<2, 3, RO, 2, PK, 1, 2>), grid, dim3(256), 0, c->stream, a); \
+    else if (nl == 2) hipLaunchKernelGGL((lif_layer_forward_kernel<2, 3, RO, 2, PK, TS_>), grid, dim3(256), 0, c->stream, a); \
+    else hipLaunchKernelGGL((lif_layer_forward_kernel<2, 3, RO, 1, PK, TS_>), grid, dim3(256), 0, c->stream, a); \
   } while (0)
 #define SNN_LFWD2(RO, PK) do { if (split) SNN_LFWD3(RO, PK, 2); else SNN_LFWD3(RO, PK, 1); } while (0)
 #define SNN_LFWD(RO) do { if (packed) SNN_LFWD2(RO, true); else SNN_LFWD2(RO, false); } while (0)
@@ -1015,8 +1015,8 @@ int launch_layer_forward(snn_ctx *c, int l, int nl, int with_readout, const int3
     }
     ro.i_ready = true;
   } else if (bn == 64) {
-    if (packed) hipLaunchKernelGGL((lif_layer_forward_kernel<1, 4, 0, 1, true>), grid, dim3(256), 0, c->stream, a);
-    else hipLaunchKernelGGL((lif_layer_forward_kernel<1, 4>), grid, dim3(256), 0, c->stream, a);
+    if (packed) hipLaunchKernelGGL((lif_layer_forward_kernel<1, 3, 0, 1, true>), grid, dim3(256), 0, c->stream, a);
+    else hipLaunchKernelGGL((lif_layer_forward_kernel<1, 3>), grid, dim3(256), 0, c->stream, a);
   } else SNN_LFWD(0);
 #undef SNN_LFWD
 #undef SNN_LFWD2
