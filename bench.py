@@ -32,8 +32,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 # all of them).  Not measured by this run: the figure is the one in the named summary, which the
 # same command produced under the profiler; --traffic replaces it.
 PROFILED_TRAFFIC = {           # (workload, kernel, input packed along time)
-    ("shd_ff128", "lif_forward", False): ((16129.8 * 2.0 + 50256.0) * 1024.0, "profiles/train_step_shd_ff128.txt"),
-    ("shd_ff128", "lif_forward", True): ((5373.2 * 2.0 + 51792.0) * 1024.0, "profiles/train_step_shd_ff128.txt"),
+    ("shd_ff128", "lif_forward", False): ((15841.0 * 2.0 + 50256.0) * 1024.0, "profiles/train_step_shd_ff128.txt"),
+    ("shd_ff128", "lif_forward", True): ((4554.7 * 2.0 + 50256.0) * 1024.0, "profiles/train_step_shd_ff128.txt"),
 }
 
 
