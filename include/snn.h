@@ -223,7 +223,11 @@ typedef enum {
  *                     that take its blocks of 64 steps in turn (the product of the next block runs
  *                     while this one is scanned; the state is handed over through memory).  Measured
  *                     no faster at 700-128-128-20, T = 128, B = 256 (each workgroup still loads all of
- *                     W per block, and the loads are what bounds the product): on request only */
+ *                     W per block, and the loads are what bounds the product): on request only
+ *   WGRAD_TR          1 (default): weight-gradient products wider than 64 columns on rounded weights use
+ *                     the kernel that brings both operand tiles into LDS as they lie in memory and
+ *                     reads the MFMA fragments through the transposing LDS reads; 0: the general
+ *                     product kernel, which transposes in registers */
 typedef enum {
   SNN_OPT_LAYER_FORWARD = 0,
   SNN_OPT_LAYER_PAIR = 1,
@@ -237,7 +241,8 @@ typedef enum {
   SNN_OPT_STREAM_GEMM = 9,
   SNN_OPT_TILE_ROWS = 10,
   SNN_OPT_LAYER_TIME_SPLIT = 11,
-  SNN_OPT_COUNT = 12
+  SNN_OPT_WGRAD_TR = 12,
+  SNN_OPT_COUNT = 13
 } snn_option;
 
 /* Validate `cfg` and report the device bytes snn_init needs (a multiple of 256).

@@ -15,6 +15,7 @@
 
 #include "gemm.hpp"
 #include "gemm_stream.hpp"
+#include "wgrad_tr.hpp"
 #include "layer_forward.hpp"
 #include "scan.hpp"
 #include "layer_reverse.hpp"
@@ -103,7 +104,7 @@ struct snn_ctx {
   const int32_t *labels_dev = nullptr;
   ReduceJobs pending;             // partial sums of the last backward pass that have not been added yet
   bool reduce_pending = false;
-  int opt[SNN_OPT_COUNT] = {4, 1, 1, 1, 1, 0, 128, 1024, 128, 1, 0, 0};   // snn_option values, in the enum's order
+  int opt[SNN_OPT_COUNT] = {4, 1, 1, 1, 1, 0, 128, 1024, 128, 1, 0, 0, 1};   // snn_option values, in the enum's order
   uint32_t *hand = nullptr;       // hand-over space of the forward launches that give a sample to two workgroups
   int hand_parts = 1;             // hand-over regions per sample (one per column block of a layer)
   int fwd_epoch = 0;              // number of such launches so far (their flags count from epoch * 1024)
@@ -201,13 +202,20 @@ hipError_t static_scratch(void **out) {
 //   * every split writes and the reduction re-reads all partial sums: with large matrices
 //     (2048 wide: 56 MB per split) more splits cost more than they gain (64 splits: 10.2 ms
 //     against 3.3 ms with 8), and 16 splits never beat 8 at 1024 wide.
-int choose_splits(long long M, int tiles, long long weights, long long row_bytes, long long *per_split) {
+//   * the kernel on transposing LDS reads (wgrad_tr.hpp) multiplies as fast with one workgroup per
+//     compute unit as with two (its MFMAs are fed by the wavefront's own instruction stream), so for
+//     it (`one_per_cu`) half as many splits cover the chip at the same product time and half the
+//     partial sums (700-128-128-20, T*B = 32768: 32 splits 19.1 us + 4.4 us for the update against
+//     64 splits 20.7 + 6.5);
+//   * 2..7 splits would leave whole XCDs without work (a split lives on one XCD): 8 then.
+int choose_splits(long long M, int tiles, long long weights, long long row_bytes, long long *per_split, bool one_per_cu) {
   const long long target = 512;                          // workgroups resident at once
   if (tiles < 1) tiles = 1;
   const long long max_by_len = M / 256;                  // at least four 64-row tiles per workgroup
   long long want = target / tiles;
   if (want > max_by_len) want = max_by_len;
   if (want < 1) want = 1;
+  if (want > 1 && want < 8 && max_by_len >= 8) want = 8;
   if (want >= 8) {
     want = want / 8 * 8;                                 // all at once, balanced over the XCDs
     // when that leaves more than 15 % of the chip idle: more, shorter workgroups, as long as
@@ -215,13 +223,14 @@ int choose_splits(long long M, int tiles, long long weights, long long row_bytes
     // operand bytes
     const long long more = ((target * 13 / 10 + tiles - 1) / tiles + 7) / 8 * 8;
     if (want * tiles * 100 < target * 85 && M / more >= 1024 && more * weights * 4 * 4 <= M * row_bytes) want = more;
+    const long long half = (target / 2 / tiles) / 8 * 8; // one workgroup per compute unit
+    if (one_per_cu && half >= 8 && half < want && half * tiles * 100 >= target / 2 * 85) want = half;
   }
   long long per = (long long)rup((size_t)((M + want - 1) / want), 64);
   *per_split = per;
   return (int)((M + per - 1) / per);
 }
 
-// Output tiles of a weight-gradient product; `tall`: 256-row tiles for the wide products.
 int wgrad_tiles(int rows, int cols, bool tall) {
   int bn = cols <= 32 ? 32 : (cols <= 64 ? 64 : 128);
   const int bm = tall && cols > 64 ? 256 : 128;
@@ -267,7 +276,14 @@ void carve(snn_ctx &c, Carver &cv) {
     return n;
   };
   c.wg_tall = c.precision != SNN_PREC_FP32 && count_tiles(false) >= 32;
-  const int wg_tiles = count_tiles(c.wg_tall);
+  // (the splits are laid out here, for the kernel that SNN_OPT_WGRAD_TR selects at this point)
+  bool wg_tr = c.opt[SNN_OPT_WGRAD_TR] && c.precision != SNN_PREC_FP32;
+  {
+    bool any_wide = false;
+    for (int l = 0; l < c.L; ++l) any_wide = any_wide || c.layers[l].N > 64;
+    wg_tr = wg_tr && any_wide;
+  }
+  const int wg_tiles = count_tiles(c.wg_tall && !wg_tr);
   long long wg_weights = 0, wg_row_bytes = 0;             // what the merged launch writes per split / reads per row
   for (int l = 0; l < c.L; ++l) {
     const Layer &y = c.layers[l];
@@ -289,7 +305,7 @@ void carve(snn_ctx &c, Carver &cv) {
     }
     // (layer 1: from the length of the contraction in packed order, T rounded up to whole bytes of
     // eight steps, so that the same splits serve a raster packed along time)
-    y.splits_w = choose_splits(l == 0 ? (long long)((c.T + 7) / 8 * 8) * c.B : c.M, wg_tiles, wg_weights, wg_row_bytes, &y.per_w);
+    y.splits_w = choose_splits(l == 0 ? (long long)((c.T + 7) / 8 * 8) * c.B : c.M, wg_tiles, wg_weights, wg_row_bytes, &y.per_w, wg_tr);
     if (y.splits_w > 1) y.part_w = cv.take<float>((size_t)y.splits_w * K * N);
     if (y.recurrent) {
       y.Rm = cv.take<float>(N * N);
@@ -300,7 +316,7 @@ void carve(snn_ctx &c, Carver &cv) {
       y.QRb = cv.take<uint16_t>((size_t)np * y.qr_plane);
       y.g[0] = cv.take<float>((size_t)c.B * y.ld);
       y.g[1] = cv.take<float>((size_t)c.B * y.ld);
-      y.splits_r = choose_splits(c.M, wg_tiles, wg_weights, wg_row_bytes, &y.per_r);
+      y.splits_r = choose_splits(c.M, wg_tiles, wg_weights, wg_row_bytes, &y.per_r, wg_tr);
       if (y.splits_r > 1) y.part_r = cv.take<float>((size_t)y.splits_r * N * N);
     }
     y.beta_v = cv.take<float>(y.ld);
@@ -513,6 +529,11 @@ struct WgradJobs {
   GemmJobs narrow, mid, wide;        // cols <= 32, <= 64, wider
 };
 
+// The wide products on rounded weights go through the kernel built on transposing LDS reads
+// (SNN_OPT_WGRAD_TR, 128 x 128 tiles), else through the general one (256 x 128 tiles when there are many).
+static bool wgrad_tr(const snn_ctx *c) { return c->opt[SNN_OPT_WGRAD_TR] && c->precision != SNN_PREC_FP32; }
+static bool wgrad_tall(const snn_ctx *c) { return c->wg_tall && !wgrad_tr(c); }
+
 int flush_tn(snn_ctx *c, WgradJobs &w, int which) {
   hipError_t e = hipSuccess;
   const bool f32 = c->precision == SNN_PREC_FP32;
@@ -526,6 +547,7 @@ int flush_tn(snn_ctx *c, WgradJobs &w, int which) {
     memset(&w.mid, 0, sizeof w.mid);
   } else if (which == 2 && w.wide.njobs) {
     e = f32 ? gemm_jobs_launch<P_T_U8, Q_T_F32S, EPI_STORE, 2, 2, 2, 2, 3, 1>(w.wide, c->stream)
+            : wgrad_tr(c) ? wgrad_tr_jobs_launch(w.wide, c->stream)
             : c->wg_tall ? gemm_jobs_launch<P_T_U8, Q_T_HL, EPI_STORE, 2, 2, 4, 2, 2, 1>(w.wide, c->stream)
                            : gemm_jobs_launch<P_T_U8, Q_T_HL, EPI_STORE, 2, 2, 2, 2, 2, 1>(w.wide, c->stream);
     memset(&w.wide, 0, sizeof w.wide);
@@ -556,7 +578,7 @@ int queue_tn(snn_ctx *c, WgradJobs &w, SpikeSrc s, int rows, const void *G, int 
   }
   if (which == 0) gemm_jobs_add<4, 1, 1, 1>(list, a, splits);
   else if (which == 1) gemm_jobs_add<2, 2, 2, 1>(list, a, splits);
-  else if (c->wg_tall) gemm_jobs_add<2, 2, 4, 2>(list, a, splits);
+  else if (wgrad_tall(c)) gemm_jobs_add<2, 2, 4, 2>(list, a, splits);
   else gemm_jobs_add<2, 2, 2, 2>(list, a, splits);
   return SNN_OK;
 }
@@ -625,7 +647,7 @@ int launch_weight_grads(snn_ctx *c, WgradJobs &w, const ReduceJobs &jobs, bool w
   for (GemmJobs *from : {&w.narrow, &w.mid})
     while (from->njobs && w.wide.njobs && w.wide.njobs < SNN_GEMM_MAX_JOBS) {
       const GemmArgs a = from->job[--from->njobs];
-      if (c->wg_tall) gemm_jobs_add<2, 2, 4, 2>(w.wide, a, a.splits);
+      if (wgrad_tall(c)) gemm_jobs_add<2, 2, 4, 2>(w.wide, a, a.splits);
       else gemm_jobs_add<2, 2, 2, 2>(w.wide, a, a.splits);
     }
   for (int which = 2; which >= 0; --which)
@@ -1576,7 +1598,7 @@ int32_t snn_weight_grad_static(const uint8_t *S_dev, const float *G_dev, float *
   // reads it, so nothing has to be cleared between calls.
   const long long weights = (long long)K * N;
   long long per = 0;
-  int splits = choose_splits(M, wgrad_tiles(K, N, false), weights, K + 4ll * N, &per);
+  int splits = choose_splits(M, wgrad_tiles(K, N, false), weights, K + 4ll * N, &per, false);
   const long long fit = (long long)SNN_STATIC_SCRATCH_BYTES / (weights * 4);
   if (splits > fit) {
     per = (long long)rup((size_t)((M + fit - 1) / fit), 64);
@@ -1623,6 +1645,7 @@ int32_t snn_set_option(snn_ctx *c, int32_t option, int32_t value) {
     case SNN_OPT_LAYER_PAIR: ok = value >= 0 && value <= 2; break;
     case SNN_OPT_LAYER_TIME_SPLIT:
     case SNN_OPT_TOP_SCANS:
+    case SNN_OPT_WGRAD_TR:
     case SNN_OPT_DEFER_REDUCE:
     case SNN_OPT_STREAM_GEMM: ok = value == 0 || value == 1; break;
     case SNN_OPT_LAYER_MIN_BATCH: ok = value >= 0; break;

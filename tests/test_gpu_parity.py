@@ -266,6 +266,42 @@ def test_layer_pair_on_two_workgroups(T, sizes, loss, packed):
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("T,B,sizes,rec,packed", [(50, 6, (203, 130, 70, 10), (False, False), False),
+                                                   (33, 5, (90, 128, 128, 20), (False, False), False),
+                                                   (70, 8, (700, 128, 128, 20), (False, False), True),
+                                                   (40, 7, (64, 300, 257, 129, 10), (False, False, False), False),
+                                                   (45, 4, (50, 140, 10), (True,), False)],
+                         ids=["ragged", "one-short-stage-tail", "packed-layer-1", "several-tiles", "recurrent"])
+def test_weight_gradients_through_transposing_reads(T, B, sizes, rec, packed):
+    """The weight-gradient products wider than 64 columns on the kernel that reads its MFMA
+    fragments through the transposing LDS reads (SNN_OPT_WGRAD_TR = 1, the default) against the
+    oracle, and against the general kernel (0) on the same context state: ragged rows, columns
+    and contraction tails (T*B not a multiple of the 32-row stage), narrow products riding along
+    in the launch, a packed layer-1 job beside them, several tiles per product, a recurrent layer."""
+    L = len(sizes) - 1
+    wl = workloads.Workload(name="wgrad-tr", index=21, T=T, B=B, sizes=sizes, recurrent=rec,
+                            beta=(0.9, 0.93, 0.95, 0.9)[:L], theta=1.0, surrogate="superspike", slope=10.0, precision="bf16",
+                            rate_lo=0.03, rate_hi=0.12, loss="max")
+    rep = full_step_parity(wl, w_gain=2.0, options={"layer_min_batch": 1, "wgrad_tr": 1}, check_sgd=False)
+    assert rep["spike_rate"][0] > 0.005
+    inp = workloads.generate(wl, w_gain=2.0)
+    grads = []
+    for knob in (1, 0):
+        snn = make(wl, inp, {"layer_min_batch": 1, "wgrad_tr": knob})
+        if packed:
+            snn.forward_packed(np.packbits(inp.X, axis=0), inp.labels)
+        else:
+            snn.forward(inp.X, inp.labels)
+        snn.backward()
+        g = [snn.get_tensor("grad_w", l + 1) for l in range(L)]
+        g += [snn.get_tensor("grad_r", l + 1) for l in range(L - 1) if rec[l]]
+        grads.append(g)
+        snn.destroy()
+    for a, b in zip(*grads):
+        # the same products of the same rounded operands; only the order of the fp32 additions differs
+        assert np.abs(a - b).max() <= 1e-5 * np.abs(b).max() + 1e-30
+
+
 def test_layer_forward_in_one_launch_same_as_separate_launches():
     """The same forward pass with and without the one-launch layers: potentials and readout
     agree to rounding, spikes are identical away from the threshold."""
