@@ -45,6 +45,13 @@ struct WgradTr {
   static constexpr int LDS_BYTES = NS * ST;
 };
 
+// PK: S is the raster packed along time (eight steps of a channel and sample in a byte, first step in
+// the most significant bit), and the contraction runs in packed order: element m = 64 q + 8 mg + r is
+// sample 8 bg + mg at step 8 tp + r for q = tp (B / 8) + bg.  The eight elements a lane feeds to an
+// MFMA are then the eight bits of one byte: the S part of a stage is 4 samples x 128 bytes, read
+// bytewise and expanded in registers; the rows of G are gathered in that order by the loads' per-lane
+// offsets, so its tile in LDS and its fragment reads are those of the plain order.
+template <bool PK>
 __device__ __forceinline__ void wgrad_tr_body(const GemmArgs &a, const int block, char *lds) {
   constexpr int BM = WgradTr::BM, BN = WgradTr::BN, MT = WgradTr::MT, NS = WgradTr::NS;
   constexpr int SP = WgradTr::SP, ST = WgradTr::ST, NL = WgradTr::NL;
@@ -68,8 +75,10 @@ __device__ __forceinline__ void wgrad_tr_body(const GemmArgs &a, const int block
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  // Rows m from kend on read as zero: the buffers end there.
-  const unsigned long long p_end = (unsigned long long)kend * a.ldp, q_end = (unsigned long long)kend * a.ldq * 4ull;
+  // Rows m from kend on read as zero: the buffers end there.  (PK: a split ends on a whole stage, and
+  // the rows of G that belong to steps beyond T lie beyond its end.)
+  const unsigned long long p_end = PK ? a.p_bytes : (unsigned long long)kend * a.ldp;
+  const unsigned long long q_end = PK ? a.q_bytes : (unsigned long long)kend * a.ldq * 4ull;
   const u32x4 rp = raw_rsrc(a.P, (unsigned)(p_end < a.p_bytes ? p_end : a.p_bytes));
   const u32x4 rq = raw_rsrc(a.Q, (unsigned)(q_end < a.q_bytes ? q_end : a.q_bytes));
   const unsigned lds0 = (unsigned)(uintptr_t)(lds_ptr_t)lds;
@@ -78,8 +87,20 @@ __device__ __forceinline__ void wgrad_tr_body(const GemmArgs &a, const int block
   // buffer's size bounds).  S: the wavefront's instruction fills rows 8 wave .. + 7 of the stage, lane
   // -> row lane / 8, slot lane % 8 holding unit slot ^ (row % 8).  G: instruction q fills rows
   // 2 (4 q + wave), + 1, lane -> row lane / 32, slot lane % 32 holding unit slot ^ 4 (row % 4).
+  // PK: S rows are the stage's four samples (lanes 0..31 of wavefront 0 fetch them, natural order);
+  // stage row rr of G is sample rr / 8 of the four at step rr % 8 of the eight: B rows apart per step.
   int pv, qv[4];
-  {
+  int pk_tp = 0, pk_rem = 0;                           // PK: the next stage to issue starts at packed row pk_tp B + pk_rem
+  if constexpr (PK) {
+    pk_tp = (kbeg >> 3) / a.pk_B;
+    pk_rem = (kbeg >> 3) - pk_tp * a.pk_B;
+    pv = wave == 0 && lane < 32 ? (lane >> 3) * a.ldp + row0 + 16 * (lane & 7) : OOB;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int rr = 2 * (4 * q + wave) + (lane >> 5), uu = (lane & 31) ^ (4 * (rr & 3));
+      qv[q] = (((rr & 7) * a.pk_B + (rr >> 3)) * a.ldq + col0 + 4 * uu) * 4;
+    }
+  } else {
     const int r = 8 * wave + (lane >> 3), u = (lane & 7) ^ (r & 7);
     pv = (kbeg + r) * a.ldp + row0 + 16 * u;
 #pragma unroll
@@ -92,6 +113,7 @@ __device__ __forceinline__ void wgrad_tr_body(const GemmArgs &a, const int block
   struct Issue {
     u32x4 p, q;
     unsigned dst;
+    int pbase, qbase;                                  // PK: byte offsets of the stage in S and G
   };
   auto issue_prepare = [&](int kt_any, int buf) {
     const int kt = __builtin_amdgcn_readfirstlane(kt_any);
@@ -99,11 +121,21 @@ __device__ __forceinline__ void wgrad_tr_body(const GemmArgs &a, const int block
     r.p = rp; r.q = rq;
     if (kt >= nk) r.p.z = r.q.z = 0;                   // beyond the contraction: same instruction count, nothing fetched
     r.dst = __builtin_amdgcn_readfirstlane(lds0 + buf * ST + 1024 * wave);
+    r.pbase = r.qbase = 0;
+    if constexpr (PK) {
+      r.pbase = __builtin_amdgcn_readfirstlane((pk_tp * a.pk_B + pk_rem) * a.ldp);
+      r.qbase = __builtin_amdgcn_readfirstlane((8 * pk_tp * a.pk_B + pk_rem) * a.ldq * 4);
+      pk_rem += 4;
+      if (pk_rem >= a.pk_B) { pk_rem = 0; ++pk_tp; }
+    }
     return r;
   };
   auto issue_load = [&](const Issue &r, auto N) {
     constexpr int n = decltype(N)::value;
-    if constexpr (n == 0) {
+    if constexpr (PK) {
+      if constexpr (n == 0) load_to_lds_b128(r.p, r.dst, pv == OOB ? OOB : pv + r.pbase, 0);
+      else load_to_lds_b128(r.q, r.dst + SP + 4096 * (n - 1), qv[n - 1] + r.qbase, 0);
+    } else if constexpr (n == 0) {
       load_to_lds_b128(r.p, r.dst, pv, 0);
       pv += pstep;
     } else {
@@ -122,13 +154,16 @@ __device__ __forceinline__ void wgrad_tr_body(const GemmArgs &a, const int block
   // B (tr_b16), step s, half e2, column tile t: stage row 16 s + 8 (g / 2) + 4 e2 + j / 4 of G, words
   // 64 wn + 16 t + 8 (g % 2) + 2 (j % 4), + 1.
   // Step, half and stage only add constants to the address (they leave row % 8 and row % 4 alone).
+  // PK, A: the byte of sample 2 s + lane / 32 of the stage's four and channel 64 wm + 32 i + lane % 32.
   const int g = lane >> 4, j = lane & 15;
   lds_char_ptr fa[2], fb[4];
   {
     lds_char_ptr base = (lds_char_ptr)lds;
     const int ra = 8 * (g >> 1) + (j >> 1), rb = 8 * (g >> 1) + (j >> 2);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) fa[i] = base + ra * 128 + (((4 * wm + 2 * i + (g & 1)) ^ (ra & 7)) << 4) + 8 * (j & 1);
+    for (int i = 0; i < 2; ++i)
+      fa[i] = PK ? base + (lane >> 5) * 128 + 64 * wm + 32 * i + (lane & 31)
+                 : base + ra * 128 + (((4 * wm + 2 * i + (g & 1)) ^ (ra & 7)) << 4) + 8 * (j & 1);
 #pragma unroll
     for (int t = 0; t < 4; ++t)
       fb[t] = base + SP + rb * 512 + ((16 * wn + 4 * (t ^ (rb & 3)) + 2 * (g & 1) + ((j >> 1) & 1)) << 4) + 8 * (j & 1);
@@ -142,9 +177,19 @@ __device__ __forceinline__ void wgrad_tr_body(const GemmArgs &a, const int block
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][t][r] = 0.f;
 
-  auto convert = [&](v2i32_t x) {                      // eight 0/1 bytes -> eight bfloat16 of value 2 x spike
-    const uint32_t t0 = (uint32_t)x.x << 6, t1 = (uint32_t)x.y << 6;
+  auto convert = [&](v2i32_t x) {                      // eight 0/1 bytes (PK: the eight bits of x.x) -> eight bfloat16 of value 2 x spike
     u32x4 d;
+    if constexpr (PK) {
+      // z holds the byte at bits 0..7 and again at bits 17..24: shifted left by 7 + 2 j, bit 14 is step
+      // 2 j and bit 30 is step 2 j + 1
+      const uint32_t z = (uint32_t)x.x | ((uint32_t)x.x << 17);
+      d.x = (z << 7) & 0x40004000u;
+      d.y = (z << 9) & 0x40004000u;
+      d.z = (z << 11) & 0x40004000u;
+      d.w = (z << 13) & 0x40004000u;
+      return __builtin_bit_cast(bf16x8, d);
+    }
+    const uint32_t t0 = (uint32_t)x.x << 6, t1 = (uint32_t)x.y << 6;
     d.x = __builtin_amdgcn_perm(0u, t0, 0x010C000Cu);
     d.y = __builtin_amdgcn_perm(0u, t0, 0x030C020Cu);
     d.z = __builtin_amdgcn_perm(0u, t1, 0x010C000Cu);
@@ -166,9 +211,16 @@ __device__ __forceinline__ void wgrad_tr_body(const GemmArgs &a, const int block
     bf16x8 af[2], bq[4];
   };
   auto read_a = [&](auto U, auto S, v2i32_t (&ar)[2]) {
-    constexpr int off = decltype(U)::value * ST + decltype(S)::value * 2048;
+    constexpr int off = decltype(U)::value * ST + decltype(S)::value * (PK ? 256 : 2048);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) ar[i] = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i32_ptr)(fa[i] + off));
+    for (int i = 0; i < 2; ++i) {
+      if constexpr (PK) {
+        ar[i].x = *(const __attribute__((address_space(3))) unsigned char *)(fa[i] + off);
+        ar[i].y = 0;
+      } else {
+        ar[i] = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i32_ptr)(fa[i] + off));
+      }
+    }
   };
   auto read_b = [&](auto U, auto S, int t, bf16x8 &bq) {
     constexpr int off = decltype(U)::value * ST + decltype(S)::value * 8192;
@@ -265,20 +317,14 @@ __device__ __forceinline__ void wgrad_tr_body(const GemmArgs &a, const int block
       }
 }
 
-// The weight-gradient jobs of wide layers (rounded weights): jobs on the raster packed along time
-// keep the general kernel's loaders.
+// The weight-gradient jobs of wide layers (rounded weights); a job's S may be the raster packed along time.
 __global__ __launch_bounds__(256, 2) void wgrad_tr_jobs_kernel(const GemmJobs jobs) {
-  constexpr int OLD = gemm_lds_bytes<P_T_BITS, Q_T_HL_PK, 2, 2, 2, 2, 2>();
-  constexpr int BYTES = WgradTr::LDS_BYTES > OLD ? WgradTr::LDS_BYTES : OLD;
-  static_assert(BYTES <= 81920, "two workgroups per compute unit");
-  __shared__ __attribute__((aligned(16))) char lds[BYTES];
+  static_assert(WgradTr::LDS_BYTES <= 81920, "two workgroups per compute unit");
+  __shared__ __attribute__((aligned(16))) char lds[WgradTr::LDS_BYTES];
   int j = 0;
   while (j + 1 < jobs.njobs && (int)blockIdx.x >= jobs.first_block[j + 1]) ++j;
-  if (jobs.job[j].packed) {
-    gemm_body<P_T_BITS, Q_T_HL_PK, EPI_STORE, 2, 2, 2, 2, 2, 1>(jobs.job[j], blockIdx.x - jobs.first_block[j], lds);
-    return;
-  }
-  wgrad_tr_body(jobs.job[j], blockIdx.x - jobs.first_block[j], lds);
+  if (jobs.job[j].packed) wgrad_tr_body<true>(jobs.job[j], blockIdx.x - jobs.first_block[j], lds);
+  else wgrad_tr_body<false>(jobs.job[j], blockIdx.x - jobs.first_block[j], lds);
 }
 
 static hipError_t wgrad_tr_jobs_launch(const GemmJobs &jobs, hipStream_t st) {

@@ -270,14 +270,18 @@ def test_layer_pair_on_two_workgroups(T, sizes, loss, packed):
                                                    (33, 5, (90, 128, 128, 20), (False, False), False),
                                                    (70, 8, (700, 128, 128, 20), (False, False), True),
                                                    (40, 7, (64, 300, 257, 129, 10), (False, False, False), False),
-                                                   (45, 4, (50, 140, 10), (True,), False)],
-                         ids=["ragged", "one-short-stage-tail", "packed-layer-1", "several-tiles", "recurrent"])
+                                                   (45, 4, (50, 140, 10), (True,), False),
+                                                   (50, 24, (300, 130, 20), (False,), True),
+                                                   (260, 16, (203, 257, 10), (False,), True)],
+                         ids=["ragged", "one-short-stage-tail", "packed-layer-1", "several-tiles", "recurrent",
+                              "packed-ragged", "packed-several-splits"])
 def test_weight_gradients_through_transposing_reads(T, B, sizes, rec, packed):
     """The weight-gradient products wider than 64 columns on the kernel that reads its MFMA
     fragments through the transposing LDS reads (SNN_OPT_WGRAD_TR = 1, the default) against the
     oracle, and against the general kernel (0) on the same context state: ragged rows, columns
     and contraction tails (T*B not a multiple of the 32-row stage), narrow products riding along
-    in the launch, a packed layer-1 job beside them, several tiles per product, a recurrent layer."""
+    in the launch, a packed layer-1 job beside them (steps beyond T in its last bytes, several
+    splits and column tiles), several tiles per product, a recurrent layer."""
     L = len(sizes) - 1
     wl = workloads.Workload(name="wgrad-tr", index=21, T=T, B=B, sizes=sizes, recurrent=rec,
                             beta=(0.9, 0.93, 0.95, 0.9)[:L], theta=1.0, surrogate="superspike", slope=10.0, precision="bf16",
