@@ -38,8 +38,9 @@ typedef __attribute__((address_space(3))) v2i32_t *lds_v2i32_ptr;
 typedef __attribute__((address_space(3))) v4i16_t *lds_v4i16_ptr;
 typedef __attribute__((address_space(3))) char *lds_char_ptr;
 
+template <int NS_>
 struct WgradTr {
-  static constexpr int BM = 128, BN = 128, MT = 32, NS = 3;
+  static constexpr int BM = 128, BN = 128, MT = 32, NS = NS_;
   static constexpr int SP = MT * 128, GP = MT * 512, ST = SP + GP;   // bytes of a stage: S part, G part
   static constexpr int NL = 5;                                       // load instructions per wavefront and stage
   static constexpr int LDS_BYTES = NS * ST;
@@ -51,10 +52,11 @@ struct WgradTr {
 // MFMA are then the eight bits of one byte: the S part of a stage is 4 samples x 128 bytes, read
 // bytewise and expanded in registers; the rows of G are gathered in that order by the loads' per-lane
 // offsets, so its tile in LDS and its fragment reads are those of the plain order.
-template <bool PK>
+template <bool PK, int NS>
 __device__ __forceinline__ void wgrad_tr_body(const GemmArgs &a, const int block, char *lds) {
-  constexpr int BM = WgradTr::BM, BN = WgradTr::BN, MT = WgradTr::MT, NS = WgradTr::NS;
-  constexpr int SP = WgradTr::SP, ST = WgradTr::ST, NL = WgradTr::NL;
+  typedef WgradTr<NS> G;
+  constexpr int BM = G::BM, BN = G::BN, MT = G::MT;
+  constexpr int SP = G::SP, ST = G::ST, NL = G::NL;
   // tile and split of this workgroup: as gemm_body
   const int ntiles = a.tiles_m * a.tiles_n;
   const int xcd = block & 7, slot = block >> 3;
@@ -318,19 +320,23 @@ __device__ __forceinline__ void wgrad_tr_body(const GemmArgs &a, const int block
 }
 
 // The weight-gradient jobs of wide layers (rounded weights); a job's S may be the raster packed along time.
+// NS: stages in flight.  3 (60 KiB) lets two workgroups share a compute unit.  More do not help, not even
+// a launch of one workgroup per compute unit (700-128-128-20, T*B = 32768, 256 workgroups: 18.1 us with
+// 3, 18.3 with 4, 19.6 with 6): the latency of the loads is covered.
+template <int NS>
 __global__ __launch_bounds__(256, 2) void wgrad_tr_jobs_kernel(const GemmJobs jobs) {
-  static_assert(WgradTr::LDS_BYTES <= 81920, "two workgroups per compute unit");
-  __shared__ __attribute__((aligned(16))) char lds[WgradTr::LDS_BYTES];
+  static_assert(WgradTr<NS>::LDS_BYTES <= 163840, "LDS of a compute unit");
+  __shared__ __attribute__((aligned(16))) char lds[WgradTr<NS>::LDS_BYTES];
   int j = 0;
   while (j + 1 < jobs.njobs && (int)blockIdx.x >= jobs.first_block[j + 1]) ++j;
-  if (jobs.job[j].packed) wgrad_tr_body<true>(jobs.job[j], blockIdx.x - jobs.first_block[j], lds);
-  else wgrad_tr_body<false>(jobs.job[j], blockIdx.x - jobs.first_block[j], lds);
+  if (jobs.job[j].packed) wgrad_tr_body<true, NS>(jobs.job[j], blockIdx.x - jobs.first_block[j], lds);
+  else wgrad_tr_body<false, NS>(jobs.job[j], blockIdx.x - jobs.first_block[j], lds);
 }
 
 static hipError_t wgrad_tr_jobs_launch(const GemmJobs &jobs, hipStream_t st) {
   if (jobs.njobs == 0) return hipSuccess;
   dim3 grid(jobs.first_block[jobs.njobs], 1, 1);
-  hipLaunchKernelGGL(wgrad_tr_jobs_kernel, grid, dim3(256), 0, st, jobs);
+  hipLaunchKernelGGL(wgrad_tr_jobs_kernel<3>, grid, dim3(256), 0, st, jobs);
   return hipGetLastError();
 }
 
