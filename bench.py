@@ -33,7 +33,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 # same command produced under the profiler; --traffic replaces it.
 PROFILED_TRAFFIC = {           # (workload, kernel, input packed along time)
     ("shd_ff128", "lif_forward", False): ((15841.0 * 2.0 + 50256.0) * 1024.0, "profiles/train_step_shd_ff128.txt"),
-    ("shd_ff128", "lif_forward", True): ((4554.7 * 2.0 + 50256.0) * 1024.0, "profiles/train_step_shd_ff128.txt"),
+    ("shd_ff128", "lif_forward", True): ((4523.0 * 2.0 + 50256.0) * 1024.0, "profiles/train_step_shd_ff128.txt"),
 }
 
 
