@@ -227,7 +227,12 @@ typedef enum {
  *   WGRAD_TR          1 (default): weight-gradient products wider than 64 columns on rounded weights use
  *                     the kernel that brings both operand tiles into LDS as they lie in memory and
  *                     reads the MFMA fragments through the transposing LDS reads; 0: the general
- *                     product kernel, which transposes in registers */
+ *                     product kernel, which transposes in registers
+ *   RLIF_PERSIST      1 (default): the forward time loop of a recurrent layer wider than 128 neurons on rounded
+ *                     weights runs as ONE launch when its grid of 32 x 32 tiles fits the compute units at a
+ *                     workgroup each and its padded width is a multiple of 256 up to 2048 (weights resident
+ *                     in LDS, spikes exchanged as bits through memory, a counter per sample tile; a wait that
+ *                     times out after about a second is reported as SNN_ERR_HIP); 0: a launch per step */
 typedef enum {
   SNN_OPT_LAYER_FORWARD = 0,
   SNN_OPT_LAYER_PAIR = 1,
@@ -242,7 +247,8 @@ typedef enum {
   SNN_OPT_TILE_ROWS = 10,
   SNN_OPT_LAYER_TIME_SPLIT = 11,
   SNN_OPT_WGRAD_TR = 12,
-  SNN_OPT_COUNT = 13
+  SNN_OPT_RLIF_PERSIST = 13,
+  SNN_OPT_COUNT = 14
 } snn_option;
 
 /* Validate `cfg` and report the device bytes snn_init needs (a multiple of 256).

@@ -20,6 +20,7 @@
 #include "scan.hpp"
 #include "layer_reverse.hpp"
 #include "rlif.hpp"
+#include "rlif_persist.hpp"
 
 using namespace snn;
 
@@ -56,6 +57,7 @@ struct Layer {
   uint8_t *S = nullptr;
   uint32_t *dI = nullptr;                             // [M][ld] fp32 bits or HL; readout: dJ
   float *g[2] = {nullptr, nullptr};                   // recurrent reverse state [B][ld]
+  void *rp_space = nullptr;                           // exchange space of the one-launch forward loop of a wide recurrent layer
   bool i_ready = true;     // I is in memory (false: the last forward pass ran the layer in one launch and never stored it)
   bool ds_ready = true;    // dS is in memory (false: the layer's reverse scan formed it itself in the last backward pass)
   int splits_w = 1, splits_r = 1;                     // contraction splits of dW and dR
@@ -91,6 +93,7 @@ struct snn_ctx {
   bool dj_ready = false;          // the fused readout kernel has already written dJ
   bool loss_ready = false;        // the mean of loss_b has been taken since the last readout
   int wall_khz = 100000;          // rate of the device's constant clock
+  int cus = 0;                    // compute units of the device
   bool wg_tall = false;           // weight-gradient products use 256 x 128 tiles
   bool integral = false;          // integral cross-entropy instead of max over time
   bool learn_beta = false;        // decays are trained: dbeta in snn_backward, clipped update in snn_sgd_step
@@ -104,7 +107,7 @@ struct snn_ctx {
   const int32_t *labels_dev = nullptr;
   ReduceJobs pending;             // partial sums of the last backward pass that have not been added yet
   bool reduce_pending = false;
-  int opt[SNN_OPT_COUNT] = {4, 1, 1, 1, 1, 0, 128, 1024, 128, 1, 0, 0, 1};   // snn_option values, in the enum's order
+  int opt[SNN_OPT_COUNT] = {4, 1, 1, 1, 1, 0, 128, 1024, 128, 1, 0, 0, 1, 1};   // snn_option values, in the enum's order
   uint32_t *hand = nullptr;       // hand-over space of the forward launches that give a sample to two workgroups
   int hand_parts = 1;             // hand-over regions per sample (one per column block of a layer)
   int fwd_epoch = 0;              // number of such launches so far (their flags count from epoch * 1024)
@@ -316,6 +319,8 @@ void carve(snn_ctx &c, Carver &cv) {
       y.QRb = cv.take<uint16_t>((size_t)np * y.qr_plane);
       y.g[0] = cv.take<float>((size_t)c.B * y.ld);
       y.g[1] = cv.take<float>((size_t)c.B * y.ld);
+      if (c.precision != SNN_PREC_FP32 && rlif_persist_fits(c.B, y.ld, y.ldqr, 1 << 30))
+        y.rp_space = cv.take<char>(rlif_persist_bytes(c.B, y.ldqr));
       y.splits_r = choose_splits(c.M, wg_tiles, wg_weights, wg_row_bytes, &y.per_r, wg_tr);
       if (y.splits_r > 1) y.part_r = cv.take<float>((size_t)y.splits_r * N * N);
     }
@@ -696,6 +701,13 @@ int launch_lif_forward(snn_ctx *c, int l) {
   Layer &y = c->layers[l];
   if (y.recurrent) {
     Bracket br(c, SNN_K_RLIF_FORWARD, l + 1);
+    // a wide layer on rounded weights whose grid fits the compute units at one workgroup each: the whole
+    // time loop in one launch (SNN_OPT_RLIF_PERSIST), else a launch per step
+    if (c->opt[SNN_OPT_RLIF_PERSIST] && y.rp_space && c->T >= 2 && rlif_persist_fits(c->B, y.ld, y.ldqr, c->cus)) {
+      HIPCHK(c, rlif_persist_forward(c->stream, c->T, c->B, y.ld, y.I, y.V, y.S, y.QRf, y.ldqr, y.beta_v, c->theta,
+                                     y.rp_space, c->err_flag));
+      return SNN_OK;
+    }
     HIPCHK(c, rlif_forward(c->stream, c->precision == SNN_PREC_FP32, c->T, c->B, y.N, y.ld, y.I, y.V, y.S, y.QRf,
                            y.ldqr, y.qr_plane, y.beta_v, c->theta));
     return SNN_OK;
@@ -1308,6 +1320,10 @@ int32_t snn_init(const snn_config *cfg, void *workspace_dev, size_t workspace_by
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
       c->wall_khz = khz;
+    int cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      c->cus = cus;
   }
   {
     void *unused = nullptr;                              // set-up of snn_weight_grad_static on this device
@@ -1646,6 +1662,7 @@ int32_t snn_set_option(snn_ctx *c, int32_t option, int32_t value) {
     case SNN_OPT_LAYER_TIME_SPLIT:
     case SNN_OPT_TOP_SCANS:
     case SNN_OPT_WGRAD_TR:
+    case SNN_OPT_RLIF_PERSIST:
     case SNN_OPT_DEFER_REDUCE:
     case SNN_OPT_STREAM_GEMM: ok = value == 0 || value == 1; break;
     case SNN_OPT_LAYER_MIN_BATCH: ok = value >= 0; break;

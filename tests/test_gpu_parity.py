@@ -306,6 +306,36 @@ def test_weight_gradients_through_transposing_reads(T, B, sizes, rec, packed):
         assert np.abs(a - b).max() <= 1e-5 * np.abs(b).max() + 1e-30
 
 
+@pytest.mark.parametrize("T,B,sizes,rec", [(37, 40, (50, 256, 10), (True,)),
+                                            (20, 33, (64, 512, 250, 10), (True, True)),
+                                            (2, 5, (30, 256, 10), (True,)),
+                                            (64, 32, (90, 768, 20), (True,))],
+                         ids=["two-sample-tiles", "two-layers-one-narrower", "single-step", "three-quarters-of-a-thousand"])
+def test_wide_recurrent_forward_in_one_launch(T, B, sizes, rec):
+    """The forward time loop of a recurrent layer wider than 128 neurons as one launch (weights resident
+    in LDS, spikes exchanged as bits through memory, a counter per sample tile; SNN_OPT_RLIF_PERSIST = 1)
+    against the oracle, and bit for bit against the launch per step (0): sample tiles with a ragged
+    tail, several neuron tiles per sample tile, a second recurrent layer whose width does not qualify,
+    the shortest raster, run twice on one context."""
+    L = len(sizes) - 1
+    wl = workloads.Workload(name="rlif-persist", index=23, T=T, B=B, sizes=sizes, recurrent=rec,
+                            beta=(0.9, 0.93, 0.95)[:L], theta=1.0, surrogate="superspike", slope=10.0, precision="bf16",
+                            rate_lo=0.03, rate_hi=0.12, loss="max")
+    rep = full_step_parity(wl, w_gain=2.0, options={"rlif_persist": 1}, check_sgd=False)
+    inp = workloads.generate(wl, w_gain=2.0)
+    outs = []
+    for knob, passes in ((1, 2), (0, 1)):
+        snn = make(wl, inp, {"rlif_persist": knob})
+        for _ in range(passes):
+            snn.forward(inp.X, inp.labels)
+            outs.append([snn.get_tensor("membrane", 1), snn.get_tensor("spikes", 1), snn.get_tensor("loss_per_sample")])
+        snn.destroy()
+    assert outs[0][1].mean() > 0.002
+    for o in outs[1:]:
+        for a, b in zip(o, outs[0]):
+            assert np.array_equal(a, b)
+
+
 def test_layer_forward_in_one_launch_same_as_separate_launches():
     """The same forward pass with and without the one-launch layers: potentials and readout
     agree to rounding, spikes are identical away from the threshold."""
