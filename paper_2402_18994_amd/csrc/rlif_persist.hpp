@@ -120,19 +120,43 @@ __global__ __launch_bounds__(256) void rlif_persist_forward_kernel(const float *
     f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    for (int s = 0; s < steps; ++s) {
-      const bf16x8 wf = *(const bf16x8 *)(fa + 32 * s);
-      // eight spikes of the lane's sample: bit r of the byte is neuron 8 (..) + r; z holds the byte at bits
-      // 0..7 and again at bits 15..22: shifted right by 2 j, bit 0 is element 2 j and bit 16 element 2 j + 1
-      const uint32_t v = fb[2 * s];
-      const uint32_t z = v | (v << 15);
-      u32x4 d;
-      d.x = (z & 0x00010001u) * 0x3F80u;
-      d.y = ((z >> 2) & 0x00010001u) * 0x3F80u;
-      d.z = ((z >> 4) & 0x00010001u) * 0x3F80u;
-      d.w = ((z >> 6) & 0x00010001u) * 0x3F80u;
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, __builtin_bit_cast(bf16x8, d), acc, 0, 0, 0);
+    // Four steps at a time, the fragments of the next four asked for before these are multiplied (left
+    // as a plain loop, every step waited a whole LDS round trip: 157 cycles per MFMA).  Eight spikes of
+    // the lane's sample are the bits of one byte, bit r = neuron 8 (..) + r: z holds the byte at bits
+    // 0..7 and again at bits 15..22; shifted left by 14 - 2 j, bit 14 is element 2 j and bit 30 element
+    // 2 j + 1, i.e. the bfloat16 pair 2.0 x spikes (the sums are halved below: exact).
+    bf16x8 wf[2][4];
+    uint32_t sv[2][4];
+    auto fetch = [&](int g, int s0) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        wf[g][q] = *(const bf16x8 *)(fa + 32 * (s0 + q));
+        sv[g][q] = fb[2 * (s0 + q)];
+      }
+    };
+    auto multiply = [&](int g) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t z = sv[g][q] | (sv[g][q] << 15);
+        u32x4 d;
+        d.x = (z << 14) & 0x40004000u;
+        d.y = (z << 12) & 0x40004000u;
+        d.z = (z << 10) & 0x40004000u;
+        d.w = (z << 8) & 0x40004000u;
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[g][q], __builtin_bit_cast(bf16x8, d), acc, 0, 0, 0);
+      }
+    };
+    fetch(0, 0);
+    for (int s = 0; s < steps; s += 8) {                 // (steps is a multiple of 4)
+      if (s + 4 < steps) fetch(1, s + 4);
+      multiply(0);
+      if (s + 4 < steps) {
+        if (s + 8 < steps) fetch(0, s + 8);
+        multiply(1);
+      }
     }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] *= 0.5f;
     const f32x4 sum = rlif_reduce(acc, red, w, lane);
     const float c4[4] = {cur.x, cur.y, cur.z, cur.w};
     uint32_t out = 0, nib = 0;
