@@ -232,7 +232,12 @@ typedef enum {
  *                     weights runs as ONE launch when its grid of 32 x 32 tiles fits the compute units at a
  *                     workgroup each and its padded width is a multiple of 256 up to 2048 (weights resident
  *                     in LDS, spikes exchanged as bits through memory, a counter per sample tile; a wait that
- *                     times out after about a second is reported as SNN_ERR_HIP); 0: a launch per step */
+ *                     times out after about a second is reported as SNN_ERR_HIP); 0: a launch per step
+ *   WAIT_LIMIT_LOG2   a workgroup of that launch polls at most 2^value times for another one's words:
+ *                     4..20 (default 18, about a second)
+ *   WAIT_FAULT        0 (default); 1: every such wait expects words that nobody writes, so it times out and
+ *                     the launch ends the way it would if a workgroup were missing (the grid drains, the next
+ *                     call that reads the error word returns SNN_ERR_HIP).  For tests of that path. */
 typedef enum {
   SNN_OPT_LAYER_FORWARD = 0,
   SNN_OPT_LAYER_PAIR = 1,
@@ -248,7 +253,9 @@ typedef enum {
   SNN_OPT_LAYER_TIME_SPLIT = 11,
   SNN_OPT_WGRAD_TR = 12,
   SNN_OPT_RLIF_PERSIST = 13,
-  SNN_OPT_COUNT = 14
+  SNN_OPT_WAIT_LIMIT_LOG2 = 14,
+  SNN_OPT_WAIT_FAULT = 15,
+  SNN_OPT_COUNT = 16
 } snn_option;
 
 /* Validate `cfg` and report the device bytes snn_init needs (a multiple of 256).

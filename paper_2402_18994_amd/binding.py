@@ -28,7 +28,8 @@ KERNELS = {"none": -1, "current_gemm": 0, "lif_forward": 1, "rlif_forward": 2, "
            "input_grad": 8, "sgd": 9, "calibrate": 10, "grad_reduce": 11, "event_pair": 12}
 OPTIONS = {"layer_forward": 0, "layer_pair": 1, "layer_reverse": 2, "top_scans": 3, "defer_reduce": 4,
            "layer_min_batch": 5, "layer_neurons": 6, "layer_max_neurons": 7, "stream_min_mb": 8,
-           "stream_gemm": 9, "tile_rows": 10, "layer_time_split": 11, "wgrad_tr": 12, "rlif_persist": 13}
+           "stream_gemm": 9, "tile_rows": 10, "layer_time_split": 11, "wgrad_tr": 12, "rlif_persist": 13, "wait_limit_log2": 14,
+           "wait_fault": 15}
 CALIBRATE_US = 10.0
 STATIC_SCRATCH_BYTES = 16 << 20
 STATUS = {0: "SNN_OK", 1: "SNN_ERR_NULL", 2: "SNN_ERR_ARG", 3: "SNN_ERR_SHAPE", 4: "SNN_ERR_WORKSPACE",

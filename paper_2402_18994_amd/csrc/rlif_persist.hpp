@@ -18,7 +18,7 @@
 //     acknowledged and polled before the words were read, took 13 us per step: three round trips.)
 // Every workgroup must be resident at once: the launch is refused unless the grid fits the compute
 // units at one workgroup each (the LDS use enforces one per unit).  A wait polls at most 2^18 times
-// (about a second); on a time-out the workgroup sets bit 1 of the error word and a flag that ends all
+// (about a second; SNN_OPT_WAIT_LIMIT_LOG2); on a time-out the workgroup sets bit 1 of the error word and a flag that ends all
 // waiting in every workgroup, so the grid always drains and the host reports the failure.
 //
 // The arithmetic is that of rlif_step_forward_kernel in the same order (a wavefront walks the same
@@ -39,10 +39,13 @@ struct RlifPersist {
 };
 
 // words [2][SB * 32][ldqr / 32] and the abort flag are zero at the launch (S_0 = 0 is what buffer 0 then says).
+// max_polls: bound of a wait; tag_bias: 0, or (tests of the time-out path) a value that makes every wait
+// expect a step nobody publishes.
 __global__ __launch_bounds__(256) void rlif_persist_forward_kernel(const float *__restrict__ I, float *__restrict__ V,
                                                                    uint8_t *__restrict__ S, const uint16_t *__restrict__ QRf,
                                                                    int ldqr, int T, int B, int ld, const float *__restrict__ beta_v,
-                                                                   float theta, uint64_t *words, uint32_t *abort_flag, int *err) {
+                                                                   float theta, uint64_t *words, uint32_t *abort_flag, int *err, int max_polls,
+                                                                   uint32_t tag_bias) {
   typedef RlifPersist G;
   __shared__ __attribute__((aligned(16))) char lds[G::LDS_BYTES];
   char *const slab = lds;
@@ -74,6 +77,7 @@ __global__ __launch_bounds__(256) void rlif_persist_forward_kernel(const float *
     *(float4 *)(V + o) = make_float4(0.f, 0.f, 0.f, 0.f);
     *(uint32_t *)(S + o) = 0u;
   }
+  for (int i = tid; i < 32 * G::SBP / 4; i += 256) ((uint32_t *)sb)[i] = 0u;   // (bits beyond the publishers' words stay zero)
   const int steps = ldqr >> 6;                         // MFMA steps (16 k) of a wavefront: a quarter of the contraction
   const char *const fa = slab + (lane & 31) * G::PITCH + (w * (ldqr >> 2) + 8 * h) * 2;
   const uint8_t *const fb = sb + (lane & 31) * G::SBP + w * (ldqr >> 5) + h;
@@ -87,34 +91,34 @@ __global__ __launch_bounds__(256) void rlif_persist_forward_kernel(const float *
     // carry step t
     {
       const uint64_t *src = words + ((size_t)(t & 1) * SB + st) * 32 * KW;
+      const uint32_t want = (uint32_t)t + (t ? tag_bias : 0u);
       uint64_t x[G::WPT] = {};
+      int at[G::WPT];                                    // word of sample i / NT, publisher i % NT (words beyond the publishers stay zero)
+#pragma unroll
+      for (int j = 0; j < G::WPT; ++j) {
+        const int i = tid + 256 * j, smp = i / NT;
+        at[j] = i < 32 * NT ? smp * KW + (i - smp * NT) : -1;
+      }
       bool ok = aborted;
       for (int spins = 0; !ok; ++spins) {
         ok = true;
 #pragma unroll
-        for (int j = 0; j < G::WPT; ++j) {
-          const int i = tid + 256 * j;
-          if (i < 32 * KW && (spins == 0 || (uint32_t)(x[j] >> 32) != (uint32_t)t))
-            x[j] = __hip_atomic_load(src + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        for (int j = 0; j < G::WPT; ++j)
+          if (at[j] >= 0 && (spins == 0 || (uint32_t)(x[j] >> 32) != want))
+            x[j] = __hip_atomic_load(src + at[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
         for (int j = 0; j < G::WPT; ++j)
-          if (tid + 256 * j < 32 * KW && (uint32_t)(x[j] >> 32) != (uint32_t)t) ok = false;
+          if (at[j] >= 0 && (uint32_t)(x[j] >> 32) != want) ok = false;
         if (!ok) {
           if ((spins & 15) == 15 && hand_load(abort_flag)) aborted = true;
-          if (spins >= (1 << 18)) { atomicOr(err, 2); hand_store(abort_flag, 1u); aborted = true; }
+          if (spins >= max_polls) { atomicOr(err, 2); hand_store(abort_flag, 1u); aborted = true; }
           if (aborted) break;
           __builtin_amdgcn_s_sleep(1);
         }
       }
 #pragma unroll
-      for (int j = 0; j < G::WPT; ++j) {
-        const int i = tid + 256 * j;
-        if (i < 32 * KW) {
-          const int smp = i / KW, d = i - smp * KW;
-          *(uint32_t *)(sb + smp * G::SBP + 4 * d) = aborted ? 0u : (uint32_t)x[j];
-        }
-      }
+      for (int j = 0; j < G::WPT; ++j)
+        if (at[j] >= 0) *(uint32_t *)(sb + 4 * at[j] + (at[j] / KW) * (G::SBP - 4 * KW)) = aborted ? 0u : (uint32_t)x[j];
     }
     __syncthreads();
     f32x16 acc;
@@ -194,14 +198,15 @@ static bool rlif_persist_fits(int B, int ld, int ldqr, int cus) {
 }
 
 static hipError_t rlif_persist_forward(hipStream_t st, int T, int B, int ld, const float *I, float *V, uint8_t *S,
-                                       const uint16_t *QRf, int ldqr, const float *beta, float theta, void *space, int *err) {
+                                       const uint16_t *QRf, int ldqr, const float *beta, float theta, void *space, int *err,
+                                       int max_polls, bool fault) {
   const int sb = (B + 31) / 32;
   hipError_t e = fill_zero(st, space, rlif_persist_bytes(B, ldqr));
   if (e != hipSuccess) return e;
   uint64_t *words = (uint64_t *)space;
   uint32_t *abort_flag = (uint32_t *)(words + 2 * (size_t)sb * 32 * (ldqr / 32));
   hipLaunchKernelGGL(rlif_persist_forward_kernel, dim3((ld + 31) / 32, sb), dim3(256), 0, st, I, V, S, QRf, ldqr, T, B, ld, beta,
-                     theta, words, abort_flag, err);
+                     theta, words, abort_flag, err, max_polls, fault ? 0x40000000u : 0u);
   return hipGetLastError();
 }
 

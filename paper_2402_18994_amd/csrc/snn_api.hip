@@ -107,7 +107,7 @@ struct snn_ctx {
   const int32_t *labels_dev = nullptr;
   ReduceJobs pending;             // partial sums of the last backward pass that have not been added yet
   bool reduce_pending = false;
-  int opt[SNN_OPT_COUNT] = {4, 1, 1, 1, 1, 0, 128, 1024, 128, 1, 0, 0, 1, 1};   // snn_option values, in the enum's order
+  int opt[SNN_OPT_COUNT] = {4, 1, 1, 1, 1, 0, 128, 1024, 128, 1, 0, 0, 1, 1, 18, 0};   // snn_option values, in the enum's order
   uint32_t *hand = nullptr;       // hand-over space of the forward launches that give a sample to two workgroups
   int hand_parts = 1;             // hand-over regions per sample (one per column block of a layer)
   int fwd_epoch = 0;              // number of such launches so far (their flags count from epoch * 1024)
@@ -705,7 +705,7 @@ int launch_lif_forward(snn_ctx *c, int l) {
     // time loop in one launch (SNN_OPT_RLIF_PERSIST), else a launch per step
     if (c->opt[SNN_OPT_RLIF_PERSIST] && y.rp_space && c->T >= 2 && rlif_persist_fits(c->B, y.ld, y.ldqr, c->cus)) {
       HIPCHK(c, rlif_persist_forward(c->stream, c->T, c->B, y.ld, y.I, y.V, y.S, y.QRf, y.ldqr, y.beta_v, c->theta,
-                                     y.rp_space, c->err_flag));
+                                     y.rp_space, c->err_flag, 1 << c->opt[SNN_OPT_WAIT_LIMIT_LOG2], c->opt[SNN_OPT_WAIT_FAULT] != 0));
       return SNN_OK;
     }
     HIPCHK(c, rlif_forward(c->stream, c->precision == SNN_PREC_FP32, c->T, c->B, y.N, y.ld, y.I, y.V, y.S, y.QRf,
@@ -1174,7 +1174,7 @@ int check_err_flag(snn_ctx *c) {
   HIPCHK(c, hipStreamSynchronize(c->stream));
   if (flag) {
     HIPCHK(c, fill_zero(c->stream, c->err_flag, 256));
-    if (flag & 2) return fail(c, SNN_ERR_HIP, "a forward launch gave up waiting for the workgroup that shares its sample");
+    if (flag & 2) return fail(c, SNN_ERR_HIP, "a forward launch gave up waiting for another workgroup");
     return fail(c, SNN_ERR_ARG, "a label was outside [0, C)");
   }
   return SNN_OK;
@@ -1663,9 +1663,11 @@ int32_t snn_set_option(snn_ctx *c, int32_t option, int32_t value) {
     case SNN_OPT_TOP_SCANS:
     case SNN_OPT_WGRAD_TR:
     case SNN_OPT_RLIF_PERSIST:
+    case SNN_OPT_WAIT_FAULT:
     case SNN_OPT_DEFER_REDUCE:
     case SNN_OPT_STREAM_GEMM: ok = value == 0 || value == 1; break;
     case SNN_OPT_LAYER_MIN_BATCH: ok = value >= 0; break;
+    case SNN_OPT_WAIT_LIMIT_LOG2: ok = value >= 4 && value <= 20; break;
     case SNN_OPT_LAYER_NEURONS: ok = value == 64 || value == 128; break;
     case SNN_OPT_LAYER_MAX_NEURONS: ok = value >= 64 && value <= 1024; break;
     case SNN_OPT_STREAM_MIN_MB: ok = value >= 0 && value <= (1 << 20); break;

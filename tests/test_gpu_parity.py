@@ -309,8 +309,10 @@ def test_weight_gradients_through_transposing_reads(T, B, sizes, rec, packed):
 @pytest.mark.parametrize("T,B,sizes,rec", [(37, 40, (50, 256, 10), (True,)),
                                             (20, 33, (64, 512, 250, 10), (True, True)),
                                             (2, 5, (30, 256, 10), (True,)),
-                                            (64, 32, (90, 768, 20), (True,))],
-                         ids=["two-sample-tiles", "two-layers-one-narrower", "single-step", "three-quarters-of-a-thousand"])
+                                            (64, 32, (90, 768, 20), (True,)),
+                                            (30, 20, (40, 200, 10), (True,))],
+                         ids=["two-sample-tiles", "two-layers-one-narrower", "single-step", "three-quarters-of-a-thousand",
+                              "fewer-publishers-than-words"])
 def test_wide_recurrent_forward_in_one_launch(T, B, sizes, rec):
     """The forward time loop of a recurrent layer wider than 128 neurons as one launch (weights resident
     in LDS, spikes exchanged as bits through memory, a counter per sample tile; SNN_OPT_RLIF_PERSIST = 1)
@@ -334,6 +336,31 @@ def test_wide_recurrent_forward_in_one_launch(T, B, sizes, rec):
     for o in outs[1:]:
         for a, b in zip(o, outs[0]):
             assert np.array_equal(a, b)
+
+
+def test_wide_recurrent_forward_wait_times_out():
+    """The bounded wait of the one-launch recurrent loop, forced from the host: with
+    SNN_OPT_WAIT_FAULT every wait expects words that nobody writes, so each workgroup gives up after
+    2^4 polls, the grid drains, and the call that reads the error word reports SNN_ERR_HIP; the
+    context works again afterwards."""
+    from paper_2402_18994_amd.binding import SnnError
+    wl = workloads.Workload(name="rlif-persist-fault", index=24, T=12, B=40, sizes=(50, 256, 10), recurrent=(True,),
+                            beta=(0.9, 0.93), theta=1.0, surrogate="superspike", slope=10.0, precision="bf16",
+                            rate_lo=0.03, rate_hi=0.12, loss="max")
+    inp = workloads.generate(wl, w_gain=2.0)
+    snn = make(wl, inp, {"rlif_persist": 1, "wait_fault": 1, "wait_limit_log2": 4})
+    with pytest.raises(SnnError) as e:
+        snn.forward(inp.X, inp.labels)
+    assert e.value.status == 6 and "waiting" in str(e.value)
+    snn.set_option("wait_fault", 0)
+    snn.set_option("wait_limit_log2", 18)
+    loss = snn.forward(inp.X, inp.labels)
+    good = [snn.get_tensor("spikes", 1), loss]
+    snn.destroy()
+    snn = make(wl, inp, {"rlif_persist": 0})
+    loss0 = snn.forward(inp.X, inp.labels)
+    assert np.array_equal(snn.get_tensor("spikes", 1), good[0]) and loss0 == good[1]
+    snn.destroy()
 
 
 def test_layer_forward_in_one_launch_same_as_separate_launches():
