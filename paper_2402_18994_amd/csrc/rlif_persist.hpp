@@ -150,14 +150,14 @@ __global__ __launch_bounds__(256) void rlif_persist_forward_kernel(const float *
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[g][q], __builtin_bit_cast(bf16x8, d), acc, 0, 0, 0);
       }
     };
+    // (branch-free body: with a fetch or a multiply under a condition the compiler moved the accumulator
+    // between its two register files in every iteration, draining the MFMA chain each time)
     fetch(0, 0);
-    for (int s = 0; s < steps; s += 8) {                 // (steps is a multiple of 4)
-      if (s + 4 < steps) fetch(1, s + 4);
+    for (int s = 0; s < steps; s += 4) {                 // (steps is a multiple of 4)
+      fetch(1, min(s + 4, steps - 4));
       multiply(0);
-      if (s + 4 < steps) {
-        if (s + 8 < steps) fetch(0, s + 8);
-        multiply(1);
-      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { wf[0][q] = wf[1][q]; sv[0][q] = sv[1][q]; }
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] *= 0.5f;
