@@ -4,11 +4,12 @@
 // bfloat16 hi (low half) and lo (high half)).
 //
 // The general kernel (gemm.hpp) transposes 8 x 4 byte blocks and 8 x 2 word blocks in registers on
-// their way to LDS: about 110 ALU instructions and 16 LDS writes per wavefront and 64 rows, and with
-// its operand buffers at size 0 it takes as long as with them: a single wavefront's instruction
-// stream is what bounds it.  Here both operand tiles go from memory straight into LDS as they lie
-// (buffer_load ... lds, the pipeline of the forward products) and the fragments are read
-// transposed:
+// their way to LDS: about 110 ALU instructions and 16 LDS writes per wavefront and 64 rows between its
+// MFMAs, and it needs two workgroups per compute unit to hide them.  Here both operand tiles go from
+// memory straight into LDS as they lie (buffer_load ... lds, the pipeline of the forward products), the
+// few instructions left are dealt out one MFMA at a time (see `stage`), so one workgroup per compute
+// unit multiplies as fast as two and the launch gets by with half the contraction splits, i.e. half
+// the partial sums.  The fragments are read transposed:
 //   ds_read_b64_tr_b8   the 16 lanes of a group each point at 8 bytes; the pieces of lanes 2r and
 //                       2r + 1 form row r of an 8 x 16 byte matrix, and lane i receives column i:
 //                       eight consecutive rows m of one spike column k - the A operand of
