@@ -233,6 +233,10 @@ typedef enum {
  *                     workgroup each and its padded width is a multiple of 256 up to 2048 (weights resident
  *                     in LDS, spikes exchanged as bits through memory, a counter per sample tile; a wait that
  *                     times out after about a second is reported as SNN_ERR_HIP); 0: a launch per step
+ *                     (LAYER_TIME_SPLIT = 1 and LAYER_PAIR = 2 tell one launch from the next by a count that the
+ *                     host passes as a kernel argument: do not replay calls made under them from a captured
+ *                     graph.  Everything else enqueues kernels only - no host read-back unless a loss pointer
+ *                     is given, no allocation, fill kernels instead of memsets - and can be captured.)
  *   WAIT_LIMIT_LOG2   a workgroup of that launch polls at most 2^value times for another one's words:
  *                     4..20 (default 18, about a second)
  *   WAIT_FAULT        0 (default); 1: every such wait expects words that nobody writes, so it times out and

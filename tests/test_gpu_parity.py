@@ -363,6 +363,64 @@ def test_wide_recurrent_forward_wait_times_out():
     snn.destroy()
 
 
+@pytest.mark.parametrize("name,T,B", [("shd_ff128", 128, 32), ("shd_rec128", 40, 32), ("wide-rec", 24, 64)],
+                         ids=["one-launch-layers", "narrow-recurrent", "one-launch-recurrent-loop"])
+def test_training_step_in_a_hip_graph(name, T, B):
+    """snn_forward + snn_backward + snn_sgd_step captured on the context's stream and replayed: the calls
+    enqueue kernels only (no host read-back without a loss pointer, no allocation, fill kernels instead
+    of memsets).  One eager step, the capture, then three replays with eager reads of the weights
+    between them; after every replay the weights are, bit for bit, those of a context that took the
+    same number of eager steps."""
+    import torch
+    if name == "wide-rec":
+        wl = workloads.Workload(name="graph-wide-rec", index=26, T=T, B=B, sizes=(50, 256, 10), recurrent=(True,),
+                                beta=(0.9, 0.93), theta=1.0, surrogate="superspike", slope=10.0, precision="bf16",
+                                rate_lo=0.03, rate_hi=0.12, loss="max")
+    else:
+        wl = workloads.CONFIGS[name].scaled(T=T, B=B)
+    inp = workloads.generate(wl, w_gain=2.0)
+    L = len(wl.sizes) - 1
+    lr = 0.05
+
+    def weights(snn):
+        return [snn.get_tensor("weight", l + 1) for l in range(L)]
+
+    ref = make(wl, inp)
+    eager = []
+    for _ in range(4):
+        ref.forward(inp.X, inp.labels, want_loss=False)
+        ref.backward()
+        ref.sgd_step(lr)
+        eager.append(weights(ref))
+    ref.destroy()
+    assert np.abs(eager[3][0] - eager[0][0]).max() > 0
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        snn = make(wl, inp)
+        x = torch.from_numpy(inp.X).cuda()
+        y = torch.from_numpy(inp.labels.astype(np.int32)).cuda()
+
+        def step():
+            snn.forward(x, y, want_loss=False)
+            snn.backward()
+            snn.sgd_step(lr)
+        step()
+        stream.synchronize()
+        for a, b in zip(weights(snn), eager[0]):
+            assert np.array_equal(a, b)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            step()
+        for k in range(1, 4):
+            graph.replay()
+            stream.synchronize()
+            for a, b in zip(weights(snn), eager[k]):
+                assert np.array_equal(a, b), f"replay {k}"
+        del graph
+        snn.destroy()
+
+
 def test_layer_forward_in_one_launch_same_as_separate_launches():
     """The same forward pass with and without the one-launch layers: potentials and readout
     agree to rounding, spikes are identical away from the threshold."""
